@@ -1,0 +1,239 @@
+"""Float64 CPU oracle for RAPID's importance-weighted group-advantage policy-gradient loss.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the HIP library is
+checked against.  Only the tests, the smoke check and the benchmark's CPU-baseline leg may call
+it; the product path never does.  It shares no code with the HIP path and imports nothing from
+the package.
+
+Every function restates a passage of the RAPID paper (arXiv 2510.03515):
+
+* Sec. 3.1 (Preliminaries): a generation y has tokens y_t; pi_theta(y|x) is the product of the
+  per-token probabilities, so log pi_theta(y|x) = sum_t log softmax(h_t W)[y_t].
+* Sec. 3.3, Eq. (2): group advantage A_n = R_n - mean of R over the group of n.
+* Sec. 3.4, Eq. (3): importance-weighted policy gradient, weight pi_theta(y_n|x_n)/mu(y_n|x_n).
+* Sec. 3.4, Eq. (4)/(5): importance-weighted group baseline, ratio clipped at eta.
+* Sec. 4.3, paragraph "Importance-weight clipping": per-token ratios are accumulated over the
+  generation first, the clip acts on the generation-level ratio.
+* Appendix A, RL hyper-parameter table: eta = 2.0.
+* Sec. 4.3, first paragraph: staleness = mean of the clipped weight in log scale.
+
+Readings of the paper taken here (each also listed in the design document):
+
+* Eq. (5) prints max{ratio, eta}; "standard importance weight clipping" that tames *large*
+  weights is min{ratio, eta}.  With min, equal policies give every weight exactly 1 and Eq. (5)
+  falls back to Eq. (2); with max it could not.  The oracle uses min.
+* The stray upper limit N on the group sums of Eq. (4)/(5) is ignored: sums run over the group.
+* The advantage is a constant with respect to theta (Alg. 1 computes it first, then the
+  gradient of Eq. (3), whose nabla acts on pi_theta only).
+* The outer weight in Eq. (3) is the unclipped ratio (coef_mode 0).  coef_mode 1 replaces it
+  by the clipped weight held constant; the paper does not print that variant: parity unpinned
+  for the *choice* between the two, both are computed the same way below.
+* Normalisation is 1/N with N the number of generations in the call; nothing is divided by a
+  length or by a group standard deviation (the paper never does).
+* The library returns the loss to descend, L = -J_surrogate, since the paper ascends J.
+
+Shapes: hidden [N,T,d]; W [d,V] (logical); tokens [N,T] int; mask [N,T] 0/1; logp_behav [N,T];
+rewards [N]; group_ids [N] ints in [0,K).
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+_F = np.float64
+
+
+def _as64(a):
+    return np.asarray(a, dtype=_F)
+
+
+def logprob(hidden, W, tokens, mask, temperature=1.0, row_chunk=2048):
+    """Per-token log-probability of the sampled token under softmax(h W / temperature).
+
+    Sec. 3.1: pi_theta(y_t | .) is the softmax of the LM head output.  Returns (logp, lse),
+    both [N,T] float64, zero at masked positions.
+    lse = max(z) + log(sum(exp(z - max(z)))), logp = z[y] - lse.
+    """
+    H = _as64(hidden)
+    Wd = _as64(W)
+    tok = np.asarray(tokens).astype(np.int64)
+    msk = np.asarray(mask) != 0
+    N, T, d = H.shape
+    V = Wd.shape[1]
+    logp = np.zeros((N, T), _F)
+    lse = np.zeros((N, T), _F)
+    rows = np.argwhere(msk)
+    for s in range(0, rows.shape[0], row_chunk):
+        rr = rows[s:s + row_chunk]
+        z = (H[rr[:, 0], rr[:, 1], :] @ Wd) / temperature
+        zmax = z.max(axis=1)
+        l = zmax + np.log(np.exp(z - zmax[:, None]).sum(axis=1))
+        y = tok[rr[:, 0], rr[:, 1]]
+        if (y < 0).any() or (y >= V).any():
+            raise ValueError("token id outside [0, V) at an unmasked position")
+        logp[rr[:, 0], rr[:, 1]] = z[np.arange(z.shape[0]), y] - l
+        lse[rr[:, 0], rr[:, 1]] = l
+    return logp, lse
+
+
+def token_logratio(logp_cur, logp_behav, mask):
+    """Delta_{n,t} = mask * (log pi_theta(y_t) - log mu(y_t)): the token-level log ratio (Fig. 3)."""
+    msk = (np.asarray(mask) != 0).astype(_F)
+    return msk * (_as64(logp_cur) - _as64(logp_behav))
+
+
+def seq_logratio(logp_cur, logp_behav, mask):
+    """s_n = sum_t Delta_{n,t} = log(pi_theta(y_n|x_n) / mu(y_n|x_n)).
+
+    Sec. 3.4, Eq. (3): the ratio is between whole-generation probabilities; Sec. 4.3 says the
+    per-token ratios are accumulated over the generation before clipping.
+    """
+    return token_logratio(logp_cur, logp_behav, mask).sum(axis=1)
+
+
+def clipped_weight(s, eta=2.0):
+    """w_n = min(exp(s_n), eta)  (Eq. (5) with the clip read as min; eta = 2.0 in Appendix A)."""
+    s = _as64(s)
+    log_eta = math.log(eta) if math.isfinite(eta) else math.inf
+    return np.exp(np.minimum(s, log_eta))
+
+
+def group_advantage(rewards, group_ids, K, s=None, eta=2.0, baseline_mode=0):
+    """Group advantage.
+
+    s is None          -> Eq. (2):  A_n = R_n - (1/N_k) sum_{n' in group k} R_n'
+    s given, eta=inf   -> Eq. (4):  A_n = R_n - (1/N_k) sum_{n'} rho_n' R_n'
+    s given, eta<inf   -> Eq. (5):  rho replaced by min(rho, eta)
+    baseline_mode 1    -> the leave-one-out sum of Sec. 3.4 (over the group without n), divided
+                          by N_k as printed; baseline_mode 2 divides by N_k - 1 instead.
+
+    Returns dict(adv[N], weight[N], group_mean[K], group_std[K], group_size[K]); mean/std are the
+    plain (population) statistics of R per group, diagnostics only.  An empty group has size 0,
+    mean 0, std 0.
+    """
+    R = _as64(rewards)
+    gid = np.asarray(group_ids).astype(np.int64)
+    N = R.shape[0]
+    if (gid < 0).any() or (gid >= K).any():
+        raise ValueError("group id outside [0, K)")
+    w = np.ones(N, _F) if s is None else clipped_weight(s, eta)
+    size = np.zeros(K, np.int64)
+    sum_wr = np.zeros(K, _F)
+    sum_r = np.zeros(K, _F)
+    for n in range(N):
+        size[gid[n]] += 1
+        sum_wr[gid[n]] += w[n] * R[n]
+        sum_r[gid[n]] += R[n]
+    mean = np.where(size > 0, sum_r / np.maximum(size, 1), 0.0)
+    sq = np.zeros(K, _F)
+    for n in range(N):
+        sq[gid[n]] += (R[n] - mean[gid[n]]) ** 2
+    std = np.where(size > 0, np.sqrt(sq / np.maximum(size, 1)), 0.0)
+    adv = np.zeros(N, _F)
+    for n in range(N):
+        k = gid[n]
+        if baseline_mode == 0:
+            b = sum_wr[k] / size[k]
+        elif baseline_mode == 1:
+            b = (sum_wr[k] - w[n] * R[n]) / size[k]
+        elif baseline_mode == 2:
+            b = (sum_wr[k] - w[n] * R[n]) / (size[k] - 1) if size[k] > 1 else 0.0
+        else:
+            raise ValueError("baseline_mode")
+        adv[n] = R[n] - b
+    return dict(adv=adv, weight=w, group_mean=mean, group_std=std, group_size=size)
+
+
+def coefficients(s, adv, eta=2.0, coef_mode=0, loss_scale=1.0, normalized=False):
+    """g_n = dL/d logp_{n,t} for every valid token t of generation n, and the loss.
+
+    L = -(loss_scale/N) sum_n c_n A_n with c_n = rho_n (Eq. (3)), or the clipped weight for
+    coef_mode 1.  d rho_n / d logp_{n,t} = rho_n, so g_n = -(loss_scale/N) c_n A_n and L = sum g_n.
+    With normalized=True everything is scaled by exp(-lam), lam = log max_n |g_n| evaluated in
+    the log domain (0 if every g_n is 0), so that values survive ratios that underflow.
+    Returns (g[N], loss, lam).
+    """
+    s = _as64(s)
+    A = _as64(adv)
+    N = s.shape[0]
+    log_c = s if coef_mode == 0 else np.minimum(s, math.log(eta) if math.isfinite(eta) else math.inf)
+    nz = A != 0
+    log_abs_g = np.full(N, -np.inf)
+    log_abs_g[nz] = log_c[nz] + np.log(np.abs(A[nz])) + math.log(loss_scale) - math.log(N)
+    lam = 0.0
+    if normalized and nz.any():
+        lam = float(log_abs_g.max())
+    g = np.zeros(N, _F)
+    g[nz] = -np.sign(A[nz]) * np.exp(log_abs_g[nz] - lam)
+    return g, float(g.sum()), lam
+
+
+def backward(hidden, W, tokens, mask, g, temperature=1.0, row_chunk=2048):
+    """Gradients of sum_{n,t valid} g_n * logp_{n,t} with respect to hidden and W.
+
+    For a valid row: p = softmax(z), dz = g_n (e_y - p) / temperature, dH = W dz,
+    dW += outer(h, dz).  Masked rows get dH = 0.  Returns (dH [N,T,d], dW [d,V]).
+    """
+    H = _as64(hidden)
+    Wd = _as64(W)
+    tok = np.asarray(tokens).astype(np.int64)
+    msk = np.asarray(mask) != 0
+    g = _as64(g)
+    N, T, d = H.shape
+    dH = np.zeros((N, T, d), _F)
+    dW = np.zeros_like(Wd)
+    rows = np.argwhere(msk)
+    for s0 in range(0, rows.shape[0], row_chunk):
+        rr = rows[s0:s0 + row_chunk]
+        h = H[rr[:, 0], rr[:, 1], :]
+        z = (h @ Wd) / temperature
+        zmax = z.max(axis=1, keepdims=True)
+        e = np.exp(z - zmax)
+        p = e / e.sum(axis=1, keepdims=True)
+        dz = -p
+        dz[np.arange(dz.shape[0]), tok[rr[:, 0], rr[:, 1]]] += 1.0
+        dz *= (g[rr[:, 0]] / temperature)[:, None]
+        dH[rr[:, 0], rr[:, 1], :] = dz @ Wd.T
+        dW += h.T @ dz
+    return dH, dW
+
+
+def iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, K,
+                       eta=2.0, coef_mode=0, baseline_mode=0, loss_scale=1.0, temperature=1.0,
+                       normalized_grads=False, coef_override=None, row_chunk=2048):
+    """The whole update-step loss of Alg. 1 (procedure IW-GRPG, one mini-batch): advantages by
+    Eq. (5), gradient by Eq. (3).  Returns a dict with loss, dH, dW and every intermediate."""
+    logp_cur, lse = logprob(hidden, W, tokens, mask, temperature, row_chunk)
+    tok_lr = token_logratio(logp_cur, logp_behav, mask)
+    s = tok_lr.sum(axis=1)
+    ga = group_advantage(rewards, group_ids, K, s=s, eta=eta, baseline_mode=baseline_mode)
+    N = s.shape[0]
+    if coef_override is not None:
+        g = _as64(coef_override)
+        loss, lam = float(g.sum()), 0.0
+    else:
+        g, loss, lam = coefficients(s, ga["adv"], eta, coef_mode, loss_scale, normalized_grads)
+    dH, dW = backward(hidden, W, tokens, mask, g, temperature, row_chunk)
+    log_eta = math.log(eta) if math.isfinite(eta) else math.inf
+    log_w = np.minimum(s, log_eta)
+    return dict(loss=loss, dH=dH, dW=dW, logp_cur=logp_cur, lse=lse, tok_logratio=tok_lr,
+                seq_logratio=s, adv=ga["adv"], weight=ga["weight"], g=g, grad_log_scale=lam,
+                group_mean=ga["group_mean"], group_std=ga["group_std"],
+                group_size=ga["group_size"],
+                n_tokens=int((np.asarray(mask) != 0).sum()),
+                n_clipped=int((s > log_eta).sum()),
+                mean_log_w=float(log_w.mean()) if N else 0.0,
+                mean_abs_log_w=float(np.abs(log_w).mean()) if N else 0.0,
+                max_abs_s=float(np.abs(s).max()) if N else 0.0)
+
+
+def compaction(mask):
+    """Integer bookkeeping of the padding mask: seq_len[N], cu_seqlen[N+1], row_index[M] (flat
+    n*T+t of every valid position in row-major order)."""
+    msk = np.asarray(mask) != 0
+    seq_len = msk.sum(axis=1).astype(np.int64)
+    cu = np.zeros(msk.shape[0] + 1, np.int64)
+    cu[1:] = np.cumsum(seq_len)
+    row_index = np.flatnonzero(msk.reshape(-1)).astype(np.int64)
+    return seq_len, cu, row_index

@@ -1,0 +1,397 @@
+"""Pins of the float64 oracle to things other than itself: hand-worked values of Eq. (2)/(4)/(5),
+closed forms, invariants, brute-force enumeration in pure Python, central finite differences of
+an independently written objective, and library routines (scipy log_softmax, torch autograd
+cross-entropy).  CPU only."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import rapid_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- helpers (independent of oracle)
+def _py_logsoftmax_at(h, W, y):
+    """log softmax(h W)[y] with explicit python loops."""
+    d, V = len(W), len(W[0])
+    z = [sum(h[k] * W[k][v] for k in range(d)) for v in range(V)]
+    return z[y] - math.log(sum(math.exp(zz) for zz in z))
+
+
+def _py_surrogate(H, W, tok, mask, logp_b, adv_fixed):
+    """-(1/N) sum_n A_n * prod_t pi(y_t)/mu(y_t): the objective whose gradient Eq. (3) gives,
+    with advantages held fixed, written with explicit loops."""
+    N, T = len(tok), len(tok[0])
+    tot = 0.0
+    for n in range(N):
+        ratio = 1.0
+        for t in range(T):
+            if mask[n][t]:
+                ratio *= math.exp(_py_logsoftmax_at(H[n][t], W, tok[n][t])) / math.exp(logp_b[n][t])
+        tot += adv_fixed[n] * ratio
+    return -tot / N
+
+
+def _tiny(seed=0, N=4, T=3, d=3, V=5, G=2):
+    rng = np.random.default_rng(seed)
+    H = rng.normal(size=(N, T, d))
+    W = rng.normal(size=(d, V)) * 0.5
+    W_old = W + rng.normal(size=(d, V)) * 0.1
+    tok = rng.integers(0, V, size=(N, T))
+    lengths = rng.integers(1, T + 1, size=N)
+    mask = (np.arange(T)[None, :] < lengths[:, None]).astype(np.uint8)
+    R = rng.random(N)
+    gid = np.arange(N) // G
+    logp_b, _ = orc.logprob(H, W_old, tok, mask)
+    return H, W, W_old, tok, mask, R, gid, logp_b
+
+
+# ---------------------------------------------------------------- group advantage (Eq. 2, 4, 5)
+def _golden():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "eq5_hand_example.txt"))
+            if l.strip() and not l.startswith("#")]
+    return np.array(rows, dtype=np.float64)
+
+
+def test_eq5_hand_example():
+    g = _golden()
+    rho, R = g[:, 0], g[:, 1]
+    gid = np.zeros(4, np.int64)
+    s = np.log(rho)
+    assert np.allclose(orc.group_advantage(R, gid, 1, s=s, eta=2.0)["adv"], g[:, 2], atol=1e-15)
+    assert np.allclose(orc.group_advantage(R, gid, 1, s=None)["adv"], g[:, 3], atol=1e-15)
+    assert np.allclose(orc.group_advantage(R, gid, 1, s=s, eta=math.inf)["adv"], g[:, 4], atol=1e-15)
+    assert np.allclose(orc.group_advantage(R, gid, 1, s=s, eta=2.0, baseline_mode=1)["adv"],
+                       g[:, 5], atol=1e-15)
+    w = orc.clipped_weight(s, 2.0)
+    assert np.allclose(w, [2.0, 1.0, 1.0, 0.5], atol=1e-15)
+
+
+def test_clip_is_min_not_max():
+    # s = ln 4, eta = 2 -> w = 2; s = ln 0.5 -> w = 0.5 (no lower clip)
+    w = orc.clipped_weight(np.log([4.0, 0.5, 2.0, 1.0]), 2.0)
+    assert np.allclose(w, [2.0, 0.5, 2.0, 1.0])
+    assert orc.clipped_weight(np.array([0.0]), 2.0)[0] == 1.0
+
+
+def test_group_adv_sums():
+    rng = np.random.default_rng(1)
+    N, K = 37, 5
+    R = rng.random(N)
+    gid = rng.integers(0, K, size=N)          # ragged, non-contiguous groups
+    out = orc.group_advantage(R, gid, K, s=None)
+    for k in range(K):                          # Eq. (2): zero sum per group
+        assert abs(out["adv"][gid == k].sum()) < 1e-12
+        assert out["group_size"][k] == (gid == k).sum()
+        if (gid == k).any():
+            assert abs(out["group_mean"][k] - R[gid == k].mean()) < 1e-14
+            assert abs(out["group_std"][k] - R[gid == k].std()) < 1e-14
+    s = rng.normal(size=N)
+    out = orc.group_advantage(R, gid, K, s=s, eta=2.0)
+    w = np.minimum(np.exp(s), 2.0)
+    for k in range(K):                          # closed form from Eq. (5): sum A = sum (1-w) R
+        m = gid == k
+        assert abs(out["adv"][m].sum() - ((1 - w[m]) * R[m]).sum()) < 1e-12
+    big = orc.group_advantage(R, gid, K, s=s, eta=1e300)
+    inf = orc.group_advantage(R, gid, K, s=s, eta=math.inf)
+    assert np.array_equal(big["adv"], inf["adv"])   # eta -> inf: Eq. (5) == Eq. (4)
+    # brute force per element
+    for n in range(N):
+        b = np.mean([min(math.exp(s[j]), 2.0) * R[j] for j in range(N) if gid[j] == gid[n]])
+        assert abs(out["adv"][n] - (R[n] - b)) < 1e-13
+
+
+def test_zero_variance_groups():
+    R = np.array([0, 0, 0, 0, 1, 1, 1, 1], float)
+    gid = np.array([0, 0, 0, 0, 1, 1, 1, 1])
+    s = np.array([0.3, -1.0, 2.0, 0.0, 0.3, -1.0, 2.0, 0.0])
+    out = orc.group_advantage(R, gid, 2, s=s, eta=2.0)
+    assert np.all(out["adv"][:4] == 0.0)             # all-0 group: A = 0 whatever the weights
+    w = np.minimum(np.exp(s[4:]), 2.0)
+    assert np.allclose(out["adv"][4:], 1.0 - w.mean())  # all-1 group: A = 1 - mean(w)
+    on = orc.group_advantage(R, gid, 2, s=None)
+    assert np.all(on["adv"] == 0.0) and np.all(on["group_std"] == 0.0)
+    empty = orc.group_advantage(R, gid, 3, s=None)
+    assert empty["group_size"][2] == 0 and empty["group_mean"][2] == 0 and empty["group_std"][2] == 0
+
+
+# ---------------------------------------------------------------- log-probabilities
+def test_logprob_closed_forms():
+    rng = np.random.default_rng(2)
+    N, T, d, V = 3, 5, 7, 11
+    H = rng.normal(size=(N, T, d))
+    tok = rng.integers(0, V, size=(N, T))
+    mask = np.ones((N, T), np.uint8)
+    mask[1, 3:] = 0
+    lp, lse = orc.logprob(H, np.zeros((d, V)), tok, mask)
+    assert np.allclose(lp[mask != 0], -math.log(V), atol=1e-15)   # W = 0 -> uniform
+    assert np.allclose(lse[mask != 0], math.log(V), atol=1e-15)
+    assert np.all(lp[mask == 0] == 0)
+    W = rng.normal(size=(d, V))
+    lp1, _ = orc.logprob(H, W, tok, mask)
+    lp2, _ = orc.logprob(H, W + rng.normal(size=(d, 1)), tok, mask)  # same vector added to every column
+    assert np.allclose(lp1, lp2, atol=1e-12)
+    ref = scipy.special.log_softmax(H @ W, axis=-1)                  # library third leg
+    pick = np.take_along_axis(ref, tok[..., None], axis=-1)[..., 0]
+    assert np.allclose(lp1[mask != 0], pick[mask != 0], atol=1e-13)
+    # probabilities over every token id sum to one
+    tot = np.zeros((N, T))
+    for v in range(V):
+        lpv, _ = orc.logprob(H, W, np.full((N, T), v), mask)
+        tot += np.exp(lpv) * (mask != 0)
+    assert np.allclose(tot[mask != 0], 1.0, atol=1e-13)
+    # temperature: logits divided by tau
+    lpt, _ = orc.logprob(H, W, tok, mask, temperature=0.7)
+    reft = scipy.special.log_softmax(H @ W / 0.7, axis=-1)
+    pickt = np.take_along_axis(reft, tok[..., None], axis=-1)[..., 0]
+    assert np.allclose(lpt[mask != 0], pickt[mask != 0], atol=1e-13)
+
+
+def test_logprob_brute_force_python():
+    H, W, _, tok, mask, *_ = _tiny(3)
+    lp, _ = orc.logprob(H, W, tok, mask)
+    for n in range(H.shape[0]):
+        for t in range(H.shape[1]):
+            if mask[n, t]:
+                ref = _py_logsoftmax_at(H[n, t].tolist(), W.tolist(), int(tok[n, t]))
+                assert abs(lp[n, t] - ref) < 1e-13
+            else:
+                assert lp[n, t] == 0.0
+
+
+def test_token_out_of_range_raises():
+    H, W, _, tok, mask, *_ = _tiny(3)
+    tok = tok.copy()
+    tok[0, 0] = W.shape[1]
+    with pytest.raises(ValueError):
+        orc.logprob(H, W, tok, mask)
+
+
+# ---------------------------------------------------------------- ratio direction and on-policy case
+def test_expected_ratio_is_one_exhaustive():
+    """E_{y~mu}[pi(y)/mu(y)] = 1 by enumerating every generation of a tiny vocabulary: pins the
+    direction of the ratio (pi/mu, not mu/pi) and the accumulation over tokens."""
+    rng = np.random.default_rng(4)
+    T, d, V = 3, 4, 3
+    H = rng.normal(size=(1, T, d))
+    W = rng.normal(size=(d, V))
+    W_old = W + 0.5 * rng.normal(size=(d, V))
+    mask = np.ones((1, T), np.uint8)
+    tot, tot_inv = 0.0, 0.0
+    for y in itertools.product(range(V), repeat=T):
+        tok = np.array([y])
+        lp_mu, _ = orc.logprob(H, W_old, tok, mask)
+        lp_pi, _ = orc.logprob(H, W, tok, mask)
+        s = orc.seq_logratio(lp_pi, lp_mu, mask)[0]
+        mu = math.exp(lp_mu.sum())
+        tot += mu * math.exp(s)
+        tot_inv += mu * math.exp(-s)
+    assert abs(tot - 1.0) < 1e-12
+    assert abs(tot_inv - 1.0) > 1e-2     # the wrong direction does not integrate to one
+
+
+def test_on_policy_reduction():
+    """Equal policies: every weight exactly 1, Eq. (5) == Eq. (2), loss exactly 0 for complete
+    groups, gradient equals the on-policy group-advantage policy gradient (Eq. (1) with Eq. (2))."""
+    H, W, _, tok, mask, R, gid, _ = _tiny(5, N=6, G=3)
+    lp, _ = orc.logprob(H, W, tok, mask)
+    out = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, lp, R, gid, 2)
+    assert np.all(out["seq_logratio"] == 0.0)
+    assert np.all(out["weight"] == 1.0)
+    assert np.array_equal(out["adv"], orc.group_advantage(R, gid, 2, s=None)["adv"])
+    assert abs(out["loss"]) < 1e-15
+    assert out["n_clipped"] == 0 and out["mean_log_w"] == 0.0
+    # on-policy gradient: d/dtheta of -(1/N) sum_n A_n log pi(y_n), by central differences
+    A = out["adv"]
+
+    def obj(Hx, Wx):
+        tot = 0.0
+        for n in range(6):
+            for t in range(H.shape[1]):
+                if mask[n, t]:
+                    tot += A[n] * _py_logsoftmax_at(Hx[n, t].tolist(), Wx.tolist(), int(tok[n, t]))
+        return -tot / 6
+
+    eps = 1e-6
+    for (i, j) in [(0, 0), (2, 3), (1, 4)]:
+        Wp, Wm = W.copy(), W.copy()
+        Wp[i, j] += eps
+        Wm[i, j] -= eps
+        fd = (obj(H, Wp) - obj(H, Wm)) / (2 * eps)
+        assert abs(out["dW"][i, j] - fd) < 1e-8
+
+
+# ---------------------------------------------------------------- gradients
+@pytest.mark.parametrize("coef_mode", [0])
+def test_finite_differences_of_surrogate(coef_mode):
+    H, W, _, tok, mask, R, gid, logp_b = _tiny(6)
+    out = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, eta=2.0, coef_mode=coef_mode)
+    A = out["adv"].tolist()
+    f0 = _py_surrogate(H.tolist(), W.tolist(), tok.tolist(), mask.tolist(), logp_b.tolist(), A)
+    assert abs(f0 - out["loss"]) < 1e-13
+    eps = 1e-6
+    for idx in itertools.product(range(W.shape[0]), range(W.shape[1])):
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += eps
+        Wm[idx] -= eps
+        fd = (_py_surrogate(H.tolist(), Wp.tolist(), tok.tolist(), mask.tolist(), logp_b.tolist(), A)
+              - _py_surrogate(H.tolist(), Wm.tolist(), tok.tolist(), mask.tolist(), logp_b.tolist(), A)) / (2 * eps)
+        assert abs(out["dW"][idx] - fd) < 1e-8, idx
+    for idx in itertools.product(range(H.shape[0]), range(H.shape[1]), range(H.shape[2])):
+        Hp, Hm = H.copy(), H.copy()
+        Hp[idx] += eps
+        Hm[idx] -= eps
+        fd = (_py_surrogate(Hp.tolist(), W.tolist(), tok.tolist(), mask.tolist(), logp_b.tolist(), A)
+              - _py_surrogate(Hm.tolist(), W.tolist(), tok.tolist(), mask.tolist(), logp_b.tolist(), A)) / (2 * eps)
+        assert abs(out["dH"][idx] - fd) < 1e-8, idx
+        if not mask[idx[0], idx[1]]:
+            assert out["dH"][idx] == 0.0
+
+
+def test_coef_mode1_is_linear_surrogate():
+    """coef_mode 1: the clipped weight is a constant coefficient on log pi; its gradient is the
+    gradient of sum_n g_n sum_t logp_{n,t}, checked by finite differences."""
+    H, W, _, tok, mask, R, gid, logp_b = _tiny(7)
+    logp_b = logp_b - 0.4 * mask      # push ratios up so that some clip
+    out = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, eta=2.0, coef_mode=1)
+    assert out["n_clipped"] > 0
+    w = np.minimum(np.exp(out["seq_logratio"]), 2.0)
+    assert np.allclose(out["g"], -w * out["adv"] / 4, atol=1e-15)
+    g = out["g"]
+
+    def obj(Wx):
+        tot = 0.0
+        for n in range(4):
+            for t in range(H.shape[1]):
+                if mask[n, t]:
+                    tot += g[n] * _py_logsoftmax_at(H[n, t].tolist(), Wx.tolist(), int(tok[n, t]))
+        return tot
+
+    eps = 1e-6
+    for idx in [(0, 0), (1, 2), (2, 4)]:
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += eps
+        Wm[idx] -= eps
+        assert abs(out["dW"][idx] - (obj(Wp) - obj(Wm)) / (2 * eps)) < 1e-8
+
+
+def test_cross_entropy_special_case_torch_autograd():
+    """Constant coefficient g = -1/M: the backward is the gradient of the mean token cross-entropy
+    of a linear layer, a library routine (torch autograd, float64)."""
+    rng = np.random.default_rng(8)
+    N, T, d, V = 3, 6, 5, 9
+    H = rng.normal(size=(N, T, d))
+    W = rng.normal(size=(d, V))
+    tok = rng.integers(0, V, size=(N, T))
+    mask = np.ones((N, T), np.uint8)
+    mask[0, 4:] = 0
+    mask[2, 1:] = 0
+    M = int(mask.sum())
+    dH, dW = orc.backward(H, W, tok, mask, np.full(N, -1.0 / M))
+    Ht = torch.tensor(H, requires_grad=True)
+    Wt = torch.tensor(W, requires_grad=True)
+    logits = (Ht @ Wt)[torch.tensor(mask != 0)]
+    loss = torch.nn.functional.cross_entropy(logits, torch.tensor(tok[mask != 0]), reduction="mean")
+    loss.backward()
+    assert np.allclose(dH, Ht.grad.numpy(), atol=1e-14)
+    assert np.allclose(dW, Wt.grad.numpy(), atol=1e-14)
+    # softmax identity: every row of dW (over the vocabulary) sums to zero
+    assert np.allclose(dW.sum(axis=1), 0.0, atol=1e-14)
+    # temperature scales logits: compare with autograd again
+    dHt, dWt = orc.backward(H, W, tok, mask, np.full(N, -1.0 / M), temperature=0.5)
+    Ht2 = torch.tensor(H, requires_grad=True)
+    Wt2 = torch.tensor(W, requires_grad=True)
+    logits = ((Ht2 @ Wt2) / 0.5)[torch.tensor(mask != 0)]
+    torch.nn.functional.cross_entropy(logits, torch.tensor(tok[mask != 0]), reduction="mean").backward()
+    assert np.allclose(dHt, Ht2.grad.numpy(), atol=1e-13)
+    assert np.allclose(dWt, Wt2.grad.numpy(), atol=1e-13)
+
+
+def test_importance_weighted_gradient_is_unbiased_exhaustive():
+    """Eq. (3) with a known advantage: sum_y mu(y) [pi(y)/mu(y)] grad log pi(y) R(y) equals the
+    gradient of J = sum_y pi(y) R(y), by enumeration of every generation and finite differences of
+    a python-loop J."""
+    rng = np.random.default_rng(9)
+    T, d, V = 2, 3, 3
+    H = rng.normal(size=(1, T, d))
+    W = rng.normal(size=(d, V))
+    W_old = W + 0.3 * rng.normal(size=(d, V))
+    mask = np.ones((1, T), np.uint8)
+    seqs = list(itertools.product(range(V), repeat=T))
+    Rtab = {y: rng.random() for y in seqs}
+
+    def J(Wx):
+        tot = 0.0
+        for y in seqs:
+            lp = sum(_py_logsoftmax_at(H[0, t].tolist(), Wx.tolist(), y[t]) for t in range(T))
+            tot += math.exp(lp) * Rtab[y]
+        return tot
+
+    acc = np.zeros_like(W)
+    for y in seqs:
+        tok = np.array([y])
+        lp_mu, _ = orc.logprob(H, W_old, tok, mask)
+        lp_pi, _ = orc.logprob(H, W, tok, mask)
+        rho = math.exp(orc.seq_logratio(lp_pi, lp_mu, mask)[0])
+        # descent coefficient -rho R (N = 1), weighted by the sampling probability mu(y)
+        _, dW = orc.backward(H, W, tok, mask, np.array([-rho * Rtab[y] * math.exp(lp_mu.sum())]))
+        acc += dW
+    eps = 1e-6
+    for idx in itertools.product(range(d), range(V)):
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += eps
+        Wm[idx] -= eps
+        assert abs(-acc[idx] - (J(Wp) - J(Wm)) / (2 * eps)) < 1e-8
+
+
+# ---------------------------------------------------------------- scaling, diagnostics, bookkeeping
+def test_normalized_grads_and_underflow():
+    H, W, _, tok, mask, R, gid, logp_b = _tiny(10)
+    a = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2)
+    b = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, normalized_grads=True)
+    lam = b["grad_log_scale"]
+    assert abs(np.abs(b["g"]).max() - 1.0) < 1e-12
+    assert np.allclose(b["dW"] * math.exp(lam), a["dW"], rtol=1e-12, atol=0)
+    assert abs(b["loss"] * math.exp(lam) - a["loss"]) < 1e-14
+    # ratios that underflow float64: normalised outputs stay finite and O(1)
+    c = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b + 900.0 * mask, R, gid, 2, normalized_grads=True)
+    assert np.isfinite(c["dW"]).all() and abs(np.abs(c["g"]).max() - 1.0) < 1e-12
+    assert c["grad_log_scale"] < -800
+    # loss_scale is linear
+    d2 = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, loss_scale=0.25)
+    assert np.allclose(d2["dW"], 0.25 * a["dW"], rtol=1e-12) and abs(d2["loss"] - 0.25 * a["loss"]) < 1e-15
+
+
+def test_diagnostics_and_empty_sequence():
+    H, W, _, tok, mask, R, gid, logp_b = _tiny(11)
+    mask = mask.copy()
+    mask[1, :] = 0                        # a generation with no valid token
+    logp_b = logp_b * mask
+    out = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b - 0.5 * mask, R, gid, 2, eta=2.0)
+    s = out["seq_logratio"]
+    assert s[1] == 0.0 and out["weight"][1] == 1.0
+    assert np.all(out["dH"][1] == 0.0)
+    assert out["n_tokens"] == int(mask.sum())
+    assert out["n_clipped"] == int((np.exp(s) > 2.0).sum())
+    lw = np.log(np.minimum(np.exp(s), 2.0))
+    assert abs(out["mean_log_w"] - lw.mean()) < 1e-14
+    assert abs(out["mean_abs_log_w"] - np.abs(lw).mean()) < 1e-14
+    # loss recomputed from rho and A
+    assert abs(out["loss"] + (np.exp(s) * out["adv"]).mean()) < 1e-14
+
+
+def test_compaction():
+    rng = np.random.default_rng(12)
+    mask = (rng.random((5, 9)) < 0.6).astype(np.uint8)   # arbitrary pattern, not only right padding
+    mask[3] = 0
+    seq_len, cu, row_index = orc.compaction(mask)
+    ref_rows = [n * 9 + t for n in range(5) for t in range(9) if mask[n, t]]
+    assert row_index.tolist() == ref_rows
+    assert seq_len.tolist() == [int(mask[n].sum()) for n in range(5)]
+    assert cu.tolist() == [0] + list(itertools.accumulate(seq_len.tolist()))
