@@ -1,0 +1,176 @@
+/*
+ * rapid.h -- C ABI of the MI355X (gfx950) library for the hot path of RAPID's off-policy update
+ * step (arXiv 2510.03515): the fused importance-weighted group-advantage policy-gradient loss.
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library never allocates,
+ *    frees or keeps device memory: scratch comes from the caller's `workspace`, whose size is
+ *    given by rapid_workspace_bytes().  `opts` of rapid_iw_pg_loss_fwd_bwd is a HOST pointer.
+ *  - All work is enqueued on the caller's HIP stream (`stream` is a hipStream_t passed as
+ *    void*; NULL = the default stream).  Calls are asynchronous and never synchronise the
+ *    device; outputs are valid once the stream has reached the end of the call's work.
+ *  - Return value: RAPID_OK or a negative RAPID_ERR_* detected on the host before any launch
+ *    (nothing has been enqueued then).  rapid_last_error() gives a thread-local message.
+ *  - Errors only the device can see (token id outside [0,V) at an unmasked position, group id
+ *    outside [0,K), non-finite reward or behaviour log-prob) OR a bit into the caller's
+ *    `dev_status` word (may be NULL); the offending element is treated as token 0 / skipped /
+ *    0 and nothing faults.  The library only ORs bits in: the caller clears the word.
+ *  - Layouts: hidden [N,T,d] row-major (padded), dtype bf16 or fp32; hidden row (n,t) is the
+ *    state that predicts tokens[n,t].  W is logically [d,V]; w_layout says how it is stored:
+ *    RAPID_W_DV = [d,V] row-major, RAPID_W_VD = [V,d] row-major.  tokens [N,T] int32;
+ *    mask [N,T] uint8 (any 0/1 pattern); per-token outputs [N,T] fp32 (0 at masked positions);
+ *    rewards [N] fp32; group_ids [N] int32 in [0,K), groups need not be contiguous or equal.
+ *  - Only gfx950 devices are accepted (RAPID_ERR_ARCH otherwise).
+ */
+#ifndef RAPID_H
+#define RAPID_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* host-side error codes */
+#define RAPID_OK 0
+#define RAPID_ERR_NULL (-1)      /* a required pointer is NULL */
+#define RAPID_ERR_SHAPE (-2)     /* a size is <= 0, too large, or unsupported (bf16 needs d % 8 == 0) */
+#define RAPID_ERR_DTYPE (-3)     /* unknown dtype / layout / mode enum */
+#define RAPID_ERR_WORKSPACE (-4) /* workspace NULL, misaligned (256 B) or below the minimum */
+#define RAPID_ERR_ARCH (-5)      /* current device is not gfx950 */
+#define RAPID_ERR_HIP (-6)       /* a HIP runtime call failed */
+
+/* bits OR-ed into *dev_status by kernels */
+#define RAPID_STATUS_BAD_TOKEN 1
+#define RAPID_STATUS_BAD_GROUP 2
+#define RAPID_STATUS_NONFINITE_REWARD 4
+#define RAPID_STATUS_NONFINITE_LOGP 8
+
+/* enums */
+#define RAPID_DTYPE_F32 0
+#define RAPID_DTYPE_BF16 1
+#define RAPID_W_DV 0
+#define RAPID_W_VD 1
+#define RAPID_OP_LOGPROB_FWD 0
+#define RAPID_OP_GROUP_ADVANTAGE 1
+#define RAPID_OP_IW_PG_FWD_BWD 2
+
+/* Options of rapid_iw_pg_loss_fwd_bwd (host struct).  rapid_iw_pg_default_opts() fills the
+ * paper's defaults: eta = 2.0 (Appendix A, RL hyper-parameter table), everything else as
+ * Sec. 3.4 states the estimator. */
+typedef struct rapid_iw_pg_opts {
+    float eta;             /* clip of the generation-level ratio in the baseline, Eq. (5); +inf => Eq. (4) */
+    int coef_mode;         /* 0: outer weight is the unclipped ratio (Eq. (3) as printed);
+                              1: outer weight is the clipped weight, held constant */
+    int baseline_mode;     /* 0: Eq. (5), sum over the whole group; 1: leave-one-out sum of Sec. 3.4
+                              divided by N_k as printed; 2: leave-one-out divided by N_k - 1 */
+    float loss_scale;      /* multiplies loss and gradients (fold in N/N_global, accumulation steps) */
+    float temperature;     /* logits are divided by it; 1.0 */
+    int w_layout;          /* RAPID_W_DV | RAPID_W_VD, for W and for dW_out */
+    int dw_dtype;          /* RAPID_DTYPE_F32 (default) | RAPID_DTYPE_BF16 */
+    int accumulate_dw;     /* 0: dW_out is overwritten; 1: dW_out += gradient (fp32 dW only) */
+    int normalized_grads;  /* 1: loss, dhidden and dW are returned multiplied by exp(-lambda), with
+                              lambda = log max_n |g_n| reported in diag->grad_log_scale, so that
+                              ratios that underflow fp32 still give usable gradients */
+    int reserved;
+    const float* coef_override; /* DEVICE [N] or NULL: use these per-generation coefficients g_n
+                              = dLoss/dlogp_{n,t} instead of the estimator's (loss = sum g_n) */
+} rapid_iw_pg_opts;
+
+/* Diagnostics written by rapid_iw_pg_loss_fwd_bwd (device struct).
+ * mean_log_w / mean_abs_log_w: mean over generations of log(clipped weight) and of its absolute
+ * value (staleness of Sec. 4.3); n_clipped: generations with ratio > eta (clip proportion,
+ * Sec. 4.3 "Importance-weight clipping"). */
+typedef struct rapid_iw_pg_diag {
+    int64_t n_tokens;
+    int32_t n_clipped;
+    int32_t n_sequences;
+    float mean_log_w;
+    float mean_abs_log_w;
+    float max_abs_s;
+    float grad_log_scale;
+} rapid_iw_pg_diag;
+
+/* Library/ABI version (monotone integer) and the last error text of the calling thread. */
+int rapid_version(void);
+const char* rapid_last_error(void);
+
+/* Fills *opts with the defaults described above.  Host pointer. */
+void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
+
+/* Process-wide tuning switches (host state, not thread-safe against concurrent calls).
+ * key 0: how the MFMA kernels bring operand tiles into LDS: 1 = direct global->LDS loads
+ * (default), 0 = staged through registers.  Results are identical either way. */
+int rapid_set_tuning(int key, int value);
+
+/* Workspace sizes in bytes for `op` at the given problem size.  rapid_workspace_bytes is the
+ * recommended size (backward row-chunks large enough to fill the chip); rapid_workspace_min_bytes
+ * the smallest the call accepts (smaller chunks, same results).  RAPID_OP_GROUP_ADVANTAGE needs
+ * none (returns 0).  Returns 0 for invalid arguments. */
+size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype);
+size_t rapid_workspace_min_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype);
+
+/*
+ * Behaviour / current-policy log-probabilities of the sampled tokens (Sec. 3.1: pi(y_t | .) is
+ * the softmax of the LM head; Alg. 1, "copy the current policy mu <- pi_theta": these are the
+ * log mu(y_t) the ratio of Eq. (3) divides by).
+ *   logp_out[n,t] = z[y] - logsumexp(z),  z = hidden[n,t,:] . W / temperature   (0 where mask = 0)
+ *   lse_out[n,t]  = logsumexp(z) (optional, may be NULL)
+ * The [N*T, V] logits are never written to memory.
+ */
+int rapid_logprob_fwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
+                      int64_t N, int64_t T, int64_t d, int64_t V, int dtype, int w_layout,
+                      float temperature, float* logp_out, float* lse_out, int32_t* dev_status,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Group advantage (Sec. 3.3 Eq. (2); Sec. 3.4 Eq. (4), (5)).
+ *   w_n = 1 if seq_logratio == NULL (on-policy, Eq. (2)), else min(exp(seq_logratio[n]), eta)
+ *   baseline_mode 0:  adv[n] = R_n - (1/N_k) sum_{n' in group(n)} w_n' R_n'
+ *   baseline_mode 1/2: the sum leaves n out; divided by N_k (as printed) / by N_k - 1
+ * group_mean_out / group_std_out [K]: plain mean and population std of R per group (diagnostic;
+ * the paper never divides by the std); group_size_out [K] int32.  Optional outputs may be NULL.
+ * A group with no member gets size 0, mean 0, std 0.
+ */
+int rapid_group_advantage(const float* rewards, const int32_t* group_ids, const float* seq_logratio,
+                          int64_t N, int64_t K, float eta, int baseline_mode, float* adv_out,
+                          float* weight_out, float* group_mean_out, float* group_std_out,
+                          int32_t* group_size_out, int32_t* dev_status, void* stream);
+
+/*
+ * One mini-batch of Alg. 1's IW-GRPG: advantages by Eq. (5), loss and gradients by Eq. (3).
+ *   logp      = as rapid_logprob_fwd on the current W
+ *   s_n       = sum_t mask (logp - logp_behav)            (generation-level log ratio, Sec. 4.3)
+ *   A_n       = rapid_group_advantage(rewards, group_ids, s, eta, baseline_mode)
+ *   loss      = -(loss_scale/N) sum_n c_n A_n,  c_n = exp(s_n)  (coef_mode 0)
+ *   g_n       = -(loss_scale/N) c_n A_n  = d loss / d logp[n,t] for every valid t
+ *   dhidden[n,t,:] = g_n (W[:,y] - W p) / temperature  (0 where mask = 0), dtype of hidden
+ *   dW        = sum_{valid n,t} outer(hidden[n,t,:], g_n (e_y - p)) / temperature, layout w_layout
+ * Optional outputs (NULL to skip): logp_cur_out, tok_logratio_out [N,T]; seq_logratio_out,
+ * adv_out [N]; diag_out.  loss_out [1], dhidden_out [N,T,d] and dW_out are required.
+ */
+int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* tokens,
+                             const uint8_t* mask, const float* logp_behav, const float* rewards,
+                             const int32_t* group_ids, int64_t N, int64_t T, int64_t d, int64_t V,
+                             int64_t K, int dtype, const rapid_iw_pg_opts* opts, float* loss_out,
+                             void* dhidden_out, void* dW_out, float* logp_cur_out,
+                             float* tok_logratio_out, float* seq_logratio_out, float* adv_out,
+                             rapid_iw_pg_diag* diag_out, int32_t* dev_status, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/*
+ * Integer bookkeeping of the padding mask (device outputs, any may be NULL):
+ *   seq_len_out [N] int32, cu_seqlen_out [N+1] int32 (exclusive prefix sum, last = M),
+ *   row_index_out [N*T] int32: the first M entries are the flat positions n*T+t of the valid
+ *   tokens in row-major order.  This is the first step of both calls above, exported so that it
+ *   can be checked bit for bit.
+ */
+int rapid_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len_out,
+                     int32_t* cu_seqlen_out, int32_t* row_index_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAPID_H */

@@ -1,0 +1,444 @@
+// bf16 MFMA contractions of the hot path for gfx950 (CDNA4), one tiled main loop and four
+// epilogues:
+//   fwd_lse : logits tile  -> per-slot (max, sum exp) of the streaming log-softmax + gathered logit
+//   dz      : logits tile  -> dz = g (onehot - softmax) / temperature, written as bf16
+//   dh      : dH = dz . W^T          (contraction over the vocabulary)
+//   dw      : dW (+)= H^T . dz       (contraction over the tokens of a row chunk)
+//
+// Main loop.  C[i][j] = sum_k A[i][k] B[j][k]; both operands are row-major with the contraction
+// index contiguous, zero padded to whole tiles, so the loop has no bounds checks.  A workgroup of
+// four 64-lane waves (2 x 2) owns a (64 WI) x (64 WJ) tile; each wave owns WI x WJ blocks of
+// 32 x 32, computed with v_mfma_f32_32x32x16_bf16 (each lane feeds 8 consecutive k of one row).
+// K advances 64 elements per step through two LDS stages (one barrier per step).  A tile row is
+// 128 bytes = 8 chunks of 16 bytes; chunk c of row r sits at chunk position c ^ (r & 7), which
+// makes the 16-byte fragment reads of 8 consecutive rows hit all banks.  Tiles arrive either by
+// global_load_lds_dwordx4 (DIRECT: memory -> LDS without passing through registers; consecutive
+// lanes fill consecutive 16-byte slots, so the swizzle is applied to the global address) or by
+// ordinary loads staged through registers.
+//
+// Accumulator layout of a 32 x 32 block (lane l, register v): j = l % 32,
+// i = 8 (v / 4) + 4 (l / 32) + v % 4: a lane owns runs of 4 consecutive i for one j, so every
+// epilogue keeps j = the token row (per-lane scalars: lse, coefficient, token id, output row) and
+// stores 4 consecutive i with one 8- or 16-byte access.
+#include "rapid_internal.h"
+
+namespace rapid {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int NT = 256;              // threads per workgroup
+constexpr float LOG2E = 1.4426950408889634f;
+
+template <int WI, int WJ>
+struct Shape {
+    static constexpr int BI = 64 * WI, BJ = 64 * WJ;
+    static constexpr int STAGE_BYTES = (BI + BJ) * 128;
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+};
+
+__device__ inline void lds_barrier() { __syncthreads(); }
+
+// Loads one K step (64 columns) of a tile with ROWS rows into LDS at `lds_tile`.
+template <int ROWS, bool DIRECT>
+__device__ inline void issue_tile_load(const bf16_t* __restrict__ gthread, int64_t ld, char* lds_tile, int wave,
+                                       int lane, uint4 (&stage)[ROWS / 32]) {
+#pragma unroll
+    for (int t = 0; t < ROWS / 32; ++t) {
+        const bf16_t* gp = gthread + (int64_t)(t * 32) * ld;
+        if constexpr (DIRECT) {
+            char* lp = lds_tile + (t * 32 + wave * 8) * 128;   // wave-uniform; lane l lands at +16 l
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                             (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
+        } else {
+            stage[t] = *(const uint4*)gp;
+        }
+    }
+}
+
+template <int ROWS>
+__device__ inline void commit_tile_store(char* lds_tile, int wave, int lane, const uint4 (&stage)[ROWS / 32]) {
+#pragma unroll
+    for (int t = 0; t < ROWS / 32; ++t)
+        *(uint4*)(lds_tile + (t * 32 + wave * 8) * 128 + lane * 16) = stage[t];
+}
+
+// acc += A_tile . B_tile^T over `ktiles` steps of 64.  A / B point at the tile's first row, k = 0.
+template <int WI, int WJ, bool DIRECT>
+__device__ inline void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
+                                int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[WI][WJ]) {
+    using S = Shape<WI, WJ>;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_i = wave & 1, wave_j = wave >> 1;
+
+    // global side of the tile loads: lane l of a wave covers row l/8 (of its 8-row band) and the
+    // chunk that belongs at slot l%8 of that row
+    const int lrow = wave * 8 + (lane >> 3);
+    const int gchunk = (lane & 7) ^ (lane >> 3);
+    const bf16_t* ga = A + (int64_t)lrow * lda + gchunk * 8;
+    const bf16_t* gb = B + (int64_t)lrow * ldb + gchunk * 8;
+
+    // LDS side of the fragment reads
+    const int frow = lane & 31, fhi = lane >> 5;
+    int xo[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) xo[ks] = (((ks * 2 + fhi) ^ (lane & 7)) * 16);
+    const int a_off = (wave_i * (WI * 32) + frow) * 128;
+    const int b_off = S::BI * 128 + (wave_j * (WJ * 32) + frow) * 128;
+
+    uint4 sa[S::BI / 32], sb[S::BJ / 32];
+
+#pragma unroll
+    for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ib][jb][v] = 0.f;
+
+    if (ktiles <= 0) return;
+
+    issue_tile_load<S::BI, DIRECT>(ga, lda, lds, wave, lane, sa);
+    issue_tile_load<S::BJ, DIRECT>(gb, ldb, lds + S::BI * 128, wave, lane, sb);
+    if constexpr (!DIRECT) {
+        commit_tile_store<S::BI>(lds, wave, lane, sa);
+        commit_tile_store<S::BJ>(lds + S::BI * 128, wave, lane, sb);
+    }
+
+    for (int kt = 0; kt < ktiles; ++kt) {
+        char* cur = lds + (kt & 1) * S::STAGE_BYTES;
+        char* nxt = lds + ((kt + 1) & 1) * S::STAGE_BYTES;
+        if constexpr (DIRECT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();   // stage `cur` is complete; nobody still reads stage `nxt`
+        const bool more = kt + 1 < ktiles;
+        if (more) {
+            ga += 64;
+            gb += 64;
+            issue_tile_load<S::BI, DIRECT>(ga, lda, nxt, wave, lane, sa);
+            issue_tile_load<S::BJ, DIRECT>(gb, ldb, nxt + S::BI * 128, wave, lane, sb);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 af[WI], bfr[WJ];
+#pragma unroll
+            for (int ib = 0; ib < WI; ++ib) af[ib] = *(const bf16x8*)(cur + a_off + ib * (32 * 128) + xo[ks]);
+#pragma unroll
+            for (int jb = 0; jb < WJ; ++jb) bfr[jb] = *(const bf16x8*)(cur + b_off + jb * (32 * 128) + xo[ks]);
+#pragma unroll
+            for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+                for (int jb = 0; jb < WJ; ++jb)
+                    acc[ib][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ib], bfr[jb], acc[ib][jb], 0, 0, 0);
+        }
+        if constexpr (!DIRECT) {
+            if (more) {
+                commit_tile_store<S::BI>(nxt, wave, lane, sa);
+                commit_tile_store<S::BJ>(nxt + S::BI * 128, wave, lane, sb);
+            }
+        }
+    }
+}
+
+// Workgroup id -> tile.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs (each
+// with its own L2), so id % 8 picks the XCD and id / 8 the position in that XCD's contiguous share
+// of a grouped order: GI tiles along i for one j, then the next j, ... so that workgroups resident
+// together on an XCD re-use each other's operand panels out of L2.
+struct TileId { int ti, tj; bool valid; };
+__device__ inline TileId map_tile(int pid, int tilesI, int tilesJ, int GI) {
+    const int total = tilesI * tilesJ;
+    const int per = (total + 7) / 8;
+    const int vid = (pid & 7) * per + (pid >> 3);
+    TileId t;
+    t.valid = vid < total;
+    const int group_sz = GI * tilesJ;
+    const int grp = vid / group_sz;
+    const int first_i = grp * GI;
+    const int gi = min(GI, tilesI - first_i);
+    const int rem = vid - grp * group_sz;
+    t.ti = first_i + rem % gi;
+    t.tj = rem / gi;
+    return t;
+}
+inline unsigned grid_for(int tilesI, int tilesJ) { return (unsigned)(((int64_t)tilesI * tilesJ + 7) / 8 * 8); }
+
+struct Lane {
+    int lane, wave_i, wave_j, hi, lj;
+    __device__ inline Lane() {
+        lane = threadIdx.x & 63;
+        const int w = threadIdx.x >> 6;
+        wave_i = w & 1;
+        wave_j = w >> 1;
+        hi = lane >> 5;
+        lj = lane & 31;
+    }
+};
+
+__device__ inline uint2 pack_bf16x4(float a, float b, float c, float d) {
+    bf16x4 r;
+    r[0] = (__bf16)a; r[1] = (__bf16)b; r[2] = (__bf16)c; r[3] = (__bf16)d;
+    return __builtin_bit_cast(uint2, r);
+}
+
+// ------------------------------------------------------------------------------------- fwd_lse
+template <int WI, int WJ, bool DIRECT>
+__global__ __launch_bounds__(NT) void fwd_lse_kernel(FwdArgs a) {
+    using S = Shape<WI, WJ>;
+    extern __shared__ __attribute__((aligned(128))) char lds[];
+    const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, 4);
+    if (!t.valid) return;
+    const int Mr = a.counts[CNT_MR];
+    if ((int64_t)t.tj * S::BJ >= Mr) return;
+    f32x16 acc[WI][WJ];
+    mainloop<WI, WJ, DIRECT>(a.Wvd + (int64_t)t.ti * S::BI * a.dpad, a.dpad,
+                             a.Hc + (int64_t)t.tj * S::BJ * a.dpad, a.dpad, (int)(a.dpad / K_TILE), lds, acc);
+    const Lane L;
+    const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
+    const bool tail = i_base + WI * 32 > a.V;
+    const int64_t slot = (int64_t)t.ti * 2 + L.wave_i;
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) {
+        const int64_t j = (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
+        const int tok = a.tokc[j];
+        float m = -INFINITY, zyv = 0.f;
+        bool found = false;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t i = i_base + ib * 32 + (v >> 2) * 8 + L.hi * 4 + (v & 3);
+                float z = acc[ib][jb][v] * a.inv_temp;
+                if (tail && i >= a.V) z = -INFINITY;
+                acc[ib][jb][v] = z;
+                m = fmaxf(m, z);
+                if (i == tok) { zyv = z; found = true; }
+            }
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        const float mm = (m == -INFINITY) ? 0.f : m;
+        float l = 0.f;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) l += __builtin_amdgcn_exp2f((acc[ib][jb][v] - mm) * LOG2E);
+        l += __shfl_xor(l, 32, 64);
+        if (L.hi == 0) {
+            a.part_max[slot * a.ld_part + j] = m;
+            a.part_sum[slot * a.ld_part + j] = l;
+        }
+        if (found) a.zy[j] = zyv;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ dz
+template <int WI, int WJ, bool DIRECT>
+__global__ __launch_bounds__(NT) void dz_kernel(DzArgs a) {
+    using S = Shape<WI, WJ>;
+    extern __shared__ __attribute__((aligned(128))) char lds[];
+    const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, 4);
+    if (!t.valid) return;
+    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
+    if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
+    f32x16 acc[WI][WJ];
+    mainloop<WI, WJ, DIRECT>(a.Wvd + (int64_t)t.ti * S::BI * a.dpad, a.dpad,
+                             a.Hc + (int64_t)t.tj * S::BJ * a.dpad, a.dpad, (int)(a.dpad / K_TILE), lds, acc);
+    const Lane L;
+    const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) {
+        const int64_t jl = (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32) + jb * 32 + L.lj;   // row in chunk
+        const int64_t j = a.m0 + jl;
+        const bool live = j < M;
+        const int tok = a.tokc[j];
+        const float gj = live ? a.g[a.seqc[j]] * a.inv_temp : 0.f;
+        const float nlse = live ? -a.lse_c[j] * LOG2E : 0.f;
+        const float zs = a.inv_temp * LOG2E;
+        bf16_t* out = a.dz + jl * a.Vpad;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t i0 = i_base + ib * 32 + q * 8 + L.hi * 4;
+                float o[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int64_t i = i0 + r;
+                    const float p = __builtin_amdgcn_exp2f(fmaf(acc[ib][jb][q * 4 + r], zs, nlse));
+                    float val = gj * ((i == tok ? 1.f : 0.f) - p);
+                    if (!live || i >= a.V) val = 0.f;
+                    o[r] = val;
+                }
+                *(uint2*)(out + i0) = pack_bf16x4(o[0], o[1], o[2], o[3]);
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ dh
+template <int WI, int WJ, bool DIRECT>
+__global__ __launch_bounds__(NT) void dh_kernel(DhArgs a) {
+    using S = Shape<WI, WJ>;
+    extern __shared__ __attribute__((aligned(128))) char lds[];
+    const int tilesD = (int)(a.dpadR / S::BI);
+    const TileId t = map_tile(blockIdx.x, tilesD, a.tilesM, tilesD);
+    if (!t.valid) return;
+    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
+    if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
+    f32x16 acc[WI][WJ];
+    mainloop<WI, WJ, DIRECT>(a.Wdv + (int64_t)t.ti * S::BI * a.Vpad, a.Vpad,
+                             a.dz + (int64_t)t.tj * S::BJ * a.Vpad, a.Vpad, (int)(a.Vpad / K_TILE), lds, acc);
+    const Lane L;
+    const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) {
+        const int64_t j = a.m0 + (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
+        if (j >= M) continue;
+        bf16_t* out = a.dhidden + (int64_t)a.row_index[j] * a.d;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t i0 = i_base + ib * 32 + q * 8 + L.hi * 4;
+                if (i0 < a.d)
+                    *(uint2*)(out + i0) = pack_bf16x4(acc[ib][jb][q * 4], acc[ib][jb][q * 4 + 1],
+                                                      acc[ib][jb][q * 4 + 2], acc[ib][jb][q * 4 + 3]);
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ dw
+template <int WI, int WJ, bool DIRECT>
+__global__ __launch_bounds__(NT) void dw_kernel(DwArgs a) {
+    using S = Shape<WI, WJ>;
+    extern __shared__ __attribute__((aligned(128))) char lds[];
+    const int tilesV = (int)(a.Vpad / S::BI), tilesD = (int)(a.dpadR / S::BJ);
+    const TileId t = map_tile(blockIdx.x, tilesV, tilesD, 8);
+    if (!t.valid) return;
+    const int Mr = a.counts[CNT_MR];
+    int64_t rows = (int64_t)Mr - a.m0;
+    rows = rows < 0 ? 0 : (rows > a.Mc ? a.Mc : rows);
+    if (rows == 0 && a.beta) return;   // nothing to add
+    f32x16 acc[WI][WJ];
+    mainloop<WI, WJ, DIRECT>(a.dzT + (int64_t)t.ti * S::BI * a.Mc, a.Mc,
+                             a.HcT + (int64_t)t.tj * S::BJ * a.ldH, a.ldH, (int)(rows / K_TILE), lds, acc);
+    const Lane L;
+    const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
+    const bool vec = (a.V % 4) == 0;
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) {
+        const int64_t jd = (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
+        if (jd >= a.d) continue;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t i0 = i_base + ib * 32 + q * 8 + L.hi * 4;
+                if (i0 >= a.V) continue;
+                float o[4] = {acc[ib][jb][q * 4], acc[ib][jb][q * 4 + 1], acc[ib][jb][q * 4 + 2],
+                              acc[ib][jb][q * 4 + 3]};
+                if (a.w_layout == RAPID_W_DV) {
+                    float* p = a.dW + jd * a.V + i0;
+                    if (vec) {
+                        float4 cur = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (a.beta) cur = *(const float4*)p;
+                        *(float4*)p = make_float4(cur.x + o[0], cur.y + o[1], cur.z + o[2], cur.w + o[3]);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (i0 + r < a.V) p[r] = (a.beta ? p[r] : 0.f) + o[r];
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (i0 + r < a.V) {
+                            float* p = a.dW + (i0 + r) * a.d + jd;
+                            *p = (a.beta ? *p : 0.f) + o[r];
+                        }
+                }
+            }
+    }
+}
+
+template <class K>
+void allow_lds(K kernel, int bytes) {
+    (void)hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+}  // namespace
+
+// variant: 0 = tiles staged through registers, 1 = direct global -> LDS loads
+void launch_fwd_lse(const FwdArgs& a, int variant, hipStream_t st) {
+    using S = Shape<4, 4>;
+    const unsigned grid = grid_for(a.tilesV, a.tilesM);
+    if (variant == 1) {
+        allow_lds(fwd_lse_kernel<4, 4, true>, S::LDS_BYTES);
+        fwd_lse_kernel<4, 4, true><<<grid, NT, S::LDS_BYTES, st>>>(a);
+    } else {
+        allow_lds(fwd_lse_kernel<4, 4, false>, S::LDS_BYTES);
+        fwd_lse_kernel<4, 4, false><<<grid, NT, S::LDS_BYTES, st>>>(a);
+    }
+}
+int fwd_slots_per_tile() { return 2; }
+
+void launch_dz(const DzArgs& a, int variant, hipStream_t st) {
+    using S = Shape<4, 4>;
+    const unsigned grid = grid_for(a.tilesV, a.tilesM);
+    if (variant == 1) {
+        allow_lds(dz_kernel<4, 4, true>, S::LDS_BYTES);
+        dz_kernel<4, 4, true><<<grid, NT, S::LDS_BYTES, st>>>(a);
+    } else {
+        allow_lds(dz_kernel<4, 4, false>, S::LDS_BYTES);
+        dz_kernel<4, 4, false><<<grid, NT, S::LDS_BYTES, st>>>(a);
+    }
+}
+
+void launch_dh(const DhArgs& a, int variant, hipStream_t st) {
+    if (a.dpadR % 256 == 0) {
+        using S = Shape<4, 4>;
+        const unsigned grid = grid_for((int)(a.dpadR / S::BI), a.tilesM);
+        if (variant == 1) {
+            allow_lds(dh_kernel<4, 4, true>, S::LDS_BYTES);
+            dh_kernel<4, 4, true><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        } else {
+            allow_lds(dh_kernel<4, 4, false>, S::LDS_BYTES);
+            dh_kernel<4, 4, false><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        }
+    } else {   // d padded to a multiple of 128 only
+        using S = Shape<2, 4>;
+        const unsigned grid = grid_for((int)(a.dpadR / S::BI), a.tilesM);
+        if (variant == 1) {
+            allow_lds(dh_kernel<2, 4, true>, S::LDS_BYTES);
+            dh_kernel<2, 4, true><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        } else {
+            allow_lds(dh_kernel<2, 4, false>, S::LDS_BYTES);
+            dh_kernel<2, 4, false><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        }
+    }
+}
+
+void launch_dw(const DwArgs& a, int variant, hipStream_t st) {
+    if (a.dpadR % 256 == 0) {
+        using S = Shape<4, 4>;
+        const unsigned grid = grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ));
+        if (variant == 1) {
+            allow_lds(dw_kernel<4, 4, true>, S::LDS_BYTES);
+            dw_kernel<4, 4, true><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        } else {
+            allow_lds(dw_kernel<4, 4, false>, S::LDS_BYTES);
+            dw_kernel<4, 4, false><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        }
+    } else {
+        using S = Shape<4, 2>;
+        const unsigned grid = grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ));
+        if (variant == 1) {
+            allow_lds(dw_kernel<4, 2, true>, S::LDS_BYTES);
+            dw_kernel<4, 2, true><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        } else {
+            allow_lds(dw_kernel<4, 2, false>, S::LDS_BYTES);
+            dw_kernel<4, 2, false><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        }
+    }
+}
+
+}  // namespace rapid

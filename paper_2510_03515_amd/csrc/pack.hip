@@ -1,0 +1,91 @@
+// Operand packing for the MFMA kernels: every contraction reads zero-padded, tile-aligned bf16
+// matrices whose contraction index is contiguous, so the hot loops need no bounds checks.  These
+// kernels are pure HBM copies (read once, write once).
+#include "rapid_internal.h"
+
+namespace rapid {
+
+namespace {
+
+struct RowLimits { int64_t R, Rpad; };
+
+__device__ inline RowLimits row_limits(const int32_t* counts, int64_t r0, int64_t R, int64_t Rpad) {
+    if (!counts) return {R, Rpad};
+    int64_t m = (int64_t)counts[CNT_M] - r0, mr = (int64_t)counts[CNT_MR] - r0;
+    m = m < 0 ? 0 : (m > R ? R : m);
+    mr = mr < 0 ? 0 : (mr > Rpad ? Rpad : mr);
+    return {m, mr};
+}
+
+// one block per destination row; 16-byte chunks (ld_dst, Cpad multiples of 8; src rows 16 B aligned
+// when C % 8 == 0, otherwise the element path is taken)
+__global__ void copy_pad_bf16_kernel(const bf16_t* __restrict__ src, int64_t ld_src,
+                                     const int32_t* __restrict__ row_index, bf16_t* __restrict__ dst,
+                                     int64_t ld_dst, int64_t R, int64_t C, int64_t Rpad, int64_t Cpad,
+                                     const int32_t* __restrict__ counts, int64_t r0, int vec_ok) {
+    const RowLimits lim = row_limits(counts, r0, R, Rpad);
+    const int64_t r = blockIdx.x;
+    if (r >= lim.Rpad) return;
+    bf16_t* drow = dst + r * ld_dst;
+    const bool live = r < lim.R;
+    const bf16_t* srow = nullptr;
+    if (live) {
+        const int64_t sr = row_index ? (int64_t)row_index[r0 + r] : r;
+        srow = src + sr * ld_src;
+    }
+    if (vec_ok) {
+        const int64_t chunks = Cpad / 8, live_chunks = C / 8;
+        for (int64_t c = threadIdx.x; c < chunks; c += blockDim.x) {
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (live && c < live_chunks) v = *(const uint4*)(srow + c * 8);
+            *(uint4*)(drow + c * 8) = v;
+        }
+    } else {
+        for (int64_t c = threadIdx.x; c < Cpad; c += blockDim.x)
+            drow[c] = (live && c < C) ? srow[c] : (bf16_t)0;
+    }
+}
+
+// 64x64 tile through LDS: dst[c][r] = src[r][c]
+__global__ void transpose_pad_bf16_kernel(const bf16_t* __restrict__ src, int64_t ld_src,
+                                          bf16_t* __restrict__ dst, int64_t ld_dst, int64_t R, int64_t C,
+                                          int64_t Rpad, int64_t Cpad, const int32_t* __restrict__ counts,
+                                          int64_t r0) {
+    __shared__ bf16_t tile[64][66];
+    const RowLimits lim = row_limits(counts, r0, R, Rpad);
+    const int64_t rb = (int64_t)blockIdx.x * 64, cb = (int64_t)blockIdx.y * 64;
+    if (rb >= lim.Rpad) return;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 256 threads: 64 x 4
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int64_t r = rb + rr, c = cb + tx;
+        bf16_t v = 0;
+        if (r < lim.R && c < C) v = src[r * ld_src + c];
+        tile[rr][tx] = v;
+    }
+    __syncthreads();
+    for (int cc = ty; cc < 64; cc += 4) {
+        const int64_t c = cb + cc, r = rb + tx;
+        if (c < Cpad && r < lim.Rpad) dst[c * ld_dst + r] = tile[tx][cc];
+    }
+}
+
+}  // namespace
+
+void launch_copy_pad_bf16(const bf16_t* src, int64_t ld_src, const int32_t* row_index, bf16_t* dst,
+                          int64_t ld_dst, int64_t R, int64_t C, int64_t Rpad, int64_t Cpad,
+                          const int32_t* counts, int64_t r0, hipStream_t st) {
+    if (Rpad <= 0) return;
+    const int vec_ok = (C % 8 == 0) && (ld_src % 8 == 0) && (((uintptr_t)src) % 16 == 0);
+    copy_pad_bf16_kernel<<<(unsigned)Rpad, 256, 0, st>>>(src, ld_src, row_index, dst, ld_dst, R, C, Rpad, Cpad,
+                                                         counts, r0, vec_ok);
+}
+
+void launch_transpose_pad_bf16(const bf16_t* src, int64_t ld_src, bf16_t* dst, int64_t ld_dst, int64_t R,
+                               int64_t C, int64_t Rpad, int64_t Cpad, const int32_t* counts, int64_t r0,
+                               hipStream_t st) {
+    if (Rpad <= 0 || Cpad <= 0) return;
+    dim3 grid((unsigned)((Rpad + 63) / 64), (unsigned)((Cpad + 63) / 64));
+    transpose_pad_bf16_kernel<<<grid, 256, 0, st>>>(src, ld_src, dst, ld_dst, R, C, Rpad, Cpad, counts, r0);
+}
+
+}  // namespace rapid

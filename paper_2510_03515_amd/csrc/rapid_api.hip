@@ -1,0 +1,514 @@
+// Host side of the C ABI declared in rapid.h: argument validation, workspace planning and the
+// order of kernel launches.  No device memory is allocated here and nothing synchronises.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <cmath>
+
+#include "rapid_internal.h"
+
+namespace rapid {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+int g_load_variant = 1;   // 1: direct global -> LDS tile loads, 0: staged through registers
+
+struct Plan {
+    int op, dtype;
+    int64_t N, T, d, V, K;
+    int64_t Mmax, Mmax_pad, dpad, dpadR, Vpad;
+    int P;              // log-sum-exp partial slots per row
+    int64_t Mc;         // rows per backward chunk (f32: also per forward chunk)
+    size_t per_row;     // chunk bytes per row
+    size_t fixed, total;
+    // offsets into the workspace
+    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, logp_tmp, s64, s32, adv, g, Hc, HcT, Wvd, Wdv,
+        part_max, part_sum, dw32, chunk0, chunk1;
+};
+
+size_t take(size_t& cur, size_t bytes) {
+    const size_t at = cur;
+    cur += (bytes + 255) / 256 * 256;
+    return at;
+}
+
+// lays the workspace out; chunk sizing is done by the caller through `avail`
+bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
+    memset(&p, 0, sizeof(p));
+    if (N <= 0 || T <= 0 || d <= 0 || V <= 0) return false;
+    if (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) return false;
+    if (N * T > (int64_t)2000000000 || V > (int64_t)2000000000 || d > 65536 || N > (int64_t)2000000000)
+        return false;
+    if (op == RAPID_OP_IW_PG_FWD_BWD && K <= 0) return false;
+    p.op = op; p.dtype = dtype; p.N = N; p.T = T; p.d = d; p.V = V; p.K = K;
+    p.Mmax = N * T;
+    p.Mmax_pad = round_up(p.Mmax, ROW_TILE);
+    p.dpad = round_up(d, K_TILE);
+    p.dpadR = round_up(d, 128);
+    p.Vpad = round_up(V, 256);
+    p.P = (int)(p.Vpad / 256) * fwd_slots_per_tile();
+    const bool bwd = op == RAPID_OP_IW_PG_FWD_BWD;
+    size_t cur = 0;
+    p.counts = take(cur, CNT_WORDS * 4);
+    p.seq_len = take(cur, (size_t)N * 4);
+    p.cu = take(cur, (size_t)(N + 1) * 4);
+    p.row_index = take(cur, (size_t)p.Mmax_pad * 4);
+    p.tokc = take(cur, (size_t)p.Mmax_pad * 4);
+    p.seqc = take(cur, (size_t)p.Mmax_pad * 4);
+    p.zy = take(cur, (size_t)p.Mmax_pad * 4);
+    p.lse_c = take(cur, (size_t)p.Mmax_pad * 4);
+    if (bwd) {
+        p.logp_tmp = take(cur, (size_t)p.Mmax * 4);
+        p.s64 = take(cur, (size_t)N * 8);
+        p.s32 = take(cur, (size_t)N * 4);
+        p.adv = take(cur, (size_t)N * 4);
+        p.g = take(cur, (size_t)N * 4);
+        p.dw32 = take(cur, (size_t)d * V * 4);
+    }
+    if (dtype == RAPID_DTYPE_BF16) {
+        p.Hc = take(cur, (size_t)p.Mmax_pad * p.dpad * 2);
+        p.Wvd = take(cur, (size_t)p.Vpad * p.dpad * 2);
+        p.part_max = take(cur, (size_t)p.P * p.Mmax_pad * 4);
+        p.part_sum = take(cur, (size_t)p.P * p.Mmax_pad * 4);
+        if (bwd) {
+            p.HcT = take(cur, (size_t)p.dpadR * p.Mmax_pad * 2);
+            p.Wdv = take(cur, (size_t)p.dpadR * p.Vpad * 2);
+            p.per_row = (size_t)p.Vpad * 2 * 2;   // dz and its transpose
+        }
+    } else {
+        p.per_row = (size_t)V * 4;                // logits / dz chunk
+    }
+    p.fixed = cur;
+    return true;
+}
+
+void size_chunks(Plan& p, int64_t Mc) {
+    Mc = Mc / ROW_TILE * ROW_TILE;
+    if (Mc < ROW_TILE) Mc = ROW_TILE;
+    if (Mc > p.Mmax_pad) Mc = p.Mmax_pad;
+    p.Mc = Mc;
+    size_t cur = p.fixed;
+    if (p.per_row) {
+        if (p.dtype == RAPID_DTYPE_BF16) {
+            p.chunk0 = take(cur, (size_t)Mc * p.Vpad * 2);
+            p.chunk1 = take(cur, (size_t)Mc * p.Vpad * 2);
+        } else {
+            p.chunk0 = take(cur, (size_t)Mc * p.V * 4);
+        }
+    }
+    p.total = cur;
+}
+
+int64_t recommended_chunk(const Plan& p) { return p.dtype == RAPID_DTYPE_BF16 ? 65536 : 4096; }
+
+// largest chunk that fits into `avail` bytes; 0 if even the minimum does not
+int64_t fit_chunk(const Plan& p, size_t avail) {
+    if (!p.per_row) return avail >= p.fixed ? ROW_TILE : 0;
+    if (avail < p.fixed + 1024) return 0;
+    int64_t Mc = (int64_t)((avail - p.fixed - 1024) / p.per_row) / ROW_TILE * ROW_TILE;
+    if (Mc > p.Mmax_pad) Mc = p.Mmax_pad;
+    return Mc;
+}
+
+int check_arch() {
+    static thread_local int cached_dev = -1, cached_rc = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        set_error("hipGetDevice failed");
+        return RAPID_ERR_HIP;
+    }
+    if (dev == cached_dev) return cached_rc;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+        set_error("hipGetDeviceProperties failed");
+        return RAPID_ERR_HIP;
+    }
+    cached_dev = dev;
+    cached_rc = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? RAPID_OK : RAPID_ERR_ARCH;
+    if (cached_rc != RAPID_OK) set_error("device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
+    return cached_rc;
+}
+
+int check_launch(const char* what) {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("%s: %s", what, hipGetErrorString(e));
+        return RAPID_ERR_HIP;
+    }
+    return RAPID_OK;
+}
+
+template <class T>
+T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
+
+struct FwdIo {
+    const void* hidden; const void* W; const int32_t* tokens; const uint8_t* mask;
+    int w_layout; float temperature;
+    float* logp_out; float* lse_out; int32_t* dev_status;
+};
+
+// compaction, operand packing and the streaming log-softmax forward; leaves lse_c, tokc, seqc,
+// row_index, counts (and for bf16 Hc, Wvd) in the workspace for the backward
+void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
+    int32_t* counts = at<int32_t>(ws, p.counts);
+    int32_t* row_index = at<int32_t>(ws, p.row_index);
+    int32_t* tokc = at<int32_t>(ws, p.tokc);
+    int32_t* seqc = at<int32_t>(ws, p.seqc);
+    float* lse_c = at<float>(ws, p.lse_c);
+    const float inv_temp = 1.0f / io.temperature;
+    launch_compaction(io.mask, p.N, p.T, at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), row_index, counts, st);
+    launch_gather_tokens(io.tokens, row_index, counts, p.Mmax_pad, p.T, p.V, tokc, seqc, io.dev_status, st);
+    launch_fill_f32(io.logp_out, p.Mmax, 0.f, st);
+    if (io.lse_out) launch_fill_f32(io.lse_out, p.Mmax, 0.f, st);
+    if (p.dtype == RAPID_DTYPE_BF16) {
+        bf16_t* Hc = at<bf16_t>(ws, p.Hc);
+        bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
+        launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc, p.dpad, p.Mmax, p.d, p.Mmax_pad, p.dpad,
+                             counts, 0, st);
+        if (io.w_layout == RAPID_W_VD)
+            launch_copy_pad_bf16((const bf16_t*)io.W, p.d, nullptr, Wvd, p.dpad, p.V, p.d, p.Vpad, p.dpad, nullptr, 0, st);
+        else
+            launch_transpose_pad_bf16((const bf16_t*)io.W, p.V, Wvd, p.dpad, p.d, p.V, p.dpad, p.Vpad, nullptr, 0, st);
+        FwdArgs a;
+        a.Wvd = Wvd; a.Hc = Hc; a.dpad = p.dpad;
+        a.tilesV = (int)(p.Vpad / 256); a.tilesM = (int)(p.Mmax_pad / 256);
+        a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
+        a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
+        a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy);
+        launch_fwd_lse(a, g_load_variant, st);
+        launch_merge_lse(a.part_max, a.part_sum, p.P, a.ld_part, a.zy, row_index, counts, p.Mmax_pad, lse_c,
+                         io.logp_out, io.lse_out, st);
+    } else {
+        float* z = at<float>(ws, p.chunk0);
+        for (int64_t m0 = 0; m0 < p.Mmax; m0 += p.Mc) {
+            const int64_t rows = (p.Mmax - m0) < p.Mc ? (p.Mmax - m0) : p.Mc;
+            F32Gemm g;
+            memset(&g, 0, sizeof(g));
+            g.A = (const float*)io.hidden; g.sa_i = p.d; g.sa_k = 1; g.a_imap = row_index;
+            g.B = (const float*)io.W;
+            if (io.w_layout == RAPID_W_DV) { g.sb_k = p.V; g.sb_j = 1; } else { g.sb_k = 1; g.sb_j = p.d; }
+            g.C = z; g.sc_i = p.V; g.sc_j = 1;
+            g.I = rows; g.J = p.V; g.Kd = p.d; g.beta = 0; g.counts = counts; g.i0 = m0; g.limit_k = 0;
+            g.alpha = inv_temp;
+            launch_f32_gemm(g, st);
+            launch_f32_row_lse(z, p.V, rows, m0, tokc, row_index, counts, lse_c, io.logp_out, io.lse_out, st);
+        }
+    }
+}
+
+int validate_common(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask, int64_t d,
+                    int dtype, int w_layout, float temperature, void* workspace) {
+    if (!hidden || !W || !tokens || !mask) {
+        set_error("hidden, W, tokens and mask must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    if (w_layout != RAPID_W_DV && w_layout != RAPID_W_VD) {
+        set_error("unknown w_layout %d", w_layout);
+        return RAPID_ERR_DTYPE;
+    }
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) {
+        set_error("temperature must be finite and > 0");
+        return RAPID_ERR_SHAPE;
+    }
+    if (dtype == RAPID_DTYPE_BF16 && d % 8 != 0) {
+        set_error("bf16 needs d %% 8 == 0 (got d = %lld)", (long long)d);
+        return RAPID_ERR_SHAPE;
+    }
+    if (((uintptr_t)hidden | (uintptr_t)W) % 16 != 0) {
+        set_error("hidden and W must be 16-byte aligned");
+        return RAPID_ERR_SHAPE;
+    }
+    if (!workspace || ((uintptr_t)workspace) % 256 != 0) {
+        set_error("workspace must be non-NULL and 256-byte aligned");
+        return RAPID_ERR_WORKSPACE;
+    }
+    return RAPID_OK;
+}
+
+}  // namespace
+}  // namespace rapid
+
+using namespace rapid;
+
+extern "C" {
+
+int rapid_version(void) { return 1; }
+
+const char* rapid_last_error(void) { return g_err; }
+
+void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
+    if (!o) return;
+    memset(o, 0, sizeof(*o));
+    o->eta = 2.0f;
+    o->coef_mode = 0;
+    o->baseline_mode = 0;
+    o->loss_scale = 1.0f;
+    o->temperature = 1.0f;
+    o->w_layout = RAPID_W_DV;
+    o->dw_dtype = RAPID_DTYPE_F32;
+    o->accumulate_dw = 0;
+    o->normalized_grads = 0;
+    o->coef_override = nullptr;
+}
+
+int rapid_set_tuning(int key, int value) {
+    if (key == 0 && (value == 0 || value == 1)) {
+        g_load_variant = value;
+        return RAPID_OK;
+    }
+    set_error("unknown tuning key/value %d/%d", key, value);
+    return RAPID_ERR_DTYPE;
+}
+
+size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
+    if (op == RAPID_OP_GROUP_ADVANTAGE) return 0;
+    if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
+    Plan p;
+    if (!make_plan(p, op, N, T, d, V, K, dtype)) return 0;
+    size_chunks(p, recommended_chunk(p));
+    return p.total + 1024;
+}
+
+size_t rapid_workspace_min_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
+    if (op == RAPID_OP_GROUP_ADVANTAGE) return 0;
+    if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
+    Plan p;
+    if (!make_plan(p, op, N, T, d, V, K, dtype)) return 0;
+    size_chunks(p, ROW_TILE);
+    return p.total + 1024;
+}
+
+int rapid_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len_out, int32_t* cu_seqlen_out,
+                     int32_t* row_index_out, void* stream) {
+    if (!mask || !seq_len_out || !cu_seqlen_out) {
+        set_error("mask, seq_len_out and cu_seqlen_out must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    if (N <= 0 || T <= 0 || N * T > (int64_t)2000000000) {
+        set_error("bad shape N=%lld T=%lld", (long long)N, (long long)T);
+        return RAPID_ERR_SHAPE;
+    }
+    int rc = check_arch();
+    if (rc) return rc;
+    launch_compaction(mask, N, T, seq_len_out, cu_seqlen_out, row_index_out, nullptr, (hipStream_t)stream);
+    return check_launch("rapid_compaction");
+}
+
+int rapid_logprob_fwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask, int64_t N,
+                      int64_t T, int64_t d, int64_t V, int dtype, int w_layout, float temperature, float* logp_out,
+                      float* lse_out, int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream) {
+    Plan p;
+    if (!make_plan(p, RAPID_OP_LOGPROB_FWD, N, T, d, V, 1, dtype)) {
+        set_error("bad shape/dtype N=%lld T=%lld d=%lld V=%lld dtype=%d", (long long)N, (long long)T, (long long)d,
+                  (long long)V, dtype);
+        return (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) ? RAPID_ERR_DTYPE : RAPID_ERR_SHAPE;
+    }
+    int rc = validate_common(hidden, W, tokens, mask, d, dtype, w_layout, temperature, workspace);
+    if (rc) return rc;
+    if (!logp_out) {
+        set_error("logp_out must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    const int64_t Mc = fit_chunk(p, workspace_bytes);
+    if (Mc < ROW_TILE) {
+        set_error("workspace of %zu bytes is below the minimum %zu", workspace_bytes,
+                  rapid_workspace_min_bytes(RAPID_OP_LOGPROB_FWD, N, T, d, V, 1, dtype));
+        return RAPID_ERR_WORKSPACE;
+    }
+    size_chunks(p, Mc < recommended_chunk(p) ? Mc : recommended_chunk(p));
+    rc = check_arch();
+    if (rc) return rc;
+    FwdIo io{hidden, W, tokens, mask, w_layout, temperature, logp_out, lse_out, dev_status};
+    run_forward(p, workspace, io, (hipStream_t)stream);
+    return check_launch("rapid_logprob_fwd");
+}
+
+int rapid_group_advantage(const float* rewards, const int32_t* group_ids, const float* seq_logratio, int64_t N,
+                          int64_t K, float eta, int baseline_mode, float* adv_out, float* weight_out,
+                          float* group_mean_out, float* group_std_out, int32_t* group_size_out, int32_t* dev_status,
+                          void* stream) {
+    if (!rewards || !group_ids || !adv_out) {
+        set_error("rewards, group_ids and adv_out must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    if (N <= 0 || K <= 0 || N > (int64_t)2000000000 || K > (int64_t)2000000000) {
+        set_error("bad shape N=%lld K=%lld", (long long)N, (long long)K);
+        return RAPID_ERR_SHAPE;
+    }
+    if (baseline_mode < 0 || baseline_mode > 2) {
+        set_error("unknown baseline_mode %d", baseline_mode);
+        return RAPID_ERR_DTYPE;
+    }
+    if (!(eta > 0.f)) {
+        set_error("eta must be > 0 (inf allowed)");
+        return RAPID_ERR_SHAPE;
+    }
+    int rc = check_arch();
+    if (rc) return rc;
+    launch_group_advantage(rewards, group_ids, seq_logratio, N, K, eta, baseline_mode, adv_out, weight_out,
+                           group_mean_out, group_std_out, group_size_out, dev_status, (hipStream_t)stream);
+    return check_launch("rapid_group_advantage");
+}
+
+int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
+                             const float* logp_behav, const float* rewards, const int32_t* group_ids, int64_t N,
+                             int64_t T, int64_t d, int64_t V, int64_t K, int dtype, const rapid_iw_pg_opts* opts,
+                             float* loss_out, void* dhidden_out, void* dW_out, float* logp_cur_out,
+                             float* tok_logratio_out, float* seq_logratio_out, float* adv_out,
+                             rapid_iw_pg_diag* diag_out, int32_t* dev_status, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    rapid_iw_pg_opts o;
+    if (opts) o = *opts; else rapid_iw_pg_default_opts(&o);
+    Plan p;
+    if (!make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype)) {
+        set_error("bad shape/dtype N=%lld T=%lld d=%lld V=%lld K=%lld dtype=%d", (long long)N, (long long)T,
+                  (long long)d, (long long)V, (long long)K, dtype);
+        return (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) ? RAPID_ERR_DTYPE : RAPID_ERR_SHAPE;
+    }
+    int rc = validate_common(hidden, W, tokens, mask, d, dtype, o.w_layout, o.temperature, workspace);
+    if (rc) return rc;
+    if (!logp_behav || !rewards || !group_ids || !loss_out || !dhidden_out || !dW_out) {
+        set_error("logp_behav, rewards, group_ids, loss_out, dhidden_out and dW_out must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    if (o.coef_mode < 0 || o.coef_mode > 1 || o.baseline_mode < 0 || o.baseline_mode > 2 ||
+        (o.dw_dtype != RAPID_DTYPE_F32 && o.dw_dtype != RAPID_DTYPE_BF16)) {
+        set_error("unknown coef_mode / baseline_mode / dw_dtype");
+        return RAPID_ERR_DTYPE;
+    }
+    if (!(o.eta > 0.f) || !(o.loss_scale > 0.f) || !std::isfinite(o.loss_scale)) {
+        set_error("eta must be > 0 (inf allowed) and loss_scale finite and > 0");
+        return RAPID_ERR_SHAPE;
+    }
+    if (o.accumulate_dw && o.dw_dtype != RAPID_DTYPE_F32) {
+        set_error("accumulate_dw needs an fp32 dW");
+        return RAPID_ERR_DTYPE;
+    }
+    if (((uintptr_t)dhidden_out | (uintptr_t)dW_out) % 16 != 0) {
+        set_error("dhidden_out and dW_out must be 16-byte aligned");
+        return RAPID_ERR_SHAPE;
+    }
+    const int64_t Mfit = fit_chunk(p, workspace_bytes);
+    if (Mfit < ROW_TILE) {
+        set_error("workspace of %zu bytes is below the minimum %zu", workspace_bytes,
+                  rapid_workspace_min_bytes(RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype));
+        return RAPID_ERR_WORKSPACE;
+    }
+    size_chunks(p, Mfit);
+    rc = check_arch();
+    if (rc) return rc;
+
+    hipStream_t st = (hipStream_t)stream;
+    void* ws = workspace;
+    int32_t* counts = at<int32_t>(ws, p.counts);
+    int32_t* row_index = at<int32_t>(ws, p.row_index);
+    int32_t* tokc = at<int32_t>(ws, p.tokc);
+    int32_t* seqc = at<int32_t>(ws, p.seqc);
+    float* lse_c = at<float>(ws, p.lse_c);
+    float* logp_cur = logp_cur_out ? logp_cur_out : at<float>(ws, p.logp_tmp);
+    double* s64 = at<double>(ws, p.s64);
+    float* s32 = seq_logratio_out ? seq_logratio_out : at<float>(ws, p.s32);
+    float* adv = adv_out ? adv_out : at<float>(ws, p.adv);
+    float* g = at<float>(ws, p.g);
+    const float inv_temp = 1.0f / o.temperature;
+
+    // forward: current-policy log-probs of the sampled tokens
+    FwdIo io{hidden, W, tokens, mask, o.w_layout, o.temperature, logp_cur, nullptr, dev_status};
+    run_forward(p, ws, io, st);
+
+    // generation-level log ratios, clipped-weight group baseline, coefficients and loss
+    launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, dev_status, st);
+    launch_group_advantage(rewards, group_ids, s32, N, K, o.eta, o.baseline_mode, adv, nullptr, nullptr, nullptr,
+                           nullptr, dev_status, st);
+    launch_coefficients(s64, adv, o.coef_override, N, o.eta, o.coef_mode, o.loss_scale, o.normalized_grads, counts,
+                        g, loss_out, diag_out, st);
+
+    // backward, in row chunks
+    const int elem = dtype == RAPID_DTYPE_BF16 ? 2 : 4;
+    launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, st);
+    const bool dw_staged = o.dw_dtype == RAPID_DTYPE_BF16;
+    float* dW32 = dw_staged ? at<float>(ws, p.dw32) : (float*)dW_out;
+
+    if (dtype == RAPID_DTYPE_BF16) {
+        bf16_t* Hc = at<bf16_t>(ws, p.Hc);
+        bf16_t* HcT = at<bf16_t>(ws, p.HcT);
+        bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
+        bf16_t* Wdv = at<bf16_t>(ws, p.Wdv);
+        bf16_t* dz = at<bf16_t>(ws, p.chunk0);
+        bf16_t* dzT = at<bf16_t>(ws, p.chunk1);
+        launch_transpose_pad_bf16(Hc, p.dpad, HcT, p.Mmax_pad, p.Mmax, p.dpad, p.Mmax_pad, p.dpadR, counts, 0, st);
+        if (o.w_layout == RAPID_W_DV)
+            launch_copy_pad_bf16((const bf16_t*)W, p.V, nullptr, Wdv, p.Vpad, p.d, p.V, p.dpadR, p.Vpad, nullptr, 0, st);
+        else
+            launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.Vpad, p.V, p.d, p.Vpad, p.dpadR, nullptr, 0, st);
+        int chunk = 0;
+        for (int64_t m0 = 0; m0 < p.Mmax_pad; m0 += p.Mc, ++chunk) {
+            const int64_t rows = (p.Mmax_pad - m0) < p.Mc ? (p.Mmax_pad - m0) : p.Mc;   // multiple of 256
+            DzArgs za;
+            za.Wvd = Wvd; za.Hc = Hc + m0 * p.dpad; za.dpad = p.dpad;
+            za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
+            za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
+            za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz;
+            launch_dz(za, g_load_variant, st);
+            launch_transpose_pad_bf16(dz, p.Vpad, dzT, p.Mc, rows, p.Vpad, rows, p.Vpad, counts, m0, st);
+            DhArgs ha;
+            ha.Wdv = Wdv; ha.dz = dz; ha.Vpad = p.Vpad; ha.d = p.d; ha.dpadR = p.dpadR;
+            ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
+            ha.dhidden = (bf16_t*)dhidden_out;
+            launch_dh(ha, g_load_variant, st);
+            DwArgs wa;
+            wa.dzT = dzT; wa.HcT = HcT + m0; wa.Mc = p.Mc; wa.ldH = p.Mmax_pad;
+            wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = m0; wa.counts = counts;
+            wa.dW = dW32; wa.w_layout = o.w_layout; wa.beta = (chunk > 0 || o.accumulate_dw) ? 1 : 0;
+            launch_dw(wa, g_load_variant, st);
+        }
+    } else {
+        float* z = at<float>(ws, p.chunk0);
+        int chunk = 0;
+        for (int64_t m0 = 0; m0 < p.Mmax; m0 += p.Mc, ++chunk) {
+            const int64_t rows = (p.Mmax - m0) < p.Mc ? (p.Mmax - m0) : p.Mc;
+            F32Gemm gz;
+            memset(&gz, 0, sizeof(gz));
+            gz.A = (const float*)hidden; gz.sa_i = d; gz.sa_k = 1; gz.a_imap = row_index;
+            gz.B = (const float*)W;
+            if (o.w_layout == RAPID_W_DV) { gz.sb_k = V; gz.sb_j = 1; } else { gz.sb_k = 1; gz.sb_j = d; }
+            gz.C = z; gz.sc_i = V; gz.sc_j = 1;
+            gz.I = rows; gz.J = V; gz.Kd = d; gz.beta = 0; gz.counts = counts; gz.i0 = m0; gz.alpha = inv_temp;
+            launch_f32_gemm(gz, st);
+            launch_f32_dz(z, V, rows, m0, tokc, seqc, lse_c, g, inv_temp, counts, st);
+            // dH[row] = dz[row, :] . W^T
+            F32Gemm gh;
+            memset(&gh, 0, sizeof(gh));
+            gh.A = z; gh.sa_i = V; gh.sa_k = 1;
+            gh.B = (const float*)W;   // B(k = v, j = k') = W(k', v)
+            if (o.w_layout == RAPID_W_DV) { gh.sb_k = 1; gh.sb_j = V; } else { gh.sb_k = d; gh.sb_j = 1; }
+            gh.C = (float*)dhidden_out; gh.sc_i = d; gh.sc_j = 1; gh.c_rows = row_index;
+            gh.I = rows; gh.J = d; gh.Kd = V; gh.beta = 0; gh.counts = counts; gh.i0 = m0; gh.alpha = 1.f;
+            launch_f32_gemm(gh, st);
+            // dW(k', v) += sum_rows H[row, k'] dz[row, v]
+            F32Gemm gw;
+            memset(&gw, 0, sizeof(gw));
+            gw.A = (const float*)hidden; gw.sa_i = 1; gw.sa_k = d; gw.a_kmap = row_index;
+            gw.B = z; gw.sb_k = V; gw.sb_j = 1;
+            gw.C = dW32;
+            if (o.w_layout == RAPID_W_DV) { gw.sc_i = V; gw.sc_j = 1; } else { gw.sc_i = 1; gw.sc_j = d; }
+            gw.I = d; gw.J = V; gw.Kd = rows; gw.beta = (chunk > 0 || o.accumulate_dw) ? 1 : 0;
+            gw.counts = counts; gw.i0 = m0; gw.limit_k = 1; gw.alpha = 1.f;
+            launch_f32_gemm(gw, st);
+        }
+    }
+    if (dw_staged) launch_f32_to_bf16(dW32, (bf16_t*)dW_out, d * V, st);
+    return check_launch("rapid_iw_pg_loss_fwd_bwd");
+}
+
+}  // extern "C"

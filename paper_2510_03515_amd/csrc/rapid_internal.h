@@ -1,0 +1,149 @@
+// Internal declarations shared by the translation units of librapid_hip.so (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rapid.h"
+
+namespace rapid {
+
+typedef unsigned short bf16_t;  // raw bf16 bits in memory
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// device counters written by the compaction step: [0] = M (valid tokens), [1] = M rounded up to 256
+enum { CNT_M = 0, CNT_MR = 1, CNT_WORDS = 64 };
+
+constexpr int ROW_TILE = 256;  // compact rows are padded to this
+constexpr int K_TILE = 64;     // contraction tile of the MFMA kernels (bf16 elements)
+
+// ---- reductions.hip ---------------------------------------------------------------------------
+void launch_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len, int32_t* cu_seqlen,
+                       int32_t* row_index, int32_t* counts, hipStream_t st);
+void launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
+void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const int32_t* counts,
+                          int64_t Mmax_pad, int64_t T, int64_t V, int32_t* tokc, int32_t* seqc,
+                          int32_t* dev_status, hipStream_t st);
+// lse/logp from per-slot partial (max, sumexp) and the gathered logit
+void launch_merge_lse(const float* part_max, const float* part_sum, int P, int64_t ld_part,
+                      const float* zy, const int32_t* row_index, const int32_t* counts, int64_t Mmax_pad,
+                      float* lse_c, float* logp_out, float* lse_out, hipStream_t st);
+void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N,
+                         int64_t T, float* tok_logratio_out, double* s64, float* s32,
+                         int32_t* dev_status, hipStream_t st);
+void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, int64_t N,
+                            int64_t K, float eta, int baseline_mode, float* adv, float* weight,
+                            float* gmean, float* gstd, int32_t* gsize, int32_t* dev_status,
+                            hipStream_t st);
+void launch_coefficients(const double* s64, const float* adv, const float* coef_override, int64_t N,
+                         float eta, int coef_mode, float loss_scale, int normalized,
+                         const int32_t* counts, float* g, float* loss_out, rapid_iw_pg_diag* diag,
+                         hipStream_t st);
+void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, int64_t d, int elem_bytes,
+                             hipStream_t st);
+void launch_f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t st);
+
+// ---- pack.hip ---------------------------------------------------------------------------------
+// dst[r][c] (ld_dst) = src[srow(r)][c] for r < R, c < C else 0, over r < Rpad, c < Cpad.
+// R may come from the device: if counts != NULL, R = counts[CNT_M] - r0 clipped to [0, R] and
+// Rpad = counts[CNT_MR] - r0 clipped to [0, Rpad].  Source row of r is row_index[r0 + r] if
+// row_index is given, else r (the caller offsets `src`).
+void launch_copy_pad_bf16(const bf16_t* src, int64_t ld_src, const int32_t* row_index, bf16_t* dst,
+                          int64_t ld_dst, int64_t R, int64_t C, int64_t Rpad, int64_t Cpad,
+                          const int32_t* counts, int64_t r0, hipStream_t st);
+// dst[c][r] (ld_dst) = src[r][c] for r < R, c < C else 0, over r < Rpad, c < Cpad.
+void launch_transpose_pad_bf16(const bf16_t* src, int64_t ld_src, bf16_t* dst, int64_t ld_dst, int64_t R,
+                               int64_t C, int64_t Rpad, int64_t Cpad, const int32_t* counts, int64_t r0,
+                               hipStream_t st);
+
+// ---- gemm_bf16.hip ----------------------------------------------------------------------------
+struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered logit
+    const bf16_t* Wvd;    // [Vpad, dpad]
+    const bf16_t* Hc;     // [Mmax_pad, dpad]
+    int64_t dpad;
+    int tilesV, tilesM;   // 256-tiles
+    int64_t V;
+    float inv_temp;
+    const int32_t* tokc;
+    const int32_t* counts;
+    float* part_max;      // [P][ld_part], P = tilesV * 2
+    float* part_sum;
+    int64_t ld_part;
+    float* zy;            // [Mmax_pad]
+};
+void launch_fwd_lse(const FwdArgs& a, int variant, hipStream_t st);
+int fwd_slots_per_tile();
+
+struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, bf16 [Mc, Vpad]
+    const bf16_t* Wvd;
+    const bf16_t* Hc;     // already offset to the chunk's first row
+    int64_t dpad;
+    int tilesV, tilesM;   // tilesM = chunk rows / 256
+    int64_t V, Vpad;
+    float inv_temp;
+    int64_t m0;           // first compact row of the chunk
+    const int32_t* tokc;  // full arrays (indexed by compact row)
+    const int32_t* seqc;
+    const float* lse_c;
+    const float* g;       // [N]
+    const int32_t* counts;
+    bf16_t* dz;           // [Mc, Vpad]
+};
+void launch_dz(const DzArgs& a, int variant, hipStream_t st);
+
+struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
+    const bf16_t* Wdv;    // [dpadR, Vpad]
+    const bf16_t* dz;     // [Mc, Vpad]
+    int64_t Vpad;
+    int64_t d, dpadR;
+    int tilesM;
+    int64_t m0;
+    const int32_t* row_index;
+    const int32_t* counts;
+    bf16_t* dhidden;      // [N*T, d]
+};
+void launch_dh(const DhArgs& a, int variant, hipStream_t st);
+
+struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
+    const bf16_t* dzT;    // [Vpad, Mc]
+    const bf16_t* HcT;    // [dpadR, Mmax_pad], already offset by m0 columns
+    int64_t Mc, ldH;
+    int64_t d, dpadR, V, Vpad;
+    int64_t m0;
+    const int32_t* counts;
+    float* dW;            // fp32, layout per w_layout
+    int w_layout;
+    int beta;             // 0 overwrite, 1 accumulate
+};
+void launch_dw(const DwArgs& a, int variant, hipStream_t st);
+
+// ---- f32_path.hip -----------------------------------------------------------------------------
+// C[i][j] (+)= alpha sum_k A(i,k) B(k,j), arbitrary strides, optional index maps, and a device-side
+// row count.  Accumulates in fp64.
+struct F32Gemm {
+    const float* A; int64_t sa_i, sa_k;
+    const int32_t* a_imap;   // optional: A row of i is a_imap[i0 + i]
+    const int32_t* a_kmap;   // optional: A position of k is a_kmap[i0 + k]
+    const float* B; int64_t sb_k, sb_j;
+    float* C; int64_t sc_i, sc_j;
+    const int32_t* c_rows;   // optional: C row of i is c_rows[i0 + i]
+    int64_t I, J, Kd;
+    int beta;
+    const int32_t* counts; int64_t i0;   // if counts: I (or Kd when limit_k) is clipped to M - i0
+    int limit_k;
+    float alpha;
+};
+void launch_f32_gemm(const F32Gemm& g, hipStream_t st);
+// row-wise: lse, logp, gathered logit from a materialised logits chunk z [rows, V]
+void launch_f32_row_lse(const float* z, int64_t V, int64_t rows, int64_t m0, const int32_t* tokc,
+                        const int32_t* row_index, const int32_t* counts, float* lse_c, float* logp_out,
+                        float* lse_out, hipStream_t st);
+// in place: z -> dz = g (onehot - softmax) * inv_temp
+void launch_f32_dz(float* z, int64_t V, int64_t rows, int64_t m0, const int32_t* tokc,
+                   const int32_t* seqc, const float* lse_c, const float* g, float inv_temp,
+                   const int32_t* counts, hipStream_t st);
+
+void set_error(const char* fmt, ...);
+
+}  // namespace rapid

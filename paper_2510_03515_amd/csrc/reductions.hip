@@ -1,0 +1,407 @@
+// Small kernels around the contractions: mask compaction, log-sum-exp merge, generation-level log
+// ratios, group advantages, loss/coefficients/diagnostics.  All HBM- or latency-bound; every
+// reduction uses a fixed tree so results are bitwise reproducible (no atomics on data).
+#include <cmath>
+
+#include "rapid_internal.h"
+
+namespace rapid {
+
+namespace {
+
+constexpr int WAVE = 64;
+
+__device__ inline double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ inline double wave_max(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+__device__ inline int wave_sum_i(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+// block-wide reductions for up to 1024 threads; `sm` holds >= 16 doubles
+__device__ inline double block_sum(double v, double* sm) {
+    v = wave_sum(v);
+    const int w = threadIdx.x / WAVE, nw = (blockDim.x + WAVE - 1) / WAVE;
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) sm[w] = v;
+    __syncthreads();
+    double r = 0.0;
+    for (int i = 0; i < nw; ++i) r += sm[i];
+    return r;
+}
+__device__ inline double block_max(double v, double* sm) {
+    v = wave_max(v);
+    const int w = threadIdx.x / WAVE, nw = (blockDim.x + WAVE - 1) / WAVE;
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) sm[w] = v;
+    __syncthreads();
+    double r = sm[0];
+    for (int i = 1; i < nw; ++i) r = fmax(r, sm[i]);
+    return r;
+}
+
+// ------------------------------------------------------------------ compaction of the padding mask
+// one wave per generation: number of valid tokens
+__global__ void seq_len_kernel(const uint8_t* __restrict__ mask, int64_t N, int64_t T,
+                               int32_t* __restrict__ seq_len) {
+    const int64_t n = blockIdx.x;
+    if (n >= N) return;
+    int cnt = 0;
+    for (int64_t t = threadIdx.x; t < T; t += WAVE) cnt += mask[n * T + t] != 0;
+    cnt = wave_sum_i(cnt);
+    if (threadIdx.x == 0) seq_len[n] = cnt;
+}
+
+// single block: exclusive prefix sum of seq_len, and the counters M / M rounded up to a row tile
+__global__ void scan_kernel(const int32_t* __restrict__ seq_len, int64_t N, int32_t* __restrict__ cu,
+                            int32_t* __restrict__ counts) {
+    __shared__ int sm[1024];
+    __shared__ int carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < N; base += 1024) {
+        const int64_t n = base + threadIdx.x;
+        const int v = n < N ? seq_len[n] : 0;
+        sm[threadIdx.x] = v;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {   // Hillis-Steele inclusive scan
+            int add = threadIdx.x >= o ? sm[threadIdx.x - o] : 0;
+            __syncthreads();
+            sm[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int incl = sm[threadIdx.x];
+        if (n < N && cu) cu[n] = carry + incl - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry += incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (cu) cu[N] = carry;
+        if (counts) {
+            counts[CNT_M] = carry;
+            counts[CNT_MR] = (carry + ROW_TILE - 1) / ROW_TILE * ROW_TILE;
+        }
+    }
+}
+
+// one wave per generation: flat positions of its valid tokens, in order
+__global__ void row_index_kernel(const uint8_t* __restrict__ mask, int64_t N, int64_t T,
+                                 const int32_t* __restrict__ cu, int32_t* __restrict__ row_index) {
+    const int64_t n = blockIdx.x;
+    if (n >= N) return;
+    int base = cu[n];
+    const int lane = threadIdx.x;
+    for (int64_t t0 = 0; t0 < T; t0 += WAVE) {
+        const int64_t t = t0 + lane;
+        const bool v = t < T && mask[n * T + t] != 0;
+        const unsigned long long b = __ballot(v);
+        const int before = __popcll(b & ((1ull << lane) - 1ull));
+        if (v) row_index[base + before] = (int32_t)(n * T + t);
+        base += __popcll(b);
+    }
+}
+
+__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// compact token ids and generation ids; out-of-range ids are flagged and replaced by 0
+__global__ void gather_tokens_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ row_index,
+                                     const int32_t* __restrict__ counts, int64_t Mmax_pad, int64_t T, int64_t V,
+                                     int32_t* __restrict__ tokc, int32_t* __restrict__ seqc,
+                                     int32_t* __restrict__ dev_status) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int M = counts[CNT_M], Mr = counts[CNT_MR];
+    if (j >= Mr || j >= Mmax_pad) return;
+    int tok = 0, seq = 0;
+    if (j < M) {
+        const int32_t pos = row_index[j];
+        tok = tokens[pos];
+        seq = (int32_t)(pos / T);
+        if (tok < 0 || tok >= V) {
+            tok = 0;
+            if (dev_status) atomicOr(dev_status, RAPID_STATUS_BAD_TOKEN);
+        }
+    }
+    tokc[j] = tok;
+    seqc[j] = seq;
+}
+
+// lse[j] = log sum_p part_sum[p][j] exp(part_max[p][j]) ; logp = zy - lse, scattered to [N,T]
+__global__ void merge_lse_kernel(const float* __restrict__ part_max, const float* __restrict__ part_sum, int P,
+                                 int64_t ld_part, const float* __restrict__ zy,
+                                 const int32_t* __restrict__ row_index, const int32_t* __restrict__ counts,
+                                 float* __restrict__ lse_c, float* __restrict__ logp_out,
+                                 float* __restrict__ lse_out) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int M = counts[CNT_M];
+    if (j >= M) return;
+    float mx = -INFINITY;
+    for (int p = 0; p < P; ++p) mx = fmaxf(mx, part_max[p * ld_part + j]);
+    double acc = 0.0;
+    for (int p = 0; p < P; ++p) {
+        const float pm = part_max[p * ld_part + j];
+        const float ps = part_sum[p * ld_part + j];
+        if (ps > 0.f) acc += (double)ps * exp((double)(pm - mx));
+    }
+    const double lse = (double)mx + log(acc);
+    const float lse_f = (float)lse;
+    lse_c[j] = lse_f;
+    const int32_t pos = row_index[j];
+    logp_out[pos] = (float)((double)zy[j] - lse);
+    if (lse_out) lse_out[pos] = lse_f;
+}
+
+// one wave per generation: token-level log ratios and their sum over the generation
+__global__ void seq_logratio_kernel(const float* __restrict__ logp_cur, const float* __restrict__ logp_behav,
+                                    const uint8_t* __restrict__ mask, int64_t N, int64_t T,
+                                    float* __restrict__ tok_lr, double* __restrict__ s64,
+                                    float* __restrict__ s32, int32_t* __restrict__ dev_status) {
+    const int64_t n = blockIdx.x;
+    if (n >= N) return;
+    double acc = 0.0;
+    bool bad = false;
+    for (int64_t t = threadIdx.x; t < T; t += WAVE) {
+        const int64_t i = n * T + t;
+        double dlt = 0.0;
+        if (mask[i] != 0) {
+            const float lb = logp_behav[i];
+            if (isfinite(lb)) dlt = (double)logp_cur[i] - (double)lb;
+            else bad = true;
+        }
+        if (tok_lr) tok_lr[i] = (float)dlt;
+        acc += dlt;
+    }
+    acc = wave_sum(acc);
+    if (__any(bad) && threadIdx.x == 0 && dev_status) atomicOr(dev_status, RAPID_STATUS_NONFINITE_LOGP);
+    if (threadIdx.x == 0) {
+        s64[n] = acc;
+        if (s32) s32[n] = (float)acc;
+    }
+}
+
+__device__ inline double clipped_weight(const float* s32, int64_t n, double log_eta) {
+    if (!s32) return 1.0;
+    return exp(fmin((double)s32[n], log_eta));
+}
+
+// pass 1 over generations: defaults for entries no group owns, and data checks
+__global__ void group_init_kernel(const float* __restrict__ rewards, const int32_t* __restrict__ group_ids,
+                                  const float* __restrict__ s32, int64_t N, int64_t K, double log_eta,
+                                  float* __restrict__ adv, float* __restrict__ weight,
+                                  int32_t* __restrict__ dev_status) {
+    const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    int bits = 0;
+    const int32_t k = group_ids[n];
+    if (k < 0 || k >= K) bits |= RAPID_STATUS_BAD_GROUP;
+    if (!isfinite(rewards[n])) bits |= RAPID_STATUS_NONFINITE_REWARD;
+    if (s32 && isnan(s32[n])) bits |= RAPID_STATUS_NONFINITE_LOGP;
+    if (bits && dev_status) atomicOr(dev_status, bits);
+    adv[n] = 0.f;
+    if (weight) weight[n] = (float)clipped_weight(s32, n, log_eta);
+}
+
+// one block per group: size, mean/std of R, clipped-weight baseline, advantages of its members
+__global__ void group_advantage_kernel(const float* __restrict__ rewards, const int32_t* __restrict__ group_ids,
+                                       const float* __restrict__ s32, int64_t N, double log_eta,
+                                       int baseline_mode, float* __restrict__ adv, float* __restrict__ gmean,
+                                       float* __restrict__ gstd, int32_t* __restrict__ gsize) {
+    __shared__ double sm[16];
+    const int k = blockIdx.x;
+    double cnt = 0.0, sum_r = 0.0, sum_wr = 0.0;
+    for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
+        if (group_ids[n] == k) {
+            float r = rewards[n];
+            if (!isfinite(r)) r = 0.f;
+            cnt += 1.0;
+            sum_r += (double)r;
+            sum_wr += clipped_weight(s32, n, log_eta) * (double)r;
+        }
+    }
+    cnt = block_sum(cnt, sm);
+    sum_r = block_sum(sum_r, sm);
+    sum_wr = block_sum(sum_wr, sm);
+    const double mean = cnt > 0.0 ? sum_r / cnt : 0.0;
+    double sq = 0.0;
+    for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
+        if (group_ids[n] == k) {
+            float r = rewards[n];
+            if (!isfinite(r)) r = 0.f;
+            const double dlt = (double)r - mean;
+            sq += dlt * dlt;
+            double b;
+            if (baseline_mode == 0) {
+                b = sum_wr / cnt;
+            } else {
+                const double rest = sum_wr - clipped_weight(s32, n, log_eta) * (double)r;
+                if (baseline_mode == 1) b = rest / cnt;
+                else b = cnt > 1.0 ? rest / (cnt - 1.0) : 0.0;
+            }
+            adv[n] = (float)((double)r - b);
+        }
+    }
+    sq = block_sum(sq, sm);
+    if (threadIdx.x == 0) {
+        if (gsize) gsize[k] = (int32_t)cnt;
+        if (gmean) gmean[k] = (float)mean;
+        if (gstd) gstd[k] = (float)(cnt > 0.0 ? sqrt(sq / cnt) : 0.0);
+    }
+}
+
+// single block: coefficients g_n, loss = sum g_n, diagnostics
+__global__ void coefficients_kernel(const double* __restrict__ s64, const float* __restrict__ adv,
+                                    const float* __restrict__ coef_override, int64_t N, double log_eta,
+                                    int coef_mode, double log_loss_scale, int normalized,
+                                    const int32_t* __restrict__ counts, float* __restrict__ g,
+                                    float* __restrict__ loss_out, rapid_iw_pg_diag* __restrict__ diag) {
+    __shared__ double sm[16];
+    const double logN = log((double)N);
+    double lam = 0.0;
+    if (!coef_override && normalized) {
+        double mx = -INFINITY;
+        for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
+            const double a = (double)adv[n];
+            if (a != 0.0) {
+                const double lc = coef_mode == 0 ? s64[n] : fmin(s64[n], log_eta);
+                mx = fmax(mx, lc + log(fabs(a)) + log_loss_scale - logN);
+            }
+        }
+        mx = block_max(mx, sm);
+        lam = (mx == -INFINITY) ? 0.0 : mx;
+    }
+    double loss = 0.0, slw = 0.0, salw = 0.0, maxs = 0.0, nclip = 0.0;
+    for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
+        const double s = s64[n];
+        double gn;
+        if (coef_override) {
+            gn = (double)coef_override[n];
+        } else {
+            const double a = (double)adv[n];
+            if (a != 0.0) {
+                const double lc = coef_mode == 0 ? s : fmin(s, log_eta);
+                gn = (a > 0.0 ? -1.0 : 1.0) * exp(lc + log(fabs(a)) + log_loss_scale - logN - lam);
+            } else {
+                gn = 0.0;
+            }
+        }
+        g[n] = (float)gn;
+        loss += gn;
+        const double lw = fmin(s, log_eta);
+        slw += lw;
+        salw += fabs(lw);
+        maxs = fmax(maxs, fabs(s));
+        nclip += s > log_eta ? 1.0 : 0.0;
+    }
+    loss = block_sum(loss, sm);
+    slw = block_sum(slw, sm);
+    salw = block_sum(salw, sm);
+    nclip = block_sum(nclip, sm);
+    maxs = block_max(maxs, sm);
+    if (threadIdx.x == 0) {
+        loss_out[0] = (float)loss;
+        if (diag) {
+            diag->n_tokens = counts[CNT_M];
+            diag->n_clipped = (int32_t)nclip;
+            diag->n_sequences = (int32_t)N;
+            diag->mean_log_w = (float)(slw / (double)N);
+            diag->mean_abs_log_w = (float)(salw / (double)N);
+            diag->max_abs_s = (float)maxs;
+            diag->grad_log_scale = (float)lam;
+        }
+    }
+}
+
+// zero the gradient rows of masked positions: one block per position
+__global__ void zero_masked_rows_kernel(uint32_t* __restrict__ dh, const uint8_t* __restrict__ mask,
+                                        int64_t rows, int64_t words_per_row) {
+    const int64_t r = blockIdx.x;
+    if (r >= rows || mask[r] != 0) return;
+    uint32_t* p = dh + r * words_per_row;
+    for (int64_t i = threadIdx.x; i < words_per_row; i += blockDim.x) p[i] = 0u;
+}
+
+__global__ void f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const __bf16 b = (__bf16)src[i];
+    dst[i] = __builtin_bit_cast(unsigned short, b);
+}
+
+inline unsigned blocks_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
+
+}  // namespace
+
+void launch_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len, int32_t* cu_seqlen,
+                       int32_t* row_index, int32_t* counts, hipStream_t st) {
+    seq_len_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, seq_len);
+    scan_kernel<<<1, 1024, 0, st>>>(seq_len, N, cu_seqlen, counts);
+    if (row_index) row_index_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, cu_seqlen, row_index);
+}
+
+void launch_fill_f32(float* p, int64_t n, float v, hipStream_t st) {
+    if (n > 0) fill_f32_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, n, v);
+}
+
+void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const int32_t* counts,
+                          int64_t Mmax_pad, int64_t T, int64_t V, int32_t* tokc, int32_t* seqc,
+                          int32_t* dev_status, hipStream_t st) {
+    gather_tokens_kernel<<<blocks_for(Mmax_pad, 256), 256, 0, st>>>(tokens, row_index, counts, Mmax_pad, T, V,
+                                                                    tokc, seqc, dev_status);
+}
+
+void launch_merge_lse(const float* part_max, const float* part_sum, int P, int64_t ld_part, const float* zy,
+                      const int32_t* row_index, const int32_t* counts, int64_t Mmax_pad, float* lse_c,
+                      float* logp_out, float* lse_out, hipStream_t st) {
+    merge_lse_kernel<<<blocks_for(Mmax_pad, 256), 256, 0, st>>>(part_max, part_sum, P, ld_part, zy, row_index,
+                                                                counts, lse_c, logp_out, lse_out);
+}
+
+void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N,
+                         int64_t T, float* tok_logratio_out, double* s64, float* s32, int32_t* dev_status,
+                         hipStream_t st) {
+    seq_logratio_kernel<<<(unsigned)N, WAVE, 0, st>>>(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64,
+                                                      s32, dev_status);
+}
+
+void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, int64_t N,
+                            int64_t K, float eta, int baseline_mode, float* adv, float* weight, float* gmean,
+                            float* gstd, int32_t* gsize, int32_t* dev_status, hipStream_t st) {
+    const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
+    group_init_kernel<<<blocks_for(N, 256), 256, 0, st>>>(rewards, group_ids, s32, N, K, log_eta, adv, weight,
+                                                          dev_status);
+    group_advantage_kernel<<<(unsigned)K, 256, 0, st>>>(rewards, group_ids, s32, N, log_eta, baseline_mode, adv,
+                                                        gmean, gstd, gsize);
+}
+
+void launch_coefficients(const double* s64, const float* adv, const float* coef_override, int64_t N, float eta,
+                         int coef_mode, float loss_scale, int normalized, const int32_t* counts, float* g,
+                         float* loss_out, rapid_iw_pg_diag* diag, hipStream_t st) {
+    const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
+    coefficients_kernel<<<1, 1024, 0, st>>>(s64, adv, coef_override, N, log_eta, coef_mode,
+                                            log((double)loss_scale), normalized, counts, g, loss_out, diag);
+}
+
+void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, int64_t d, int elem_bytes,
+                             hipStream_t st) {
+    // d * elem_bytes is a multiple of 4 for every accepted shape (bf16 needs d % 8 == 0)
+    zero_masked_rows_kernel<<<(unsigned)rows, 128, 0, st>>>((uint32_t*)dhidden, mask, rows,
+                                                            d * elem_bytes / 4);
+}
+
+void launch_f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t st) {
+    if (n > 0) f32_to_bf16_kernel<<<blocks_for(n, 256), 256, 0, st>>>(src, dst, n);
+}
+
+}  // namespace rapid

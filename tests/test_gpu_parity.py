@@ -1,0 +1,309 @@
+"""Parity of the HIP path (through the C ABI) against the float64 oracle, element by element, on
+seeded synthetic inputs small enough for the oracle to finish in seconds but spanning several
+tiles and ragged tails.  Tolerances: integer/index outputs bit-exact; loss rel <= 1e-3;
+dHidden/dW relative (Frobenius) error <= 2e-2 in bf16 and <= 1e-5 in fp32."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rapid_oracle as orc
+from paper_2510_03515_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+LOSS_RTOL = 1e-3
+GRAD_RTOL = {"bf16": 2e-2, "f32": 1e-5}
+LOGP_ATOL = {"bf16": 2e-5, "f32": 2e-6}     # |logp| ~ 7..12, fp32 storage: a few ulp
+S_ATOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def rb():
+    from paper_2510_03515_amd import binding
+    binding.load()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64) if t.is_floating_point() else t.cpu().numpy()
+
+
+def _rel(a, ref):
+    a, ref = np.asarray(a, np.float64), np.asarray(ref, np.float64)
+    return float(np.linalg.norm(a - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def _make(spec, seed=0):
+    w = wl.make_workload(spec, seed=seed, device="cpu")
+    g = {k: (v.cuda() if torch.is_tensor(v) else v) for k, v in w.items()}
+    return w, g
+
+
+def _oracle_inputs(w):
+    return (_np(w["hidden"]), _np(w["W"]), _np(w["tokens"]), _np(w["mask"]))
+
+
+# ----------------------------------------------------------------------------- integer work
+@pytest.mark.parametrize("N,T,p", [(1, 1, 1.0), (5, 9, 0.6), (37, 200, 0.5), (3, 1500, 0.9), (64, 64, 0.0)])
+def test_compaction_bit_exact(rb, N, T, p):
+    print(f"compaction N={N} T={T} p={p}", flush=True)
+    rng = np.random.default_rng(N * 1000 + T)
+    mask = (rng.random((N, T)) < p).astype(np.uint8)      # arbitrary pattern, not only right padding
+    seq_len, cu, row_index = rb.rapid_compaction(torch.from_numpy(mask).cuda())
+    torch.cuda.synchronize()
+    o_len, o_cu, o_rows = orc.compaction(mask)
+    assert np.array_equal(seq_len.cpu().numpy(), o_len)
+    assert np.array_equal(cu.cpu().numpy(), o_cu)
+    M = int(o_cu[-1])
+    assert np.array_equal(row_index.cpu().numpy()[:M], o_rows)
+
+
+@pytest.mark.parametrize("mode", ["eq2", "eq5", "eq4", "loo1", "loo2"])
+def test_group_advantage(rb, mode):
+    print(f"group_advantage {mode}", flush=True)
+    rng = np.random.default_rng(3)
+    N, K = 1000, 37
+    R = rng.random(N).astype(np.float32)
+    gid = rng.integers(0, K - 2, size=N).astype(np.int32)     # ragged, shuffled, two empty groups
+    s = (rng.normal(size=N) * 0.8).astype(np.float32)
+    kw = dict(eq2=dict(s=None), eq5=dict(s=s, eta=2.0), eq4=dict(s=s, eta=math.inf),
+              loo1=dict(s=s, eta=2.0, baseline_mode=1), loo2=dict(s=s, eta=2.0, baseline_mode=2))[mode]
+    ref = orc.group_advantage(R, gid, K, **kw)
+    out = rb.rapid_group_advantage(torch.from_numpy(R).cuda(), torch.from_numpy(gid).cuda(), K,
+                                   seq_logratio=None if kw["s"] is None else torch.from_numpy(s).cuda(),
+                                   eta=kw.get("eta", 2.0), baseline_mode=kw.get("baseline_mode", 0))
+    torch.cuda.synchronize()
+    assert np.array_equal(out["group_size"].cpu().numpy(), ref["group_size"])     # bit-exact
+    assert np.allclose(_np(out["adv"]), ref["adv"], atol=2e-6)
+    assert np.allclose(_np(out["weight"]), ref["weight"], rtol=1e-6)
+    assert np.allclose(_np(out["group_mean"]), ref["group_mean"], atol=1e-6)
+    assert np.allclose(_np(out["group_std"]), ref["group_std"], atol=1e-6)
+
+
+def test_group_advantage_hand_example_and_status(rb):
+    rho = torch.tensor([4.0, 1.0, 1.0, 0.5]).log().cuda()
+    R = torch.tensor([1.0, 0.0, 0.0, 1.0]).cuda()
+    gid = torch.zeros(4, dtype=torch.int32).cuda()
+    out = rb.rapid_group_advantage(R, gid, 1, seq_logratio=rho, eta=2.0)
+    assert np.allclose(_np(out["adv"]), [0.375, -0.625, -0.625, 0.375], atol=1e-6)
+    status = torch.zeros(1, dtype=torch.int32).cuda()
+    bad_gid = torch.tensor([0, 5, -1, 0], dtype=torch.int32).cuda()
+    out = rb.rapid_group_advantage(R, bad_gid, 1, dev_status=status)
+    torch.cuda.synchronize()
+    assert status.item() & rb.STATUS_BAD_GROUP
+    assert out["group_size"].item() == 2 and _np(out["adv"])[1] == 0.0
+
+
+# ----------------------------------------------------------------------------- log-probabilities
+SPECS = {
+    "f32_cfg0": wl.CONFIGS[0],
+    "f32_ragged": wl.small_spec("f32_ragged", "f32", d=50, V=777, prompts=3, G=3, len_lo=1, len_hi=70),
+    "bf16_small": wl.small_spec("bf16_small", "bf16", d=128, V=1000, prompts=4, G=4, len_lo=3, len_hi=40),
+    "bf16_ragged": wl.small_spec("bf16_ragged", "bf16", d=200, V=1321, prompts=5, G=3, len_lo=1, len_hi=90,
+                                 sigma=0.02, reward="uniform"),
+}
+
+
+@pytest.mark.parametrize("name", list(SPECS))
+@pytest.mark.parametrize("layout", ["dv", "vd"])
+def test_logprob_fwd(rb, name, layout):
+    print(f"logprob_fwd {name} {layout}", flush=True)
+    spec = SPECS[name]
+    w, g = _make(spec)
+    H, W, tok, mask = _oracle_inputs(w)
+    ref_lp, ref_lse = orc.logprob(H, W, tok, mask)
+    Wg = g["W"] if layout == "dv" else g["W"].t().contiguous()
+    variants = [1, 0] if spec.dtype == "bf16" else [1]
+    for variant in variants:
+        rb.rapid_set_tuning(0, variant)
+        lp, lse = rb.rapid_logprob_fwd(g["hidden"], Wg, g["tokens"], g["mask"],
+                                       w_layout=rb.W_DV if layout == "dv" else rb.W_VD, want_lse=True)
+        torch.cuda.synchronize()
+        assert np.abs(_np(lp) - ref_lp).max() <= LOGP_ATOL[spec.dtype], f"variant {variant}"
+        assert np.abs(_np(lse) - ref_lse).max() <= LOGP_ATOL[spec.dtype]
+        assert np.all(_np(lp)[mask == 0] == 0.0)
+    rb.rapid_set_tuning(0, 1)
+
+
+def test_logprob_closed_form_and_temperature(rb):
+    spec = SPECS["bf16_small"]
+    w, g = _make(spec)
+    lp, lse = rb.rapid_logprob_fwd(g["hidden"], torch.zeros_like(g["W"]), g["tokens"], g["mask"], want_lse=True)
+    torch.cuda.synchronize()
+    m = _np(g["mask"]) != 0
+    assert np.allclose(_np(lp)[m], -math.log(spec.V), atol=2e-6)       # W = 0 -> uniform over V
+    assert np.allclose(_np(lse)[m], math.log(spec.V), atol=2e-6)
+    H, W, tok, mask = _oracle_inputs(w)
+    ref, _ = orc.logprob(H, W, tok, mask, temperature=0.7)
+    lp, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"], temperature=0.7)
+    assert np.abs(_np(lp) - ref).max() <= LOGP_ATOL["bf16"]
+
+
+# ----------------------------------------------------------------------------- fused forward + backward
+def _run_pair(rb, spec, seed=0, layout="dv", min_ws=False, dw_dtype=torch.float32, **kw):
+    w, g = _make(spec, seed)
+    H, W, tok, mask = _oracle_inputs(w)
+    lay = rb.W_DV if layout == "dv" else rb.W_VD
+    Wg = g["W"] if layout == "dv" else g["W"].t().contiguous()
+    Wold = g["W_old"] if layout == "dv" else g["W_old"].t().contiguous()
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], Wold, g["tokens"], g["mask"], w_layout=lay,
+                                     temperature=kw.get("temperature", 1.0))
+    buf = rb.IwPgBuffers(g["hidden"], Wg, w["K"], w_layout=lay, dw_dtype=dw_dtype, minimum_workspace=min_ws)
+    coef = kw.pop("coef_override", None)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], Wg, g["tokens"], g["mask"], logp_b, g["rewards"],
+                                      g["group_ids"], w["K"], buffers=buf, w_layout=lay,
+                                      coef_override=None if coef is None else torch.from_numpy(coef).cuda(), **kw)
+    torch.cuda.synchronize()
+    okw = {k: v for k, v in kw.items() if k != "accumulate_dw"}
+    ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(w["rewards"]), _np(w["group_ids"]), w["K"],
+                                 coef_override=coef, **okw)
+    return w, out, ref
+
+
+def _check_pair(rb, spec, out, ref, layout="dv"):
+    tol = GRAD_RTOL[spec.dtype]
+    dW = _np(out.dW) if layout == "dv" else _np(out.dW).T
+    assert out.dev_status.item() == 0
+    assert np.abs(_np(out.seq_logratio) - ref["seq_logratio"]).max() <= S_ATOL
+    assert np.abs(_np(out.logp_cur) - ref["logp_cur"]).max() <= LOGP_ATOL[spec.dtype]
+    assert np.abs(_np(out.tok_logratio) - ref["tok_logratio"]).max() <= 2 * LOGP_ATOL[spec.dtype]
+    assert np.allclose(_np(out.adv), ref["adv"], atol=1e-3 if spec.dtype == "bf16" else 1e-5)
+    loss = out.loss.item()
+    assert abs(loss - ref["loss"]) <= LOSS_RTOL * max(abs(ref["loss"]), 1e-30), (loss, ref["loss"])
+    assert _rel(_np(out.dhidden), ref["dH"]) <= tol
+    assert _rel(dW, ref["dW"]) <= tol
+    mask0 = ref["logp_cur"] == 0
+    assert np.all(_np(out.dhidden)[mask0 & (np.abs(ref["dH"]).sum(-1) == 0)] == 0.0)
+    dg = out.read_diag()
+    assert dg["n_tokens"] == ref["n_tokens"]                     # bit-exact
+    assert dg["n_sequences"] == len(ref["adv"])
+    near = int((np.abs(ref["seq_logratio"] - math.log(2.0)) < 1e-3).sum())
+    assert abs(dg["n_clipped"] - ref["n_clipped"]) <= near
+    assert abs(dg["mean_log_w"] - ref["mean_log_w"]) <= 1e-3
+    assert abs(dg["mean_abs_log_w"] - ref["mean_abs_log_w"]) <= 1e-3
+
+
+@pytest.mark.parametrize("name", list(SPECS))
+@pytest.mark.parametrize("layout", ["dv", "vd"])
+def test_fwd_bwd_parity(rb, name, layout):
+    print(f"fwd_bwd {name} {layout}", flush=True)
+    spec = SPECS[name]
+    w, out, ref = _run_pair(rb, spec, layout=layout)
+    _check_pair(rb, spec, out, ref, layout)
+
+
+@pytest.mark.parametrize("name", ["f32_ragged", "bf16_ragged"])
+def test_fwd_bwd_minimum_workspace_and_variants(rb, name):
+    """Smallest workspace: the backward runs in 256-row chunks (several chunks, ragged last one);
+    register-staged tile loads instead of direct-to-LDS."""
+    print(f"fwd_bwd min workspace {name}", flush=True)
+    spec = SPECS[name]
+    rb.rapid_set_tuning(0, 0)
+    try:
+        w, out, ref = _run_pair(rb, spec, min_ws=True)
+        _check_pair(rb, spec, out, ref)
+    finally:
+        rb.rapid_set_tuning(0, 1)
+    w, out2, ref = _run_pair(rb, spec, min_ws=True)
+    _check_pair(rb, spec, out2, ref)
+
+
+@pytest.mark.parametrize("name", ["f32_cfg0", "bf16_small"])
+def test_fwd_bwd_options(rb, name):
+    print(f"fwd_bwd options {name}", flush=True)
+    spec = SPECS[name]
+    for kw in (dict(coef_mode=1), dict(baseline_mode=1), dict(baseline_mode=2), dict(eta=math.inf),
+               dict(loss_scale=0.25), dict(temperature=0.8), dict(normalized_grads=True), dict(eta=1.05)):
+        print("  ", kw, flush=True)
+        w, out, ref = _run_pair(rb, spec, **kw)
+        _check_pair(rb, spec, out, ref)
+        if kw.get("normalized_grads"):
+            assert abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]) <= 1e-3
+
+
+def test_cross_entropy_special_case(rb):
+    """coef_override g = -1/M: mean token cross-entropy of a linear layer (heavy kernels checked
+    independently of the RL scalars)."""
+    spec = SPECS["bf16_small"]
+    w0 = wl.make_workload(spec, seed=0, device="cpu")
+    M = int(w0["mask"].sum())
+    coef = np.full(spec.N, -1.0 / M, np.float32)
+    w, out, ref = _run_pair(rb, spec, coef_override=coef)
+    assert _rel(_np(out.dhidden), ref["dH"]) <= GRAD_RTOL["bf16"]
+    assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+    assert abs(out.loss.item() - coef.astype(np.float64).sum()) <= 1e-5
+    assert np.abs(_np(out.dW).sum(axis=1)).max() <= 1e-3 * np.abs(_np(out.dW)).sum(axis=1).max()
+
+
+def test_dw_bf16_and_accumulate(rb):
+    spec = SPECS["bf16_small"]
+    w, out, ref = _run_pair(rb, spec, dw_dtype=torch.bfloat16)
+    assert out.dW.dtype == torch.bfloat16
+    assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+    # accumulate: dW_out starts at a known value
+    w, g = _make(spec)
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+    buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"])
+    buf.dW.fill_(0.5)
+    rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"],
+                                g["group_ids"], w["K"], buffers=buf, accumulate_dw=True)
+    torch.cuda.synchronize()
+    assert _rel(_np(buf.dW) - 0.5, ref["dW"]) <= GRAD_RTOL["bf16"]
+
+
+@pytest.mark.parametrize("name", ["f32_cfg0", "bf16_small"])
+def test_on_policy_reduction_exact(rb, name):
+    """Behaviour log-probs produced by the library itself with the same W: every generation-level
+    log ratio is exactly 0, every weight exactly 1, advantages equal Eq. (2) and the loss is 0."""
+    spec = SPECS[name]
+    w, g = _make(spec)
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])
+    out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"],
+                                      g["group_ids"], w["K"])
+    torch.cuda.synchronize()
+    assert torch.equal(out.logp_cur, logp_b)                                   # bitwise
+    assert torch.all(out.seq_logratio == 0) and torch.all(out.tok_logratio == 0)
+    on = orc.group_advantage(_np(w["rewards"]), _np(w["group_ids"]), w["K"], s=None)
+    assert np.allclose(_np(out.adv), on["adv"], atol=1e-6)
+    assert abs(out.loss.item()) <= 1e-7
+    dg = out.read_diag()
+    assert dg["n_clipped"] == 0 and dg["mean_log_w"] == 0.0
+    # and twice the same call gives bitwise identical gradients (no atomics, fixed order)
+    out2 = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"],
+                                       g["group_ids"], w["K"])
+    torch.cuda.synchronize()
+    assert torch.equal(out.dW, out2.dW) and torch.equal(out.dhidden, out2.dhidden)
+
+
+def test_edge_cases(rb):
+    spec = SPECS["bf16_small"]
+    w, g = _make(spec)
+    # (a) one generation with no valid token, (b) everything masked
+    mask = g["mask"].clone()
+    mask[2] = 0
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], mask)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], mask, logp_b, g["rewards"],
+                                      g["group_ids"], w["K"])
+    torch.cuda.synchronize()
+    H, W, tok, _ = _oracle_inputs(w)
+    ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, _np(mask), _np(logp_b), _np(w["rewards"]), _np(w["group_ids"]), w["K"])
+    assert out.seq_logratio[2].item() == 0.0 and torch.all(out.dhidden[2] == 0)
+    assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+    assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    mask.zero_()
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], mask)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], mask, logp_b, g["rewards"],
+                                      g["group_ids"], w["K"])
+    torch.cuda.synchronize()
+    assert torch.all(logp_b == 0) and torch.all(out.dW == 0) and torch.all(out.dhidden == 0)
+    assert out.read_diag()["n_tokens"] == 0
+    # (c) token id outside the vocabulary at an unmasked position: flagged, no fault
+    tok = g["tokens"].clone()
+    tok[0, 0] = spec.V + 5
+    status = torch.zeros(1, dtype=torch.int32).cuda()
+    rb.rapid_logprob_fwd(g["hidden"], g["W"], tok, g["mask"], dev_status=status)
+    torch.cuda.synchronize()
+    assert status.item() & rb.STATUS_BAD_TOKEN

@@ -1,0 +1,113 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
+its host-side validation and workspace arithmetic behave (no kernel is launched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def rb():
+    from paper_2510_03515_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2510_03515_amd import build
+        build.build(verbose=False)
+    binding.load()
+    return binding
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "rapid.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(rapid_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_exports_every_declared_symbol(rb):
+    lib = rb.load()
+    names = _declared()
+    assert "rapid_logprob_fwd" in names and "rapid_group_advantage" in names
+    assert "rapid_iw_pg_loss_fwd_bwd" in names and len(names) >= 9
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(rb.EXPORTS) == names
+    assert rb.rapid_version() >= 1
+
+
+def test_struct_layouts_match_header(rb):
+    assert C.sizeof(rb.IwPgDiag) == 32
+    assert C.sizeof(rb.IwPgOpts) == 48
+    o = rb.default_opts()
+    assert o.eta == 2.0 and o.loss_scale == 1.0 and o.temperature == 1.0
+    assert o.coef_mode == 0 and o.baseline_mode == 0 and o.w_layout == rb.W_DV and o.dw_dtype == rb.DTYPE_F32
+
+
+def test_workspace_sizes(rb):
+    args = (256, 2048, 1536, 151936, 32, rb.DTYPE_BF16)
+    rec = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, *args)
+    mn = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, *args, minimum=True)
+    assert 0 < mn < rec < 288 * 2**30
+    assert rb.rapid_workspace_bytes(rb.OP_GROUP_ADVANTAGE, *args) == 0
+    assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, 0, 1, 1, 1, 1, 0) == 0       # invalid shape
+    assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, 4, 4, 8, 8, 1, 7) == 0       # invalid dtype
+    assert rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, *args) < rec
+
+
+def test_host_validation_returns_codes_without_a_gpu(rb):
+    lib = rb.load()
+    one = C.c_void_p(256)   # fake, aligned, never dereferenced: validation fails first
+    # NULL hidden
+    rc = lib.rapid_logprob_fwd(None, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None,
+                               one, 1 << 30, None)
+    assert rc == -1 and b"NULL" in lib.rapid_last_error()
+    # bad dtype, bad shape, bf16 with d % 8 != 0, bad layout, bad temperature, misaligned workspace
+    assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 8, 9, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -3
+    assert lib.rapid_logprob_fwd(one, one, one, one, 0, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -2
+    assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 12, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -2
+    assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, 5, 1.0, one, None, None, one, 1 << 30, None) == -3
+    assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 0.0, one, None, None, one, 1 << 30, None) == -2
+    assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, C.c_void_p(8), 1 << 30, None) == -4
+    # workspace too small
+    assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 16, None) == -4
+    assert b"minimum" in lib.rapid_last_error()
+    # group advantage
+    assert lib.rapid_group_advantage(None, one, None, 4, 1, 2.0, 0, one, None, None, None, None, None, None) == -1
+    assert lib.rapid_group_advantage(one, one, None, 4, 0, 2.0, 0, one, None, None, None, None, None, None) == -2
+    assert lib.rapid_group_advantage(one, one, None, 4, 1, 2.0, 9, one, None, None, None, None, None, None) == -3
+    # fused call: missing outputs, unknown mode, accumulate into bf16
+    o = rb.default_opts()
+    args = lambda **k: [one, one, one, one, one, one, one, 4, 4, 8, 8, 1, rb.DTYPE_BF16, C.byref(o),
+                        k.get("loss", one), one, one, None, None, None, None, None, None, one, 1 << 30, None]
+    assert lib.rapid_iw_pg_loss_fwd_bwd(*args(loss=None)) == -1
+    o.coef_mode = 7
+    assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -3
+    o = rb.default_opts()
+    o.accumulate_dw, o.dw_dtype = 1, rb.DTYPE_BF16
+    assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -3
+    o = rb.default_opts()
+    o.loss_scale = -1.0
+    assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
+    assert lib.rapid_set_tuning(99, 0) == -3
+
+
+def test_workload_generator_recipe():
+    import torch
+    from paper_2510_03515_amd import workloads as wl
+    w = wl.make_workload(wl.CONFIGS[0], seed=0)
+    spec = w["spec"]
+    assert w["hidden"].shape == (32, 32, 64) and w["W"].shape == (64, 1000)
+    L = w["lengths"]
+    assert int(L.min()) >= 8 and int(L.max()) <= 32
+    assert torch.equal(w["mask"].sum(1).long(), L)
+    rms = w["hidden"].float().pow(2).mean(-1).sqrt()
+    assert torch.allclose(rms, torch.ones_like(rms), atol=1e-5)
+    assert int(w["tokens"].min()) >= 0 and int(w["tokens"].max()) < spec.V
+    assert torch.all(w["tokens"][w["mask"] == 0] == 0)
+    assert set(w["rewards"].tolist()) <= {0.0, 1.0}
+    assert w["group_ids"].tolist() == [n // 4 for n in range(32)]
+    w2 = wl.make_workload(wl.CONFIGS[0], seed=0)
+    assert torch.equal(w["tokens"], w2["tokens"]) and torch.equal(w["hidden"], w2["hidden"])
+    c = wl.calibrated(wl.CONFIGS[2])
+    assert abs(c.sigma - (0.5 / (2048 * 1536)) ** 0.5) < 1e-12
