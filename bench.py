@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused importance-weighted group-advantage policy-gradient step on one MI355X.
+
+A step = one rapid_iw_pg_loss_fwd_bwd call (all stages of the hot path) on one synthetic
+Qwen2.5-1.5B-shaped mini-batch (d=1536, V=151936, 32 prompts x 8 generations, response length
+U[256,2048]) whose inputs, including the stored behaviour log-probs, are resident in HBM.
+Prints ONE JSON line: response tokens/s, the roofline of the dominant kernel (HIP-event timing of
+every stage, taken inside the timed region) and the float64 oracle timed on this machine's cores on
+a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
+PEAK_HBM = 8.0e12         # B/s
+
+
+def cpu_baseline(w, tokens_per_seq=256):
+    """Oracle (float64 numpy, as it stands) on the first group, generations truncated to
+    `tokens_per_seq` tokens, at the full d and V."""
+    import numpy as np
+    import torch
+
+    from oracle import rapid_oracle as orc
+    spec = w["spec"]
+    G = spec.G
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    H = f64(w["hidden"][:G, :tokens_per_seq])
+    W = f64(w["W"])
+    tok = w["tokens"][:G, :tokens_per_seq].cpu().numpy()
+    mask = w["mask"][:G, :tokens_per_seq].cpu().numpy()
+    logp_b = f64(w["logp_behav"][:G, :tokens_per_seq])
+    R = f64(w["rewards"][:G])
+    gid = np.zeros(G, np.int64)
+    n_tok = int(mask.sum())
+    t0 = time.perf_counter()
+    orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 1, row_chunk=512)
+    dt = time.perf_counter() - t0
+    threads = torch.get_num_threads()
+    try:
+        import threadpoolctl
+        infos = [i for i in threadpoolctl.threadpool_info() if i.get("user_api") == "blas"]
+        if infos:
+            threads = max(i["num_threads"] for i in infos)
+    except Exception:
+        pass
+    return {"value": n_tok / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first group ({G} generations) truncated to {tokens_per_seq} tokens each = {n_tok} "
+                      f"tokens at full d={spec.d}, V={spec.V}; {dt:.1f} s of float64 numpy",
+            "host_cpus": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2, help="index into the workload list (2 = headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workspace-gib", type=float, default=0.0, help="0 = the library's recommended size")
+    ap.add_argument("--load-variant", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
+
+    import torch
+
+    from paper_2510_03515_amd import binding as rb
+    from paper_2510_03515_amd import workloads as wl
+
+    rb.load()   # raises if the HIP library is not built: there is no other path
+    torch.cuda.set_device(0)
+    spec = wl.CONFIGS[args.config]
+    w = wl.make_workload(spec, seed=0, device="cuda")
+    N, T, d, V, K = spec.N, spec.T, spec.d, spec.V, w["K"]
+    M = int(w["mask"].sum().item())
+    rb.rapid_set_tuning(0, args.load_variant)
+
+    fwd_only = spec.fwd_only
+    if fwd_only:
+        ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, rb.DTYPE_BF16)
+        ws = rb.alloc_workspace(ws_bytes)
+        step = lambda: rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], workspace=ws)
+        flops_per_token = 2.0 * d * V
+    else:
+        logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"])
+        w["logp_behav"] = logp_b
+        ws_bytes = int(args.workspace_gib * 2**30) if args.workspace_gib > 0 else None
+        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes)
+        ws_bytes = buf.workspace.numel()
+        step = lambda: rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b,
+                                                   w["rewards"], w["group_ids"], K, buffers=buf,
+                                                   optional_outputs=False)
+        flops_per_token = 6.0 * d * V
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rb.rapid_set_tuning(1, 1)          # per-stage HIP events inside the timed region
+    rb.rapid_profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = rb.rapid_profile_read()
+    rb.rapid_set_tuning(1, 0)
+
+    ms_per_step = dt / args.steps * 1e3
+    tok_s = M * args.steps / dt
+    stages = {k: {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
+                  "avg_ms": (ms / n if n else 0.0)} for k, (ms, n) in prof.items() if n}
+
+    # roofline of the dominant kernel: algorithmic flop of ONE launch / its average duration.
+    # Every contraction kernel does 2*d*V flop per token it processes; a step's tokens are split
+    # over the launches of a stage (the row chunks of the backward), so one launch processes
+    # M / launches_per_step tokens on average.
+    gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages]
+    dom = max(gemm_stages, key=lambda s: stages[s]["ms_per_step"])
+    launches = stages[dom]["launches_per_step"]
+    # chunks past the last valid row exit at once: count only launches that had rows
+    Mmax_pad = (N * T + 255) // 256 * 256
+    if dom != "fwd_lse":
+        chunk_rows = Mmax_pad / launches
+        live = max(1, -(-M // int(chunk_rows)))
+        tokens_per_launch = M / live
+        avg_ms = stages[dom]["ms_per_step"] / live
+    else:
+        live, tokens_per_launch, avg_ms = 1, M, stages[dom]["avg_ms"]
+    achieved = 2.0 * d * V * tokens_per_launch / (avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA / 1e12,
+                "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_MFMA / 1e12), "traffic": None,
+                "avg_launch_ms": avg_ms, "live_launches_per_step": live,
+                "tokens_per_launch": tokens_per_launch, "flop_per_token": 2.0 * d * V}
+
+    out = {
+        "metric": "response tokens/s for fused IW group-adv PG fwd+bwd; % bf16 MFMA peak",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": spec.name, "d": d, "V": V, "prompts": spec.prompts, "G": spec.G, "N": N,
+                   "T": T, "response_tokens": M, "workspace_gib": ws_bytes / 2**30,
+                   "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd"},
+        "frac_bf16_mfma_peak_algorithmic": flops_per_token * tok_s / PEAK_BF16_MFMA,
+        "roofline": roofline,
+        "stages": stages,
+    }
+    if not args.no_cpu_baseline and not fwd_only:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

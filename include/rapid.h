@@ -102,8 +102,20 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
 
 /* Process-wide tuning switches (host state, not thread-safe against concurrent calls).
  * key 0: how the MFMA kernels bring operand tiles into LDS: 1 = direct global->LDS loads
- * (default), 0 = staged through registers.  Results are identical either way. */
+ * (default), 0 = staged through registers.  Results are identical either way.
+ * key 1: per-stage event timing on (1) / off (0, default); see rapid_profile_read. */
 int rapid_set_tuning(int key, int value);
+
+/* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of
+ * its stages with HIP events on the caller's stream (host objects, no device memory);
+ * rapid_profile_read waits for those events, writes the milliseconds and the number of timed spans
+ * per stage into two HOST arrays of n_stages >= RAPID_N_STAGES entries, and clears the record.
+ * Stage order: 0 compaction/gather, 1 operand packing, 2 forward logits+log-sum-exp kernel,
+ * 3 log-sum-exp merge, 4 estimator reductions (ratios, advantages, loss), 5 zeroing of masked
+ * gradient rows, 6 dz kernel, 7 dz transpose, 8 dHidden kernel, 9 dW kernel, 10 fp32 path,
+ * 11 dW conversion. */
+#define RAPID_N_STAGES 12
+int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stages);
 
 /* Workspace sizes in bytes for `op` at the given problem size.  rapid_workspace_bytes is the
  * recommended size (backward row-chunks large enough to fill the chip); rapid_workspace_min_bytes

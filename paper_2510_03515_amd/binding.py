@@ -23,7 +23,9 @@ STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LO
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_logprob_fwd",
-           "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction"]
+           "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read"]
+STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
+          "dw", "f32_path", "dw_convert"]
 
 
 class RapidError(RuntimeError):
@@ -75,6 +77,8 @@ def load():
     lib.rapid_iw_pg_loss_fwd_bwd.restype = ci
     lib.rapid_compaction.argtypes = [vp, i64, i64, vp, vp, vp, vp]
     lib.rapid_compaction.restype = ci
+    lib.rapid_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64), ci]
+    lib.rapid_profile_read.restype = ci
     _lib = lib
     return lib
 
@@ -111,6 +115,16 @@ def rapid_version():
 
 def rapid_set_tuning(key, value):
     _check(load().rapid_set_tuning(key, value))
+
+
+def rapid_profile_read():
+    """Returns {stage: (milliseconds, spans)} for the calls made since profiling was switched on
+    (rapid_set_tuning(1, 1)) or last read."""
+    n = len(STAGES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(load().rapid_profile_read(ms, cnt, n))
+    return {STAGES[i]: (ms[i], cnt[i]) for i in range(n)}
 
 
 def rapid_workspace_bytes(op, N, T, d, V, K, dtype, minimum=False):

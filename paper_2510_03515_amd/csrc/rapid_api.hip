@@ -23,6 +23,37 @@ namespace {
 
 int g_load_variant = 1;   // 1: direct global -> LDS tile loads, 0: staged through registers
 
+// Optional per-stage timing with HIP events on the caller's stream (off by default).
+enum Stage { ST_COMPACT = 0, ST_PACK, ST_FWD_LSE, ST_MERGE, ST_ESTIMATOR, ST_ZERO, ST_DZ, ST_DZ_T, ST_DH, ST_DW,
+             ST_F32, ST_CONVERT, ST_COUNT };
+struct Profiler {
+    bool on = false;
+    static constexpr int MAX_SPANS = 8192;
+    hipEvent_t ev[2 * MAX_SPANS];
+    int stage[MAX_SPANS];
+    int created = 0, used = 0;
+    void begin(int st_id, hipStream_t st) {
+        if (!on || used >= MAX_SPANS) return;
+        while (created < 2 * (used + 1)) {
+            if (hipEventCreate(&ev[created]) != hipSuccess) { on = false; return; }
+            ++created;
+        }
+        stage[used] = st_id;
+        (void)hipEventRecord(ev[2 * used], st);
+    }
+    void end(hipStream_t st) {
+        if (!on || used >= MAX_SPANS) return;
+        (void)hipEventRecord(ev[2 * used + 1], st);
+        ++used;
+    }
+};
+Profiler g_prof;
+struct Span {
+    hipStream_t st;
+    Span(int id, hipStream_t s) : st(s) { g_prof.begin(id, s); }
+    ~Span() { g_prof.end(st); }
+};
+
 struct Plan {
     int op, dtype;
     int64_t N, T, d, V, K;
@@ -166,30 +197,45 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
     int32_t* seqc = at<int32_t>(ws, p.seqc);
     float* lse_c = at<float>(ws, p.lse_c);
     const float inv_temp = 1.0f / io.temperature;
-    launch_compaction(io.mask, p.N, p.T, at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), row_index, counts, st);
-    launch_gather_tokens(io.tokens, row_index, counts, p.Mmax_pad, p.T, p.V, tokc, seqc, io.dev_status, st);
-    launch_fill_f32(io.logp_out, p.Mmax, 0.f, st);
-    if (io.lse_out) launch_fill_f32(io.lse_out, p.Mmax, 0.f, st);
+    {
+        Span sp(ST_COMPACT, st);
+        launch_compaction(io.mask, p.N, p.T, at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), row_index, counts, st);
+        launch_gather_tokens(io.tokens, row_index, counts, p.Mmax_pad, p.T, p.V, tokc, seqc, io.dev_status, st);
+        launch_fill_f32(io.logp_out, p.Mmax, 0.f, st);
+        if (io.lse_out) launch_fill_f32(io.lse_out, p.Mmax, 0.f, st);
+    }
     if (p.dtype == RAPID_DTYPE_BF16) {
         bf16_t* Hc = at<bf16_t>(ws, p.Hc);
         bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
-        launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc, p.dpad, p.Mmax, p.d, p.Mmax_pad, p.dpad,
-                             counts, 0, st);
-        if (io.w_layout == RAPID_W_VD)
-            launch_copy_pad_bf16((const bf16_t*)io.W, p.d, nullptr, Wvd, p.dpad, p.V, p.d, p.Vpad, p.dpad, nullptr, 0, st);
-        else
-            launch_transpose_pad_bf16((const bf16_t*)io.W, p.V, Wvd, p.dpad, p.d, p.V, p.dpad, p.Vpad, nullptr, 0, st);
+        {
+            Span sp(ST_PACK, st);
+            launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc, p.dpad, p.Mmax, p.d, p.Mmax_pad,
+                                 p.dpad, counts, 0, st);
+            if (io.w_layout == RAPID_W_VD)
+                launch_copy_pad_bf16((const bf16_t*)io.W, p.d, nullptr, Wvd, p.dpad, p.V, p.d, p.Vpad, p.dpad,
+                                     nullptr, 0, st);
+            else
+                launch_transpose_pad_bf16((const bf16_t*)io.W, p.V, Wvd, p.dpad, p.d, p.V, p.dpad, p.Vpad, nullptr,
+                                          0, st);
+        }
         FwdArgs a;
         a.Wvd = Wvd; a.Hc = Hc; a.dpad = p.dpad;
         a.tilesV = (int)(p.Vpad / 256); a.tilesM = (int)(p.Mmax_pad / 256);
         a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
         a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
         a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy);
-        launch_fwd_lse(a, g_load_variant, st);
-        launch_merge_lse(a.part_max, a.part_sum, p.P, a.ld_part, a.zy, row_index, counts, p.Mmax_pad, lse_c,
-                         io.logp_out, io.lse_out, st);
+        {
+            Span sp(ST_FWD_LSE, st);
+            launch_fwd_lse(a, g_load_variant, st);
+        }
+        {
+            Span sp(ST_MERGE, st);
+            launch_merge_lse(a.part_max, a.part_sum, p.P, a.ld_part, a.zy, row_index, counts, p.Mmax_pad, lse_c,
+                             io.logp_out, io.lse_out, st);
+        }
     } else {
         float* z = at<float>(ws, p.chunk0);
+        Span sp(ST_F32, st);
         for (int64_t m0 = 0; m0 < p.Mmax; m0 += p.Mc) {
             const int64_t rows = (p.Mmax - m0) < p.Mc ? (p.Mmax - m0) : p.Mc;
             F32Gemm g;
@@ -266,8 +312,34 @@ int rapid_set_tuning(int key, int value) {
         g_load_variant = value;
         return RAPID_OK;
     }
+    if (key == 1 && (value == 0 || value == 1)) {
+        g_prof.on = value != 0;
+        g_prof.used = 0;
+        return RAPID_OK;
+    }
     set_error("unknown tuning key/value %d/%d", key, value);
     return RAPID_ERR_DTYPE;
+}
+
+int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stages) {
+    if (!ms_by_stage || !spans_by_stage || n_stages < ST_COUNT) {
+        set_error("rapid_profile_read needs two arrays of at least %d entries", (int)ST_COUNT);
+        return RAPID_ERR_NULL;
+    }
+    for (int i = 0; i < n_stages; ++i) { ms_by_stage[i] = 0.0; spans_by_stage[i] = 0; }
+    for (int i = 0; i < g_prof.used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess) {
+            set_error("rapid_profile_read: event query failed");
+            g_prof.used = 0;
+            return RAPID_ERR_HIP;
+        }
+        ms_by_stage[g_prof.stage[i]] += ms;
+        spans_by_stage[g_prof.stage[i]] += 1;
+    }
+    g_prof.used = 0;
+    return RAPID_OK;
 }
 
 size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
@@ -427,15 +499,21 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     run_forward(p, ws, io, st);
 
     // generation-level log ratios, clipped-weight group baseline, coefficients and loss
-    launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, dev_status, st);
-    launch_group_advantage(rewards, group_ids, s32, N, K, o.eta, o.baseline_mode, adv, nullptr, nullptr, nullptr,
-                           nullptr, dev_status, st);
-    launch_coefficients(s64, adv, o.coef_override, N, o.eta, o.coef_mode, o.loss_scale, o.normalized_grads, counts,
-                        g, loss_out, diag_out, st);
+    {
+        Span sp(ST_ESTIMATOR, st);
+        launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, dev_status, st);
+        launch_group_advantage(rewards, group_ids, s32, N, K, o.eta, o.baseline_mode, adv, nullptr, nullptr,
+                               nullptr, nullptr, dev_status, st);
+        launch_coefficients(s64, adv, o.coef_override, N, o.eta, o.coef_mode, o.loss_scale, o.normalized_grads,
+                            counts, g, loss_out, diag_out, st);
+    }
 
     // backward, in row chunks
     const int elem = dtype == RAPID_DTYPE_BF16 ? 2 : 4;
-    launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, st);
+    {
+        Span sp(ST_ZERO, st);
+        launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, st);
+    }
     const bool dw_staged = o.dw_dtype == RAPID_DTYPE_BF16;
     float* dW32 = dw_staged ? at<float>(ws, p.dw32) : (float*)dW_out;
 
@@ -446,11 +524,17 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         bf16_t* Wdv = at<bf16_t>(ws, p.Wdv);
         bf16_t* dz = at<bf16_t>(ws, p.chunk0);
         bf16_t* dzT = at<bf16_t>(ws, p.chunk1);
-        launch_transpose_pad_bf16(Hc, p.dpad, HcT, p.Mmax_pad, p.Mmax, p.dpad, p.Mmax_pad, p.dpadR, counts, 0, st);
-        if (o.w_layout == RAPID_W_DV)
-            launch_copy_pad_bf16((const bf16_t*)W, p.V, nullptr, Wdv, p.Vpad, p.d, p.V, p.dpadR, p.Vpad, nullptr, 0, st);
-        else
-            launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.Vpad, p.V, p.d, p.Vpad, p.dpadR, nullptr, 0, st);
+        {
+            Span sp(ST_PACK, st);
+            launch_transpose_pad_bf16(Hc, p.dpad, HcT, p.Mmax_pad, p.Mmax, p.dpad, p.Mmax_pad, p.dpadR, counts, 0,
+                                      st);
+            if (o.w_layout == RAPID_W_DV)
+                launch_copy_pad_bf16((const bf16_t*)W, p.V, nullptr, Wdv, p.Vpad, p.d, p.V, p.dpadR, p.Vpad,
+                                     nullptr, 0, st);
+            else
+                launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.Vpad, p.V, p.d, p.Vpad, p.dpadR, nullptr,
+                                          0, st);
+        }
         int chunk = 0;
         for (int64_t m0 = 0; m0 < p.Mmax_pad; m0 += p.Mc, ++chunk) {
             const int64_t rows = (p.Mmax_pad - m0) < p.Mc ? (p.Mmax_pad - m0) : p.Mc;   // multiple of 256
@@ -459,22 +543,35 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
             za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
             za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz;
-            launch_dz(za, g_load_variant, st);
-            launch_transpose_pad_bf16(dz, p.Vpad, dzT, p.Mc, rows, p.Vpad, rows, p.Vpad, counts, m0, st);
+            {
+                Span sp(ST_DZ, st);
+                launch_dz(za, g_load_variant, st);
+            }
+            {
+                Span sp(ST_DZ_T, st);
+                launch_transpose_pad_bf16(dz, p.Vpad, dzT, p.Mc, rows, p.Vpad, rows, p.Vpad, counts, m0, st);
+            }
             DhArgs ha;
             ha.Wdv = Wdv; ha.dz = dz; ha.Vpad = p.Vpad; ha.d = p.d; ha.dpadR = p.dpadR;
             ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
             ha.dhidden = (bf16_t*)dhidden_out;
-            launch_dh(ha, g_load_variant, st);
+            {
+                Span sp(ST_DH, st);
+                launch_dh(ha, g_load_variant, st);
+            }
             DwArgs wa;
             wa.dzT = dzT; wa.HcT = HcT + m0; wa.Mc = p.Mc; wa.ldH = p.Mmax_pad;
             wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = m0; wa.counts = counts;
             wa.dW = dW32; wa.w_layout = o.w_layout; wa.beta = (chunk > 0 || o.accumulate_dw) ? 1 : 0;
-            launch_dw(wa, g_load_variant, st);
+            {
+                Span sp(ST_DW, st);
+                launch_dw(wa, g_load_variant, st);
+            }
         }
     } else {
         float* z = at<float>(ws, p.chunk0);
         int chunk = 0;
+        Span sp(ST_F32, st);
         for (int64_t m0 = 0; m0 < p.Mmax; m0 += p.Mc, ++chunk) {
             const int64_t rows = (p.Mmax - m0) < p.Mc ? (p.Mmax - m0) : p.Mc;
             F32Gemm gz;
@@ -507,7 +604,10 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             launch_f32_gemm(gw, st);
         }
     }
-    if (dw_staged) launch_f32_to_bf16(dW32, (bf16_t*)dW_out, d * V, st);
+    if (dw_staged) {
+        Span sp(ST_CONVERT, st);
+        launch_f32_to_bf16(dW32, (bf16_t*)dW_out, d * V, st);
+    }
     return check_launch("rapid_iw_pg_loss_fwd_bwd");
 }
 
