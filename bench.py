@@ -66,6 +66,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workspace-gib", type=float, default=0.0, help="0 = the library's recommended size")
     ap.add_argument("--load-variant", type=int, default=1)
+    ap.add_argument("--debug-alias", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -82,6 +83,8 @@ def main():
     N, T, d, V, K = spec.N, spec.T, spec.d, spec.V, w["K"]
     M = int(w["mask"].sum().item())
     rb.rapid_set_tuning(0, args.load_variant)
+    if args.debug_alias:
+        rb.rapid_set_tuning(99, args.debug_alias)
 
     fwd_only = spec.fwd_only
     if fwd_only:

@@ -10,8 +10,8 @@
 // four 64-lane waves (2 x 2) owns a (64 WI) x (64 WJ) tile; each wave owns WI x WJ blocks of
 // 32 x 32, computed with v_mfma_f32_32x32x16_bf16 (each lane feeds 8 consecutive k of one row).
 // K advances 64 elements per step through two LDS stages (one barrier per step).  A tile row is
-// 128 bytes = 8 chunks of 16 bytes; chunk c of row r sits at chunk position c ^ (r & 7), which
-// makes the 16-byte fragment reads of 8 consecutive rows hit all banks.  Tiles arrive either by
+// 128 bytes = 8 chunks of 16 bytes; chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), so
+// the 16-byte fragment reads of 16 consecutive rows (one 256-byte LDS cycle) hit 64 distinct banks.  Tiles arrive either by
 // global_load_lds_dwordx4 (DIRECT: memory -> LDS without passing through registers; consecutive
 // lanes fill consecutive 16-byte slots, so the swizzle is applied to the global address) or by
 // ordinary loads staged through registers.
@@ -42,15 +42,18 @@ struct Shape {
 
 __device__ inline void lds_barrier() { __syncthreads(); }
 
-// Loads one K step (64 columns) of a tile with ROWS rows into LDS at `lds_tile`.
+// Loads one K step (64 columns) of a tile with ROWS rows into LDS at `lds_tile`.  `gwave` is the
+// wave-uniform address of the wave's first row of round 0 (scalar registers), `voff` the lane's
+// byte offset from it (row lane/8 of the 8-row band, swizzled chunk), `round_bytes` the uniform
+// distance between rounds (32 rows).
 template <int ROWS, bool DIRECT>
-__device__ inline void issue_tile_load(const bf16_t* __restrict__ gthread, int64_t ld, char* lds_tile, int wave,
-                                       int lane, uint4 (&stage)[ROWS / 32]) {
+__device__ inline void issue_tile_load(const char* __restrict__ gwave, uint32_t voff, int64_t round_bytes,
+                                       char* lds_wave, uint4 (&stage)[ROWS / 32]) {
 #pragma unroll
     for (int t = 0; t < ROWS / 32; ++t) {
-        const bf16_t* gp = gthread + (int64_t)(t * 32) * ld;
+        const char* gp = gwave + t * round_bytes + voff;
         if constexpr (DIRECT) {
-            char* lp = lds_tile + (t * 32 + wave * 8) * 128;   // wave-uniform; lane l lands at +16 l
+            char* lp = lds_wave + t * (32 * 128);   // wave-uniform; lane l lands at +16 l
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
                                              (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
         } else {
@@ -60,34 +63,74 @@ __device__ inline void issue_tile_load(const bf16_t* __restrict__ gthread, int64
 }
 
 template <int ROWS>
-__device__ inline void commit_tile_store(char* lds_tile, int wave, int lane, const uint4 (&stage)[ROWS / 32]) {
+__device__ inline void commit_tile_store(char* lds_wave, int lane, const uint4 (&stage)[ROWS / 32]) {
 #pragma unroll
-    for (int t = 0; t < ROWS / 32; ++t)
-        *(uint4*)(lds_tile + (t * 32 + wave * 8) * 128 + lane * 16) = stage[t];
+    for (int t = 0; t < ROWS / 32; ++t) *(uint4*)(lds_wave + t * (32 * 128) + lane * 16) = stage[t];
+}
+
+template <int WI, int WJ>
+struct Frags {
+    bf16x8 a[WI], b[WJ];
+};
+
+template <int WI, int WJ>
+__device__ inline void load_frags(Frags<WI, WJ>& f, const char* cur, int a_off, int b_off, int xo) {
+#pragma unroll
+    for (int ib = 0; ib < WI; ++ib) f.a[ib] = *(const bf16x8*)(cur + a_off + ib * (32 * 128) + xo);
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) f.b[jb] = *(const bf16x8*)(cur + b_off + jb * (32 * 128) + xo);
+}
+
+template <int WI, int WJ>
+__device__ inline void mma_block(const Frags<WI, WJ>& f, f32x16 (&acc)[WI][WJ]) {
+#pragma unroll
+    for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb)
+            acc[ib][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ib], f.b[jb], acc[ib][jb], 0, 0, 0);
+}
+
+// Scheduling hints: keep the matrix pipe fed by spreading the LDS fragment reads (and, in the
+// first sub-step, the tile loads of the next stage) between the MFMAs instead of in front of them.
+template <int N_DS, int N_VMEM, int N_MFMA>
+__device__ inline void interleave_hint() {
+    constexpr int groups = N_DS < N_MFMA ? (N_DS > 0 ? N_DS : 1) : N_MFMA;
+    constexpr int mfma_per = N_MFMA / groups;
+    constexpr int ds_per = (N_DS + groups - 1) / groups;
+    constexpr int vmem_per = (N_VMEM + groups - 1) / groups;
+#pragma unroll
+    for (int g = 0; g < groups; ++g) {
+        if (ds_per > 0) __builtin_amdgcn_sched_group_barrier(0x100, ds_per, 0);       // LDS reads
+        if (vmem_per > 0) __builtin_amdgcn_sched_group_barrier(0x010, vmem_per, 0);   // tile loads
+        __builtin_amdgcn_sched_group_barrier(0x008, mfma_per, 0);                     // MFMAs
+    }
 }
 
 // acc += A_tile . B_tile^T over `ktiles` steps of 64.  A / B point at the tile's first row, k = 0.
 template <int WI, int WJ, bool DIRECT>
 __device__ inline void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
-                                int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[WI][WJ]) {
+                                int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[WI][WJ], int dbg = 0) {
     using S = Shape<WI, WJ>;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_i = wave & 1, wave_j = wave >> 1;
 
-    // global side of the tile loads: lane l of a wave covers row l/8 (of its 8-row band) and the
-    // chunk that belongs at slot l%8 of that row
-    const int lrow = wave * 8 + (lane >> 3);
-    const int gchunk = (lane & 7) ^ (lane >> 3);
-    const bf16_t* ga = A + (int64_t)lrow * lda + gchunk * 8;
-    const bf16_t* gb = B + (int64_t)lrow * ldb + gchunk * 8;
+    // global side of the tile loads: lane l of a wave covers row l/8 of the wave's 8-row band and
+    // the chunk that belongs at slot l%8 of that row
+    const int gchunk = (lane & 7) ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);
+    const uint32_t voff_a = (uint32_t)(((int64_t)(lane >> 3) * lda + gchunk * 8) * 2);
+    const uint32_t voff_b = (uint32_t)(((int64_t)(lane >> 3) * ldb + gchunk * 8) * 2);
+    const char* ga = (const char*)(A + (int64_t)(wave * 8) * lda);
+    const char* gb = (const char*)(B + (int64_t)(wave * 8) * ldb);
+    const int64_t round_a = 32 * lda * 2, round_b = 32 * ldb * 2;
+    const int lds_wave_off = wave * 8 * 128;
 
     // LDS side of the fragment reads
     const int frow = lane & 31, fhi = lane >> 5;
     int xo[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) xo[ks] = (((ks * 2 + fhi) ^ (lane & 7)) * 16);
+    for (int ks = 0; ks < 4; ++ks) xo[ks] = (((ks * 2 + fhi) ^ ((lane >> 1) & 7)) * 16);
     const int a_off = (wave_i * (WI * 32) + frow) * 128;
     const int b_off = S::BI * 128 + (wave_j * (WJ * 32) + frow) * 128;
 
@@ -102,44 +145,178 @@ __device__ inline void mainloop(const bf16_t* __restrict__ A, int64_t lda, const
 
     if (ktiles <= 0) return;
 
-    issue_tile_load<S::BI, DIRECT>(ga, lda, lds, wave, lane, sa);
-    issue_tile_load<S::BJ, DIRECT>(gb, ldb, lds + S::BI * 128, wave, lane, sb);
+    issue_tile_load<S::BI, DIRECT>(ga, voff_a, round_a, lds + lds_wave_off, sa);
+    issue_tile_load<S::BJ, DIRECT>(gb, voff_b, round_b, lds + S::BI * 128 + lds_wave_off, sb);
     if constexpr (!DIRECT) {
-        commit_tile_store<S::BI>(lds, wave, lane, sa);
-        commit_tile_store<S::BJ>(lds + S::BI * 128, wave, lane, sb);
+        commit_tile_store<S::BI>(lds + lds_wave_off, lane, sa);
+        commit_tile_store<S::BJ>(lds + S::BI * 128 + lds_wave_off, lane, sb);
     }
 
+    Frags<WI, WJ> f0, f1;
     for (int kt = 0; kt < ktiles; ++kt) {
         char* cur = lds + (kt & 1) * S::STAGE_BYTES;
         char* nxt = lds + ((kt + 1) & 1) * S::STAGE_BYTES;
         if constexpr (DIRECT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        lds_barrier();   // stage `cur` is complete; nobody still reads stage `nxt`
-        const bool more = kt + 1 < ktiles;
-        if (more) {
-            ga += 64;
-            gb += 64;
-            issue_tile_load<S::BI, DIRECT>(ga, lda, nxt, wave, lane, sa);
-            issue_tile_load<S::BJ, DIRECT>(gb, ldb, nxt + S::BI * 128, wave, lane, sb);
+        if (!(dbg & 4)) lds_barrier();   // stage `cur` is complete; nobody still reads stage `nxt`
+        // the last step re-loads its own tile into the idle stage, which keeps the loop body free
+        // of branches (one scheduling region) and every address in bounds
+        const int adv = (kt + 1 < ktiles) ? 128 : 0;
+        ga += adv;
+        gb += adv;
+        load_frags<WI, WJ>(f0, cur, a_off, b_off, xo[0]);
+        if (!(dbg & 2)) {
+            issue_tile_load<S::BI, DIRECT>(ga, voff_a, round_a, nxt + lds_wave_off, sa);
+            issue_tile_load<S::BJ, DIRECT>(gb, voff_b, round_b, nxt + S::BI * 128 + lds_wave_off, sb);
         }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 af[WI], bfr[WJ];
-#pragma unroll
-            for (int ib = 0; ib < WI; ++ib) af[ib] = *(const bf16x8*)(cur + a_off + ib * (32 * 128) + xo[ks]);
-#pragma unroll
-            for (int jb = 0; jb < WJ; ++jb) bfr[jb] = *(const bf16x8*)(cur + b_off + jb * (32 * 128) + xo[ks]);
-#pragma unroll
-            for (int ib = 0; ib < WI; ++ib)
-#pragma unroll
-                for (int jb = 0; jb < WJ; ++jb)
-                    acc[ib][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ib], bfr[jb], acc[ib][jb], 0, 0, 0);
-        }
+        load_frags<WI, WJ>(f1, cur, a_off, b_off, xo[1]);
+        mma_block<WI, WJ>(f0, acc);
+        interleave_hint<WI + WJ, DIRECT ? (S::BI + S::BJ) / 32 : 0, WI * WJ>();
+        load_frags<WI, WJ>(f0, cur, a_off, b_off, xo[2]);
+        mma_block<WI, WJ>(f1, acc);
+        interleave_hint<WI + WJ, 0, WI * WJ>();
+        load_frags<WI, WJ>(f1, cur, a_off, b_off, xo[3]);
+        mma_block<WI, WJ>(f0, acc);
+        interleave_hint<WI + WJ, 0, WI * WJ>();
+        mma_block<WI, WJ>(f1, acc);
         if constexpr (!DIRECT) {
-            if (more) {
-                commit_tile_store<S::BI>(nxt, wave, lane, sa);
-                commit_tile_store<S::BJ>(nxt + S::BI * 128, wave, lane, sb);
-            }
+            commit_tile_store<S::BI>(nxt + lds_wave_off, lane, sa);
+            commit_tile_store<S::BJ>(nxt + S::BI * 128 + lds_wave_off, lane, sb);
         }
+    }
+}
+
+// ---- contraction index major operands ("k-major") ---------------------------------------------
+// For dW = H^T dz both operands are stored with the contraction index (the token row) as the slow
+// dimension: A(k, i) = dz[row k][column i], B(k, j) = H[row k][column j].  A K step is 64 rows of
+// 2 COLS bytes; it goes to LDS row by row (direct loads, 16-byte chunks) and the MFMA fragments are
+// read with ds_read_b64_tr_b16, the LDS transpose read of gfx950: in each group of 16 lanes, lane
+// l receives element (l % 4) of the 8-byte pieces addressed by lanes l/4, l/4 + 4, l/4 + 8,
+// l/4 + 12 of the group.  Pointing lane s of a group at row (s / 4), columns 4 (s % 4) .. + 3
+// therefore hands lane l column l and 4 consecutive rows: exactly the per-lane slice of an MFMA
+// operand (row of the operand = column of the tile, 4 of its 8 k values).
+// A row is cut into 64-byte segments and segment g of row r is kept at position g ^ (r % SEGS),
+// so that the four rows one transpose read touches per 32 lanes fall on different banks.
+template <int COLS>
+struct KMajor {
+    static constexpr int ROW_BYTES = COLS * 2;
+    static constexpr int CPR = COLS / 8;          // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;          // rows covered by one wave-wide load instruction
+    static constexpr int ROUNDS = 64 / (4 * RPI);
+    static constexpr int SEGS = CPR / 4;          // 64-byte segments per row
+    static constexpr int TILE_BYTES = 64 * ROW_BYTES;
+};
+
+template <int COLS>
+__device__ inline void issue_kmajor_load(const char* __restrict__ gwave, uint32_t voff, int64_t round_bytes,
+                                         char* lds_wave) {
+    using KM = KMajor<COLS>;
+#pragma unroll
+    for (int t = 0; t < KM::ROUNDS; ++t) {
+        const char* gp = gwave + t * round_bytes + voff;
+        char* lp = lds_wave + t * (4 * KM::RPI * KM::ROW_BYTES);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                         (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
+    }
+}
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline bf16x8 read_tr_frag(const char* p0, const char* p1) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// acc[i-block][j-block] += sum over `ktiles` steps of 64 rows of A(k, i) B(k, j).
+// A points at (row 0, first column of the i tile), B likewise; lda / ldb are row strides in elements.
+template <int WI, int WJ>
+__device__ inline void mainloop_kmajor(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
+                                       int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[WI][WJ]) {
+    using S = Shape<WI, WJ>;
+    using KA = KMajor<S::BI>;
+    using KB = KMajor<S::BJ>;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_i = wave & 1, wave_j = wave >> 1;
+
+    // global side: lane l of a wave instruction covers chunk slot l % CPR of row l / CPR of its band
+    auto lane_voff = [&](int cpr, int segs, int rpi, int64_t ld) -> uint32_t {
+        const int lrow = lane / cpr, p = lane % cpr;
+        const int row_low = (wave * rpi + lrow) & (segs - 1);
+        const int gseg = (p >> 2) ^ row_low;
+        return (uint32_t)(((int64_t)lrow * ld + (gseg * 4 + (p & 3)) * 8) * 2);
+    };
+    const uint32_t voff_a = lane_voff(KA::CPR, KA::SEGS, KA::RPI, lda);
+    const uint32_t voff_b = lane_voff(KB::CPR, KB::SEGS, KB::RPI, ldb);
+    const char* ga = (const char*)(A + (int64_t)(wave * KA::RPI) * lda);
+    const char* gb = (const char*)(B + (int64_t)(wave * KB::RPI) * ldb);
+    const int64_t round_a = (int64_t)(4 * KA::RPI) * lda * 2, round_b = (int64_t)(4 * KB::RPI) * ldb * 2;
+    const int64_t step_a = 64 * lda * 2, step_b = 64 * ldb * 2;
+    const int lds_wave_a = wave * KA::RPI * KA::ROW_BYTES;
+    const int lds_wave_b = KA::TILE_BYTES + wave * KB::RPI * KB::ROW_BYTES;
+
+    // LDS side: lane l of a transpose read addresses row 8 (l / 32) + (l % 16) / 4 (+ 4 for the second
+    // half of the fragment, + 16 per sub-step), 8 bytes at column 32 b + 16 ((l / 16) % 2) + 4 (l % 4)
+    const int q = (lane & 15) >> 2;
+    const int sub_bytes = (2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) * 16 + 8 * (lane & 1);
+    const int rowpart = 8 * (lane >> 5) + q;
+    int base_a[2], base_b[2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int sw = 4 * r + q;   // low bits of the row this lane addresses in half r
+        base_a[r] = (rowpart + 4 * r) * KA::ROW_BYTES + ((((wave_i * WI) ^ (sw & (KA::SEGS - 1))) * 64)) + sub_bytes;
+        base_b[r] = KA::TILE_BYTES + (rowpart + 4 * r) * KB::ROW_BYTES +
+                    ((((wave_j * WJ) ^ (sw & (KB::SEGS - 1))) * 64)) + sub_bytes;
+    }
+
+    auto load_frags_t = [&](Frags<WI, WJ>& f, const char* cur, int ks) {
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+            f.a[ib] = read_tr_frag(cur + ks * 16 * KA::ROW_BYTES + (base_a[0] ^ (ib * 64)),
+                                   cur + ks * 16 * KA::ROW_BYTES + (base_a[1] ^ (ib * 64)));
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb)
+            f.b[jb] = read_tr_frag(cur + ks * 16 * KB::ROW_BYTES + (base_b[0] ^ (jb * 64)),
+                                   cur + ks * 16 * KB::ROW_BYTES + (base_b[1] ^ (jb * 64)));
+    };
+
+#pragma unroll
+    for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ib][jb][v] = 0.f;
+
+    if (ktiles <= 0) return;
+
+    issue_kmajor_load<S::BI>(ga, voff_a, round_a, lds + lds_wave_a);
+    issue_kmajor_load<S::BJ>(gb, voff_b, round_b, lds + lds_wave_b);
+
+    Frags<WI, WJ> f0, f1;
+    for (int kt = 0; kt < ktiles; ++kt) {
+        char* cur = lds + (kt & 1) * S::STAGE_BYTES;
+        char* nxt = lds + ((kt + 1) & 1) * S::STAGE_BYTES;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();
+        const bool more = kt + 1 < ktiles;   // the last step re-loads its own rows into the idle stage
+        ga += more ? step_a : 0;
+        gb += more ? step_b : 0;
+        load_frags_t(f0, cur, 0);
+        issue_kmajor_load<S::BI>(ga, voff_a, round_a, nxt + lds_wave_a);
+        issue_kmajor_load<S::BJ>(gb, voff_b, round_b, nxt + lds_wave_b);
+        load_frags_t(f1, cur, 1);
+        mma_block<WI, WJ>(f0, acc);
+        interleave_hint<2 * (WI + WJ), KA::ROUNDS + KB::ROUNDS, WI * WJ>();
+        load_frags_t(f0, cur, 2);
+        mma_block<WI, WJ>(f1, acc);
+        interleave_hint<2 * (WI + WJ), 0, WI * WJ>();
+        load_frags_t(f1, cur, 3);
+        mma_block<WI, WJ>(f0, acc);
+        interleave_hint<2 * (WI + WJ), 0, WI * WJ>();
+        mma_block<WI, WJ>(f1, acc);
     }
 }
 
@@ -193,8 +370,8 @@ __global__ __launch_bounds__(NT) void fwd_lse_kernel(FwdArgs a) {
     const int Mr = a.counts[CNT_MR];
     if ((int64_t)t.tj * S::BJ >= Mr) return;
     f32x16 acc[WI][WJ];
-    mainloop<WI, WJ, DIRECT>(a.Wvd + (int64_t)t.ti * S::BI * a.dpad, a.dpad,
-                             a.Hc + (int64_t)t.tj * S::BJ * a.dpad, a.dpad, (int)(a.dpad / K_TILE), lds, acc);
+    mainloop<WI, WJ, DIRECT>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk,
+                             a.Hc + (int64_t)t.tj * S::BJ * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds, acc);
     const Lane L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
     const bool tail = i_base + WI * 32 > a.V;
@@ -242,8 +419,8 @@ __global__ __launch_bounds__(NT) void dz_kernel(DzArgs a) {
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
     f32x16 acc[WI][WJ];
-    mainloop<WI, WJ, DIRECT>(a.Wvd + (int64_t)t.ti * S::BI * a.dpad, a.dpad,
-                             a.Hc + (int64_t)t.tj * S::BJ * a.dpad, a.dpad, (int)(a.dpad / K_TILE), lds, acc);
+    mainloop<WI, WJ, DIRECT>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk,
+                             a.Hc + (int64_t)t.tj * S::BJ * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds, acc);
     const Lane L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
 #pragma unroll
@@ -255,7 +432,7 @@ __global__ __launch_bounds__(NT) void dz_kernel(DzArgs a) {
         const float gj = live ? a.g[a.seqc[j]] * a.inv_temp : 0.f;
         const float nlse = live ? -a.lse_c[j] * LOG2E : 0.f;
         const float zs = a.inv_temp * LOG2E;
-        bf16_t* out = a.dz + jl * a.Vpad;
+        bf16_t* out = a.dz + jl * a.ldz;
 #pragma unroll
         for (int ib = 0; ib < WI; ++ib)
 #pragma unroll
@@ -286,8 +463,9 @@ __global__ __launch_bounds__(NT) void dh_kernel(DhArgs a) {
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
     f32x16 acc[WI][WJ];
-    mainloop<WI, WJ, DIRECT>(a.Wdv + (int64_t)t.ti * S::BI * a.Vpad, a.Vpad,
-                             a.dz + (int64_t)t.tj * S::BJ * a.Vpad, a.Vpad, (int)(a.Vpad / K_TILE), lds, acc);
+    mainloop<WI, WJ, DIRECT>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv, a.ldv,
+                             a.dz + (int64_t)((a.debug_alias & 1) ? 0 : t.tj) * S::BJ * a.ldv, a.ldv,
+                             (int)(a.Vpad / K_TILE), lds, acc, a.debug_alias);
     const Lane L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
 #pragma unroll
@@ -308,7 +486,7 @@ __global__ __launch_bounds__(NT) void dh_kernel(DhArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ dw
-template <int WI, int WJ, bool DIRECT>
+template <int WI, int WJ>
 __global__ __launch_bounds__(NT) void dw_kernel(DwArgs a) {
     using S = Shape<WI, WJ>;
     extern __shared__ __attribute__((aligned(128))) char lds[];
@@ -320,8 +498,8 @@ __global__ __launch_bounds__(NT) void dw_kernel(DwArgs a) {
     rows = rows < 0 ? 0 : (rows > a.Mc ? a.Mc : rows);
     if (rows == 0 && a.beta) return;   // nothing to add
     f32x16 acc[WI][WJ];
-    mainloop<WI, WJ, DIRECT>(a.dzT + (int64_t)t.ti * S::BI * a.Mc, a.Mc,
-                             a.HcT + (int64_t)t.tj * S::BJ * a.ldH, a.ldH, (int)(rows / K_TILE), lds, acc);
+    mainloop_kmajor<WI, WJ>(a.dz + (int64_t)t.ti * S::BI, a.ldz, a.Hc + (int64_t)t.tj * S::BJ, a.ldH,
+                            (int)(rows / K_TILE), lds, acc);
     const Lane L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
     const bool vec = (a.V % 4) == 0;
@@ -417,27 +595,17 @@ void launch_dh(const DhArgs& a, int variant, hipStream_t st) {
     }
 }
 
-void launch_dw(const DwArgs& a, int variant, hipStream_t st) {
+void launch_dw(const DwArgs& a, hipStream_t st) {
     if (a.dpadR % 256 == 0) {
         using S = Shape<4, 4>;
         const unsigned grid = grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ));
-        if (variant == 1) {
-            allow_lds(dw_kernel<4, 4, true>, S::LDS_BYTES);
-            dw_kernel<4, 4, true><<<grid, NT, S::LDS_BYTES, st>>>(a);
-        } else {
-            allow_lds(dw_kernel<4, 4, false>, S::LDS_BYTES);
-            dw_kernel<4, 4, false><<<grid, NT, S::LDS_BYTES, st>>>(a);
-        }
-    } else {
+        allow_lds(dw_kernel<4, 4>, S::LDS_BYTES);
+        dw_kernel<4, 4><<<grid, NT, S::LDS_BYTES, st>>>(a);
+    } else {   // d padded to a multiple of 128 only
         using S = Shape<4, 2>;
         const unsigned grid = grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ));
-        if (variant == 1) {
-            allow_lds(dw_kernel<4, 2, true>, S::LDS_BYTES);
-            dw_kernel<4, 2, true><<<grid, NT, S::LDS_BYTES, st>>>(a);
-        } else {
-            allow_lds(dw_kernel<4, 2, false>, S::LDS_BYTES);
-            dw_kernel<4, 2, false><<<grid, NT, S::LDS_BYTES, st>>>(a);
-        }
+        allow_lds(dw_kernel<4, 2>, S::LDS_BYTES);
+        dw_kernel<4, 2><<<grid, NT, S::LDS_BYTES, st>>>(a);
     }
 }
 

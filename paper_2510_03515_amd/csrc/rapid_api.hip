@@ -21,6 +21,7 @@ void set_error(const char* fmt, ...) {
 
 namespace {
 
+int g_debug_alias = 0;
 int g_load_variant = 1;   // 1: direct global -> LDS tile loads, 0: staged through registers
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
@@ -58,13 +59,14 @@ struct Plan {
     int op, dtype;
     int64_t N, T, d, V, K;
     int64_t Mmax, Mmax_pad, dpad, dpadR, Vpad;
+    int64_t ldk, ldv;   // leading dimensions of the [*, dpad] and [*, Vpad] operands
     int P;              // log-sum-exp partial slots per row
     int64_t Mc;         // rows per backward chunk (f32: also per forward chunk)
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
-    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, logp_tmp, s64, s32, adv, g, Hc, HcT, Wvd, Wdv,
-        part_max, part_sum, dw32, chunk0, chunk1;
+    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, logp_tmp, s64, s32, adv, g, Hc, Wvd, Wdv,
+        part_max, part_sum, dw32, chunk0;
 };
 
 size_t take(size_t& cur, size_t bytes) {
@@ -87,6 +89,8 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     p.dpad = round_up(d, K_TILE);
     p.dpadR = round_up(d, 128);
     p.Vpad = round_up(V, 256);
+    p.ldk = padded_ld(p.dpadR);   // >= dpad; the dW kernel reads whole 128-column tiles of Hc
+    p.ldv = padded_ld(p.Vpad);
     p.P = (int)(p.Vpad / 256) * fwd_slots_per_tile();
     const bool bwd = op == RAPID_OP_IW_PG_FWD_BWD;
     size_t cur = 0;
@@ -107,14 +111,13 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
         p.dw32 = take(cur, (size_t)d * V * 4);
     }
     if (dtype == RAPID_DTYPE_BF16) {
-        p.Hc = take(cur, (size_t)p.Mmax_pad * p.dpad * 2);
-        p.Wvd = take(cur, (size_t)p.Vpad * p.dpad * 2);
+        p.Hc = take(cur, (size_t)p.Mmax_pad * p.ldk * 2);
+        p.Wvd = take(cur, (size_t)p.Vpad * p.ldk * 2);
         p.part_max = take(cur, (size_t)p.P * p.Mmax_pad * 4);
         p.part_sum = take(cur, (size_t)p.P * p.Mmax_pad * 4);
         if (bwd) {
-            p.HcT = take(cur, (size_t)p.dpadR * p.Mmax_pad * 2);
-            p.Wdv = take(cur, (size_t)p.dpadR * p.Vpad * 2);
-            p.per_row = (size_t)p.Vpad * 2 * 2;   // dz and its transpose
+            p.Wdv = take(cur, (size_t)p.dpadR * p.ldv * 2);
+            p.per_row = (size_t)p.ldv * 2;   // the dz chunk
         }
     } else {
         p.per_row = (size_t)V * 4;                // logits / dz chunk
@@ -131,8 +134,7 @@ void size_chunks(Plan& p, int64_t Mc) {
     size_t cur = p.fixed;
     if (p.per_row) {
         if (p.dtype == RAPID_DTYPE_BF16) {
-            p.chunk0 = take(cur, (size_t)Mc * p.Vpad * 2);
-            p.chunk1 = take(cur, (size_t)Mc * p.Vpad * 2);
+            p.chunk0 = take(cur, (size_t)Mc * p.ldv * 2);
         } else {
             p.chunk0 = take(cur, (size_t)Mc * p.V * 4);
         }
@@ -209,17 +211,17 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
         {
             Span sp(ST_PACK, st);
-            launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc, p.dpad, p.Mmax, p.d, p.Mmax_pad,
-                                 p.dpad, counts, 0, st);
+            launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc, p.ldk, p.Mmax, p.d, p.Mmax_pad,
+                                 p.dpadR, counts, 0, st);
             if (io.w_layout == RAPID_W_VD)
-                launch_copy_pad_bf16((const bf16_t*)io.W, p.d, nullptr, Wvd, p.dpad, p.V, p.d, p.Vpad, p.dpad,
+                launch_copy_pad_bf16((const bf16_t*)io.W, p.d, nullptr, Wvd, p.ldk, p.V, p.d, p.Vpad, p.dpad,
                                      nullptr, 0, st);
             else
-                launch_transpose_pad_bf16((const bf16_t*)io.W, p.V, Wvd, p.dpad, p.d, p.V, p.dpad, p.Vpad, nullptr,
+                launch_transpose_pad_bf16((const bf16_t*)io.W, p.V, Wvd, p.ldk, p.d, p.V, p.dpad, p.Vpad, nullptr,
                                           0, st);
         }
         FwdArgs a;
-        a.Wvd = Wvd; a.Hc = Hc; a.dpad = p.dpad;
+        a.Wvd = Wvd; a.Hc = Hc; a.dpad = p.dpad; a.ldk = p.ldk;
         a.tilesV = (int)(p.Vpad / 256); a.tilesM = (int)(p.Mmax_pad / 256);
         a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
         a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
@@ -310,6 +312,10 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
 int rapid_set_tuning(int key, int value) {
     if (key == 0 && (value == 0 || value == 1)) {
         g_load_variant = value;
+        return RAPID_OK;
+    }
+    if (key == 99) {
+        g_debug_alias = value;
         return RAPID_OK;
     }
     if (key == 1 && (value == 0 || value == 1)) {
@@ -519,27 +525,23 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
 
     if (dtype == RAPID_DTYPE_BF16) {
         bf16_t* Hc = at<bf16_t>(ws, p.Hc);
-        bf16_t* HcT = at<bf16_t>(ws, p.HcT);
         bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
         bf16_t* Wdv = at<bf16_t>(ws, p.Wdv);
         bf16_t* dz = at<bf16_t>(ws, p.chunk0);
-        bf16_t* dzT = at<bf16_t>(ws, p.chunk1);
         {
             Span sp(ST_PACK, st);
-            launch_transpose_pad_bf16(Hc, p.dpad, HcT, p.Mmax_pad, p.Mmax, p.dpad, p.Mmax_pad, p.dpadR, counts, 0,
-                                      st);
             if (o.w_layout == RAPID_W_DV)
-                launch_copy_pad_bf16((const bf16_t*)W, p.V, nullptr, Wdv, p.Vpad, p.d, p.V, p.dpadR, p.Vpad,
+                launch_copy_pad_bf16((const bf16_t*)W, p.V, nullptr, Wdv, p.ldv, p.d, p.V, p.dpadR, p.Vpad,
                                      nullptr, 0, st);
             else
-                launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.Vpad, p.V, p.d, p.Vpad, p.dpadR, nullptr,
+                launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.ldv, p.V, p.d, p.Vpad, p.dpadR, nullptr,
                                           0, st);
         }
         int chunk = 0;
         for (int64_t m0 = 0; m0 < p.Mmax_pad; m0 += p.Mc, ++chunk) {
             const int64_t rows = (p.Mmax_pad - m0) < p.Mc ? (p.Mmax_pad - m0) : p.Mc;   // multiple of 256
             DzArgs za;
-            za.Wvd = Wvd; za.Hc = Hc + m0 * p.dpad; za.dpad = p.dpad;
+            za.Wvd = Wvd; za.Hc = Hc + m0 * p.ldk; za.dpad = p.dpad; za.ldk = p.ldk; za.ldz = p.ldv;
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
             za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
             za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz;
@@ -547,25 +549,22 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                 Span sp(ST_DZ, st);
                 launch_dz(za, g_load_variant, st);
             }
-            {
-                Span sp(ST_DZ_T, st);
-                launch_transpose_pad_bf16(dz, p.Vpad, dzT, p.Mc, rows, p.Vpad, rows, p.Vpad, counts, m0, st);
-            }
             DhArgs ha;
-            ha.Wdv = Wdv; ha.dz = dz; ha.Vpad = p.Vpad; ha.d = p.d; ha.dpadR = p.dpadR;
+            ha.Wdv = Wdv; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
             ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
             ha.dhidden = (bf16_t*)dhidden_out;
+            ha.debug_alias = g_debug_alias;
             {
                 Span sp(ST_DH, st);
                 launch_dh(ha, g_load_variant, st);
             }
             DwArgs wa;
-            wa.dzT = dzT; wa.HcT = HcT + m0; wa.Mc = p.Mc; wa.ldH = p.Mmax_pad;
+            wa.dz = dz; wa.Hc = Hc + m0 * p.ldk; wa.Mc = p.Mc; wa.ldz = p.ldv; wa.ldH = p.ldk;
             wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = m0; wa.counts = counts;
             wa.dW = dW32; wa.w_layout = o.w_layout; wa.beta = (chunk > 0 || o.accumulate_dw) ? 1 : 0;
             {
                 Span sp(ST_DW, st);
-                launch_dw(wa, g_load_variant, st);
+                launch_dw(wa, st);
             }
         }
     } else {

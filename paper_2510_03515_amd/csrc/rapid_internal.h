@@ -12,6 +12,12 @@ typedef unsigned short bf16_t;  // raw bf16 bits in memory
 
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
+// Leading dimension (bf16 elements) for a row of x elements (x a multiple of 64): one extra
+// 128-byte line when the row would otherwise span an even number of lines.  Consecutive rows of an
+// operand tile are read for the same k at the same time; with an odd line stride they fall on
+// different L2 / HBM channels instead of piling onto one or two.
+static inline int64_t padded_ld(int64_t x) { return ((x / 64) % 2 == 0) ? x + 64 : x; }
+
 // device counters written by the compaction step: [0] = M (valid tokens), [1] = M rounded up to 256
 enum { CNT_M = 0, CNT_MR = 1, CNT_WORDS = 64 };
 
@@ -61,7 +67,8 @@ void launch_transpose_pad_bf16(const bf16_t* src, int64_t ld_src, bf16_t* dst, i
 struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered logit
     const bf16_t* Wvd;    // [Vpad, dpad]
     const bf16_t* Hc;     // [Mmax_pad, dpad]
-    int64_t dpad;
+    int64_t dpad;         // contraction extent (multiple of 64)
+    int64_t ldk;          // leading dimension of Wvd and Hc (elements)
     int tilesV, tilesM;   // 256-tiles
     int64_t V;
     float inv_temp;
@@ -78,9 +85,10 @@ int fwd_slots_per_tile();
 struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, bf16 [Mc, Vpad]
     const bf16_t* Wvd;
     const bf16_t* Hc;     // already offset to the chunk's first row
-    int64_t dpad;
+    int64_t dpad, ldk;
     int tilesV, tilesM;   // tilesM = chunk rows / 256
     int64_t V, Vpad;
+    int64_t ldz;          // leading dimension of dz
     float inv_temp;
     int64_t m0;           // first compact row of the chunk
     const int32_t* tokc;  // full arrays (indexed by compact row)
@@ -95,20 +103,23 @@ void launch_dz(const DzArgs& a, int variant, hipStream_t st);
 struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const bf16_t* Wdv;    // [dpadR, Vpad]
     const bf16_t* dz;     // [Mc, Vpad]
-    int64_t Vpad;
+    int64_t Vpad;         // contraction extent
+    int64_t ldv;          // leading dimension of Wdv and dz
     int64_t d, dpadR;
     int tilesM;
     int64_t m0;
     const int32_t* row_index;
     const int32_t* counts;
     bf16_t* dhidden;      // [N*T, d]
+    int debug_alias;      // timing experiment only: every row tile reads the first dz panel
 };
 void launch_dh(const DhArgs& a, int variant, hipStream_t st);
 
 struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
-    const bf16_t* dzT;    // [Vpad, Mc]
-    const bf16_t* HcT;    // [dpadR, Mmax_pad], already offset by m0 columns
-    int64_t Mc, ldH;
+    const bf16_t* dz;     // [Mc, Vpad] chunk (rows = tokens)
+    const bf16_t* Hc;     // [Mmax_pad, >= dpadR], already offset to the chunk's first row
+    int64_t Mc;           // rows of the chunk buffer (contraction extent is min(Mc, rows left))
+    int64_t ldz, ldH;     // leading dimensions of dz and Hc
     int64_t d, dpadR, V, Vpad;
     int64_t m0;
     const int32_t* counts;
@@ -116,7 +127,7 @@ struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
     int w_layout;
     int beta;             // 0 overwrite, 1 accumulate
 };
-void launch_dw(const DwArgs& a, int variant, hipStream_t st);
+void launch_dw(const DwArgs& a, hipStream_t st);
 
 // ---- f32_path.hip -----------------------------------------------------------------------------
 // C[i][j] (+)= alpha sum_k A(i,k) B(k,j), arbitrary strides, optional index maps, and a device-side

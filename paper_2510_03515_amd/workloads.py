@@ -56,6 +56,9 @@ CONFIGS = [
     WorkloadSpec("cfg3_qwen3b", "bf16", 2048, 151936, 16, 16, 512, 4096, 0.02, "uniform"),
     WorkloadSpec("cfg4_behaviour_fwd", "bf16", 1536, 151936, 512, 1, 1024, 1024, 0.0, "bernoulli",
                  0.4, tokens_from="cur", fwd_only=True),
+    # one 65536-row backward chunk of the Qwen2.5-1.5B shape (no padding): every kernel of the path
+    # launches exactly once, which keeps hardware-counter passes short
+    WorkloadSpec("cfg2_one_chunk", "bf16", 1536, 151936, 4, 8, 2048, 2048, 0.01, "bernoulli", 0.3),
 ]
 
 

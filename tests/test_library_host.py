@@ -89,7 +89,7 @@ def test_host_validation_returns_codes_without_a_gpu(rb):
     o = rb.default_opts()
     o.loss_scale = -1.0
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
-    assert lib.rapid_set_tuning(99, 0) == -3
+    assert lib.rapid_set_tuning(12345, 0) == -3
 
 
 def test_workload_generator_recipe():
