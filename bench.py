@@ -65,8 +65,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (2 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workspace-gib", type=float, default=0.0, help="0 = the library's recommended size")
-    ap.add_argument("--load-variant", type=int, default=1)
-    ap.add_argument("--debug-alias", type=int, default=0)
+    ap.add_argument("--dbg", type=int, default=0, help="kernel timing experiments (results invalid)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -82,10 +81,9 @@ def main():
     w = wl.make_workload(spec, seed=0, device="cuda")
     N, T, d, V, K = spec.N, spec.T, spec.d, spec.V, w["K"]
     M = int(w["mask"].sum().item())
-    rb.rapid_set_tuning(0, args.load_variant)
-    if args.debug_alias:
-        rb.rapid_set_tuning(99, args.debug_alias)
 
+    if args.dbg:
+        rb.rapid_set_tuning(99, args.dbg)
     fwd_only = spec.fwd_only
     if fwd_only:
         ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, rb.DTYPE_BF16)

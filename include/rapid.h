@@ -100,9 +100,7 @@ const char* rapid_last_error(void);
 /* Fills *opts with the defaults described above.  Host pointer. */
 void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
 
-/* Process-wide tuning switches (host state, not thread-safe against concurrent calls).
- * key 0: how the MFMA kernels bring operand tiles into LDS: 1 = direct global->LDS loads
- * (default), 0 = staged through registers.  Results are identical either way.
+/* Process-wide switches (host state, not thread-safe against concurrent calls).
  * key 1: per-stage event timing on (1) / off (0, default); see rapid_profile_read. */
 int rapid_set_tuning(int key, int value);
 

@@ -69,7 +69,7 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     const bf16_t* Hc;     // [Mmax_pad, dpad]
     int64_t dpad;         // contraction extent (multiple of 64)
     int64_t ldk;          // leading dimension of Wvd and Hc (elements)
-    int tilesV, tilesM;   // 256-tiles
+    int tilesV, tilesM;   // 256-tiles (tilesM: upper bound; the kernel uses the rows that hold tokens)
     int64_t V;
     float inv_temp;
     const int32_t* tokc;
@@ -78,8 +78,9 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     float* part_sum;
     int64_t ld_part;
     float* zy;            // [Mmax_pad]
+    int dbg;              // timing experiments: 1 = tile loads only, 2 = no tile loads (results invalid)
 };
-void launch_fwd_lse(const FwdArgs& a, int variant, hipStream_t st);
+void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
 int fwd_slots_per_tile();
 
 struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, bf16 [Mc, Vpad]
@@ -97,8 +98,9 @@ struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, b
     const float* g;       // [N]
     const int32_t* counts;
     bf16_t* dz;           // [Mc, Vpad]
+    int dbg;              // timing experiments: 1 = tile loads only, 2 = no tile loads (results invalid)
 };
-void launch_dz(const DzArgs& a, int variant, hipStream_t st);
+void launch_dz(const DzArgs& a, hipStream_t st);
 
 struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const bf16_t* Wdv;    // [dpadR, Vpad]
@@ -111,9 +113,9 @@ struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const int32_t* row_index;
     const int32_t* counts;
     bf16_t* dhidden;      // [N*T, d]
-    int debug_alias;      // timing experiment only: every row tile reads the first dz panel
+    int dbg;              // timing experiments: 1 = tile loads only, 2 = no tile loads (results invalid)
 };
-void launch_dh(const DhArgs& a, int variant, hipStream_t st);
+void launch_dh(const DhArgs& a, hipStream_t st);
 
 struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
     const bf16_t* dz;     // [Mc, Vpad] chunk (rows = tokens)
@@ -126,6 +128,7 @@ struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
     float* dW;            // fp32, layout per w_layout
     int w_layout;
     int beta;             // 0 overwrite, 1 accumulate
+    int dbg;              // timing experiments: 1 = tile loads only, 2 = no tile loads (results invalid)
 };
 void launch_dw(const DwArgs& a, hipStream_t st);
 
