@@ -65,7 +65,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (2 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workspace-gib", type=float, default=0.0, help="0 = the library's recommended size")
-    ap.add_argument("--dbg", type=int, default=0, help="kernel timing experiments (results invalid)")
+    ap.add_argument("--chunk-rows", type=int, default=0, help="size the workspace for backward chunks of this many rows")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -82,8 +82,6 @@ def main():
     N, T, d, V, K = spec.N, spec.T, spec.d, spec.V, w["K"]
     M = int(w["mask"].sum().item())
 
-    if args.dbg:
-        rb.rapid_set_tuning(99, args.dbg)
     fwd_only = spec.fwd_only
     if fwd_only:
         ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, rb.DTYPE_BF16)
@@ -94,6 +92,11 @@ def main():
         logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"])
         w["logp_behav"] = logp_b
         ws_bytes = int(args.workspace_gib * 2**30) if args.workspace_gib > 0 else None
+        if args.chunk_rows:
+            mn = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, N, T, d, V, K, rb.DTYPE_BF16, minimum=True)
+            vpad = (V + 255) // 256 * 256
+            ldv = vpad + 64 if (vpad // 64) % 2 == 0 else vpad
+            ws_bytes = mn + (args.chunk_rows - 256) * ldv * 2
         buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes)
         ws_bytes = buf.workspace.numel()
         step = lambda: rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b,

@@ -78,7 +78,6 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     float* part_sum;
     int64_t ld_part;
     float* zy;            // [Mmax_pad]
-    int dbg;              // timing experiments: 1 = tile loads only, 2 = no tile loads (results invalid)
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
 int fwd_slots_per_tile();
@@ -98,7 +97,6 @@ struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, b
     const float* g;       // [N]
     const int32_t* counts;
     bf16_t* dz;           // [Mc, Vpad]
-    int dbg;              // timing experiments: 1 = tile loads only, 2 = no tile loads (results invalid)
 };
 void launch_dz(const DzArgs& a, hipStream_t st);
 
@@ -113,7 +111,6 @@ struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const int32_t* row_index;
     const int32_t* counts;
     bf16_t* dhidden;      // [N*T, d]
-    int dbg;              // timing experiments: 1 = tile loads only, 2 = no tile loads (results invalid)
 };
 void launch_dh(const DhArgs& a, hipStream_t st);
 
@@ -128,7 +125,6 @@ struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
     float* dW;            // fp32, layout per w_layout
     int w_layout;
     int beta;             // 0 overwrite, 1 accumulate
-    int dbg;              // timing experiments: 1 = tile loads only, 2 = no tile loads (results invalid)
 };
 void launch_dw(const DwArgs& a, hipStream_t st);
 
