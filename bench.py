@@ -20,6 +20,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
 PEAK_HBM = 8.0e12         # B/s
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled (see the profile named in the output), per launch:
+# fwd_lse on 300630 rows; dz / dh / dw on a full 65536-row chunk
+MEASURED_TRAFFIC_BYTES = {"fwd_lse": 207e9 + 11.7e9, "dz": 45.1e9 + 20.4e9, "dh": 59e9 + 0.2e9, "dw": 64.5e9 + 0.93e9}
 
 
 def cpu_baseline(w, tokens_per_seq=256):
@@ -140,8 +143,13 @@ def main():
     else:
         live, tokens_per_launch, avg_ms = 1, M, stages[dom]["avg_ms"]
     achieved = 2.0 * d * V * tokens_per_launch / (avg_ms * 1e-3) / 1e12
+    # HBM-side bytes per full launch from rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by a copy
+    # kernel of known size); measured on the headline workload only, see profiles/
+    traffic = MEASURED_TRAFFIC_BYTES.get(dom) if spec.name == "cfg2_qwen1.5b" else None
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA / 1e12,
-                "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_MFMA / 1e12), "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_MFMA / 1e12), "traffic": traffic,
+                "traffic_unit": "bytes per full launch (fabric reads + writes)",
+                "traffic_source": "profiles/bench_cfg2_qwen1.5b_kernel_trace_and_traffic.md",
                 "avg_launch_ms": avg_ms, "live_launches_per_step": live,
                 "tokens_per_launch": tokens_per_launch, "flop_per_token": 2.0 * d * V}
 

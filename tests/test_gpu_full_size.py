@@ -1,0 +1,145 @@
+"""Full-size parity, in the launch configuration bench.py times (config 2: d=1536, V=151936,
+256 generations, ~300k response tokens, recommended workspace), on sampled outputs the oracle can
+compute one by one and on properties that hold at any size.  Also the forward-only behaviour pass
+of config 4 on sampled rows."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rapid_oracle as orc
+from paper_2510_03515_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rb():
+    from paper_2510_03515_amd import binding
+    binding.load()
+    return binding
+
+
+def _f64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def _row_oracle(w, W64, n, t):
+    """Oracle log-prob / lse of one position: the slice [n:n+1, t:t+1] of the batch."""
+    lp, lse = orc.logprob(_f64(w["hidden"][n:n + 1, t:t + 1]), W64, w["tokens"][n:n + 1, t:t + 1].cpu().numpy(),
+                          np.ones((1, 1), np.uint8))
+    return lp[0, 0], lse[0, 0]
+
+
+def test_config2_sampled_parity(rb):
+    spec = wl.CONFIGS[2]
+    print("generating", spec.name, flush=True)
+    w = wl.make_workload(spec, seed=0, device="cuda")
+    N, T, K = spec.N, spec.T, w["K"]
+    logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"])
+    buf = rb.IwPgBuffers(w["hidden"], w["W"], K)
+    print("fused call", flush=True)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b, w["rewards"],
+                                      w["group_ids"], K, buffers=buf, normalized_grads=True)
+    lp_cur2, lse_gpu = rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], want_lse=True)
+    torch.cuda.synchronize()
+    assert out.dev_status.item() == 0
+    assert torch.equal(lp_cur2, out.logp_cur)          # same bits from both entry points
+    mask = w["mask"].cpu().numpy()
+    lengths = mask.sum(1)
+    W64 = _f64(w["W"])
+    rng = np.random.default_rng(0)
+
+    # (a) bit-exact integer work
+    seq_len, cu, row_index = rb.rapid_compaction(w["mask"])
+    o_len, o_cu, o_rows = orc.compaction(mask)
+    M = int(o_cu[-1])
+    assert np.array_equal(seq_len.cpu().numpy(), o_len) and np.array_equal(cu.cpu().numpy(), o_cu)
+    assert np.array_equal(row_index.cpu().numpy()[:M], o_rows)
+    dg = out.read_diag()
+    assert dg["n_tokens"] == M and dg["n_sequences"] == N
+
+    # (b) sampled log-probs against the oracle, position by position (incl. first/last rows and tiles)
+    print("sampled logp", flush=True)
+    pos = [(0, 0), (N - 1, int(lengths[N - 1]) - 1)]
+    for _ in range(30):
+        n = int(rng.integers(0, N))
+        pos.append((n, int(rng.integers(0, lengths[n]))))
+    lp_gpu, lse_g = _f64(out.logp_cur), _f64(lse_gpu)
+    for n, t in pos:
+        lp, lse = _row_oracle(w, W64, n, t)
+        assert abs(lp_gpu[n, t] - lp) <= 2e-5, (n, t)
+        assert abs(lse_g[n, t] - lse) <= 2e-5, (n, t)
+    assert np.all(lp_gpu[mask == 0] == 0.0)
+
+    # (c) generation-level log ratio of the two shortest generations, whole sequences by the oracle
+    print("sequence ratios", flush=True)
+    s_gpu = _f64(out.seq_logratio)
+    for n in np.argsort(lengths)[:2]:
+        L = int(lengths[n])
+        lp, _ = orc.logprob(_f64(w["hidden"][n:n + 1, :L]), W64, w["tokens"][n:n + 1, :L].cpu().numpy(),
+                            np.ones((1, L), np.uint8))
+        s = orc.seq_logratio(lp, _f64(logp_b[n:n + 1, :L]), np.ones((1, L), np.uint8))[0]
+        assert abs(s_gpu[n] - s) <= 1e-3, (n, s_gpu[n], s)
+    # every s_n equals the sum of the token log ratios the library reports (fp64 sum on the host)
+    assert np.abs(_f64(out.tok_logratio).sum(1) - s_gpu).max() <= 1e-3
+
+    # (d) advantages, coefficients, loss recomputed by the oracle from the generation-level ratios
+    R, gid = _f64(w["rewards"]), w["group_ids"].cpu().numpy()
+    ga = orc.group_advantage(R, gid, K, s=s_gpu, eta=2.0)
+    assert np.abs(_f64(out.adv) - ga["adv"]).max() <= 1e-5
+    assert np.all(_f64(out.adv)[gid == 0] == 0.0)                       # forced all-0 group
+    g_ref, loss_ref, lam = orc.coefficients(s_gpu, ga["adv"], 2.0, 0, 1.0, normalized=True)
+    assert abs(dg["grad_log_scale"] - lam) <= 1e-3
+    assert abs(out.loss.item() - loss_ref) <= 1e-3 * abs(loss_ref)
+    assert dg["n_clipped"] == int((s_gpu > math.log(2.0)).sum())
+
+    # (e) sampled dHidden rows: g_n (W[:, y] - W p) with p from the oracle for that row
+    print("sampled dH rows", flush=True)
+    live = np.argsort(-np.abs(g_ref))[:4]        # generations that carry the gradient
+    dH = out.dhidden
+    for n in live:
+        for t in {0, int(lengths[n]) - 1, int(rng.integers(0, lengths[n]))}:
+            dh_ref, _ = orc.backward(_f64(w["hidden"][n:n + 1, t:t + 1]), W64,
+                                     w["tokens"][n:n + 1, t:t + 1].cpu().numpy(), np.ones((1, 1), np.uint8),
+                                     np.array([g_ref[n]]))
+            got = _f64(dH[n, t])
+            assert np.linalg.norm(got - dh_ref[0, 0]) <= 2e-2 * np.linalg.norm(dh_ref[0, 0]), (n, t)
+    n_pad = int(np.argmin(lengths))
+    assert torch.all(dH[n_pad, int(lengths[n_pad]):] == 0)              # masked rows are zero
+
+    # (f) dW: every row sums to zero over the vocabulary (softmax identity, any size); sampled columns
+    # against sum_m g_m (1[y_m = v] - exp(h_m . W_v - lse_m)) h_m with the (sample-checked) lse
+    print("dW properties", flush=True)
+    dW = out.dW
+    rowsum = dW.double().sum(1).cpu().numpy()
+    scale = dW.double().abs().sum(1).cpu().numpy()
+    assert np.abs(rowsum).max() <= 2e-3 * scale.max()
+    idx = torch.nonzero(w["mask"].view(-1), as_tuple=False).view(-1)
+    Hv = w["hidden"].view(N * T, -1)[idx].double()                      # [M, d] on the GPU, fp64
+    g_rows = torch.tensor(g_ref, device="cuda")[idx // T]
+    lse_rows = lse_gpu.view(-1)[idx].double()
+    tok_rows = w["tokens"].view(-1)[idx]
+    for v in [0, 5, spec.V - 1, int(w["tokens"][int(live[0]), 0].item())] + [int(x) for x in rng.integers(0, spec.V, 3)]:
+        z = Hv @ w["W"][:, v].double()
+        coef = g_rows * ((tok_rows == v).double() - torch.exp(z - lse_rows))
+        col = (Hv * coef[:, None]).sum(0).cpu().numpy()
+        got = _f64(dW[:, v])
+        assert np.linalg.norm(got - col) <= 2e-2 * max(np.linalg.norm(col), 1e-30), v
+
+
+def test_config4_behaviour_pass_sampled(rb):
+    spec = wl.CONFIGS[4]
+    print("generating", spec.name, flush=True)
+    w = wl.make_workload(spec, seed=0, device="cuda")
+    lp, lse = rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], want_lse=True)
+    torch.cuda.synchronize()
+    W64 = _f64(w["W"])
+    rng = np.random.default_rng(1)
+    lp_g, lse_g = _f64(lp), _f64(lse)
+    for n, t in [(0, 0), (spec.N - 1, spec.T - 1)] + [(int(rng.integers(0, spec.N)), int(rng.integers(0, spec.T)))
+                                                       for _ in range(20)]:
+        r_lp, r_lse = _row_oracle(w, W64, n, t)
+        assert abs(lp_g[n, t] - r_lp) <= 2e-5 and abs(lse_g[n, t] - r_lse) <= 2e-5, (n, t)
+    assert np.isfinite(lp_g).all() and (lp_g < 0).all()
