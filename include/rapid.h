@@ -101,7 +101,9 @@ const char* rapid_last_error(void);
 void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
 
 /* Process-wide switches (host state, not thread-safe against concurrent calls).
- * key 1: per-stage event timing on (1) / off (0, default); see rapid_profile_read. */
+ * key 1: per-stage event timing on (1) / off (0, default); see rapid_profile_read.
+ * key 2: waves per workgroup of the contraction kernels, 8 (default: 2 x 4 waves of 128 x 64) or
+ *        4 (2 x 2 waves of 128 x 128).  Same 256 x 256 tile and same results either way. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

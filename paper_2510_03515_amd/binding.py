@@ -80,6 +80,8 @@ def load():
     lib.rapid_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64), ci]
     lib.rapid_profile_read.restype = ci
     _lib = lib
+    if os.environ.get("RAPID_WAVES"):      # 4, 8 or 16 waves per contraction workgroup (tuning only)
+        lib.rapid_set_tuning(2, int(os.environ["RAPID_WAVES"]))
     return lib
 
 

@@ -37,12 +37,17 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int NT = 256;              // threads per workgroup
 constexpr float LOG2E = 1.4426950408889634f;
 
-template <int WI, int WJ>
-struct Shape {
-    static constexpr int BI = 64 * WI, BJ = 64 * WJ;
+// Geometry of a workgroup: NWI x NWJ waves, each owning WI x WJ blocks of 32 x 32.
+// Two are used: 2 x 2 waves of 128 x 128 (one wave per SIMD, 256 accumulator registers per lane) and
+// 2 x 4 waves of 128 x 64 (two waves per SIMD, which lets the hardware overlap one wave's LDS and
+// barrier waits with the other's MFMAs at the price of 1.5x the LDS fragment reads).
+template <int NWI_, int NWJ_, int WI_, int WJ_>
+struct Geo {
+    static constexpr int NWI = NWI_, NWJ = NWJ_, WI = WI_, WJ = WJ_;
+    static constexpr int NW = NWI * NWJ, NT = 64 * NW;
+    static constexpr int BI = NWI * WI * 32, BJ = NWJ * WJ * 32;
     static constexpr int STAGE_BYTES = (BI + BJ) * 128;
     static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
 };
@@ -52,15 +57,15 @@ __device__ __forceinline__ void lds_barrier() { __syncthreads(); }
 // Requests one K step (64 columns) of a tile with ROWS rows: direct memory -> LDS loads, 16 bytes
 // per lane.  `gwave` is the wave-uniform address of the wave's first row of round 0 (scalar
 // registers), `voff` the lane's byte offset from it (row lane/8 of the 8-row band, swizzled chunk),
-// `round_bytes` the uniform distance between rounds (32 rows); lane l's chunk lands at
+// `round_bytes` the uniform distance between rounds (8 rows per wave); lane l's chunk lands at
 // lds_wave + 16 l of each round.
-template <int ROWS>
+template <int ROWS, int NW>
 __device__ __forceinline__ void issue_tile_load(const char* __restrict__ gwave, uint32_t voff, int64_t round_bytes,
                                                 char* lds_wave) {
 #pragma unroll
-    for (int t = 0; t < ROWS / 32; ++t)
+    for (int t = 0; t < ROWS / (8 * NW); ++t)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gwave + t * round_bytes + voff),
-                                         (__attribute__((address_space(3))) void*)(lds_wave + t * (32 * 128)), 16, 0, 0);
+                                         (__attribute__((address_space(3))) void*)(lds_wave + t * (8 * NW * 128)), 16, 0, 0);
 }
 
 template <int WI, int WJ>
@@ -102,14 +107,14 @@ __device__ __forceinline__ void interleave_hint() {
 }
 
 // acc += A_tile . B_tile^T over `ktiles` steps of 64.  A / B point at the tile's first row, k = 0.
-template <int WI, int WJ>
+template <class S>
 __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
-                                int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[WI][WJ]) {
-    using S = Shape<WI, WJ>;
+                                         int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[S::WI][S::WJ]) {
+    constexpr int WI = S::WI, WJ = S::WJ;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_i = wave & 1, wave_j = wave >> 1;
+    const int wave_i = wave % S::NWI, wave_j = wave / S::NWI;
 
     // global side of the tile loads: lane l of a wave covers row l/8 of the wave's 8-row band and
     // the chunk that belongs at slot l%8 of that row
@@ -118,7 +123,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     const uint32_t voff_b = (uint32_t)(((int64_t)(lane >> 3) * ldb + gchunk * 8) * 2);
     const char* ga = (const char*)(A + (int64_t)(wave * 8) * lda);
     const char* gb = (const char*)(B + (int64_t)(wave * 8) * ldb);
-    const int64_t round_a = 32 * lda * 2, round_b = 32 * ldb * 2;
+    const int64_t round_a = (8 * S::NW) * lda * 2, round_b = (8 * S::NW) * ldb * 2;
     const int lds_wave_off = wave * 8 * 128;
 
     // LDS side of the fragment reads
@@ -138,8 +143,8 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 
     if (ktiles <= 0) return;
 
-    issue_tile_load<S::BI>(ga, voff_a, round_a, lds + lds_wave_off);
-    issue_tile_load<S::BJ>(gb, voff_b, round_b, lds + S::BI * 128 + lds_wave_off);
+    issue_tile_load<S::BI, S::NW>(ga, voff_a, round_a, lds + lds_wave_off);
+    issue_tile_load<S::BJ, S::NW>(gb, voff_b, round_b, lds + S::BI * 128 + lds_wave_off);
 
     Frags<WI, WJ> f0, f1;
     for (int kt = 0; kt < ktiles; ++kt) {
@@ -153,11 +158,11 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         ga += adv;
         gb += adv;
         load_frags<WI, WJ>(f0, cur, a_off, b_off, xo[0]);
-        issue_tile_load<S::BI>(ga, voff_a, round_a, nxt + lds_wave_off);
-        issue_tile_load<S::BJ>(gb, voff_b, round_b, nxt + S::BI * 128 + lds_wave_off);
+        issue_tile_load<S::BI, S::NW>(ga, voff_a, round_a, nxt + lds_wave_off);
+        issue_tile_load<S::BJ, S::NW>(gb, voff_b, round_b, nxt + S::BI * 128 + lds_wave_off);
         load_frags<WI, WJ>(f1, cur, a_off, b_off, xo[1]);
         mma_block<WI, WJ>(f0, acc);
-        interleave_hint<WI + WJ, (S::BI + S::BJ) / 32, WI * WJ>();
+        interleave_hint<WI + WJ, (S::BI + S::BJ) / (8 * S::NW), WI * WJ>();
         load_frags<WI, WJ>(f0, cur, a_off, b_off, xo[2]);
         mma_block<WI, WJ>(f1, acc);
         interleave_hint<WI + WJ, 0, WI * WJ>();
@@ -179,24 +184,25 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 // operand (row of the operand = column of the tile, 4 of its 8 k values).
 // A row is cut into 64-byte segments and segment g of row r is kept at position g ^ (r % SEGS),
 // so that the four rows one transpose read touches per 32 lanes fall on different banks.
-template <int COLS>
+template <int COLS, int NW>
 struct KMajor {
     static constexpr int ROW_BYTES = COLS * 2;
     static constexpr int CPR = COLS / 8;          // 16-byte chunks per row
     static constexpr int RPI = 64 / CPR;          // rows covered by one wave-wide load instruction
-    static constexpr int ROUNDS = 64 / (4 * RPI);
+    static constexpr int ROUNDS = 64 / (NW * RPI);
+    static constexpr int ROUND_ROWS = NW * RPI;
     static constexpr int SEGS = CPR / 4;          // 64-byte segments per row
     static constexpr int TILE_BYTES = 64 * ROW_BYTES;
 };
 
-template <int COLS>
+template <int COLS, int NW>
 __device__ __forceinline__ void issue_kmajor_load(const char* __restrict__ gwave, uint32_t voff, int64_t round_bytes,
-                                         char* lds_wave) {
-    using KM = KMajor<COLS>;
+                                                  char* lds_wave) {
+    using KM = KMajor<COLS, NW>;
 #pragma unroll
     for (int t = 0; t < KM::ROUNDS; ++t) {
         const char* gp = gwave + t * round_bytes + voff;
-        char* lp = lds_wave + t * (4 * KM::RPI * KM::ROW_BYTES);
+        char* lp = lds_wave + t * (KM::ROUND_ROWS * KM::ROW_BYTES);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
                                          (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
     }
@@ -214,16 +220,16 @@ __device__ __forceinline__ bf16x8 read_tr_frag(const char* p0, const char* p1) {
 
 // acc[i-block][j-block] += sum over `ktiles` steps of 64 rows of A(k, i) B(k, j).
 // A points at (row 0, first column of the i tile), B likewise; lda / ldb are row strides in elements.
-template <int WI, int WJ>
+template <class S>
 __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
-                                       int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[WI][WJ]) {
-    using S = Shape<WI, WJ>;
-    using KA = KMajor<S::BI>;
-    using KB = KMajor<S::BJ>;
+                                                int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[S::WI][S::WJ]) {
+    constexpr int WI = S::WI, WJ = S::WJ;
+    using KA = KMajor<S::BI, S::NW>;
+    using KB = KMajor<S::BJ, S::NW>;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_i = wave & 1, wave_j = wave >> 1;
+    const int wave_i = wave % S::NWI, wave_j = wave / S::NWI;
 
     // global side: lane l of a wave instruction covers chunk slot l % CPR of row l / CPR of its band
     auto lane_voff = [&](int cpr, int segs, int rpi, int64_t ld) -> uint32_t {
@@ -236,7 +242,7 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
     const uint32_t voff_b = lane_voff(KB::CPR, KB::SEGS, KB::RPI, ldb);
     const char* ga = (const char*)(A + (int64_t)(wave * KA::RPI) * lda);
     const char* gb = (const char*)(B + (int64_t)(wave * KB::RPI) * ldb);
-    const int64_t round_a = (int64_t)(4 * KA::RPI) * lda * 2, round_b = (int64_t)(4 * KB::RPI) * ldb * 2;
+    const int64_t round_a = (int64_t)KA::ROUND_ROWS * lda * 2, round_b = (int64_t)KB::ROUND_ROWS * ldb * 2;
     const int64_t step_a = 64 * lda * 2, step_b = 64 * ldb * 2;
     const int lds_wave_a = wave * KA::RPI * KA::ROW_BYTES;
     const int lds_wave_b = KA::TILE_BYTES + wave * KB::RPI * KB::ROW_BYTES;
@@ -275,8 +281,8 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
 
     if (ktiles <= 0) return;
 
-    issue_kmajor_load<S::BI>(ga, voff_a, round_a, lds + lds_wave_a);
-    issue_kmajor_load<S::BJ>(gb, voff_b, round_b, lds + lds_wave_b);
+    issue_kmajor_load<S::BI, S::NW>(ga, voff_a, round_a, lds + lds_wave_a);
+    issue_kmajor_load<S::BJ, S::NW>(gb, voff_b, round_b, lds + lds_wave_b);
 
     Frags<WI, WJ> f0, f1;
     for (int kt = 0; kt < ktiles; ++kt) {
@@ -288,8 +294,8 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
         ga += more ? step_a : 0;
         gb += more ? step_b : 0;
         load_frags_t(f0, cur, 0);
-        issue_kmajor_load<S::BI>(ga, voff_a, round_a, nxt + lds_wave_a);
-        issue_kmajor_load<S::BJ>(gb, voff_b, round_b, nxt + lds_wave_b);
+        issue_kmajor_load<S::BI, S::NW>(ga, voff_a, round_a, nxt + lds_wave_a);
+        issue_kmajor_load<S::BJ, S::NW>(gb, voff_b, round_b, nxt + lds_wave_b);
         load_frags_t(f1, cur, 1);
         mma_block<WI, WJ>(f0, acc);
         interleave_hint<2 * (WI + WJ), KA::ROUNDS + KB::ROUNDS, WI * WJ>();
@@ -325,13 +331,14 @@ __device__ __forceinline__ TileId map_tile(int pid, int tilesI, int tilesJ, int 
 }
 inline unsigned grid_for(int tilesI, int tilesJ) { return (unsigned)(((int64_t)tilesI * tilesJ + 7) / 8 * 8); }
 
+template <class S>
 struct Lane {
-    int lane, wave_i, wave_j, hi, lj;
+    int lane, wave, wave_i, wave_j, hi, lj;
     __device__ __forceinline__ Lane() {
         lane = threadIdx.x & 63;
-        const int w = threadIdx.x >> 6;
-        wave_i = w & 1;
-        wave_j = w >> 1;
+        wave = threadIdx.x >> 6;
+        wave_i = wave % S::NWI;
+        wave_j = wave / S::NWI;
         hi = lane >> 5;
         lj = lane & 31;
     }
@@ -344,24 +351,24 @@ __device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d)
 }
 
 // ------------------------------------------------------------------------------------- fwd_lse
-template <int WI, int WJ>
-__global__ __launch_bounds__(NT) void fwd_lse_kernel(FwdArgs a) {
-    using S = Shape<WI, WJ>;
+template <class S>
+__global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
+    constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, 4);
     if (!t.valid) return;
     const int Mr = a.counts[CNT_MR];
     if ((int64_t)t.tj * S::BJ >= Mr) return;
     f32x16 acc[WI][WJ];
-    mainloop<WI, WJ>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk,
+    mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk,
                              a.Hc + (int64_t)t.tj * S::BJ * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds, acc);
     // Epilogue: per token row j (one lane pair) the max and the sum of exponentials over this wave's
     // 128 vocabulary columns.  The logit of the sampled token is gathered by a separate small kernel,
     // so the per-element work is one max, one fma, one exp and one add.
-    const Lane L;
+    const Lane<S> L;
     const int i_base = t.ti * S::BI + L.wave_i * (WI * 32);
     const int n_valid = (int)a.V - i_base;          // columns of this wave that exist (>= 128: all)
-    const int64_t slot = (int64_t)t.ti * 2 + L.wave_i;
+    const int64_t slot = (int64_t)t.ti * S::NWI + L.wave_i;
     const float zs = a.inv_temp * LOG2E;            // inv_temp > 0: max commutes with the scaling
     if (n_valid < WI * 32) {                        // ragged last vocabulary tile: mask the padding
 #pragma unroll
@@ -403,25 +410,25 @@ __global__ __launch_bounds__(NT) void fwd_lse_kernel(FwdArgs a) {
 // the four regions are exactly the two idle LDS stages).  A lane writes its runs of 4 consecutive
 // columns (8 bytes) at 16-byte chunk c ^ (row % 16) of the row, then the wave reads the region
 // back row-wise, 16 lanes x 16 bytes per row, and stores 4 full rows per instruction.
-template <int WI, int WJ>
-__global__ __launch_bounds__(NT) void dz_kernel(DzArgs a) {
-    using S = Shape<WI, WJ>;
-    static_assert(WI == 4 && WJ == 4, "the LDS-staged epilogue is laid out for 128 x 128 per wave");
+template <class S>
+__global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
+    constexpr int WI = S::WI, WJ = S::WJ;
+    static_assert(WI == 4, "the LDS-staged epilogue is laid out for 128 columns (256 bytes) per wave row");
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, 4);
     if (!t.valid) return;
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
     f32x16 acc[WI][WJ];
-    mainloop<WI, WJ>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk,
+    mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk,
                      a.Hc + (int64_t)t.tj * S::BJ * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds, acc);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the spare tile request of the last step
     __syncthreads();                                    // every wave is done with both stages
     // dz = -g p here; the +g of the sampled token's column is added by a separate small kernel, so
     // the per-element work is one fma, one exp, one multiply and half a convert.  Rows past the last
     // token get g = 0; columns past V hold finite values that only ever meet zero weights.
-    const Lane L;
-    char* region = lds + (threadIdx.x >> 6) * 32768;
+    const Lane<S> L;
+    char* region = lds + L.wave * (WJ * 32 * 256);   // WJ * 32 rows of 256 bytes per wave
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
     const int64_t jl_base = (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32);   // row in chunk
     const float zs = a.inv_temp * LOG2E;
@@ -449,7 +456,7 @@ __global__ __launch_bounds__(NT) void dz_kernel(DzArgs a) {
     const int c = L.lane & 15, r4 = L.lane >> 4;
     bf16_t* out = a.dz + (jl_base + r4) * a.ldz + i_base + c * 8;
 #pragma unroll 8
-    for (int tt = 0; tt < 32; ++tt) {
+    for (int tt = 0; tt < WJ * 8; ++tt) {
         const int row = tt * 4 + r4;
         const uint4 v = *(const uint4*)(region + row * 256 + ((c ^ (row & 15)) * 16));
         *(uint4*)(out + (int64_t)tt * 4 * a.ldz) = v;
@@ -457,9 +464,9 @@ __global__ __launch_bounds__(NT) void dz_kernel(DzArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ dh
-template <int WI, int WJ>
-__global__ __launch_bounds__(NT) void dh_kernel(DhArgs a) {
-    using S = Shape<WI, WJ>;
+template <class S>
+__global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
+    constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const int tilesD = (int)(a.dpadR / S::BI);
     const TileId t = map_tile(blockIdx.x, tilesD, a.tilesM, tilesD);
@@ -467,9 +474,9 @@ __global__ __launch_bounds__(NT) void dh_kernel(DhArgs a) {
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
     f32x16 acc[WI][WJ];
-    mainloop<WI, WJ>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv, a.ldv,
+    mainloop<S>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv, a.ldv,
                              a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, (int)(a.Vpad / K_TILE), lds, acc);
-    const Lane L;
+    const Lane<S> L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
 #pragma unroll
     for (int jb = 0; jb < WJ; ++jb) {
@@ -489,9 +496,9 @@ __global__ __launch_bounds__(NT) void dh_kernel(DhArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ dw
-template <int WI, int WJ>
-__global__ __launch_bounds__(NT) void dw_kernel(DwArgs a) {
-    using S = Shape<WI, WJ>;
+template <class S>
+__global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
+    constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const int tilesV = (int)(a.Vpad / S::BI), tilesD = (int)(a.dpadR / S::BJ);
     const TileId t = map_tile(blockIdx.x, tilesV, tilesD, 8);
@@ -501,9 +508,9 @@ __global__ __launch_bounds__(NT) void dw_kernel(DwArgs a) {
     rows = rows < 0 ? 0 : (rows > a.Mc ? a.Mc : rows);
     if (rows == 0 && a.beta) return;   // nothing to add
     f32x16 acc[WI][WJ];
-    mainloop_kmajor<WI, WJ>(a.dz + (int64_t)t.ti * S::BI, a.ldz, a.Hc + (int64_t)t.tj * S::BJ, a.ldH,
+    mainloop_kmajor<S>(a.dz + (int64_t)t.ti * S::BI, a.ldz, a.Hc + (int64_t)t.tj * S::BJ, a.ldH,
                             (int)(rows / K_TILE), lds, acc);
-    const Lane L;
+    const Lane<S> L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
     const bool vec = (a.V % 4) == 0;
 #pragma unroll
@@ -581,12 +588,45 @@ void allow_lds(K kernel, int bytes) {
     (void)hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+int g_waves = 8;   // waves per workgroup: 4 (2 x 2 of 128 x 128) or 8 (2 x 4 of 128 x 64)
+
+using G4 = Geo<2, 2, 4, 4>;        // 256 x 256, 4 waves
+using G4_I128 = Geo<2, 2, 2, 4>;   // 128 x 256
+using G4_J128 = Geo<2, 2, 4, 2>;   // 256 x 128
+using G8 = Geo<2, 4, 4, 2>;        // 256 x 256, 8 waves
+using G8_I128 = Geo<2, 4, 2, 2>;   // 128 x 256
+using G8_J128 = Geo<2, 4, 4, 1>;   // 256 x 128
+using G16 = Geo<2, 8, 4, 1>;       // 256 x 256, 16 waves of 128 x 32
+using G16_I128 = Geo<2, 8, 2, 1>;  // 128 x 256
+using G16_J128 = Geo<4, 4, 2, 1>;  // 256 x 128
+
+template <class S>
+void launch_fwd_lse_t(const FwdArgs& a, hipStream_t st) {
+    allow_lds(fwd_lse_kernel<S>, S::LDS_BYTES);
+    fwd_lse_kernel<S><<<grid_for(a.tilesV, a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
+}
+template <class S>
+void launch_dz_t(const DzArgs& a, hipStream_t st) {
+    allow_lds(dz_kernel<S>, S::LDS_BYTES);
+    dz_kernel<S><<<grid_for(a.tilesV, a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
+}
+template <class S>
+void launch_dh_t(const DhArgs& a, hipStream_t st) {
+    allow_lds(dh_kernel<S>, S::LDS_BYTES);
+    dh_kernel<S><<<grid_for((int)(a.dpadR / S::BI), a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
+}
+template <class S>
+void launch_dw_t(const DwArgs& a, hipStream_t st) {
+    allow_lds(dw_kernel<S>, S::LDS_BYTES);
+    dw_kernel<S><<<grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ)), S::NT, S::LDS_BYTES, st>>>(a);
+}
+
 }  // namespace
 
+void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 16) ? n : 8; }
+
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
-    using S = Shape<4, 4>;
-    allow_lds(fwd_lse_kernel<4, 4>, S::LDS_BYTES);
-    fwd_lse_kernel<4, 4><<<grid_for(a.tilesV, a.tilesM), NT, S::LDS_BYTES, st>>>(a);
+    if (g_waves == 16) launch_fwd_lse_t<G16>(a, st); else if (g_waves == 8) launch_fwd_lse_t<G8>(a, st); else launch_fwd_lse_t<G4>(a, st);
     const int64_t rows_max = (int64_t)a.tilesM * 256;
     token_logit_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(a.Hc, a.Wvd, a.ldk, a.dpad, a.tokc, a.counts,
                                                                      a.inv_temp, a.zy);
@@ -594,9 +634,7 @@ void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
 int fwd_slots_per_tile() { return 2; }
 
 void launch_dz(const DzArgs& a, hipStream_t st) {
-    using S = Shape<4, 4>;
-    allow_lds(dz_kernel<4, 4>, S::LDS_BYTES);
-    dz_kernel<4, 4><<<grid_for(a.tilesV, a.tilesM), NT, S::LDS_BYTES, st>>>(a);
+    if (g_waves == 16) launch_dz_t<G16>(a, st); else if (g_waves == 8) launch_dz_t<G8>(a, st); else launch_dz_t<G4>(a, st);
     const int64_t rows = (int64_t)a.tilesM * 256;
     token_onehot_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, st>>>(a.dz, a.ldz, a.m0, rows, a.tokc, a.seqc, a.g,
                                                                       a.inv_temp, a.counts);
@@ -604,27 +642,17 @@ void launch_dz(const DzArgs& a, hipStream_t st) {
 
 void launch_dh(const DhArgs& a, hipStream_t st) {
     if (a.dpadR % 256 == 0) {
-        using S = Shape<4, 4>;
-        allow_lds(dh_kernel<4, 4>, S::LDS_BYTES);
-        dh_kernel<4, 4><<<grid_for((int)(a.dpadR / S::BI), a.tilesM), NT, S::LDS_BYTES, st>>>(a);
+        if (g_waves == 16) launch_dh_t<G16>(a, st); else if (g_waves == 8) launch_dh_t<G8>(a, st); else launch_dh_t<G4>(a, st);
     } else {   // d padded to a multiple of 128 only
-        using S = Shape<2, 4>;
-        allow_lds(dh_kernel<2, 4>, S::LDS_BYTES);
-        dh_kernel<2, 4><<<grid_for((int)(a.dpadR / S::BI), a.tilesM), NT, S::LDS_BYTES, st>>>(a);
+        if (g_waves == 16) launch_dh_t<G16_I128>(a, st); else if (g_waves == 8) launch_dh_t<G8_I128>(a, st); else launch_dh_t<G4_I128>(a, st);
     }
 }
 
 void launch_dw(const DwArgs& a, hipStream_t st) {
     if (a.dpadR % 256 == 0) {
-        using S = Shape<4, 4>;
-        const unsigned grid = grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ));
-        allow_lds(dw_kernel<4, 4>, S::LDS_BYTES);
-        dw_kernel<4, 4><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        if (g_waves == 16) launch_dw_t<G16>(a, st); else if (g_waves == 8) launch_dw_t<G8>(a, st); else launch_dw_t<G4>(a, st);
     } else {   // d padded to a multiple of 128 only
-        using S = Shape<4, 2>;
-        const unsigned grid = grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ));
-        allow_lds(dw_kernel<4, 2>, S::LDS_BYTES);
-        dw_kernel<4, 2><<<grid, NT, S::LDS_BYTES, st>>>(a);
+        if (g_waves == 16) launch_dw_t<G16_J128>(a, st); else if (g_waves == 8) launch_dw_t<G8_J128>(a, st); else launch_dw_t<G4_J128>(a, st);
     }
 }
 

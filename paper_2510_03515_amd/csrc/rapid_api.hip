@@ -308,6 +308,10 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
 }
 
 int rapid_set_tuning(int key, int value) {
+    if (key == 2 && (value == 4 || value == 8 || value == 16)) {
+        set_waves_per_workgroup(value);
+        return RAPID_OK;
+    }
     if (key == 1 && (value == 0 || value == 1)) {
         g_prof.on = value != 0;
         g_prof.used = 0;
