@@ -103,7 +103,10 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
 /* Process-wide switches (host state, not thread-safe against concurrent calls).
  * key 1: per-stage event timing on (1) / off (0, default); see rapid_profile_read.
  * key 2: waves per workgroup of the contraction kernels, 8 (default: 2 x 4 waves of 128 x 64) or
- *        4 (2 x 2 waves of 128 x 128).  Same 256 x 256 tile and same results either way. */
+ *        4 (2 x 2 waves of 128 x 128) or 16.  Same 256 x 256 tile and same results either way.
+ * keys 10, 11, 12: tile-order blocking (tiles along the first tile dimension that share one tile of
+ *        the second before the order moves on) of the logits kernels, the dHidden kernel (0 = all)
+ *        and the dW kernel; defaults 6, 0, 4 were measured best on MI355X.  Results are identical. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

@@ -355,7 +355,7 @@ template <class S>
 __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
-    const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, 4);
+    const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, a.gi);
     if (!t.valid) return;
     const int Mr = a.counts[CNT_MR];
     if ((int64_t)t.tj * S::BJ >= Mr) return;
@@ -415,7 +415,7 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     static_assert(WI == 4, "the LDS-staged epilogue is laid out for 128 columns (256 bytes) per wave row");
     extern __shared__ __attribute__((aligned(128))) char lds[];
-    const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, 4);
+    const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, a.gi);
     if (!t.valid) return;
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
@@ -469,7 +469,7 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const int tilesD = (int)(a.dpadR / S::BI);
-    const TileId t = map_tile(blockIdx.x, tilesD, a.tilesM, tilesD);
+    const TileId t = map_tile(blockIdx.x, tilesD, a.tilesM, a.gi > 0 ? a.gi : tilesD);
     if (!t.valid) return;
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const int tilesV = (int)(a.Vpad / S::BI), tilesD = (int)(a.dpadR / S::BJ);
-    const TileId t = map_tile(blockIdx.x, tilesV, tilesD, 8);
+    const TileId t = map_tile(blockIdx.x, tilesV, tilesD, a.gi);
     if (!t.valid) return;
     const int Mr = a.counts[CNT_MR];
     int64_t rows = (int64_t)Mr - a.m0;

@@ -22,6 +22,8 @@ void set_error(const char* fmt, ...) {
 namespace {
 
 
+int g_gi_fwd = 6, g_gi_dh = 0, g_gi_dw = 4;   // L2 blocking of the tile order (tuning keys 10..12)
+
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
 enum Stage { ST_COMPACT = 0, ST_PACK, ST_FWD_LSE, ST_MERGE, ST_ESTIMATOR, ST_ZERO, ST_DZ, ST_DZ_T, ST_DH, ST_DW,
              ST_F32, ST_CONVERT, ST_COUNT };
@@ -223,7 +225,7 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         a.tilesV = (int)(p.Vpad / 256); a.tilesM = (int)(p.Mmax_pad / 256);
         a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
         a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
-        a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy);
+        a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy); a.gi = g_gi_fwd;
         {
             Span sp(ST_FWD_LSE, st);
             launch_fwd_lse(a, st);
@@ -308,6 +310,10 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
 }
 
 int rapid_set_tuning(int key, int value) {
+    if (key >= 10 && key <= 12 && value >= 0 && value <= 1024) {
+        (key == 10 ? g_gi_fwd : key == 11 ? g_gi_dh : g_gi_dw) = (key != 11 && value == 0) ? 1 : value;
+        return RAPID_OK;
+    }
     if (key == 2 && (value == 4 || value == 8 || value == 16)) {
         set_waves_per_workgroup(value);
         return RAPID_OK;
@@ -538,7 +544,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             za.Wvd = Wvd; za.Hc = Hc + m0 * p.ldk; za.dpad = p.dpad; za.ldk = p.ldk; za.ldz = p.ldv;
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
             za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
-            za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz;
+            za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz; za.gi = g_gi_fwd;
             {
                 Span sp(ST_DZ, st);
                 launch_dz(za, st);
@@ -546,7 +552,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             DhArgs ha;
             ha.Wdv = Wdv; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
             ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
-            ha.dhidden = (bf16_t*)dhidden_out;
+            ha.dhidden = (bf16_t*)dhidden_out; ha.gi = g_gi_dh;
             {
                 Span sp(ST_DH, st);
                 launch_dh(ha, st);
@@ -554,7 +560,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             DwArgs wa;
             wa.dz = dz; wa.Hc = Hc + m0 * p.ldk; wa.Mc = p.Mc; wa.ldz = p.ldv; wa.ldH = p.ldk;
             wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = m0; wa.counts = counts;
-            wa.dW = dW32; wa.w_layout = o.w_layout; wa.beta = (chunk > 0 || o.accumulate_dw) ? 1 : 0;
+            wa.dW = dW32; wa.w_layout = o.w_layout; wa.beta = (chunk > 0 || o.accumulate_dw) ? 1 : 0; wa.gi = g_gi_dw;
             {
                 Span sp(ST_DW, st);
                 launch_dw(wa, st);

@@ -78,6 +78,7 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     float* part_sum;
     int64_t ld_part;
     float* zy;            // [Mmax_pad]
+    int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
 int fwd_slots_per_tile();
@@ -97,6 +98,7 @@ struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, b
     const float* g;       // [N]
     const int32_t* counts;
     bf16_t* dz;           // [Mc, Vpad]
+    int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_dz(const DzArgs& a, hipStream_t st);
 
@@ -111,6 +113,7 @@ struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const int32_t* row_index;
     const int32_t* counts;
     bf16_t* dhidden;      // [N*T, d]
+    int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_dh(const DhArgs& a, hipStream_t st);
 
@@ -125,6 +128,7 @@ struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
     float* dW;            // fp32, layout per w_layout
     int w_layout;
     int beta;             // 0 overwrite, 1 accumulate
+    int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_dw(const DwArgs& a, hipStream_t st);
 void set_waves_per_workgroup(int n);   // 4 or 8 waves per contraction workgroup
