@@ -70,6 +70,7 @@ def main():
     ap.add_argument("--workspace-gib", type=float, default=0.0, help="0 = the library's recommended size")
     ap.add_argument("--waves", type=int, default=0, help="4 or 8 waves per contraction workgroup (0 = library default)")
     ap.add_argument("--gi", type=str, default="", help="tile-order blocking fwd,dh,dw (tuning experiment)")
+    ap.add_argument("--tune", type=str, default="", help="library tuning keys, key=value[,key=value...] (experiments)")
     ap.add_argument("--chunk-rows", type=int, default=0, help="size the workspace for backward chunks of this many rows")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -92,6 +93,10 @@ def main():
     if args.gi:
         for key, val in zip((10, 11, 12), args.gi.split(",")):
             rb.rapid_set_tuning(key, int(val))
+    if args.tune:
+        for kv in args.tune.split(","):
+            key, val = kv.split("=")
+            rb.rapid_set_tuning(int(key), int(val))
     fwd_only = spec.fwd_only
     if fwd_only:
         ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, rb.DTYPE_BF16)

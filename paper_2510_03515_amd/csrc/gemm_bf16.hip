@@ -27,6 +27,8 @@
 // i = 8 (v / 4) + 4 (l / 32) + v % 4: a lane owns runs of 4 consecutive i for one j, so every
 // epilogue keeps j = the token row (per-lane scalars: lse, coefficient, token id, output row) and
 // stores 4 consecutive i with one 8- or 16-byte access.
+#include <utility>
+
 #include "rapid_internal.h"
 
 namespace rapid {
@@ -36,6 +38,8 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 constexpr float LOG2E = 1.4426950408889634f;
 
@@ -52,7 +56,14 @@ struct Geo {
     static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
 };
 
-__device__ __forceinline__ void lds_barrier() { __syncthreads(); }
+
+// Barrier without the memory fence of __syncthreads; the loops place their own waits before it.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 
 // Requests one K step (64 columns) of a tile with ROWS rows: direct memory -> LDS loads, 16 bytes
 // per lane.  `gwave` is the wave-uniform address of the wave's first row of round 0 (scalar
@@ -73,12 +84,46 @@ struct Frags {
     bf16x8 a[WI], b[WJ];
 };
 
+// LDS fragment reads and their waits are issued by hand.  With direct memory -> LDS loads in the
+// loop the compiler's wait insertion falls back to lgkmcnt(0) before every MFMA block, which also
+// waits for the reads just issued for the NEXT sub-step and so undoes the software pipelining.
+// LDS reads of a wave complete in order, so "at most n reads outstanding" after issuing the next
+// sub-step's n reads means exactly "the current sub-step's fragments have arrived".
+__device__ __forceinline__ uint32_t lds_addr(const char* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+template <int OFF>
+__device__ __forceinline__ bf16x8 ds_read128(uint32_t addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
+template <int OFF>
+__device__ __forceinline__ s16x4 ds_read_tr64(uint32_t addr) {
+    s16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
+// waits until at most N LDS reads are outstanding, and makes the fragments depend on the wait
+template <int N, int WI, int WJ>
+__device__ __forceinline__ void wait_frags(Frags<WI, WJ>& f) {
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N < 15 ? N : 15) : "memory");
+#pragma unroll
+    for (int ib = 0; ib < WI; ++ib) asm volatile("" : "+v"(f.a[ib]));
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) asm volatile("" : "+v"(f.b[jb]));
+}
+
+template <int WI, int WJ, int... IB, int... JB>
+__device__ __forceinline__ void load_frags_seq(Frags<WI, WJ>& f, uint32_t a_addr, uint32_t b_addr,
+                                               std::integer_sequence<int, IB...>, std::integer_sequence<int, JB...>) {
+    ((f.a[IB] = ds_read128<IB * (32 * 128)>(a_addr)), ...);
+    ((f.b[JB] = ds_read128<JB * (32 * 128)>(b_addr)), ...);
+}
+// a_addr / b_addr: LDS byte addresses of this lane's chunk in block 0 of each operand
 template <int WI, int WJ>
-__device__ __forceinline__ void load_frags(Frags<WI, WJ>& f, const char* cur, int a_off, int b_off, int xo) {
-#pragma unroll
-    for (int ib = 0; ib < WI; ++ib) f.a[ib] = *(const bf16x8*)(cur + a_off + ib * (32 * 128) + xo);
-#pragma unroll
-    for (int jb = 0; jb < WJ; ++jb) f.b[jb] = *(const bf16x8*)(cur + b_off + jb * (32 * 128) + xo);
+__device__ __forceinline__ void load_frags(Frags<WI, WJ>& f, uint32_t a_addr, uint32_t b_addr) {
+    load_frags_seq<WI, WJ>(f, a_addr, b_addr, std::make_integer_sequence<int, WI>{}, std::make_integer_sequence<int, WJ>{});
 }
 
 template <int WI, int WJ>
@@ -90,21 +135,49 @@ __device__ __forceinline__ void mma_block(const Frags<WI, WJ>& f, f32x16 (&acc)[
             acc[ib][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ib], f.b[jb], acc[ib][jb], 0, 0, 0);
 }
 
-// Scheduling hints: keep the matrix pipe fed by spreading the LDS fragment reads (and, in the
-// first sub-step, the tile loads of the next stage) between the MFMAs instead of in front of them.
-template <int N_DS, int N_VMEM, int N_MFMA>
-__device__ __forceinline__ void interleave_hint() {
-    constexpr int groups = N_DS < N_MFMA ? (N_DS > 0 ? N_DS : 1) : N_MFMA;
-    constexpr int mfma_per = N_MFMA / groups;
-    constexpr int ds_per = (N_DS + groups - 1) / groups;
-    constexpr int vmem_per = (N_VMEM + groups - 1) / groups;
+// One MFMA block of a K step that also carries half of the step's tile-load requests (HALF = 0 / 1),
+// one request after every few MFMAs.  A memory instruction holds its wave at issue until the memory
+// pipeline accepts it, and that pipeline takes most of a step to accept a whole stage; requests
+// bunched at the top of the step kept every wave out of its MFMAs for hundreds of cycles, spread out
+// they are accepted at once and the SIMD's other wave fills the gaps.
+// A wave makes T requests per step, numbered in the order `request(r)` is to be called; the block with
+// HALF = 0 carries the first half of them, request_first_half makes the same ones without MFMAs.
+template <class S, int HALF, int T, class F>
+__device__ __forceinline__ void mma_block_requesting(const Frags<S::WI, S::WJ>& f, f32x16 (&acc)[S::WI][S::WJ],
+                                                     F&& request) {
+    constexpr int NB = S::WI * S::WJ;
 #pragma unroll
-    for (int g = 0; g < groups; ++g) {
-        if (ds_per > 0) __builtin_amdgcn_sched_group_barrier(0x100, ds_per, 0);       // LDS reads
-        if (vmem_per > 0) __builtin_amdgcn_sched_group_barrier(0x010, vmem_per, 0);   // tile loads
-        __builtin_amdgcn_sched_group_barrier(0x008, mfma_per, 0);                     // MFMAs
-    }
+    for (int ib = 0; ib < S::WI; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < S::WJ; ++jb) {
+            acc[ib][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[ib], f.b[jb], acc[ib][jb], 0, 0, 0);
+            const int slot = HALF * NB + ib * S::WJ + jb;
+#pragma unroll
+            for (int r = 0; r < T; ++r)
+                if (r * 2 * NB / T == slot) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    request(r);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        }
 }
+template <class S, int T, class F>
+__device__ __forceinline__ void request_first_half(F&& request) {
+    constexpr int NB = S::WI * S::WJ;
+#pragma unroll
+    for (int r = 0; r < T; ++r)
+        if (r * 2 * NB / T < NB) request(r);
+}
+__device__ __forceinline__ void load_to_lds_16(const char* gp, char* lp) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gp,
+                                     (__attribute__((address_space(3))) void*)lp, 16, 0, 0);
+}
+
+// Scheduling fence: nothing is moved across it.  The K step is written in the order that software-
+// pipelines it (fragments of the next sub-step are requested before the MFMAs of the current one)
+// and the fences keep that order, so the compiler's waits before each MFMA block only cover the
+// fragments that block needs (partial lgkmcnt) while the next sub-step's reads are in flight.
+__device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
 
 // acc += A_tile . B_tile^T over `ktiles` steps of 64.  A / B point at the tile's first row, k = 0.
 template <class S>
@@ -117,13 +190,13 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     const int wave_i = wave % S::NWI, wave_j = wave / S::NWI;
 
     // global side of the tile loads: lane l of a wave covers row l/8 of the wave's 8-row band and
-    // the chunk that belongs at slot l%8 of that row
+    // the chunk that belongs at slot l%8 of that row; a wave's bands are 8 * (waves that share the
+    // tile) rows apart.
     const int gchunk = (lane & 7) ^ ((((wave & 1) << 2) + (lane >> 4)) & 7);
     const uint32_t voff_a = (uint32_t)(((int64_t)(lane >> 3) * lda + gchunk * 8) * 2);
     const uint32_t voff_b = (uint32_t)(((int64_t)(lane >> 3) * ldb + gchunk * 8) * 2);
     const char* ga = (const char*)(A + (int64_t)(wave * 8) * lda);
     const char* gb = (const char*)(B + (int64_t)(wave * 8) * ldb);
-    const int64_t round_a = (8 * S::NW) * lda * 2, round_b = (8 * S::NW) * ldb * 2;
     const int lds_wave_off = wave * 8 * 128;
 
     // LDS side of the fragment reads
@@ -143,34 +216,79 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 
     if (ktiles <= 0) return;
 
-    issue_tile_load<S::BI, S::NW>(ga, voff_a, round_a, lds + lds_wave_off);
-    issue_tile_load<S::BJ, S::NW>(gb, voff_b, round_b, lds + S::BI * 128 + lds_wave_off);
+    issue_tile_load<S::BI, S::NW>(ga, voff_a, (int64_t)(8 * S::NW) * lda * 2, lds + lds_wave_off);
+    issue_tile_load<S::BJ, S::NW>(gb, voff_b, (int64_t)(8 * S::NW) * ldb * 2, lds + S::BI * 128 + lds_wave_off);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
 
+    // One K step on stage `cur` = kt % 2 (its first fragments f0 were read at the end of the step before,
+    // and the first half of tile kt+1 was requested there too):
+    //   read f1 (sub-step 1) | MFMA f0 + second half of the requests for tile kt+1
+    //   read f0 (sub-step 2) | MFMA f1
+    //   read f1 (sub-step 3) | MFMA f0
+    //   wait: own requests landed, own reads of `cur` done; barrier
+    //   read f0 of tile kt+1 | MFMA f1 + first half of the requests for tile kt+2 (into `cur`)
+    // After the barrier tile kt+1 is complete and nobody reads `cur` any more.  Steps past the last
+    // tile re-request the last tile into the idle stage, which keeps the loop free of branches and
+    // every address in bounds.
     Frags<WI, WJ> f0, f1;
+    constexpr int NR = WI + WJ;   // LDS reads per sub-step
+    constexpr int RA = S::BI / (8 * S::NW), RB = S::BJ / (8 * S::NW), SR = 8 * S::NW;
+    char* dst = lds + S::STAGE_BYTES;   // stage the requests go to
+    auto request = [&](int r) {
+        if (r < RA)
+            load_to_lds_16(ga + (int64_t)(r * SR) * lda * 2 + voff_a, dst + lds_wave_off + r * (SR * 128));
+        else
+            load_to_lds_16(gb + (int64_t)((r - RA) * SR) * ldb * 2 + voff_b,
+                           dst + S::BI * 128 + lds_wave_off + (r - RA) * (SR * 128));
+    };
+    {
+        const uint32_t la = lds_addr(lds) + a_off, lb = lds_addr(lds) + b_off;
+        load_frags<WI, WJ>(f0, la + xo[0], lb + xo[0]);
+        const int adv = ktiles > 1 ? 128 : 0;
+        ga += adv;
+        gb += adv;
+        request_first_half<S, RA + RB>(request);   // of tile 1
+        // A register that an LDS read (issued from inline assembly) is still writing must not meet
+        // a compiler-made copy, and copies appear where control flow splits or joins: every read is
+        // therefore waited for in the block that issued it.
+        wait_frags<0>(f0);
+    }
     for (int kt = 0; kt < ktiles; ++kt) {
         char* cur = lds + (kt & 1) * S::STAGE_BYTES;
         char* nxt = lds + ((kt + 1) & 1) * S::STAGE_BYTES;
+        const uint32_t la = lds_addr(cur) + a_off, lb = lds_addr(cur) + b_off;
+        const uint32_t na = lds_addr(nxt) + a_off, nb = lds_addr(nxt) + b_off;
+        fence();
+        load_frags<WI, WJ>(f1, la + xo[1], lb + xo[1]);
+        fence();
+        dst = nxt;
+        mma_block_requesting<S, 1, RA + RB>(f0, acc, request);
+        fence();
+        load_frags<WI, WJ>(f0, la + xo[2], lb + xo[2]);
+        wait_frags<NR>(f1);
+        fence();
+        mma_block<WI, WJ>(f1, acc);
+        fence();
+        load_frags<WI, WJ>(f1, la + xo[3], lb + xo[3]);
+        wait_frags<NR>(f0);
+        fence();
+        mma_block<WI, WJ>(f0, acc);
+        fence();
+        wait_frags<0>(f1);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        lds_barrier();   // stage `cur` is complete; nobody still reads stage `nxt`
-        // the last step re-loads its own tile into the idle stage, which keeps the loop body free
-        // of branches (one scheduling region) and every address in bounds
-        const int adv = (kt + 1 < ktiles) ? 128 : 0;
+        lds_barrier();
+        load_frags<WI, WJ>(f0, na + xo[0], nb + xo[0]);
+        fence();
+        const int adv = (kt + 2 < ktiles) ? 128 : 0;
         ga += adv;
         gb += adv;
-        load_frags<WI, WJ>(f0, cur, a_off, b_off, xo[0]);
-        issue_tile_load<S::BI, S::NW>(ga, voff_a, round_a, nxt + lds_wave_off);
-        issue_tile_load<S::BJ, S::NW>(gb, voff_b, round_b, nxt + S::BI * 128 + lds_wave_off);
-        load_frags<WI, WJ>(f1, cur, a_off, b_off, xo[1]);
-        mma_block<WI, WJ>(f0, acc);
-        interleave_hint<WI + WJ, (S::BI + S::BJ) / (8 * S::NW), WI * WJ>();
-        load_frags<WI, WJ>(f0, cur, a_off, b_off, xo[2]);
-        mma_block<WI, WJ>(f1, acc);
-        interleave_hint<WI + WJ, 0, WI * WJ>();
-        load_frags<WI, WJ>(f1, cur, a_off, b_off, xo[3]);
-        mma_block<WI, WJ>(f0, acc);
-        interleave_hint<WI + WJ, 0, WI * WJ>();
-        mma_block<WI, WJ>(f1, acc);
+        dst = cur;
+        mma_block_requesting<S, 0, RA + RB>(f1, acc, request);
+        fence();
+        wait_frags<0>(f0);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests for steps that do not exist
 }
 
 // ---- contraction index major operands ("k-major") ---------------------------------------------
@@ -208,14 +326,23 @@ __device__ __forceinline__ void issue_kmajor_load(const char* __restrict__ gwave
     }
 }
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ bf16x8 read_tr_frag(const char* p0, const char* p1) {
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
-    typedef short s16x8 __attribute__((ext_vector_type(8)));
+template <int OFF>
+__device__ __forceinline__ bf16x8 read_tr_frag(uint32_t a0, uint32_t a1) {
+    const s16x4 lo = ds_read_tr64<OFF>(a0);
+    const s16x4 hi = ds_read_tr64<OFF>(a1);
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
+}
+
+// xa / xb: this lane's LDS byte offsets (two half-fragments per block) within a stage, sub-step 0
+template <int KS, class S>
+__device__ __forceinline__ void load_frags_kmajor(Frags<S::WI, S::WJ>& f, uint32_t cur, const int (&xa)[S::WI][2],
+                                                  const int (&xb)[S::WJ][2]) {
+    constexpr int OA = KS * 16 * KMajor<S::BI, S::NW>::ROW_BYTES, OB = KS * 16 * KMajor<S::BJ, S::NW>::ROW_BYTES;
+#pragma unroll
+    for (int ib = 0; ib < S::WI; ++ib) f.a[ib] = read_tr_frag<OA>(cur + xa[ib][0], cur + xa[ib][1]);
+#pragma unroll
+    for (int jb = 0; jb < S::WJ; ++jb) f.b[jb] = read_tr_frag<OB>(cur + xb[jb][0], cur + xb[jb][1]);
 }
 
 // acc[i-block][j-block] += sum over `ktiles` steps of 64 rows of A(k, i) B(k, j).
@@ -230,6 +357,7 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_i = wave % S::NWI, wave_j = wave / S::NWI;
+
 
     // global side: lane l of a wave instruction covers chunk slot l % CPR of row l / CPR of its band
     auto lane_voff = [&](int cpr, int segs, int rpi, int64_t ld) -> uint32_t {
@@ -261,16 +389,15 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
                     ((((wave_j * WJ) ^ (sw & (KB::SEGS - 1))) * 64)) + sub_bytes;
     }
 
-    auto load_frags_t = [&](Frags<WI, WJ>& f, const char* cur, int ks) {
+    int xa[WI][2], xb[WJ][2];
 #pragma unroll
-        for (int ib = 0; ib < WI; ++ib)
-            f.a[ib] = read_tr_frag(cur + ks * 16 * KA::ROW_BYTES + (base_a[0] ^ (ib * 64)),
-                                   cur + ks * 16 * KA::ROW_BYTES + (base_a[1] ^ (ib * 64)));
+    for (int r = 0; r < 2; ++r) {
 #pragma unroll
-        for (int jb = 0; jb < WJ; ++jb)
-            f.b[jb] = read_tr_frag(cur + ks * 16 * KB::ROW_BYTES + (base_b[0] ^ (jb * 64)),
-                                   cur + ks * 16 * KB::ROW_BYTES + (base_b[1] ^ (jb * 64)));
-    };
+        for (int ib = 0; ib < WI; ++ib) xa[ib][r] = base_a[r] ^ (ib * 64);
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb) xb[jb][r] = base_b[r] ^ (jb * 64);
+    }
+    constexpr int NR = 2 * (WI + WJ);   // LDS reads per sub-step
 
 #pragma unroll
     for (int ib = 0; ib < WI; ++ib)
@@ -283,30 +410,62 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
 
     issue_kmajor_load<S::BI, S::NW>(ga, voff_a, round_a, lds + lds_wave_a);
     issue_kmajor_load<S::BJ, S::NW>(gb, voff_b, round_b, lds + lds_wave_b);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
 
+    // same step structure as mainloop
     Frags<WI, WJ> f0, f1;
+    char* dst = lds + S::STAGE_BYTES;
+    auto request = [&](int r) {
+        if (r < KA::ROUNDS)
+            load_to_lds_16(ga + r * round_a + voff_a, dst + lds_wave_a + r * (KA::ROUND_ROWS * KA::ROW_BYTES));
+        else
+            load_to_lds_16(gb + (r - KA::ROUNDS) * round_b + voff_b,
+                           dst + lds_wave_b + (r - KA::ROUNDS) * (KB::ROUND_ROWS * KB::ROW_BYTES));
+    };
+    constexpr int T = KA::ROUNDS + KB::ROUNDS;
+    {
+        load_frags_kmajor<0, S>(f0, lds_addr(lds), xa, xb);
+        const bool more = ktiles > 1;
+        ga += more ? step_a : 0;
+        gb += more ? step_b : 0;
+        request_first_half<S, T>(request);   // of tile 1
+        wait_frags<0>(f0);
+    }
     for (int kt = 0; kt < ktiles; ++kt) {
         char* cur = lds + (kt & 1) * S::STAGE_BYTES;
         char* nxt = lds + ((kt + 1) & 1) * S::STAGE_BYTES;
+        const uint32_t lc = lds_addr(cur), ln = lds_addr(nxt);
+        fence();
+        load_frags_kmajor<1, S>(f1, lc, xa, xb);
+        fence();
+        dst = nxt;
+        mma_block_requesting<S, 1, T>(f0, acc, request);
+        fence();
+        load_frags_kmajor<2, S>(f0, lc, xa, xb);
+        wait_frags<NR>(f1);
+        fence();
+        mma_block<WI, WJ>(f1, acc);
+        fence();
+        load_frags_kmajor<3, S>(f1, lc, xa, xb);
+        wait_frags<NR>(f0);
+        fence();
+        mma_block<WI, WJ>(f0, acc);
+        fence();
+        wait_frags<0>(f1);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         lds_barrier();
-        const bool more = kt + 1 < ktiles;   // the last step re-loads its own rows into the idle stage
+        load_frags_kmajor<0, S>(f0, ln, xa, xb);
+        fence();
+        const bool more = kt + 2 < ktiles;
         ga += more ? step_a : 0;
         gb += more ? step_b : 0;
-        load_frags_t(f0, cur, 0);
-        issue_kmajor_load<S::BI, S::NW>(ga, voff_a, round_a, nxt + lds_wave_a);
-        issue_kmajor_load<S::BJ, S::NW>(gb, voff_b, round_b, nxt + lds_wave_b);
-        load_frags_t(f1, cur, 1);
-        mma_block<WI, WJ>(f0, acc);
-        interleave_hint<2 * (WI + WJ), KA::ROUNDS + KB::ROUNDS, WI * WJ>();
-        load_frags_t(f0, cur, 2);
-        mma_block<WI, WJ>(f1, acc);
-        interleave_hint<2 * (WI + WJ), 0, WI * WJ>();
-        load_frags_t(f1, cur, 3);
-        mma_block<WI, WJ>(f0, acc);
-        interleave_hint<2 * (WI + WJ), 0, WI * WJ>();
-        mma_block<WI, WJ>(f1, acc);
+        dst = cur;
+        mma_block_requesting<S, 0, T>(f1, acc, request);
+        fence();
+        wait_frags<0>(f0);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests for steps that do not exist
 }
 
 // Workgroup id -> tile.  Hardware deals consecutive workgroup ids round-robin to the 8 XCDs (each
@@ -329,6 +488,7 @@ __device__ __forceinline__ TileId map_tile(int pid, int tilesI, int tilesJ, int 
     t.tj = rem / gi;
     return t;
 }
+
 inline unsigned grid_for(int tilesI, int tilesJ) { return (unsigned)(((int64_t)tilesI * tilesJ + 7) / 8 * 8); }
 
 template <class S>
@@ -624,6 +784,7 @@ void launch_dw_t(const DwArgs& a, hipStream_t st) {
 }  // namespace
 
 void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 16) ? n : 8; }
+
 
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
     if (g_waves == 16) launch_fwd_lse_t<G16>(a, st); else if (g_waves == 8) launch_fwd_lse_t<G8>(a, st); else launch_fwd_lse_t<G4>(a, st);

@@ -131,7 +131,8 @@ struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_dw(const DwArgs& a, hipStream_t st);
-void set_waves_per_workgroup(int n);   // 4 or 8 waves per contraction workgroup
+void set_waves_per_workgroup(int n);   // 4, 8 or 16 waves per contraction workgroup
+
 
 // ---- f32_path.hip -----------------------------------------------------------------------------
 // C[i][j] (+)= alpha sum_k A(i,k) B(k,j), arbitrary strides, optional index maps, and a device-side
