@@ -147,13 +147,10 @@ def main():
     launches = stages[dom]["launches_per_step"]
     # chunks past the last valid row exit at once: count only launches that had rows
     Mmax_pad = (N * T + 255) // 256 * 256
-    if dom != "fwd_lse":
-        chunk_rows = Mmax_pad / launches
-        live = max(1, -(-M // int(chunk_rows)))
-        tokens_per_launch = M / live
-        avg_ms = stages[dom]["ms_per_step"] / live
-    else:
-        live, tokens_per_launch, avg_ms = 1, M, stages[dom]["avg_ms"]
+    chunk_rows = Mmax_pad / launches
+    live = max(1, -(-M // int(chunk_rows)))
+    tokens_per_launch = M / live
+    avg_ms = stages[dom]["ms_per_step"] / live
     achieved = 2.0 * d * V * tokens_per_launch / (avg_ms * 1e-3) / 1e12
     # HBM-side bytes per full launch from rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by a copy
     # kernel of known size); measured on the headline workload only, see profiles/

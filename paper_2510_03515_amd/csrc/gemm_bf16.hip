@@ -216,6 +216,9 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 
     if (ktiles <= 0) return;
 
+    // A workgroup runs tile after tile: everybody must be done with the LDS stages of the tile before
+    // (its last reads, its trailing requests, a staged epilogue) before they are filled again.
+    lds_barrier();
     issue_tile_load<S::BI, S::NW>(ga, voff_a, (int64_t)(8 * S::NW) * lda * 2, lds + lds_wave_off);
     issue_tile_load<S::BJ, S::NW>(gb, voff_b, (int64_t)(8 * S::NW) * ldb * 2, lds + S::BI * 128 + lds_wave_off);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -408,6 +411,7 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
 
     if (ktiles <= 0) return;
 
+    lds_barrier();   // see mainloop
     issue_kmajor_load<S::BI, S::NW>(ga, voff_a, round_a, lds + lds_wave_a);
     issue_kmajor_load<S::BJ, S::NW>(gb, voff_b, round_b, lds + lds_wave_b);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -489,7 +493,16 @@ __device__ __forceinline__ TileId map_tile(int pid, int tilesI, int tilesJ, int 
     return t;
 }
 
-inline unsigned grid_for(int tilesI, int tilesJ) { return (unsigned)(((int64_t)tilesI * tilesJ + 7) / 8 * 8); }
+__host__ __device__ inline int ids_for(int tilesI, int tilesJ) { return (int)(((int64_t)tilesI * tilesJ + 7) / 8 * 8); }
+// The kernels are persistent: one workgroup per CU (LDS admits no more) walks the ids
+// blockIdx.x, blockIdx.x + gridDim.x, ...; gridDim.x is a multiple of 8, so a workgroup stays on its
+// XCD's share of the order and the workgroups of an XCD stay on neighbouring tiles.  This saves the
+// launch gap between workgroups and the dispatch of the ids whose tiles hold no token rows.
+int g_num_cu = 256;
+inline unsigned grid_for(int tilesI, int tilesJ) {
+    const int ids = ids_for(tilesI, tilesJ), cus = g_num_cu / 8 * 8;
+    return (unsigned)(ids < cus ? ids : cus);
+}
 
 template <class S>
 struct Lane {
@@ -515,13 +528,17 @@ template <class S>
 __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
-    const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, a.gi);
-    if (!t.valid) return;
     const int Mr = a.counts[CNT_MR];
-    if ((int64_t)t.tj * S::BJ >= Mr) return;
+    if (a.row0 >= Mr) return;
+    // the order (and with it the split over the XCDs) covers the row tiles that hold tokens only
+    const int tilesM = min(a.tilesM, (int)((Mr - a.row0 + S::BJ - 1) / S::BJ));
+    for (int pid = blockIdx.x, ids = ids_for(a.tilesV, tilesM); pid < ids; pid += gridDim.x) {
+    const TileId t = map_tile(pid, a.tilesV, tilesM, a.gi);
+    const int64_t j_tile = a.row0 + (int64_t)t.tj * S::BJ;   // first token row of the tile
+    if (!t.valid) continue;
     f32x16 acc[WI][WJ];
-    mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk,
-                             a.Hc + (int64_t)t.tj * S::BJ * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds, acc);
+    mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk, a.Hc + j_tile * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds,
+                acc);
     // Epilogue: per token row j (one lane pair) the max and the sum of exponentials over this wave's
     // 128 vocabulary columns.  The logit of the sampled token is gathered by a separate small kernel,
     // so the per-element work is one max, one fma, one exp and one add.
@@ -543,7 +560,7 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     }
 #pragma unroll
     for (int jb = 0; jb < WJ; ++jb) {
-        const int64_t j = (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
+        const int64_t j = j_tile + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
         float m = -INFINITY;
 #pragma unroll
         for (int ib = 0; ib < WI; ++ib)
@@ -562,6 +579,7 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
             a.part_sum[slot * a.ld_part + j] = l;
         }
     }
+    }
 }
 
 // ------------------------------------------------------------------------------------------ dz
@@ -575,10 +593,12 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     static_assert(WI == 4, "the LDS-staged epilogue is laid out for 128 columns (256 bytes) per wave row");
     extern __shared__ __attribute__((aligned(128))) char lds[];
-    const TileId t = map_tile(blockIdx.x, a.tilesV, a.tilesM, a.gi);
-    if (!t.valid) return;
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
-    if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
+    if (a.m0 >= Mr) return;
+    const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));   // row tiles that hold tokens
+    for (int pid = blockIdx.x, ids = ids_for(a.tilesV, tilesM); pid < ids; pid += gridDim.x) {
+    const TileId t = map_tile(pid, a.tilesV, tilesM, a.gi);
+    if (!t.valid) continue;
     f32x16 acc[WI][WJ];
     mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk,
                      a.Hc + (int64_t)t.tj * S::BJ * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds, acc);
@@ -621,6 +641,7 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
         const uint4 v = *(const uint4*)(region + row * 256 + ((c ^ (row & 15)) * 16));
         *(uint4*)(out + (int64_t)tt * 4 * a.ldz) = v;
     }
+    }
 }
 
 // ------------------------------------------------------------------------------------------ dh
@@ -629,10 +650,14 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const int tilesD = (int)(a.dpadR / S::BI);
-    const TileId t = map_tile(blockIdx.x, tilesD, a.tilesM, a.gi > 0 ? a.gi : tilesD);
-    if (!t.valid) return;
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
-    if (a.m0 + (int64_t)t.tj * S::BJ >= Mr) return;
+    if (a.m0 >= Mr) return;
+    // the order (and with it the split over the XCDs) covers the row tiles that hold tokens only: a
+    // short last chunk would otherwise leave whole XCDs with nothing but empty tiles
+    const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));
+    for (int pid = blockIdx.x, ids = ids_for(tilesD, tilesM); pid < ids; pid += gridDim.x) {
+    const TileId t = map_tile(pid, tilesD, tilesM, a.gi > 0 ? a.gi : tilesD);
+    if (!t.valid) continue;
     f32x16 acc[WI][WJ];
     mainloop<S>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv, a.ldv,
                              a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, (int)(a.Vpad / K_TILE), lds, acc);
@@ -653,6 +678,7 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
                                                       acc[ib][jb][q * 4 + 2], acc[ib][jb][q * 4 + 3]);
             }
     }
+    }
 }
 
 // ------------------------------------------------------------------------------------------ dw
@@ -661,12 +687,13 @@ __global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const int tilesV = (int)(a.Vpad / S::BI), tilesD = (int)(a.dpadR / S::BJ);
-    const TileId t = map_tile(blockIdx.x, tilesV, tilesD, a.gi);
-    if (!t.valid) return;
     const int Mr = a.counts[CNT_MR];
     int64_t rows = (int64_t)Mr - a.m0;
     rows = rows < 0 ? 0 : (rows > a.Mc ? a.Mc : rows);
     if (rows == 0 && a.beta) return;   // nothing to add
+    for (int pid = blockIdx.x, ids = ids_for(tilesV, tilesD); pid < ids; pid += gridDim.x) {
+    const TileId t = map_tile(pid, tilesV, tilesD, a.gi);
+    if (!t.valid) continue;
     f32x16 acc[WI][WJ];
     mainloop_kmajor<S>(a.dz + (int64_t)t.ti * S::BI, a.ldz, a.Hc + (int64_t)t.tj * S::BJ, a.ldH,
                             (int)(rows / K_TILE), lds, acc);
@@ -705,6 +732,7 @@ __global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
                         }
                 }
             }
+    }
     }
 }
 
@@ -784,11 +812,13 @@ void launch_dw_t(const DwArgs& a, hipStream_t st) {
 }  // namespace
 
 void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 16) ? n : 8; }
+void set_cu_count(int n) { g_num_cu = n >= 8 ? n : 8; }
 
 
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
     if (g_waves == 16) launch_fwd_lse_t<G16>(a, st); else if (g_waves == 8) launch_fwd_lse_t<G8>(a, st); else launch_fwd_lse_t<G4>(a, st);
-    const int64_t rows_max = (int64_t)a.tilesM * 256;
+}
+void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st) {
     token_logit_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(a.Hc, a.Wvd, a.ldk, a.dpad, a.tokc, a.counts,
                                                                      a.inv_temp, a.zy);
 }

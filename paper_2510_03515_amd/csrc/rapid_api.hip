@@ -23,6 +23,7 @@ namespace {
 
 
 int g_gi_fwd = 6, g_gi_dh = 0, g_gi_dw = 4;   // L2 blocking of the tile order (tuning keys 10..12)
+int g_fwd_block_tiles = 256;                  // row tiles per forward launch (tuning key 13)
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
 enum Stage { ST_COMPACT = 0, ST_PACK, ST_FWD_LSE, ST_MERGE, ST_ESTIMATOR, ST_ZERO, ST_DZ, ST_DZ_T, ST_DH, ST_DW,
@@ -168,6 +169,7 @@ int check_arch() {
     }
     cached_dev = dev;
     cached_rc = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? RAPID_OK : RAPID_ERR_ARCH;
+    if (cached_rc == RAPID_OK) set_cu_count(prop.multiProcessorCount);
     if (cached_rc != RAPID_OK) set_error("device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
     return cached_rc;
 }
@@ -226,12 +228,20 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
         a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
         a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy); a.gi = g_gi_fwd;
-        {
+        // The forward runs in blocks of token rows, all vocabulary tiles per block, so that a block's
+        // hidden rows stay in the memory-side cache while every XCD sweeps its share of W over them
+        // (one launch over all rows re-reads the hidden rows from HBM once per group of W panels).
+        const int64_t block_rows = (int64_t)g_fwd_block_tiles * 256;
+        for (int64_t r0 = 0; r0 < p.Mmax_pad; r0 += block_rows) {
+            const int64_t rows = (p.Mmax_pad - r0) < block_rows ? (p.Mmax_pad - r0) : block_rows;
+            a.row0 = r0;
+            a.tilesM = (int)(rows / 256);
             Span sp(ST_FWD_LSE, st);
             launch_fwd_lse(a, st);
         }
         {
             Span sp(ST_MERGE, st);
+            launch_token_logit(a, p.Mmax_pad, st);
             launch_merge_lse(a.part_max, a.part_sum, p.P, a.ld_part, a.zy, row_index, counts, p.Mmax_pad, lse_c,
                              io.logp_out, io.lse_out, st);
         }
@@ -312,6 +322,10 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
 int rapid_set_tuning(int key, int value) {
     if (key >= 10 && key <= 12 && value >= 0 && value <= 1024) {
         (key == 10 ? g_gi_fwd : key == 11 ? g_gi_dh : g_gi_dw) = (key != 11 && value == 0) ? 1 : value;
+        return RAPID_OK;
+    }
+    if (key == 13 && value >= 1 && value <= (1 << 20)) {
+        g_fwd_block_tiles = value;
         return RAPID_OK;
     }
     if (key == 2 && (value == 4 || value == 8 || value == 16)) {

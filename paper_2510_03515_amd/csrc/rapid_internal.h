@@ -69,7 +69,8 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     const bf16_t* Hc;     // [Mmax_pad, dpad]
     int64_t dpad;         // contraction extent (multiple of 64)
     int64_t ldk;          // leading dimension of Wvd and Hc (elements)
-    int tilesV, tilesM;   // 256-tiles (tilesM: upper bound; the kernel uses the rows that hold tokens)
+    int tilesV, tilesM;   // 256-tiles (tilesM: row tiles of this launch, from row0 on; rows past the last token are skipped)
+    int64_t row0;         // first compact token row of this launch
     int64_t V;
     float inv_temp;
     const int32_t* tokc;
@@ -81,6 +82,7 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
+void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st);   // zy for all rows
 int fwd_slots_per_tile();
 
 struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, bf16 [Mc, Vpad]
@@ -132,6 +134,7 @@ struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
 };
 void launch_dw(const DwArgs& a, hipStream_t st);
 void set_waves_per_workgroup(int n);   // 4, 8 or 16 waves per contraction workgroup
+void set_cu_count(int n);              // compute units of the device: the contraction kernels launch one workgroup each
 
 
 // ---- f32_path.hip -----------------------------------------------------------------------------
