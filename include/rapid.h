@@ -106,7 +106,10 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
  *        4 (2 x 2 waves of 128 x 128) or 16.  Same 256 x 256 tile and same results either way.
  * keys 10, 11, 12: tile-order blocking (tiles along the first tile dimension that share one tile of
  *        the second before the order moves on) of the logits kernels, the dHidden kernel (0 = all)
- *        and the dW kernel; defaults 6, 0, 4 were measured best on MI355X.  Results are identical. */
+ *        and the dW kernel; defaults 6, 0, 4 were measured best on MI355X.  Results are identical.
+ * key 13: token-row tiles (of 256 rows) per launch of the forward logits kernel, default 256: the
+ *        forward sweeps all of W over one such block of rows at a time so that the block stays in
+ *        the memory-side cache.  Results are identical. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of
@@ -119,6 +122,16 @@ int rapid_set_tuning(int key, int value);
  * 11 dW conversion. */
 #define RAPID_N_STAGES 12
 int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stages);
+
+/* Diagnostic for benchmarks: the rate the bf16 matrix pipe sustains on its own (32 x 32 x 16 MFMAs
+ * out of registers on every SIMD of the device, no LDS or memory traffic), the ceiling the roofline
+ * of the contraction kernels (Sec. 3.1's LM head; the backward of Eq. (3)) can be read against at
+ * the clock the chip holds under load.  random_operands = 0 uses small-integer operands (the
+ * published peak is reached), 1 uses random bf16 values in [-1, 1] (the power management lowers the
+ * clock).  Runs `iters` (1 .. 10^7) MFMAs per accumulator on `stream`, WAITS for them, and writes
+ * TFLOP/s and the elapsed milliseconds to HOST pointers (either may be NULL).  Allocates nothing.
+ * Errors: RAPID_ERR_SHAPE (iters out of range), RAPID_ERR_ARCH, RAPID_ERR_HIP. */
+int rapid_mfma_probe(int random_operands, int iters, double* tflops_out, double* ms_out, void* stream);
 
 /* Workspace sizes in bytes for `op` at the given problem size.  rapid_workspace_bytes is the
  * recommended size (backward row-chunks large enough to fill the chip); rapid_workspace_min_bytes

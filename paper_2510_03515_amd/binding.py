@@ -23,7 +23,7 @@ STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LO
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_logprob_fwd",
-           "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read"]
+           "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe"]
 STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
           "dw", "f32_path", "dw_convert"]
 
@@ -79,6 +79,8 @@ def load():
     lib.rapid_compaction.restype = ci
     lib.rapid_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64), ci]
     lib.rapid_profile_read.restype = ci
+    lib.rapid_mfma_probe.argtypes = [ci, ci, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
+    lib.rapid_mfma_probe.restype = ci
     _lib = lib
     if os.environ.get("RAPID_WAVES"):      # 4, 8 or 16 waves per contraction workgroup (tuning only)
         lib.rapid_set_tuning(2, int(os.environ["RAPID_WAVES"]))
@@ -117,6 +119,13 @@ def rapid_version():
 
 def rapid_set_tuning(key, value):
     _check(load().rapid_set_tuning(key, value))
+
+
+def rapid_mfma_probe(random_operands, iters=100000):
+    """Returns (TFLOP/s, milliseconds) of the MFMA-only probe kernel."""
+    tf, ms = C.c_double(0.0), C.c_double(0.0)
+    _check(load().rapid_mfma_probe(int(bool(random_operands)), int(iters), C.byref(tf), C.byref(ms), _stream()))
+    return tf.value, ms.value
 
 
 def rapid_profile_read():

@@ -23,6 +23,7 @@ namespace {
 
 
 int g_gi_fwd = 6, g_gi_dh = 0, g_gi_dw = 4;   // L2 blocking of the tile order (tuning keys 10..12)
+int g_probe_cus = 256;                        // compute units of the current device
 int g_fwd_block_tiles = 256;                  // row tiles per forward launch (tuning key 13)
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
@@ -169,7 +170,10 @@ int check_arch() {
     }
     cached_dev = dev;
     cached_rc = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? RAPID_OK : RAPID_ERR_ARCH;
-    if (cached_rc == RAPID_OK) set_cu_count(prop.multiProcessorCount);
+    if (cached_rc == RAPID_OK) {
+        set_cu_count(prop.multiProcessorCount);
+        g_probe_cus = prop.multiProcessorCount;
+    }
     if (cached_rc != RAPID_OK) set_error("device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
     return cached_rc;
 }
@@ -339,6 +343,21 @@ int rapid_set_tuning(int key, int value) {
     }
     set_error("unknown tuning key/value %d/%d", key, value);
     return RAPID_ERR_DTYPE;
+}
+
+int rapid_mfma_probe(int random_operands, int iters, double* tflops_out, double* ms_out, void* stream) {
+    if (iters < 1 || iters > 10000000) {
+        set_error("iters must be in 1 .. 10^7");
+        return RAPID_ERR_SHAPE;
+    }
+    int rc = check_arch();
+    if (rc) return rc;
+    rc = run_mfma_probe(random_operands != 0, iters, g_probe_cus, tflops_out, ms_out, (hipStream_t)stream);
+    if (rc) {
+        set_error("rapid_mfma_probe: HIP event or launch failure");
+        return rc;
+    }
+    return check_launch("rapid_mfma_probe");
 }
 
 int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stages) {

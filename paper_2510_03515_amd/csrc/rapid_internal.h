@@ -137,6 +137,9 @@ void set_waves_per_workgroup(int n);   // 4, 8 or 16 waves per contraction workg
 void set_cu_count(int n);              // compute units of the device: the contraction kernels launch one workgroup each
 
 
+// ---- probe.hip -----------------------------------------------------------------------------------
+int run_mfma_probe(int random_operands, int iters, int num_cu, double* tflops_out, double* ms_out, hipStream_t st);
+
 // ---- f32_path.hip -----------------------------------------------------------------------------
 // C[i][j] (+)= alpha sum_k A(i,k) B(k,j), arbitrary strides, optional index maps, and a device-side
 // row count.  Accumulates in fp64.

@@ -296,3 +296,21 @@ def test_edge_cases(rb):
     rb.rapid_logprob_fwd(g["hidden"], g["W"], tok, g["mask"], dev_status=status)
     torch.cuda.synchronize()
     assert status.item() & rb.STATUS_BAD_TOKEN
+
+
+def test_mfma_probe_and_forward_row_blocks(rb):
+    """The probe reports a rate between zero and the published peak, random operands never beat
+    integer ones by more than noise; the forward gives the same bits for any row-block size."""
+    tf_int, ms = rb.rapid_mfma_probe(0, 20000)
+    tf_rnd, _ = rb.rapid_mfma_probe(1, 20000)
+    assert ms > 0 and 100.0 < tf_int < 2500.0 * 1.05
+    assert 100.0 < tf_rnd < tf_int * 1.1
+    spec = wl.small_spec("row_blocks", d=192, V=1500, prompts=6, G=4, len_lo=20, len_hi=90)
+    w = wl.make_workload(spec, seed=3, device="cuda")
+    ref, _ = rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"])
+    try:
+        rb.rapid_set_tuning(13, 1)   # one 256-row tile per launch: several launches, the last ones empty
+        got, _ = rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"])
+    finally:
+        rb.rapid_set_tuning(13, 256)
+    assert torch.equal(ref, got)
