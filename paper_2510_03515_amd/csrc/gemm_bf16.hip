@@ -38,6 +38,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -639,7 +640,8 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
     for (int tt = 0; tt < WJ * 8; ++tt) {
         const int row = tt * 4 + r4;
         const uint4 v = *(const uint4*)(region + row * 256 + ((c ^ (row & 15)) * 16));
-        *(uint4*)(out + (int64_t)tt * 4 * a.ldz) = v;
+        // streamed: the chunk is far larger than the L2s and must not push the operand panels out
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4*)(out + (int64_t)tt * 4 * a.ldz));
     }
     }
 }
