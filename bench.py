@@ -20,9 +20,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
 PEAK_HBM = 8.0e12         # B/s
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled (see the profile named in the output), per launch:
-# fwd_lse on 300630 rows; dz / dh / dw on a full 65536-row chunk
-MEASURED_TRAFFIC_BYTES = {"fwd_lse": 207e9 + 11.7e9, "dz": 45.1e9 + 20.4e9, "dh": 59e9 + 0.2e9, "dw": 64.5e9 + 0.93e9}
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled (see the profile named in the output), of one launch on a
+# full 65536-row block
+MEASURED_TRAFFIC_BYTES = {"fwd_lse": 48.0e9 + 0.6e9, "dz": 54.9e9 + 20.3e9, "dh": 59.5e9 + 0.2e9, "dw": 55.9e9 + 1.0e9}
 
 
 def cpu_baseline(w, tokens_per_seq=640):

@@ -106,7 +106,7 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
  *        4 (2 x 2 waves of 128 x 128) or 16.  Same 256 x 256 tile and same results either way.
  * keys 10, 11, 12: tile-order blocking (tiles along the first tile dimension that share one tile of
  *        the second before the order moves on) of the logits kernels, the dHidden kernel (0 = all)
- *        and the dW kernel; defaults 6, 0, 4 were measured best on MI355X.  Results are identical.
+ *        and the dW kernel; defaults 4, 0, 2 were measured best on MI355X.  Results are identical.
  * key 13: token-row tiles (of 256 rows) per launch of the forward logits kernel, default 256: the
  *        forward sweeps all of W over one such block of rows at a time so that the block stays in
  *        the memory-side cache.  Results are identical. */

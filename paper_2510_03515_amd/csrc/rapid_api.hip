@@ -22,7 +22,7 @@ void set_error(const char* fmt, ...) {
 namespace {
 
 
-int g_gi_fwd = 6, g_gi_dh = 0, g_gi_dw = 4;   // L2 blocking of the tile order (tuning keys 10..12)
+int g_gi_fwd = 4, g_gi_dh = 0, g_gi_dw = 2;   // L2 blocking of the tile order (tuning keys 10..12)
 int g_probe_cus = 256;                        // compute units of the current device
 int g_fwd_block_tiles = 256;                  // row tiles per forward launch (tuning key 13)
 
