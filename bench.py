@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--waves", type=int, default=0, help="4 or 8 waves per contraction workgroup (0 = library default)")
     ap.add_argument("--gi", type=str, default="", help="tile-order blocking fwd,dh,dw (tuning experiment)")
     ap.add_argument("--tune", type=str, default="", help="library tuning keys, key=value[,key=value...] (experiments)")
+    ap.add_argument("--logits-cache", action="store_true",
+                    help="time the opt-in mode that keeps bf16 logits in the workspace instead of the default")
+    ap.add_argument("--no-cache-mode", action="store_true", help="skip the extra measurement of the opt-in mode")
     ap.add_argument("--chunk-rows", type=int, default=0, help="size the workspace for backward chunks of this many rows")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -112,11 +115,11 @@ def main():
             vpad = (V + 255) // 256 * 256
             ldv = vpad + 64 if (vpad // 64) % 2 == 0 else vpad
             ws_bytes = mn + (args.chunk_rows - 256) * ldv * 2
-        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes)
+        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes, logits_cache=args.logits_cache)
         ws_bytes = buf.workspace.numel()
         step = lambda: rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b,
                                                    w["rewards"], w["group_ids"], K, buffers=buf,
-                                                   optional_outputs=False)
+                                                   optional_outputs=False, logits_cache=args.logits_cache)
         flops_per_token = 6.0 * d * V
     torch.cuda.synchronize()
 
@@ -180,6 +183,39 @@ def main():
     tf_rnd, _ = rb.rapid_mfma_probe(1, 100000)
     out["mfma_probe"] = {"unit": "TFLOP/s", "small_integer_operands": tf_int, "random_bf16_operands": tf_rnd,
                          "note": "8 independent 32x32x16 bf16 MFMA chains per wave, 2 waves per SIMD, registers only"}
+    # The opt-in mode that trades workspace for work (bf16 logits kept by the forward, no recomputation
+    # in the backward), timed the same way; reported next to the default, never as `value`.
+    if not fwd_only and not args.logits_cache and not args.no_cache_mode:
+        need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16)
+        del buf
+        torch.cuda.empty_cache()
+        free, _ = torch.cuda.mem_get_info()
+        if need and need + (8 << 30) < free:
+            cbuf = rb.IwPgBuffers(w["hidden"], w["W"], K, logits_cache=True)
+            cstep = lambda: rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b,
+                                                        w["rewards"], w["group_ids"], K, buffers=cbuf,
+                                                        optional_outputs=False, logits_cache=True)
+            for _ in range(args.warmup):
+                cstep()
+            torch.cuda.synchronize()
+            rb.rapid_set_tuning(1, 1)
+            rb.rapid_profile_read()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                cstep()
+            torch.cuda.synchronize()
+            cdt = time.perf_counter() - t0
+            cprof = rb.rapid_profile_read()
+            rb.rapid_set_tuning(1, 0)
+            out["logits_cache_mode"] = {
+                "value": M * args.steps / cdt, "unit": "tokens/s", "ms_per_step": cdt / args.steps * 1e3,
+                "frac_bf16_mfma_peak_algorithmic": flops_per_token * M * args.steps / cdt / PEAK_BF16_MFMA,
+                "workspace_gib": need / 2**30,
+                "stages_ms_per_step": {k: ms / args.steps for k, (ms, n) in cprof.items() if n},
+                "note": "opts.logits_cache = 1: 6 d V flop per token executed instead of 8"}
+            del cbuf
+        else:
+            out["logits_cache_mode"] = None
     if not args.no_cpu_baseline and not fwd_only:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -56,6 +56,7 @@ extern "C" {
 #define RAPID_OP_LOGPROB_FWD 0
 #define RAPID_OP_GROUP_ADVANTAGE 1
 #define RAPID_OP_IW_PG_FWD_BWD 2
+#define RAPID_OP_IW_PG_FWD_BWD_CACHED 3 /* workspace query only: rapid_iw_pg_loss_fwd_bwd with logits_cache = 1 */
 
 /* Options of rapid_iw_pg_loss_fwd_bwd (host struct).  rapid_iw_pg_default_opts() fills the
  * paper's defaults: eta = 2.0 (Appendix A, RL hyper-parameter table), everything else as
@@ -74,7 +75,13 @@ typedef struct rapid_iw_pg_opts {
     int normalized_grads;  /* 1: loss, dhidden and dW are returned multiplied by exp(-lambda), with
                               lambda = log max_n |g_n| reported in diag->grad_log_scale, so that
                               ratios that underflow fp32 still give usable gradients */
-    int reserved;
+    int logits_cache;      /* 0 (default): the backward regenerates the logits tile by tile from hidden and W;
+                              nothing of size rows x V outlives a row chunk.  1 (bf16 inputs only): the
+                              forward also stores the logits (bf16) of every row in the workspace and the
+                              backward turns them into dz in place instead of recomputing them: one
+                              contraction fewer, for N*T*V*2 more bytes of workspace (size:
+                              rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...)) and logits rounded
+                              to bf16 before the softmax is regenerated */
     const float* coef_override; /* DEVICE [N] or NULL: use these per-generation coefficients g_n
                               = dLoss/dlogp_{n,t} instead of the estimator's (loss = sum g_n) */
 } rapid_iw_pg_opts;

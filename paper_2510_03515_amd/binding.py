@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librapid_hip.so")
 RAPID_OK = 0
 DTYPE_F32, DTYPE_BF16 = 0, 1
 W_DV, W_VD = 0, 1
-OP_LOGPROB_FWD, OP_GROUP_ADVANTAGE, OP_IW_PG_FWD_BWD = 0, 1, 2
+OP_LOGPROB_FWD, OP_GROUP_ADVANTAGE, OP_IW_PG_FWD_BWD, OP_IW_PG_FWD_BWD_CACHED = 0, 1, 2, 3
 STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LOGP = 1, 2, 4, 8
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
@@ -38,7 +38,7 @@ class IwPgOpts(C.Structure):
     _fields_ = [("eta", C.c_float), ("coef_mode", C.c_int), ("baseline_mode", C.c_int),
                 ("loss_scale", C.c_float), ("temperature", C.c_float), ("w_layout", C.c_int),
                 ("dw_dtype", C.c_int), ("accumulate_dw", C.c_int), ("normalized_grads", C.c_int),
-                ("reserved", C.c_int), ("coef_override", C.c_void_p)]
+                ("logits_cache", C.c_int), ("coef_override", C.c_void_p)]
 
 
 class IwPgDiag(C.Structure):
@@ -205,13 +205,14 @@ class IwPgBuffers:
     """Output and workspace tensors of rapid_iw_pg_loss_fwd_bwd, allocated once and reusable."""
 
     def __init__(self, hidden, W, K, w_layout=W_DV, dw_dtype=torch.float32, workspace_bytes=None,
-                 minimum_workspace=False):
+                 minimum_workspace=False, logits_cache=False):
         N, T, d = hidden.shape
         V = W.shape[1] if w_layout == W_DV else W.shape[0]
         dev = hidden.device
         dt = _dtype_code(hidden)
         if workspace_bytes is None:
-            workspace_bytes = rapid_workspace_bytes(OP_IW_PG_FWD_BWD, N, T, d, V, K, dt, minimum=minimum_workspace)
+            op = OP_IW_PG_FWD_BWD_CACHED if logits_cache else OP_IW_PG_FWD_BWD
+            workspace_bytes = rapid_workspace_bytes(op, N, T, d, V, K, dt, minimum=minimum_workspace)
         self.workspace = alloc_workspace(workspace_bytes, dev)
         self.loss = torch.empty(1, dtype=torch.float32, device=dev)
         self.dhidden = torch.empty_like(hidden)
@@ -232,7 +233,7 @@ class IwPgBuffers:
 def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, K, buffers=None,
                              eta=2.0, coef_mode=0, baseline_mode=0, loss_scale=1.0, temperature=1.0,
                              w_layout=W_DV, accumulate_dw=False, normalized_grads=False, coef_override=None,
-                             optional_outputs=True):
+                             optional_outputs=True, logits_cache=False):
     """Enqueues the fused forward+backward on the current stream and returns the IwPgBuffers that
     hold the outputs (loss, dhidden, dW, logp_cur, tok_logratio, seq_logratio, adv, diag)."""
     N, T, d = hidden.shape
@@ -253,6 +254,7 @@ def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group
     o.dw_dtype = _dtype_code(b.dW)
     o.accumulate_dw = int(bool(accumulate_dw))
     o.normalized_grads = int(bool(normalized_grads))
+    o.logits_cache = int(bool(logits_cache))
     if coef_override is not None:
         _need(coef_override, torch.float32, "coef_override")
         o.coef_override = coef_override.data_ptr()

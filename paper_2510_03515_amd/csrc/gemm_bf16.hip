@@ -524,8 +524,47 @@ __device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d)
     return __builtin_bit_cast(uint2, r);
 }
 
+// A 256 x 256 tile of bf16 values leaves through LDS so that it reaches memory as whole 256-byte row
+// segments.  Each wave owns a private region (its WJ * 32 token rows x 128 columns, 256 bytes per
+// row; the regions are exactly the two idle LDS stages).  A lane writes its runs of 4 consecutive
+// columns (8 bytes) at 16-byte chunk c ^ (row % 16) of the row, then the wave reads the region back
+// row-wise, 16 lanes x 16 bytes per row, and stores 4 full rows per instruction.  The stores are
+// streamed (non-temporal): the destination is far larger than the L2s and must not push the
+// operand panels out.  `value(ib, jb, v)` is the element the lane holds in accumulator register v of
+// block (ib, jb); `out` points at (first row of the wave, first column of the wave) of the tile.
+// All waves must be done with both LDS stages (barrier) before the call.
+template <class S, class F>
+__device__ __forceinline__ void store_tile_through_lds(char* lds, const Lane<S>& L, bf16_t* out, int64_t ld, F&& value) {
+    constexpr int WI = S::WI, WJ = S::WJ;
+    static_assert(WI == 4, "laid out for 128 columns (256 bytes) per wave row");
+    char* region = lds + L.wave * (WJ * 32 * 256);
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) {
+        const int row = jb * 32 + L.lj;
+        char* lrow = region + row * 256 + L.hi * 8;
+        const int rx = row & 15;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(uint2*)(lrow + (((ib * 4 + q) ^ rx) * 16)) =
+                    pack_bf16x4(value(ib, jb, q * 4), value(ib, jb, q * 4 + 1), value(ib, jb, q * 4 + 2),
+                                value(ib, jb, q * 4 + 3));
+    }
+    // read back row-wise and store: lane l covers chunk l % 16 of row 4 t + l / 16
+    const int c = L.lane & 15, r4 = L.lane >> 4;
+    bf16_t* o = out + (int64_t)r4 * ld + c * 8;
+#pragma unroll 8
+    for (int tt = 0; tt < WJ * 8; ++tt) {
+        const int row = tt * 4 + r4;
+        const uint4 v = *(const uint4*)(region + row * 256 + ((c ^ (row & 15)) * 16));
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4*)(o + (int64_t)tt * 4 * ld));
+    }
+}
+
 // ------------------------------------------------------------------------------------- fwd_lse
-template <class S>
+// STORE: also keep the tile's logits (bf16, before the temperature) in a.zc for a backward that reloads them.
+template <class S, bool STORE>
 __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
@@ -540,6 +579,13 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     f32x16 acc[WI][WJ];
     mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk, a.Hc + j_tile * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds,
                 acc);
+    if (STORE) {
+        __syncthreads();   // every wave is done with both stages
+        const Lane<S> Ls;
+        store_tile_through_lds<S>(lds, Ls,
+                                  a.zc + (j_tile + Ls.wave_j * (WJ * 32)) * a.ldz + (int64_t)t.ti * S::BI + Ls.wave_i * (WI * 32),
+                                  a.ldz, [&](int ib, int jb, int v) { return acc[ib][jb][v]; });
+    }
     // Epilogue: per token row j (one lane pair) the max and the sum of exponentials over this wave's
     // 128 vocabulary columns.  The logit of the sampled token is gathered by a separate small kernel,
     // so the per-element work is one max, one fma, one exp and one add.
@@ -584,15 +630,9 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ dz
-// Epilogue: the tile leaves through LDS so that it reaches memory as whole 256-byte row segments.
-// Each wave owns a private 32 KiB region (its 128 rows x 128 columns of bf16, 256 bytes per row;
-// the four regions are exactly the two idle LDS stages).  A lane writes its runs of 4 consecutive
-// columns (8 bytes) at 16-byte chunk c ^ (row % 16) of the row, then the wave reads the region
-// back row-wise, 16 lanes x 16 bytes per row, and stores 4 full rows per instruction.
 template <class S>
 __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
-    static_assert(WI == 4, "the LDS-staged epilogue is laid out for 128 columns (256 bytes) per wave row");
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.m0 >= Mr) return;
@@ -609,40 +649,20 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
     // the per-element work is one fma, one exp, one multiply and half a convert.  Rows past the last
     // token get g = 0; columns past V hold finite values that only ever meet zero weights.
     const Lane<S> L;
-    char* region = lds + L.wave * (WJ * 32 * 256);   // WJ * 32 rows of 256 bytes per wave
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
     const int64_t jl_base = (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32);   // row in chunk
     const float zs = a.inv_temp * LOG2E;
+    float ngj[WJ], nlse[WJ];
 #pragma unroll
     for (int jb = 0; jb < WJ; ++jb) {
-        const int row = jb * 32 + L.lj;
-        const int64_t j = a.m0 + jl_base + row;
+        const int64_t j = a.m0 + jl_base + jb * 32 + L.lj;
         const bool live = j < M;
-        const float ngj = live ? -a.g[a.seqc[j]] * a.inv_temp : 0.f;
-        const float nlse = live ? -a.lse_c[j] * LOG2E : 0.f;
-        char* lrow = region + row * 256 + L.hi * 8;
-        const int rx = row & 15;
-#pragma unroll
-        for (int ib = 0; ib < WI; ++ib)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float o[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    o[r] = ngj * __builtin_amdgcn_exp2f(fmaf(acc[ib][jb][q * 4 + r], zs, nlse));
-                *(uint2*)(lrow + (((ib * 4 + q) ^ rx) * 16)) = pack_bf16x4(o[0], o[1], o[2], o[3]);
-            }
+        ngj[jb] = live ? -a.g[a.seqc[j]] * a.inv_temp : 0.f;
+        nlse[jb] = live ? -a.lse_c[j] * LOG2E : 0.f;
     }
-    // read back row-wise and store: lane l covers chunk l % 16 of row 4 t + l / 16
-    const int c = L.lane & 15, r4 = L.lane >> 4;
-    bf16_t* out = a.dz + (jl_base + r4) * a.ldz + i_base + c * 8;
-#pragma unroll 8
-    for (int tt = 0; tt < WJ * 8; ++tt) {
-        const int row = tt * 4 + r4;
-        const uint4 v = *(const uint4*)(region + row * 256 + ((c ^ (row & 15)) * 16));
-        // streamed: the chunk is far larger than the L2s and must not push the operand panels out
-        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4*)(out + (int64_t)tt * 4 * a.ldz));
-    }
+    store_tile_through_lds<S>(lds, L, a.dz + jl_base * a.ldz + i_base, a.ldz, [&](int ib, int jb, int v) {
+        return ngj[jb] * __builtin_amdgcn_exp2f(fmaf(acc[ib][jb][v], zs, nlse[jb]));
+    });
     }
 }
 
@@ -773,6 +793,43 @@ __global__ void token_onehot_kernel(bf16_t* __restrict__ dz, int64_t ldz, int64_
     *p = __builtin_bit_cast(bf16_t, r);
 }
 
+// dz from cached logits, in place: one workgroup per token row of the block.
+// dz[v] = g (onehot_y[v] - exp(z[v] / temperature - lse)) / temperature; rows past the last token give 0.
+__global__ __launch_bounds__(256) void dz_from_logits_kernel(bf16_t* __restrict__ zc, int64_t ldz, int64_t m0, int64_t Vpad,
+                                                             const int32_t* __restrict__ tokc,
+                                                             const int32_t* __restrict__ seqc,
+                                                             const float* __restrict__ lse_c, const float* __restrict__ g,
+                                                             float inv_temp, const int32_t* __restrict__ counts) {
+    const int64_t j = m0 + blockIdx.x;
+    const int M = counts[CNT_M], Mr = counts[CNT_MR];
+    if (j >= Mr) return;
+    const bool live = j < M;
+    const float gj = live ? g[seqc[j]] * inv_temp : 0.f;
+    const float nlse = live ? -lse_c[j] * LOG2E : 0.f;
+    const int tok = live ? tokc[j] : -1;
+    const float zs = inv_temp * LOG2E;
+    uint4* row = (uint4*)(zc + (int64_t)blockIdx.x * ldz);
+    for (int c = threadIdx.x; c < Vpad / 8; c += 256) {
+        const u32x4 in = __builtin_nontemporal_load((const u32x4*)(row + c));
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float lo = __builtin_bit_cast(float, in[e] << 16), hi = __builtin_bit_cast(float, in[e] & 0xffff0000u);
+            o[2 * e] = -gj * __builtin_amdgcn_exp2f(fmaf(lo, zs, nlse));
+            o[2 * e + 1] = -gj * __builtin_amdgcn_exp2f(fmaf(hi, zs, nlse));
+        }
+        const int rel = tok - c * 8;
+        if (rel >= 0 && rel < 8) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += (e == rel) ? gj : 0.f;
+        }
+        const uint2 a0 = pack_bf16x4(o[0], o[1], o[2], o[3]), a1 = pack_bf16x4(o[4], o[5], o[6], o[7]);
+        u32x4 out;
+        out[0] = a0.x; out[1] = a0.y; out[2] = a1.x; out[3] = a1.y;
+        __builtin_nontemporal_store(out, (u32x4*)(row + c));
+    }
+}
+
 template <class K>
 void allow_lds(K kernel, int bytes) {
     (void)hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
@@ -792,8 +849,13 @@ using G16_J128 = Geo<4, 4, 2, 1>;  // 256 x 128
 
 template <class S>
 void launch_fwd_lse_t(const FwdArgs& a, hipStream_t st) {
-    allow_lds(fwd_lse_kernel<S>, S::LDS_BYTES);
-    fwd_lse_kernel<S><<<grid_for(a.tilesV, a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
+    if (a.zc) {
+        allow_lds(fwd_lse_kernel<S, true>, S::LDS_BYTES);
+        fwd_lse_kernel<S, true><<<grid_for(a.tilesV, a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
+    } else {
+        allow_lds(fwd_lse_kernel<S, false>, S::LDS_BYTES);
+        fwd_lse_kernel<S, false><<<grid_for(a.tilesV, a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
+    }
 }
 template <class S>
 void launch_dz_t(const DzArgs& a, hipStream_t st) {
@@ -831,6 +893,12 @@ void launch_dz(const DzArgs& a, hipStream_t st) {
     const int64_t rows = (int64_t)a.tilesM * 256;
     token_onehot_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, st>>>(a.dz, a.ldz, a.m0, rows, a.tokc, a.seqc, a.g,
                                                                       a.inv_temp, a.counts);
+}
+
+void launch_dz_from_logits(const DzArgs& a, hipStream_t st) {
+    const int64_t rows = (int64_t)a.tilesM * 256;
+    dz_from_logits_kernel<<<(unsigned)rows, 256, 0, st>>>(a.dz, a.ldz, a.m0, a.Vpad, a.tokc, a.seqc, a.lse_c, a.g,
+                                                       a.inv_temp, a.counts);
 }
 
 void launch_dh(const DhArgs& a, hipStream_t st) {

@@ -194,6 +194,7 @@ struct FwdIo {
     const void* hidden; const void* W; const int32_t* tokens; const uint8_t* mask;
     int w_layout; float temperature;
     float* logp_out; float* lse_out; int32_t* dev_status;
+    bf16_t* zc = nullptr;   // if set: [Mmax_pad, ldv], the forward also stores the logits there
 };
 
 // compaction, operand packing and the streaming log-softmax forward; leaves lse_c, tokc, seqc,
@@ -232,6 +233,7 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
         a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
         a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy); a.gi = g_gi_fwd;
+        a.zc = io.zc; a.ldz = p.ldv;
         // The forward runs in blocks of token rows, all vocabulary tiles per block, so that a block's
         // hidden rows stay in the memory-side cache while every XCD sweeps its share of W over them
         // (one launch over all rows re-reads the hidden rows from HBM once per group of W panels).
@@ -304,7 +306,7 @@ using namespace rapid;
 
 extern "C" {
 
-int rapid_version(void) { return 1; }
+int rapid_version(void) { return 2; }
 
 const char* rapid_last_error(void) { return g_err; }
 
@@ -320,6 +322,7 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
     o->dw_dtype = RAPID_DTYPE_F32;
     o->accumulate_dw = 0;
     o->normalized_grads = 0;
+    o->logits_cache = 0;
     o->coef_override = nullptr;
 }
 
@@ -383,6 +386,12 @@ int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stage
 
 size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
     if (op == RAPID_OP_GROUP_ADVANTAGE) return 0;
+    if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) {   // the chunk buffer holds every row
+        Plan p;
+        if (dtype != RAPID_DTYPE_BF16 || !make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype)) return 0;
+        size_chunks(p, p.Mmax_pad);
+        return p.total + 1024;
+    }
     if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
     Plan p;
     if (!make_plan(p, op, N, T, d, V, K, dtype)) return 0;
@@ -392,6 +401,7 @@ size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V,
 
 size_t rapid_workspace_min_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
     if (op == RAPID_OP_GROUP_ADVANTAGE) return 0;
+    if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) return rapid_workspace_bytes(op, N, T, d, V, K, dtype);
     if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
     Plan p;
     if (!make_plan(p, op, N, T, d, V, K, dtype)) return 0;
@@ -505,6 +515,10 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         set_error("accumulate_dw needs an fp32 dW");
         return RAPID_ERR_DTYPE;
     }
+    if (o.logits_cache != 0 && (o.logits_cache != 1 || dtype != RAPID_DTYPE_BF16)) {
+        set_error("logits_cache must be 0 or 1, and 1 needs bf16 inputs");
+        return RAPID_ERR_DTYPE;
+    }
     if (((uintptr_t)dhidden_out | (uintptr_t)dW_out) % 16 != 0) {
         set_error("dhidden_out and dW_out must be 16-byte aligned");
         return RAPID_ERR_SHAPE;
@@ -513,6 +527,12 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     if (Mfit < ROW_TILE) {
         set_error("workspace of %zu bytes is below the minimum %zu", workspace_bytes,
                   rapid_workspace_min_bytes(RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype));
+        return RAPID_ERR_WORKSPACE;
+    }
+    const bool cached = o.logits_cache == 1;
+    if (cached && Mfit < p.Mmax_pad) {
+        set_error("workspace of %zu bytes is below the %zu the logits cache needs", workspace_bytes,
+                  rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dtype));
         return RAPID_ERR_WORKSPACE;
     }
     size_chunks(p, Mfit);
@@ -535,6 +555,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
 
     // forward: current-policy log-probs of the sampled tokens
     FwdIo io{hidden, W, tokens, mask, o.w_layout, o.temperature, logp_cur, nullptr, dev_status};
+    if (cached) io.zc = at<bf16_t>(ws, p.chunk0);   // the chunk buffer holds all rows
     run_forward(p, ws, io, st);
 
     // generation-level log ratios, clipped-weight group baseline, coefficients and loss
@@ -560,7 +581,6 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         bf16_t* Hc = at<bf16_t>(ws, p.Hc);
         bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
         bf16_t* Wdv = at<bf16_t>(ws, p.Wdv);
-        bf16_t* dz = at<bf16_t>(ws, p.chunk0);
         {
             Span sp(ST_PACK, st);
             if (o.w_layout == RAPID_W_DV)
@@ -570,9 +590,12 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                 launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.ldv, p.V, p.d, p.Vpad, p.dpadR, nullptr,
                                           0, st);
         }
+        // with cached logits the chunk buffer holds every row and the backward walks it in blocks
+        const int64_t step = cached ? (recommended_chunk(p) < p.Mc ? recommended_chunk(p) : p.Mc) : p.Mc;
         int chunk = 0;
-        for (int64_t m0 = 0; m0 < p.Mmax_pad; m0 += p.Mc, ++chunk) {
-            const int64_t rows = (p.Mmax_pad - m0) < p.Mc ? (p.Mmax_pad - m0) : p.Mc;   // multiple of 256
+        for (int64_t m0 = 0; m0 < p.Mmax_pad; m0 += step, ++chunk) {
+            const int64_t rows = (p.Mmax_pad - m0) < step ? (p.Mmax_pad - m0) : step;   // multiple of 256
+            bf16_t* dz = at<bf16_t>(ws, p.chunk0) + (cached ? m0 * p.ldv : 0);
             DzArgs za;
             za.Wvd = Wvd; za.Hc = Hc + m0 * p.ldk; za.dpad = p.dpad; za.ldk = p.ldk; za.ldz = p.ldv;
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
@@ -580,7 +603,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz; za.gi = g_gi_fwd;
             {
                 Span sp(ST_DZ, st);
-                launch_dz(za, st);
+                if (cached) launch_dz_from_logits(za, st); else launch_dz(za, st);
             }
             DhArgs ha;
             ha.Wdv = Wdv; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
@@ -591,7 +614,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                 launch_dh(ha, st);
             }
             DwArgs wa;
-            wa.dz = dz; wa.Hc = Hc + m0 * p.ldk; wa.Mc = p.Mc; wa.ldz = p.ldv; wa.ldH = p.ldk;
+            wa.dz = dz; wa.Hc = Hc + m0 * p.ldk; wa.Mc = step; wa.ldz = p.ldv; wa.ldH = p.ldk;
             wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = m0; wa.counts = counts;
             wa.dW = dW32; wa.w_layout = o.w_layout; wa.beta = (chunk > 0 || o.accumulate_dw) ? 1 : 0; wa.gi = g_gi_dw;
             {

@@ -80,6 +80,8 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     int64_t ld_part;
     float* zy;            // [Mmax_pad]
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
+    bf16_t* zc;           // NULL, or [Mmax_pad, ldz]: the kernel also stores the logits (before the temperature)
+    int64_t ldz;
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
 void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st);   // zy for all rows
@@ -103,6 +105,8 @@ struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, b
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_dz(const DzArgs& a, hipStream_t st);
+// dz in place from logits the forward stored in a.dz (rows m0 .. of the chunk buffer); uses the row fields of `a` only
+void launch_dz_from_logits(const DzArgs& a, hipStream_t st);
 
 struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const bf16_t* Wdv;    // [dpadR, Vpad]

@@ -147,13 +147,14 @@ def _run_pair(rb, spec, seed=0, layout="dv", min_ws=False, dw_dtype=torch.float3
     Wold = g["W_old"] if layout == "dv" else g["W_old"].t().contiguous()
     logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], Wold, g["tokens"], g["mask"], w_layout=lay,
                                      temperature=kw.get("temperature", 1.0))
-    buf = rb.IwPgBuffers(g["hidden"], Wg, w["K"], w_layout=lay, dw_dtype=dw_dtype, minimum_workspace=min_ws)
+    buf = rb.IwPgBuffers(g["hidden"], Wg, w["K"], w_layout=lay, dw_dtype=dw_dtype, minimum_workspace=min_ws,
+                         logits_cache=kw.get("logits_cache", False))
     coef = kw.pop("coef_override", None)
     out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], Wg, g["tokens"], g["mask"], logp_b, g["rewards"],
                                       g["group_ids"], w["K"], buffers=buf, w_layout=lay,
                                       coef_override=None if coef is None else torch.from_numpy(coef).cuda(), **kw)
     torch.cuda.synchronize()
-    okw = {k: v for k, v in kw.items() if k != "accumulate_dw"}
+    okw = {k: v for k, v in kw.items() if k not in ("accumulate_dw", "logits_cache")}
     ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(w["rewards"]), _np(w["group_ids"]), w["K"],
                                  coef_override=coef, **okw)
     return w, out, ref
@@ -314,3 +315,36 @@ def test_mfma_probe_and_forward_row_blocks(rb):
     finally:
         rb.rapid_set_tuning(13, 256)
     assert torch.equal(ref, got)
+
+
+@pytest.mark.parametrize("name", ["bf16_small", "bf16_ragged"])
+@pytest.mark.parametrize("layout", ["dv", "vd"])
+def test_fwd_bwd_logits_cache(rb, name, layout):
+    """logits_cache = 1: the forward keeps bf16 logits, the backward reloads them instead of
+    recomputing; same tolerances against the oracle, same forward bits as the default mode."""
+    print(f"fwd_bwd logits_cache {name} {layout}", flush=True)
+    spec = SPECS[name]
+    w, out, ref = _run_pair(rb, spec, layout=layout, logits_cache=True)
+    _check_pair(rb, spec, out, ref, layout)
+    w2, out2, _ = _run_pair(rb, spec, layout=layout)
+    assert torch.equal(out.logp_cur, out2.logp_cur) and torch.equal(out.loss, out2.loss)
+    for kw in (dict(temperature=0.8), dict(normalized_grads=True), dict(coef_mode=1, eta=1.05)):
+        w, out, ref = _run_pair(rb, spec, layout=layout, logits_cache=True, **kw)
+        _check_pair(rb, spec, out, ref, layout)
+
+
+def test_logits_cache_workspace_and_errors(rb):
+    spec = SPECS["bf16_small"]
+    w, g = _make(spec)
+    N, T, d = g["hidden"].shape
+    V = g["W"].shape[1]
+    need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, w["K"], rb.DTYPE_BF16)
+    plain = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, N, T, d, V, w["K"], rb.DTYPE_BF16, minimum=True)
+    assert need >= plain + (N * T - 256) * V * 2
+    assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, w["K"], rb.DTYPE_F32) == 0
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+    small = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], minimum_workspace=True)
+    with pytest.raises(rb.RapidError) as e:
+        rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"],
+                                    g["group_ids"], w["K"], buffers=small, logits_cache=True)
+    assert e.value.code == -4

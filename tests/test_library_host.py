@@ -87,6 +87,10 @@ def test_host_validation_returns_codes_without_a_gpu(rb):
     o.accumulate_dw, o.dw_dtype = 1, rb.DTYPE_BF16
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -3
     o = rb.default_opts()
+    o.logits_cache = 2
+    assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -3
+    o = rb.default_opts()
+    assert o.logits_cache == 0
     o.loss_scale = -1.0
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
     assert lib.rapid_set_tuning(12345, 0) == -3
