@@ -6,15 +6,16 @@
 //   dw      : dW (+)= H^T . dz       (contraction over the tokens of a row chunk)
 //
 // Tiling.  C[i][j] = sum_k A(i,k) B(j,k); operands are zero padded to whole tiles, so the loop has
-// no bounds checks.  A workgroup of four 64-lane waves (2 x 2) owns a (64 WI) x (64 WJ) tile, each
-// wave WI x WJ blocks of 32 x 32 computed with v_mfma_f32_32x32x16_bf16 (a lane feeds 8 consecutive
-// k of one row).  The 256 x 256 tile fills the register file (256 accumulator registers per lane)
-// and is the largest a CU can hold, which minimises L2 -> LDS bytes per flop.  K advances 64
-// elements per step through two LDS stages of 64 KiB (one barrier per step); operand tiles arrive
-// by global_load_lds_dwordx4 (memory -> LDS without passing through registers; consecutive lanes
-// fill consecutive 16-byte slots, so the LDS swizzle is applied to the global address).  One
-// workgroup computes one tile; workgroup ids are mapped to tiles so that the workgroups resident
-// on an XCD (ids equal mod 8) own neighbouring tiles and share operand panels in that XCD's L2.
+// no bounds checks.  A workgroup of NWI x NWJ 64-lane waves owns a 256 x 256 tile (the largest whose
+// fp32 accumulators a CU's registers hold, which minimises L2 -> LDS bytes per flop), each wave
+// WI x WJ blocks of 32 x 32 computed with v_mfma_f32_32x32x16_bf16 (a lane feeds 8 consecutive k of
+// one row).  The default is 2 x 4 waves of 128 x 64, two waves per SIMD.  K advances 64 elements
+// per step through two LDS stages of 64 KiB (one barrier per step); operand tiles arrive by
+// global_load_lds_dwordx4 (memory -> LDS without passing through registers; consecutive lanes fill
+// consecutive 16-byte slots, so the LDS swizzle is applied to the global address).  The kernels
+// are persistent: one workgroup per CU walks tile ids that are mapped to tiles so that the
+// workgroups resident on an XCD (ids equal mod 8) own neighbouring tiles and share operand panels
+// in that XCD's L2.
 //
 // LDS layouts (both conflict-free for a 256-byte LDS cycle, checked with SQ_LDS_BANK_CONFLICT):
 //  * row-major operands ([row][k], k contiguous): a tile row of a step is 128 bytes = 8 chunks of
@@ -45,9 +46,10 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 constexpr float LOG2E = 1.4426950408889634f;
 
 // Geometry of a workgroup: NWI x NWJ waves, each owning WI x WJ blocks of 32 x 32.
-// Two are used: 2 x 2 waves of 128 x 128 (one wave per SIMD, 256 accumulator registers per lane) and
-// 2 x 4 waves of 128 x 64 (two waves per SIMD, which lets the hardware overlap one wave's LDS and
-// barrier waits with the other's MFMAs at the price of 1.5x the LDS fragment reads).
+// 2 x 4 waves of 128 x 64 is the default (two waves per SIMD, which lets the hardware overlap one
+// wave's LDS, barrier and memory-issue waits with the other's MFMAs at the price of 1.5x the LDS
+// fragment reads); 2 x 2 waves of 128 x 128 (one wave per SIMD, 256 accumulator registers per lane)
+// and 2 x 8 waves of 128 x 32 are selectable.
 template <int NWI_, int NWJ_, int WI_, int WJ_>
 struct Geo {
     static constexpr int NWI = NWI_, NWJ = NWJ_, WI = WI_, WJ = WJ_;
@@ -57,14 +59,12 @@ struct Geo {
     static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
 };
 
-
 // Barrier without the memory fence of __syncthreads; the loops place their own waits before it.
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 }
-
 
 // Requests one K step (64 columns) of a tile with ROWS rows: direct memory -> LDS loads, 16 bytes
 // per lane.  `gwave` is the wave-uniform address of the wave's first row of round 0 (scalar
@@ -175,9 +175,8 @@ __device__ __forceinline__ void load_to_lds_16(const char* gp, char* lp) {
 }
 
 // Scheduling fence: nothing is moved across it.  The K step is written in the order that software-
-// pipelines it (fragments of the next sub-step are requested before the MFMAs of the current one)
-// and the fences keep that order, so the compiler's waits before each MFMA block only cover the
-// fragments that block needs (partial lgkmcnt) while the next sub-step's reads are in flight.
+// pipelines it (fragments of the next sub-step are requested before the MFMAs of the current one,
+// tile requests sit between given MFMAs) and the fences keep that order.
 __device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
 
 // acc += A_tile . B_tile^T over `ktiles` steps of 64.  A / B point at the tile's first row, k = 0.
