@@ -89,7 +89,9 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     p.Mmax = N * T;
     p.Mmax_pad = round_up(p.Mmax, ROW_TILE);
     p.dpad = round_up(d, K_TILE);
-    p.dpadR = round_up(d, 128);
+    // dHidden / dW tile d by 256 when that pads by at most a sixth (full-size tiles beat the padding),
+    // else by 128
+    p.dpadR = (round_up(d, 256) - d) * 6 <= d ? round_up(d, 256) : round_up(d, 128);
     p.Vpad = round_up(V, 256);
     p.ldk = padded_ld(p.dpadR);   // >= dpad; the dW kernel reads whole 128-column tiles of Hc
     p.ldv = padded_ld(p.Vpad);
