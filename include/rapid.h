@@ -9,7 +9,8 @@
  *    given by rapid_workspace_bytes().  `opts` of rapid_iw_pg_loss_fwd_bwd is a HOST pointer.
  *  - All work is enqueued on the caller's HIP stream (`stream` is a hipStream_t passed as
  *    void*; NULL = the default stream).  Calls are asynchronous and never synchronise the
- *    device; outputs are valid once the stream has reached the end of the call's work.
+ *    device; outputs are valid once the stream has reached the end of the call's work.  (The two
+ *    benchmark helpers rapid_profile_read and rapid_mfma_probe wait for their own events.)
  *  - Return value: RAPID_OK or a negative RAPID_ERR_* detected on the host before any launch
  *    (nothing has been enqueued then).  rapid_last_error() gives a thread-local message.
  *  - Errors only the device can see (token id outside [0,V) at an unmasked position, group id
@@ -143,7 +144,8 @@ int rapid_mfma_probe(int random_operands, int iters, double* tflops_out, double*
 /* Workspace sizes in bytes for `op` at the given problem size.  rapid_workspace_bytes is the
  * recommended size (backward row-chunks large enough to fill the chip); rapid_workspace_min_bytes
  * the smallest the call accepts (smaller chunks, same results).  RAPID_OP_GROUP_ADVANTAGE needs
- * none (returns 0).  Returns 0 for invalid arguments. */
+ * none (returns 0).  RAPID_OP_IW_PG_FWD_BWD_CACHED is the size rapid_iw_pg_loss_fwd_bwd needs with
+ * opts->logits_cache = 1 (bf16 only; minimum = recommended).  Returns 0 for invalid arguments. */
 size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype);
 size_t rapid_workspace_min_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype);
 
