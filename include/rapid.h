@@ -198,6 +198,15 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                              size_t workspace_bytes, void* stream);
 
 /*
+ * The parameter update of Alg. 1's inner loop ("update theta with the gradient of Eq. (3)"), for
+ * the LM head alone and as plain gradient descent on the returned loss:
+ *   master[i] -= lr * grad[i]   (fp32, n elements, same layout as dW_out)
+ * and, if w_out != NULL, w_out[i] = the updated weight in `dtype` (the W of the next call).
+ * The optimiser of the paper's experiments (Appendix A) is not part of this library.
+ */
+int rapid_sgd_step(float* master, const float* grad, int64_t n, float lr, void* w_out, int dtype, void* stream);
+
+/*
  * Integer bookkeeping of the padding mask (device outputs, any may be NULL):
  *   seq_len_out [N] int32, cu_seqlen_out [N+1] int32 (exclusive prefix sum, last = M),
  *   row_index_out [N*T] int32: the first M entries are the flat positions n*T+t of the valid

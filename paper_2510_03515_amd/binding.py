@@ -23,7 +23,7 @@ STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LO
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_logprob_fwd",
-           "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe"]
+           "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step"]
 STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
           "dw", "f32_path", "dw_convert"]
 
@@ -81,6 +81,8 @@ def load():
     lib.rapid_profile_read.restype = ci
     lib.rapid_mfma_probe.argtypes = [ci, ci, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
     lib.rapid_mfma_probe.restype = ci
+    lib.rapid_sgd_step.argtypes = [vp, vp, i64, C.c_float, vp, ci, vp]
+    lib.rapid_sgd_step.restype = ci
     _lib = lib
     if os.environ.get("RAPID_WAVES"):      # 4, 8 or 16 waves per contraction workgroup (tuning only)
         lib.rapid_set_tuning(2, int(os.environ["RAPID_WAVES"]))
@@ -126,6 +128,14 @@ def rapid_mfma_probe(random_operands, iters=100000):
     tf, ms = C.c_double(0.0), C.c_double(0.0)
     _check(load().rapid_mfma_probe(int(bool(random_operands)), int(iters), C.byref(tf), C.byref(ms), _stream()))
     return tf.value, ms.value
+
+
+def rapid_sgd_step(master, grad, lr, w_out=None):
+    """master (fp32) -= lr * grad (fp32), and w_out (bf16 or fp32, optional) = the updated weights."""
+    _need(master, torch.float32, "master"); _need(grad, torch.float32, "grad")
+    assert master.numel() == grad.numel() and (w_out is None or w_out.numel() == master.numel())
+    dt = DTYPE_F32 if w_out is None else _dtype_code(w_out)
+    _check(load().rapid_sgd_step(_ptr(master), _ptr(grad), master.numel(), float(lr), _ptr(w_out), dt, _stream()))
 
 
 def rapid_profile_read():

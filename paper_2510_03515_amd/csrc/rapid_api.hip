@@ -350,6 +350,25 @@ int rapid_set_tuning(int key, int value) {
     return RAPID_ERR_DTYPE;
 }
 
+int rapid_sgd_step(float* master, const float* grad, int64_t n, float lr, void* w_out, int dtype, void* stream) {
+    if (!master || !grad) {
+        set_error("master and grad must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    if (n <= 0 || !std::isfinite(lr)) {
+        set_error("n must be > 0 and lr finite");
+        return RAPID_ERR_SHAPE;
+    }
+    if (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) {
+        set_error("unknown dtype %d", dtype);
+        return RAPID_ERR_DTYPE;
+    }
+    int rc = check_arch();
+    if (rc) return rc;
+    launch_sgd_step(master, grad, n, lr, w_out, dtype, (hipStream_t)stream);
+    return check_launch("rapid_sgd_step");
+}
+
 int rapid_mfma_probe(int random_operands, int iters, double* tflops_out, double* ms_out, void* stream) {
     if (iters < 1 || iters > 10000000) {
         set_error("iters must be in 1 .. 10^7");

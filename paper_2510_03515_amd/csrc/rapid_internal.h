@@ -141,6 +141,8 @@ void set_waves_per_workgroup(int n);   // 4, 8 or 16 waves per contraction workg
 void set_cu_count(int n);              // compute units of the device: the contraction kernels launch one workgroup each
 
 
+void launch_sgd_step(float* master, const float* grad, int64_t n, float lr, void* w_out, int dtype, hipStream_t st);
+
 // ---- probe.hip -----------------------------------------------------------------------------------
 int run_mfma_probe(int random_operands, int iters, int num_cu, double* tflops_out, double* ms_out, hipStream_t st);
 

@@ -400,6 +400,26 @@ void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, i
                                                             d * elem_bytes / 4);
 }
 
+// master -= lr * grad; optionally also the updated weights in the contraction dtype
+__global__ void sgd_step_kernel(float* __restrict__ master, const float* __restrict__ grad, int64_t n, float lr,
+                                void* __restrict__ w_out, int dtype) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float w = master[i] - lr * grad[i];
+    master[i] = w;
+    if (w_out) {
+        if (dtype == RAPID_DTYPE_BF16) {
+            const __bf16 r = (__bf16)w;
+            ((bf16_t*)w_out)[i] = __builtin_bit_cast(bf16_t, r);
+        } else {
+            ((float*)w_out)[i] = w;
+        }
+    }
+}
+void launch_sgd_step(float* master, const float* grad, int64_t n, float lr, void* w_out, int dtype, hipStream_t st) {
+    if (n > 0) sgd_step_kernel<<<blocks_for(n, 256), 256, 0, st>>>(master, grad, n, lr, w_out, dtype);
+}
+
 void launch_f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t st) {
     if (n > 0) f32_to_bf16_kernel<<<blocks_for(n, 256), 256, 0, st>>>(src, dst, n);
 }

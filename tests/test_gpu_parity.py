@@ -348,3 +348,35 @@ def test_logits_cache_workspace_and_errors(rb):
         rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"],
                                     g["group_ids"], w["K"], buffers=small, logits_cache=True)
     assert e.value.code == -4
+
+
+def test_inner_loop_on_synthetic_bandit(rb):
+    """Alg. 1's inner loop, H updates on one inference batch: the first step is exactly on-policy,
+    staleness and the estimated reward of the current policy grow, and the last step's outputs
+    still match the oracle evaluated at the weights the loop arrived at."""
+    from paper_2510_03515_amd import iw_grpg as loop
+    spec = wl.small_spec("bandit", "bf16", d=128, V=1000, prompts=8, G=4, len_lo=4, len_hi=24, sigma=0.0,
+                         tokens_from="cur")
+    w, g = _make(spec, seed=1)
+    log, W_end = loop.iw_grpg(g, steps=6, lr=0.02)
+    assert log[0]["staleness"] == 0.0 and log[0]["clip_fraction"] == 0.0 and log[0]["max_abs_s"] == 0.0
+    assert abs(log[0]["loss"]) <= 1e-6                 # complete groups, all weights 1: the advantages cancel
+    st = [r["staleness"] for r in log]
+    assert all(b > a for a, b in zip(st, st[1:])) and st[1] > 0      # grows with the number of inner steps
+    assert log[-1]["is_reward"] > log[0]["is_reward"]
+    # one more evaluation at the final weights against the oracle
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])
+    out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], W_end, g["tokens"], g["mask"], logp_b, g["rewards"],
+                                      g["group_ids"], w["K"], coef_mode=1)
+    torch.cuda.synchronize()
+    H, _, tok, mask = _oracle_inputs(w)
+    ref = orc.iw_pg_loss_fwd_bwd(H, _np(W_end).astype(np.float64), tok, mask, _np(logp_b), _np(w["rewards"]),
+                                 _np(w["group_ids"]), w["K"], coef_mode=1)
+    assert np.abs(_np(out.seq_logratio) - ref["seq_logratio"]).max() <= S_ATOL
+    assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+    # the update itself: fp32 master, bf16 copy
+    m = torch.randn(1000, device="cuda"); gr = torch.randn(1000, device="cuda"); wo = torch.empty(1000, dtype=torch.bfloat16, device="cuda")
+    m0 = m.clone()
+    rb.rapid_sgd_step(m, gr, 0.5, w_out=wo)
+    assert torch.equal(m, m0 - 0.5 * gr) and torch.equal(wo, m.to(torch.bfloat16))
