@@ -147,13 +147,21 @@ __global__ void merge_lse_kernel(const float* __restrict__ part_max, const float
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int M = counts[CNT_M];
     if (j >= M) return;
+    // one pass with a running maximum; slots are merged in slot order, so the result is reproducible.
+    // The weights exp(pm - mx) are fp32 (relative error 1e-7, far below the fp32 rounding of the
+    // partial sums themselves), the accumulation fp64.
     float mx = -INFINITY;
-    for (int p = 0; p < P; ++p) mx = fmaxf(mx, part_max[p * ld_part + j]);
     double acc = 0.0;
     for (int p = 0; p < P; ++p) {
         const float pm = part_max[p * ld_part + j];
         const float ps = part_sum[p * ld_part + j];
-        if (ps > 0.f) acc += (double)ps * exp((double)(pm - mx));
+        if (!(ps > 0.f)) continue;
+        if (pm > mx) {
+            acc = acc * (double)__expf(mx - pm) + (double)ps;   // exp(-inf) = 0 on the first slot
+            mx = pm;
+        } else {
+            acc += (double)ps * (double)__expf(pm - mx);
+        }
     }
     const double lse = (double)mx + log(acc);
     const float lse_f = (float)lse;
