@@ -118,3 +118,26 @@ def test_workload_generator_recipe():
     assert torch.equal(w["tokens"], w2["tokens"]) and torch.equal(w["hidden"], w2["hidden"])
     c = wl.calibrated(wl.CONFIGS[2])
     assert abs(c.sigma - (0.5 / (2048 * 1536)) ** 0.5) < 1e-12
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/rapid.h compiles as C99 with nothing but the standard headers, and a C program that
+    references every declared entry point links against the built library (no compute is run)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    names = _declared()
+    src = tmp_path / "link_check.c"
+    src.write_text('#include "rapid.h"\n#include <stdio.h>\ntypedef void (*fn_t)(void);\nint main(void) {\n  fn_t f[] = {'
+                   + ", ".join(f"(fn_t){n}" for n in names)
+                   + '};\n  printf("%d %d\\n", (int)(sizeof f / sizeof f[0]), rapid_version());\n  return f[0] == 0;\n}\n')
+    lib_dir = os.path.join(ROOT, "paper_2510_03515_amd")
+    exe = tmp_path / "link_check"
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                        "-L", lib_dir, "-l:librapid_hip.so", f"-Wl,-rpath,{lib_dir}", "-o", str(exe)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.split()[0] == str(len(names))
