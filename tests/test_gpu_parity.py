@@ -380,3 +380,19 @@ def test_inner_loop_on_synthetic_bandit(rb):
     m0 = m.clone()
     rb.rapid_sgd_step(m, gr, 0.5, w_out=wo)
     assert torch.equal(m, m0 - 0.5 * gr) and torch.equal(wo, m.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("waves", [4, 16])
+def test_other_workgroup_geometries(rb, waves):
+    """The 4- and 16-wave geometries of the contraction kernels (rapid_set_tuning key 2) compute the
+    same tiles in a different split: same tolerances against the oracle."""
+    print(f"geometry {waves} waves", flush=True)
+    try:
+        rb.rapid_set_tuning(2, waves)
+        for name in ("bf16_small", "bf16_ragged"):
+            w, out, ref = _run_pair(rb, SPECS[name])
+            _check_pair(rb, SPECS[name], out, ref)
+        w, out, ref = _run_pair(rb, SPECS["bf16_ragged"], layout="vd", logits_cache=True)
+        _check_pair(rb, SPECS["bf16_ragged"], out, ref, "vd")
+    finally:
+        rb.rapid_set_tuning(2, 8)
