@@ -396,3 +396,35 @@ def test_other_workgroup_geometries(rb, waves):
         _check_pair(rb, SPECS["bf16_ragged"], out, ref, "vd")
     finally:
         rb.rapid_set_tuning(2, 8)
+
+
+def test_hip_graph_replay_matches_eager(rb):
+    """The fused call only enqueues kernels on the caller's stream (no allocation, no host read of
+    device data, no memset nodes), so it can be captured into a HIP graph; every replay, with eager
+    work in between, gives the bits of the eager call."""
+    spec = SPECS["bf16_ragged"]
+    w, g = _make(spec)
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+    buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"])
+    call = lambda: rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"],
+                                               g["group_ids"], w["K"], buffers=buf)
+    call()
+    torch.cuda.synchronize()
+    ref = {k: getattr(buf, k).clone() for k in ("loss", "dhidden", "dW", "logp_cur", "seq_logratio", "adv")}
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()                                   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for k in ref:                            # eager work between replays: wipe the outputs
+            getattr(buf, k).fill_(float("nan") if getattr(buf, k).is_floating_point() else 0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in ref.items():
+            assert torch.equal(getattr(buf, k), v), (rep, k)
