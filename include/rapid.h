@@ -115,9 +115,9 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
  * keys 10, 11, 12: tile-order blocking (tiles along the first tile dimension that share one tile of
  *        the second before the order moves on) of the logits kernels, the dHidden kernel (0 = all)
  *        and the dW kernel; defaults 4, 0, 2 were measured best on MI355X.  Results are identical.
- * key 13: token-row tiles (of 256 rows) per launch of the forward logits kernel, default 256: the
- *        forward sweeps all of W over one such block of rows at a time so that the block stays in
- *        the memory-side cache.  Results are identical. */
+ * key 13: token-row tiles (of 256 rows) per launch of the two logits kernels (forward and dz),
+ *        default 64: they sweep all of W over one such block of rows at a time so that the block's
+ *        hidden rows stay in the memory-side cache.  Results are identical. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

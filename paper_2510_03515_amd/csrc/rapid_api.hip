@@ -24,7 +24,7 @@ namespace {
 
 int g_gi_fwd = 4, g_gi_dh = 0, g_gi_dw = 2;   // L2 blocking of the tile order (tuning keys 10..12)
 int g_probe_cus = 256;                        // compute units of the current device
-int g_fwd_block_tiles = 256;                  // row tiles per forward launch (tuning key 13)
+int g_fwd_block_tiles = 64;                   // row tiles per launch of the two logits kernels (tuning key 13)
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
 enum Stage { ST_COMPACT = 0, ST_PACK, ST_FWD_LSE, ST_MERGE, ST_ESTIMATOR, ST_ZERO, ST_DZ, ST_DZ_T, ST_DH, ST_DW,
@@ -622,9 +622,20 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
             za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
             za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz; za.gi = g_gi_fwd;
-            {
+            if (cached) {
                 Span sp(ST_DZ, st);
-                if (cached) launch_dz_from_logits(za, st); else launch_dz(za, st);
+                launch_dz_from_logits(za, st);
+            } else {
+                // like the forward, in sub-blocks of rows whose hidden rows stay in the memory-side cache
+                const int64_t sub = (int64_t)g_fwd_block_tiles * 256;
+                for (int64_t r0 = 0; r0 < rows; r0 += sub) {
+                    const int64_t nrows = (rows - r0) < sub ? (rows - r0) : sub;
+                    DzArgs zs = za;
+                    zs.Hc = za.Hc + r0 * p.ldk; zs.dz = za.dz + r0 * p.ldv; zs.m0 = m0 + r0;
+                    zs.tilesM = (int)(nrows / 256);
+                    Span sp(ST_DZ, st);
+                    launch_dz(zs, st);
+                }
             }
             DhArgs ha;
             ha.Wdv = Wdv; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
