@@ -49,7 +49,11 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, unsigned see
 
 int run_mfma_probe(int random_operands, int iters, int num_cu, double* tflops_out, double* ms_out, hipStream_t st) {
     hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return RAPID_ERR_HIP;
+    if (hipEventCreate(&e0) != hipSuccess) return RAPID_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return RAPID_ERR_HIP;
+    }
     const unsigned blocks = (unsigned)num_cu * 2;   // two workgroups of four waves per CU: two waves per SIMD
     const unsigned seed = random_operands ? 7u : 0u;
     mfma_probe_kernel<<<blocks, 256, 0, st>>>(iters / 10 + 1, seed, nullptr);   // warm-up, clocks ramp
