@@ -428,3 +428,50 @@ def test_hip_graph_replay_matches_eager(rb):
         torch.cuda.synchronize()
         for k, v in ref.items():
             assert torch.equal(getattr(buf, k), v), (rep, k)
+
+
+def test_fused_shuffled_groups_mask_holes_and_bad_values(rb):
+    """Groups in arbitrary order with unequal sizes and an empty group, a mask with holes (not just
+    right padding), and non-finite rewards / behaviour log-probs (flagged in dev_status and counted
+    as 0): the fused call against the oracle on the same inputs with the bad values zeroed."""
+    spec = SPECS["bf16_ragged"]
+    w, g = _make(spec, seed=5)
+    rng = np.random.default_rng(11)
+    N, T = w["mask"].shape
+    K = w["K"] + 1                                            # group K-1 stays empty
+    gid = rng.integers(0, K - 1, size=N).astype(np.int32)
+    mask = (w["mask"].numpy() & (rng.random((N, T)) < 0.8)).astype(np.uint8)
+    mask[0, :] = 0
+    mask[0, 5] = 1                                            # a generation with a single, isolated token
+    mask_g = torch.from_numpy(mask).cuda()
+    gid_g = torch.from_numpy(gid).cuda()
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], mask_g)
+    H, W, tok, _ = _oracle_inputs(w)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], mask_g, logp_b, g["rewards"], gid_g, K)
+    torch.cuda.synchronize()
+    ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(w["rewards"]), gid, K)
+    assert out.dev_status.item() == 0
+    assert np.abs(_np(out.seq_logratio) - ref["seq_logratio"]).max() <= S_ATOL
+    assert np.allclose(_np(out.adv), ref["adv"], atol=1e-3)
+    assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    assert _rel(_np(out.dhidden), ref["dH"]) <= GRAD_RTOL["bf16"] and _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+    assert torch.all(out.dhidden[mask_g == 0] == 0)
+    assert out.read_diag()["n_tokens"] == int(mask.sum())
+    # non-finite reward and behaviour log-prob: flagged, treated as 0
+    rewards = g["rewards"].clone()
+    rewards[3] = float("nan")
+    lb = logp_b.clone()
+    n_bad, t_bad = np.argwhere(mask == 1)[7]
+    lb[n_bad, t_bad] = float("inf")
+    out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], mask_g, lb, rewards, gid_g, K)
+    torch.cuda.synchronize()
+    st = out.dev_status.item()
+    assert st & rb.STATUS_NONFINITE_REWARD and st & rb.STATUS_NONFINITE_LOGP
+    r0 = _np(w["rewards"]).copy(); r0[3] = 0.0
+    assert torch.isfinite(out.dW).all() and torch.isfinite(out.loss).all()
+    # the bad log-prob's token contributes a log ratio of 0: same as a behaviour log-prob equal to the current one
+    lb0 = _np(logp_b).copy(); lb0[n_bad, t_bad] = _np(out.logp_cur)[n_bad, t_bad]
+    ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, lb0, r0, gid, K)
+    assert np.abs(_np(out.seq_logratio) - ref["seq_logratio"]).max() <= S_ATOL
+    assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
