@@ -187,7 +187,7 @@ def main():
     # in the backward), timed the same way; reported next to the default, never as `value`.
     if not fwd_only and not args.logits_cache and not args.no_cache_mode:
         need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16)
-        del buf
+        del buf, step          # the default mode's workspace goes back before the larger one is taken
         torch.cuda.empty_cache()
         free, _ = torch.cuda.mem_get_info()
         if need and need + (8 << 30) < free:
