@@ -351,19 +351,19 @@ def test_logits_cache_workspace_and_errors(rb):
 
 
 def test_inner_loop_on_synthetic_bandit(rb):
-    """Alg. 1's inner loop, H updates on one inference batch: the first step is exactly on-policy,
-    staleness and the estimated reward of the current policy grow, and the last step's outputs
-    still match the oracle evaluated at the weights the loop arrived at."""
+    """Alg. 1's inner loop, H mini-batches of one inference batch: the first step is exactly on-policy,
+    staleness grows with the step index, the estimated reward of the policy improves, and a call at
+    the weights the loop arrived at still matches the oracle."""
     from paper_2510_03515_amd import iw_grpg as loop
-    spec = wl.small_spec("bandit", "bf16", d=128, V=1000, prompts=8, G=4, len_lo=4, len_hi=24, sigma=0.0,
+    spec = wl.small_spec("bandit", "bf16", d=128, V=1000, prompts=24, G=4, len_lo=4, len_hi=24, sigma=0.0,
                          tokens_from="cur")
     w, g = _make(spec, seed=1)
-    log, W_end = loop.iw_grpg(g, steps=6, lr=0.02)
+    log, summary, W_end = loop.iw_grpg(g, inner_steps=6, lr=0.05)
     assert log[0]["staleness"] == 0.0 and log[0]["clip_fraction"] == 0.0 and log[0]["max_abs_s"] == 0.0
     assert abs(log[0]["loss"]) <= 1e-6                 # complete groups, all weights 1: the advantages cancel
     st = [r["staleness"] for r in log]
-    assert all(b > a for a, b in zip(st, st[1:])) and st[1] > 0      # grows with the number of inner steps
-    assert log[-1]["is_reward"] > log[0]["is_reward"]
+    assert st[1] > 0 and st[-1] > st[1] and sum(st[3:]) > sum(st[:3])   # grows with the number of inner steps
+    assert summary["reward_final_is_estimate"] > summary["reward_behaviour"]
     # one more evaluation at the final weights against the oracle
     logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])
     out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], W_end, g["tokens"], g["mask"], logp_b, g["rewards"],
