@@ -185,6 +185,8 @@ int rapid_group_advantage(const float* rewards, const int32_t* group_ids, const 
  *   g_n       = -(loss_scale/N) c_n A_n  = d loss / d logp[n,t] for every valid t
  *   dhidden[n,t,:] = g_n (W[:,y] - W p) / temperature  (0 where mask = 0), dtype of hidden
  *   dW        = sum_{valid n,t} outer(hidden[n,t,:], g_n (e_y - p)) / temperature, layout w_layout
+ * logp_behav == NULL means on-policy: every ratio is exactly 1 and the call is the group relative
+ * policy gradient of Sec. 3.3 (Eq. (1) with the advantages of Eq. (2)).
  * Optional outputs (NULL to skip): logp_cur_out, tok_logratio_out [N,T]; seq_logratio_out,
  * adv_out [N]; diag_out.  loss_out [1], dhidden_out [N,T,d] and dW_out are required.
  */

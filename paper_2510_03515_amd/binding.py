@@ -251,7 +251,9 @@ def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group
     dt = _dtype_code(hidden)
     _need(hidden, hidden.dtype, "hidden"); _need(W, hidden.dtype, "W")
     _need(tokens, torch.int32, "tokens"); _need(mask, torch.uint8, "mask")
-    _need(logp_behav, torch.float32, "logp_behav"); _need(rewards, torch.float32, "rewards")
+    if logp_behav is not None:          # None: on-policy (Sec. 3.3), all ratios 1
+        _need(logp_behav, torch.float32, "logp_behav")
+    _need(rewards, torch.float32, "rewards")
     _need(group_ids, torch.int32, "group_ids")
     if buffers is None:
         buffers = IwPgBuffers(hidden, W, K, w_layout)

@@ -519,8 +519,8 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     }
     int rc = validate_common(hidden, W, tokens, mask, d, dtype, o.w_layout, o.temperature, workspace);
     if (rc) return rc;
-    if (!logp_behav || !rewards || !group_ids || !loss_out || !dhidden_out || !dW_out) {
-        set_error("logp_behav, rewards, group_ids, loss_out, dhidden_out and dW_out must not be NULL");
+    if (!rewards || !group_ids || !loss_out || !dhidden_out || !dW_out) {
+        set_error("rewards, group_ids, loss_out, dhidden_out and dW_out must not be NULL");
         return RAPID_ERR_NULL;
     }
     if (o.coef_mode < 0 || o.coef_mode > 1 || o.baseline_mode < 0 || o.baseline_mode > 2 ||

@@ -183,7 +183,7 @@ __global__ void seq_logratio_kernel(const float* __restrict__ logp_cur, const fl
     for (int64_t t = threadIdx.x; t < T; t += WAVE) {
         const int64_t i = n * T + t;
         double dlt = 0.0;
-        if (mask[i] != 0) {
+        if (mask[i] != 0 && logp_behav != nullptr) {   // no behaviour log-probs: on-policy, every ratio is 1
             const float lb = logp_behav[i];
             if (isfinite(lb)) dlt = (double)logp_cur[i] - (double)lb;
             else bad = true;

@@ -266,6 +266,12 @@ def test_on_policy_reduction_exact(rb, name):
                                        g["group_ids"], w["K"])
     torch.cuda.synchronize()
     assert torch.equal(out.dW, out2.dW) and torch.equal(out.dhidden, out2.dhidden)
+    # no behaviour log-probs at all = the on-policy estimator of Sec. 3.3: the same bits
+    out3 = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], None, g["rewards"],
+                                       g["group_ids"], w["K"])
+    torch.cuda.synchronize()
+    for k in ("loss", "dW", "dhidden", "adv", "seq_logratio", "logp_cur"):
+        assert torch.equal(getattr(out3, k), getattr(out, k)), k
 
 
 def test_edge_cases(rb):
