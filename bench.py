@@ -25,27 +25,39 @@ PEAK_HBM = 8.0e12         # B/s
 MEASURED_TRAFFIC_BYTES = {"fwd_lse": 11.9e9 + 0.2e9, "dz": 11.5e9 + 5.1e9, "dh": 57.1e9 + 0.2e9, "dw": 49.8e9 + 1.0e9}
 
 
-def cpu_baseline(w, tokens_per_seq=640):
-    """Oracle (float64 numpy, as it stands) on the first group, generations truncated to
-    `tokens_per_seq` tokens, at the full d and V."""
+def cpu_baseline(w, rb, group=2):
+    """Oracle (float64 numpy, as it stands) on one whole group of the workload at the full d and V: the
+    first group whose rewards are not forced (its 8 generations, every token), timed on this machine's
+    cores.  The same slice also goes through the library as a call of its own, and the oracle's
+    outputs, which are there anyway, give a full-size check of every output element of that call."""
     import numpy as np
     import torch
 
     from oracle import rapid_oracle as orc
     spec = w["spec"]
     G = spec.G
+    group = group if spec.prompts > group else 0
+    n0, n1 = group * G, (group + 1) * G
+    Tm = int(w["lengths"][n0:n1].max().item())
     f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
-    H = f64(w["hidden"][:G, :tokens_per_seq])
-    W = f64(w["W"])
-    tok = w["tokens"][:G, :tokens_per_seq].cpu().numpy()
-    mask = w["mask"][:G, :tokens_per_seq].cpu().numpy()
-    logp_b = f64(w["logp_behav"][:G, :tokens_per_seq])
-    R = f64(w["rewards"][:G])
-    gid = np.zeros(G, np.int64)
+    hid, tok_g, mask_g = w["hidden"][n0:n1, :Tm].contiguous(), w["tokens"][n0:n1, :Tm].contiguous(), w["mask"][n0:n1, :Tm].contiguous()
+    lb_g, rew_g = w["logp_behav"][n0:n1, :Tm].contiguous(), w["rewards"][n0:n1].contiguous()
+    gid_g = torch.zeros(G, dtype=torch.int32, device=hid.device)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(hid, w["W"], tok_g, mask_g, lb_g, rew_g, gid_g, 1, normalized_grads=True)
+    torch.cuda.synchronize()
+    H, W = f64(hid), f64(w["W"])
+    tok, mask = tok_g.cpu().numpy(), mask_g.cpu().numpy()
     n_tok = int(mask.sum())
     t0 = time.perf_counter()
-    orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 1, row_chunk=512)
+    ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, f64(lb_g), f64(rew_g), np.zeros(G, np.int64), 1, normalized_grads=True,
+                                 row_chunk=512)
     dt = time.perf_counter() - t0
+    rel = lambda a, b: float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+    parity = {"loss_rel": abs(out.loss.item() - ref["loss"]) / max(abs(ref["loss"]), 1e-30),
+              "dH_rel": rel(f64(out.dhidden), ref["dH"]), "dW_rel": rel(f64(out.dW), ref["dW"]),
+              "seq_logratio_abs": float(np.abs(f64(out.seq_logratio) - ref["seq_logratio"]).max()),
+              "grad_log_scale_abs": abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]),
+              "tolerances": {"loss_rel": 1e-3, "dH_rel": 2e-2, "dW_rel": 2e-2, "seq_logratio_abs": 1e-3}}
     threads = torch.get_num_threads()
     try:
         import threadpoolctl
@@ -55,9 +67,9 @@ def cpu_baseline(w, tokens_per_seq=640):
     except Exception:
         pass
     return {"value": n_tok / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first group ({G} generations) truncated to {tokens_per_seq} tokens each = {n_tok} "
-                      f"tokens at full d={spec.d}, V={spec.V}; {dt:.1f} s of float64 numpy",
-            "host_cpus": os.cpu_count()}
+            "sample": f"group {group} of the workload, whole ({G} generations, {n_tok} tokens) at full d={spec.d}, "
+                      f"V={spec.V}; {dt:.1f} s of float64 numpy",
+            "host_cpus": os.cpu_count(), "parity_of_the_library_on_this_sample": parity}
 
 
 def main():
@@ -217,7 +229,7 @@ def main():
         else:
             out["logits_cache_mode"] = None
     if not args.no_cpu_baseline and not fwd_only:
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, rb)
     print(json.dumps(out))
 
 
