@@ -169,3 +169,32 @@ def test_one_chunk_twice_bitwise(rb):
             assert torch.equal(outs[0][k], outs[1][k]), (cache, k)
         assert torch.isfinite(outs[0]["dW"]).all() and outs[0]["dW"].abs().max() > 0
         del buf
+
+
+def test_config2_one_group_every_element(rb):
+    """One whole group of the headline workload (8 generations, ~8k tokens) at the full d and V as a call
+    of its own: every element of loss, log-probs, ratios, advantages, dHidden and dW against the oracle."""
+    spec = wl.CONFIGS[2]
+    print("generating", spec.name, flush=True)
+    w = wl.make_workload(spec, seed=0, device="cuda")
+    G, grp = spec.G, 2
+    n0, n1 = grp * G, (grp + 1) * G
+    Tm = int(w["lengths"][n0:n1].max().item())
+    hid, tok, mask = (w[k][n0:n1, :Tm].contiguous() for k in ("hidden", "tokens", "mask"))
+    rew = w["rewards"][n0:n1].contiguous()
+    gid = torch.zeros(G, dtype=torch.int32, device="cuda")
+    logp_b, _ = rb.rapid_logprob_fwd(hid, w["W_old"], tok, mask)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(hid, w["W"], tok, mask, logp_b, rew, gid, 1, normalized_grads=True)
+    torch.cuda.synchronize()
+    print("oracle", flush=True)
+    ref = orc.iw_pg_loss_fwd_bwd(_f64(hid), _f64(w["W"]), tok.cpu().numpy(), mask.cpu().numpy(), _f64(logp_b), _f64(rew),
+                                 np.zeros(G, np.int64), 1, normalized_grads=True, row_chunk=512)
+    rel = lambda a, b: np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+    assert out.dev_status.item() == 0
+    assert np.abs(_f64(out.logp_cur) - ref["logp_cur"]).max() <= 2e-5
+    assert np.abs(_f64(out.seq_logratio) - ref["seq_logratio"]).max() <= 1e-3
+    assert np.abs(_f64(out.adv) - ref["adv"]).max() <= 1e-3
+    assert abs(out.loss.item() - ref["loss"]) <= 1e-3 * abs(ref["loss"])
+    assert abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]) <= 1e-3
+    assert rel(_f64(out.dhidden), ref["dH"]) <= 2e-2 and rel(_f64(out.dW), ref["dW"]) <= 2e-2
+    assert out.read_diag()["n_tokens"] == ref["n_tokens"]
