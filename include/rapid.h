@@ -117,7 +117,10 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
  *        and the dW kernel; defaults 4, 0, 2 were measured best on MI355X.  Results are identical.
  * key 13: token-row tiles (of 256 rows) per launch of the two logits kernels (forward and dz),
  *        default 64: they sweep all of W over one such block of rows at a time so that the block's
- *        hidden rows stay in the memory-side cache.  Results are identical. */
+ *        hidden rows stay in the memory-side cache.  Results are identical.
+ * key 14: 1 (default) / 0: the dHidden kernel reads W from a tile-blocked copy (one contiguous
+ *        32 KiB block per 256-row tile and 64-column step) / from the row-major copy.  Results
+ *        are identical. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

@@ -182,7 +182,8 @@ __device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
 // acc += A_tile . B_tile^T over `ktiles` steps of 64.  A / B point at the tile's first row, k = 0.
 template <class S>
 __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
-                                         int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[S::WI][S::WJ]) {
+                                         int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[S::WI][S::WJ],
+                                         int step_a = 128, int step_b = 128) {
     constexpr int WI = S::WI, WJ = S::WJ;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -248,9 +249,8 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     {
         const uint32_t la = lds_addr(lds) + a_off, lb = lds_addr(lds) + b_off;
         load_frags<WI, WJ>(f0, la + xo[0], lb + xo[0]);
-        const int adv = ktiles > 1 ? 128 : 0;
-        ga += adv;
-        gb += adv;
+        ga += ktiles > 1 ? step_a : 0;
+        gb += ktiles > 1 ? step_b : 0;
         request_first_half<S, RA + RB>(request);   // of tile 1
         // A register that an LDS read (issued from inline assembly) is still writing must not meet
         // a compiler-made copy, and copies appear where control flow splits or joins: every read is
@@ -283,9 +283,8 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         lds_barrier();
         load_frags<WI, WJ>(f0, na + xo[0], nb + xo[0]);
         fence();
-        const int adv = (kt + 2 < ktiles) ? 128 : 0;
-        ga += adv;
-        gb += adv;
+        ga += (kt + 2 < ktiles) ? step_a : 0;
+        gb += (kt + 2 < ktiles) ? step_b : 0;
         dst = cur;
         mma_block_requesting<S, 0, RA + RB>(f1, acc, request);
         fence();
@@ -680,8 +679,12 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
     const TileId t = map_tile(pid, tilesD, tilesM, a.gi > 0 ? a.gi : tilesD);
     if (!t.valid) continue;
     f32x16 acc[WI][WJ];
-    mainloop<S>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv, a.ldv,
-                             a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, (int)(a.Vpad / K_TILE), lds, acc);
+    if (a.WdvB)   // A from the tile-blocked copy: one contiguous 128-byte-row block per K step
+        mainloop<S>(a.WdvB + (int64_t)t.ti * (a.Vpad / K_TILE) * (S::BI * 64), 64,
+                    a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, (int)(a.Vpad / K_TILE), lds, acc, S::BI * 128, 128);
+    else
+        mainloop<S>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv, a.ldv,
+                    a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, (int)(a.Vpad / K_TILE), lds, acc);
     const Lane<S> L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
 #pragma unroll

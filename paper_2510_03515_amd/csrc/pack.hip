@@ -80,6 +80,23 @@ void launch_copy_pad_bf16(const bf16_t* src, int64_t ld_src, const int32_t* row_
                                                          counts, r0, vec_ok);
 }
 
+// Row-major [R, ld] (R multiple of RB, C multiple of 64) -> tile-blocked: block (rt, kt) holds rows
+// rt*RB .. +RB, columns kt*64 .. +64 as RB contiguous 128-byte rows; blocks ordered (rt, kt).
+__global__ void block_rows_bf16_kernel(const bf16_t* __restrict__ src, int64_t ld, bf16_t* __restrict__ dst, int RB,
+                                       int64_t KT) {
+    const int64_t rt = blockIdx.y, kt = blockIdx.x;
+    const bf16_t* s = src + rt * RB * ld + kt * 64;
+    bf16_t* d = dst + (rt * KT + kt) * RB * 64;
+    for (int c = threadIdx.x; c < RB * 8; c += blockDim.x) {
+        const int r = c >> 3, q = c & 7;
+        *(uint4*)(d + r * 64 + q * 8) = *(const uint4*)(s + (int64_t)r * ld + q * 8);
+    }
+}
+void launch_block_rows_bf16(const bf16_t* src, int64_t ld, bf16_t* dst, int64_t R, int64_t C, int RB, hipStream_t st) {
+    dim3 grid((unsigned)(C / 64), (unsigned)(R / RB));
+    block_rows_bf16_kernel<<<grid, 256, 0, st>>>(src, ld, dst, RB, C / 64);
+}
+
 void launch_transpose_pad_bf16(const bf16_t* src, int64_t ld_src, bf16_t* dst, int64_t ld_dst, int64_t R,
                                int64_t C, int64_t Rpad, int64_t Cpad, const int32_t* counts, int64_t r0,
                                hipStream_t st) {

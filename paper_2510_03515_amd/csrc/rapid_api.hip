@@ -23,6 +23,7 @@ namespace {
 
 
 int g_gi_fwd = 4, g_gi_dh = 0, g_gi_dw = 2;   // L2 blocking of the tile order (tuning keys 10..12)
+int g_blocked_wdv = 1;                        // dH reads W from a tile-blocked copy (tuning key 14)
 int g_probe_cus = 256;                        // compute units of the current device
 int g_fwd_block_tiles = 64;                   // row tiles per launch of the two logits kernels (tuning key 13)
 
@@ -67,7 +68,7 @@ struct Plan {
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
-    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, logp_tmp, s64, s32, adv, g, Hc, Wvd, Wdv,
+    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, logp_tmp, s64, s32, adv, g, Hc, Wvd, Wdv, WdvB,
         part_max, part_sum, dw32, chunk0;
 };
 
@@ -121,6 +122,7 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
         p.part_sum = take(cur, (size_t)p.P * p.Mmax_pad * 4);
         if (bwd) {
             p.Wdv = take(cur, (size_t)p.dpadR * p.ldv * 2);
+            p.WdvB = take(cur, (size_t)p.dpadR * p.Vpad * 2);
             p.per_row = (size_t)p.ldv * 2;   // the dz chunk
         }
     } else {
@@ -335,6 +337,10 @@ int rapid_set_tuning(int key, int value) {
     }
     if (key == 13 && value >= 1 && value <= (1 << 20)) {
         g_fwd_block_tiles = value;
+        return RAPID_OK;
+    }
+    if (key == 14 && (value == 0 || value == 1)) {
+        g_blocked_wdv = value;
         return RAPID_OK;
     }
     if (key == 2 && (value == 4 || value == 8 || value == 16)) {
@@ -610,6 +616,8 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             else
                 launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.ldv, p.V, p.d, p.Vpad, p.dpadR, nullptr,
                                           0, st);
+            if (g_blocked_wdv)
+                launch_block_rows_bf16(Wdv, p.ldv, at<bf16_t>(ws, p.WdvB), p.dpadR, p.Vpad, p.dpadR % 256 == 0 ? 256 : 128, st);
         }
         // with cached logits the chunk buffer holds every row and the backward walks it in blocks
         const int64_t step = cached ? (recommended_chunk(p) < p.Mc ? recommended_chunk(p) : p.Mc) : p.Mc;
@@ -638,7 +646,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                 }
             }
             DhArgs ha;
-            ha.Wdv = Wdv; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
+            ha.Wdv = Wdv; ha.WdvB = g_blocked_wdv ? at<bf16_t>(ws, p.WdvB) : nullptr; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
             ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
             ha.dhidden = (bf16_t*)dhidden_out; ha.gi = g_gi_dh;
             {

@@ -59,6 +59,7 @@ void launch_copy_pad_bf16(const bf16_t* src, int64_t ld_src, const int32_t* row_
                           int64_t ld_dst, int64_t R, int64_t C, int64_t Rpad, int64_t Cpad,
                           const int32_t* counts, int64_t r0, hipStream_t st);
 // dst[c][r] (ld_dst) = src[r][c] for r < R, c < C else 0, over r < Rpad, c < Cpad.
+void launch_block_rows_bf16(const bf16_t* src, int64_t ld, bf16_t* dst, int64_t R, int64_t C, int RB, hipStream_t st);
 void launch_transpose_pad_bf16(const bf16_t* src, int64_t ld_src, bf16_t* dst, int64_t ld_dst, int64_t R,
                                int64_t C, int64_t Rpad, int64_t Cpad, const int32_t* counts, int64_t r0,
                                hipStream_t st);
@@ -110,6 +111,7 @@ void launch_dz_from_logits(const DzArgs& a, hipStream_t st);
 
 struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const bf16_t* Wdv;    // [dpadR, Vpad]
+    const bf16_t* WdvB;   // the same, tile-blocked (blocks of tile-rows x 64 columns), or NULL
     const bf16_t* dz;     // [Mc, Vpad]
     int64_t Vpad;         // contraction extent
     int64_t ldv;          // leading dimension of Wdv and dz

@@ -404,6 +404,18 @@ def test_other_workgroup_geometries(rb, waves):
         rb.rapid_set_tuning(2, 8)
 
 
+def test_row_major_w_for_dhidden(rb):
+    """Tuning key 14 = 0: dHidden from the row-major copy of W instead of the tile-blocked one: same bits."""
+    spec = SPECS["bf16_ragged"]
+    w, out, ref = _run_pair(rb, spec)
+    try:
+        rb.rapid_set_tuning(14, 0)
+        w2, out2, _ = _run_pair(rb, spec)
+    finally:
+        rb.rapid_set_tuning(14, 1)
+    assert torch.equal(out.dhidden, out2.dhidden) and torch.equal(out.dW, out2.dW)
+
+
 def test_hip_graph_replay_matches_eager(rb):
     """The fused call only enqueues kernels on the caller's stream (no allocation, no host read of
     device data, no memset nodes), so it can be captured into a HIP graph; every replay, with eager
