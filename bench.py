@@ -22,7 +22,7 @@ PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
 PEAK_HBM = 8.0e12         # B/s
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled (see the profile named in the output), of one full launch:
 # 16384 token rows for the two logits kernels, 65536 for dH and dW
-MEASURED_TRAFFIC_BYTES = {"fwd_lse": 11.9e9 + 0.2e9, "dz": 11.5e9 + 5.1e9, "dh": 57.1e9 + 0.2e9, "dw": 49.8e9 + 1.0e9}
+MEASURED_TRAFFIC_BYTES = {"fwd_lse": 11.8e9 + 0.2e9, "dz": 11.5e9 + 5.1e9, "dh": 62.6e9 + 0.2e9, "dw": 49.7e9 + 1.0e9}
 
 
 def cpu_baseline(w, rb, group=2):
