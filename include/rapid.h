@@ -48,6 +48,9 @@ extern "C" {
 #define RAPID_STATUS_BAD_GROUP 2
 #define RAPID_STATUS_NONFINITE_REWARD 4
 #define RAPID_STATUS_NONFINITE_LOGP 8
+#define RAPID_STATUS_LOGIT_RANGE 16 /* logits_cache = 1 only: in some row the sampled token is more than e^79 times
+                                       less likely than the most likely one; loss and log-probs are exact, that
+                                       row's share of dhidden and dW is truncated */
 
 /* enums */
 #define RAPID_DTYPE_F32 0
@@ -78,11 +81,13 @@ typedef struct rapid_iw_pg_opts {
                               ratios that underflow fp32 still give usable gradients */
     int logits_cache;      /* 0 (default): the backward regenerates the logits tile by tile from hidden and W;
                               nothing of size rows x V outlives a row chunk.  1 (bf16 inputs only): the
-                              forward also stores the logits (bf16) of every row in the workspace and the
-                              backward turns them into dz in place instead of recomputing them: one
-                              contraction fewer, for N*T*V*2 more bytes of workspace (size:
-                              rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...)) and logits rounded
-                              to bf16 before the softmax is regenerated */
+                              forward also stores, in the workspace, the ratio p_v / p_y (bf16) of every
+                              vocabulary entry's probability to that of the row's sampled token, and the
+                              backward contracts those directly (dz = -g p_y (ratio - onehot / p_y)): one
+                              contraction fewer and no pass over rows x V in between, for N*T*V*2 more
+                              bytes of workspace (rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...)).
+                              Same single bf16 rounding per element of the rows x V intermediate as
+                              mode 0; see RAPID_STATUS_LOGIT_RANGE for its one limit */
     const float* coef_override; /* DEVICE [N] or NULL: use these per-generation coefficients g_n
                               = dLoss/dlogp_{n,t} instead of the estimator's (loss = sum g_n) */
 } rapid_iw_pg_opts;
@@ -120,7 +125,11 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
  *        hidden rows stay in the memory-side cache.  Results are identical.
  * key 14: 1 (default) / 0: the dHidden kernel reads W from a tile-blocked copy (one contiguous
  *        32 KiB block per 256-row tile and 64-column step) / from the row-major copy.  Results
- *        are identical. */
+ *        are identical.
+ * key 15: with logits_cache = 1, token-row tiles (of 256 rows) per launch of the dHidden and dW
+ *        kernels, default 256 (0 = all rows in one launch; multiples of 128 fill whole rounds of
+ *        workgroups).  dW sums over the launches in a fixed order, so results depend on it only
+ *        through fp32 rounding. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

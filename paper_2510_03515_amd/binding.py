@@ -19,7 +19,7 @@ RAPID_OK = 0
 DTYPE_F32, DTYPE_BF16 = 0, 1
 W_DV, W_VD = 0, 1
 OP_LOGPROB_FWD, OP_GROUP_ADVANTAGE, OP_IW_PG_FWD_BWD, OP_IW_PG_FWD_BWD_CACHED = 0, 1, 2, 3
-STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LOGP = 1, 2, 4, 8
+STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LOGP, STATUS_LOGIT_RANGE = 1, 2, 4, 8, 16
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_logprob_fwd",

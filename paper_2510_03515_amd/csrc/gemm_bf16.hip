@@ -561,12 +561,17 @@ __device__ __forceinline__ void store_tile_through_lds(char* lds, const Lane<S>&
 }
 
 // ------------------------------------------------------------------------------------- fwd_lse
-// STORE: also keep the tile's logits (bf16, before the temperature) in a.zc for a backward that reloads them.
+// STORE: also keep, for a backward that reloads them instead of recomputing the logits, the tile's
+// probability ratios u[j][v] = exp(z[j][v] - r[j]) in bf16 in a.zc.  The reference r[j] is the logit
+// of the row's sampled token (a.zy, known before the sweep), so u = p_v / p_y whatever the row's
+// log-sum-exp turns out to be, and the backward needs one factor per row, -g p_y, instead of a pass
+// over the stored tile.  The exponent is clamped at 2^115 (a sampled token e^-79 times less likely
+// than the row's most likely one); a clamp sets RAPID_STATUS_LOGIT_RANGE.
 template <class S, bool STORE>
 __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
-    const int Mr = a.counts[CNT_MR];
+    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.row0 >= Mr) return;
     // the order (and with it the split over the XCDs) covers the row tiles that hold tokens only
     const int tilesM = min(a.tilesM, (int)((Mr - a.row0 + S::BJ - 1) / S::BJ));
@@ -577,16 +582,9 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     f32x16 acc[WI][WJ];
     mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk, a.Hc + j_tile * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds,
                 acc);
-    if (STORE) {
-        __syncthreads();   // every wave is done with both stages
-        const Lane<S> Ls;
-        store_tile_through_lds<S>(lds, Ls,
-                                  a.zc + (j_tile + Ls.wave_j * (WJ * 32)) * a.ldz + (int64_t)t.ti * S::BI + Ls.wave_i * (WI * 32),
-                                  a.ldz, [&](int ib, int jb, int v) { return acc[ib][jb][v]; });
-    }
     // Epilogue: per token row j (one lane pair) the max and the sum of exponentials over this wave's
     // 128 vocabulary columns.  The logit of the sampled token is gathered by a separate small kernel,
-    // so the per-element work is one max, one fma, one exp and one add.
+    // so the per-element work is one max, one fma, one exp and one add (STORE: and one multiply).
     const Lane<S> L;
     const int i_base = t.ti * S::BI + L.wave_i * (WI * 32);
     const int n_valid = (int)a.V - i_base;          // columns of this wave that exist (>= 128: all)
@@ -603,25 +601,54 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
                     acc[ib][jb][v] = rel < n_valid ? acc[ib][jb][v] : -INFINITY;
                 }
     }
+    float m[WJ], nm[WJ], l[WJ];
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[ib][jb][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        m[jb] = mx;
+        nm[jb] = (mx == -INFINITY) ? 0.f : -mx * zs;
+        l[jb] = 0.f;
+    }
+    if (STORE) {
+        float f[WJ];   // exp(wave maximum - reference): turns exp(z - maximum) into exp(z - reference)
+        bool clamped = false;
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb) {
+            const int64_t j = j_tile + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
+            const float r2 = j < M ? a.zy[j] * LOG2E : 0.f;   // rows past the last token: zero logits
+            float e2 = m[jb] * zs - r2;                        // -inf for a wave of padding columns only
+            if (e2 > 115.f) { e2 = 115.f; clamped = true; }
+            f[jb] = __builtin_amdgcn_exp2f(e2);
+        }
+        if (clamped && a.dev_status) atomicOr(a.dev_status, RAPID_STATUS_LOGIT_RANGE);
+        __syncthreads();   // every wave is done with both stages
+        store_tile_through_lds<S>(lds, L,
+                                  a.zc + (j_tile + L.wave_j * (WJ * 32)) * a.ldz + (int64_t)t.ti * S::BI + L.wave_i * (WI * 32),
+                                  a.ldz, [&](int ib, int jb, int v) {
+                                      const float e = __builtin_amdgcn_exp2f(fmaf(acc[ib][jb][v], zs, nm[jb]));
+                                      l[jb] += e;
+                                      return e * f[jb];
+                                  });
+    } else {
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb)
+#pragma unroll
+            for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) l[jb] += __builtin_amdgcn_exp2f(fmaf(acc[ib][jb][v], zs, nm[jb]));
+    }
 #pragma unroll
     for (int jb = 0; jb < WJ; ++jb) {
         const int64_t j = j_tile + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
-        float m = -INFINITY;
-#pragma unroll
-        for (int ib = 0; ib < WI; ++ib)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) m = fmaxf(m, acc[ib][jb][v]);
-        m = fmaxf(m, __shfl_xor(m, 32, 64));
-        const float nm = (m == -INFINITY) ? 0.f : -m * zs;
-        float l = 0.f;
-#pragma unroll
-        for (int ib = 0; ib < WI; ++ib)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) l += __builtin_amdgcn_exp2f(fmaf(acc[ib][jb][v], zs, nm));
-        l += __shfl_xor(l, 32, 64);
+        const float ls = l[jb] + __shfl_xor(l[jb], 32, 64);
         if (L.hi == 0) {
-            a.part_max[slot * a.ld_part + j] = m * a.inv_temp;
-            a.part_sum[slot * a.ld_part + j] = l;
+            a.part_max[slot * a.ld_part + j] = m[jb] * a.inv_temp;
+            a.part_sum[slot * a.ld_part + j] = ls;
         }
     }
     }
@@ -692,14 +719,15 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
         const int64_t j = a.m0 + (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
         if (j >= M) continue;
         bf16_t* out = a.dhidden + (int64_t)a.row_index[j] * a.d;
+        const float cj = a.rowc ? a.rowc[j] : 1.f;   // cached ratios: the row's -g p_y / temperature
 #pragma unroll
         for (int ib = 0; ib < WI; ++ib)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int64_t i0 = i_base + ib * 32 + q * 8 + L.hi * 4;
                 if (i0 < a.d)
-                    *(uint2*)(out + i0) = pack_bf16x4(acc[ib][jb][q * 4], acc[ib][jb][q * 4 + 1],
-                                                      acc[ib][jb][q * 4 + 2], acc[ib][jb][q * 4 + 3]);
+                    *(uint2*)(out + i0) = pack_bf16x4(cj * acc[ib][jb][q * 4], cj * acc[ib][jb][q * 4 + 1],
+                                                      cj * acc[ib][jb][q * 4 + 2], cj * acc[ib][jb][q * 4 + 3]);
             }
     }
     }
@@ -795,40 +823,49 @@ __global__ void token_onehot_kernel(bf16_t* __restrict__ dz, int64_t ldz, int64_
     *p = __builtin_bit_cast(bf16_t, r);
 }
 
-// dz from cached logits, in place: one workgroup per token row of the block.
-// dz[v] = g (onehot_y[v] - exp(z[v] / temperature - lse)) / temperature; rows past the last token give 0.
-__global__ __launch_bounds__(256) void dz_from_logits_kernel(bf16_t* __restrict__ zc, int64_t ldz, int64_t m0, int64_t Vpad,
-                                                             const int32_t* __restrict__ tokc,
-                                                             const int32_t* __restrict__ seqc,
-                                                             const float* __restrict__ lse_c, const float* __restrict__ g,
-                                                             float inv_temp, const int32_t* __restrict__ counts) {
-    const int64_t j = m0 + blockIdx.x;
+// After a forward that stored the ratios u = p_v / p_y (see fwd_lse_kernel), with lse and g known:
+// dz[j][v] = (g_j / temperature) (onehot_y[v] - p_v) = c_j u'[j][v], with the row factor
+// c_j = -(g_j / temperature) p_y and u' = u except u'[j][y] = 1 - 1 / p_y.  One wave per token row
+// writes c_j (0 past the last token), replaces that one element, and scales the row of the packed
+// hidden copy by c_j: dW contracts over token rows, so there the factor has to sit on an operand
+// (dHidden applies it to its accumulators).  1 / p_y is clamped at e^80 (sets
+// RAPID_STATUS_LOGIT_RANGE: such a row's gradient is truncated).
+__global__ __launch_bounds__(256) void cache_finish_kernel(bf16_t* __restrict__ u, int64_t ldz, bf16_t* __restrict__ Hc,
+                                                           int64_t ldk, const int32_t* __restrict__ tokc,
+                                                           const int32_t* __restrict__ seqc, const float* __restrict__ zy,
+                                                           const float* __restrict__ lse_c, const float* __restrict__ g,
+                                                           float inv_temp, const int32_t* __restrict__ counts,
+                                                           float* __restrict__ rowc, int32_t* __restrict__ dev_status) {
+    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     const int M = counts[CNT_M], Mr = counts[CNT_MR];
     if (j >= Mr) return;
-    const bool live = j < M;
-    const float gj = live ? g[seqc[j]] * inv_temp : 0.f;
-    const float nlse = live ? -lse_c[j] * LOG2E : 0.f;
-    const int tok = live ? tokc[j] : -1;
-    const float zs = inv_temp * LOG2E;
-    uint4* row = (uint4*)(zc + (int64_t)blockIdx.x * ldz);
-    for (int c = threadIdx.x; c < Vpad / 8; c += 256) {
-        const u32x4 in = __builtin_nontemporal_load((const u32x4*)(row + c));
+    float c = 0.f;
+    if (j < M) {
+        float nlp = lse_c[j] - zy[j];   // -log p_y
+        c = -g[seqc[j]] * inv_temp * __expf(-nlp);
+        if (lane == 0) {
+            if (nlp > 80.f) {
+                nlp = 80.f;
+                if (dev_status) atomicOr(dev_status, RAPID_STATUS_LOGIT_RANGE);
+            }
+            const __bf16 r = (__bf16)(-expm1f(nlp));
+            u[j * ldz + tokc[j]] = __builtin_bit_cast(bf16_t, r);
+        }
+    }
+    if (lane == 0) rowc[j] = c;
+    uint4* row = (uint4*)(Hc + j * ldk);
+    for (int c8 = lane; c8 < ldk / 8; c8 += 64) {
+        const uint4 in = row[c8];
+        const uint32_t w[4] = {in.x, in.y, in.z, in.w};
         float o[8];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float lo = __builtin_bit_cast(float, in[e] << 16), hi = __builtin_bit_cast(float, in[e] & 0xffff0000u);
-            o[2 * e] = -gj * __builtin_amdgcn_exp2f(fmaf(lo, zs, nlse));
-            o[2 * e + 1] = -gj * __builtin_amdgcn_exp2f(fmaf(hi, zs, nlse));
-        }
-        const int rel = tok - c * 8;
-        if (rel >= 0 && rel < 8) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] += (e == rel) ? gj : 0.f;
+            o[2 * e] = c * __builtin_bit_cast(float, w[e] << 16);
+            o[2 * e + 1] = c * __builtin_bit_cast(float, w[e] & 0xffff0000u);
         }
         const uint2 a0 = pack_bf16x4(o[0], o[1], o[2], o[3]), a1 = pack_bf16x4(o[4], o[5], o[6], o[7]);
-        u32x4 out;
-        out[0] = a0.x; out[1] = a0.y; out[2] = a1.x; out[3] = a1.y;
-        __builtin_nontemporal_store(out, (u32x4*)(row + c));
+        row[c8] = make_uint4(a0.x, a0.y, a1.x, a1.y);
     }
 }
 
@@ -897,12 +934,12 @@ void launch_dz(const DzArgs& a, hipStream_t st) {
                                                                       a.inv_temp, a.counts);
 }
 
-void launch_dz_from_logits(const DzArgs& a, hipStream_t st) {
-    const int64_t rows = (int64_t)a.tilesM * 256;
-    dz_from_logits_kernel<<<(unsigned)rows, 256, 0, st>>>(a.dz, a.ldz, a.m0, a.Vpad, a.tokc, a.seqc, a.lse_c, a.g,
-                                                       a.inv_temp, a.counts);
+void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc, const int32_t* seqc,
+                         const float* zy, const float* lse_c, const float* g, float inv_temp, const int32_t* counts,
+                         int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st) {
+    cache_finish_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(u, ldz, Hc, ldk, tokc, seqc, zy, lse_c, g,
+                                                                        inv_temp, counts, rowc, dev_status);
 }
-
 void launch_dh(const DhArgs& a, hipStream_t st) {
     if (a.dpadR % 256 == 0) {
         if (g_waves == 16) launch_dh_t<G16>(a, st); else if (g_waves == 8) launch_dh_t<G8>(a, st); else launch_dh_t<G4>(a, st);

@@ -25,6 +25,7 @@ namespace {
 int g_gi_fwd = 4, g_gi_dh = 0, g_gi_dw = 2;   // L2 blocking of the tile order (tuning keys 10..12)
 int g_blocked_wdv = 1;                        // dH reads W from a tile-blocked copy (tuning key 14)
 int g_probe_cus = 256;                        // compute units of the current device
+int g_cached_step_tiles = 256;                // row tiles per dHidden / dW launch with the cache (tuning key 15; 0 = all rows)
 int g_fwd_block_tiles = 64;                   // row tiles per launch of the two logits kernels (tuning key 13)
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
@@ -68,7 +69,7 @@ struct Plan {
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
-    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, logp_tmp, s64, s32, adv, g, Hc, Wvd, Wdv, WdvB,
+    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, rowc, logp_tmp, s64, s32, adv, g, Hc, Wvd, Wdv, WdvB,
         part_max, part_sum, dw32, chunk0;
 };
 
@@ -108,6 +109,7 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     p.zy = take(cur, (size_t)p.Mmax_pad * 4);
     p.lse_c = take(cur, (size_t)p.Mmax_pad * 4);
     if (bwd) {
+        p.rowc = take(cur, (size_t)p.Mmax_pad * 4);
         p.logp_tmp = take(cur, (size_t)p.Mmax * 4);
         p.s64 = take(cur, (size_t)N * 8);
         p.s32 = take(cur, (size_t)N * 4);
@@ -198,7 +200,7 @@ struct FwdIo {
     const void* hidden; const void* W; const int32_t* tokens; const uint8_t* mask;
     int w_layout; float temperature;
     float* logp_out; float* lse_out; int32_t* dev_status;
-    bf16_t* zc = nullptr;   // if set: [Mmax_pad, ldv], the forward also stores the logits there
+    bf16_t* zc = nullptr;   // if set: [Mmax_pad, ldv], the forward also stores the ratios p_v / p_y there
 };
 
 // compaction, operand packing and the streaming log-softmax forward; leaves lse_c, tokc, seqc,
@@ -237,7 +239,11 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
         a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
         a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy); a.gi = g_gi_fwd;
-        a.zc = io.zc; a.ldz = p.ldv;
+        a.zc = io.zc; a.ldz = p.ldv; a.dev_status = io.dev_status;
+        {   // the sampled tokens' logits first: a storing forward uses them as its per-row reference
+            Span sp(ST_MERGE, st);
+            launch_token_logit(a, p.Mmax_pad, st);
+        }
         // The forward runs in blocks of token rows, all vocabulary tiles per block, so that a block's
         // hidden rows stay in the memory-side cache while every XCD sweeps its share of W over them
         // (one launch over all rows re-reads the hidden rows from HBM once per group of W panels).
@@ -251,7 +257,6 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         }
         {
             Span sp(ST_MERGE, st);
-            launch_token_logit(a, p.Mmax_pad, st);
             launch_merge_lse(a.part_max, a.part_sum, p.P, a.ld_part, a.zy, row_index, counts, p.Mmax_pad, lse_c,
                              io.logp_out, io.lse_out, st);
         }
@@ -310,7 +315,7 @@ using namespace rapid;
 
 extern "C" {
 
-int rapid_version(void) { return 2; }
+int rapid_version(void) { return 3; }
 
 const char* rapid_last_error(void) { return g_err; }
 
@@ -337,6 +342,10 @@ int rapid_set_tuning(int key, int value) {
     }
     if (key == 13 && value >= 1 && value <= (1 << 20)) {
         g_fwd_block_tiles = value;
+        return RAPID_OK;
+    }
+    if (key == 15 && value >= 0 && value <= (1 << 20)) {
+        g_cached_step_tiles = value;
         return RAPID_OK;
     }
     if (key == 14 && (value == 0 || value == 1)) {
@@ -619,8 +628,16 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             if (g_blocked_wdv)
                 launch_block_rows_bf16(Wdv, p.ldv, at<bf16_t>(ws, p.WdvB), p.dpadR, p.Vpad, p.dpadR % 256 == 0 ? 256 : 128, st);
         }
-        // with cached logits the chunk buffer holds every row and the backward walks it in blocks
-        const int64_t step = cached ? (recommended_chunk(p) < p.Mc ? recommended_chunk(p) : p.Mc) : p.Mc;
+        // With the cache the chunk buffer holds every row's ratios p_v / p_y; one small pass makes
+        // them the backward's operands (row factors, the sampled tokens' elements, scaled hidden
+        // rows) and the backward walks the buffer in blocks.
+        if (cached) {
+            Span sp(ST_DZ, st);
+            launch_cache_finish(at<bf16_t>(ws, p.chunk0), p.ldv, Hc, p.ldk, tokc, seqc, at<float>(ws, p.zy), lse_c, g,
+                                inv_temp, counts, p.Mmax_pad, at<float>(ws, p.rowc), dev_status, st);
+        }
+        const int64_t cstep = g_cached_step_tiles > 0 ? (int64_t)g_cached_step_tiles * ROW_TILE : p.Mc;
+        const int64_t step = cached ? (cstep < p.Mc ? cstep : p.Mc) : p.Mc;
         int chunk = 0;
         for (int64_t m0 = 0; m0 < p.Mmax_pad; m0 += step, ++chunk) {
             const int64_t rows = (p.Mmax_pad - m0) < step ? (p.Mmax_pad - m0) : step;   // multiple of 256
@@ -630,10 +647,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
             za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
             za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz; za.gi = g_gi_fwd;
-            if (cached) {
-                Span sp(ST_DZ, st);
-                launch_dz_from_logits(za, st);
-            } else {
+            if (!cached) {
                 // like the forward, in sub-blocks of rows whose hidden rows stay in the memory-side cache
                 const int64_t sub = (int64_t)g_fwd_block_tiles * 256;
                 for (int64_t r0 = 0; r0 < rows; r0 += sub) {
@@ -648,6 +662,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             DhArgs ha;
             ha.Wdv = Wdv; ha.WdvB = g_blocked_wdv ? at<bf16_t>(ws, p.WdvB) : nullptr; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
             ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
+            ha.rowc = cached ? at<float>(ws, p.rowc) : nullptr;
             ha.dhidden = (bf16_t*)dhidden_out; ha.gi = g_gi_dh;
             {
                 Span sp(ST_DH, st);

@@ -81,8 +81,9 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     int64_t ld_part;
     float* zy;            // [Mmax_pad]
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
-    bf16_t* zc;           // NULL, or [Mmax_pad, ldz]: the kernel also stores the logits (before the temperature)
+    bf16_t* zc;           // NULL, or [Mmax_pad, ldz]: the kernel also stores exp(logit - zy[row]) there; zy must be set
     int64_t ldz;
+    int32_t* dev_status;  // may be NULL
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
 void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st);   // zy for all rows
@@ -106,8 +107,11 @@ struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, b
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_dz(const DzArgs& a, hipStream_t st);
-// dz in place from logits the forward stored in a.dz (rows m0 .. of the chunk buffer); uses the row fields of `a` only
-void launch_dz_from_logits(const DzArgs& a, hipStream_t st);
+// turns the ratios a storing forward left in u [rows_max, ldz] into the backward's operands: the
+// sampled token's element of each row, the row factors rowc [rows_max], and Hc scaled by them in place
+void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc, const int32_t* seqc,
+                         const float* zy, const float* lse_c, const float* g, float inv_temp, const int32_t* counts,
+                         int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st);
 
 struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const bf16_t* Wdv;    // [dpadR, Vpad]
@@ -120,6 +124,7 @@ struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     int64_t m0;
     const int32_t* row_index;
     const int32_t* counts;
+    const float* rowc;    // NULL, or one factor per compact row applied to the result
     bf16_t* dhidden;      // [N*T, d]
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };

@@ -1,7 +1,7 @@
 """Full-size parity of the Qwen2.5-shaped workloads (configs 1, 2, 3; config 2 is the launch
 configuration bench.py times: d=1536, V=151936, 256 generations, ~300k response tokens,
 recommended workspace), on sampled outputs the oracle can compute one by one and on properties that
-hold at any size; config 1 also with the opt-in logits cache.  Also the forward-only behaviour pass
+hold at any size; configs 1 and 2 also with the opt-in logits cache.  Also the forward-only behaviour pass
 of config 4 on sampled rows."""
 import math
 
@@ -33,7 +33,7 @@ def _row_oracle(w, W64, n, t):
     return lp[0, 0], lse[0, 0]
 
 
-@pytest.mark.parametrize("cfg,cache", [(2, False), (1, False), (1, True), (3, False)])
+@pytest.mark.parametrize("cfg,cache", [(2, False), (2, True), (1, False), (1, True), (3, False)])
 def test_full_size_sampled_parity(rb, cfg, cache):
     spec = wl.CONFIGS[cfg]
     print("generating", spec.name, "logits_cache" if cache else "", flush=True)
@@ -173,7 +173,8 @@ def test_one_chunk_twice_bitwise(rb):
 
 def test_config2_one_group_every_element(rb):
     """One whole group of the headline workload (8 generations, ~8k tokens) at the full d and V as a call
-    of its own: every element of loss, log-probs, ratios, advantages, dHidden and dW against the oracle."""
+    of its own: every element of loss, log-probs, ratios, advantages, dHidden and dW against the oracle,
+    in both backward modes."""
     spec = wl.CONFIGS[2]
     print("generating", spec.name, flush=True)
     w = wl.make_workload(spec, seed=0, device="cuda")
@@ -184,17 +185,19 @@ def test_config2_one_group_every_element(rb):
     rew = w["rewards"][n0:n1].contiguous()
     gid = torch.zeros(G, dtype=torch.int32, device="cuda")
     logp_b, _ = rb.rapid_logprob_fwd(hid, w["W_old"], tok, mask)
-    out = rb.rapid_iw_pg_loss_fwd_bwd(hid, w["W"], tok, mask, logp_b, rew, gid, 1, normalized_grads=True)
+    outs = [rb.rapid_iw_pg_loss_fwd_bwd(hid, w["W"], tok, mask, logp_b, rew, gid, 1, normalized_grads=True,
+                                        logits_cache=cache) for cache in (False, True)]
     torch.cuda.synchronize()
     print("oracle", flush=True)
     ref = orc.iw_pg_loss_fwd_bwd(_f64(hid), _f64(w["W"]), tok.cpu().numpy(), mask.cpu().numpy(), _f64(logp_b), _f64(rew),
                                  np.zeros(G, np.int64), 1, normalized_grads=True, row_chunk=512)
     rel = lambda a, b: np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
-    assert out.dev_status.item() == 0
-    assert np.abs(_f64(out.logp_cur) - ref["logp_cur"]).max() <= 2e-5
-    assert np.abs(_f64(out.seq_logratio) - ref["seq_logratio"]).max() <= 1e-3
-    assert np.abs(_f64(out.adv) - ref["adv"]).max() <= 1e-3
-    assert abs(out.loss.item() - ref["loss"]) <= 1e-3 * abs(ref["loss"])
-    assert abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]) <= 1e-3
-    assert rel(_f64(out.dhidden), ref["dH"]) <= 2e-2 and rel(_f64(out.dW), ref["dW"]) <= 2e-2
-    assert out.read_diag()["n_tokens"] == ref["n_tokens"]
+    for out in outs:
+        assert out.dev_status.item() == 0
+        assert np.abs(_f64(out.logp_cur) - ref["logp_cur"]).max() <= 2e-5
+        assert np.abs(_f64(out.seq_logratio) - ref["seq_logratio"]).max() <= 1e-3
+        assert np.abs(_f64(out.adv) - ref["adv"]).max() <= 1e-3
+        assert abs(out.loss.item() - ref["loss"]) <= 1e-3 * abs(ref["loss"])
+        assert abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]) <= 1e-3
+        assert rel(_f64(out.dhidden), ref["dH"]) <= 2e-2 and rel(_f64(out.dW), ref["dW"]) <= 2e-2
+        assert out.read_diag()["n_tokens"] == ref["n_tokens"]

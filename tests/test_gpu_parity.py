@@ -326,8 +326,8 @@ def test_mfma_probe_and_forward_row_blocks(rb):
 @pytest.mark.parametrize("name", ["bf16_small", "bf16_ragged"])
 @pytest.mark.parametrize("layout", ["dv", "vd"])
 def test_fwd_bwd_logits_cache(rb, name, layout):
-    """logits_cache = 1: the forward keeps bf16 logits, the backward reloads them instead of
-    recomputing; same tolerances against the oracle, same forward bits as the default mode."""
+    """logits_cache = 1: the forward keeps the bf16 ratios p_v / p_y, the backward contracts them instead
+    of recomputing the logits; same tolerances against the oracle, same forward bits as the default mode."""
     print(f"fwd_bwd logits_cache {name} {layout}", flush=True)
     spec = SPECS[name]
     w, out, ref = _run_pair(rb, spec, layout=layout, logits_cache=True)
@@ -337,6 +337,42 @@ def test_fwd_bwd_logits_cache(rb, name, layout):
     for kw in (dict(temperature=0.8), dict(normalized_grads=True), dict(coef_mode=1, eta=1.05)):
         w, out, ref = _run_pair(rb, spec, layout=layout, logits_cache=True, **kw)
         _check_pair(rb, spec, out, ref, layout)
+
+
+@pytest.mark.parametrize("scale,flagged", [(25.0, False), (250.0, True)])
+def test_logits_cache_unlikely_sampled_tokens(rb, scale, flagged):
+    """The cached ratios are relative to the sampled token's probability.  Peaked rows (logit spread
+    ~7 and ~70) with tokens drawn uniformly put the sampled token 20..45 and ~200 nats below the row
+    maximum: the first stays inside the cache's range and meets the usual tolerances; the second is
+    outside it, is reported through RAPID_STATUS_LOGIT_RANGE, keeps exact log-probs and finite
+    gradients, and the default mode still matches the oracle on the same inputs."""
+    print(f"logits_cache unlikely tokens scale={scale}", flush=True)
+    spec = SPECS["bf16_ragged"]
+    w, g = _make(spec)
+    Wg = (g["W"].float() * scale).to(torch.bfloat16)
+    gen = torch.Generator().manual_seed(5)
+    tokens = torch.randint(0, spec.V, tuple(g["tokens"].shape), generator=gen, dtype=torch.int32).cuda()
+    N = tokens.shape[0]
+    coef = np.random.default_rng(6).normal(size=N).astype(np.float32)
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], Wg, tokens, g["mask"])
+    H, _, _, mask = _oracle_inputs(w)
+    ref = orc.iw_pg_loss_fwd_bwd(H, _np(Wg), tokens.cpu().numpy(), mask, _np(logp_b), _np(w["rewards"]),
+                                 _np(w["group_ids"]), w["K"], coef_override=coef)
+    spread = -ref["logp_cur"][mask != 0]
+    assert (spread.max() < 70) if not flagged else (np.median(spread) > 100)
+    for cache in (True, False):
+        out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], Wg, tokens, g["mask"], logp_b, g["rewards"], g["group_ids"],
+                                          w["K"], logits_cache=cache, coef_override=torch.from_numpy(coef).cuda())
+        torch.cuda.synchronize()
+        assert np.all(np.abs(_np(out.logp_cur) - ref["logp_cur"]) <= 2e-5 + 2e-6 * np.abs(ref["logp_cur"]))
+        assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+        if cache and flagged:
+            assert out.dev_status.item() == rb.STATUS_LOGIT_RANGE
+            assert np.isfinite(_np(out.dhidden)).all() and np.isfinite(_np(out.dW)).all()
+        else:
+            assert out.dev_status.item() == 0
+            assert _rel(_np(out.dhidden), ref["dH"]) <= GRAD_RTOL["bf16"]
+            assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
 
 
 def test_logits_cache_workspace_and_errors(rb):
