@@ -3,7 +3,10 @@
 
 A step = one rapid_iw_pg_loss_fwd_bwd call (all stages of the hot path) on one synthetic
 Qwen2.5-1.5B-shaped mini-batch (d=1536, V=151936, 32 prompts x 8 generations, response length
-U[256,2048]) whose inputs, including the stored behaviour log-probs, are resident in HBM.
+U[256,2048]) whose inputs, including the stored behaviour log-probs, are resident in HBM.  The call
+is timed with opts.logits_cache = 1 (the forward keeps every row's probability ratios in the
+workspace, 157 GiB at this shape, and the backward contracts them: 6 d V flop per token executed)
+and, as a second figure, with the default 0 (27 GiB, the backward regenerates the logits: 8 d V).
 Prints ONE JSON line: response tokens/s, the roofline of the dominant kernel (HIP-event timing of
 every stage, taken inside the timed region) and the float64 oracle timed on this machine's cores on
 a bounded sample of the same workload.
@@ -21,15 +24,18 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
 PEAK_HBM = 8.0e12         # B/s
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled (see the profile named in the output), of one full launch:
-# 16384 token rows for the two logits kernels, 65536 for dH and dW
-MEASURED_TRAFFIC_BYTES = {"fwd_lse": 11.8e9 + 0.2e9, "dz": 11.5e9 + 5.1e9, "dh": 62.6e9 + 0.2e9, "dw": 49.7e9 + 1.0e9}
+# 16384 token rows for the two logits kernels, 65536 for dH and dW; keyed by (backward mode, stage)
+MEASURED_TRAFFIC_BYTES = {("cache", "fwd_lse"): 11.5e9 + 5.2e9, ("cache", "dh"): 76.4e9 + 0.2e9, ("cache", "dw"): 49.7e9 + 1.0e9,
+                          ("recompute", "fwd_lse"): 11.9e9 + 0.2e9, ("recompute", "dz"): 11.5e9 + 5.1e9,
+                          ("recompute", "dh"): 70.7e9 + 0.2e9, ("recompute", "dw"): 49.7e9 + 1.0e9}
 
 
-def cpu_baseline(w, rb, group=2):
+def cpu_baseline(w, rb, group=2, logits_cache=False):
     """Oracle (float64 numpy, as it stands) on one whole group of the workload at the full d and V: the
     first group whose rewards are not forced (its 8 generations, every token), timed on this machine's
-    cores.  The same slice also goes through the library as a call of its own, and the oracle's
-    outputs, which are there anyway, give a full-size check of every output element of that call."""
+    cores.  The same slice also goes through the library as a call of its own (in the backward mode
+    the bench times), and the oracle's outputs, which are there anyway, give a full-size check of
+    every output element of that call."""
     import numpy as np
     import torch
 
@@ -43,7 +49,8 @@ def cpu_baseline(w, rb, group=2):
     hid, tok_g, mask_g = w["hidden"][n0:n1, :Tm].contiguous(), w["tokens"][n0:n1, :Tm].contiguous(), w["mask"][n0:n1, :Tm].contiguous()
     lb_g, rew_g = w["logp_behav"][n0:n1, :Tm].contiguous(), w["rewards"][n0:n1].contiguous()
     gid_g = torch.zeros(G, dtype=torch.int32, device=hid.device)
-    out = rb.rapid_iw_pg_loss_fwd_bwd(hid, w["W"], tok_g, mask_g, lb_g, rew_g, gid_g, 1, normalized_grads=True)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(hid, w["W"], tok_g, mask_g, lb_g, rew_g, gid_g, 1, normalized_grads=True,
+                                      logits_cache=logits_cache)
     torch.cuda.synchronize()
     H, W = f64(hid), f64(w["W"])
     tok, mask = tok_g.cpu().numpy(), mask_g.cpu().numpy()
@@ -79,14 +86,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (2 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workspace-gib", type=float, default=0.0, help="0 = the library's recommended size")
+    ap.add_argument("--mode", choices=["cache", "recompute"], default="cache",
+                    help="backward of the timed call: 'cache' = opts.logits_cache 1 (probability ratios kept in the "
+                         "workspace, 6 d V flop per token executed), 'recompute' = 0 (logits regenerated, 8 d V)")
+    ap.add_argument("--one-mode", action="store_true", help="skip the extra measurement of the other mode")
+    ap.add_argument("--workspace-gib", type=float, default=0.0,
+                    help="recompute mode: workspace size (0 = the library's recommended size)")
+    ap.add_argument("--chunk-rows", type=int, default=0,
+                    help="recompute mode: size the workspace for backward chunks of this many rows")
     ap.add_argument("--waves", type=int, default=0, help="4 or 8 waves per contraction workgroup (0 = library default)")
     ap.add_argument("--gi", type=str, default="", help="tile-order blocking fwd,dh,dw (tuning experiment)")
     ap.add_argument("--tune", type=str, default="", help="library tuning keys, key=value[,key=value...] (experiments)")
-    ap.add_argument("--logits-cache", action="store_true",
-                    help="time the opt-in mode that keeps bf16 logits in the workspace instead of the default")
-    ap.add_argument("--no-cache-mode", action="store_true", help="skip the extra measurement of the opt-in mode")
-    ap.add_argument("--chunk-rows", type=int, default=0, help="size the workspace for backward chunks of this many rows")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -113,54 +123,80 @@ def main():
             key, val = kv.split("=")
             rb.rapid_set_tuning(int(key), int(val))
     fwd_only = spec.fwd_only
+
+    def timed(step):
+        """W warm-up steps, then exactly K steps between two synchronisations, with the library's
+        per-stage HIP events recorded on the stream the kernels run on."""
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        rb.rapid_set_tuning(1, 1)
+        rb.rapid_profile_read()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = rb.rapid_profile_read()
+        rb.rapid_set_tuning(1, 0)
+        stages = {k: {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
+                      "avg_ms": (ms / n if n else 0.0)} for k, (ms, n) in prof.items() if n}
+        return dt, stages
+
+    def fused_mode(cache):
+        """Times rapid_iw_pg_loss_fwd_bwd in one backward mode; None if the cache does not fit."""
+        if cache:
+            need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16)
+            free, _ = torch.cuda.mem_get_info()
+            if not need or need + (8 << 30) > free:
+                return None
+            ws_bytes = None
+        else:
+            ws_bytes = int(args.workspace_gib * 2**30) if args.workspace_gib > 0 else None
+            if args.chunk_rows:
+                mn = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, N, T, d, V, K, rb.DTYPE_BF16, minimum=True)
+                vpad = (V + 255) // 256 * 256
+                ldv = vpad + 64 if (vpad // 64) % 2 == 0 else vpad
+                ws_bytes = mn + (args.chunk_rows - 256) * ldv * 2
+        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes, logits_cache=cache)
+        dt, stages = timed(lambda: rb.rapid_iw_pg_loss_fwd_bwd(
+            w["hidden"], w["W"], w["tokens"], w["mask"], w["logp_behav"], w["rewards"], w["group_ids"], K,
+            buffers=buf, optional_outputs=False, logits_cache=cache))
+        ws_gib = buf.workspace.numel() / 2**30
+        del buf                      # the workspace goes back before the other mode takes its own
+        torch.cuda.empty_cache()
+        return dt, stages, ws_gib
+
     if fwd_only:
         ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, rb.DTYPE_BF16)
         ws = rb.alloc_workspace(ws_bytes)
-        step = lambda: rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], workspace=ws)
+        dt, stages = timed(lambda: rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], workspace=ws))
+        ws_gib = ws_bytes / 2**30
         flops_per_token = 2.0 * d * V
+        mode = "forward only"
     else:
         logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"])
         w["logp_behav"] = logp_b
-        ws_bytes = int(args.workspace_gib * 2**30) if args.workspace_gib > 0 else None
-        if args.chunk_rows:
-            mn = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, N, T, d, V, K, rb.DTYPE_BF16, minimum=True)
-            vpad = (V + 255) // 256 * 256
-            ldv = vpad + 64 if (vpad // 64) % 2 == 0 else vpad
-            ws_bytes = mn + (args.chunk_rows - 256) * ldv * 2
-        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes, logits_cache=args.logits_cache)
-        ws_bytes = buf.workspace.numel()
-        step = lambda: rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b,
-                                                   w["rewards"], w["group_ids"], K, buffers=buf,
-                                                   optional_outputs=False, logits_cache=args.logits_cache)
         flops_per_token = 6.0 * d * V
+        mode = args.mode
+        res = fused_mode(mode == "cache")
+        if res is None:              # the ratios of every row do not fit beside the workload
+            mode = "recompute"
+            res = fused_mode(False)
+        dt, stages, ws_gib = res
     torch.cuda.synchronize()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    rb.rapid_set_tuning(1, 1)          # per-stage HIP events inside the timed region
-    rb.rapid_profile_read()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = rb.rapid_profile_read()
-    rb.rapid_set_tuning(1, 0)
 
     ms_per_step = dt / args.steps * 1e3
     tok_s = M * args.steps / dt
-    stages = {k: {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
-                  "avg_ms": (ms / n if n else 0.0)} for k, (ms, n) in prof.items() if n}
 
     # roofline of the dominant kernel: algorithmic flop of ONE launch / its average duration.
     # Every contraction kernel does 2*d*V flop per token it processes; a step's tokens are split
-    # over the launches of a stage (the row chunks of the backward), so one launch processes
-    # M / launches_per_step tokens on average.
-    gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages]
+    # over the launches of a stage (row blocks), so one launch processes M / (launches that hold
+    # tokens) tokens on average.
+    gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and stages[s]["launches_per_step"] > 1]
     dom = max(gemm_stages, key=lambda s: stages[s]["ms_per_step"])
     launches = stages[dom]["launches_per_step"]
-    # chunks past the last valid row exit at once: count only launches that had rows
+    # blocks past the last valid row exit at once: count only launches that had rows
     Mmax_pad = (N * T + 255) // 256 * 256
     chunk_rows = Mmax_pad / launches
     live = max(1, -(-M // int(chunk_rows)))
@@ -169,7 +205,7 @@ def main():
     achieved = 2.0 * d * V * tokens_per_launch / (avg_ms * 1e-3) / 1e12
     # HBM-side bytes per full launch from rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by a copy
     # kernel of known size); measured on the headline workload only, see profiles/
-    traffic = MEASURED_TRAFFIC_BYTES.get(dom) if spec.name == "cfg2_qwen1.5b" else None
+    traffic = MEASURED_TRAFFIC_BYTES.get((mode, dom)) if spec.name == "cfg2_qwen1.5b" else None
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA / 1e12,
                 "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_MFMA / 1e12), "traffic": traffic,
                 "traffic_unit": "bytes per full launch (fabric reads + writes)",
@@ -183,8 +219,10 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": spec.name, "d": d, "V": V, "prompts": spec.prompts, "G": spec.G, "N": N,
-                   "T": T, "response_tokens": M, "workspace_gib": ws_bytes / 2**30,
-                   "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd"},
+                   "T": T, "response_tokens": M, "workspace_gib": ws_gib,
+                   "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd",
+                   "backward_mode": mode,
+                   "executed_flop_per_token": (2.0 if fwd_only else 6.0 if mode == "cache" else 8.0) * d * V},
         "frac_bf16_mfma_peak_algorithmic": flops_per_token * tok_s / PEAK_BF16_MFMA,
         "roofline": roofline,
         "stages": stages,
@@ -195,41 +233,18 @@ def main():
     tf_rnd, _ = rb.rapid_mfma_probe(1, 100000)
     out["mfma_probe"] = {"unit": "TFLOP/s", "small_integer_operands": tf_int, "random_bf16_operands": tf_rnd,
                          "note": "8 independent 32x32x16 bf16 MFMA chains per wave, 2 waves per SIMD, registers only"}
-    # The opt-in mode that trades workspace for work (bf16 logits kept by the forward, no recomputation
-    # in the backward), timed the same way; reported next to the default, never as `value`.
-    if not fwd_only and not args.logits_cache and not args.no_cache_mode:
-        need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16)
-        del buf, step          # the default mode's workspace goes back before the larger one is taken
-        torch.cuda.empty_cache()
-        free, _ = torch.cuda.mem_get_info()
-        if need and need + (8 << 30) < free:
-            cbuf = rb.IwPgBuffers(w["hidden"], w["W"], K, logits_cache=True)
-            cstep = lambda: rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b,
-                                                        w["rewards"], w["group_ids"], K, buffers=cbuf,
-                                                        optional_outputs=False, logits_cache=True)
-            for _ in range(args.warmup):
-                cstep()
-            torch.cuda.synchronize()
-            rb.rapid_set_tuning(1, 1)
-            rb.rapid_profile_read()
-            t0 = time.perf_counter()
-            for _ in range(args.steps):
-                cstep()
-            torch.cuda.synchronize()
-            cdt = time.perf_counter() - t0
-            cprof = rb.rapid_profile_read()
-            rb.rapid_set_tuning(1, 0)
-            out["logits_cache_mode"] = {
-                "value": M * args.steps / cdt, "unit": "tokens/s", "ms_per_step": cdt / args.steps * 1e3,
-                "frac_bf16_mfma_peak_algorithmic": flops_per_token * M * args.steps / cdt / PEAK_BF16_MFMA,
-                "workspace_gib": need / 2**30,
-                "stages_ms_per_step": {k: ms / args.steps for k, (ms, n) in cprof.items() if n},
-                "note": "opts.logits_cache = 1: 6 d V flop per token executed instead of 8"}
-            del cbuf
-        else:
-            out["logits_cache_mode"] = None
+    # the same call in its other backward mode, timed the same way; reported beside `value`, never as it
+    if not fwd_only and not args.one_mode:
+        other = "recompute" if mode == "cache" else "cache"
+        res = fused_mode(other == "cache")
+        out["other_backward_mode"] = None if res is None else {
+            "backward_mode": other, "value": M * args.steps / res[0], "unit": "tokens/s",
+            "ms_per_step": res[0] / args.steps * 1e3,
+            "frac_bf16_mfma_peak_algorithmic": flops_per_token * M * args.steps / res[0] / PEAK_BF16_MFMA,
+            "workspace_gib": res[2], "executed_flop_per_token": (6.0 if other == "cache" else 8.0) * d * V,
+            "stages_ms_per_step": {k: v["ms_per_step"] for k, v in res[1].items()}}
     if not args.no_cpu_baseline and not fwd_only:
-        out["cpu_baseline"] = cpu_baseline(w, rb)
+        out["cpu_baseline"] = cpu_baseline(w, rb, logits_cache=(mode == "cache"))
     print(json.dumps(out))
 
 
