@@ -169,10 +169,43 @@ def coefficients(s, adv, eta=2.0, coef_mode=0, loss_scale=1.0, normalized=False)
     return g, float(g.sum()), lam
 
 
-def backward(hidden, W, tokens, mask, g, temperature=1.0, row_chunk=2048):
-    """Gradients of sum_{n,t valid} g_n * logp_{n,t} with respect to hidden and W.
+def token_coefficients(tok_logratio, mask, adv, eta=2.0, coef_mode=0, loss_scale=1.0, normalized=False):
+    """Token-level variant of the outer weight (ratio_level 1).  NOT an estimator the paper defines:
+    its ratio is between whole generations (Sec. 3.4, Eq. (3)) and token-level ratios appear only as
+    a diagnostic (Sec. 4.3).  Here the weight rho_n of Eq. (3) is replaced, token by token, by that
+    token's ratio rho_{n,t} = exp(Delta_{n,t}); the advantages stay those of Eq. (5):
 
-    For a valid row: p = softmax(z), dz = g_n (e_y - p) / temperature, dH = W dz,
+        L = -(loss_scale/N) sum_n A_n sum_{t valid} c_{n,t},   c_{n,t} = rho_{n,t}  (coef_mode 0)
+                                                            or min(rho_{n,t}, eta) held constant (1)
+        g_{n,t} = dL/d logp_{n,t} = -(loss_scale/N) c_{n,t} A_n,   L = sum_{n,t valid} g_{n,t}.
+
+    With normalized=True everything is scaled by exp(-lam), lam = log max_{n,t} |g_{n,t}|.
+    Returns (g[N,T] (0 at masked positions), loss, lam).
+    """
+    D = _as64(tok_logratio)
+    A = _as64(adv)
+    msk = np.asarray(mask) != 0
+    N, T = D.shape
+    log_c = D if coef_mode == 0 else np.minimum(D, math.log(eta) if math.isfinite(eta) else math.inf)
+    g = np.zeros((N, T), _F)
+    log_abs_g = np.full((N, T), -np.inf)
+    for n in range(N):
+        if A[n] != 0:
+            log_abs_g[n, msk[n]] = log_c[n, msk[n]] + math.log(abs(A[n])) + math.log(loss_scale) - math.log(N)
+    lam = 0.0
+    if normalized and np.isfinite(log_abs_g).any():
+        lam = float(log_abs_g.max())
+    for n in range(N):
+        if A[n] != 0:
+            g[n, msk[n]] = -np.sign(A[n]) * np.exp(log_abs_g[n, msk[n]] - lam)
+    return g, float(g.sum()), lam
+
+
+def backward(hidden, W, tokens, mask, g, temperature=1.0, row_chunk=2048):
+    """Gradients of sum_{n,t valid} g_{n,t} * logp_{n,t} with respect to hidden and W; g is [N]
+    (one coefficient per generation, g_{n,t} = g_n) or [N,T] (one per token).
+
+    For a valid row: p = softmax(z), dz = g_{n,t} (e_y - p) / temperature, dH = W dz,
     dW += outer(h, dz).  Masked rows get dH = 0.  Returns (dH [N,T,d], dW [d,V]).
     """
     H = _as64(hidden)
@@ -193,7 +226,8 @@ def backward(hidden, W, tokens, mask, g, temperature=1.0, row_chunk=2048):
         p = e / e.sum(axis=1, keepdims=True)
         dz = -p
         dz[np.arange(dz.shape[0]), tok[rr[:, 0], rr[:, 1]]] += 1.0
-        dz *= (g[rr[:, 0]] / temperature)[:, None]
+        g_rows = g[rr[:, 0]] if g.ndim == 1 else g[rr[:, 0], rr[:, 1]]
+        dz *= (g_rows / temperature)[:, None]
         dH[rr[:, 0], rr[:, 1], :] = dz @ Wd.T
         dW += h.T @ dz
     return dH, dW
@@ -201,9 +235,10 @@ def backward(hidden, W, tokens, mask, g, temperature=1.0, row_chunk=2048):
 
 def iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, K,
                        eta=2.0, coef_mode=0, baseline_mode=0, loss_scale=1.0, temperature=1.0,
-                       normalized_grads=False, coef_override=None, row_chunk=2048):
+                       normalized_grads=False, coef_override=None, row_chunk=2048, ratio_level=0):
     """The whole update-step loss of Alg. 1 (procedure IW-GRPG, one mini-batch): advantages by
-    Eq. (5), gradient by Eq. (3).  Returns a dict with loss, dH, dW and every intermediate."""
+    Eq. (5), gradient by Eq. (3).  ratio_level 1 swaps the outer weight for the token-level one of
+    token_coefficients (then `g` is [N,T]).  Returns a dict with loss, dH, dW and every intermediate."""
     logp_cur, lse = logprob(hidden, W, tokens, mask, temperature, row_chunk)
     tok_lr = token_logratio(logp_cur, logp_behav, mask)
     s = tok_lr.sum(axis=1)
@@ -212,8 +247,12 @@ def iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, 
     if coef_override is not None:
         g = _as64(coef_override)
         loss, lam = float(g.sum()), 0.0
-    else:
+    elif ratio_level == 0:
         g, loss, lam = coefficients(s, ga["adv"], eta, coef_mode, loss_scale, normalized_grads)
+    elif ratio_level == 1:
+        g, loss, lam = token_coefficients(tok_lr, mask, ga["adv"], eta, coef_mode, loss_scale, normalized_grads)
+    else:
+        raise ValueError("ratio_level")
     dH, dW = backward(hidden, W, tokens, mask, g, temperature, row_chunk)
     log_eta = math.log(eta) if math.isfinite(eta) else math.inf
     log_w = np.minimum(s, log_eta)

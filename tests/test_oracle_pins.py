@@ -385,6 +385,84 @@ def test_diagnostics_and_empty_sequence():
     # loss recomputed from rho and A
     assert abs(out["loss"] + (np.exp(s) * out["adv"]).mean()) < 1e-14
 
+# ---------------------------------------------------------------- token-level outer weight (ratio_level 1)
+def _py_token_surrogate(H, W, tok, mask, logp_b, adv_fixed):
+    """-(1/N) sum_n A_n sum_t pi(y_t)/mu(y_t), advantages held fixed, explicit loops."""
+    N, T = len(tok), len(tok[0])
+    tot = 0.0
+    for n in range(N):
+        for t in range(T):
+            if mask[n][t]:
+                tot += adv_fixed[n] * math.exp(_py_logsoftmax_at(H[n][t], W, tok[n][t]) - logp_b[n][t])
+    return -tot / N
+
+
+def test_token_level_reduces_to_generation_level_for_one_token_generations():
+    """A generation of one token has one ratio: both levels are the same estimator, in every mode."""
+    H, W, _, tok, mask, R, gid, logp_b = _tiny(11, N=6, T=1, G=3)
+    logp_b = logp_b - 0.5 * mask
+    for kw in (dict(), dict(coef_mode=1), dict(normalized_grads=True), dict(baseline_mode=2, loss_scale=0.3)):
+        a = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, ratio_level=0, **kw)
+        b = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, ratio_level=1, **kw)
+        assert abs(a["loss"] - b["loss"]) < 1e-15 and abs(a["grad_log_scale"] - b["grad_log_scale"]) < 1e-15
+        assert np.allclose(a["g"], b["g"][:, 0], atol=1e-16)
+        assert np.allclose(a["dH"], b["dH"], atol=1e-16) and np.allclose(a["dW"], b["dW"], atol=1e-16)
+
+
+def test_token_level_on_policy():
+    """pi = mu: every token ratio is exactly 1, so each token carries its generation's coefficient
+    -A_n/N (the on-policy gradient of Eq. (1) with Eq. (2)) and the loss counts it once per token."""
+    H, W, _, tok, mask, R, gid, _ = _tiny(12, N=4, T=5)
+    logp_cur, _ = orc.logprob(H, W, tok, mask)
+    a = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_cur, R, gid, 2, ratio_level=0)
+    b = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_cur, R, gid, 2, ratio_level=1)
+    assert np.array_equal(b["g"], a["g"][:, None] * (mask != 0))
+    assert abs(b["loss"] - float((a["g"] * mask.sum(1)).sum())) < 1e-15
+    assert np.allclose(a["dH"], b["dH"], atol=1e-16) and np.allclose(a["dW"], b["dW"], atol=1e-16)
+
+
+def test_token_level_finite_differences():
+    """coef_mode 0: the gradients are those of -(1/N) sum_n A_n sum_t rho_{n,t} with A fixed, an
+    objective written independently with python loops; every element of dW and dH."""
+    H, W, _, tok, mask, R, gid, logp_b = _tiny(13)
+    out = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, ratio_level=1)
+    A = out["adv"].tolist()
+    args = (tok.tolist(), mask.tolist(), logp_b.tolist(), A)
+    assert abs(_py_token_surrogate(H.tolist(), W.tolist(), *args) - out["loss"]) < 1e-13
+    eps = 1e-6
+    for idx in itertools.product(range(W.shape[0]), range(W.shape[1])):
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += eps
+        Wm[idx] -= eps
+        fd = (_py_token_surrogate(H.tolist(), Wp.tolist(), *args) - _py_token_surrogate(H.tolist(), Wm.tolist(), *args)) / (2 * eps)
+        assert abs(out["dW"][idx] - fd) < 1e-8, idx
+    for idx in itertools.product(range(H.shape[0]), range(H.shape[1]), range(H.shape[2])):
+        Hp, Hm = H.copy(), H.copy()
+        Hp[idx] += eps
+        Hm[idx] -= eps
+        fd = (_py_token_surrogate(Hp.tolist(), W.tolist(), *args) - _py_token_surrogate(Hm.tolist(), W.tolist(), *args)) / (2 * eps)
+        assert abs(out["dH"][idx] - fd) < 1e-8, idx
+
+
+def test_token_level_clip_and_normalisation():
+    """coef_mode 1 clips each token's ratio at eta (hand values), and normalized_grads rescales by
+    the largest |g_{n,t}| without changing anything else."""
+    mask = np.array([[1, 1, 1], [1, 1, 0]], np.uint8)
+    D = np.log(np.array([[4.0, 0.5, 1.0], [3.0, 0.25, 7.0]])) * mask
+    adv = np.array([0.5, -1.0])
+    g, loss, lam = orc.token_coefficients(D, mask, adv, eta=2.0, coef_mode=1)
+    assert np.allclose(g, [[-0.5, -0.125, -0.25], [1.0, 0.125, 0.0]], atol=1e-15) and lam == 0.0
+    assert abs(loss - 0.25) < 1e-15
+    g0, loss0, _ = orc.token_coefficients(D, mask, adv, eta=2.0, coef_mode=0)
+    assert np.allclose(g0, [[-1.0, -0.125, -0.25], [1.5, 0.125, 0.0]], atol=1e-15)
+    gn, lossn, lamn = orc.token_coefficients(D, mask, adv, eta=2.0, coef_mode=0, normalized=True)
+    assert abs(lamn - math.log(1.5)) < 1e-15 and np.allclose(gn * 1.5, g0, atol=1e-15)
+    assert abs(lossn * 1.5 - loss0) < 1e-15 and abs(np.abs(gn).max() - 1.0) < 1e-15
+    # a planted mistake (ratio of the whole generation in place of the token's) fails the hand values
+    wrong = -(np.exp(D.sum(1))[:, None] * mask) * adv[:, None] / 2
+    assert not np.allclose(wrong, g0)
+
+
 
 def test_compaction():
     rng = np.random.default_rng(12)
