@@ -88,6 +88,13 @@ typedef struct rapid_iw_pg_opts {
                               bytes of workspace (rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...)).
                               Same single bf16 rounding per element of the rows x V intermediate as
                               mode 0; see RAPID_STATUS_LOGIT_RANGE for its one limit */
+    int ratio_level;       /* 0 (default): the outer weight of Eq. (3) is the generation-level ratio rho_n, as
+                              the paper defines it.  1: a variant the paper does not define (its token-level
+                              ratios are a diagnostic, Sec. 4.3): every token carries its own ratio,
+                              loss = -(loss_scale/N) sum_n A_n sum_t c_{n,t}, c_{n,t} = rho_{n,t} (coef_mode 0)
+                              or min(rho_{n,t}, eta) held constant (coef_mode 1); the advantages stay those of
+                              Eq. (5) with generation-level clipped weights.  grad_log_scale is then
+                              log max |dLoss/dlogp_{n,t}| over tokens.  Ignored with coef_override */
     const float* coef_override; /* DEVICE [N] or NULL: use these per-generation coefficients g_n
                               = dLoss/dlogp_{n,t} instead of the estimator's (loss = sum g_n) */
 } rapid_iw_pg_opts;

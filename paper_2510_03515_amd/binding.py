@@ -38,7 +38,7 @@ class IwPgOpts(C.Structure):
     _fields_ = [("eta", C.c_float), ("coef_mode", C.c_int), ("baseline_mode", C.c_int),
                 ("loss_scale", C.c_float), ("temperature", C.c_float), ("w_layout", C.c_int),
                 ("dw_dtype", C.c_int), ("accumulate_dw", C.c_int), ("normalized_grads", C.c_int),
-                ("logits_cache", C.c_int), ("coef_override", C.c_void_p)]
+                ("logits_cache", C.c_int), ("ratio_level", C.c_int), ("coef_override", C.c_void_p)]
 
 
 class IwPgDiag(C.Structure):
@@ -243,7 +243,7 @@ class IwPgBuffers:
 def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, K, buffers=None,
                              eta=2.0, coef_mode=0, baseline_mode=0, loss_scale=1.0, temperature=1.0,
                              w_layout=W_DV, accumulate_dw=False, normalized_grads=False, coef_override=None,
-                             optional_outputs=True, logits_cache=False):
+                             optional_outputs=True, logits_cache=False, ratio_level=0):
     """Enqueues the fused forward+backward on the current stream and returns the IwPgBuffers that
     hold the outputs (loss, dhidden, dW, logp_cur, tok_logratio, seq_logratio, adv, diag)."""
     N, T, d = hidden.shape
@@ -267,6 +267,7 @@ def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group
     o.accumulate_dw = int(bool(accumulate_dw))
     o.normalized_grads = int(bool(normalized_grads))
     o.logits_cache = int(bool(logits_cache))
+    o.ratio_level = int(ratio_level)
     if coef_override is not None:
         _need(coef_override, torch.float32, "coef_override")
         o.coef_override = coef_override.data_ptr()

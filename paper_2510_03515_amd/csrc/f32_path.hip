@@ -95,13 +95,13 @@ __global__ void f32_row_lse_kernel(const float* __restrict__ z, int64_t V, int64
 }
 
 __global__ void f32_dz_kernel(float* __restrict__ z, int64_t V, int64_t m0, const int32_t* __restrict__ tokc,
-                              const int32_t* __restrict__ seqc, const float* __restrict__ lse_c,
-                              const float* __restrict__ g, float inv_temp, const int32_t* __restrict__ counts) {
+                              const float* __restrict__ lse_c, const float* __restrict__ rowg, float inv_temp,
+                              const int32_t* __restrict__ counts) {
     const int64_t jl = blockIdx.x, j = m0 + jl;
     if (j >= counts[CNT_M]) return;
     float* row = z + jl * V;
     const double lse = (double)lse_c[j];
-    const double gj = (double)g[seqc[j]] * (double)inv_temp;
+    const double gj = (double)rowg[j] * (double)inv_temp;
     const int tok = tokc[j];
     for (int64_t v = threadIdx.x; v < V; v += blockDim.x) {
         const double p = exp((double)row[v] - lse);
@@ -125,9 +125,9 @@ void launch_f32_row_lse(const float* z, int64_t V, int64_t rows, int64_t m0, con
                                                            lse_out);
 }
 
-void launch_f32_dz(float* z, int64_t V, int64_t rows, int64_t m0, const int32_t* tokc, const int32_t* seqc,
-                   const float* lse_c, const float* g, float inv_temp, const int32_t* counts, hipStream_t st) {
-    if (rows > 0) f32_dz_kernel<<<(unsigned)rows, 256, 0, st>>>(z, V, m0, tokc, seqc, lse_c, g, inv_temp, counts);
+void launch_f32_dz(float* z, int64_t V, int64_t rows, int64_t m0, const int32_t* tokc, const float* lse_c,
+                   const float* rowg, float inv_temp, const int32_t* counts, hipStream_t st) {
+    if (rows > 0) f32_dz_kernel<<<(unsigned)rows, 256, 0, st>>>(z, V, m0, tokc, lse_c, rowg, inv_temp, counts);
 }
 
 }  // namespace rapid

@@ -682,7 +682,7 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
     for (int jb = 0; jb < WJ; ++jb) {
         const int64_t j = a.m0 + jl_base + jb * 32 + L.lj;
         const bool live = j < M;
-        ngj[jb] = live ? -a.g[a.seqc[j]] * a.inv_temp : 0.f;
+        ngj[jb] = live ? -a.rowg[j] * a.inv_temp : 0.f;
         nlse[jb] = live ? -a.lse_c[j] * LOG2E : 0.f;
     }
     store_tile_through_lds<S>(lds, L, a.dz + jl_base * a.ldz + i_base, a.ldz, [&](int ib, int jb, int v) {
@@ -812,14 +812,14 @@ __global__ __launch_bounds__(256) void token_logit_kernel(const bf16_t* __restri
 
 // dz[row][tok_row] += g: the one-hot part of dz = g (onehot - p)
 __global__ void token_onehot_kernel(bf16_t* __restrict__ dz, int64_t ldz, int64_t m0, int64_t rows,
-                                    const int32_t* __restrict__ tokc, const int32_t* __restrict__ seqc,
-                                    const float* __restrict__ g, float inv_temp, const int32_t* __restrict__ counts) {
+                                    const int32_t* __restrict__ tokc, const float* __restrict__ rowg, float inv_temp,
+                                    const int32_t* __restrict__ counts) {
     const int64_t jl = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t j = m0 + jl;
     if (jl >= rows || j >= counts[CNT_M]) return;
     bf16_t* p = dz + jl * ldz + tokc[j];
     const float cur = (float)__builtin_bit_cast(__bf16, *p);
-    const __bf16 r = (__bf16)(cur + g[seqc[j]] * inv_temp);
+    const __bf16 r = (__bf16)(cur + rowg[j] * inv_temp);
     *p = __builtin_bit_cast(bf16_t, r);
 }
 
@@ -832,8 +832,8 @@ __global__ void token_onehot_kernel(bf16_t* __restrict__ dz, int64_t ldz, int64_
 // RAPID_STATUS_LOGIT_RANGE: such a row's gradient is truncated).
 __global__ __launch_bounds__(256) void cache_finish_kernel(bf16_t* __restrict__ u, int64_t ldz, bf16_t* __restrict__ Hc,
                                                            int64_t ldk, const int32_t* __restrict__ tokc,
-                                                           const int32_t* __restrict__ seqc, const float* __restrict__ zy,
-                                                           const float* __restrict__ lse_c, const float* __restrict__ g,
+                                                           const float* __restrict__ zy,
+                                                           const float* __restrict__ lse_c, const float* __restrict__ rowg,
                                                            float inv_temp, const int32_t* __restrict__ counts,
                                                            float* __restrict__ rowc, int32_t* __restrict__ dev_status) {
     const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -843,7 +843,7 @@ __global__ __launch_bounds__(256) void cache_finish_kernel(bf16_t* __restrict__ 
     float c = 0.f;
     if (j < M) {
         float nlp = lse_c[j] - zy[j];   // -log p_y
-        c = -g[seqc[j]] * inv_temp * __expf(-nlp);
+        c = -rowg[j] * inv_temp * __expf(-nlp);
         if (lane == 0) {
             if (nlp > 80.f) {
                 nlp = 80.f;
@@ -930,14 +930,14 @@ int fwd_slots_per_tile() { return 2; }
 void launch_dz(const DzArgs& a, hipStream_t st) {
     if (g_waves == 16) launch_dz_t<G16>(a, st); else if (g_waves == 8) launch_dz_t<G8>(a, st); else launch_dz_t<G4>(a, st);
     const int64_t rows = (int64_t)a.tilesM * 256;
-    token_onehot_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, st>>>(a.dz, a.ldz, a.m0, rows, a.tokc, a.seqc, a.g,
+    token_onehot_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, st>>>(a.dz, a.ldz, a.m0, rows, a.tokc, a.rowg,
                                                                       a.inv_temp, a.counts);
 }
 
-void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc, const int32_t* seqc,
-                         const float* zy, const float* lse_c, const float* g, float inv_temp, const int32_t* counts,
+void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc,
+                         const float* zy, const float* lse_c, const float* rowg, float inv_temp, const int32_t* counts,
                          int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st) {
-    cache_finish_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(u, ldz, Hc, ldk, tokc, seqc, zy, lse_c, g,
+    cache_finish_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(u, ldz, Hc, ldk, tokc, zy, lse_c, rowg,
                                                                         inv_temp, counts, rowc, dev_status);
 }
 void launch_dh(const DhArgs& a, hipStream_t st) {

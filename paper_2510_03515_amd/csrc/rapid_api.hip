@@ -69,8 +69,8 @@ struct Plan {
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
-    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, rowc, logp_tmp, s64, s32, adv, g, Hc, Wvd, Wdv, WdvB,
-        part_max, part_sum, dw32, chunk0;
+    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, rowc, rowg, logp_tmp, s64, s32, adv, g, g64, tsum, tmax,
+        Hc, Wvd, Wdv, WdvB, part_max, part_sum, dw32, chunk0;
 };
 
 size_t take(size_t& cur, size_t bytes) {
@@ -110,6 +110,10 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     p.lse_c = take(cur, (size_t)p.Mmax_pad * 4);
     if (bwd) {
         p.rowc = take(cur, (size_t)p.Mmax_pad * 4);
+        p.rowg = take(cur, (size_t)p.Mmax_pad * 4);
+        p.g64 = take(cur, (size_t)N * 8);
+        p.tsum = take(cur, (size_t)N * 8);
+        p.tmax = take(cur, (size_t)N * 8);
         p.logp_tmp = take(cur, (size_t)p.Mmax * 4);
         p.s64 = take(cur, (size_t)N * 8);
         p.s32 = take(cur, (size_t)N * 4);
@@ -315,7 +319,7 @@ using namespace rapid;
 
 extern "C" {
 
-int rapid_version(void) { return 3; }
+int rapid_version(void) { return 4; }
 
 const char* rapid_last_error(void) { return g_err; }
 
@@ -332,6 +336,7 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
     o->accumulate_dw = 0;
     o->normalized_grads = 0;
     o->logits_cache = 0;
+    o->ratio_level = 0;
     o->coef_override = nullptr;
 }
 
@@ -538,9 +543,9 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         set_error("rewards, group_ids, loss_out, dhidden_out and dW_out must not be NULL");
         return RAPID_ERR_NULL;
     }
-    if (o.coef_mode < 0 || o.coef_mode > 1 || o.baseline_mode < 0 || o.baseline_mode > 2 ||
-        (o.dw_dtype != RAPID_DTYPE_F32 && o.dw_dtype != RAPID_DTYPE_BF16)) {
-        set_error("unknown coef_mode / baseline_mode / dw_dtype");
+    if (o.coef_mode < 0 || o.coef_mode > 1 || o.baseline_mode < 0 || o.baseline_mode > 2 || o.ratio_level < 0 ||
+        o.ratio_level > 1 || (o.dw_dtype != RAPID_DTYPE_F32 && o.dw_dtype != RAPID_DTYPE_BF16)) {
+        set_error("unknown coef_mode / baseline_mode / ratio_level / dw_dtype");
         return RAPID_ERR_DTYPE;
     }
     if (!(o.eta > 0.f) || !(o.loss_scale > 0.f) || !std::isfinite(o.loss_scale)) {
@@ -587,6 +592,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     float* s32 = seq_logratio_out ? seq_logratio_out : at<float>(ws, p.s32);
     float* adv = adv_out ? adv_out : at<float>(ws, p.adv);
     float* g = at<float>(ws, p.g);
+    float* rowg = at<float>(ws, p.rowg);
     const float inv_temp = 1.0f / o.temperature;
 
     // forward: current-policy log-probs of the sampled tokens
@@ -597,11 +603,18 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     // generation-level log ratios, clipped-weight group baseline, coefficients and loss
     {
         Span sp(ST_ESTIMATOR, st);
-        launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, dev_status, st);
+        // token-level outer weight: per generation the sum and the log-maximum of its tokens' ratios
+        const bool per_token = o.ratio_level == 1 && !o.coef_override;
+        double* tsum = per_token ? at<double>(ws, p.tsum) : nullptr;
+        double* tmax = per_token ? at<double>(ws, p.tmax) : nullptr;
+        launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, o.eta, o.coef_mode == 1,
+                            tsum, tmax, dev_status, st);
         launch_group_advantage(rewards, group_ids, s32, N, K, o.eta, o.baseline_mode, adv, nullptr, nullptr,
                                nullptr, nullptr, dev_status, st);
         launch_coefficients(s64, adv, o.coef_override, N, o.eta, o.coef_mode, o.loss_scale, o.normalized_grads,
-                            counts, g, loss_out, diag_out, st);
+                            tsum, tmax, counts, g, at<double>(ws, p.g64), loss_out, diag_out, st);
+        launch_row_coefficients(g, at<double>(ws, p.g64), seqc, row_index, counts, logp_cur, logp_behav, per_token,
+                                o.eta, o.coef_mode == 1, p.Mmax_pad, rowg, st);
     }
 
     // backward, in row chunks
@@ -633,7 +646,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         // rows) and the backward walks the buffer in blocks.
         if (cached) {
             Span sp(ST_DZ, st);
-            launch_cache_finish(at<bf16_t>(ws, p.chunk0), p.ldv, Hc, p.ldk, tokc, seqc, at<float>(ws, p.zy), lse_c, g,
+            launch_cache_finish(at<bf16_t>(ws, p.chunk0), p.ldv, Hc, p.ldk, tokc, at<float>(ws, p.zy), lse_c, rowg,
                                 inv_temp, counts, p.Mmax_pad, at<float>(ws, p.rowc), dev_status, st);
         }
         const int64_t cstep = g_cached_step_tiles > 0 ? (int64_t)g_cached_step_tiles * ROW_TILE : p.Mc;
@@ -646,7 +659,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             za.Wvd = Wvd; za.Hc = Hc + m0 * p.ldk; za.dpad = p.dpad; za.ldk = p.ldk; za.ldz = p.ldv;
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
             za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
-            za.tokc = tokc; za.seqc = seqc; za.lse_c = lse_c; za.g = g; za.counts = counts; za.dz = dz; za.gi = g_gi_fwd;
+            za.tokc = tokc; za.lse_c = lse_c; za.rowg = rowg; za.counts = counts; za.dz = dz; za.gi = g_gi_fwd;
             if (!cached) {
                 // like the forward, in sub-blocks of rows whose hidden rows stay in the memory-side cache
                 const int64_t sub = (int64_t)g_fwd_block_tiles * 256;
@@ -691,7 +704,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             gz.C = z; gz.sc_i = V; gz.sc_j = 1;
             gz.I = rows; gz.J = V; gz.Kd = d; gz.beta = 0; gz.counts = counts; gz.i0 = m0; gz.alpha = inv_temp;
             launch_f32_gemm(gz, st);
-            launch_f32_dz(z, V, rows, m0, tokc, seqc, lse_c, g, inv_temp, counts, st);
+            launch_f32_dz(z, V, rows, m0, tokc, lse_c, rowg, inv_temp, counts, st);
             // dH[row] = dz[row, :] . W^T
             F32Gemm gh;
             memset(&gh, 0, sizeof(gh));

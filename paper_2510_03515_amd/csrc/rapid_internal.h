@@ -35,17 +35,23 @@ void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const
 void launch_merge_lse(const float* part_max, const float* part_sum, int P, int64_t ld_part,
                       const float* zy, const int32_t* row_index, const int32_t* counts, int64_t Mmax_pad,
                       float* lse_c, float* logp_out, float* lse_out, hipStream_t st);
+// tsum/tmax (NULL or [N]): per generation, sum and log-maximum of its tokens' (clipped if clip_tokens) ratios
 void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N,
-                         int64_t T, float* tok_logratio_out, double* s64, float* s32,
-                         int32_t* dev_status, hipStream_t st);
+                         int64_t T, float* tok_logratio_out, double* s64, float* s32, float eta, int clip_tokens,
+                         double* tsum, double* tmax, int32_t* dev_status, hipStream_t st);
 void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, int64_t N,
                             int64_t K, float eta, int baseline_mode, float* adv, float* weight,
                             float* gmean, float* gstd, int32_t* gsize, int32_t* dev_status,
                             hipStream_t st);
+// tsum/tmax given: token-level outer weight (g_n is then the generation's factor without a ratio)
 void launch_coefficients(const double* s64, const float* adv, const float* coef_override, int64_t N,
-                         float eta, int coef_mode, float loss_scale, int normalized,
-                         const int32_t* counts, float* g, float* loss_out, rapid_iw_pg_diag* diag,
-                         hipStream_t st);
+                         float eta, int coef_mode, float loss_scale, int normalized, const double* tsum,
+                         const double* tmax, const int32_t* counts, float* g, double* g64, float* loss_out,
+                         rapid_iw_pg_diag* diag, hipStream_t st);
+// rowg[j] = dL/dlogp of compact row j (0 for padding rows): g of its generation, times its own ratio if per_token
+void launch_row_coefficients(const float* g, const double* g64, const int32_t* seqc, const int32_t* row_index,
+                             const int32_t* counts, const float* logp_cur, const float* logp_behav, int per_token,
+                             float eta, int clip_tokens, int64_t rows_max, float* rowg, hipStream_t st);
 void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, int64_t d, int elem_bytes,
                              hipStream_t st);
 void launch_f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t st);
@@ -99,9 +105,8 @@ struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, b
     float inv_temp;
     int64_t m0;           // first compact row of the chunk
     const int32_t* tokc;  // full arrays (indexed by compact row)
-    const int32_t* seqc;
     const float* lse_c;
-    const float* g;       // [N]
+    const float* rowg;    // dL/dlogp per compact row
     const int32_t* counts;
     bf16_t* dz;           // [Mc, Vpad]
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
@@ -109,8 +114,8 @@ struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, b
 void launch_dz(const DzArgs& a, hipStream_t st);
 // turns the ratios a storing forward left in u [rows_max, ldz] into the backward's operands: the
 // sampled token's element of each row, the row factors rowc [rows_max], and Hc scaled by them in place
-void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc, const int32_t* seqc,
-                         const float* zy, const float* lse_c, const float* g, float inv_temp, const int32_t* counts,
+void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc,
+                         const float* zy, const float* lse_c, const float* rowg, float inv_temp, const int32_t* counts,
                          int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st);
 
 struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
@@ -176,8 +181,7 @@ void launch_f32_row_lse(const float* z, int64_t V, int64_t rows, int64_t m0, con
                         float* lse_out, hipStream_t st);
 // in place: z -> dz = g (onehot - softmax) * inv_temp
 void launch_f32_dz(float* z, int64_t V, int64_t rows, int64_t m0, const int32_t* tokc,
-                   const int32_t* seqc, const float* lse_c, const float* g, float inv_temp,
-                   const int32_t* counts, hipStream_t st);
+                   const float* lse_c, const float* rowg, float inv_temp, const int32_t* counts, hipStream_t st);
 
 void set_error(const char* fmt, ...);
 

@@ -171,31 +171,49 @@ __global__ void merge_lse_kernel(const float* __restrict__ part_max, const float
     if (lse_out) lse_out[pos] = lse_f;
 }
 
-// one wave per generation: token-level log ratios and their sum over the generation
+// one wave per generation: token-level log ratios and their sum over the generation; for the
+// token-level outer weight also sum_t c_{n,t} and max_t log c_{n,t} of the generation's valid tokens
+// (c = the token's ratio, clipped at eta if clip_tokens), tsum/tmax may be NULL
 __global__ void seq_logratio_kernel(const float* __restrict__ logp_cur, const float* __restrict__ logp_behav,
                                     const uint8_t* __restrict__ mask, int64_t N, int64_t T,
                                     float* __restrict__ tok_lr, double* __restrict__ s64,
-                                    float* __restrict__ s32, int32_t* __restrict__ dev_status) {
+                                    float* __restrict__ s32, double log_eta, int clip_tokens,
+                                    double* __restrict__ tsum, double* __restrict__ tmax,
+                                    int32_t* __restrict__ dev_status) {
     const int64_t n = blockIdx.x;
     if (n >= N) return;
-    double acc = 0.0;
+    double acc = 0.0, csum = 0.0, cmax = -INFINITY;
     bool bad = false;
     for (int64_t t = threadIdx.x; t < T; t += WAVE) {
         const int64_t i = n * T + t;
         double dlt = 0.0;
-        if (mask[i] != 0 && logp_behav != nullptr) {   // no behaviour log-probs: on-policy, every ratio is 1
+        const bool valid = mask[i] != 0;
+        if (valid && logp_behav != nullptr) {   // no behaviour log-probs: on-policy, every ratio is 1
             const float lb = logp_behav[i];
             if (isfinite(lb)) dlt = (double)logp_cur[i] - (double)lb;
             else bad = true;
         }
         if (tok_lr) tok_lr[i] = (float)dlt;
         acc += dlt;
+        if (valid) {
+            const double lc = clip_tokens ? fmin(dlt, log_eta) : dlt;
+            csum += exp(lc);
+            cmax = fmax(cmax, lc);
+        }
     }
     acc = wave_sum(acc);
     if (__any(bad) && threadIdx.x == 0 && dev_status) atomicOr(dev_status, RAPID_STATUS_NONFINITE_LOGP);
+    if (tsum) {
+        csum = wave_sum(csum);
+        cmax = wave_max(cmax);
+    }
     if (threadIdx.x == 0) {
         s64[n] = acc;
         if (s32) s32[n] = (float)acc;
+        if (tsum) {
+            tsum[n] = csum;
+            tmax[n] = cmax;
+        }
     }
 }
 
@@ -268,22 +286,28 @@ __global__ void group_advantage_kernel(const float* __restrict__ rewards, const 
     }
 }
 
-// single block: coefficients g_n, loss = sum g_n, diagnostics
+// single block: coefficients g_n, the loss, diagnostics.  Generation-level outer weight (tsum NULL):
+// g_n = -(loss_scale/N) c_n A_n, loss = sum_n g_n.  Token-level (tsum, tmax given): g_n is the
+// generation's factor -(loss_scale/N) A_n, a token's coefficient is g_n c_{n,t}, and
+// loss = sum_n g_n sum_t c_{n,t}.  g64 keeps g_n in double for the per-row pass.
 __global__ void coefficients_kernel(const double* __restrict__ s64, const float* __restrict__ adv,
                                     const float* __restrict__ coef_override, int64_t N, double log_eta,
                                     int coef_mode, double log_loss_scale, int normalized,
+                                    const double* __restrict__ tsum, const double* __restrict__ tmax,
                                     const int32_t* __restrict__ counts, float* __restrict__ g,
-                                    float* __restrict__ loss_out, rapid_iw_pg_diag* __restrict__ diag) {
+                                    double* __restrict__ g64, float* __restrict__ loss_out,
+                                    rapid_iw_pg_diag* __restrict__ diag) {
     __shared__ double sm[16];
     const double logN = log((double)N);
+    const bool per_token = tsum != nullptr && !coef_override;
     double lam = 0.0;
     if (!coef_override && normalized) {
         double mx = -INFINITY;
         for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
             const double a = (double)adv[n];
             if (a != 0.0) {
-                const double lc = coef_mode == 0 ? s64[n] : fmin(s64[n], log_eta);
-                mx = fmax(mx, lc + log(fabs(a)) + log_loss_scale - logN);
+                const double lc = per_token ? tmax[n] : (coef_mode == 0 ? s64[n] : fmin(s64[n], log_eta));
+                mx = fmax(mx, lc + log(fabs(a)) + log_loss_scale - logN);   // -inf for a generation without tokens
             }
         }
         mx = block_max(mx, sm);
@@ -298,14 +322,15 @@ __global__ void coefficients_kernel(const double* __restrict__ s64, const float*
         } else {
             const double a = (double)adv[n];
             if (a != 0.0) {
-                const double lc = coef_mode == 0 ? s : fmin(s, log_eta);
+                const double lc = per_token ? 0.0 : (coef_mode == 0 ? s : fmin(s, log_eta));
                 gn = (a > 0.0 ? -1.0 : 1.0) * exp(lc + log(fabs(a)) + log_loss_scale - logN - lam);
             } else {
                 gn = 0.0;
             }
         }
         g[n] = (float)gn;
-        loss += gn;
+        g64[n] = gn;
+        loss += per_token ? (gn != 0.0 ? gn * tsum[n] : 0.0) : gn;
         const double lw = fmin(s, log_eta);
         slw += lw;
         salw += fabs(lw);
@@ -329,6 +354,34 @@ __global__ void coefficients_kernel(const double* __restrict__ s64, const float*
             diag->grad_log_scale = (float)lam;
         }
     }
+}
+
+// the coefficient dL/dlogp of every compact token row: the generation's g_n, times the token's own
+// (clipped) ratio for the token-level outer weight; 0 for the padding rows up to the row-tile boundary
+__global__ void row_coefficients_kernel(const float* __restrict__ g, const double* __restrict__ g64,
+                                        const int32_t* __restrict__ seqc, const int32_t* __restrict__ row_index,
+                                        const int32_t* __restrict__ counts, const float* __restrict__ logp_cur,
+                                        const float* __restrict__ logp_behav, int per_token, double log_eta,
+                                        int clip_tokens, float* __restrict__ rowg) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int M = counts[CNT_M], Mr = counts[CNT_MR];
+    if (j >= Mr) return;
+    float v = 0.f;
+    if (j < M) {
+        const int32_t n = seqc[j];
+        if (!per_token) {
+            v = g[n];
+        } else {
+            double dlt = 0.0;
+            if (logp_behav != nullptr) {
+                const int32_t pos = row_index[j];
+                const float lb = logp_behav[pos];
+                if (isfinite(lb)) dlt = (double)logp_cur[pos] - (double)lb;
+            }
+            v = (float)(g64[n] * exp(clip_tokens ? fmin(dlt, log_eta) : dlt));
+        }
+    }
+    rowg[j] = v;
 }
 
 // zero the gradient rows of masked positions: one block per position
@@ -377,10 +430,11 @@ void launch_merge_lse(const float* part_max, const float* part_sum, int P, int64
 }
 
 void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N,
-                         int64_t T, float* tok_logratio_out, double* s64, float* s32, int32_t* dev_status,
-                         hipStream_t st) {
+                         int64_t T, float* tok_logratio_out, double* s64, float* s32, float eta, int clip_tokens,
+                         double* tsum, double* tmax, int32_t* dev_status, hipStream_t st) {
+    const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
     seq_logratio_kernel<<<(unsigned)N, WAVE, 0, st>>>(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64,
-                                                      s32, dev_status);
+                                                      s32, log_eta, clip_tokens, tsum, tmax, dev_status);
 }
 
 void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, int64_t N,
@@ -394,11 +448,22 @@ void launch_group_advantage(const float* rewards, const int32_t* group_ids, cons
 }
 
 void launch_coefficients(const double* s64, const float* adv, const float* coef_override, int64_t N, float eta,
-                         int coef_mode, float loss_scale, int normalized, const int32_t* counts, float* g,
-                         float* loss_out, rapid_iw_pg_diag* diag, hipStream_t st) {
+                         int coef_mode, float loss_scale, int normalized, const double* tsum, const double* tmax,
+                         const int32_t* counts, float* g, double* g64, float* loss_out, rapid_iw_pg_diag* diag,
+                         hipStream_t st) {
     const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
     coefficients_kernel<<<1, 1024, 0, st>>>(s64, adv, coef_override, N, log_eta, coef_mode,
-                                            log((double)loss_scale), normalized, counts, g, loss_out, diag);
+                                            log((double)loss_scale), normalized, tsum, tmax, counts, g, g64,
+                                            loss_out, diag);
+}
+
+void launch_row_coefficients(const float* g, const double* g64, const int32_t* seqc, const int32_t* row_index,
+                             const int32_t* counts, const float* logp_cur, const float* logp_behav, int per_token,
+                             float eta, int clip_tokens, int64_t rows_max, float* rowg, hipStream_t st) {
+    const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
+    row_coefficients_kernel<<<blocks_for(rows_max, 256), 256, 0, st>>>(g, g64, seqc, row_index, counts, logp_cur,
+                                                                       logp_behav, per_token, log_eta, clip_tokens,
+                                                                       rowg);
 }
 
 void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, int64_t d, int elem_bytes,

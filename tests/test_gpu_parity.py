@@ -154,7 +154,7 @@ def _run_pair(rb, spec, seed=0, layout="dv", min_ws=False, dw_dtype=torch.float3
                                       g["group_ids"], w["K"], buffers=buf, w_layout=lay,
                                       coef_override=None if coef is None else torch.from_numpy(coef).cuda(), **kw)
     torch.cuda.synchronize()
-    okw = {k: v for k, v in kw.items() if k not in ("accumulate_dw", "logits_cache")}
+    okw = {k: v for k, v in kw.items() if k not in ("accumulate_dw", "logits_cache")}   # the rest means the same to the oracle
     ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(w["rewards"]), _np(w["group_ids"]), w["K"],
                                  coef_override=coef, **okw)
     return w, out, ref
@@ -337,6 +337,31 @@ def test_fwd_bwd_logits_cache(rb, name, layout):
     for kw in (dict(temperature=0.8), dict(normalized_grads=True), dict(coef_mode=1, eta=1.05)):
         w, out, ref = _run_pair(rb, spec, layout=layout, logits_cache=True, **kw)
         _check_pair(rb, spec, out, ref, layout)
+
+
+@pytest.mark.parametrize("name", ["f32_ragged", "bf16_small", "bf16_ragged"])
+@pytest.mark.parametrize("cache", [False, True])
+def test_fwd_bwd_token_level_ratio(rb, name, cache):
+    """ratio_level 1 (every token carries its own ratio; not an estimator of the paper): every
+    element against the oracle's token_coefficients path, both coefficient modes, plain and
+    normalised, in both backward modes; on-policy it gives the generation-level gradients."""
+    spec = SPECS[name]
+    if cache and spec.dtype != "bf16":
+        pytest.skip("the cache is a bf16 mode")
+    print(f"fwd_bwd token-level {name} cache={cache}", flush=True)
+    for kw in (dict(), dict(coef_mode=1, eta=1.05), dict(normalized_grads=True), dict(temperature=0.8, loss_scale=0.5)):
+        w, out, ref = _run_pair(rb, spec, ratio_level=1, logits_cache=cache, **kw)
+        _check_pair(rb, spec, out, ref)
+        if kw.get("normalized_grads"):
+            assert abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]) <= 1e-3
+    w, g = _make(spec)
+    lp, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])
+    a = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], lp, g["rewards"], g["group_ids"], w["K"],
+                                    logits_cache=cache)
+    b = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], lp, g["rewards"], g["group_ids"], w["K"],
+                                    logits_cache=cache, ratio_level=1)
+    torch.cuda.synchronize()
+    assert torch.equal(a.dhidden, b.dhidden) and torch.equal(a.dW, b.dW)      # all ratios exactly 1
 
 
 @pytest.mark.parametrize("scale,flagged", [(25.0, False), (250.0, True)])

@@ -38,10 +38,11 @@ def test_exports_every_declared_symbol(rb):
 
 def test_struct_layouts_match_header(rb):
     assert C.sizeof(rb.IwPgDiag) == 32
-    assert C.sizeof(rb.IwPgOpts) == 48
+    assert C.sizeof(rb.IwPgOpts) == 56 and rb.IwPgOpts.coef_override.offset == 48
     o = rb.default_opts()
     assert o.eta == 2.0 and o.loss_scale == 1.0 and o.temperature == 1.0
     assert o.coef_mode == 0 and o.baseline_mode == 0 and o.w_layout == rb.W_DV and o.dw_dtype == rb.DTYPE_F32
+    assert o.logits_cache == 0 and o.ratio_level == 0 and not o.coef_override
 
 
 def test_workspace_sizes(rb):
@@ -90,7 +91,9 @@ def test_host_validation_returns_codes_without_a_gpu(rb):
     o.logits_cache = 2
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -3
     o = rb.default_opts()
-    assert o.logits_cache == 0
+    o.ratio_level = 2
+    assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -3
+    o = rb.default_opts()
     o.loss_scale = -1.0
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
     assert lib.rapid_set_tuning(12345, 0) == -3
