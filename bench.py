@@ -4,9 +4,10 @@
 A step = one rapid_iw_pg_loss_fwd_bwd call (all stages of the hot path) on one synthetic
 Qwen2.5-1.5B-shaped mini-batch (d=1536, V=151936, 32 prompts x 8 generations, response length
 U[256,2048]) whose inputs, including the stored behaviour log-probs, are resident in HBM.  The call
-is timed with opts.logits_cache = 1 (the forward keeps every row's probability ratios in the
-workspace, 157 GiB at this shape, and the backward contracts them: 6 d V flop per token executed)
-and, as a second figure, with the default 0 (27 GiB, the backward regenerates the logits: 8 d V).
+is timed with opts.logits_cache = 1 (the forward keeps every token row's probability ratios in the
+workspace, 93 GiB at this shape with opts.max_tokens = the batch's token count, and the backward
+contracts them: 6 d V flop per token executed) and, as a second figure, with the default 0 (27 GiB,
+the backward regenerates the logits: 8 d V).
 Prints ONE JSON line: response tokens/s, the roofline of the dominant kernel (HIP-event timing of
 every stage, taken inside the timed region) and the float64 oracle timed on this machine's cores on
 a bounded sample of the same workload.
@@ -146,7 +147,8 @@ def main():
     def fused_mode(cache):
         """Times rapid_iw_pg_loss_fwd_bwd in one backward mode; None if the cache does not fit."""
         if cache:
-            need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16)
+            # the cache is sized for the batch's token count, which a trainer knows from its sampler
+            need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16, max_tokens=M)
             free, _ = torch.cuda.mem_get_info()
             if not need or need + (8 << 30) > free:
                 return None
@@ -158,10 +160,10 @@ def main():
                 vpad = (V + 255) // 256 * 256
                 ldv = vpad + 64 if (vpad // 64) % 2 == 0 else vpad
                 ws_bytes = mn + (args.chunk_rows - 256) * ldv * 2
-        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes, logits_cache=cache)
+        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes, logits_cache=cache, max_tokens=M)
         dt, stages = timed(lambda: rb.rapid_iw_pg_loss_fwd_bwd(
             w["hidden"], w["W"], w["tokens"], w["mask"], w["logp_behav"], w["rewards"], w["group_ids"], K,
-            buffers=buf, optional_outputs=False, logits_cache=cache))
+            buffers=buf, optional_outputs=False, logits_cache=cache, max_tokens=M))
         ws_gib = buf.workspace.numel() / 2**30
         del buf                      # the workspace goes back before the other mode takes its own
         torch.cuda.empty_cache()

@@ -48,6 +48,8 @@ extern "C" {
 #define RAPID_STATUS_BAD_GROUP 2
 #define RAPID_STATUS_NONFINITE_REWARD 4
 #define RAPID_STATUS_NONFINITE_LOGP 8
+#define RAPID_STATUS_TOKEN_BOUND 32 /* more valid tokens than opts->max_tokens promised (logits_cache = 1): the tokens
+                                      past the bound were left out; the call's outputs are not usable */
 #define RAPID_STATUS_LOGIT_RANGE 16 /* logits_cache = 1 only: in some row the sampled token is more than e^79 times
                                        less likely than the most likely one; loss and log-probs are exact, that
                                        row's share of dhidden and dW is truncated */
@@ -95,6 +97,11 @@ typedef struct rapid_iw_pg_opts {
                               or min(rho_{n,t}, eta) held constant (coef_mode 1); the advantages stay those of
                               Eq. (5) with generation-level clipped weights.  grad_log_scale is then
                               log max |dLoss/dlogp_{n,t}| over tokens.  Ignored with coef_override */
+    int64_t max_tokens;    /* 0, or the caller's upper bound on the number of valid tokens (sum of mask), which it
+                              knows from its sampler: with logits_cache = 1 the workspace then has to hold
+                              the ratios of that many rows only instead of N*T
+                              (rapid_workspace_bytes_max_tokens).  Checked on the device:
+                              RAPID_STATUS_TOKEN_BOUND */
     const float* coef_override; /* DEVICE [N] or NULL: use these per-generation coefficients g_n
                               = dLoss/dlogp_{n,t} instead of the estimator's (loss = sum g_n) */
 } rapid_iw_pg_opts;
@@ -164,9 +171,13 @@ int rapid_mfma_probe(int random_operands, int iters, double* tflops_out, double*
  * recommended size (backward row-chunks large enough to fill the chip); rapid_workspace_min_bytes
  * the smallest the call accepts (smaller chunks, same results).  RAPID_OP_GROUP_ADVANTAGE needs
  * none (returns 0).  RAPID_OP_IW_PG_FWD_BWD_CACHED is the size rapid_iw_pg_loss_fwd_bwd needs with
- * opts->logits_cache = 1 (bf16 only; minimum = recommended).  Returns 0 for invalid arguments. */
+ * opts->logits_cache = 1 (bf16 only; minimum = recommended).  rapid_workspace_bytes_max_tokens is
+ * rapid_workspace_bytes for a call that passes the same opts->max_tokens (only the cached size
+ * depends on it; 0 = no bound).  Returns 0 for invalid arguments. */
 size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype);
 size_t rapid_workspace_min_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype);
+size_t rapid_workspace_bytes_max_tokens(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype,
+                                        int64_t max_tokens);
 
 /*
  * Behaviour / current-policy log-probabilities of the sampled tokens (Sec. 3.1: pi(y_t | .) is

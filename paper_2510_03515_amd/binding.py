@@ -20,9 +20,10 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 W_DV, W_VD = 0, 1
 OP_LOGPROB_FWD, OP_GROUP_ADVANTAGE, OP_IW_PG_FWD_BWD, OP_IW_PG_FWD_BWD_CACHED = 0, 1, 2, 3
 STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LOGP, STATUS_LOGIT_RANGE = 1, 2, 4, 8, 16
+STATUS_TOKEN_BOUND = 32
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
-           "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_logprob_fwd",
+           "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_workspace_bytes_max_tokens", "rapid_logprob_fwd",
            "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step"]
 STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
           "dw", "f32_path", "dw_convert"]
@@ -38,7 +39,8 @@ class IwPgOpts(C.Structure):
     _fields_ = [("eta", C.c_float), ("coef_mode", C.c_int), ("baseline_mode", C.c_int),
                 ("loss_scale", C.c_float), ("temperature", C.c_float), ("w_layout", C.c_int),
                 ("dw_dtype", C.c_int), ("accumulate_dw", C.c_int), ("normalized_grads", C.c_int),
-                ("logits_cache", C.c_int), ("ratio_level", C.c_int), ("coef_override", C.c_void_p)]
+                ("logits_cache", C.c_int), ("ratio_level", C.c_int), ("max_tokens", C.c_int64),
+                ("coef_override", C.c_void_p)]
 
 
 class IwPgDiag(C.Structure):
@@ -68,6 +70,8 @@ def load():
     for fn in (lib.rapid_workspace_bytes, lib.rapid_workspace_min_bytes):
         fn.argtypes = [ci, i64, i64, i64, i64, i64, ci]
         fn.restype = sz
+    lib.rapid_workspace_bytes_max_tokens.argtypes = [ci, i64, i64, i64, i64, i64, ci, i64]
+    lib.rapid_workspace_bytes_max_tokens.restype = sz
     lib.rapid_logprob_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, f32, vp, vp, vp, vp, sz, vp]
     lib.rapid_logprob_fwd.restype = ci
     lib.rapid_group_advantage.argtypes = [vp, vp, vp, i64, i64, f32, ci, vp, vp, vp, vp, vp, vp, vp]
@@ -148,8 +152,10 @@ def rapid_profile_read():
     return {STAGES[i]: (ms[i], cnt[i]) for i in range(n)}
 
 
-def rapid_workspace_bytes(op, N, T, d, V, K, dtype, minimum=False):
+def rapid_workspace_bytes(op, N, T, d, V, K, dtype, minimum=False, max_tokens=0):
     lib = load()
+    if max_tokens:
+        return lib.rapid_workspace_bytes_max_tokens(op, N, T, d, V, K, dtype, int(max_tokens))
     fn = lib.rapid_workspace_min_bytes if minimum else lib.rapid_workspace_bytes
     return fn(op, N, T, d, V, K, dtype)
 
@@ -215,14 +221,15 @@ class IwPgBuffers:
     """Output and workspace tensors of rapid_iw_pg_loss_fwd_bwd, allocated once and reusable."""
 
     def __init__(self, hidden, W, K, w_layout=W_DV, dw_dtype=torch.float32, workspace_bytes=None,
-                 minimum_workspace=False, logits_cache=False):
+                 minimum_workspace=False, logits_cache=False, max_tokens=0):
         N, T, d = hidden.shape
         V = W.shape[1] if w_layout == W_DV else W.shape[0]
         dev = hidden.device
         dt = _dtype_code(hidden)
         if workspace_bytes is None:
             op = OP_IW_PG_FWD_BWD_CACHED if logits_cache else OP_IW_PG_FWD_BWD
-            workspace_bytes = rapid_workspace_bytes(op, N, T, d, V, K, dt, minimum=minimum_workspace)
+            workspace_bytes = rapid_workspace_bytes(op, N, T, d, V, K, dt, minimum=minimum_workspace,
+                                                    max_tokens=max_tokens if logits_cache else 0)
         self.workspace = alloc_workspace(workspace_bytes, dev)
         self.loss = torch.empty(1, dtype=torch.float32, device=dev)
         self.dhidden = torch.empty_like(hidden)
@@ -243,7 +250,7 @@ class IwPgBuffers:
 def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, K, buffers=None,
                              eta=2.0, coef_mode=0, baseline_mode=0, loss_scale=1.0, temperature=1.0,
                              w_layout=W_DV, accumulate_dw=False, normalized_grads=False, coef_override=None,
-                             optional_outputs=True, logits_cache=False, ratio_level=0):
+                             optional_outputs=True, logits_cache=False, ratio_level=0, max_tokens=0):
     """Enqueues the fused forward+backward on the current stream and returns the IwPgBuffers that
     hold the outputs (loss, dhidden, dW, logp_cur, tok_logratio, seq_logratio, adv, diag)."""
     N, T, d = hidden.shape
@@ -268,6 +275,7 @@ def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group
     o.normalized_grads = int(bool(normalized_grads))
     o.logits_cache = int(bool(logits_cache))
     o.ratio_level = int(ratio_level)
+    o.max_tokens = int(max_tokens)
     if coef_override is not None:
         _need(coef_override, torch.float32, "coef_override")
         o.coef_override = coef_override.data_ptr()

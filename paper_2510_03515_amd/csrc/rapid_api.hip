@@ -154,6 +154,12 @@ void size_chunks(Plan& p, int64_t Mc) {
     p.total = cur;
 }
 
+// rows the cache must hold: the caller's bound on the number of valid tokens (0 = none given), at most N*T
+int64_t cache_rows(const Plan& p, int64_t max_tokens) {
+    const int64_t t = (max_tokens > 0 && max_tokens < p.Mmax) ? max_tokens : p.Mmax;
+    return round_up(t, ROW_TILE);
+}
+
 int64_t recommended_chunk(const Plan& p) { return p.dtype == RAPID_DTYPE_BF16 ? 65536 : 4096; }
 
 // largest chunk that fits into `avail` bytes; 0 if even the minimum does not
@@ -204,7 +210,8 @@ struct FwdIo {
     const void* hidden; const void* W; const int32_t* tokens; const uint8_t* mask;
     int w_layout; float temperature;
     float* logp_out; float* lse_out; int32_t* dev_status;
-    bf16_t* zc = nullptr;   // if set: [Mmax_pad, ldv], the forward also stores the ratios p_v / p_y there
+    bf16_t* zc = nullptr;   // if set: [row_cap, ldv], the forward also stores the ratios p_v / p_y there
+    int64_t row_cap = INT64_MAX;   // compact rows the caller's buffers hold (the cache may be sized for fewer than N*T)
 };
 
 // compaction, operand packing and the streaming log-softmax forward; leaves lse_c, tokc, seqc,
@@ -218,7 +225,8 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
     const float inv_temp = 1.0f / io.temperature;
     {
         Span sp(ST_COMPACT, st);
-        launch_compaction(io.mask, p.N, p.T, at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), row_index, counts, st);
+        launch_compaction(io.mask, p.N, p.T, at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), row_index, counts,
+                          io.row_cap, io.dev_status, st);
         launch_gather_tokens(io.tokens, row_index, counts, p.Mmax_pad, p.T, p.V, tokc, seqc, io.dev_status, st);
         launch_fill_f32(io.logp_out, p.Mmax, 0.f, st);
         if (io.lse_out) launch_fill_f32(io.lse_out, p.Mmax, 0.f, st);
@@ -319,7 +327,7 @@ using namespace rapid;
 
 extern "C" {
 
-int rapid_version(void) { return 4; }
+int rapid_version(void) { return 5; }
 
 const char* rapid_last_error(void) { return g_err; }
 
@@ -337,6 +345,7 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
     o->normalized_grads = 0;
     o->logits_cache = 0;
     o->ratio_level = 0;
+    o->max_tokens = 0;
     o->coef_override = nullptr;
 }
 
@@ -425,14 +434,19 @@ int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stage
     return RAPID_OK;
 }
 
+size_t rapid_workspace_bytes_max_tokens(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype,
+                                        int64_t max_tokens) {
+    if (op != RAPID_OP_IW_PG_FWD_BWD_CACHED) return rapid_workspace_bytes(op, N, T, d, V, K, dtype);
+    Plan p;   // the chunk buffer holds every row that can hold a token
+    if (max_tokens < 0 || dtype != RAPID_DTYPE_BF16 || !make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype))
+        return 0;
+    size_chunks(p, cache_rows(p, max_tokens));
+    return p.total + 1024;
+}
+
 size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
     if (op == RAPID_OP_GROUP_ADVANTAGE) return 0;
-    if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) {   // the chunk buffer holds every row
-        Plan p;
-        if (dtype != RAPID_DTYPE_BF16 || !make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype)) return 0;
-        size_chunks(p, p.Mmax_pad);
-        return p.total + 1024;
-    }
+    if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) return rapid_workspace_bytes_max_tokens(op, N, T, d, V, K, dtype, 0);
     if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
     Plan p;
     if (!make_plan(p, op, N, T, d, V, K, dtype)) return 0;
@@ -462,7 +476,8 @@ int rapid_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len
     }
     int rc = check_arch();
     if (rc) return rc;
-    launch_compaction(mask, N, T, seq_len_out, cu_seqlen_out, row_index_out, nullptr, (hipStream_t)stream);
+    launch_compaction(mask, N, T, seq_len_out, cu_seqlen_out, row_index_out, nullptr, INT64_MAX, nullptr,
+                      (hipStream_t)stream);
     return check_launch("rapid_compaction");
 }
 
@@ -571,9 +586,13 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         return RAPID_ERR_WORKSPACE;
     }
     const bool cached = o.logits_cache == 1;
-    if (cached && Mfit < p.Mmax_pad) {
+    if (o.max_tokens < 0) {
+        set_error("max_tokens must be >= 0");
+        return RAPID_ERR_SHAPE;
+    }
+    if (cached && Mfit < cache_rows(p, o.max_tokens)) {
         set_error("workspace of %zu bytes is below the %zu the logits cache needs", workspace_bytes,
-                  rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dtype));
+                  rapid_workspace_bytes_max_tokens(RAPID_OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dtype, o.max_tokens));
         return RAPID_ERR_WORKSPACE;
     }
     size_chunks(p, Mfit);
@@ -597,7 +616,10 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
 
     // forward: current-policy log-probs of the sampled tokens
     FwdIo io{hidden, W, tokens, mask, o.w_layout, o.temperature, logp_cur, nullptr, dev_status};
-    if (cached) io.zc = at<bf16_t>(ws, p.chunk0);   // the chunk buffer holds all rows
+    if (cached) {   // the chunk buffer holds the ratios of every row, up to the p.Mc rows it was sized for
+        io.zc = at<bf16_t>(ws, p.chunk0);
+        io.row_cap = p.Mc;
+    }
     run_forward(p, ws, io, st);
 
     // generation-level log ratios, clipped-weight group baseline, coefficients and loss

@@ -25,8 +25,9 @@ constexpr int ROW_TILE = 256;  // compact rows are padded to this
 constexpr int K_TILE = 64;     // contraction tile of the MFMA kernels (bf16 elements)
 
 // ---- reductions.hip ---------------------------------------------------------------------------
+// counts (optional): M and M rounded up to a row tile, both clipped to row_cap (sets RAPID_STATUS_TOKEN_BOUND)
 void launch_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len, int32_t* cu_seqlen,
-                       int32_t* row_index, int32_t* counts, hipStream_t st);
+                       int32_t* row_index, int32_t* counts, int64_t row_cap, int32_t* dev_status, hipStream_t st);
 void launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
 void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const int32_t* counts,
                           int64_t Mmax_pad, int64_t T, int64_t V, int32_t* tokc, int32_t* seqc,

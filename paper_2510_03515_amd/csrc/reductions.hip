@@ -61,9 +61,11 @@ __global__ void seq_len_kernel(const uint8_t* __restrict__ mask, int64_t N, int6
     if (threadIdx.x == 0) seq_len[n] = cnt;
 }
 
-// single block: exclusive prefix sum of seq_len, and the counters M / M rounded up to a row tile
+// single block: exclusive prefix sum of seq_len, and the counters M / M rounded up to a row tile.
+// The counters never exceed row_cap (the rows the caller's buffers hold): tokens past it are left
+// out of everything downstream and RAPID_STATUS_TOKEN_BOUND is set.
 __global__ void scan_kernel(const int32_t* __restrict__ seq_len, int64_t N, int32_t* __restrict__ cu,
-                            int32_t* __restrict__ counts) {
+                            int32_t* __restrict__ counts, int64_t row_cap, int32_t* __restrict__ dev_status) {
     __shared__ int sm[1024];
     __shared__ int carry;
     if (threadIdx.x == 0) carry = 0;
@@ -88,8 +90,13 @@ __global__ void scan_kernel(const int32_t* __restrict__ seq_len, int64_t N, int3
     if (threadIdx.x == 0) {
         if (cu) cu[N] = carry;
         if (counts) {
-            counts[CNT_M] = carry;
-            counts[CNT_MR] = (carry + ROW_TILE - 1) / ROW_TILE * ROW_TILE;
+            int m = carry;
+            if ((int64_t)m > row_cap) {
+                m = (int)row_cap;
+                if (dev_status) atomicOr(dev_status, RAPID_STATUS_TOKEN_BOUND);
+            }
+            counts[CNT_M] = m;
+            counts[CNT_MR] = (m + ROW_TILE - 1) / ROW_TILE * ROW_TILE;
         }
     }
 }
@@ -405,9 +412,9 @@ inline unsigned blocks_for(int64_t n, int bs) { return (unsigned)((n + bs - 1) /
 }  // namespace
 
 void launch_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len, int32_t* cu_seqlen,
-                       int32_t* row_index, int32_t* counts, hipStream_t st) {
+                       int32_t* row_index, int32_t* counts, int64_t row_cap, int32_t* dev_status, hipStream_t st) {
     seq_len_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, seq_len);
-    scan_kernel<<<1, 1024, 0, st>>>(seq_len, N, cu_seqlen, counts);
+    scan_kernel<<<1, 1024, 0, st>>>(seq_len, N, cu_seqlen, counts, row_cap, dev_status);
     if (row_index) row_index_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, cu_seqlen, row_index);
 }
 

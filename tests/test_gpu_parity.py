@@ -400,6 +400,35 @@ def test_logits_cache_unlikely_sampled_tokens(rb, scale, flagged):
             assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
 
 
+def test_logits_cache_sized_for_a_token_bound(rb):
+    """opts.max_tokens: the cache holds the promised number of tokens instead of N*T rows; with the
+    exact count the results are the bits of the unbounded cache, a workspace sized for fewer rows
+    than the bound is refused, and a broken promise is reported on the device, nothing else."""
+    spec = wl.small_spec("bound", "bf16", d=128, V=1000, prompts=6, G=4, len_lo=30, len_hi=200)
+    w, g = _make(spec)
+    N, T, d = g["hidden"].shape
+    M = int(g["mask"].sum().item())
+    assert M + 512 < N * T
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+    args = (g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"], g["group_ids"], w["K"])
+    full = rb.rapid_iw_pg_loss_fwd_bwd(*args, logits_cache=True)
+    small_buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], logits_cache=True, max_tokens=M)
+    assert small_buf.workspace.numel() < full.workspace.numel()
+    out = rb.rapid_iw_pg_loss_fwd_bwd(*args, buffers=small_buf, logits_cache=True, max_tokens=M)
+    torch.cuda.synchronize()
+    assert out.dev_status.item() == 0
+    for k in ("loss", "dhidden", "dW", "logp_cur", "seq_logratio", "adv"):
+        assert torch.equal(getattr(out, k), getattr(full, k)), k
+    with pytest.raises(rb.RapidError) as e:       # same workspace, larger promise
+        rb.rapid_iw_pg_loss_fwd_bwd(*args, buffers=small_buf, logits_cache=True, max_tokens=M + 600)
+    assert e.value.code == -4
+    tiny = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], logits_cache=True, max_tokens=M - 300)
+    bad = rb.rapid_iw_pg_loss_fwd_bwd(*args, buffers=tiny, logits_cache=True, max_tokens=M - 300)
+    torch.cuda.synchronize()
+    assert bad.dev_status.item() & rb.STATUS_TOKEN_BOUND
+    assert bad.read_diag()["n_tokens"] == (M - 300 + 255) // 256 * 256        # the rows the cache was sized for
+
+
 def test_logits_cache_workspace_and_errors(rb):
     spec = SPECS["bf16_small"]
     w, g = _make(spec)

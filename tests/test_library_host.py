@@ -38,11 +38,11 @@ def test_exports_every_declared_symbol(rb):
 
 def test_struct_layouts_match_header(rb):
     assert C.sizeof(rb.IwPgDiag) == 32
-    assert C.sizeof(rb.IwPgOpts) == 56 and rb.IwPgOpts.coef_override.offset == 48
+    assert C.sizeof(rb.IwPgOpts) == 64 and rb.IwPgOpts.max_tokens.offset == 48 and rb.IwPgOpts.coef_override.offset == 56
     o = rb.default_opts()
     assert o.eta == 2.0 and o.loss_scale == 1.0 and o.temperature == 1.0
     assert o.coef_mode == 0 and o.baseline_mode == 0 and o.w_layout == rb.W_DV and o.dw_dtype == rb.DTYPE_F32
-    assert o.logits_cache == 0 and o.ratio_level == 0 and not o.coef_override
+    assert o.logits_cache == 0 and o.ratio_level == 0 and o.max_tokens == 0 and not o.coef_override
 
 
 def test_workspace_sizes(rb):
@@ -54,6 +54,13 @@ def test_workspace_sizes(rb):
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, 0, 1, 1, 1, 1, 0) == 0       # invalid shape
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, 4, 4, 8, 8, 1, 7) == 0       # invalid dtype
     assert rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, *args) < rec
+    # the cache: every padded position by default, the promised number of tokens (rounded to 256 rows) with a bound
+    full = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args)
+    half = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, max_tokens=300630)
+    ldv = 152064 + 64
+    assert full - half == (256 * 2048 - 300800) * ldv * 2
+    assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, max_tokens=10**9) == full
+    assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, *args, max_tokens=1000) == rec       # other ops ignore it
 
 
 def test_host_validation_returns_codes_without_a_gpu(rb):
@@ -93,6 +100,9 @@ def test_host_validation_returns_codes_without_a_gpu(rb):
     o = rb.default_opts()
     o.ratio_level = 2
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -3
+    o = rb.default_opts()
+    o.max_tokens = -5
+    assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
     o = rb.default_opts()
     o.loss_scale = -1.0
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
