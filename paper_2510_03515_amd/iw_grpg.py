@@ -10,7 +10,7 @@ staleness of Sec. 4.3 (mean |log clipped weight|) and the clip proportion grow w
 the paper's study of the number of inner steps.  Everything numeric runs in the library; this
 module only sequences calls and slices tensors.
 
-    python -m paper_2510_03515_amd.iw_grpg [--inner-steps 8] [--lr 0.02]
+    python -m paper_2510_03515_amd.iw_grpg [--inner-steps 8] [--lr 0.02] [--logits-cache]
 """
 from __future__ import annotations
 
@@ -31,14 +31,16 @@ def _is_reward(w, W, logp_b):
     return (rho * w["rewards"].double()).sum().item() / rho.sum().item()
 
 
-def iw_grpg(w, inner_steps=8, lr=0.02, eta=2.0, coef_mode=1):
+def iw_grpg(w, inner_steps=8, lr=0.02, eta=2.0, coef_mode=1, logits_cache=False):
     """Runs Alg. 1's IW-GRPG on the workload dict `w` (device tensors of workloads.make_workload with
     sigma = 0 and tokens_from = "cur": the batch is sampled from W itself, and group_ids = n // G).
     The number of prompts must be a multiple of `inner_steps`.  Returns (per-step log, summary dict,
     final weights in the workload dtype).
 
     coef_mode 1 (clipped outer weight) is the default here: with the unclipped ratio of coef_mode 0
-    a few generations whose ratio has grown dominate the later steps."""
+    a few generations whose ratio has grown dominate the later steps.  logits_cache (bf16 only): the
+    backward of every step contracts the probability ratios its forward kept instead of regenerating
+    the logits."""
     spec = w["spec"]
     K, G, H = w["K"], spec.G, int(inner_steps)
     assert K % H == 0, "prompts must divide into equal mini-batches"
@@ -48,13 +50,13 @@ def iw_grpg(w, inner_steps=8, lr=0.02, eta=2.0, coef_mode=1):
     logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], W, w["tokens"], w["mask"])   # log mu, stored at "inference"
     reward_mu = _is_reward(w, W, logp_b)
     gid_local = w["group_ids"][:Nh].contiguous()                                # 0 .. Kh-1 in every mini-batch
-    buf = rb.IwPgBuffers(w["hidden"][:Nh], W, Kh)
+    buf = rb.IwPgBuffers(w["hidden"][:Nh], W, Kh, logits_cache=logits_cache)
     log = []
     for h in range(H):
         sl = slice(h * Nh, (h + 1) * Nh)
         out = rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"][sl], W, w["tokens"][sl], w["mask"][sl], logp_b[sl],
                                           w["rewards"][sl], gid_local, Kh, buffers=buf, eta=eta,
-                                          coef_mode=coef_mode)
+                                          coef_mode=coef_mode, logits_cache=logits_cache)
         dg = out.read_diag()
         log.append(dict(step=h + 1, loss=out.loss.item(), staleness=dg["mean_abs_log_w"],
                         clip_fraction=dg["n_clipped"] / dg["n_sequences"], max_abs_s=dg["max_abs_s"]))
@@ -69,12 +71,13 @@ def main():
     ap.add_argument("--inner-steps", type=int, default=8)
     ap.add_argument("--lr", type=float, default=0.02)
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--logits-cache", action="store_true", help="bf16 only: keep the forward's ratios for the backward")
     args = ap.parse_args()
     rb.load()
     spec = wl.small_spec("bandit", args.dtype, d=256, V=4096, prompts=64, G=8, len_lo=8, len_hi=48, sigma=0.0,
                          reward="bernoulli", tokens_from="cur")
     w = wl.make_workload(spec, seed=0, device="cuda")
-    log, summary, _ = iw_grpg(w, inner_steps=args.inner_steps, lr=args.lr)
+    log, summary, _ = iw_grpg(w, inner_steps=args.inner_steps, lr=args.lr, logits_cache=args.logits_cache)
     print("step  loss        staleness  clip_frac  max|s|")
     for r in log:
         print(f"{r['step']:4d}  {r['loss']:+.4e}  {r['staleness']:.4f}     {r['clip_fraction']:.3f}      {r['max_abs_s']:.3f}")

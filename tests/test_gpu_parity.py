@@ -455,6 +455,10 @@ def test_inner_loop_on_synthetic_bandit(rb):
                          tokens_from="cur")
     w, g = _make(spec, seed=1)
     log, summary, W_end = loop.iw_grpg(g, inner_steps=6, lr=0.05)
+    log_c, _, W_end_c = loop.iw_grpg(g, inner_steps=6, lr=0.05, logits_cache=True)    # same run on the cached ratios
+    assert [r["loss"] for r in log_c][:1] == [r["loss"] for r in log][:1]
+    assert max(abs(a["staleness"] - b["staleness"]) for a, b in zip(log, log_c)) < 0.02
+    assert _rel(_np(W_end_c), _np(W_end)) < 1e-2
     assert log[0]["staleness"] == 0.0 and log[0]["clip_fraction"] == 0.0 and log[0]["max_abs_s"] == 0.0
     assert abs(log[0]["loss"]) <= 1e-6                 # complete groups, all weights 1: the advantages cancel
     st = [r["staleness"] for r in log]
@@ -506,16 +510,18 @@ def test_row_major_w_for_dhidden(rb):
     assert torch.equal(out.dhidden, out2.dhidden) and torch.equal(out.dW, out2.dW)
 
 
-def test_hip_graph_replay_matches_eager(rb):
+@pytest.mark.parametrize("mode", [dict(), dict(logits_cache=True, ratio_level=1, coef_mode=1)])
+def test_hip_graph_replay_matches_eager(rb, mode):
     """The fused call only enqueues kernels on the caller's stream (no allocation, no host read of
     device data, no memset nodes), so it can be captured into a HIP graph; every replay, with eager
-    work in between, gives the bits of the eager call."""
+    work in between, gives the bits of the eager call (default options, and the cache with the
+    token-level weight)."""
     spec = SPECS["bf16_ragged"]
     w, g = _make(spec)
     logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
-    buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"])
+    buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], logits_cache=mode.get("logits_cache", False))
     call = lambda: rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"],
-                                               g["group_ids"], w["K"], buffers=buf)
+                                               g["group_ids"], w["K"], buffers=buf, **mode)
     call()
     torch.cuda.synchronize()
     ref = {k: getattr(buf, k).clone() for k in ("loss", "dhidden", "dW", "logp_cur", "seq_logratio", "adv")}
