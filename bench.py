@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (2 = headline)")
+    ap.add_argument("--calibrated", action="store_true",
+                    help="the workload's calibrated companion: same shapes and seed, behaviour weights close enough "
+                         "that the generation-level ratios are O(1) (every generation carries gradient, dz is dense)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=["cache", "recompute"], default="cache",
                     help="backward of the timed call: 'cache' = opts.logits_cache 1 (probability ratios kept in the "
@@ -109,7 +112,7 @@ def main():
 
     rb.load()   # raises if the HIP library is not built: there is no other path
     torch.cuda.set_device(0)
-    spec = wl.CONFIGS[args.config]
+    spec = wl.calibrated(wl.CONFIGS[args.config]) if args.calibrated else wl.CONFIGS[args.config]
     w = wl.make_workload(spec, seed=0, device="cuda")
     N, T, d, V, K = spec.N, spec.T, spec.d, spec.V, w["K"]
     M = int(w["mask"].sum().item())

@@ -33,17 +33,23 @@ def _row_oracle(w, W64, n, t):
     return lp[0, 0], lse[0, 0]
 
 
-@pytest.mark.parametrize("cfg,cache", [(2, False), (2, True), (1, False), (1, True), (3, False)])
-def test_full_size_sampled_parity(rb, cfg, cache):
-    spec = wl.CONFIGS[cfg]
+@pytest.mark.parametrize("cfg,cache,cal", [(2, False, False), (2, True, False), (2, True, True), (2, False, True),
+                                           (1, False, False), (1, True, False), (3, False, False), (3, True, True)])
+def test_full_size_sampled_parity(rb, cfg, cache, cal):
+    """cal: the calibrated companion of the workload (same shapes and seed, behaviour weights close
+    enough that the generation-level ratios are O(1) and a few per cent clip: the paper's regime,
+    where every generation carries gradient and dz is dense)."""
+    spec = wl.calibrated(wl.CONFIGS[cfg]) if cal else wl.CONFIGS[cfg]
     print("generating", spec.name, "logits_cache" if cache else "", flush=True)
     w = wl.make_workload(spec, seed=0, device="cuda")
     N, T, K = spec.N, spec.T, w["K"]
+    n_tok = int(w["mask"].sum().item())
     logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"])
-    buf = rb.IwPgBuffers(w["hidden"], w["W"], K, logits_cache=cache)
+    buf = rb.IwPgBuffers(w["hidden"], w["W"], K, logits_cache=cache, max_tokens=n_tok)
     print("fused call", flush=True)
     out = rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b, w["rewards"],
-                                      w["group_ids"], K, buffers=buf, normalized_grads=True, logits_cache=cache)
+                                      w["group_ids"], K, buffers=buf, normalized_grads=True, logits_cache=cache,
+                                      max_tokens=n_tok)
     lp_cur2, lse_gpu = rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], want_lse=True)
     torch.cuda.synchronize()
     assert out.dev_status.item() == 0
@@ -97,6 +103,9 @@ def test_full_size_sampled_parity(rb, cfg, cache):
     assert abs(dg["grad_log_scale"] - lam) <= 1e-3
     assert abs(out.loss.item() - loss_ref) <= 1e-3 * abs(loss_ref)
     assert dg["n_clipped"] == int((s_gpu > math.log(2.0)).sum())
+    if cal:       # the regime the companion is made for
+        assert np.abs(s_gpu).max() < 6.0 and 0.01 * N <= dg["n_clipped"] <= 0.25 * N
+        assert abs(lam) < 12.0 and (np.abs(g_ref) > 1e-3).sum() > N // 4      # most generations carry gradient
 
     # (e) sampled dHidden rows: g_n (W[:, y] - W p) with p from the oracle for that row
     print("sampled dH rows", flush=True)
