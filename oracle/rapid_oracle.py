@@ -77,6 +77,38 @@ def logprob(hidden, W, tokens, mask, temperature=1.0, row_chunk=2048):
     return logp, lse
 
 
+def round_to_bf16(x):
+    """x rounded to the nearest bfloat16 (ties to even), returned as float64: the value a bf16
+    operand of the contraction kernels holds.  float64 -> float32 (IEEE rounding of numpy), then the
+    low 16 bits of the float32 pattern are rounded away."""
+    x32 = np.ascontiguousarray(np.asarray(x, np.float32))
+    bits = x32.view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).astype(_F).reshape(x32.shape)
+
+
+def rmsnorm(x, weight, eps=1e-6):
+    """Root-mean-square layer normalisation over the last axis (Zhang & Sennrich 2019), the final
+    norm of the Qwen2.5 models the paper trains: h = x * weight / sqrt(mean(x^2) + eps).  Not part of
+    the paper's method: the operand the fused call can normalise on the way in."""
+    x = _as64(x)
+    inv = 1.0 / np.sqrt((x * x).mean(axis=-1, keepdims=True) + eps)
+    return x * inv * _as64(weight)
+
+
+def rmsnorm_backward(x, weight, eps, dh):
+    """Gradients of sum(dh * rmsnorm(x, weight)) with respect to x and weight.
+    With r = 1/sqrt(mean(x^2) + eps):  dweight_k = sum_rows dh_k x_k r;
+    dx_k = r weight_k dh_k - x_k r^3 (sum_j dh_j weight_j x_j) / d."""
+    x, w, dh = _as64(x), _as64(weight), _as64(dh)
+    d = x.shape[-1]
+    r = 1.0 / np.sqrt((x * x).mean(axis=-1, keepdims=True) + eps)
+    dweight = (dh * x * r).reshape(-1, d).sum(axis=0)
+    t = (dh * w * x).sum(axis=-1, keepdims=True)
+    dx = r * w * dh - x * (r ** 3) * t / d
+    return dx, dweight
+
+
 def token_logratio(logp_cur, logp_behav, mask):
     """Delta_{n,t} = mask * (log pi_theta(y_t) - log mu(y_t)): the token-level log ratio (Fig. 3)."""
     msk = (np.asarray(mask) != 0).astype(_F)
@@ -235,10 +267,20 @@ def backward(hidden, W, tokens, mask, g, temperature=1.0, row_chunk=2048):
 
 def iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, K,
                        eta=2.0, coef_mode=0, baseline_mode=0, loss_scale=1.0, temperature=1.0,
-                       normalized_grads=False, coef_override=None, row_chunk=2048, ratio_level=0):
+                       normalized_grads=False, coef_override=None, row_chunk=2048, ratio_level=0,
+                       rms_weight=None, rms_eps=1e-6, round_normed_hidden=False):
     """The whole update-step loss of Alg. 1 (procedure IW-GRPG, one mini-batch): advantages by
     Eq. (5), gradient by Eq. (3).  ratio_level 1 swaps the outer weight for the token-level one of
-    token_coefficients (then `g` is [N,T]).  Returns a dict with loss, dH, dW and every intermediate."""
+    token_coefficients (then `g` is [N,T]).  With rms_weight, `hidden` is the input x of a final
+    RMSNorm: the path runs on h = rmsnorm(x) (rounded to bf16 first if round_normed_hidden, the
+    precision a bf16 contraction sees; the rounding passes gradients through unchanged), dH is the
+    gradient with respect to x and d_rms_weight is returned too.
+    Returns a dict with loss, dH, dW and every intermediate."""
+    x_in = hidden
+    if rms_weight is not None:
+        hidden = rmsnorm(x_in, rms_weight, rms_eps)
+        if round_normed_hidden:
+            hidden = round_to_bf16(hidden)
     logp_cur, lse = logprob(hidden, W, tokens, mask, temperature, row_chunk)
     tok_lr = token_logratio(logp_cur, logp_behav, mask)
     s = tok_lr.sum(axis=1)
@@ -254,9 +296,12 @@ def iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, 
     else:
         raise ValueError("ratio_level")
     dH, dW = backward(hidden, W, tokens, mask, g, temperature, row_chunk)
+    d_rms_weight = None
+    if rms_weight is not None:
+        dH, d_rms_weight = rmsnorm_backward(x_in, rms_weight, rms_eps, dH)
     log_eta = math.log(eta) if math.isfinite(eta) else math.inf
     log_w = np.minimum(s, log_eta)
-    return dict(loss=loss, dH=dH, dW=dW, logp_cur=logp_cur, lse=lse, tok_logratio=tok_lr,
+    return dict(loss=loss, dH=dH, dW=dW, d_rms_weight=d_rms_weight, logp_cur=logp_cur, lse=lse, tok_logratio=tok_lr,
                 seq_logratio=s, adv=ga["adv"], weight=ga["weight"], g=g, grad_log_scale=lam,
                 group_mean=ga["group_mean"], group_std=ga["group_std"],
                 group_size=ga["group_size"],

@@ -463,6 +463,69 @@ def test_token_level_clip_and_normalisation():
     assert not np.allclose(wrong, g0)
 
 
+# ---------------------------------------------------------------- RMSNorm on the way in
+def test_round_to_bf16_matches_library():
+    rng = np.random.default_rng(21)
+    x = np.concatenate([rng.normal(size=4000) * 10.0 ** rng.integers(-6, 6, size=4000),
+                        [0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.3895314e38]])   # ties: to even
+    ref = torch.tensor(x, dtype=torch.float64).to(torch.float32).to(torch.bfloat16).double().numpy()
+    assert np.array_equal(orc.round_to_bf16(x), ref)
+    assert orc.round_to_bf16(np.array([1.00390625]))[0] == 1.0 and orc.round_to_bf16(np.array([1.01171875]))[0] == 1.015625
+
+
+def test_rmsnorm_forward_backward_against_torch_autograd():
+    rng = np.random.default_rng(22)
+    x = rng.normal(size=(3, 4, 7)) * 2.0
+    wgt = rng.normal(size=7)
+    dh = rng.normal(size=(3, 4, 7))
+    xt = torch.tensor(x, requires_grad=True)
+    wt = torch.tensor(wgt, requires_grad=True)
+    ht = torch.nn.functional.rms_norm(xt, (7,), wt, eps=1e-5)
+    (ht * torch.tensor(dh)).sum().backward()
+    assert np.allclose(orc.rmsnorm(x, wgt, 1e-5), ht.detach().numpy(), atol=1e-13)
+    dx, dwt = orc.rmsnorm_backward(x, wgt, 1e-5, dh)
+    assert np.allclose(dx, xt.grad.numpy(), atol=1e-13) and np.allclose(dwt, wt.grad.numpy(), atol=1e-13)
+    # closed form: unit weight, eps = 0 => every row has mean square 1, and scaling x changes nothing
+    h = orc.rmsnorm(x, np.ones(7), 0.0)
+    assert np.allclose((h * h).mean(-1), 1.0, atol=1e-14)
+    assert np.allclose(orc.rmsnorm(3.7 * x, np.ones(7), 0.0), h, atol=1e-14)
+
+
+def test_fused_path_with_rmsnorm_finite_differences():
+    """hidden = x before the norm: loss is the loss of the path on rmsnorm(x); dH = dL/dx and
+    d_rms_weight by finite differences of the independently written surrogate."""
+    H, W, _, tok, mask, R, gid, logp_b = _tiny(23)
+    wgt = 1.0 + 0.3 * np.random.default_rng(24).normal(size=H.shape[2])
+    eps_n = 1e-3
+    out = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, rms_weight=wgt, rms_eps=eps_n)
+    plain = orc.iw_pg_loss_fwd_bwd(orc.rmsnorm(H, wgt, eps_n), W, tok, mask, logp_b, R, gid, 2)
+    assert out["loss"] == plain["loss"] and np.array_equal(out["dW"], plain["dW"])
+    A = out["adv"].tolist()
+
+    def py_norm(Hx, wx):
+        return [[[Hx[n][t][k] * wx[k] / math.sqrt(sum(v * v for v in Hx[n][t]) / len(wx) + eps_n) for k in range(len(wx))]
+                 for t in range(len(Hx[0]))] for n in range(len(Hx))]
+
+    def obj(Hx, wx):
+        return _py_surrogate(py_norm(Hx.tolist(), wx.tolist()), W.tolist(), tok.tolist(), mask.tolist(), logp_b.tolist(), A)
+
+    assert abs(obj(H, wgt) - out["loss"]) < 1e-13
+    e = 1e-6
+    for idx in itertools.product(range(H.shape[0]), range(H.shape[1]), range(H.shape[2])):
+        Hp, Hm = H.copy(), H.copy()
+        Hp[idx] += e
+        Hm[idx] -= e
+        assert abs(out["dH"][idx] - (obj(Hp, wgt) - obj(Hm, wgt)) / (2 * e)) < 1e-8, idx
+    for k in range(len(wgt)):
+        wp, wm = wgt.copy(), wgt.copy()
+        wp[k] += e
+        wm[k] -= e
+        assert abs(out["d_rms_weight"][k] - (obj(H, wp) - obj(H, wm)) / (2 * e)) < 1e-8, k
+    # rounding the normalised hidden state to bf16 moves the loss by bf16's relative precision, no more
+    r = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 2, rms_weight=wgt, rms_eps=eps_n, round_normed_hidden=True)
+    assert 0 < abs(r["loss"] - out["loss"]) < 0.05 * abs(out["loss"])
+
+
 
 def test_compaction():
     rng = np.random.default_rng(12)
