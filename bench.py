@@ -89,6 +89,9 @@ def main():
     ap.add_argument("--calibrated", action="store_true",
                     help="the workload's calibrated companion: same shapes and seed, behaviour weights close enough "
                          "that the generation-level ratios are O(1) (every generation carries gradient, dz is dense)")
+    ap.add_argument("--rmsnorm", action="store_true",
+                    help="treat the workload's hidden states as the input of a final RMSNorm that the call applies "
+                         "on the way in and differentiates on the way out (opts.rms_weight); not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=["cache", "recompute"], default="cache",
                     help="backward of the timed call: 'cache' = opts.logits_cache 1 (probability ratios kept in the "
@@ -127,6 +130,10 @@ def main():
             key, val = kv.split("=")
             rb.rapid_set_tuning(int(key), int(val))
     fwd_only = spec.fwd_only
+    rms = {}
+    if args.rmsnorm:
+        gen = torch.Generator(device="cuda").manual_seed(1)
+        rms = dict(rms_weight=(1.0 + 0.1 * torch.randn(d, device="cuda", generator=gen)).to(torch.bfloat16), rms_eps=1e-6)
 
     def timed(step):
         """W warm-up steps, then exactly K steps between two synchronisations, with the library's
@@ -166,7 +173,7 @@ def main():
         buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes, logits_cache=cache, max_tokens=M)
         dt, stages = timed(lambda: rb.rapid_iw_pg_loss_fwd_bwd(
             w["hidden"], w["W"], w["tokens"], w["mask"], w["logp_behav"], w["rewards"], w["group_ids"], K,
-            buffers=buf, optional_outputs=False, logits_cache=cache, max_tokens=M))
+            buffers=buf, optional_outputs=False, logits_cache=cache, max_tokens=M, **rms))
         ws_gib = buf.workspace.numel() / 2**30
         del buf                      # the workspace goes back before the other mode takes its own
         torch.cuda.empty_cache()
@@ -175,12 +182,12 @@ def main():
     if fwd_only:
         ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, rb.DTYPE_BF16)
         ws = rb.alloc_workspace(ws_bytes)
-        dt, stages = timed(lambda: rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], workspace=ws))
+        dt, stages = timed(lambda: rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], workspace=ws, **rms))
         ws_gib = ws_bytes / 2**30
         flops_per_token = 2.0 * d * V
         mode = "forward only"
     else:
-        logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"])
+        logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"], **rms)
         w["logp_behav"] = logp_b
         flops_per_token = 6.0 * d * V
         mode = args.mode
@@ -226,7 +233,7 @@ def main():
         "config": {"workload": spec.name, "d": d, "V": V, "prompts": spec.prompts, "G": spec.G, "N": N,
                    "T": T, "response_tokens": M, "workspace_gib": ws_gib,
                    "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd",
-                   "backward_mode": mode,
+                   "backward_mode": mode, "final_rmsnorm": bool(args.rmsnorm),
                    "executed_flop_per_token": (2.0 if fwd_only else 6.0 if mode == "cache" else 8.0) * d * V},
         "frac_bf16_mfma_peak_algorithmic": flops_per_token * tok_s / PEAK_BF16_MFMA,
         "roofline": roofline,
@@ -248,7 +255,7 @@ def main():
             "frac_bf16_mfma_peak_algorithmic": flops_per_token * M * args.steps / res[0] / PEAK_BF16_MFMA,
             "workspace_gib": res[2], "executed_flop_per_token": (6.0 if other == "cache" else 8.0) * d * V,
             "stages_ms_per_step": {k: v["ms_per_step"] for k, v in res[1].items()}}
-    if not args.no_cpu_baseline and not fwd_only:
+    if not args.no_cpu_baseline and not fwd_only and not args.rmsnorm:
         out["cpu_baseline"] = cpu_baseline(w, rb, logits_cache=(mode == "cache"))
     print(json.dumps(out))
 

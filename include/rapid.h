@@ -104,6 +104,12 @@ typedef struct rapid_iw_pg_opts {
                               RAPID_STATUS_TOKEN_BOUND */
     const float* coef_override; /* DEVICE [N] or NULL: use these per-generation coefficients g_n
                               = dLoss/dlogp_{n,t} instead of the estimator's (loss = sum g_n) */
+    const void* rms_weight; /* NULL, or DEVICE [d] (bf16; bf16 inputs only): `hidden` is then the input x of the
+                              model's final RMSNorm and the path runs on h = x * rms_weight / sqrt(mean(x^2) +
+                              rms_eps), formed (and rounded to bf16) while the rows are packed; dhidden_out
+                              is dLoss/dx.  Not part of the paper's method, whose path starts at h */
+    float* drms_weight_out; /* NULL, or DEVICE [d] fp32: dLoss/d rms_weight (only read with rms_weight) */
+    float rms_eps;          /* >= 0; 1e-6 */
 } rapid_iw_pg_opts;
 
 /* Diagnostics written by rapid_iw_pg_loss_fwd_bwd (device struct).
@@ -191,6 +197,16 @@ int rapid_logprob_fwd(const void* hidden, const void* W, const int32_t* tokens, 
                       int64_t N, int64_t T, int64_t d, int64_t V, int dtype, int w_layout,
                       float temperature, float* logp_out, float* lse_out, int32_t* dev_status,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* rapid_logprob_fwd on h = hidden * rms_weight / sqrt(mean(hidden^2) + rms_eps) (see
+ * rapid_iw_pg_opts.rms_weight; rms_weight: DEVICE [d] bf16, dtype must be RAPID_DTYPE_BF16): the
+ * log-probs a behaviour policy with that final norm assigns.  Same workspace size, same errors,
+ * plus RAPID_ERR_NULL / RAPID_ERR_DTYPE / RAPID_ERR_SHAPE for rms_weight, dtype and rms_eps. */
+int rapid_logprob_fwd_rmsnorm(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
+                              int64_t N, int64_t T, int64_t d, int64_t V, int dtype, int w_layout,
+                              float temperature, const void* rms_weight, float rms_eps, float* logp_out,
+                              float* lse_out, int32_t* dev_status, void* workspace, size_t workspace_bytes,
+                              void* stream);
 
 /*
  * Group advantage (Sec. 3.3 Eq. (2); Sec. 3.4 Eq. (4), (5)).

@@ -23,7 +23,7 @@ STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LO
 STATUS_TOKEN_BOUND = 32
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
-           "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_workspace_bytes_max_tokens", "rapid_logprob_fwd",
+           "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_workspace_bytes_max_tokens", "rapid_logprob_fwd", "rapid_logprob_fwd_rmsnorm",
            "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step"]
 STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
           "dw", "f32_path", "dw_convert"]
@@ -40,7 +40,8 @@ class IwPgOpts(C.Structure):
                 ("loss_scale", C.c_float), ("temperature", C.c_float), ("w_layout", C.c_int),
                 ("dw_dtype", C.c_int), ("accumulate_dw", C.c_int), ("normalized_grads", C.c_int),
                 ("logits_cache", C.c_int), ("ratio_level", C.c_int), ("max_tokens", C.c_int64),
-                ("coef_override", C.c_void_p)]
+                ("coef_override", C.c_void_p), ("rms_weight", C.c_void_p), ("drms_weight_out", C.c_void_p),
+                ("rms_eps", C.c_float)]
 
 
 class IwPgDiag(C.Structure):
@@ -74,6 +75,8 @@ def load():
     lib.rapid_workspace_bytes_max_tokens.restype = sz
     lib.rapid_logprob_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, f32, vp, vp, vp, vp, sz, vp]
     lib.rapid_logprob_fwd.restype = ci
+    lib.rapid_logprob_fwd_rmsnorm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, f32, vp, f32, vp, vp, vp, vp, sz, vp]
+    lib.rapid_logprob_fwd_rmsnorm.restype = ci
     lib.rapid_group_advantage.argtypes = [vp, vp, vp, i64, i64, f32, ci, vp, vp, vp, vp, vp, vp, vp]
     lib.rapid_group_advantage.restype = ci
     lib.rapid_iw_pg_loss_fwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci,
@@ -175,8 +178,9 @@ def rapid_compaction(mask):
 
 
 def rapid_logprob_fwd(hidden, W, tokens, mask, w_layout=W_DV, temperature=1.0, want_lse=False,
-                      workspace=None, dev_status=None):
-    """Returns (logp [N,T] f32, lse [N,T] f32 or None)."""
+                      workspace=None, dev_status=None, rms_weight=None, rms_eps=1e-6):
+    """Returns (logp [N,T] f32, lse [N,T] f32 or None).  With rms_weight [d] (bf16), `hidden` is the
+    input of the final RMSNorm, which is applied on the way in."""
     N, T, d = hidden.shape
     V = W.shape[1] if w_layout == W_DV else W.shape[0]
     dt = _dtype_code(hidden)
@@ -186,6 +190,13 @@ def rapid_logprob_fwd(hidden, W, tokens, mask, w_layout=W_DV, temperature=1.0, w
         workspace = alloc_workspace(rapid_workspace_bytes(OP_LOGPROB_FWD, N, T, d, V, 1, dt), hidden.device)
     logp = torch.empty((N, T), dtype=torch.float32, device=hidden.device)
     lse = torch.empty((N, T), dtype=torch.float32, device=hidden.device) if want_lse else None
+    if rms_weight is not None:
+        _need(rms_weight, hidden.dtype, "rms_weight")
+        _check(load().rapid_logprob_fwd_rmsnorm(_ptr(hidden), _ptr(W), _ptr(tokens), _ptr(mask), N, T, d, V, dt,
+                                                w_layout, float(temperature), _ptr(rms_weight), float(rms_eps),
+                                                _ptr(logp), _ptr(lse), _ptr(dev_status), _ptr(workspace),
+                                                workspace.numel(), _stream()))
+        return logp, lse
     _check(load().rapid_logprob_fwd(_ptr(hidden), _ptr(W), _ptr(tokens), _ptr(mask), N, T, d, V, dt, w_layout,
                                     float(temperature), _ptr(logp), _ptr(lse), _ptr(dev_status),
                                     _ptr(workspace), workspace.numel(), _stream()))
@@ -250,7 +261,8 @@ class IwPgBuffers:
 def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, K, buffers=None,
                              eta=2.0, coef_mode=0, baseline_mode=0, loss_scale=1.0, temperature=1.0,
                              w_layout=W_DV, accumulate_dw=False, normalized_grads=False, coef_override=None,
-                             optional_outputs=True, logits_cache=False, ratio_level=0, max_tokens=0):
+                             optional_outputs=True, logits_cache=False, ratio_level=0, max_tokens=0,
+                             rms_weight=None, rms_eps=1e-6):
     """Enqueues the fused forward+backward on the current stream and returns the IwPgBuffers that
     hold the outputs (loss, dhidden, dW, logp_cur, tok_logratio, seq_logratio, adv, diag)."""
     N, T, d = hidden.shape
@@ -276,6 +288,11 @@ def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group
     o.logits_cache = int(bool(logits_cache))
     o.ratio_level = int(ratio_level)
     o.max_tokens = int(max_tokens)
+    if rms_weight is not None:          # hidden is the input of the final RMSNorm; dhidden is dLoss/d(that input)
+        _need(rms_weight, hidden.dtype, "rms_weight")
+        if getattr(b, "drms_weight", None) is None:
+            b.drms_weight = torch.empty(d, dtype=torch.float32, device=hidden.device)
+        o.rms_weight, o.rms_eps, o.drms_weight_out = rms_weight.data_ptr(), float(rms_eps), b.drms_weight.data_ptr()
     if coef_override is not None:
         _need(coef_override, torch.float32, "coef_override")
         o.coef_override = coef_override.data_ptr()

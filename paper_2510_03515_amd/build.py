@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librapid_hip.so")
-SOURCES = ["rapid_api.hip", "reductions.hip", "pack.hip", "gemm_bf16.hip", "f32_path.hip", "probe.hip"]
+SOURCES = ["rapid_api.hip", "reductions.hip", "pack.hip", "gemm_bf16.hip", "f32_path.hip", "probe.hip", "rmsnorm.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

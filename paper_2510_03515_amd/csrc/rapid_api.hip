@@ -69,7 +69,7 @@ struct Plan {
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
-    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, rowc, rowg, logp_tmp, s64, s32, adv, g, g64, tsum, tmax,
+    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, g, g64, tsum, tmax,
         Hc, Wvd, Wdv, WdvB, part_max, part_sum, dw32, chunk0;
 };
 
@@ -108,8 +108,10 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     p.seqc = take(cur, (size_t)p.Mmax_pad * 4);
     p.zy = take(cur, (size_t)p.Mmax_pad * 4);
     p.lse_c = take(cur, (size_t)p.Mmax_pad * 4);
+    if (dtype == RAPID_DTYPE_BF16) p.inv_rms = take(cur, (size_t)p.Mmax_pad * 4);   // final-norm option
     if (bwd) {
         p.rowc = take(cur, (size_t)p.Mmax_pad * 4);
+        if (dtype == RAPID_DTYPE_BF16) p.rms_part = take(cur, (size_t)rmsnorm_dweight_blocks(p.Mmax_pad) * d * 4);
         p.rowg = take(cur, (size_t)p.Mmax_pad * 4);
         p.g64 = take(cur, (size_t)N * 8);
         p.tsum = take(cur, (size_t)N * 8);
@@ -212,6 +214,8 @@ struct FwdIo {
     float* logp_out; float* lse_out; int32_t* dev_status;
     bf16_t* zc = nullptr;   // if set: [row_cap, ldv], the forward also stores the ratios p_v / p_y there
     int64_t row_cap = INT64_MAX;   // compact rows the caller's buffers hold (the cache may be sized for fewer than N*T)
+    const void* rms_weight = nullptr;   // if set (bf16 only): hidden is normalised while it is packed
+    float rms_eps = 0.f;
 };
 
 // compaction, operand packing and the streaming log-softmax forward; leaves lse_c, tokc, seqc,
@@ -236,8 +240,12 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
         {
             Span sp(ST_PACK, st);
-            launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc, p.ldk, p.Mmax, p.d, p.Mmax_pad,
-                                 p.dpadR, counts, 0, st);
+            if (io.rms_weight)
+                launch_rmsnorm_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, (const bf16_t*)io.rms_weight,
+                                        io.rms_eps, Hc, p.ldk, p.Mmax_pad, p.dpadR, counts, at<float>(ws, p.inv_rms), st);
+            else
+                launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc, p.ldk, p.Mmax, p.d, p.Mmax_pad,
+                                     p.dpadR, counts, 0, st);
             if (io.w_layout == RAPID_W_VD)
                 launch_copy_pad_bf16((const bf16_t*)io.W, p.d, nullptr, Wvd, p.ldk, p.V, p.d, p.Vpad, p.dpad,
                                      nullptr, 0, st);
@@ -320,6 +328,53 @@ int validate_common(const void* hidden, const void* W, const int32_t* tokens, co
     return RAPID_OK;
 }
 
+int validate_rms(const void* rms_weight, float rms_eps, int dtype) {
+    if (!rms_weight) return RAPID_OK;
+    if (dtype != RAPID_DTYPE_BF16) {
+        set_error("rms_weight needs bf16 inputs");
+        return RAPID_ERR_DTYPE;
+    }
+    if (((uintptr_t)rms_weight) % 16 != 0 || !(rms_eps >= 0.f) || !std::isfinite(rms_eps)) {
+        set_error("rms_weight must be 16-byte aligned and rms_eps finite and >= 0");
+        return RAPID_ERR_SHAPE;
+    }
+    return RAPID_OK;
+}
+
+int logprob_fwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask, int64_t N, int64_t T,
+                int64_t d, int64_t V, int dtype, int w_layout, float temperature, const void* rms_weight,
+                float rms_eps, float* logp_out, float* lse_out, int32_t* dev_status, void* workspace,
+                size_t workspace_bytes, void* stream) {
+    Plan p;
+    if (!make_plan(p, RAPID_OP_LOGPROB_FWD, N, T, d, V, 1, dtype)) {
+        set_error("bad shape/dtype N=%lld T=%lld d=%lld V=%lld dtype=%d", (long long)N, (long long)T, (long long)d,
+                  (long long)V, dtype);
+        return (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) ? RAPID_ERR_DTYPE : RAPID_ERR_SHAPE;
+    }
+    int rc = validate_common(hidden, W, tokens, mask, d, dtype, w_layout, temperature, workspace);
+    if (rc) return rc;
+    rc = validate_rms(rms_weight, rms_eps, dtype);
+    if (rc) return rc;
+    if (!logp_out) {
+        set_error("logp_out must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    const int64_t Mc = fit_chunk(p, workspace_bytes);
+    if (Mc < ROW_TILE) {
+        set_error("workspace of %zu bytes is below the minimum %zu", workspace_bytes,
+                  rapid_workspace_min_bytes(RAPID_OP_LOGPROB_FWD, N, T, d, V, 1, dtype));
+        return RAPID_ERR_WORKSPACE;
+    }
+    size_chunks(p, Mc < recommended_chunk(p) ? Mc : recommended_chunk(p));
+    rc = check_arch();
+    if (rc) return rc;
+    FwdIo io{hidden, W, tokens, mask, w_layout, temperature, logp_out, lse_out, dev_status};
+    io.rms_weight = rms_weight;
+    io.rms_eps = rms_eps;
+    run_forward(p, workspace, io, (hipStream_t)stream);
+    return check_launch("rapid_logprob_fwd");
+}
+
 }  // namespace
 }  // namespace rapid
 
@@ -327,7 +382,7 @@ using namespace rapid;
 
 extern "C" {
 
-int rapid_version(void) { return 5; }
+int rapid_version(void) { return 6; }
 
 const char* rapid_last_error(void) { return g_err; }
 
@@ -346,6 +401,9 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
     o->logits_cache = 0;
     o->ratio_level = 0;
     o->max_tokens = 0;
+    o->rms_weight = nullptr;
+    o->drms_weight_out = nullptr;
+    o->rms_eps = 1e-6f;
     o->coef_override = nullptr;
 }
 
@@ -484,30 +542,20 @@ int rapid_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len
 int rapid_logprob_fwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask, int64_t N,
                       int64_t T, int64_t d, int64_t V, int dtype, int w_layout, float temperature, float* logp_out,
                       float* lse_out, int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream) {
-    Plan p;
-    if (!make_plan(p, RAPID_OP_LOGPROB_FWD, N, T, d, V, 1, dtype)) {
-        set_error("bad shape/dtype N=%lld T=%lld d=%lld V=%lld dtype=%d", (long long)N, (long long)T, (long long)d,
-                  (long long)V, dtype);
-        return (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) ? RAPID_ERR_DTYPE : RAPID_ERR_SHAPE;
-    }
-    int rc = validate_common(hidden, W, tokens, mask, d, dtype, w_layout, temperature, workspace);
-    if (rc) return rc;
-    if (!logp_out) {
-        set_error("logp_out must not be NULL");
+    return logprob_fwd(hidden, W, tokens, mask, N, T, d, V, dtype, w_layout, temperature, nullptr, 0.f, logp_out,
+                       lse_out, dev_status, workspace, workspace_bytes, stream);
+}
+
+int rapid_logprob_fwd_rmsnorm(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask, int64_t N,
+                              int64_t T, int64_t d, int64_t V, int dtype, int w_layout, float temperature,
+                              const void* rms_weight, float rms_eps, float* logp_out, float* lse_out,
+                              int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!rms_weight) {
+        set_error("rms_weight must not be NULL");
         return RAPID_ERR_NULL;
     }
-    const int64_t Mc = fit_chunk(p, workspace_bytes);
-    if (Mc < ROW_TILE) {
-        set_error("workspace of %zu bytes is below the minimum %zu", workspace_bytes,
-                  rapid_workspace_min_bytes(RAPID_OP_LOGPROB_FWD, N, T, d, V, 1, dtype));
-        return RAPID_ERR_WORKSPACE;
-    }
-    size_chunks(p, Mc < recommended_chunk(p) ? Mc : recommended_chunk(p));
-    rc = check_arch();
-    if (rc) return rc;
-    FwdIo io{hidden, W, tokens, mask, w_layout, temperature, logp_out, lse_out, dev_status};
-    run_forward(p, workspace, io, (hipStream_t)stream);
-    return check_launch("rapid_logprob_fwd");
+    return logprob_fwd(hidden, W, tokens, mask, N, T, d, V, dtype, w_layout, temperature, rms_weight, rms_eps,
+                       logp_out, lse_out, dev_status, workspace, workspace_bytes, stream);
 }
 
 int rapid_group_advantage(const float* rewards, const int32_t* group_ids, const float* seq_logratio, int64_t N,
@@ -590,6 +638,8 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         set_error("max_tokens must be >= 0");
         return RAPID_ERR_SHAPE;
     }
+    rc = validate_rms(o.rms_weight, o.rms_eps, dtype);
+    if (rc) return rc;
     if (cached && Mfit < cache_rows(p, o.max_tokens)) {
         set_error("workspace of %zu bytes is below the %zu the logits cache needs", workspace_bytes,
                   rapid_workspace_bytes_max_tokens(RAPID_OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dtype, o.max_tokens));
@@ -620,6 +670,8 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         io.zc = at<bf16_t>(ws, p.chunk0);
         io.row_cap = p.Mc;
     }
+    io.rms_weight = o.rms_weight;
+    io.rms_eps = o.rms_eps;
     run_forward(p, ws, io, st);
 
     // generation-level log ratios, clipped-weight group baseline, coefficients and loss
@@ -711,6 +763,12 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                 Span sp(ST_DW, st);
                 launch_dw(wa, st);
             }
+        }
+        if (o.rms_weight) {   // dhidden holds dL/dh of the normalised state: on to dL/dweight and dL/dx
+            Span sp(ST_ZERO, st);
+            launch_rmsnorm_backward((const bf16_t*)hidden, (bf16_t*)dhidden_out, d, (const bf16_t*)o.rms_weight,
+                                    row_index, counts, at<float>(ws, p.inv_rms), p.Mmax_pad, at<float>(ws, p.rms_part),
+                                    o.drms_weight_out, st);
         }
     } else {
         float* z = at<float>(ws, p.chunk0);

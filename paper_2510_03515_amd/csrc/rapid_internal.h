@@ -71,6 +71,19 @@ void launch_transpose_pad_bf16(const bf16_t* src, int64_t ld_src, bf16_t* dst, i
                                int64_t C, int64_t Rpad, int64_t Cpad, const int32_t* counts, int64_t r0,
                                hipStream_t st);
 
+// ---- rmsnorm.hip ------------------------------------------------------------------------------
+// dst row r (< counts[CNT_MR], grid covers Rpad) = bf16(src[row_index[r]] * weight / rms) for r < counts[CNT_M],
+// zero otherwise and in columns C .. Cpad; inv_rms[r] = 1 / sqrt(mean(x^2) + eps).  C % 8 == 0.
+void launch_rmsnorm_pad_bf16(const bf16_t* src, int64_t C, const int32_t* row_index, const bf16_t* weight, float eps,
+                             bf16_t* dst, int64_t ld_dst, int64_t Rpad, int64_t Cpad, const int32_t* counts,
+                             float* inv_rms, hipStream_t st);
+// dh [N*T, d] holds dL/dh at the valid positions: dweight (if not NULL) = dL/dweight via `part`
+// (rmsnorm_dweight_blocks(rows_max) x d floats), then dh becomes dL/dx in place
+int64_t rmsnorm_dweight_blocks(int64_t rows_max);
+void launch_rmsnorm_backward(const bf16_t* x, bf16_t* dh, int64_t d, const bf16_t* weight, const int32_t* row_index,
+                             const int32_t* counts, const float* inv_rms, int64_t rows_max, float* part,
+                             float* dweight, hipStream_t st);
+
 // ---- gemm_bf16.hip ----------------------------------------------------------------------------
 struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered logit
     const bf16_t* Wvd;    // [Vpad, dpad]

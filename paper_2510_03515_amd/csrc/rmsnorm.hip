@@ -1,0 +1,191 @@
+// Final RMSNorm folded into the operand pack of the fused call (not part of the paper's method: its
+// path starts at the hidden state; the Qwen2.5 models it trains end in this norm, and the pack pass
+// reads every hidden row anyway).  Forward: the packed, zero-padded bf16 operand holds
+// h = x * weight / sqrt(mean(x^2) + eps) instead of a copy of x.  Backward: the dHidden kernel has
+// written dL/dh (bf16) into the caller's dhidden buffer; two passes over the valid rows turn it into
+// dL/dweight (fixed-order partial sums) and, in place, dL/dx.
+#include "rapid_internal.h"
+
+namespace rapid {
+
+namespace {
+
+constexpr int WAVE = 64;
+
+__device__ inline float wave_sum_f(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+// sum over the 256 threads of a block, same value in every thread, fixed order
+__device__ inline float block_sum_f(float v, float* sm) {
+    v = wave_sum_f(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) sm[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    return (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+
+__device__ inline void unpack8(const uint4& v, float (&f)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = __builtin_bit_cast(float, w[e] << 16);
+        f[2 * e + 1] = __builtin_bit_cast(float, w[e] & 0xffff0000u);
+    }
+}
+
+__device__ inline uint32_t pack2(float a, float b) {
+    const __bf16 x = (__bf16)a, y = (__bf16)b;
+    return (uint32_t)__builtin_bit_cast(unsigned short, x) | ((uint32_t)__builtin_bit_cast(unsigned short, y) << 16);
+}
+
+__device__ inline uint4 pack8(const float (&f)[8]) {
+    return make_uint4(pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7]));
+}
+
+// one block per destination row r < Mr (device count): rows < M hold the normalised source row
+// row_index[r], the rest and the columns C .. Cpad are zero; inv_rms[r] = 1 / sqrt(mean(x^2) + eps)
+__global__ __launch_bounds__(256) void rmsnorm_pad_bf16_kernel(const bf16_t* __restrict__ src, int64_t C,
+                                                               const int32_t* __restrict__ row_index,
+                                                               const bf16_t* __restrict__ weight, float eps,
+                                                               bf16_t* __restrict__ dst, int64_t ld_dst, int64_t Cpad,
+                                                               const int32_t* __restrict__ counts,
+                                                               float* __restrict__ inv_rms) {
+    __shared__ float sm[4];
+    const int64_t r = blockIdx.x;
+    const int M = counts[CNT_M], Mr = counts[CNT_MR];
+    if (r >= Mr) return;
+    bf16_t* drow = dst + r * ld_dst;
+    const int64_t chunks = Cpad / 8, live_chunks = C / 8;
+    if (r >= M) {
+        for (int64_t c = threadIdx.x; c < chunks; c += blockDim.x) *(uint4*)(drow + c * 8) = make_uint4(0u, 0u, 0u, 0u);
+        return;
+    }
+    const bf16_t* srow = src + (int64_t)row_index[r] * C;
+    float ss = 0.f;
+    for (int64_t c = threadIdx.x; c < live_chunks; c += blockDim.x) {
+        float x[8];
+        unpack8(*(const uint4*)(srow + c * 8), x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+    }
+    ss = block_sum_f(ss, sm);
+    const float inv = 1.0f / sqrtf(ss / (float)C + eps);
+    if (threadIdx.x == 0) inv_rms[r] = inv;
+    for (int64_t c = threadIdx.x; c < chunks; c += blockDim.x) {
+        uint4 out = make_uint4(0u, 0u, 0u, 0u);
+        if (c < live_chunks) {
+            float x[8], g[8], h[8];
+            unpack8(*(const uint4*)(srow + c * 8), x);
+            unpack8(*(const uint4*)(weight + c * 8), g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = x[e] * inv * g[e];
+            out = pack8(h);
+        }
+        *(uint4*)(drow + c * 8) = out;
+    }
+}
+
+// dweight partials: block (cb, rb) sums dh[row][k] x[row][k] inv_rms[row] over the valid compact rows
+// rb*RB .. +RB for the 8 columns of each of its threads; part[rb][k]
+constexpr int RB = 512;
+__global__ __launch_bounds__(256) void rmsnorm_dweight_partial_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dh,
+                                                                      int64_t d, const int32_t* __restrict__ row_index,
+                                                                      const int32_t* __restrict__ counts,
+                                                                      const float* __restrict__ inv_rms,
+                                                                      float* __restrict__ part) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // 8-column chunk
+    const int64_t r0 = (int64_t)blockIdx.y * RB;
+    const int M = counts[CNT_M];
+    if (c * 8 >= d || r0 >= M) return;   // the reduction reads the blocks that hold tokens only
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const int64_t r1 = r0 + RB < M ? r0 + RB : M;
+    for (int64_t r = r0; r < r1; ++r) {
+        const int64_t pos = row_index[r];
+        float xv[8], gv[8];
+        unpack8(*(const uint4*)(x + pos * d + c * 8), xv);
+        unpack8(*(const uint4*)(dh + pos * d + c * 8), gv);
+        const float inv = inv_rms[r];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(gv[e] * inv, xv[e], acc[e]);
+    }
+    float* o = part + (int64_t)blockIdx.y * d + c * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = acc[e];
+}
+
+// dweight[k] = sum over the row blocks that hold tokens, in block order (fp64 accumulate)
+__global__ void rmsnorm_dweight_reduce_kernel(const float* __restrict__ part, int64_t d, int64_t nblk_max,
+                                              const int32_t* __restrict__ counts, float* __restrict__ dweight) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= d) return;
+    const int64_t nblk = ((int64_t)counts[CNT_M] + RB - 1) / RB;
+    double acc = 0.0;
+    for (int64_t b = 0; b < nblk && b < nblk_max; ++b) acc += (double)part[b * d + k];
+    dweight[k] = (float)acc;
+}
+
+// in place, one block per valid compact row: dh -> dx = r (w dh) - x r^3 sum_k(dh_k w_k x_k) / d
+__global__ __launch_bounds__(256) void rmsnorm_dx_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ dh, int64_t d,
+                                                         const bf16_t* __restrict__ weight,
+                                                         const int32_t* __restrict__ row_index,
+                                                         const int32_t* __restrict__ counts,
+                                                         const float* __restrict__ inv_rms) {
+    __shared__ float sm[4];
+    const int64_t r = blockIdx.x;
+    if (r >= counts[CNT_M]) return;
+    const int64_t pos = row_index[r];
+    const bf16_t* xr = x + pos * d;
+    bf16_t* gr = dh + pos * d;
+    const int64_t chunks = d / 8;
+    float t = 0.f;
+    for (int64_t c = threadIdx.x; c < chunks; c += blockDim.x) {
+        float xv[8], gv[8], wv[8];
+        unpack8(*(const uint4*)(xr + c * 8), xv);
+        unpack8(*(const uint4*)(gr + c * 8), gv);
+        unpack8(*(const uint4*)(weight + c * 8), wv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t = fmaf(gv[e] * wv[e], xv[e], t);
+    }
+    t = block_sum_f(t, sm);   // also orders every thread's reads of the row before the writes below
+    const float inv = inv_rms[r];
+    const float k3 = inv * inv * inv * t / (float)d;
+    for (int64_t c = threadIdx.x; c < chunks; c += blockDim.x) {
+        float xv[8], gv[8], wv[8], o[8];
+        unpack8(*(const uint4*)(xr + c * 8), xv);
+        unpack8(*(const uint4*)(gr + c * 8), gv);
+        unpack8(*(const uint4*)(weight + c * 8), wv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = inv * wv[e] * gv[e] - xv[e] * k3;
+        *(uint4*)(gr + c * 8) = pack8(o);
+    }
+}
+
+}  // namespace
+
+void launch_rmsnorm_pad_bf16(const bf16_t* src, int64_t C, const int32_t* row_index, const bf16_t* weight, float eps,
+                             bf16_t* dst, int64_t ld_dst, int64_t Rpad, int64_t Cpad, const int32_t* counts,
+                             float* inv_rms, hipStream_t st) {
+    if (Rpad <= 0) return;
+    rmsnorm_pad_bf16_kernel<<<(unsigned)Rpad, 256, 0, st>>>(src, C, row_index, weight, eps, dst, ld_dst, Cpad, counts,
+                                                            inv_rms);
+}
+
+int64_t rmsnorm_dweight_blocks(int64_t rows_max) { return (rows_max + RB - 1) / RB; }
+
+void launch_rmsnorm_backward(const bf16_t* x, bf16_t* dh, int64_t d, const bf16_t* weight, const int32_t* row_index,
+                             const int32_t* counts, const float* inv_rms, int64_t rows_max, float* part,
+                             float* dweight, hipStream_t st) {
+    if (rows_max <= 0) return;
+    if (dweight) {
+        const int64_t nblk = rmsnorm_dweight_blocks(rows_max);
+        dim3 grid((unsigned)((d / 8 + 255) / 256), (unsigned)nblk);
+        rmsnorm_dweight_partial_kernel<<<grid, 256, 0, st>>>(x, dh, d, row_index, counts, inv_rms, part);
+        rmsnorm_dweight_reduce_kernel<<<(unsigned)((d + 255) / 256), 256, 0, st>>>(part, d, nblk, counts, dweight);
+    }
+    rmsnorm_dx_kernel<<<(unsigned)rows_max, 256, 0, st>>>(x, dh, d, weight, row_index, counts, inv_rms);
+}
+
+}  // namespace rapid

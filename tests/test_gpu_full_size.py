@@ -210,3 +210,43 @@ def test_config2_one_group_every_element(rb):
         assert abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]) <= 1e-3
         assert rel(_f64(out.dhidden), ref["dH"]) <= 2e-2 and rel(_f64(out.dW), ref["dW"]) <= 2e-2
         assert out.read_diag()["n_tokens"] == ref["n_tokens"]
+
+
+def test_config2_one_group_with_final_rmsnorm(rb):
+    """The same kind of slice (group 3 of the headline workload, full d and V) with the hidden states
+    taken as the input of a final RMSNorm: every element of log-probs, loss, dW, dL/dx and dL/dweight
+    against the oracle (which rounds the normalised state to bf16, as the contraction's operand is)."""
+    spec = wl.CONFIGS[2]
+    print("generating", spec.name, flush=True)
+    w = wl.make_workload(spec, seed=0, device="cuda")
+    G, grp = spec.G, 3
+    n0, n1 = grp * G, (grp + 1) * G
+    Tm = int(w["lengths"][n0:n1].max().item())
+    gen = torch.Generator(device="cuda").manual_seed(2)
+    scale = 0.5 + 2.0 * torch.rand((G, Tm, 1), device="cuda", generator=gen)
+    hid = (w["hidden"][n0:n1, :Tm].float() * scale).to(torch.bfloat16).contiguous()
+    tok, mask = (w[k][n0:n1, :Tm].contiguous() for k in ("tokens", "mask"))
+    wgt = (1.0 + 0.1 * torch.randn(spec.d, device="cuda", generator=gen)).to(torch.bfloat16)
+    rew = w["rewards"][n0:n1].contiguous()
+    gid = torch.zeros(G, dtype=torch.int32, device="cuda")
+    logp_b, _ = rb.rapid_logprob_fwd(hid, w["W_old"], tok, mask, rms_weight=wgt)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(hid, w["W"], tok, mask, logp_b, rew, gid, 1, normalized_grads=True,
+                                      logits_cache=True, rms_weight=wgt)
+    torch.cuda.synchronize()
+    print("oracle", flush=True)
+    ref = orc.iw_pg_loss_fwd_bwd(_f64(hid), _f64(w["W"]), tok.cpu().numpy(), mask.cpu().numpy(), _f64(logp_b), _f64(rew),
+                                 np.zeros(G, np.int64), 1, normalized_grads=True, row_chunk=512, rms_weight=_f64(wgt),
+                                 round_normed_hidden=True)
+    rel = lambda a, b: np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+    assert out.dev_status.item() == 0
+    # A normalised element on a bf16 rounding boundary can round one way from the kernel's fp32 product
+    # and the other way from the oracle's fp64 one (about 2.5e-5 of the elements, a few per cent of the
+    # rows); one such element moves the row's log-prob by ulp(h) * |W| ~ 1e-4.  Everything else
+    # agrees to the usual 2e-5.
+    err = np.abs(_f64(out.logp_cur) - ref["logp_cur"])[mask.cpu().numpy() != 0]
+    assert err.max() <= 2e-3 and (err <= 2e-5).mean() >= 0.9
+    assert np.abs(_f64(out.seq_logratio) - ref["seq_logratio"]).max() <= 5e-3
+    assert abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]) <= 5e-3
+    assert abs(out.loss.item() - ref["loss"]) <= 1e-2 * abs(ref["loss"])
+    assert rel(_f64(out.dhidden), ref["dH"]) <= 2e-2 and rel(_f64(out.dW), ref["dW"]) <= 2e-2
+    assert rel(_f64(out.drms_weight), ref["d_rms_weight"]) <= 2e-2

@@ -364,6 +364,48 @@ def test_fwd_bwd_token_level_ratio(rb, name, cache):
     assert torch.equal(a.dhidden, b.dhidden) and torch.equal(a.dW, b.dW)      # all ratios exactly 1
 
 
+@pytest.mark.parametrize("name", ["bf16_small", "bf16_ragged"])
+@pytest.mark.parametrize("cache", [False, True])
+def test_fwd_bwd_with_final_rmsnorm(rb, name, cache):
+    """rms_weight: hidden is the input x of the final RMSNorm, applied while the rows are packed.
+    The oracle runs the path on rmsnorm(x) rounded to bf16 (what the contraction reads) and pushes dH
+    through the norm: log-probs, ratios, loss, dW, dL/dx and dL/dweight, every element.  A normalised
+    element that sits on a bf16 rounding boundary may round the other way from the kernel's fp32
+    product than from the oracle's fp64 one, which moves that row's log-prob by ~1e-4: a few rows may
+    be off by that much, the rest agree to the usual 2e-5."""
+    print(f"fwd_bwd rmsnorm {name} cache={cache}", flush=True)
+    spec = SPECS[name]
+    w, g = _make(spec)
+    rng = np.random.default_rng(31)
+    d = spec.d
+    x = (g["hidden"].float() * torch.from_numpy(rng.uniform(0.3, 3.0, size=g["hidden"].shape[:2] + (1,))).float().cuda()
+         ).to(torch.bfloat16)                                         # rows of different scale: the norm matters
+    wgt = torch.from_numpy(1.0 + 0.2 * rng.normal(size=d)).float().cuda().to(torch.bfloat16)
+    eps = 1e-5
+    logp_b, _ = rb.rapid_logprob_fwd(x, g["W_old"], g["tokens"], g["mask"], rms_weight=wgt, rms_eps=eps)
+    out = rb.rapid_iw_pg_loss_fwd_bwd(x, g["W"], g["tokens"], g["mask"], logp_b, g["rewards"], g["group_ids"], w["K"],
+                                      logits_cache=cache, rms_weight=wgt, rms_eps=eps)
+    lp2, _ = rb.rapid_logprob_fwd(x, g["W"], g["tokens"], g["mask"], rms_weight=wgt, rms_eps=eps)
+    torch.cuda.synchronize()
+    assert out.dev_status.item() == 0 and torch.equal(lp2, out.logp_cur)
+    _, W, tok, mask = _oracle_inputs(w)
+    ref = orc.iw_pg_loss_fwd_bwd(_np(x), W, tok, mask, _np(logp_b), _np(w["rewards"]), _np(w["group_ids"]), w["K"],
+                                 rms_weight=_np(wgt), rms_eps=eps, round_normed_hidden=True)
+    err = np.abs(_np(out.logp_cur) - ref["logp_cur"])[mask != 0]
+    assert err.max() <= 2e-3 and (err <= 2e-5).mean() >= 0.9
+    assert np.abs(_np(out.seq_logratio) - ref["seq_logratio"]).max() <= 2e-3
+    assert abs(out.loss.item() - ref["loss"]) <= 3e-3 * abs(ref["loss"])
+    assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+    assert _rel(_np(out.dhidden), ref["dH"]) <= GRAD_RTOL["bf16"]
+    assert _rel(_np(out.drms_weight), ref["d_rms_weight"]) <= GRAD_RTOL["bf16"]
+    assert np.all(_np(out.dhidden)[mask == 0] == 0.0)
+    # the norm really is inside: unit weight and rows already of unit mean square change nothing but rounding
+    ones = torch.ones(d, dtype=torch.bfloat16, device="cuda")
+    lp_plain, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])
+    lp_unit, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"], rms_weight=ones, rms_eps=0.0)
+    assert (lp_plain - lp_unit).abs().max().item() < 0.05 and not torch.equal(logp_b, lp_plain)
+
+
 @pytest.mark.parametrize("scale,flagged", [(25.0, False), (250.0, True)])
 def test_logits_cache_unlikely_sampled_tokens(rb, scale, flagged):
     """The cached ratios are relative to the sampled token's probability.  Peaked rows (logit spread

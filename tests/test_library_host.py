@@ -38,11 +38,13 @@ def test_exports_every_declared_symbol(rb):
 
 def test_struct_layouts_match_header(rb):
     assert C.sizeof(rb.IwPgDiag) == 32
-    assert C.sizeof(rb.IwPgOpts) == 64 and rb.IwPgOpts.max_tokens.offset == 48 and rb.IwPgOpts.coef_override.offset == 56
+    assert C.sizeof(rb.IwPgOpts) == 88 and rb.IwPgOpts.max_tokens.offset == 48 and rb.IwPgOpts.coef_override.offset == 56
+    assert rb.IwPgOpts.rms_weight.offset == 64 and rb.IwPgOpts.drms_weight_out.offset == 72 and rb.IwPgOpts.rms_eps.offset == 80
     o = rb.default_opts()
     assert o.eta == 2.0 and o.loss_scale == 1.0 and o.temperature == 1.0
     assert o.coef_mode == 0 and o.baseline_mode == 0 and o.w_layout == rb.W_DV and o.dw_dtype == rb.DTYPE_F32
     assert o.logits_cache == 0 and o.ratio_level == 0 and o.max_tokens == 0 and not o.coef_override
+    assert not o.rms_weight and not o.drms_weight_out and abs(o.rms_eps - 1e-6) < 1e-12
 
 
 def test_workspace_sizes(rb):
@@ -103,6 +105,14 @@ def test_host_validation_returns_codes_without_a_gpu(rb):
     o = rb.default_opts()
     o.max_tokens = -5
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
+    o = rb.default_opts()
+    o.rms_weight, o.rms_eps = 256, -1.0                     # negative eps
+    assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
+    # the final norm is a bf16 option
+    assert lib.rapid_logprob_fwd_rmsnorm(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_F32, rb.W_DV, 1.0, one, 1e-6, one, None,
+                                         None, one, 1 << 30, None) == -3
+    assert lib.rapid_logprob_fwd_rmsnorm(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, None, 1e-6, one, None,
+                                         None, one, 1 << 30, None) == -1
     o = rb.default_opts()
     o.loss_scale = -1.0
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
