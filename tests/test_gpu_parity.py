@@ -305,6 +305,35 @@ def test_edge_cases(rb):
     assert status.item() & rb.STATUS_BAD_TOKEN
 
 
+@pytest.mark.parametrize("shape", [dict(d=8, V=5, prompts=1, G=2, len_lo=1, len_hi=1),
+                                   dict(d=24, V=300, prompts=2, G=2, len_lo=1, len_hi=3),
+                                   dict(d=264, V=257, prompts=3, G=2, len_lo=100, len_hi=130)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_smallest_and_off_tile_shapes(rb, shape, dtype):
+    """The smallest accepted shapes (one token per generation, d = 8, a vocabulary of 5; two generations,
+    because a group of one has the advantage R (1 - w), a difference of nearly equal numbers whose
+    fp32 rounding no gradient tolerance survives) and sizes just past a tile
+    boundary (d = 256 + 8, V = 256 + 1, more than 256 rows), in both backward modes, with the
+    token-level weight as well; and a batch without a single valid token in the cache mode."""
+    print(f"small shapes {shape} {dtype}", flush=True)
+    spec = wl.small_spec("edge", dtype, reward="uniform", **shape)
+    for kw in (dict(), dict(logits_cache=True), dict(logits_cache=True, ratio_level=1, coef_mode=1)):
+        if kw.get("logits_cache") and dtype != "bf16":
+            continue
+        w, out, ref = _run_pair(rb, spec, **kw)
+        _check_pair(rb, spec, out, ref)
+    if dtype == "bf16":
+        w, g = _make(spec)
+        mask = torch.zeros_like(g["mask"])
+        wgt = torch.ones(spec.d, dtype=torch.bfloat16, device="cuda")
+        out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], mask, None, g["rewards"], g["group_ids"], w["K"],
+                                          logits_cache=True, rms_weight=wgt)
+        torch.cuda.synchronize()
+        assert out.dev_status.item() == 0 and out.read_diag()["n_tokens"] == 0
+        assert torch.all(out.dW == 0) and torch.all(out.dhidden == 0) and torch.all(out.drms_weight == 0)
+        assert torch.all(out.logp_cur == 0) and torch.all(out.seq_logratio == 0)
+
+
 def test_mfma_probe_and_forward_row_blocks(rb):
     """The probe reports a rate between zero and the published peak, random operands never beat
     integer ones by more than noise; the forward gives the same bits for any row-block size."""
