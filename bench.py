@@ -159,6 +159,7 @@ def main():
         if cache:
             # the cache is sized for the batch's token count, which a trainer knows from its sampler
             need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16, max_tokens=M)
+            torch.cuda.empty_cache()     # what the workload generator left in torch's allocator counts as free
             free, _ = torch.cuda.mem_get_info()
             if not need or need + (8 << 30) > free:
                 return None
