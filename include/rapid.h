@@ -50,9 +50,11 @@ extern "C" {
 #define RAPID_STATUS_NONFINITE_LOGP 8
 #define RAPID_STATUS_TOKEN_BOUND 32 /* more valid tokens than opts->max_tokens promised (logits_cache = 1): the tokens
                                       past the bound were left out; the call's outputs are not usable */
-#define RAPID_STATUS_LOGIT_RANGE 16 /* logits_cache = 1 only: in some row the sampled token is more than e^79 times
-                                       less likely than the most likely one; loss and log-probs are exact, that
-                                       row's share of dhidden and dW is truncated */
+#define RAPID_STATUS_LOGIT_RANGE 16 /* logits_cache = 1 only: in some row a logit, or the log-sum-exp, is more than 79
+                                       away from the reference the cached values are relative to (the sampled
+                                       token's logit minus its behaviour log-prob; the sampled token's logit alone
+                                       without logp_behav).  Loss and log-probs are exact, that row's share of
+                                       dhidden and dW is truncated */
 
 /* enums */
 #define RAPID_DTYPE_F32 0
@@ -83,11 +85,13 @@ typedef struct rapid_iw_pg_opts {
                               ratios that underflow fp32 still give usable gradients */
     int logits_cache;      /* 0 (default): the backward regenerates the logits tile by tile from hidden and W;
                               nothing of size rows x V outlives a row chunk.  1 (bf16 inputs only): the
-                              forward also stores, in the workspace, the ratio p_v / p_y (bf16) of every
-                              vocabulary entry's probability to that of the row's sampled token, and the
-                              backward contracts those directly (dz = -g p_y (ratio - onehot / p_y)): one
-                              contraction fewer and no pass over rows x V in between, for N*T*V*2 more
-                              bytes of workspace (rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...)).
+                              forward also stores, in the workspace, exp(z_v - r) (bf16) for every vocabulary
+                              entry, r = the sampled token's logit minus its behaviour log-prob (an estimate
+                              of the row's log-sum-exp that is known before the sweep, so the stored value
+                              is close to the probability p_v), and the backward contracts those directly
+                              (dz = -g exp(r - lse) (stored - onehot exp(lse - r))): one contraction fewer
+                              and no pass over rows x V in between, for 2 bytes x rows x V more workspace
+                              (rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...), or ..._max_tokens).
                               Same single bf16 rounding per element of the rows x V intermediate as
                               mode 0; see RAPID_STATUS_LOGIT_RANGE for its one limit */
     int ratio_level;       /* 0 (default): the outer weight of Eq. (3) is the generation-level ratio rho_n, as

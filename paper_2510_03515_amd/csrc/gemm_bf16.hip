@@ -562,11 +562,13 @@ __device__ __forceinline__ void store_tile_through_lds(char* lds, const Lane<S>&
 
 // ------------------------------------------------------------------------------------- fwd_lse
 // STORE: also keep, for a backward that reloads them instead of recomputing the logits, the tile's
-// probability ratios u[j][v] = exp(z[j][v] - r[j]) in bf16 in a.zc.  The reference r[j] is the logit
-// of the row's sampled token (a.zy, known before the sweep), so u = p_v / p_y whatever the row's
-// log-sum-exp turns out to be, and the backward needs one factor per row, -g p_y, instead of a pass
-// over the stored tile.  The exponent is clamped at 2^115 (a sampled token e^-79 times less likely
-// than the row's most likely one); a clamp sets RAPID_STATUS_LOGIT_RANGE.
+// scaled probabilities u[j][v] = exp(z[j][v] - r[j]) in bf16 in a.zc.  The reference r[j] (a.refz) is
+// known before the sweep, so the row's log-sum-exp is not needed to write u, and the backward needs
+// one factor per row, -g exp(r - lse), instead of a pass over the stored tile.  r is the logit of
+// the row's sampled token minus its behaviour log-prob: the behaviour policy's log-sum-exp, moved by
+// the token's own drift, so u is close to the probability itself; without behaviour log-probs it is
+// the sampled token's logit and u = p_v / p_y.  The exponent is clamped at 2^115 (a logit 79 above
+// the reference); a clamp sets RAPID_STATUS_LOGIT_RANGE.
 template <class S, bool STORE>
 __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
@@ -620,7 +622,7 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
 #pragma unroll
         for (int jb = 0; jb < WJ; ++jb) {
             const int64_t j = j_tile + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
-            const float r2 = j < M ? a.zy[j] * LOG2E : 0.f;   // rows past the last token: zero logits
+            const float r2 = j < M ? a.refz[j] * LOG2E : 0.f;   // rows past the last token: zero logits
             float e2 = m[jb] * zs - r2;                        // -inf for a wave of padding columns only
             if (e2 > 115.f) { e2 = 115.f; clamped = true; }
             f[jb] = __builtin_amdgcn_exp2f(e2);
@@ -790,10 +792,14 @@ __global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
 
 // Logit of the sampled token: zy[j] = inv_temp * <Hc[j, :], Wvd[tok_j, :]>, one wave per token row
 // (16-byte loads, fp32 accumulation, fixed reduction tree).
+// If refz is given it receives the reference of the storing forward: zy[j] - ref_logp[row_index[j]]
+// (zy[j] alone without ref_logp or where that value is not finite).
 __global__ __launch_bounds__(256) void token_logit_kernel(const bf16_t* __restrict__ Hc, const bf16_t* __restrict__ Wvd,
                                                           int64_t ldk, int64_t dpad, const int32_t* __restrict__ tokc,
                                                           const int32_t* __restrict__ counts, float inv_temp,
-                                                          float* __restrict__ zy) {
+                                                          float* __restrict__ zy, const float* __restrict__ ref_logp,
+                                                          const int32_t* __restrict__ row_index,
+                                                          float* __restrict__ refz) {
     const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (j >= counts[CNT_M]) return;
     const int lane = threadIdx.x & 63;
@@ -807,7 +813,15 @@ __global__ __launch_bounds__(256) void token_logit_kernel(const bf16_t* __restri
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (lane == 0) zy[j] = acc * inv_temp;
+    if (lane == 0) {
+        const float z = acc * inv_temp;
+        zy[j] = z;
+        if (refz) {
+            float lb = ref_logp ? ref_logp[row_index[j]] : 0.f;
+            if (!isfinite(lb)) lb = 0.f;
+            refz[j] = z - lb;
+        }
+    }
 }
 
 // dz[row][tok_row] += g: the one-hot part of dz = g (onehot - p)
@@ -823,16 +837,17 @@ __global__ void token_onehot_kernel(bf16_t* __restrict__ dz, int64_t ldz, int64_
     *p = __builtin_bit_cast(bf16_t, r);
 }
 
-// After a forward that stored the ratios u = p_v / p_y (see fwd_lse_kernel), with lse and g known:
-// dz[j][v] = (g_j / temperature) (onehot_y[v] - p_v) = c_j u'[j][v], with the row factor
-// c_j = -(g_j / temperature) p_y and u' = u except u'[j][y] = 1 - 1 / p_y.  One wave per token row
-// writes c_j (0 past the last token), replaces that one element, and scales the row of the packed
-// hidden copy by c_j: dW contracts over token rows, so there the factor has to sit on an operand
-// (dHidden applies it to its accumulators).  1 / p_y is clamped at e^80 (sets
-// RAPID_STATUS_LOGIT_RANGE: such a row's gradient is truncated).
+// After a forward that stored u = exp(z - r) (see fwd_lse_kernel), with lse and the row coefficients
+// g known: dz[j][v] = (g_j / temperature) (onehot_y[v] - p_v) = c_j u'[j][v], with the row factor
+// c_j = -(g_j / temperature) exp(r_j - lse_j) and u' = u except at the sampled token, where
+// u'[j][y] = exp(lse_j - r_j) (p_y - 1).  One wave per token row writes c_j (0 past the last
+// token), replaces that one element, and scales the row of the packed hidden copy by c_j: dW
+// contracts over token rows, so there the factor has to sit on an operand (dHidden applies it to
+// its accumulators).  |lse - r| is clamped at 80 (sets RAPID_STATUS_LOGIT_RANGE: such a row's
+// gradient is truncated).
 __global__ __launch_bounds__(256) void cache_finish_kernel(bf16_t* __restrict__ u, int64_t ldz, bf16_t* __restrict__ Hc,
                                                            int64_t ldk, const int32_t* __restrict__ tokc,
-                                                           const float* __restrict__ zy,
+                                                           const float* __restrict__ zy, const float* __restrict__ refz,
                                                            const float* __restrict__ lse_c, const float* __restrict__ rowg,
                                                            float inv_temp, const int32_t* __restrict__ counts,
                                                            float* __restrict__ rowc, int32_t* __restrict__ dev_status) {
@@ -842,14 +857,15 @@ __global__ __launch_bounds__(256) void cache_finish_kernel(bf16_t* __restrict__ 
     if (j >= Mr) return;
     float c = 0.f;
     if (j < M) {
-        float nlp = lse_c[j] - zy[j];   // -log p_y
-        c = -rowg[j] * inv_temp * __expf(-nlp);
+        const float lse = lse_c[j];
+        float a = lse - refz[j];
+        if (!(fabsf(a) <= 80.f)) {
+            a = a > 0.f ? 80.f : -80.f;
+            if (lane == 0 && dev_status) atomicOr(dev_status, RAPID_STATUS_LOGIT_RANGE);
+        }
+        c = -rowg[j] * inv_temp * __expf(-a);
         if (lane == 0) {
-            if (nlp > 80.f) {
-                nlp = 80.f;
-                if (dev_status) atomicOr(dev_status, RAPID_STATUS_LOGIT_RANGE);
-            }
-            const __bf16 r = (__bf16)(-expm1f(nlp));
+            const __bf16 r = (__bf16)(__expf(a) * expm1f(zy[j] - lse));   // exp(lse - r) (p_y - 1)
             u[j * ldz + tokc[j]] = __builtin_bit_cast(bf16_t, r);
         }
     }
@@ -923,7 +939,8 @@ void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
 }
 void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st) {
     token_logit_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(a.Hc, a.Wvd, a.ldk, a.dpad, a.tokc, a.counts,
-                                                                     a.inv_temp, a.zy);
+                                                                     a.inv_temp, a.zy, a.ref_logp, a.row_index,
+                                                                     a.zc ? a.refz : nullptr);
 }
 int fwd_slots_per_tile() { return 2; }
 
@@ -935,9 +952,9 @@ void launch_dz(const DzArgs& a, hipStream_t st) {
 }
 
 void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc,
-                         const float* zy, const float* lse_c, const float* rowg, float inv_temp, const int32_t* counts,
-                         int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st) {
-    cache_finish_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(u, ldz, Hc, ldk, tokc, zy, lse_c, rowg,
+                         const float* zy, const float* refz, const float* lse_c, const float* rowg, float inv_temp,
+                         const int32_t* counts, int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st) {
+    cache_finish_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(u, ldz, Hc, ldk, tokc, zy, refz, lse_c, rowg,
                                                                         inv_temp, counts, rowc, dev_status);
 }
 void launch_dh(const DhArgs& a, hipStream_t st) {

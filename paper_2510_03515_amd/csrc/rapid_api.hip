@@ -69,7 +69,7 @@ struct Plan {
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
-    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, g, g64, tsum, tmax,
+    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, refz, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, g, g64, tsum, tmax,
         Hc, Wvd, Wdv, WdvB, part_max, part_sum, dw32, chunk0;
 };
 
@@ -107,6 +107,7 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     p.tokc = take(cur, (size_t)p.Mmax_pad * 4);
     p.seqc = take(cur, (size_t)p.Mmax_pad * 4);
     p.zy = take(cur, (size_t)p.Mmax_pad * 4);
+    p.refz = take(cur, (size_t)p.Mmax_pad * 4);
     p.lse_c = take(cur, (size_t)p.Mmax_pad * 4);
     if (dtype == RAPID_DTYPE_BF16) p.inv_rms = take(cur, (size_t)p.Mmax_pad * 4);   // final-norm option
     if (bwd) {
@@ -214,6 +215,7 @@ struct FwdIo {
     float* logp_out; float* lse_out; int32_t* dev_status;
     bf16_t* zc = nullptr;   // if set: [row_cap, ldv], the forward also stores the ratios p_v / p_y there
     int64_t row_cap = INT64_MAX;   // compact rows the caller's buffers hold (the cache may be sized for fewer than N*T)
+    const float* ref_logp = nullptr;    // with zc: the behaviour log-probs, for the reference of the stored values
     const void* rms_weight = nullptr;   // if set (bf16 only): hidden is normalised while it is packed
     float rms_eps = 0.f;
 };
@@ -260,6 +262,7 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
         a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy); a.gi = g_gi_fwd;
         a.zc = io.zc; a.ldz = p.ldv; a.dev_status = io.dev_status;
+        a.refz = at<float>(ws, p.refz); a.ref_logp = io.ref_logp; a.row_index = row_index;
         {   // the sampled tokens' logits first: a storing forward uses them as its per-row reference
             Span sp(ST_MERGE, st);
             launch_token_logit(a, p.Mmax_pad, st);
@@ -669,6 +672,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     if (cached) {   // the chunk buffer holds the ratios of every row, up to the p.Mc rows it was sized for
         io.zc = at<bf16_t>(ws, p.chunk0);
         io.row_cap = p.Mc;
+        io.ref_logp = logp_behav;
     }
     io.rms_weight = o.rms_weight;
     io.rms_eps = o.rms_eps;
@@ -720,8 +724,8 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         // rows) and the backward walks the buffer in blocks.
         if (cached) {
             Span sp(ST_DZ, st);
-            launch_cache_finish(at<bf16_t>(ws, p.chunk0), p.ldv, Hc, p.ldk, tokc, at<float>(ws, p.zy), lse_c, rowg,
-                                inv_temp, counts, p.Mmax_pad, at<float>(ws, p.rowc), dev_status, st);
+            launch_cache_finish(at<bf16_t>(ws, p.chunk0), p.ldv, Hc, p.ldk, tokc, at<float>(ws, p.zy), at<float>(ws, p.refz), lse_c,
+                                rowg, inv_temp, counts, p.Mmax_pad, at<float>(ws, p.rowc), dev_status, st);
         }
         const int64_t cstep = g_cached_step_tiles > 0 ? (int64_t)g_cached_step_tiles * ROW_TILE : p.Mc;
         const int64_t step = cached ? (cstep < p.Mc ? cstep : p.Mc) : p.Mc;

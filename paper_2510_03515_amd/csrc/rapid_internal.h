@@ -101,12 +101,15 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     int64_t ld_part;
     float* zy;            // [Mmax_pad]
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
-    bf16_t* zc;           // NULL, or [Mmax_pad, ldz]: the kernel also stores exp(logit - zy[row]) there; zy must be set
+    bf16_t* zc;           // NULL, or [rows, ldz]: the kernel also stores exp(logit - refz[row]) there; refz must be set
     int64_t ldz;
+    float* refz;          // [Mmax_pad] reference of the stored exponentials, written by launch_token_logit if zc is set
+    const float* ref_logp;   // NULL, or [N*T] log-probs subtracted from zy to form refz
+    const int32_t* row_index;
     int32_t* dev_status;  // may be NULL
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
-void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st);   // zy for all rows
+void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st);   // zy (and refz) for all rows
 int fwd_slots_per_tile();
 
 struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, bf16 [Mc, Vpad]
@@ -129,8 +132,8 @@ void launch_dz(const DzArgs& a, hipStream_t st);
 // turns the ratios a storing forward left in u [rows_max, ldz] into the backward's operands: the
 // sampled token's element of each row, the row factors rowc [rows_max], and Hc scaled by them in place
 void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc,
-                         const float* zy, const float* lse_c, const float* rowg, float inv_temp, const int32_t* counts,
-                         int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st);
+                         const float* zy, const float* refz, const float* lse_c, const float* rowg, float inv_temp,
+                         const int32_t* counts, int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st);
 
 struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const bf16_t* Wdv;    // [dpadR, Vpad]

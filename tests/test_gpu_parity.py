@@ -435,40 +435,51 @@ def test_fwd_bwd_with_final_rmsnorm(rb, name, cache):
     assert (lp_plain - lp_unit).abs().max().item() < 0.05 and not torch.equal(logp_b, lp_plain)
 
 
-@pytest.mark.parametrize("scale,flagged", [(25.0, False), (250.0, True)])
-def test_logits_cache_unlikely_sampled_tokens(rb, scale, flagged):
-    """The cached ratios are relative to the sampled token's probability.  Peaked rows (logit spread
-    ~7 and ~70) with tokens drawn uniformly put the sampled token 20..45 and ~200 nats below the row
-    maximum: the first stays inside the cache's range and meets the usual tolerances; the second is
-    outside it, is reported through RAPID_STATUS_LOGIT_RANGE, keeps exact log-probs and finite
-    gradients, and the default mode still matches the oracle on the same inputs."""
+@pytest.mark.parametrize("scale", [25.0, 250.0])
+def test_logits_cache_unlikely_sampled_tokens(rb, scale):
+    """The cached values are relative to a reference known before the sweep: the sampled token's
+    logit minus its behaviour log-prob (the behaviour policy's log-sum-exp, up to the token's drift).
+    Peaked rows (logit spread ~7 and ~70) with tokens drawn uniformly put the sampled token 20..45
+    and ~200 nats below the row maximum: with behaviour log-probs both stay inside the cache's range
+    and meet the usual tolerances.  Without them (on-policy call) the reference is the sampled
+    token's logit: the second case is then out of range, is reported through
+    RAPID_STATUS_LOGIT_RANGE, and keeps exact log-probs and finite gradients."""
     print(f"logits_cache unlikely tokens scale={scale}", flush=True)
     spec = SPECS["bf16_ragged"]
     w, g = _make(spec)
     Wg = (g["W"].float() * scale).to(torch.bfloat16)
+    # behaviour weights: drifted by ~10 nats per logit in the first case, the current ones in the second
+    Wold = (g["W_old"].float() * scale).to(torch.bfloat16) if scale < 100 else Wg
     gen = torch.Generator().manual_seed(5)
     tokens = torch.randint(0, spec.V, tuple(g["tokens"].shape), generator=gen, dtype=torch.int32).cuda()
     N = tokens.shape[0]
     coef = np.random.default_rng(6).normal(size=N).astype(np.float32)
-    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], Wg, tokens, g["mask"])
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], Wold, tokens, g["mask"])
     H, _, _, mask = _oracle_inputs(w)
     ref = orc.iw_pg_loss_fwd_bwd(H, _np(Wg), tokens.cpu().numpy(), mask, _np(logp_b), _np(w["rewards"]),
                                  _np(w["group_ids"]), w["K"], coef_override=coef)
     spread = -ref["logp_cur"][mask != 0]
-    assert (spread.max() < 70) if not flagged else (np.median(spread) > 100)
+    assert (spread.max() < 70) if scale < 100 else (np.median(spread) > 100)
+    logp_ok = lambda out: np.all(np.abs(_np(out.logp_cur) - ref["logp_cur"]) <= 2e-5 + 2e-6 * np.abs(ref["logp_cur"]))
     for cache in (True, False):
         out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], Wg, tokens, g["mask"], logp_b, g["rewards"], g["group_ids"],
                                           w["K"], logits_cache=cache, coef_override=torch.from_numpy(coef).cuda())
         torch.cuda.synchronize()
-        assert np.all(np.abs(_np(out.logp_cur) - ref["logp_cur"]) <= 2e-5 + 2e-6 * np.abs(ref["logp_cur"]))
-        assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
-        if cache and flagged:
-            assert out.dev_status.item() == rb.STATUS_LOGIT_RANGE
-            assert np.isfinite(_np(out.dhidden)).all() and np.isfinite(_np(out.dW)).all()
-        else:
-            assert out.dev_status.item() == 0
-            assert _rel(_np(out.dhidden), ref["dH"]) <= GRAD_RTOL["bf16"]
-            assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+        assert logp_ok(out) and abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+        assert out.dev_status.item() == 0
+        assert _rel(_np(out.dhidden), ref["dH"]) <= GRAD_RTOL["bf16"]
+        assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+    # no behaviour log-probs: the reference is the sampled token's own logit
+    out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], Wg, tokens, g["mask"], None, g["rewards"], g["group_ids"],
+                                      w["K"], logits_cache=True, coef_override=torch.from_numpy(coef).cuda())
+    torch.cuda.synchronize()
+    assert logp_ok(out)
+    if scale < 100:
+        assert out.dev_status.item() == 0
+        assert _rel(_np(out.dhidden), ref["dH"]) <= GRAD_RTOL["bf16"] and _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+    else:
+        assert out.dev_status.item() == rb.STATUS_LOGIT_RANGE
+        assert np.isfinite(_np(out.dhidden)).all() and np.isfinite(_np(out.dW)).all()
 
 
 def test_logits_cache_sized_for_a_token_bound(rb):
