@@ -159,15 +159,25 @@ __global__ void merge_lse_kernel(const float* __restrict__ part_max, const float
     // partial sums themselves), the accumulation fp64.
     float mx = -INFINITY;
     double acc = 0.0;
-    for (int p = 0; p < P; ++p) {
-        const float pm = part_max[p * ld_part + j];
-        const float ps = part_sum[p * ld_part + j];
-        if (!(ps > 0.f)) continue;
-        if (pm > mx) {
-            acc = acc * (double)__expf(mx - pm) + (double)ps;   // exp(-inf) = 0 on the first slot
-            mx = pm;
-        } else {
-            acc += (double)ps * (double)__expf(pm - mx);
+    constexpr int UN = 8;   // slots loaded ahead of the fold: the loads of a batch are in flight together
+    for (int p0 = 0; p0 < P; p0 += UN) {
+        float pmv[UN], psv[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const bool in = p0 + u < P;
+            pmv[u] = in ? part_max[(int64_t)(p0 + u) * ld_part + j] : 0.f;
+            psv[u] = in ? part_sum[(int64_t)(p0 + u) * ld_part + j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const float pm = pmv[u], ps = psv[u];
+            if (!(ps > 0.f)) continue;
+            if (pm > mx) {
+                acc = acc * (double)__expf(mx - pm) + (double)ps;   // exp(-inf) = 0 on the first slot
+                mx = pm;
+            } else {
+                acc += (double)ps * (double)__expf(pm - mx);
+            }
         }
     }
     const double lse = (double)mx + log(acc);
