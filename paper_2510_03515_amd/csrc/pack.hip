@@ -46,15 +46,49 @@ __global__ void copy_pad_bf16_kernel(const bf16_t* __restrict__ src, int64_t ld_
     }
 }
 
-// 64x64 tile through LDS: dst[c][r] = src[r][c]
-__global__ void transpose_pad_bf16_kernel(const bf16_t* __restrict__ src, int64_t ld_src,
-                                          bf16_t* __restrict__ dst, int64_t ld_dst, int64_t R, int64_t C,
-                                          int64_t Rpad, int64_t Cpad, const int32_t* __restrict__ counts,
-                                          int64_t r0) {
+// 64x64 tile through LDS: dst[c][r] = src[r][c].  16-byte global accesses on both sides when the
+// shapes allow (vec: ld_src, ld_dst multiples of 8, 16-byte aligned bases), elements otherwise.
+// LDS rows are 66 elements (33 banks) apart: the transposed read of 8 rows x 8 columns per 64 lanes
+// is conflict free.
+__global__ __launch_bounds__(256) void transpose_pad_bf16_kernel(const bf16_t* __restrict__ src, int64_t ld_src,
+                                                                 bf16_t* __restrict__ dst, int64_t ld_dst, int64_t R,
+                                                                 int64_t C, int64_t Rpad, int64_t Cpad,
+                                                                 const int32_t* __restrict__ counts, int64_t r0, int vec) {
     __shared__ bf16_t tile[64][66];
     const RowLimits lim = row_limits(counts, r0, R, Rpad);
     const int64_t rb = (int64_t)blockIdx.x * 64, cb = (int64_t)blockIdx.y * 64;
     if (rb >= lim.Rpad) return;
+    if (vec) {
+        for (int t = threadIdx.x; t < 512; t += 256) {          // 64 rows x 8 chunks of 8 columns
+            const int rr = t >> 3, q = t & 7;
+            const int64_t r = rb + rr, c = cb + q * 8;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (r < lim.R && c + 8 <= C) {
+                v = *(const uint4*)(src + r * ld_src + c);
+            } else if (r < lim.R && c < C) {
+                bf16_t e[8];
+                for (int i = 0; i < 8; ++i) e[i] = c + i < C ? src[r * ld_src + c + i] : (bf16_t)0;
+                v = *(const uint4*)e;
+            }
+            uint32_t* p = (uint32_t*)&tile[rr][q * 8];          // 4-byte aligned: row stride 132 bytes
+            p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w;
+        }
+        __syncthreads();
+        for (int t = threadIdx.x; t < 512; t += 256) {          // 64 destination rows x 8 chunks of 8
+            const int cc = t >> 3, q = t & 7;
+            const int64_t c = cb + cc, r = rb + q * 8;
+            if (c >= Cpad || r >= lim.Rpad) continue;
+            bf16_t e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) e[i] = tile[q * 8 + i][cc];
+            if (r + 8 <= lim.Rpad) {
+                *(uint4*)(dst + c * ld_dst + r) = *(const uint4*)e;
+            } else {
+                for (int i = 0; i < 8 && r + i < lim.Rpad; ++i) dst[c * ld_dst + r + i] = e[i];
+            }
+        }
+        return;
+    }
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;   // 256 threads: 64 x 4
     for (int rr = ty; rr < 64; rr += 4) {
         const int64_t r = rb + rr, c = cb + tx;
@@ -102,7 +136,8 @@ void launch_transpose_pad_bf16(const bf16_t* src, int64_t ld_src, bf16_t* dst, i
                                hipStream_t st) {
     if (Rpad <= 0 || Cpad <= 0) return;
     dim3 grid((unsigned)((Rpad + 63) / 64), (unsigned)((Cpad + 63) / 64));
-    transpose_pad_bf16_kernel<<<grid, 256, 0, st>>>(src, ld_src, dst, ld_dst, R, C, Rpad, Cpad, counts, r0);
+    const int vec = (ld_src % 8 == 0) && (ld_dst % 8 == 0) && (((uintptr_t)src) % 16 == 0) && (((uintptr_t)dst) % 16 == 0);
+    transpose_pad_bf16_kernel<<<grid, 256, 0, st>>>(src, ld_src, dst, ld_dst, R, C, Rpad, Cpad, counts, r0, vec);
 }
 
 }  // namespace rapid
