@@ -65,7 +65,8 @@ def cpu_baseline(w, rb, group=2, logits_cache=False):
               "dH_rel": rel(f64(out.dhidden), ref["dH"]), "dW_rel": rel(f64(out.dW), ref["dW"]),
               "seq_logratio_abs": float(np.abs(f64(out.seq_logratio) - ref["seq_logratio"]).max()),
               "grad_log_scale_abs": abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]),
-              "tolerances": {"loss_rel": 1e-3, "dH_rel": 2e-2, "dW_rel": 2e-2, "seq_logratio_abs": 1e-3}}
+              "tolerances": {"loss_rel": 1e-3, "dH_rel": 2e-2 if spec.dtype == "bf16" else 1e-5,
+                             "dW_rel": 2e-2 if spec.dtype == "bf16" else 1e-5, "seq_logratio_abs": 1e-3}}
     threads = torch.get_num_threads()
     try:
         import threadpoolctl
@@ -130,6 +131,7 @@ def main():
             key, val = kv.split("=")
             rb.rapid_set_tuning(int(key), int(val))
     fwd_only = spec.fwd_only
+    dt_code = rb.DTYPE_BF16 if spec.dtype == "bf16" else rb.DTYPE_F32   # config 0 is the fp32 accuracy path
     rms = {}
     if args.rmsnorm:
         gen = torch.Generator(device="cuda").manual_seed(1)
@@ -156,9 +158,11 @@ def main():
 
     def fused_mode(cache):
         """Times rapid_iw_pg_loss_fwd_bwd in one backward mode; None if the cache does not fit."""
+        if cache and spec.dtype != "bf16":
+            return None              # the cache is a bf16 mode
         if cache:
             # the cache is sized for the batch's token count, which a trainer knows from its sampler
-            need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16, max_tokens=M)
+            need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dt_code, max_tokens=M)
             torch.cuda.empty_cache()     # what the workload generator left in torch's allocator counts as free
             free, _ = torch.cuda.mem_get_info()
             if not need or need + (8 << 30) > free:
@@ -167,7 +171,7 @@ def main():
         else:
             ws_bytes = int(args.workspace_gib * 2**30) if args.workspace_gib > 0 else None
             if args.chunk_rows:
-                mn = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, N, T, d, V, K, rb.DTYPE_BF16, minimum=True)
+                mn = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, N, T, d, V, K, dt_code, minimum=True)
                 vpad = (V + 255) // 256 * 256
                 ldv = vpad + 64 if (vpad // 64) % 2 == 0 else vpad
                 ws_bytes = mn + (args.chunk_rows - 256) * ldv * 2
@@ -181,7 +185,7 @@ def main():
         return dt, stages, ws_gib
 
     if fwd_only:
-        ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, rb.DTYPE_BF16)
+        ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, dt_code)
         ws = rb.alloc_workspace(ws_bytes)
         dt, stages = timed(lambda: rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], workspace=ws, **rms))
         ws_gib = ws_bytes / 2**30
@@ -207,30 +211,39 @@ def main():
     # over the launches of a stage (row blocks), so one launch processes M / (launches that hold
     # tokens) tokens on average.
     gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and stages[s]["launches_per_step"] > 1]
-    dom = max(gemm_stages, key=lambda s: stages[s]["ms_per_step"])
-    launches = stages[dom]["launches_per_step"]
-    # blocks past the last valid row exit at once: count only launches that had rows
-    Mmax_pad = (N * T + 255) // 256 * 256
-    chunk_rows = Mmax_pad / launches
-    live = max(1, -(-M // int(chunk_rows)))
-    tokens_per_launch = M / live
-    avg_ms = stages[dom]["ms_per_step"] / live
-    achieved = 2.0 * d * V * tokens_per_launch / (avg_ms * 1e-3) / 1e12
-    # HBM-side bytes per full launch from rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by a copy
-    # kernel of known size); measured on the headline workload only, see profiles/
-    traffic = MEASURED_TRAFFIC_BYTES.get((mode, dom)) if spec.name == "cfg2_qwen1.5b" else None
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA / 1e12,
-                "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_MFMA / 1e12), "traffic": traffic,
-                "traffic_unit": "bytes per full launch (fabric reads + writes)",
-                "traffic_source": "profiles/bench_cfg2_qwen1.5b_kernel_trace_and_traffic.md",
-                "avg_launch_ms": avg_ms, "live_launches_per_step": live,
-                "tokens_per_launch": tokens_per_launch, "flop_per_token": 2.0 * d * V}
+    if gemm_stages:
+        dom = max(gemm_stages, key=lambda s: stages[s]["ms_per_step"])
+        launches = stages[dom]["launches_per_step"]
+        # blocks past the last valid row exit at once: count only launches that had rows
+        Mmax_pad = (N * T + 255) // 256 * 256
+        chunk_rows = Mmax_pad / launches
+        live = max(1, -(-M // int(chunk_rows)))
+        tokens_per_launch = M / live
+        avg_ms = stages[dom]["ms_per_step"] / live
+        achieved = 2.0 * d * V * tokens_per_launch / (avg_ms * 1e-3) / 1e12
+        # HBM-side bytes per full launch from rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by a copy
+        # kernel of known size); measured on the headline workload only, see profiles/
+        traffic = MEASURED_TRAFFIC_BYTES.get((mode, dom)) if spec.name == "cfg2_qwen1.5b" else None
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA / 1e12,
+                    "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_MFMA / 1e12), "traffic": traffic,
+                    "traffic_unit": "bytes per full launch (fabric reads + writes)",
+                    "traffic_source": "profiles/bench_cfg2_qwen1.5b_kernel_trace_and_traffic.md",
+                    "avg_launch_ms": avg_ms, "live_launches_per_step": live,
+                    "tokens_per_launch": tokens_per_launch, "flop_per_token": 2.0 * d * V}
+    else:
+        # the fp32 accuracy path (config 0): plain strided contractions with fp64 accumulation on the
+        # vector ALUs, four of them per call (logits twice, dHidden, dW); all its launches are one stage
+        ms = stages["f32_path"]["ms_per_step"]
+        achieved = 8.0 * d * V * M / (ms * 1e-3) / 1e12
+        roofline = {"bound": "alu", "kernel": "f32_path", "achieved": achieved, "peak": 78.6, "unit": "TFLOP/s",
+                    "frac": achieved / 78.6, "traffic": None, "avg_launch_ms": ms,
+                    "note": "fp64 vector peak; the path is an accuracy path and a few launches of tiny size"}
 
     out = {
         "metric": "response tokens/s for fused IW group-adv PG fwd+bwd; % bf16 MFMA peak",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "d": d, "V": V, "prompts": spec.prompts, "G": spec.G, "N": N,
                    "T": T, "response_tokens": M, "workspace_gib": ws_gib,
                    "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd",
