@@ -334,6 +334,34 @@ def test_smallest_and_off_tile_shapes(rb, shape, dtype):
         assert torch.all(out.logp_cur == 0) and torch.all(out.seq_logratio == 0)
 
 
+def test_seeded_random_shapes_and_options(rb):
+    """Twelve seeded draws of shape (d a multiple of 8 up to 400, V up to 2000, up to ~1500 token rows)
+    and options (layout, backward mode, coefficient mode, ratio level, baseline, temperature, dW
+    dtype), each against the oracle element by element.  (Behaviour weights always differ from the
+    current ones here: on-policy the loss is an exact zero, which has its own test.)"""
+    rng = np.random.default_rng(2024)
+    for case in range(12):
+        d = int(rng.integers(1, 51)) * 8
+        V = int(rng.integers(2, 2001))
+        prompts, G = int(rng.integers(1, 6)), int(rng.integers(2, 5))
+        hi = int(rng.integers(1, 120))
+        lo = int(rng.integers(1, hi + 1))
+        spec = wl.small_spec(f"rand{case}", "bf16", d=d, V=V, prompts=prompts, G=G, len_lo=lo, len_hi=hi,
+                             sigma=float(rng.choice([0.002, 0.005, 0.02])), reward=str(rng.choice(["bernoulli", "uniform"])))
+        kw = dict(logits_cache=bool(rng.integers(0, 2)), coef_mode=int(rng.integers(0, 2)),
+                  ratio_level=int(rng.integers(0, 2)), baseline_mode=int(rng.integers(0, 3)),
+                  temperature=float(rng.choice([1.0, 0.7, 1.3])), normalized_grads=bool(rng.integers(0, 2)))
+        layout = str(rng.choice(["dv", "vd"]))
+        dw_dtype = torch.bfloat16 if rng.integers(0, 4) == 0 else torch.float32
+        print(f"random case {case}: d={d} V={V} N={prompts * G} T={hi} {layout} {kw} dW={dw_dtype}", flush=True)
+        w, out, ref = _run_pair(rb, spec, seed=case, layout=layout, dw_dtype=dw_dtype, **kw)
+        if dw_dtype == torch.bfloat16:          # the stored gradient is itself rounded: compare apart from that
+            dW = _np(out.dW) if layout == "dv" else _np(out.dW).T
+            assert _rel(dW, ref["dW"]) <= GRAD_RTOL["bf16"]
+            out.dW = torch.from_numpy(ref["dW"] if layout == "dv" else ref["dW"].T.copy()).float().cuda()
+        _check_pair(rb, spec, out, ref, layout)
+
+
 def test_mfma_probe_and_forward_row_blocks(rb):
     """The probe reports a rate between zero and the published peak, random operands never beat
     integer ones by more than noise; the forward gives the same bits for any row-block size."""
