@@ -84,8 +84,8 @@ def cpu_baseline(w, rb, group=2, logits_cache=False):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (2 = headline)")
     ap.add_argument("--calibrated", action="store_true",
                     help="the workload's calibrated companion: same shapes and seed, behaviour weights close enough "
