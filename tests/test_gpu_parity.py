@@ -699,3 +699,46 @@ def test_fused_shuffled_groups_mask_holes_and_bad_values(rb):
     assert np.abs(_np(out.seq_logratio) - ref["seq_logratio"]).max() <= S_ATOL
     assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
     assert _rel(_np(out.dW), ref["dW"]) <= GRAD_RTOL["bf16"]
+
+
+def test_autograd_wrapper_against_plain_pytorch(rb):
+    """The fused call as a PyTorch loss: gradients reach a PyTorch body through `hidden`, and they
+    agree with torch's own autograd of the same estimator written in plain fp32 PyTorch ops on the
+    GPU (a leg independent of the oracle): loss, dL/dW and dL/d(body weight)."""
+    from paper_2510_03515_amd.autograd import iw_pg_loss
+    spec = SPECS["bf16_small"]
+    w, g = _make(spec)
+    N, T, d = g["hidden"].shape
+    torch.manual_seed(3)
+    body = torch.nn.Linear(d, d, bias=False).cuda()
+    with torch.no_grad():
+        body.weight.copy_(torch.eye(d, device="cuda") + 0.05 * torch.randn(d, d, device="cuda"))
+    x = g["hidden"].float()
+    mask, tok, R, gid, K = g["mask"], g["tokens"], g["rewards"], g["group_ids"].long(), w["K"]
+    logp_b, _ = rb.rapid_logprob_fwd(body(x).to(torch.bfloat16).detach(), g["W_old"], tok, mask)
+
+    def plain(hidden, W):
+        z = hidden.float() @ W.float()
+        logp = torch.log_softmax(z, -1).gather(-1, tok.long()[..., None]).squeeze(-1)
+        s = ((logp - logp_b) * mask).sum(1)
+        wgt = torch.exp(torch.clamp(s, max=math.log(2.0))).detach()
+        cnt = torch.zeros(K, device="cuda").index_add(0, gid, torch.ones_like(R))
+        base = torch.zeros(K, device="cuda").index_add(0, gid, wgt * R) / cnt
+        adv = (R - base[gid]).detach()
+        return -(torch.exp(s) * adv).mean()
+
+    grads = []
+    for fn in (lambda h, W: iw_pg_loss(h, W, tok, mask, logp_b, R, g["group_ids"], K), plain):
+        body.zero_grad()
+        W = g["W"].clone().requires_grad_(True)
+        loss = fn(body(x).to(torch.bfloat16), W)
+        loss.backward()
+        grads.append((loss.item(), W.grad.float().clone(), body.weight.grad.clone()))
+    (l0, dW0, db0), (l1, dW1, db1) = grads
+    assert abs(l0 - l1) <= 2e-3 * abs(l1)
+    assert _rel(_np(dW0), _np(dW1)) <= 3e-2 and _rel(_np(db0), _np(db1)) <= 3e-2
+    # the incoming gradient scales both
+    body.zero_grad()
+    W = g["W"].clone().requires_grad_(True)
+    (3.0 * iw_pg_loss(body(x).to(torch.bfloat16), W, tok, mask, logp_b, R, g["group_ids"], K)).backward()
+    assert _rel(_np(W.grad.float()), 3.0 * _np(dW0)) <= 1e-2
