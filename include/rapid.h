@@ -14,9 +14,10 @@
  *  - Return value: RAPID_OK or a negative RAPID_ERR_* detected on the host before any launch
  *    (nothing has been enqueued then).  rapid_last_error() gives a thread-local message.
  *  - Errors only the device can see (token id outside [0,V) at an unmasked position, group id
- *    outside [0,K), non-finite reward or behaviour log-prob) OR a bit into the caller's
- *    `dev_status` word (may be NULL); the offending element is treated as token 0 / skipped /
- *    0 and nothing faults.  The library only ORs bits in: the caller clears the word.
+ *    outside [0,K), non-finite reward or behaviour log-prob; with opts->logits_cache also the two
+ *    conditions documented at RAPID_STATUS_LOGIT_RANGE and RAPID_STATUS_TOKEN_BOUND) OR a bit into
+ *    the caller's `dev_status` word (may be NULL); the offending element is treated as token 0 /
+ *    skipped / 0 and nothing faults.  The library only ORs bits in: the caller clears the word.
  *  - Layouts: hidden [N,T,d] row-major (padded), dtype bf16 or fp32; hidden row (n,t) is the
  *    state that predicts tokens[n,t].  W is logically [d,V]; w_layout says how it is stored:
  *    RAPID_W_DV = [d,V] row-major, RAPID_W_VD = [V,d] row-major.  tokens [N,T] int32;
@@ -48,13 +49,13 @@ extern "C" {
 #define RAPID_STATUS_BAD_GROUP 2
 #define RAPID_STATUS_NONFINITE_REWARD 4
 #define RAPID_STATUS_NONFINITE_LOGP 8
-#define RAPID_STATUS_TOKEN_BOUND 32 /* more valid tokens than opts->max_tokens promised (logits_cache = 1): the tokens
-                                      past the bound were left out; the call's outputs are not usable */
 #define RAPID_STATUS_LOGIT_RANGE 16 /* logits_cache = 1 only: in some row a logit, or the log-sum-exp, is more than 79
                                        away from the reference the cached values are relative to (the sampled
                                        token's logit minus its behaviour log-prob; the sampled token's logit alone
                                        without logp_behav).  Loss and log-probs are exact, that row's share of
                                        dhidden and dW is truncated */
+#define RAPID_STATUS_TOKEN_BOUND 32 /* more valid tokens than opts->max_tokens promised (logits_cache = 1): the tokens
+                                      past the bound were left out; the call's outputs are not usable */
 
 /* enums */
 #define RAPID_DTYPE_F32 0
