@@ -161,10 +161,11 @@ int rapid_set_tuning(int key, int value);
  * its stages with HIP events on the caller's stream (host objects, no device memory);
  * rapid_profile_read waits for those events, writes the milliseconds and the number of timed spans
  * per stage into two HOST arrays of n_stages >= RAPID_N_STAGES entries, and clears the record.
- * Stage order: 0 compaction/gather, 1 operand packing, 2 forward logits+log-sum-exp kernel,
- * 3 log-sum-exp merge, 4 estimator reductions (ratios, advantages, loss), 5 zeroing of masked
- * gradient rows, 6 dz kernel, 7 dz transpose, 8 dHidden kernel, 9 dW kernel, 10 fp32 path,
- * 11 dW conversion. */
+ * Stage order: 0 compaction/gather, 1 operand packing (with rms_weight: the final norm), 2 forward
+ * logits+log-sum-exp kernel, 3 sampled-token logits and log-sum-exp merge, 4 estimator reductions
+ * (ratios, advantages, loss, row coefficients), 5 zeroing of masked gradient rows (with rms_weight
+ * also the norm's backward), 6 dz kernel (with logits_cache: the row-factor pass), 7 unused,
+ * 8 dHidden kernel, 9 dW kernel, 10 fp32 path, 11 dW conversion. */
 #define RAPID_N_STAGES 12
 int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stages);
 
