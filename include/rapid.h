@@ -154,7 +154,12 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
  * key 15: with logits_cache = 1, token-row tiles (of 256 rows) per launch of the dHidden and dW
  *        kernels, default 256 (0 = all rows in one launch; multiples of 128 fill whole rounds of
  *        workgroups).  dW sums over the launches in a fixed order, so results depend on it only
- *        through fp32 rounding. */
+ *        through fp32 rounding.
+ * key 16: K steps (of 64 vocabulary entries; a power of two, 0 = off, default 256) between meetings
+ *        of the dHidden kernel's workgroups: they count themselves in on a workspace word and wait,
+ *        for a bounded time, for the others, so that all XCDs sweep W together and share it through
+ *        the memory-side cache.  A timing hint only: results are identical, and a meeting that runs
+ *        out of time switches the pacing off for the rest of the launch. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

@@ -179,11 +179,43 @@ __device__ __forceinline__ void load_to_lds_16(const char* gp, char* lp) {
 // tile requests sit between given MFMAs) and the fences keep that order.
 __device__ __forceinline__ void fence() { __builtin_amdgcn_sched_barrier(0); }
 
+struct NoPace {
+    __device__ __forceinline__ void operator()(int) const {}
+};
+
+// Keeps all workgroups of a launch within a few K steps of each other, so that a W panel one XCD
+// has pulled through the memory-side cache is still there when the others ask for it.  Every
+// `every` K steps thread 0 counts its workgroup in and polls, a bounded number of times, until the
+// others of the round have arrived; the rest of the workgroup meets it at the next barrier.  Purely
+// a pacing hint: nothing depends on it, a poll that runs out sets the counter's top bit, which
+// satisfies every later target, and the kernel goes on unpaced.
+struct GridPace {
+    unsigned* ctr;      // arrival counter, zero at launch
+    unsigned base;      // arrivals of the rounds before this tile
+    unsigned n;         // workgroups that work on a tile in this round
+    int every;          // K steps between meetings (power of two), 0 = off
+    __device__ __forceinline__ void operator()(int kt) const {
+        if (every == 0 || ((kt + 1) & (every - 1)) != 0) return;
+        if (threadIdx.x == 0) {
+            const unsigned target = base + n * (unsigned)((kt + 1) / every);
+            __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int polls = 0;
+            while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                if (++polls == 256) {
+                    __hip_atomic_fetch_or(ctr, 0x80000000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+            }
+        }
+    }
+};
+
 // acc += A_tile . B_tile^T over `ktiles` steps of 64.  A / B point at the tile's first row, k = 0.
-template <class S>
+template <class S, class Pace = NoPace>
 __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
                                          int64_t ldb, int ktiles, char* lds, f32x16 (&acc)[S::WI][S::WJ],
-                                         int step_a = 128, int step_b = 128) {
+                                         int step_a = 128, int step_b = 128, Pace pace = Pace()) {
     constexpr int WI = S::WI, WJ = S::WJ;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -281,6 +313,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         wait_frags<0>(f1);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         lds_barrier();
+        pace(kt);   // no LDS read or tile request is in flight here
         load_frags<WI, WJ>(f0, na + xo[0], nb + xo[0]);
         fence();
         ga += (kt + 2 < ktiles) ? step_a : 0;
@@ -704,13 +737,30 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
     // the order (and with it the split over the XCDs) covers the row tiles that hold tokens only: a
     // short last chunk would otherwise leave whole XCDs with nothing but empty tiles
     const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));
-    for (int pid = blockIdx.x, ids = ids_for(tilesD, tilesM); pid < ids; pid += gridDim.x) {
+    // pacing of the launch's workgroups (see GridPace): with total = 8 * per tiles (or fewer in the last
+    // XCD shares) the workgroups of round r are those whose id is a valid tile
+    const int total = tilesD * tilesM, per = (total + 7) / 8, wgs = gridDim.x / 8;
+    const int ktiles = (int)(a.Vpad / K_TILE);
+    GridPace pace{a.pace, 0u, 0u, a.pace ? a.pace_every : 0};
+    int round = 0;
+    unsigned before = 0;   // valid tiles of the rounds before this one, over all XCDs
+    for (int pid = blockIdx.x, ids = ids_for(tilesD, tilesM); pid < ids; pid += gridDim.x, ++round) {
+    unsigned now = 0;
+    if (pace.every) {
+        for (int x = 0; x < 8; ++x) {
+            const int mine = max(0, min(per, total - x * per));
+            now += (unsigned)max(0, min(wgs, mine - round * wgs));
+        }
+    }
     const TileId t = map_tile(pid, tilesD, tilesM, a.gi > 0 ? a.gi : tilesD);
-    if (!t.valid) continue;
+    if (!t.valid) { before += now; continue; }
     f32x16 acc[WI][WJ];
+    pace.n = now;
+    pace.base = (unsigned)(ktiles / (pace.every ? pace.every : 1)) * before;
+    before += now;
     if (a.WdvB)   // A from the tile-blocked copy: one contiguous 128-byte-row block per K step
-        mainloop<S>(a.WdvB + (int64_t)t.ti * (a.Vpad / K_TILE) * (S::BI * 64), 64,
-                    a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, (int)(a.Vpad / K_TILE), lds, acc, S::BI * 128, 128);
+        mainloop<S, GridPace>(a.WdvB + (int64_t)t.ti * (a.Vpad / K_TILE) * (S::BI * 64), 64,
+                    a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, ktiles, lds, acc, S::BI * 128, 128, pace);
     else
         mainloop<S>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv, a.ldv,
                     a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, (int)(a.Vpad / K_TILE), lds, acc);

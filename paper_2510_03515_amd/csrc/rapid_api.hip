@@ -26,6 +26,7 @@ int g_gi_fwd = 4, g_gi_dh = 0, g_gi_dw = 2;   // L2 blocking of the tile order (
 int g_blocked_wdv = 1;                        // dH reads W from a tile-blocked copy (tuning key 14)
 int g_probe_cus = 256;                        // compute units of the current device
 int g_cached_step_tiles = 256;                // row tiles per dHidden / dW launch with the cache (tuning key 15; 0 = all rows)
+int g_pace_every = 256;                       // K steps between meetings of the dHidden workgroups (tuning key 16; 0 = off)
 int g_fwd_block_tiles = 64;                   // row tiles per launch of the two logits kernels (tuning key 13)
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
@@ -69,7 +70,7 @@ struct Plan {
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
-    size_t counts, seq_len, cu, row_index, tokc, seqc, zy, refz, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, g, g64, tsum, tmax,
+    size_t counts, pace, seq_len, cu, row_index, tokc, seqc, zy, refz, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, g, g64, tsum, tmax,
         Hc, Wvd, Wdv, WdvB, part_max, part_sum, dw32, chunk0;
 };
 
@@ -101,6 +102,7 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     const bool bwd = op == RAPID_OP_IW_PG_FWD_BWD;
     size_t cur = 0;
     p.counts = take(cur, CNT_WORDS * 4);
+    p.pace = take(cur, 64 * 4);
     p.seq_len = take(cur, (size_t)N * 4);
     p.cu = take(cur, (size_t)(N + 1) * 4);
     p.row_index = take(cur, (size_t)p.Mmax_pad * 4);
@@ -421,6 +423,10 @@ int rapid_set_tuning(int key, int value) {
     }
     if (key == 15 && value >= 0 && value <= (1 << 20)) {
         g_cached_step_tiles = value;
+        return RAPID_OK;
+    }
+    if (key == 16 && value >= 0 && value <= 4096 && (value & (value - 1)) == 0) {
+        g_pace_every = value;
         return RAPID_OK;
     }
     if (key == 14 && (value == 0 || value == 1)) {
@@ -754,6 +760,8 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             ha.Wdv = Wdv; ha.WdvB = g_blocked_wdv ? at<bf16_t>(ws, p.WdvB) : nullptr; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
             ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
             ha.rowc = cached ? at<float>(ws, p.rowc) : nullptr;
+            ha.pace = g_pace_every > 0 ? at<unsigned>(ws, p.pace) : nullptr; ha.pace_every = g_pace_every;
+            if (ha.pace) launch_fill_f32((float*)ha.pace, 64, 0.f, st);
             ha.dhidden = (bf16_t*)dhidden_out; ha.gi = g_gi_dh;
             {
                 Span sp(ST_DH, st);

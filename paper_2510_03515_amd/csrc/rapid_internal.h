@@ -147,6 +147,8 @@ struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const int32_t* row_index;
     const int32_t* counts;
     const float* rowc;    // NULL, or one factor per compact row applied to the result
+    unsigned* pace;       // NULL, or one word, zero at launch: arrival counter of the launch's workgroups
+    int pace_every;       // K steps between meetings (power of two)
     bf16_t* dhidden;      // [N*T, d]
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
