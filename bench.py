@@ -230,6 +230,11 @@ def main():
                     "traffic_source": "profiles/bench_cfg2_qwen1.5b_kernel_trace_and_traffic.md",
                     "avg_launch_ms": avg_ms, "live_launches_per_step": live,
                     "tokens_per_launch": tokens_per_launch, "flop_per_token": 2.0 * d * V}
+        # the same figure for every contraction stage of the step (each does 2 d V flop per token)
+        roofline["all_contraction_stages"] = {
+            st: {"achieved": 2.0 * d * V * M / (stages[st]["ms_per_step"] * 1e-3) / 1e12,
+                 "frac": 2.0 * d * V * M / (stages[st]["ms_per_step"] * 1e-3) / PEAK_BF16_MFMA,
+                 "ms_per_step": stages[st]["ms_per_step"]} for st in gemm_stages}
     else:
         # the fp32 accuracy path (config 0): plain strided contractions with fp64 accumulation on the
         # vector ALUs, four of them per call (logits twice, dHidden, dW); all its launches are one stage
