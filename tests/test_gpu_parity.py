@@ -608,6 +608,25 @@ def test_other_workgroup_geometries(rb, waves):
         rb.rapid_set_tuning(2, 8)
 
 
+def test_dhidden_pacing_is_timing_only(rb):
+    """Tuning key 16: the dHidden workgroups meet every so many K steps (a vocabulary of 20 000 makes
+    313 steps, so meetings every 64 steps do happen here, with fewer workgroups than CUs): same bits
+    as unpaced, and the result matches the oracle."""
+    spec = wl.small_spec("pace", "bf16", d=64, V=20000, prompts=3, G=4, len_lo=20, len_hi=70)
+    try:
+        rb.rapid_set_tuning(16, 64)
+        w, out, ref = _run_pair(rb, spec)
+        _check_pair(rb, spec, out, ref)
+        w, outc, _ = _run_pair(rb, spec, logits_cache=True)
+        rb.rapid_set_tuning(16, 0)
+        w, out0, _ = _run_pair(rb, spec)
+        w, outc0, _ = _run_pair(rb, spec, logits_cache=True)
+    finally:
+        rb.rapid_set_tuning(16, 256)
+    assert torch.equal(out.dhidden, out0.dhidden) and torch.equal(out.dW, out0.dW)
+    assert torch.equal(outc.dhidden, outc0.dhidden) and torch.equal(outc.dW, outc0.dW)
+
+
 def test_row_major_w_for_dhidden(rb):
     """Tuning key 14 = 0: dHidden from the row-major copy of W instead of the tile-blocked one: same bits."""
     spec = SPECS["bf16_ragged"]
