@@ -140,8 +140,9 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
 
 /* Process-wide switches (host state, not thread-safe against concurrent calls).
  * key 1: per-stage event timing on (1) / off (0, default); see rapid_profile_read.
- * key 2: waves per workgroup of the contraction kernels, 8 (default: 2 x 4 waves of 128 x 64) or
- *        4 (2 x 2 waves of 128 x 128) or 16.  Same 256 x 256 tile and same results either way.
+ * key 2: waves per workgroup of the contraction kernels: 0 (default) = each kernel's own choice (8,
+ *        i.e. 2 x 4 waves of 128 x 64, for the logits kernels and dW; 4, i.e. 2 x 2 waves of 128 x 128,
+ *        for dHidden), or 4 / 8 / 16 for all of them.  Same 256 x 256 tile and same results either way.
  * keys 10, 11, 12: tile-order blocking (tiles along the first tile dimension that share one tile of
  *        the second before the order moves on) of the logits kernels, the dHidden kernel (0 = all)
  *        and the dW kernel; defaults 4, 0, 2 were measured best on MI355X.  Results are identical.
@@ -155,7 +156,7 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
  *        kernels, default 256 (0 = all rows in one launch; multiples of 128 fill whole rounds of
  *        workgroups).  dW sums over the launches in a fixed order, so results depend on it only
  *        through fp32 rounding.
- * key 16: K steps (of 64 vocabulary entries; a power of two, 0 = off, default 256) between meetings
+ * key 16: K steps (of 64 vocabulary entries; a power of two; default 0 = off) between meetings
  *        of the dHidden kernel's workgroups: they count themselves in on a workspace word and wait,
  *        for a bounded time, for the others, so that all XCDs sweep W together and share it through
  *        the memory-side cache.  A timing hint only: results are identical, and a meeting that runs

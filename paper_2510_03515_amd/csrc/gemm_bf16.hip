@@ -940,7 +940,11 @@ void allow_lds(K kernel, int bytes) {
     (void)hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-int g_waves = 8;   // waves per workgroup: 4 (2 x 2 of 128 x 128) or 8 (2 x 4 of 128 x 64)
+// waves per workgroup: 4 (2 x 2 of 128 x 128), 8 (2 x 4 of 128 x 64) or 16; 0 = each kernel's own
+// default: 8 for the logits kernels and dW, 4 for dHidden (measured: its long K loop gains more from
+// the 4-wave tile's third fewer LDS reads than it loses in latency hiding)
+int g_waves = 0;
+static int waves_for(int own_default) { return g_waves ? g_waves : own_default; }
 
 using G4 = Geo<2, 2, 4, 4>;        // 256 x 256, 4 waves
 using G4_I128 = Geo<2, 2, 2, 4>;   // 128 x 256
@@ -980,12 +984,13 @@ void launch_dw_t(const DwArgs& a, hipStream_t st) {
 
 }  // namespace
 
-void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 16) ? n : 8; }
+void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 8 || n == 16) ? n : 0; }
 void set_cu_count(int n) { g_num_cu = n >= 8 ? n : 8; }
 
 
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
-    if (g_waves == 16) launch_fwd_lse_t<G16>(a, st); else if (g_waves == 8) launch_fwd_lse_t<G8>(a, st); else launch_fwd_lse_t<G4>(a, st);
+    const int w = waves_for(8);
+    if (w == 16) launch_fwd_lse_t<G16>(a, st); else if (w == 8) launch_fwd_lse_t<G8>(a, st); else launch_fwd_lse_t<G4>(a, st);
 }
 void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st) {
     token_logit_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(a.Hc, a.Wvd, a.ldk, a.dpad, a.tokc, a.counts,
@@ -995,7 +1000,8 @@ void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st) {
 int fwd_slots_per_tile() { return 2; }
 
 void launch_dz(const DzArgs& a, hipStream_t st) {
-    if (g_waves == 16) launch_dz_t<G16>(a, st); else if (g_waves == 8) launch_dz_t<G8>(a, st); else launch_dz_t<G4>(a, st);
+    const int w = waves_for(8);
+    if (w == 16) launch_dz_t<G16>(a, st); else if (w == 8) launch_dz_t<G8>(a, st); else launch_dz_t<G4>(a, st);
     const int64_t rows = (int64_t)a.tilesM * 256;
     token_onehot_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, st>>>(a.dz, a.ldz, a.m0, rows, a.tokc, a.rowg,
                                                                       a.inv_temp, a.counts);
@@ -1008,18 +1014,20 @@ void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const 
                                                                         inv_temp, counts, rowc, dev_status);
 }
 void launch_dh(const DhArgs& a, hipStream_t st) {
+    const int w = waves_for(4);
     if (a.dpadR % 256 == 0) {
-        if (g_waves == 16) launch_dh_t<G16>(a, st); else if (g_waves == 8) launch_dh_t<G8>(a, st); else launch_dh_t<G4>(a, st);
+        if (w == 16) launch_dh_t<G16>(a, st); else if (w == 8) launch_dh_t<G8>(a, st); else launch_dh_t<G4>(a, st);
     } else {   // d padded to a multiple of 128 only
-        if (g_waves == 16) launch_dh_t<G16_I128>(a, st); else if (g_waves == 8) launch_dh_t<G8_I128>(a, st); else launch_dh_t<G4_I128>(a, st);
+        if (w == 16) launch_dh_t<G16_I128>(a, st); else if (w == 8) launch_dh_t<G8_I128>(a, st); else launch_dh_t<G4_I128>(a, st);
     }
 }
 
 void launch_dw(const DwArgs& a, hipStream_t st) {
+    const int w = waves_for(8);
     if (a.dpadR % 256 == 0) {
-        if (g_waves == 16) launch_dw_t<G16>(a, st); else if (g_waves == 8) launch_dw_t<G8>(a, st); else launch_dw_t<G4>(a, st);
+        if (w == 16) launch_dw_t<G16>(a, st); else if (w == 8) launch_dw_t<G8>(a, st); else launch_dw_t<G4>(a, st);
     } else {   // d padded to a multiple of 128 only
-        if (g_waves == 16) launch_dw_t<G16_J128>(a, st); else if (g_waves == 8) launch_dw_t<G8_J128>(a, st); else launch_dw_t<G4_J128>(a, st);
+        if (w == 16) launch_dw_t<G16_J128>(a, st); else if (w == 8) launch_dw_t<G8_J128>(a, st); else launch_dw_t<G4_J128>(a, st);
     }
 }
 

@@ -26,7 +26,7 @@ int g_gi_fwd = 4, g_gi_dh = 0, g_gi_dw = 2;   // L2 blocking of the tile order (
 int g_blocked_wdv = 1;                        // dH reads W from a tile-blocked copy (tuning key 14)
 int g_probe_cus = 256;                        // compute units of the current device
 int g_cached_step_tiles = 256;                // row tiles per dHidden / dW launch with the cache (tuning key 15; 0 = all rows)
-int g_pace_every = 256;                       // K steps between meetings of the dHidden workgroups (tuning key 16; 0 = off)
+int g_pace_every = 0;                         // K steps between meetings of the dHidden workgroups (tuning key 16; 0 = off)
 int g_fwd_block_tiles = 64;                   // row tiles per launch of the two logits kernels (tuning key 13)
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
@@ -433,7 +433,7 @@ int rapid_set_tuning(int key, int value) {
         g_blocked_wdv = value;
         return RAPID_OK;
     }
-    if (key == 2 && (value == 4 || value == 8 || value == 16)) {
+    if (key == 2 && (value == 0 || value == 4 || value == 8 || value == 16)) {
         set_waves_per_workgroup(value);
         return RAPID_OK;
     }

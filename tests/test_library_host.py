@@ -124,7 +124,7 @@ def test_host_validation_returns_codes_without_a_gpu(rb):
     assert lib.rapid_set_tuning(12345, 0) == -3
     assert lib.rapid_set_tuning(13, 0) == -3          # forward row block of 0 tiles
     assert lib.rapid_set_tuning(16, 100) == -3        # pacing interval must be a power of two (or 0)
-    assert lib.rapid_set_tuning(16, 128) == 0 and lib.rapid_set_tuning(16, 256) == 0
+    assert lib.rapid_set_tuning(16, 128) == 0 and lib.rapid_set_tuning(16, 0) == 0
     assert lib.rapid_mfma_probe(0, 0, None, None, None) == -2       # iters out of range, checked before the device
     assert lib.rapid_mfma_probe(1, 10**8, None, None, None) == -2
 
