@@ -26,9 +26,9 @@ PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
 PEAK_HBM = 8.0e12         # B/s
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled (see the profile named in the output), of one full launch:
 # 16384 token rows for the two logits kernels, 65536 for dH and dW; keyed by (backward mode, stage)
-MEASURED_TRAFFIC_BYTES = {("cache", "fwd_lse"): 11.5e9 + 5.2e9, ("cache", "dh"): 45.0e9 + 0.2e9, ("cache", "dw"): 49.7e9 + 1.0e9,
-                          ("recompute", "fwd_lse"): 11.9e9 + 0.2e9, ("recompute", "dz"): 11.5e9 + 5.1e9,
-                          ("recompute", "dh"): 45.0e9 + 0.2e9, ("recompute", "dw"): 49.7e9 + 1.0e9}
+MEASURED_TRAFFIC_BYTES = {("cache", "fwd_lse"): 11.5e9 + 5.2e9, ("cache", "dh"): 48.3e9 + 0.2e9, ("cache", "dw"): 49.7e9 + 1.0e9,
+                          ("recompute", "fwd_lse"): 11.8e9 + 0.2e9, ("recompute", "dz"): 11.5e9 + 5.1e9,
+                          ("recompute", "dh"): 51.2e9 + 0.2e9, ("recompute", "dw"): 49.8e9 + 1.0e9}
 
 
 def cpu_baseline(w, rb, group=2, logits_cache=False):
