@@ -38,7 +38,8 @@ extern "C" {
 /* host-side error codes */
 #define RAPID_OK 0
 #define RAPID_ERR_NULL (-1)      /* a required pointer is NULL */
-#define RAPID_ERR_SHAPE (-2)     /* a size is <= 0, too large, or unsupported (bf16 needs d % 8 == 0) */
+#define RAPID_ERR_SHAPE (-2)     /* a size is <= 0, too large (limits: N * T <= 2e9 positions, d <= 65536,
+                                    V <= 4e6), or unsupported (bf16 needs d % 8 == 0) */
 #define RAPID_ERR_DTYPE (-3)     /* unknown dtype / layout / mode enum */
 #define RAPID_ERR_WORKSPACE (-4) /* workspace NULL, misaligned (256 B) or below the minimum */
 #define RAPID_ERR_ARCH (-5)      /* current device is not gfx950 */

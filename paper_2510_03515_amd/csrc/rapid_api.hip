@@ -85,7 +85,9 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     memset(&p, 0, sizeof(p));
     if (N <= 0 || T <= 0 || d <= 0 || V <= 0) return false;
     if (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) return false;
-    if (N * T > (int64_t)2000000000 || V > (int64_t)2000000000 || d > 65536 || N > (int64_t)2000000000)
+    // limits: positions and generations fit int32 indices; V keeps every two-dimensional launch inside the
+    // 65535-block limit of the second grid dimension (V / 64 blocks in the transposing pack)
+    if (N * T > (int64_t)2000000000 || V > (int64_t)4000000 || d > 65536 || N > (int64_t)2000000000)
         return false;
     if (op == RAPID_OP_IW_PG_FWD_BWD && K <= 0) return false;
     p.op = op; p.dtype = dtype; p.N = N; p.T = T; p.d = d; p.V = V; p.K = K;

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(256) void rmsnorm_pad_bf16_kernel(const bf16_t* __r
     }
 }
 
-// dweight partials: block (cb, rb) sums dh[row][k] x[row][k] inv_rms[row] over the valid compact rows
+// dweight partials: block (rb, cb) sums dh[row][k] x[row][k] inv_rms[row] over the valid compact rows
 // rb*RB .. +RB for the 8 columns of each of its threads; part[rb][k]
 constexpr int RB = 512;
 __global__ __launch_bounds__(256) void rmsnorm_dweight_partial_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dh,
@@ -96,8 +96,8 @@ __global__ __launch_bounds__(256) void rmsnorm_dweight_partial_kernel(const bf16
                                                                       const int32_t* __restrict__ counts,
                                                                       const float* __restrict__ inv_rms,
                                                                       float* __restrict__ part) {
-    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // 8-column chunk
-    const int64_t r0 = (int64_t)blockIdx.y * RB;
+    const int64_t c = (int64_t)blockIdx.y * blockDim.x + threadIdx.x;   // 8-column chunk
+    const int64_t r0 = (int64_t)blockIdx.x * RB;                       // row blocks along x: no 65535 limit
     const int M = counts[CNT_M];
     if (c * 8 >= d || r0 >= M) return;   // the reduction reads the blocks that hold tokens only
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void rmsnorm_dweight_partial_kernel(const bf16
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = fmaf(gv[e] * inv, xv[e], acc[e]);
     }
-    float* o = part + (int64_t)blockIdx.y * d + c * 8;
+    float* o = part + (int64_t)blockIdx.x * d + c * 8;
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = acc[e];
 }
@@ -181,7 +181,7 @@ void launch_rmsnorm_backward(const bf16_t* x, bf16_t* dh, int64_t d, const bf16_
     if (rows_max <= 0) return;
     if (dweight) {
         const int64_t nblk = rmsnorm_dweight_blocks(rows_max);
-        dim3 grid((unsigned)((d / 8 + 255) / 256), (unsigned)nblk);
+        dim3 grid((unsigned)nblk, (unsigned)((d / 8 + 255) / 256));
         rmsnorm_dweight_partial_kernel<<<grid, 256, 0, st>>>(x, dh, d, row_index, counts, inv_rms, part);
         rmsnorm_dweight_reduce_kernel<<<(unsigned)((d + 255) / 256), 256, 0, st>>>(part, d, nblk, counts, dweight);
     }

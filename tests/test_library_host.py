@@ -76,10 +76,10 @@ def test_host_validation_returns_codes_without_a_gpu(rb):
     assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 8, 9, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -3
     assert lib.rapid_logprob_fwd(one, one, one, one, 0, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -2
     assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 12, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -2
-    # past the maximum sizes: N * T <= 2e9 positions, d <= 65536, V <= 2e9
+    # past the maximum sizes: N * T <= 2e9 positions, d <= 65536, V <= 4e6
     assert lib.rapid_logprob_fwd(one, one, one, one, 1 << 20, 1 << 12, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -2
     assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 65536 + 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -2
-    assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 3 * 10**9, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -2
+    assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 4 * 10**6 + 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, one, 1 << 30, None) == -2
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, 1 << 20, 1 << 12, 8, 8, 1, rb.DTYPE_BF16) == 0
     assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, 5, 1.0, one, None, None, one, 1 << 30, None) == -3
     assert lib.rapid_logprob_fwd(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 0.0, one, None, None, one, 1 << 30, None) == -2
