@@ -69,6 +69,8 @@ def test_eq5_hand_example():
     assert np.allclose(orc.group_advantage(R, gid, 1, s=s, eta=math.inf)["adv"], g[:, 4], atol=1e-15)
     assert np.allclose(orc.group_advantage(R, gid, 1, s=s, eta=2.0, baseline_mode=1)["adv"],
                        g[:, 5], atol=1e-15)
+    assert np.allclose(orc.group_advantage(R, gid, 1, s=s, eta=2.0, baseline_mode=2)["adv"],
+                       g[:, 6], atol=1e-15)        # leave-one-out over N_k - 1 = 3 (hand values 5/6, -5/6, -5/6, 1/3)
     w = orc.clipped_weight(s, 2.0)
     assert np.allclose(w, [2.0, 1.0, 1.0, 0.5], atol=1e-15)
 
@@ -105,6 +107,56 @@ def test_group_adv_sums():
     for n in range(N):
         b = np.mean([min(math.exp(s[j]), 2.0) * R[j] for j in range(N) if gid[j] == gid[n]])
         assert abs(out["adv"][n] - (R[n] - b)) < 1e-13
+
+
+def test_leave_one_out_over_the_others():
+    """baseline_mode 2 (Sec. 3.4, leave-one-out paragraph, normalised by N_k - 1): the baseline of
+    sample n is the clipped-weight mean reward of the OTHER members of its group.  Pinned by explicit
+    loops, by its independence of sample n's own reward and ratio (what makes the estimator unbiased),
+    by the relation to the sum printed with 1/N_k, and by the degenerate group sizes."""
+    rng = np.random.default_rng(8)
+    N, K = 41, 6
+    R = rng.random(N)
+    gid = rng.integers(0, K - 1, size=N)         # ragged, shuffled; group K-1 empty
+    gid[7] = K - 1                                # ... except for one lonely member
+    s = rng.normal(size=N)
+    eta = 2.0
+    out = orc.group_advantage(R, gid, K, s=s, eta=eta, baseline_mode=2)
+    as_printed = orc.group_advantage(R, gid, K, s=s, eta=eta, baseline_mode=1)
+    for n in range(N):
+        others = [j for j in range(N) if gid[j] == gid[n] and j != n]
+        b = sum(min(math.exp(s[j]), eta) * R[j] for j in others) / len(others) if others else 0.0
+        assert abs(out["adv"][n] - (R[n] - b)) < 1e-13
+        # the same leave-one-out sum, divided by N_k as printed: b' = b (N_k - 1) / N_k
+        nk = len(others) + 1
+        assert abs((R[n] - as_printed["adv"][n]) * nk - b * (nk - 1)) < 1e-12
+    assert out["adv"][7] == R[7]                  # a group of one: nobody else, baseline 0
+    # sample n's own reward and ratio do not enter its baseline (they do enter Eq. (5)'s)
+    for n in (0, 3, 19):
+        R2, s2 = R.copy(), s.copy()
+        R2[n] += 0.7
+        s2[n] -= 1.3
+        moved = orc.group_advantage(R2, gid, K, s=s2, eta=eta, baseline_mode=2)
+        assert abs((R2[n] - moved["adv"][n]) - (R[n] - out["adv"][n])) < 1e-14
+        eq5, eq5_moved = (orc.group_advantage(r, gid, K, s=ss, eta=eta)["adv"] for r, ss in ((R, s), (R2, s2)))
+        assert abs((R2[n] - eq5_moved[n]) - (R[n] - eq5[n])) > 1e-3
+    # on-policy, equal rewards in a group: every other member has the same reward, so A = 0
+    flat = orc.group_advantage(np.full(N, 0.25), gid, K, s=None, baseline_mode=2)["adv"]
+    assert np.allclose(np.delete(flat, 7), 0.0, atol=1e-15) and flat[7] == 0.25
+    # exhaustive expectation on a two-armed bandit sampled on-policy: with the baseline of the others,
+    # E[A_n grad log pi(y_n)] equals the exact policy gradient (it does not with Eq. (2)'s own-sample mean)
+    p, r = np.array([0.3, 0.7]), np.array([1.0, 0.2])
+    exact = p * (r - (p * r).sum())               # dJ/dlogit_a for a softmax policy
+    est2, est0 = np.zeros(2), np.zeros(2)
+    G = 3
+    for ys in itertools.product(range(2), repeat=G):
+        pr = np.prod(p[list(ys)])
+        for mode, acc in ((2, est2), (0, est0)):
+            A = orc.group_advantage(r[list(ys)], np.zeros(G, int), 1, s=None, baseline_mode=mode)["adv"]
+            for n, y in enumerate(ys):
+                acc += pr * A[n] * ((np.arange(2) == y) - p) / G
+    assert np.allclose(est2, exact, atol=1e-14)
+    assert np.allclose(est0, exact * (G - 1) / G, atol=1e-14)       # Eq. (2): biased by the factor (G-1)/G
 
 
 def test_zero_variance_groups():
