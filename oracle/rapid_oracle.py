@@ -78,13 +78,26 @@ def logprob(hidden, W, tokens, mask, temperature=1.0, row_chunk=2048):
 
 
 def round_to_bf16(x):
-    """x rounded to the nearest bfloat16 (ties to even), returned as float64: the value a bf16
-    operand of the contraction kernels holds.  float64 -> float32 (IEEE rounding of numpy), then the
-    low 16 bits of the float32 pattern are rounded away."""
-    x32 = np.ascontiguousarray(np.asarray(x, np.float32))
-    bits = x32.view(np.uint32).astype(np.uint64)
-    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
-    return bits.astype(np.uint32).view(np.float32).astype(_F).reshape(x32.shape)
+    """x (float64) rounded ONCE to the nearest bfloat16, ties to even, returned as float64: the value a
+    bf16 tensor holds.  bfloat16 = sign, 8 exponent bits (those of float32), 7 fraction bits.  A normal
+    float64 keeps the top 7 of its 52 fraction bits: the other 45 are rounded away on the integer
+    pattern (a carry into the exponent is the correct result); values above the largest bfloat16
+    become infinity; below 2^-126 (bfloat16 subnormals) the spacing is the fixed 2^-133.  Going
+    through float32 first would round twice and differ for values within 2^-25 (relative) above or
+    below a bfloat16 midpoint."""
+    x64 = np.ascontiguousarray(np.asarray(x, _F))
+    bits = x64.view(np.uint64)
+    keep = np.uint64(45)
+    low = np.uint64((1 << 45) - 1)
+    rounded = (bits + np.uint64((1 << 44) - 1) + ((bits >> keep) & np.uint64(1))) & ~low
+    out = rounded.view(_F).copy()
+    big = np.abs(out) > 3.3895313892515355e38            # largest bfloat16 = (2 - 2^-7) 2^127
+    out[big] = np.sign(out[big]) * np.inf
+    tiny = np.abs(x64) < 2.0 ** -126
+    out[tiny] = np.rint(x64[tiny] * 2.0 ** 133) * 2.0 ** -133
+    nan = np.isnan(x64)
+    out[nan] = np.nan
+    return out.reshape(np.shape(x))
 
 
 def rmsnorm(x, weight, eps=1e-6):
@@ -272,9 +285,9 @@ def iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group_ids, 
     """The whole update-step loss of Alg. 1 (procedure IW-GRPG, one mini-batch): advantages by
     Eq. (5), gradient by Eq. (3).  ratio_level 1 swaps the outer weight for the token-level one of
     token_coefficients (then `g` is [N,T]).  With rms_weight, `hidden` is the input x of a final
-    RMSNorm: the path runs on h = rmsnorm(x) (rounded to bf16 first if round_normed_hidden, the
-    precision a bf16 contraction sees; the rounding passes gradients through unchanged), dH is the
-    gradient with respect to x and d_rms_weight is returned too.
+    RMSNorm: the path runs on h = rmsnorm(x) (rounded to bf16 if round_normed_hidden: the
+    normalised state of a bf16 model is a bf16 tensor; the rounding passes gradients through
+    unchanged), dH is the gradient with respect to x and d_rms_weight is returned too.
     Returns a dict with loss, dH, dW and every intermediate."""
     x_in = hidden
     if rms_weight is not None:

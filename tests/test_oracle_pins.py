@@ -517,12 +517,27 @@ def test_token_level_clip_and_normalisation():
 
 # ---------------------------------------------------------------- RMSNorm on the way in
 def test_round_to_bf16_matches_library():
+    """One rounding, to nearest, ties to even.  On float32-representable inputs that is torch's
+    float32 -> bfloat16 conversion (library leg); next to a bfloat16 midpoint, where a detour through
+    float32 would round twice, the values are worked out by hand."""
     rng = np.random.default_rng(21)
     x = np.concatenate([rng.normal(size=4000) * 10.0 ** rng.integers(-6, 6, size=4000),
-                        [0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.3895314e38]])   # ties: to even
+                        [0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.3895314e38, 1e-39, -3e-41]])   # ties: to even
+    x = x.astype(np.float32).astype(np.float64)
     ref = torch.tensor(x, dtype=torch.float64).to(torch.float32).to(torch.bfloat16).double().numpy()
     assert np.array_equal(orc.round_to_bf16(x), ref)
     assert orc.round_to_bf16(np.array([1.00390625]))[0] == 1.0 and orc.round_to_bf16(np.array([1.01171875]))[0] == 1.015625
+    # bfloat16 neighbours of 1 are 1 and 1 + 2^-7; their midpoint is 1 + 2^-8.  A value 2^-30 above the
+    # midpoint rounds up, 2^-30 below rounds down; float32 (spacing 2^-23) would first move both ONTO
+    # the midpoint and the tie would then go to the even neighbour 1.0 in both cases.
+    up, down = 1.0 + 2.0 ** -8 + 2.0 ** -30, 1.0 + 2.0 ** -8 - 2.0 ** -30
+    assert orc.round_to_bf16(np.array([up, down, -up, -down])).tolist() == [1.0 + 2.0 ** -7, 1.0, -(1.0 + 2.0 ** -7), -1.0]
+    # odd neighbour below: midpoint of 1 + 2^-7 (odd) and 1 + 2^-6 (even) is 1 + 3 * 2^-8
+    assert orc.round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8 - 2.0 ** -40]))[0] == 1.0 + 2.0 ** -7
+    assert orc.round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6                      # exact tie: to even
+    # carry into the exponent, overflow, shape kept
+    assert orc.round_to_bf16(np.array([2.0 - 2.0 ** -9]))[0] == 2.0
+    assert np.isinf(orc.round_to_bf16(np.array([3.4e38]))[0]) and orc.round_to_bf16(np.zeros((2, 3))).shape == (2, 3)
 
 
 def test_rmsnorm_forward_backward_against_torch_autograd():
