@@ -36,6 +36,21 @@ __device__ inline void unpack8(const uint4& v, float (&f)[8]) {
     }
 }
 
+// double -> float such that rounding the float to bf16 (nearest even) gives what rounding the double
+// to bf16 directly would: truncate, and set the last bit if anything was cut off ("round to odd"; the
+// sticky bit keeps a value just off a bf16 midpoint from landing on it)
+__device__ inline float round_to_odd_f32(double v) {
+    float f = (float)v;                       // nearest; repaired below if it moved the value
+    if ((double)f != v && isfinite(f)) {
+        uint32_t b = __builtin_bit_cast(uint32_t, f);
+        const bool away = fabs((double)f) > fabs(v);   // rounded away from zero: step back to the truncation
+        if (away) b -= 1u;
+        b |= 1u;
+        f = __builtin_bit_cast(float, b);
+    }
+    return f;
+}
+
 __device__ inline uint32_t pack2(float a, float b) {
     const __bf16 x = (__bf16)a, y = (__bf16)b;
     return (uint32_t)__builtin_bit_cast(unsigned short, x) | ((uint32_t)__builtin_bit_cast(unsigned short, y) << 16);
@@ -45,15 +60,32 @@ __device__ inline uint4 pack8(const float (&f)[8]) {
     return make_uint4(pack2(f[0], f[1]), pack2(f[2], f[3]), pack2(f[4], f[5]), pack2(f[6], f[7]));
 }
 
+__device__ inline double wave_sum_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ inline double block_sum_d(double v, double* sm) {
+    v = wave_sum_d(v);
+    __syncthreads();
+    if ((threadIdx.x & (WAVE - 1)) == 0) sm[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    return (sm[0] + sm[1]) + (sm[2] + sm[3]);
+}
+
 // one block per destination row r < Mr (device count): rows < M hold the normalised source row
-// row_index[r], the rest and the columns C .. Cpad are zero; inv_rms[r] = 1 / sqrt(mean(x^2) + eps)
+// row_index[r], the rest and the columns C .. Cpad are zero; inv_rms[r] = 1 / sqrt(mean(x^2) + eps).
+// The normalised value is formed in fp64 and rounded to bf16 once: which of two neighbouring bf16
+// values an element becomes is a decision, and taken from an fp32 product it would fall the other
+// way than the exact value's for about one element in 40 000, each moving its row's log-prob by
+// ~1e-4.  The pass is bound by its memory traffic either way.
 __global__ __launch_bounds__(256) void rmsnorm_pad_bf16_kernel(const bf16_t* __restrict__ src, int64_t C,
                                                                const int32_t* __restrict__ row_index,
                                                                const bf16_t* __restrict__ weight, float eps,
                                                                bf16_t* __restrict__ dst, int64_t ld_dst, int64_t Cpad,
                                                                const int32_t* __restrict__ counts,
                                                                float* __restrict__ inv_rms) {
-    __shared__ float sm[4];
+    __shared__ double sm[4];
     const int64_t r = blockIdx.x;
     const int M = counts[CNT_M], Mr = counts[CNT_MR];
     if (r >= Mr) return;
@@ -64,16 +96,16 @@ __global__ __launch_bounds__(256) void rmsnorm_pad_bf16_kernel(const bf16_t* __r
         return;
     }
     const bf16_t* srow = src + (int64_t)row_index[r] * C;
-    float ss = 0.f;
+    double ss = 0.0;
     for (int64_t c = threadIdx.x; c < live_chunks; c += blockDim.x) {
         float x[8];
         unpack8(*(const uint4*)(srow + c * 8), x);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
+        for (int e = 0; e < 8; ++e) ss = fma((double)x[e], (double)x[e], ss);
     }
-    ss = block_sum_f(ss, sm);
-    const float inv = 1.0f / sqrtf(ss / (float)C + eps);
-    if (threadIdx.x == 0) inv_rms[r] = inv;
+    ss = block_sum_d(ss, sm);
+    const double inv = 1.0 / sqrt(ss / (double)C + (double)eps);
+    if (threadIdx.x == 0) inv_rms[r] = (float)inv;
     for (int64_t c = threadIdx.x; c < chunks; c += blockDim.x) {
         uint4 out = make_uint4(0u, 0u, 0u, 0u);
         if (c < live_chunks) {
@@ -81,7 +113,7 @@ __global__ __launch_bounds__(256) void rmsnorm_pad_bf16_kernel(const bf16_t* __r
             unpack8(*(const uint4*)(srow + c * 8), x);
             unpack8(*(const uint4*)(weight + c * 8), g);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = x[e] * inv * g[e];
+            for (int e = 0; e < 8; ++e) h[e] = round_to_odd_f32((double)x[e] * inv * (double)g[e]);
             out = pack8(h);
         }
         *(uint4*)(drow + c * 8) = out;
