@@ -3,14 +3,20 @@
 
 A step = one rapid_iw_pg_loss_fwd_bwd call (all stages of the hot path) on one synthetic
 Qwen2.5-1.5B-shaped mini-batch (d=1536, V=151936, 32 prompts x 8 generations, response length
-U[256,2048]) whose inputs, including the stored behaviour log-probs, are resident in HBM.  The call
-is timed with opts.logits_cache = 1 (the forward keeps every token row's probability ratios in the
-workspace, 93 GiB at this shape with opts.max_tokens = the batch's token count, and the backward
-contracts them: 6 d V flop per token executed) and, as a second figure, with the default 0 (27 GiB,
-the backward regenerates the logits: 8 d V).
+U[256,2048]) whose inputs, including the stored behaviour log-probs, are resident in HBM.
+
+`value` is timed with opts.logits_cache = 1 and the library's recommended workspace for it (a cache
+of 65536 token rows, 25 GiB in all at this shape): the batch is worked through in chunks of whole
+groups, the forward of a chunk keeps its rows' scaled probabilities in the cache and the chunk's
+dHidden and dW contract them, so 6 d V flop per token are executed and nothing of size tokens x V
+outlives a chunk.  Beside it, never as `value`: the same call with a cache that holds the whole batch
+at once ("whole", 94 GiB), with the backward that regenerates the logits ("recompute", 8 d V flop
+per token), and on the workload's calibrated companion (dense gradients: every generation carries
+weight).
+
 Prints ONE JSON line: response tokens/s, the roofline of the dominant kernel (HIP-event timing of
-every stage, taken inside the timed region) and the float64 oracle timed on this machine's cores on
-a bounded sample of the same workload.
+every stage, taken inside the timed region on the stream the kernels run on) and the float64 oracle
+timed on this machine's cores on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -23,12 +29,38 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
-PEAK_HBM = 8.0e12         # B/s
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled (see the profile named in the output), of one full launch:
-# 16384 token rows for the two logits kernels, 65536 for dH and dW; keyed by (backward mode, stage)
-MEASURED_TRAFFIC_BYTES = {("cache", "fwd_lse"): 11.5e9 + 5.2e9, ("cache", "dh"): 48.3e9 + 0.2e9, ("cache", "dw"): 49.7e9 + 1.0e9,
-                          ("recompute", "fwd_lse"): 11.8e9 + 0.2e9, ("recompute", "dz"): 11.5e9 + 5.1e9,
-                          ("recompute", "dh"): 51.2e9 + 0.2e9, ("recompute", "dw"): 49.8e9 + 1.0e9}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_cfg2_qwen1.5b.json")
+CACHE_ROWS = 65536        # cache rows of the library's recommended workspace for logits_cache = 1
+FWD_BLOCK_ROWS = 16384    # token rows per launch of the forward kernel
+
+
+def measured_traffic(version, mode, stage):
+    """HBM-side bytes per launch of `stage` from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes, as the
+    profiling run of this library version wrote them into profiles/ (None if that file is from another
+    version of the kernels: a stale figure is worse than none)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+    except (OSError, ValueError):
+        return None, None
+    if t.get("rapid_version") != version:
+        return None, None
+    e = t.get("modes", {}).get(mode, {}).get(stage)
+    return (e.get("bytes_per_launch"), t.get("source")) if e else (None, None)
+
+
+def chunk_rows_of(lengths, G, cap):
+    """Host replica of the library's chunking (whole groups in order, each chunk as full as the cache
+    allows), for reporting only: the tokens of every chunk."""
+    chunks, cur = [], 0
+    for k in range(0, len(lengths), G):
+        rows = int(sum(lengths[k:k + G]))
+        if cur and cur + rows > cap:
+            chunks.append(cur)
+            cur = 0
+        cur += rows
+    chunks.append(cur)
+    return chunks
 
 
 def cpu_baseline(w, rb, group=2, logits_cache=False):
@@ -61,12 +93,19 @@ def cpu_baseline(w, rb, group=2, logits_cache=False):
                                  row_chunk=512)
     dt = time.perf_counter() - t0
     rel = lambda a, b: float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+    def worst(got, want, axis):     # largest error of an element in units of 2^-7 of its row's / column's largest magnitude
+        return float((np.abs(got - want) / (2.0 ** -7 * np.abs(want).max(axis=axis, keepdims=True) + 1e-30)).max())
+    dH, dW = f64(out.dhidden), f64(out.dW)
     parity = {"loss_rel": abs(out.loss.item() - ref["loss"]) / max(abs(ref["loss"]), 1e-30),
-              "dH_rel": rel(f64(out.dhidden), ref["dH"]), "dW_rel": rel(f64(out.dW), ref["dW"]),
+              "dH_rel": rel(dH, ref["dH"]), "dW_rel": rel(dW, ref["dW"]),
+              "dH_worst_element_in_units_of_its_bound": worst(dH, ref["dH"], -1),
+              "dW_worst_element_in_units_of_its_bound": worst(dW, ref["dW"], 0),
               "seq_logratio_abs": float(np.abs(f64(out.seq_logratio) - ref["seq_logratio"]).max()),
               "grad_log_scale_abs": abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]),
               "tolerances": {"loss_rel": 1e-3, "dH_rel": 2e-2 if spec.dtype == "bf16" else 1e-5,
-                             "dW_rel": 2e-2 if spec.dtype == "bf16" else 1e-5, "seq_logratio_abs": 1e-3}}
+                             "dW_rel": 2e-2 if spec.dtype == "bf16" else 1e-5, "seq_logratio_abs": 1e-3,
+                             "worst_element": 1.0}}
     threads = torch.get_num_threads()
     try:
         import threadpoolctl
@@ -88,23 +127,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (2 = headline)")
     ap.add_argument("--calibrated", action="store_true",
-                    help="the workload's calibrated companion: same shapes and seed, behaviour weights close enough "
-                         "that the generation-level ratios are O(1) (every generation carries gradient, dz is dense)")
+                    help="time the workload's calibrated companion instead: same shapes and seed, behaviour weights close "
+                         "enough that the generation-level ratios are O(1) (every generation carries gradient, dz is dense)")
     ap.add_argument("--rmsnorm", action="store_true",
                     help="treat the workload's hidden states as the input of a final RMSNorm that the call applies "
                          "on the way in and differentiates on the way out (opts.rms_weight); not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", choices=["cache", "recompute"], default="cache",
-                    help="backward of the timed call: 'cache' = opts.logits_cache 1 (probability ratios kept in the "
-                         "workspace, 6 d V flop per token executed), 'recompute' = 0 (logits regenerated, 8 d V)")
-    ap.add_argument("--one-mode", action="store_true", help="skip the extra measurement of the other mode")
-    ap.add_argument("--workspace-gib", type=float, default=0.0,
-                    help="recompute mode: workspace size (0 = the library's recommended size)")
-    ap.add_argument("--chunk-rows", type=int, default=0,
-                    help="recompute mode: size the workspace for backward chunks of this many rows")
-    ap.add_argument("--waves", type=int, default=0, help="4 or 8 waves per contraction workgroup (0 = library default)")
-    ap.add_argument("--gi", type=str, default="", help="tile-order blocking fwd,dh,dw (tuning experiment)")
-    ap.add_argument("--tune", type=str, default="", help="library tuning keys, key=value[,key=value...] (experiments)")
+    ap.add_argument("--mode", choices=["chunks", "whole", "recompute"], default="chunks",
+                    help="backward of the timed call: 'chunks' = opts.logits_cache 1 with the recommended workspace (a cache "
+                         "of 65536 rows, chunks of whole groups, 6 d V flop per token executed); 'whole' = the same with a "
+                         "cache for every token of the batch; 'recompute' = logits_cache 0 (logits regenerated, 8 d V)")
+    ap.add_argument("--one-mode", action="store_true", help="skip the extra measurements (other modes, calibrated companion)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -116,26 +149,11 @@ def main():
 
     rb.load()   # raises if the HIP library is not built: there is no other path
     torch.cuda.set_device(0)
-    spec = wl.calibrated(wl.CONFIGS[args.config]) if args.calibrated else wl.CONFIGS[args.config]
-    w = wl.make_workload(spec, seed=0, device="cuda")
-    N, T, d, V, K = spec.N, spec.T, spec.d, spec.V, w["K"]
-    M = int(w["mask"].sum().item())
-
-    if args.waves:
-        rb.rapid_set_tuning(2, args.waves)
-    if args.gi:
-        for key, val in zip((10, 11, 12), args.gi.split(",")):
-            rb.rapid_set_tuning(key, int(val))
-    if args.tune:
-        for kv in args.tune.split(","):
-            key, val = kv.split("=")
-            rb.rapid_set_tuning(int(key), int(val))
+    base_spec = wl.CONFIGS[args.config]
+    spec = wl.calibrated(base_spec) if args.calibrated else base_spec
     fwd_only = spec.fwd_only
     dt_code = rb.DTYPE_BF16 if spec.dtype == "bf16" else rb.DTYPE_F32   # config 0 is the fp32 accuracy path
-    rms = {}
-    if args.rmsnorm:
-        gen = torch.Generator(device="cuda").manual_seed(1)
-        rms = dict(rms_weight=(1.0 + 0.1 * torch.randn(d, device="cuda", generator=gen)).to(torch.bfloat16), rms_eps=1e-6)
+    N, T, d, V = spec.N, spec.T, spec.d, spec.V
 
     def timed(step):
         """W warm-up steps, then exactly K steps between two synchronisations, with the library's
@@ -152,38 +170,46 @@ def main():
         dt = time.perf_counter() - t0
         prof = rb.rapid_profile_read()
         rb.rapid_set_tuning(1, 0)
-        stages = {k: {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
-                      "avg_ms": (ms / n if n else 0.0)} for k, (ms, n) in prof.items() if n}
+        stages = {k: {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps}
+                  for k, (ms, n) in prof.items() if n}
         return dt, stages
 
-    def fused_mode(cache):
-        """Times rapid_iw_pg_loss_fwd_bwd in one backward mode; None if the cache does not fit."""
+    def prepare(sp):
+        w = wl.make_workload(sp, seed=0, device="cuda")
+        rms = {}
+        if args.rmsnorm:
+            gen = torch.Generator(device="cuda").manual_seed(1)
+            rms = dict(rms_weight=(1.0 + 0.1 * torch.randn(d, device="cuda", generator=gen)).to(torch.bfloat16), rms_eps=1e-6)
+        if not sp.fwd_only:
+            w["logp_behav"], _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"], **rms)
+        return w, rms, int(w["mask"].sum().item())
+
+    def fused_mode(w, rms, M, mode):
+        """Times rapid_iw_pg_loss_fwd_bwd in one backward mode; None if its workspace does not fit."""
+        K = w["K"]
+        cache = mode in ("chunks", "whole")
         if cache and spec.dtype != "bf16":
             return None              # the cache is a bf16 mode
-        if cache:
-            # the cache is sized for the batch's token count, which a trainer knows from its sampler
-            need = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dt_code, max_tokens=M)
-            torch.cuda.empty_cache()     # what the workload generator left in torch's allocator counts as free
-            free, _ = torch.cuda.mem_get_info()
-            if not need or need + (8 << 30) > free:
-                return None
-            ws_bytes = None
-        else:
-            ws_bytes = int(args.workspace_gib * 2**30) if args.workspace_gib > 0 else None
-            if args.chunk_rows:
-                mn = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, N, T, d, V, K, dt_code, minimum=True)
-                vpad = (V + 255) // 256 * 256
-                ldv = vpad + 64 if (vpad // 64) % 2 == 0 else vpad
-                ws_bytes = mn + (args.chunk_rows - 256) * ldv * 2
-        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=ws_bytes, logits_cache=cache, max_tokens=M)
+        op = rb.OP_IW_PG_FWD_BWD_CACHED if cache else rb.OP_IW_PG_FWD_BWD
+        # "whole": sized for the batch's token count, which a trainer knows from its sampler
+        need = rb.rapid_workspace_bytes(op, N, T, d, V, K, dt_code, max_tokens=M if mode == "whole" else 0)
+        torch.cuda.empty_cache()     # what the workload generator left in torch's allocator counts as free
+        free, _ = torch.cuda.mem_get_info()
+        if not need or need + (8 << 30) > free:
+            return None
+        buf = rb.IwPgBuffers(w["hidden"], w["W"], K, workspace_bytes=need)
         dt, stages = timed(lambda: rb.rapid_iw_pg_loss_fwd_bwd(
             w["hidden"], w["W"], w["tokens"], w["mask"], w["logp_behav"], w["rewards"], w["group_ids"], K,
             buffers=buf, optional_outputs=False, logits_cache=cache, max_tokens=M, **rms))
+        status = int(buf.dev_status.item())
         ws_gib = buf.workspace.numel() / 2**30
-        del buf                      # the workspace goes back before the other mode takes its own
+        del buf                      # the workspace goes back before the next mode takes its own
         torch.cuda.empty_cache()
+        if status:
+            raise SystemExit(f"bench.py: the library reported device status {status} in mode {mode}")
         return dt, stages, ws_gib
 
+    w, rms, M = prepare(spec)
     if fwd_only:
         ws_bytes = rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, N, T, d, V, 1, dt_code)
         ws = rb.alloc_workspace(ws_bytes)
@@ -192,49 +218,50 @@ def main():
         flops_per_token = 2.0 * d * V
         mode = "forward only"
     else:
-        logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"], **rms)
-        w["logp_behav"] = logp_b
         flops_per_token = 6.0 * d * V
         mode = args.mode
-        res = fused_mode(mode == "cache")
-        if res is None:              # the ratios of every row do not fit beside the workload
+        res = fused_mode(w, rms, M, mode)
+        if res is None:              # no cache for this dtype, or no room
             mode = "recompute"
-            res = fused_mode(False)
+            res = fused_mode(w, rms, M, mode)
         dt, stages, ws_gib = res
     torch.cuda.synchronize()
 
     ms_per_step = dt / args.steps * 1e3
     tok_s = M * args.steps / dt
+    executed = {"forward only": 2.0, "chunks": 6.0, "whole": 6.0, "recompute": 8.0}[mode] * d * V
 
-    # roofline of the dominant kernel: algorithmic flop of ONE launch / its average duration.
-    # Every contraction kernel does 2*d*V flop per token it processes; a step's tokens are split
-    # over the launches of a stage (row blocks), so one launch processes M / (launches that hold
-    # tokens) tokens on average.
-    gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and stages[s]["launches_per_step"] > 1]
+    # the MFMA pipe on its own (no memory traffic), outside the timed region: what the published
+    # peak turns into at the clock the chip sustains with integer-valued and with random operands
+    tf_int, _ = rb.rapid_mfma_probe(0, 100000)
+    tf_rnd, _ = rb.rapid_mfma_probe(1, 100000)
+
+    # Roofline of the dominant kernel.  Every contraction stage does 2 d V algorithmic flop per token, so a
+    # stage's rate is 2 d V M / (its time per step); a launch that holds tokens (the launches are made for the
+    # padded upper bound, those past the last token return at once) processes M / (live launches) of them.
+    lengths = w["lengths"].tolist()
+    if mode == "chunks":
+        chunks = chunk_rows_of(lengths, spec.G, CACHE_ROWS)
+        live = {"fwd_lse": sum(-(-r // FWD_BLOCK_ROWS) for r in chunks), "dh": len(chunks), "dw": len(chunks)}
+    else:
+        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-M // FWD_BLOCK_ROWS), "dh": -(-M // 65536), "dw": -(-M // 65536)}
+    gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and (s != "dz" or mode == "recompute")]
     if gemm_stages:
+        per_stage = {}
+        for st_name in gemm_stages:
+            ms = stages[st_name]["ms_per_step"]
+            rate = 2.0 * d * V * M / (ms * 1e-3) / 1e12
+            per_stage[st_name] = {"achieved": rate, "frac": rate * 1e12 / PEAK_BF16_MFMA, "frac_of_probe": rate / tf_rnd,
+                                  "ms_per_step": ms, "live_launches_per_step": live.get(st_name),
+                                  "avg_live_launch_ms": ms / live[st_name] if live.get(st_name) else None}
         dom = max(gemm_stages, key=lambda s: stages[s]["ms_per_step"])
-        launches = stages[dom]["launches_per_step"]
-        # blocks past the last valid row exit at once: count only launches that had rows
-        Mmax_pad = (N * T + 255) // 256 * 256
-        chunk_rows = Mmax_pad / launches
-        live = max(1, -(-M // int(chunk_rows)))
-        tokens_per_launch = M / live
-        avg_ms = stages[dom]["ms_per_step"] / live
-        achieved = 2.0 * d * V * tokens_per_launch / (avg_ms * 1e-3) / 1e12
-        # HBM-side bytes per full launch from rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by a copy
-        # kernel of known size); measured on the headline workload only, see profiles/
-        traffic = MEASURED_TRAFFIC_BYTES.get((mode, dom)) if spec.name == "cfg2_qwen1.5b" else None
-        roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA / 1e12,
-                    "unit": "TFLOP/s", "frac": achieved / (PEAK_BF16_MFMA / 1e12), "traffic": traffic,
-                    "traffic_unit": "bytes per full launch (fabric reads + writes)",
-                    "traffic_source": "profiles/bench_cfg2_qwen1.5b_kernel_trace_and_traffic.md",
-                    "avg_launch_ms": avg_ms, "live_launches_per_step": live,
-                    "tokens_per_launch": tokens_per_launch, "flop_per_token": 2.0 * d * V}
-        # the same figure for every contraction stage of the step (each does 2 d V flop per token)
-        roofline["all_contraction_stages"] = {
-            st: {"achieved": 2.0 * d * V * M / (stages[st]["ms_per_step"] * 1e-3) / 1e12,
-                 "frac": 2.0 * d * V * M / (stages[st]["ms_per_step"] * 1e-3) / PEAK_BF16_MFMA,
-                 "ms_per_step": stages[st]["ms_per_step"]} for st in gemm_stages}
+        traffic, source = (measured_traffic(rb.rapid_version(), mode, dom) if spec.name == "cfg2_qwen1.5b" else (None, None))
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": per_stage[dom]["achieved"], "peak": PEAK_BF16_MFMA / 1e12,
+                    "unit": "TFLOP/s", "frac": per_stage[dom]["frac"], "frac_of_probe": per_stage[dom]["frac_of_probe"],
+                    "traffic": traffic, "traffic_unit": "bytes per live launch (fabric reads + writes)", "traffic_source": source,
+                    "avg_launch_ms": per_stage[dom]["avg_live_launch_ms"], "live_launches_per_step": live.get(dom),
+                    "tokens_per_launch": M / live[dom] if live.get(dom) else None, "flop_per_token": 2.0 * d * V,
+                    "all_contraction_stages": per_stage}
     else:
         # the fp32 accuracy path (config 0): plain strided contractions with fp64 accumulation on the
         # vector ALUs, four of them per call (logits twice, dHidden, dW); all its launches are one stage
@@ -252,30 +279,35 @@ def main():
         "config": {"workload": spec.name, "d": d, "V": V, "prompts": spec.prompts, "G": spec.G, "N": N,
                    "T": T, "response_tokens": M, "workspace_gib": ws_gib,
                    "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd",
-                   "backward_mode": mode, "final_rmsnorm": bool(args.rmsnorm),
-                   "executed_flop_per_token": (2.0 if fwd_only else 6.0 if mode == "cache" else 8.0) * d * V},
+                   "backward_mode": mode, "final_rmsnorm": bool(args.rmsnorm), "executed_flop_per_token": executed},
         "frac_bf16_mfma_peak_algorithmic": flops_per_token * tok_s / PEAK_BF16_MFMA,
+        "frac_of_mfma_probe_algorithmic": flops_per_token * tok_s / (tf_rnd * 1e12),
         "roofline": roofline,
         "stages": stages,
+        "mfma_probe": {"unit": "TFLOP/s", "small_integer_operands": tf_int, "random_bf16_operands": tf_rnd,
+                       "note": "8 independent 32x32x16 bf16 MFMA chains per wave, 2 waves per SIMD, registers only"},
     }
-    # the MFMA pipe on its own (no memory traffic), outside the timed region: what the published
-    # peak turns into at the clock the chip sustains with integer-valued and with random operands
-    tf_int, _ = rb.rapid_mfma_probe(0, 100000)
-    tf_rnd, _ = rb.rapid_mfma_probe(1, 100000)
-    out["mfma_probe"] = {"unit": "TFLOP/s", "small_integer_operands": tf_int, "random_bf16_operands": tf_rnd,
-                         "note": "8 independent 32x32x16 bf16 MFMA chains per wave, 2 waves per SIMD, registers only"}
-    # the same call in its other backward mode, timed the same way; reported beside `value`, never as it
     if not fwd_only and not args.one_mode:
-        other = "recompute" if mode == "cache" else "cache"
-        res = fused_mode(other == "cache")
-        out["other_backward_mode"] = None if res is None else {
-            "backward_mode": other, "value": M * args.steps / res[0], "unit": "tokens/s",
-            "ms_per_step": res[0] / args.steps * 1e3,
-            "frac_bf16_mfma_peak_algorithmic": flops_per_token * M * args.steps / res[0] / PEAK_BF16_MFMA,
-            "workspace_gib": res[2], "executed_flop_per_token": (6.0 if other == "cache" else 8.0) * d * V,
-            "stages_ms_per_step": {k: v["ms_per_step"] for k, v in res[1].items()}}
+        def summary(res, m, M_):
+            return None if res is None else {
+                "backward_mode": m, "value": M_ * args.steps / res[0], "unit": "tokens/s", "ms_per_step": res[0] / args.steps * 1e3,
+                "frac_bf16_mfma_peak_algorithmic": flops_per_token * M_ * args.steps / res[0] / PEAK_BF16_MFMA,
+                "workspace_gib": res[2], "executed_flop_per_token": (8.0 if m == "recompute" else 6.0) * d * V,
+                "stages_ms_per_step": {k: v["ms_per_step"] for k, v in res[1].items()}}
+        # the same call in its other backward modes, timed the same way; reported beside `value`, never as it
+        out["other_backward_modes"] = [summary(fused_mode(w, rms, M, m), m, M) for m in ("chunks", "whole", "recompute") if m != mode]
+        # and the timed mode on the workload's calibrated companion: dense gradient operands (the regime of the
+        # paper's staleness table), which cost this power-limited chip a few per cent of clock
+        if not args.calibrated and spec.sigma > 0:
+            del w
+            torch.cuda.empty_cache()
+            wc, rmsc, Mc = prepare(wl.calibrated(base_spec))
+            out["calibrated_companion"] = summary(fused_mode(wc, rmsc, Mc, mode), mode, Mc)
+            del wc
+            torch.cuda.empty_cache()
+            w, rms, M = prepare(spec)
     if not args.no_cpu_baseline and not fwd_only and not args.rmsnorm:
-        out["cpu_baseline"] = cpu_baseline(w, rb, logits_cache=(mode == "cache"))
+        out["cpu_baseline"] = cpu_baseline(w, rb, logits_cache=(mode != "recompute"))
     print(json.dumps(out))
 
 

@@ -9,10 +9,13 @@
  *    given by rapid_workspace_bytes().  `opts` of rapid_iw_pg_loss_fwd_bwd is a HOST pointer.
  *  - All work is enqueued on the caller's HIP stream (`stream` is a hipStream_t passed as
  *    void*; NULL = the default stream).  Calls are asynchronous and never synchronise the
- *    device; outputs are valid once the stream has reached the end of the call's work.  (The two
- *    benchmark helpers rapid_profile_read and rapid_mfma_probe wait for their own events.)
- *  - Return value: RAPID_OK or a negative RAPID_ERR_* detected on the host before any launch
- *    (nothing has been enqueued then).  rapid_last_error() gives a thread-local message.
+ *    device; outputs are valid once the stream has reached the end of the call's work.
+ *  - Return value: RAPID_OK or a negative RAPID_ERR_*.  Every code except RAPID_ERR_HIP is found on
+ *    the host before any launch (nothing has been enqueued then).  RAPID_ERR_HIP after the
+ *    validation means that the HIP runtime reported an error while or after the call's kernels were
+ *    enqueued (hipGetLastError at the end of the call, which also returns an error another library
+ *    left behind on this thread): part of the work may be on the stream and the outputs are not
+ *    usable.  rapid_last_error() gives a thread-local message.
  *  - Errors only the device can see (token id outside [0,V) at an unmasked position, group id
  *    outside [0,K), non-finite reward or behaviour log-prob; with opts->logits_cache also the two
  *    conditions documented at RAPID_STATUS_LOGIT_RANGE and RAPID_STATUS_TOKEN_BOUND) OR a bit into
@@ -57,6 +60,12 @@ extern "C" {
                                        dhidden and dW is truncated */
 #define RAPID_STATUS_TOKEN_BOUND 32 /* more valid tokens than opts->max_tokens promised (logits_cache = 1): the tokens
                                       past the bound were left out; the call's outputs are not usable */
+#define RAPID_STATUS_GROUP_LAYOUT 64 /* logits_cache = 1 with a workspace that cannot cache the whole batch: the batch is
+                                      then worked through in chunks of whole groups, which needs the members of every
+                                      group next to each other in the batch and every group's tokens to fit into the
+                                      cache rows the workspace affords.  Set when one of the two does not hold; the
+                                      call's outputs are not usable.  Repeat the call with logits_cache = 0, or with
+                                      the workspace of rapid_workspace_bytes_max_tokens (one chunk, any layout) */
 
 /* enums */
 #define RAPID_DTYPE_F32 0
@@ -92,10 +101,18 @@ typedef struct rapid_iw_pg_opts {
                               of the row's log-sum-exp that is known before the sweep, so the stored value
                               is close to the probability p_v), and the backward contracts those directly
                               (dz = -g exp(r - lse) (stored - onehot exp(lse - r))): one contraction fewer
-                              and no pass over rows x V in between, for 2 bytes x rows x V more workspace
-                              (rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...), or ..._max_tokens).
-                              Same single bf16 rounding per element of the rows x V intermediate as
-                              mode 0; see RAPID_STATUS_LOGIT_RANGE for its one limit */
+                              and no pass over rows x V in between.  The cache holds as many token rows as
+                              the workspace affords (2 bytes x V per row).  If that is every token of the batch
+                              (rapid_workspace_bytes_max_tokens), the call is one sweep.  If not
+                              (rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...): 65536 rows), the batch is
+                              worked through in chunks of whole groups, in order, each chunk as many groups as the
+                              cache holds: forward with store, the chunk's ratios, advantages (Eq. (5) needs only
+                              the group) and coefficients (Eq. (3)'s 1/N is known beforehand), dHidden and dW of
+                              the chunk, then the next; with normalized_grads the sums are rescaled on the way
+                              whenever a chunk raises the maximum.  This needs every group's members adjacent in
+                              the batch (see RAPID_STATUS_GROUP_LAYOUT).  Same single bf16 rounding per element
+                              of the rows x V intermediate as mode 0; see RAPID_STATUS_LOGIT_RANGE for its one
+                              limit */
     int ratio_level;       /* 0 (default): the outer weight of Eq. (3) is the generation-level ratio rho_n, as
                               the paper defines it.  1: a variant the paper does not define (its token-level
                               ratios are a diagnostic, Sec. 4.3): every token carries its own ratio,
@@ -104,9 +121,9 @@ typedef struct rapid_iw_pg_opts {
                               Eq. (5) with generation-level clipped weights.  grad_log_scale is then
                               log max |dLoss/dlogp_{n,t}| over tokens.  Ignored with coef_override */
     int64_t max_tokens;    /* 0, or the caller's upper bound on the number of valid tokens (sum of mask), which it
-                              knows from its sampler: with logits_cache = 1 the workspace then has to hold
-                              the ratios of that many rows only instead of N*T
-                              (rapid_workspace_bytes_max_tokens).  Checked on the device:
+                              knows from its sampler: with logits_cache = 1 the cache holds the whole batch
+                              once it has that many rows instead of N*T (rapid_workspace_bytes_max_tokens), and
+                              a chunked call is laid out for that many tokens.  Checked on the device:
                               RAPID_STATUS_TOKEN_BOUND */
     const float* coef_override; /* DEVICE [N] or NULL: use these per-generation coefficients g_n
                               = dLoss/dlogp_{n,t} instead of the estimator's (loss = sum g_n) */
@@ -139,60 +156,16 @@ const char* rapid_last_error(void);
 /* Fills *opts with the defaults described above.  Host pointer. */
 void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
 
-/* Process-wide switches (host state, not thread-safe against concurrent calls).
- * key 1: per-stage event timing on (1) / off (0, default); see rapid_profile_read.
- * key 2: waves per workgroup of the contraction kernels: 0 (default) = each kernel's own choice (8,
- *        i.e. 2 x 4 waves of 128 x 64, for the logits kernels and dW; 4, i.e. 2 x 2 waves of 128 x 128,
- *        for dHidden), or 4 / 8 / 16 for all of them.  Same 256 x 256 tile and same results either way.
- * keys 10, 11, 12: tile-order blocking (tiles along the first tile dimension that share one tile of
- *        the second before the order moves on) of the logits kernels, the dHidden kernel (0 = all)
- *        and the dW kernel; defaults 4, 0, 2 were measured best on MI355X.  Results are identical.
- * key 13: token-row tiles (of 256 rows) per launch of the two logits kernels (forward and dz),
- *        default 64: they sweep all of W over one such block of rows at a time so that the block's
- *        hidden rows stay in the memory-side cache.  Results are identical.
- * key 14: 1 (default) / 0: the dHidden kernel reads W from a tile-blocked copy (one contiguous
- *        32 KiB block per 256-row tile and 64-column step) / from the row-major copy.  Results
- *        are identical.
- * key 15: with logits_cache = 1, token-row tiles (of 256 rows) per launch of the dHidden and dW
- *        kernels, default 256 (0 = all rows in one launch; multiples of 128 fill whole rounds of
- *        workgroups).  dW sums over the launches in a fixed order, so results depend on it only
- *        through fp32 rounding.
- * key 16: K steps (of 64 vocabulary entries; a power of two; default 0 = off) between meetings
- *        of the dHidden kernel's workgroups: they count themselves in on a workspace word and wait,
- *        for a bounded time, for the others, so that all XCDs sweep W together and share it through
- *        the memory-side cache.  A timing hint only: results are identical, and a meeting that runs
- *        out of time switches the pacing off for the rest of the launch. */
-int rapid_set_tuning(int key, int value);
-
-/* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of
- * its stages with HIP events on the caller's stream (host objects, no device memory);
- * rapid_profile_read waits for those events, writes the milliseconds and the number of timed spans
- * per stage into two HOST arrays of n_stages >= RAPID_N_STAGES entries, and clears the record.
- * Stage order: 0 compaction/gather, 1 operand packing (with rms_weight: the final norm), 2 forward
- * logits+log-sum-exp kernel, 3 sampled-token logits and log-sum-exp merge, 4 estimator reductions
- * (ratios, advantages, loss, row coefficients), 5 zeroing of masked gradient rows (with rms_weight
- * also the norm's backward), 6 dz kernel (with logits_cache: the row-factor pass), 7 unused,
- * 8 dHidden kernel, 9 dW kernel, 10 fp32 path, 11 dW conversion. */
-#define RAPID_N_STAGES 12
-int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stages);
-
-/* Diagnostic for benchmarks: the rate the bf16 matrix pipe sustains on its own (32 x 32 x 16 MFMAs
- * out of registers on every SIMD of the device, no LDS or memory traffic), the ceiling the roofline
- * of the contraction kernels (Sec. 3.1's LM head; the backward of Eq. (3)) can be read against at
- * the clock the chip holds under load.  random_operands = 0 uses small-integer operands (the
- * published peak is reached), 1 uses random bf16 values in [-1, 1] (the power management lowers the
- * clock).  Runs `iters` (1 .. 10^7) MFMAs per accumulator on `stream`, WAITS for them, and writes
- * TFLOP/s and the elapsed milliseconds to HOST pointers (either may be NULL).  Allocates nothing.
- * Errors: RAPID_ERR_SHAPE (iters out of range), RAPID_ERR_ARCH, RAPID_ERR_HIP. */
-int rapid_mfma_probe(int random_operands, int iters, double* tflops_out, double* ms_out, void* stream);
-
 /* Workspace sizes in bytes for `op` at the given problem size.  rapid_workspace_bytes is the
  * recommended size (backward row-chunks large enough to fill the chip); rapid_workspace_min_bytes
  * the smallest the call accepts (smaller chunks, same results).  RAPID_OP_GROUP_ADVANTAGE needs
- * none (returns 0).  RAPID_OP_IW_PG_FWD_BWD_CACHED is the size rapid_iw_pg_loss_fwd_bwd needs with
- * opts->logits_cache = 1 (bf16 only; minimum = recommended).  rapid_workspace_bytes_max_tokens is
- * rapid_workspace_bytes for a call that passes the same opts->max_tokens (only the cached size
- * depends on it; 0 = no bound).  Returns 0 for invalid arguments. */
+ * none (returns 0).  RAPID_OP_IW_PG_FWD_BWD_CACHED are the sizes for rapid_iw_pg_loss_fwd_bwd with
+ * opts->logits_cache = 1 (bf16 only): recommended = a cache of 65536 token rows (or of all N * T positions
+ * if those are fewer), minimum = a cache of 256 rows; the call uses as many cache rows as the workspace
+ * it is given affords.  rapid_workspace_bytes_max_tokens (cached op only; the others ignore the bound) is
+ * the size with which the cache holds every token of a batch of at most max_tokens valid tokens (0 = N * T)
+ * at once: the largest useful size, and the one that puts no condition on where the members of a group
+ * lie in the batch.  Returns 0 for invalid arguments. */
 size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype);
 size_t rapid_workspace_min_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype);
 size_t rapid_workspace_bytes_max_tokens(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype,
@@ -200,8 +173,8 @@ size_t rapid_workspace_bytes_max_tokens(int op, int64_t N, int64_t T, int64_t d,
 
 /*
  * Behaviour / current-policy log-probabilities of the sampled tokens (Sec. 3.1: pi(y_t | .) is
- * the softmax of the LM head; Alg. 1, "copy the current policy mu <- pi_theta": these are the
- * log mu(y_t) the ratio of Eq. (3) divides by).
+ * the softmax of the LM head; Alg. 1, the step that snapshots the current policy as the behaviour
+ * policy mu: these are the log mu(y_t) the ratio of Eq. (3) divides by).
  *   logp_out[n,t] = z[y] - logsumexp(z),  z = hidden[n,t,:] . W / temperature   (0 where mask = 0)
  *   lse_out[n,t]  = logsumexp(z) (optional, may be NULL)
  * The [N*T, V] logits are never written to memory.
@@ -259,7 +232,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                              size_t workspace_bytes, void* stream);
 
 /*
- * The parameter update of Alg. 1's inner loop ("update theta with the gradient of Eq. (3)"), for
+ * The parameter update of Alg. 1's inner loop (the step after the gradient of Eq. (3)), for
  * the LM head alone and as plain gradient descent on the returned loss:
  *   master[i] -= lr * grad[i]   (fp32, n elements, same layout as dW_out)
  * and, if w_out != NULL, w_out[i] = the updated weight in `dtype` (the W of the next call).
@@ -268,7 +241,8 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
 int rapid_sgd_step(float* master, const float* grad, int64_t n, float lr, void* w_out, int dtype, void* stream);
 
 /*
- * Integer bookkeeping of the padding mask (device outputs, any may be NULL):
+ * Integer bookkeeping of the padding mask (device outputs; seq_len_out and cu_seqlen_out are
+ * required, RAPID_ERR_NULL otherwise; row_index_out may be NULL):
  *   seq_len_out [N] int32, cu_seqlen_out [N+1] int32 (exclusive prefix sum, last = M),
  *   row_index_out [N*T] int32: the first M entries are the flat positions n*T+t of the valid
  *   tokens in row-major order.  This is the first step of both calls above, exported so that it

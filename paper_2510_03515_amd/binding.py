@@ -21,6 +21,7 @@ W_DV, W_VD = 0, 1
 OP_LOGPROB_FWD, OP_GROUP_ADVANTAGE, OP_IW_PG_FWD_BWD, OP_IW_PG_FWD_BWD_CACHED = 0, 1, 2, 3
 STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LOGP, STATUS_LOGIT_RANGE = 1, 2, 4, 8, 16
 STATUS_TOKEN_BOUND = 32
+STATUS_GROUP_LAYOUT = 64
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_workspace_bytes_max_tokens", "rapid_logprob_fwd", "rapid_logprob_fwd_rmsnorm",
@@ -91,8 +92,6 @@ def load():
     lib.rapid_sgd_step.argtypes = [vp, vp, i64, C.c_float, vp, ci, vp]
     lib.rapid_sgd_step.restype = ci
     _lib = lib
-    if os.environ.get("RAPID_WAVES"):      # 4, 8 or 16 waves per contraction workgroup (tuning only)
-        lib.rapid_set_tuning(2, int(os.environ["RAPID_WAVES"]))
     return lib
 
 
@@ -275,7 +274,7 @@ def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group
     _need(rewards, torch.float32, "rewards")
     _need(group_ids, torch.int32, "group_ids")
     if buffers is None:
-        buffers = IwPgBuffers(hidden, W, K, w_layout)
+        buffers = IwPgBuffers(hidden, W, K, w_layout, logits_cache=logits_cache, max_tokens=max_tokens)
     b = buffers
     o = default_opts()
     o.eta = float(eta) if math.isfinite(eta) else float("inf")

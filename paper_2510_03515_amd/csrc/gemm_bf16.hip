@@ -28,6 +28,7 @@
 // i = 8 (v / 4) + 4 (l / 32) + v % 4: a lane owns runs of 4 consecutive i for one j, so every
 // epilogue keeps j = the token row (per-lane scalars: lse, coefficient, token id, output row) and
 // stores 4 consecutive i with one 8- or 16-byte access.
+#include <atomic>
 #include <utility>
 
 #include "rapid_internal.h"
@@ -509,10 +510,9 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
 // of a grouped order: GI tiles along i for one j, then the next j, ... so that workgroups resident
 // together on an XCD re-use each other's operand panels out of L2.
 struct TileId { int ti, tj; bool valid; };
-__device__ __forceinline__ TileId map_tile(int pid, int tilesI, int tilesJ, int GI) {
+// position `vid` of the grouped order -> tile
+__device__ __forceinline__ TileId tile_of_vid(int vid, int tilesI, int tilesJ, int GI) {
     const int total = tilesI * tilesJ;
-    const int per = (total + 7) / 8;
-    const int vid = (pid & 7) * per + (pid >> 3);
     TileId t;
     t.valid = vid < total;
     const int group_sz = GI * tilesJ;
@@ -524,15 +524,19 @@ __device__ __forceinline__ TileId map_tile(int pid, int tilesI, int tilesJ, int 
     t.tj = rem / gi;
     return t;
 }
+__device__ __forceinline__ TileId map_tile(int pid, int tilesI, int tilesJ, int GI) {
+    const int per = (tilesI * tilesJ + 7) / 8;
+    return tile_of_vid((pid & 7) * per + (pid >> 3), tilesI, tilesJ, GI);
+}
 
 __host__ __device__ inline int ids_for(int tilesI, int tilesJ) { return (int)(((int64_t)tilesI * tilesJ + 7) / 8 * 8); }
 // The kernels are persistent: one workgroup per CU (LDS admits no more) walks the ids
 // blockIdx.x, blockIdx.x + gridDim.x, ...; gridDim.x is a multiple of 8, so a workgroup stays on its
 // XCD's share of the order and the workgroups of an XCD stay on neighbouring tiles.  This saves the
 // launch gap between workgroups and the dispatch of the ids whose tiles hold no token rows.
-int g_num_cu = 256;
+std::atomic<int> g_num_cu{256};
 inline unsigned grid_for(int tilesI, int tilesJ) {
-    const int ids = ids_for(tilesI, tilesJ), cus = g_num_cu / 8 * 8;
+    const int ids = ids_for(tilesI, tilesJ), cus = g_num_cu.load() / 8 * 8;
     return (unsigned)(ids < cus ? ids : cus);
 }
 
@@ -663,7 +667,7 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
         if (clamped && a.dev_status) atomicOr(a.dev_status, RAPID_STATUS_LOGIT_RANGE);
         __syncthreads();   // every wave is done with both stages
         store_tile_through_lds<S>(lds, L,
-                                  a.zc + (j_tile + L.wave_j * (WJ * 32)) * a.ldz + (int64_t)t.ti * S::BI + L.wave_i * (WI * 32),
+                                  a.zc + (j_tile - a.zc_row0 + L.wave_j * (WJ * 32)) * a.ldz + (int64_t)t.ti * S::BI + L.wave_i * (WI * 32),
                                   a.ldz, [&](int ib, int jb, int v) {
                                       const float e = __builtin_amdgcn_exp2f(fmaf(acc[ib][jb][v], zs, nm[jb]));
                                       l[jb] += e;
@@ -682,8 +686,8 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
         const int64_t j = j_tile + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
         const float ls = l[jb] + __shfl_xor(l[jb], 32, 64);
         if (L.hi == 0) {
-            a.part_max[slot * a.ld_part + j] = m[jb] * a.inv_temp;
-            a.part_sum[slot * a.ld_part + j] = ls;
+            a.part_max[slot * a.ld_part + (j - a.part_row0)] = m[jb] * a.inv_temp;
+            a.part_sum[slot * a.ld_part + (j - a.part_row0)] = ls;
         }
     }
     }
@@ -727,43 +731,27 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------ dh
-template <class S>
-__global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
-    constexpr int WI = S::WI, WJ = S::WJ;
-    extern __shared__ __attribute__((aligned(128))) char lds[];
-    const int tilesD = (int)(a.dpadR / S::BI);
-    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
-    if (a.m0 >= Mr) return;
-    // the order (and with it the split over the XCDs) covers the row tiles that hold tokens only: a
-    // short last chunk would otherwise leave whole XCDs with nothing but empty tiles
-    const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));
-    // pacing of the launch's workgroups (see GridPace): with total = 8 * per tiles (or fewer in the last
-    // XCD shares) the workgroups of round r are those whose id is a valid tile
-    const int total = tilesD * tilesM, per = (total + 7) / 8, wgs = gridDim.x / 8;
-    const int ktiles = (int)(a.Vpad / K_TILE);
-    GridPace pace{a.pace, 0u, 0u, a.pace ? a.pace_every : 0};
-    int round = 0;
-    unsigned before = 0;   // valid tiles of the rounds before this one, over all XCDs
-    for (int pid = blockIdx.x, ids = ids_for(tilesD, tilesM); pid < ids; pid += gridDim.x, ++round) {
-    unsigned now = 0;
-    if (pace.every) {
-        for (int x = 0; x < 8; ++x) {
-            const int mine = max(0, min(per, total - x * per));
-            now += (unsigned)max(0, min(wgs, mine - round * wgs));
-        }
+// The tiles of dHidden are long (the contraction runs over the whole vocabulary) and few: a launch has
+// a handful of rounds of one tile per workgroup, and a last round that is only partly filled would
+// leave most of the chip idle for a whole tile.  So in the last, partial round of an XCD's share the
+// rem tiles that are left are cut along the contraction into S = floor(workgroups / rem) slices each;
+// a workgroup computes one slice and leaves its fp32 accumulators in `part`, and dh_reduce_kernel adds
+// the slices of a tile in slice order and stores the result: the last round then takes 1/S of a tile's
+// time, and the result does not depend on timing.
+struct DhShare {       // an XCD's share of the order, and how its last round is cut
+    int total, per, wgs, mine, full_rounds, rem, slices;
+    __device__ __forceinline__ DhShare(int tilesD, int tilesM, int grid, int x, bool can_split) {
+        total = tilesD * tilesM; per = (total + 7) / 8; wgs = grid / 8;
+        mine = max(0, min(per, total - x * per));
+        full_rounds = mine / wgs; rem = mine - full_rounds * wgs;
+        slices = (can_split && rem > 0) ? wgs / rem : 1;
     }
-    const TileId t = map_tile(pid, tilesD, tilesM, a.gi > 0 ? a.gi : tilesD);
-    if (!t.valid) { before += now; continue; }
-    f32x16 acc[WI][WJ];
-    pace.n = now;
-    pace.base = (unsigned)(ktiles / (pace.every ? pace.every : 1)) * before;
-    before += now;
-    if (a.WdvB)   // A from the tile-blocked copy: one contiguous 128-byte-row block per K step
-        mainloop<S, GridPace>(a.WdvB + (int64_t)t.ti * (a.Vpad / K_TILE) * (S::BI * 64), 64,
-                    a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, ktiles, lds, acc, S::BI * 128, 128, pace);
-    else
-        mainloop<S>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv, a.ldv,
-                    a.dz + (int64_t)t.tj * S::BJ * a.ldv, a.ldv, (int)(a.Vpad / K_TILE), lds, acc);
+};
+
+// stores a tile of dHidden: accumulators times the row factor (if any), bf16, to the rows' positions
+template <class S>
+__device__ __forceinline__ void dh_store(const DhArgs& a, const TileId& t, int M, const f32x16 (&acc)[S::WI][S::WJ]) {
+    constexpr int WI = S::WI, WJ = S::WJ;
     const Lane<S> L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
 #pragma unroll
@@ -782,7 +770,109 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
                                                       cj * acc[ib][jb][q * 4 + 2], cj * acc[ib][jb][q * 4 + 3]);
             }
     }
+}
+
+template <class S>
+__global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
+    constexpr int WI = S::WI, WJ = S::WJ;
+    extern __shared__ __attribute__((aligned(128))) char lds[];
+    const int tilesD = (int)(a.dpadR / S::BI);
+    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
+    if (a.m0 >= Mr) return;
+    // the order (and with it the split over the XCDs) covers the row tiles that hold tokens only: a
+    // short last chunk would otherwise leave whole XCDs with nothing but empty tiles
+    const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));
+    const int x = blockIdx.x & 7, w = blockIdx.x >> 3;
+    const DhShare sh(tilesD, tilesM, gridDim.x, x, a.part != nullptr && a.pace == nullptr);
+    const int ktiles = (int)(a.Vpad / K_TILE);
+    const int gi = a.gi > 0 ? a.gi : tilesD;
+    // pacing of the launch's workgroups (see GridPace): with total = 8 * per tiles (or fewer in the last
+    // XCD shares) the workgroups of round r are those whose id is a valid tile
+    GridPace pace{a.pace, 0u, 0u, a.pace ? a.pace_every : 0};
+    unsigned before = 0;   // valid tiles of the rounds before this one, over all XCDs
+    for (int round = 0;; ++round) {
+        const bool split = sh.slices >= 2 && round == sh.full_rounds;
+        int pos, k0 = 0, k1 = ktiles;
+        if (!split) {
+            pos = round * sh.wgs + w;
+            if (round * sh.wgs >= sh.per) break;           // uniform over the launch: nobody has a tile in this round
+        } else {
+            if (w >= sh.rem * sh.slices) break;
+            const int slice = w / sh.rem;
+            pos = sh.full_rounds * sh.wgs + w % sh.rem;
+            k0 = (int)((int64_t)ktiles * slice / sh.slices);
+            k1 = (int)((int64_t)ktiles * (slice + 1) / sh.slices);
+        }
+        unsigned now = 0;
+        if (pace.every) {
+            for (int xx = 0; xx < 8; ++xx) {
+                const int mine = max(0, min(sh.per, sh.total - xx * sh.per));
+                now += (unsigned)max(0, min(sh.wgs, mine - round * sh.wgs));
+            }
+        }
+        if (pos >= sh.mine) {
+            if (split) break;
+            before += now;
+            continue;
+        }
+        const TileId t = tile_of_vid(x * sh.per + pos, tilesD, tilesM, gi);
+        f32x16 acc[WI][WJ];
+        pace.n = now;
+        pace.base = (unsigned)(ktiles / (pace.every ? pace.every : 1)) * before;
+        before += now;
+        if (a.WdvB)   // A from the tile-blocked copy: one contiguous 128-byte-row block per K step
+            mainloop<S, GridPace>(a.WdvB + ((int64_t)t.ti * (a.Vpad / K_TILE) + k0) * (S::BI * 64), 64,
+                                  a.dz + (int64_t)t.tj * S::BJ * a.ldv + (int64_t)k0 * K_TILE, a.ldv, k1 - k0, lds, acc,
+                                  S::BI * 128, 128, pace);
+        else
+            mainloop<S>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv + (int64_t)k0 * K_TILE, a.ldv,
+                        a.dz + (int64_t)t.tj * S::BJ * a.ldv + (int64_t)k0 * K_TILE, a.ldv, k1 - k0, lds, acc);
+        if (!split) {
+            dh_store<S>(a, t, M, acc);
+        } else {   // one slice of a tile: the accumulators as they are, register r of thread tid at part[r][tid]
+            float* o = a.part + (int64_t)blockIdx.x * (S::BI * S::BJ) + threadIdx.x;
+#pragma unroll
+            for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+                for (int jb = 0; jb < WJ; ++jb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[((ib * WJ + jb) * 16 + v) * S::NT] = acc[ib][jb][v];
+            break;
+        }
     }
+}
+
+// adds the slices of the tiles that dh_kernel cut (same launch geometry: grid_of_dh says how many
+// workgroups that launch had) and stores them; one workgroup per (XCD, tile of its last round)
+template <class S>
+__global__ __launch_bounds__(S::NT) void dh_reduce_kernel(DhArgs a, int grid_of_dh) {
+    constexpr int WI = S::WI, WJ = S::WJ;
+    const int tilesD = (int)(a.dpadR / S::BI);
+    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
+    if (a.m0 >= Mr) return;
+    const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));
+    const int x = blockIdx.x & 7, tpos = blockIdx.x >> 3;
+    const DhShare sh(tilesD, tilesM, grid_of_dh, x, true);
+    if (sh.slices < 2 || tpos >= sh.rem) return;
+    const TileId t = tile_of_vid(x * sh.per + sh.full_rounds * sh.wgs + tpos, tilesD, tilesM, a.gi > 0 ? a.gi : tilesD);
+    f32x16 acc[WI][WJ];
+#pragma unroll
+    for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ib][jb][v] = 0.f;
+    for (int slice = 0; slice < sh.slices; ++slice) {
+        const int wg = x + 8 * (slice * sh.rem + tpos);        // the workgroup of dh_kernel that computed this slice
+        const float* in = a.part + (int64_t)wg * (S::BI * S::BJ) + threadIdx.x;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+            for (int jb = 0; jb < WJ; ++jb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[ib][jb][v] += in[((ib * WJ + jb) * 16 + v) * S::NT];
+    }
+    dh_store<S>(a, t, M, acc);
 }
 
 // ------------------------------------------------------------------------------------------ dw
@@ -804,6 +894,7 @@ __global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
     const Lane<S> L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
     const bool vec = (a.V % 4) == 0;
+    const float bs = (a.beta && a.beta_scale) ? a.beta_scale[0] : 1.f;   // what the sum so far is multiplied by
 #pragma unroll
     for (int jb = 0; jb < WJ; ++jb) {
         const int64_t jd = (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
@@ -821,18 +912,18 @@ __global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
                     if (vec) {
                         float4 cur = make_float4(0.f, 0.f, 0.f, 0.f);
                         if (a.beta) cur = *(const float4*)p;
-                        *(float4*)p = make_float4(cur.x + o[0], cur.y + o[1], cur.z + o[2], cur.w + o[3]);
+                        *(float4*)p = make_float4(cur.x * bs + o[0], cur.y * bs + o[1], cur.z * bs + o[2], cur.w * bs + o[3]);
                     } else {
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
-                            if (i0 + r < a.V) p[r] = (a.beta ? p[r] : 0.f) + o[r];
+                            if (i0 + r < a.V) p[r] = (a.beta ? p[r] * bs : 0.f) + o[r];
                     }
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
                         if (i0 + r < a.V) {
                             float* p = a.dW + (i0 + r) * a.d + jd;
-                            *p = (a.beta ? *p : 0.f) + o[r];
+                            *p = (a.beta ? *p * bs : 0.f) + o[r];
                         }
                 }
             }
@@ -849,8 +940,8 @@ __global__ __launch_bounds__(256) void token_logit_kernel(const bf16_t* __restri
                                                           const int32_t* __restrict__ counts, float inv_temp,
                                                           float* __restrict__ zy, const float* __restrict__ ref_logp,
                                                           const int32_t* __restrict__ row_index,
-                                                          float* __restrict__ refz) {
-    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+                                                          float* __restrict__ refz, int64_t row0) {
+    const int64_t j = row0 + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (j >= counts[CNT_M]) return;
     const int lane = threadIdx.x & 63;
     const bf16x8* h = (const bf16x8*)(Hc + j * ldk);
@@ -900,8 +991,9 @@ __global__ __launch_bounds__(256) void cache_finish_kernel(bf16_t* __restrict__ 
                                                            const float* __restrict__ zy, const float* __restrict__ refz,
                                                            const float* __restrict__ lse_c, const float* __restrict__ rowg,
                                                            float inv_temp, const int32_t* __restrict__ counts,
-                                                           float* __restrict__ rowc, int32_t* __restrict__ dev_status) {
-    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+                                                           int64_t row0, float* __restrict__ rowc,
+                                                           int32_t* __restrict__ dev_status) {
+    const int64_t j = row0 + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int M = counts[CNT_M], Mr = counts[CNT_MR];
     if (j >= Mr) return;
@@ -916,7 +1008,7 @@ __global__ __launch_bounds__(256) void cache_finish_kernel(bf16_t* __restrict__ 
         c = -rowg[j] * inv_temp * __expf(-a);
         if (lane == 0) {
             const __bf16 r = (__bf16)(__expf(a) * expm1f(zy[j] - lse));   // exp(lse - r) (p_y - 1)
-            u[j * ldz + tokc[j]] = __builtin_bit_cast(bf16_t, r);
+            u[(j - row0) * ldz + tokc[j]] = __builtin_bit_cast(bf16_t, r);
         }
     }
     if (lane == 0) rowc[j] = c;
@@ -935,16 +1027,27 @@ __global__ __launch_bounds__(256) void cache_finish_kernel(bf16_t* __restrict__ 
     }
 }
 
-template <class K>
-void allow_lds(K kernel, int bytes) {
-    (void)hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+// Lets `kernel` use `bytes` of dynamic LDS: once per kernel and device (the attribute belongs to the
+// device's copy of the function), not once per launch.  One static bit mask per kernel.
+template <auto kernel>
+void allow_lds(int bytes) {
+    static std::atomic<uint64_t> done{0};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return;
+    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess)
+        done.fetch_or(bit, std::memory_order_release);
 }
 
 // waves per workgroup: 4 (2 x 2 of 128 x 128), 8 (2 x 4 of 128 x 64) or 16; 0 = each kernel's own
 // default: 8 for the logits kernels and dW, 4 for dHidden (measured: its long K loop gains more from
 // the 4-wave tile's third fewer LDS reads than it loses in latency hiding)
-int g_waves = 0;
-static int waves_for(int own_default) { return g_waves ? g_waves : own_default; }
+std::atomic<int> g_waves{0};
+static int waves_for(int own_default) {
+    const int w = g_waves.load();
+    return w ? w : own_default;
+}
 
 using G4 = Geo<2, 2, 4, 4>;        // 256 x 256, 4 waves
 using G4_I128 = Geo<2, 2, 2, 4>;   // 128 x 256
@@ -959,31 +1062,39 @@ using G16_J128 = Geo<4, 4, 2, 1>;  // 256 x 128
 template <class S>
 void launch_fwd_lse_t(const FwdArgs& a, hipStream_t st) {
     if (a.zc) {
-        allow_lds(fwd_lse_kernel<S, true>, S::LDS_BYTES);
+        allow_lds<&fwd_lse_kernel<S, true>>(S::LDS_BYTES);
         fwd_lse_kernel<S, true><<<grid_for(a.tilesV, a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
     } else {
-        allow_lds(fwd_lse_kernel<S, false>, S::LDS_BYTES);
+        allow_lds<&fwd_lse_kernel<S, false>>(S::LDS_BYTES);
         fwd_lse_kernel<S, false><<<grid_for(a.tilesV, a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
     }
 }
 template <class S>
 void launch_dz_t(const DzArgs& a, hipStream_t st) {
-    allow_lds(dz_kernel<S>, S::LDS_BYTES);
+    allow_lds<&dz_kernel<S>>(S::LDS_BYTES);
     dz_kernel<S><<<grid_for(a.tilesV, a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
 }
 template <class S>
 void launch_dh_t(const DhArgs& a, hipStream_t st) {
-    allow_lds(dh_kernel<S>, S::LDS_BYTES);
-    dh_kernel<S><<<grid_for((int)(a.dpadR / S::BI), a.tilesM), S::NT, S::LDS_BYTES, st>>>(a);
+    allow_lds<&dh_kernel<S>>(S::LDS_BYTES);
+    const unsigned grid = grid_for((int)(a.dpadR / S::BI), a.tilesM);
+    DhArgs b = a;
+    // a cut last round needs 64 K floats of scratch per workgroup and whole XCD shares of workgroups
+    if (grid % 8 != 0 || grid < 16 || (size_t)grid * S::BI * S::BJ * 4 > a.part_bytes) b.part = nullptr;
+    dh_kernel<S><<<grid, S::NT, S::LDS_BYTES, st>>>(b);
+    if (b.part && !b.pace) dh_reduce_kernel<S><<<8 * (grid / 16), S::NT, 0, st>>>(b, (int)grid);
 }
 template <class S>
 void launch_dw_t(const DwArgs& a, hipStream_t st) {
-    allow_lds(dw_kernel<S>, S::LDS_BYTES);
+    allow_lds<&dw_kernel<S>>(S::LDS_BYTES);
     dw_kernel<S><<<grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ)), S::NT, S::LDS_BYTES, st>>>(a);
 }
 
 }  // namespace
 
+// one 256 x 256 fp32 tile per workgroup of a launch of 256 (the compute units of an MI355X); a launch with
+// more workgroups than that does not cut its last round
+size_t dh_part_bytes() { return (size_t)256 * 256 * 256 * 4; }
 void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 8 || n == 16) ? n : 0; }
 void set_cu_count(int n) { g_num_cu = n >= 8 ? n : 8; }
 
@@ -992,10 +1103,11 @@ void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
     const int w = waves_for(8);
     if (w == 16) launch_fwd_lse_t<G16>(a, st); else if (w == 8) launch_fwd_lse_t<G8>(a, st); else launch_fwd_lse_t<G4>(a, st);
 }
-void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st) {
+void launch_token_logit(const FwdArgs& a, int64_t row0, int64_t rows_max, hipStream_t st) {
+    if (rows_max <= 0) return;
     token_logit_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(a.Hc, a.Wvd, a.ldk, a.dpad, a.tokc, a.counts,
                                                                      a.inv_temp, a.zy, a.ref_logp, a.row_index,
-                                                                     a.zc ? a.refz : nullptr);
+                                                                     a.zc ? a.refz : nullptr, row0);
 }
 int fwd_slots_per_tile() { return 2; }
 
@@ -1009,9 +1121,11 @@ void launch_dz(const DzArgs& a, hipStream_t st) {
 
 void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc,
                          const float* zy, const float* refz, const float* lse_c, const float* rowg, float inv_temp,
-                         const int32_t* counts, int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st) {
+                         const int32_t* counts, int64_t row0, int64_t rows_max, float* rowc, int32_t* dev_status,
+                         hipStream_t st) {
+    if (rows_max <= 0) return;
     cache_finish_kernel<<<(unsigned)((rows_max + 3) / 4), 256, 0, st>>>(u, ldz, Hc, ldk, tokc, zy, refz, lse_c, rowg,
-                                                                        inv_temp, counts, rowc, dev_status);
+                                                                        inv_temp, counts, row0, rowc, dev_status);
 }
 void launch_dh(const DhArgs& a, hipStream_t st) {
     const int w = waves_for(4);

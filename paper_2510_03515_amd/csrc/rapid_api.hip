@@ -4,9 +4,11 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <cmath>
 
 #include "rapid_internal.h"
+#include "rapid_tuning.h"
 
 namespace rapid {
 
@@ -22,12 +24,15 @@ void set_error(const char* fmt, ...) {
 namespace {
 
 
-int g_gi_fwd = 4, g_gi_dh = 0, g_gi_dw = 2;   // L2 blocking of the tile order (tuning keys 10..12)
-int g_blocked_wdv = 1;                        // dH reads W from a tile-blocked copy (tuning key 14)
-int g_probe_cus = 256;                        // compute units of the current device
-int g_cached_step_tiles = 256;                // row tiles per dHidden / dW launch with the cache (tuning key 15; 0 = all rows)
-int g_pace_every = 0;                         // K steps between meetings of the dHidden workgroups (tuning key 16; 0 = off)
-int g_fwd_block_tiles = 64;                   // row tiles per launch of the two logits kernels (tuning key 13)
+// tuning switches (rapid_tuning.h): one atomic word each, so that a change made by another thread is
+// seen whole
+std::atomic<int> g_gi_fwd{4}, g_gi_dh{0}, g_gi_dw{2};   // L2 blocking of the tile order (tuning keys 10..12)
+std::atomic<int> g_blocked_wdv{1};            // dH reads W from a tile-blocked copy (tuning key 14)
+std::atomic<int> g_probe_cus{256};            // compute units of the current device
+std::atomic<int> g_cached_step_tiles{256};    // row tiles per dHidden / dW launch with the cache (tuning key 15; 0 = all rows)
+std::atomic<int> g_pace_every{0};             // K steps between meetings of the dHidden workgroups (tuning key 16; 0 = off)
+std::atomic<int> g_fwd_block_tiles{64};       // row tiles per launch of the two logits kernels (tuning key 13)
+std::atomic<int> g_dh_split{1};               // dHidden cuts the tiles of a partly filled last round along the contraction (tuning key 17)
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
 enum Stage { ST_COMPACT = 0, ST_PACK, ST_FWD_LSE, ST_MERGE, ST_ESTIMATOR, ST_ZERO, ST_DZ, ST_DZ_T, ST_DH, ST_DW,
@@ -67,11 +72,17 @@ struct Plan {
     int64_t ldk, ldv;   // leading dimensions of the [*, dpad] and [*, Vpad] operands
     int P;              // log-sum-exp partial slots per row
     int64_t Mc;         // rows per backward chunk (f32: also per forward chunk)
+    // Cached backward: the compact rows come in Cmax regions of Rcap rows, one per chunk of whole groups
+    // (Mmax_pad = Cmax * Rcap then); the cache and the log-sum-exp partials hold one region.  Cmax = 0 otherwise.
+    int64_t Rcap;
+    int Cmax;
+    int64_t ld_part;    // columns of the log-sum-exp partials
+    int64_t rms_blocks; // row blocks of the final norm's dweight partial sums
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
-    size_t counts, pace, seq_len, cu, row_index, tokc, seqc, zy, refz, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, g, g64, tsum, tmax,
-        Hc, Wvd, Wdv, WdvB, part_max, part_sum, dw32, chunk0;
+    size_t counts, pace, seq_len, cu, row_index, tokc, seqc, zy, refz, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, adv64, g, g64, tsum, tmax,
+        Hc, Wvd, Wdv, WdvB, dh_part, part_max, part_sum, dw32, chunk0, tab, gen_row0, gen_chunk, gseen, lam_state, lam_chunk, beta_scale;
 };
 
 size_t take(size_t& cur, size_t bytes) {
@@ -80,8 +91,10 @@ size_t take(size_t& cur, size_t bytes) {
     return at;
 }
 
-// lays the workspace out; chunk sizing is done by the caller through `avail`
-bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
+// lays the workspace out; chunk sizing is done by the caller through `avail`.  Cmax > 0: the layout of the
+// cached backward with Cmax regions of Rcap rows (bf16, RAPID_OP_IW_PG_FWD_BWD only).
+bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype, int64_t Rcap = 0,
+               int Cmax = 0) {
     memset(&p, 0, sizeof(p));
     if (N <= 0 || T <= 0 || d <= 0 || V <= 0) return false;
     if (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) return false;
@@ -92,7 +105,10 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     if (op == RAPID_OP_IW_PG_FWD_BWD && K <= 0) return false;
     p.op = op; p.dtype = dtype; p.N = N; p.T = T; p.d = d; p.V = V; p.K = K;
     p.Mmax = N * T;
-    p.Mmax_pad = round_up(p.Mmax, ROW_TILE);
+    p.Mmax_pad = Cmax > 0 ? (int64_t)Cmax * Rcap : round_up(p.Mmax, ROW_TILE);
+    p.Rcap = Rcap; p.Cmax = Cmax;
+    p.ld_part = Cmax > 0 ? Rcap : p.Mmax_pad;
+    if (p.Mmax_pad > (int64_t)2100000000) return false;   // compact row indices are int32
     p.dpad = round_up(d, K_TILE);
     // dHidden / dW tile d by 256 when that pads by at most a sixth (full-size tiles beat the padding),
     // else by 128
@@ -116,8 +132,19 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     if (dtype == RAPID_DTYPE_BF16) p.inv_rms = take(cur, (size_t)p.Mmax_pad * 4);   // final-norm option
     if (bwd) {
         p.rowc = take(cur, (size_t)p.Mmax_pad * 4);
-        if (dtype == RAPID_DTYPE_BF16) p.rms_part = take(cur, (size_t)rmsnorm_dweight_blocks(p.Mmax_pad) * d * 4);
+        p.rms_blocks = Cmax > 0 ? (int64_t)Cmax * rmsnorm_dweight_blocks(Rcap) : rmsnorm_dweight_blocks(p.Mmax_pad);
+        if (dtype == RAPID_DTYPE_BF16) p.rms_part = take(cur, (size_t)p.rms_blocks * d * 4);
         p.rowg = take(cur, (size_t)p.Mmax_pad * 4);
+        p.adv64 = take(cur, (size_t)N * 8);
+        if (Cmax > 0) {
+            p.tab = take(cur, (size_t)Cmax * CH_WORDS * 4);
+            p.gen_row0 = take(cur, (size_t)N * 4);
+            p.gen_chunk = take(cur, (size_t)N * 4);
+            p.gseen = take(cur, (size_t)K * 4);
+            p.lam_state = take(cur, 2 * 8);
+            p.lam_chunk = take(cur, (size_t)Cmax * 8);
+            p.beta_scale = take(cur, 64);
+        }
         p.g64 = take(cur, (size_t)N * 8);
         p.tsum = take(cur, (size_t)N * 8);
         p.tmax = take(cur, (size_t)N * 8);
@@ -131,11 +158,12 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     if (dtype == RAPID_DTYPE_BF16) {
         p.Hc = take(cur, (size_t)p.Mmax_pad * p.ldk * 2);
         p.Wvd = take(cur, (size_t)p.Vpad * p.ldk * 2);
-        p.part_max = take(cur, (size_t)p.P * p.Mmax_pad * 4);
-        p.part_sum = take(cur, (size_t)p.P * p.Mmax_pad * 4);
+        p.part_max = take(cur, (size_t)p.P * p.ld_part * 4);
+        p.part_sum = take(cur, (size_t)p.P * p.ld_part * 4);
         if (bwd) {
             p.Wdv = take(cur, (size_t)p.dpadR * p.ldv * 2);
             p.WdvB = take(cur, (size_t)p.dpadR * p.Vpad * 2);
+            p.dh_part = take(cur, dh_part_bytes());
             p.per_row = (size_t)p.ldv * 2;   // the dz chunk
         }
     } else {
@@ -149,6 +177,7 @@ void size_chunks(Plan& p, int64_t Mc) {
     Mc = Mc / ROW_TILE * ROW_TILE;
     if (Mc < ROW_TILE) Mc = ROW_TILE;
     if (Mc > p.Mmax_pad) Mc = p.Mmax_pad;
+    if (p.Cmax > 0) Mc = p.Rcap;   // the cache holds one region
     p.Mc = Mc;
     size_t cur = p.fixed;
     if (p.per_row) {
@@ -168,6 +197,23 @@ int64_t cache_rows(const Plan& p, int64_t max_tokens) {
 }
 
 int64_t recommended_chunk(const Plan& p) { return p.dtype == RAPID_DTYPE_BF16 ? 65536 : 4096; }
+
+// Chunks the cached backward may need when the cache holds Rcap rows and the batch at most `rows` tokens:
+// chunks are filled greedily with whole groups, so two consecutive chunks together hold more than Rcap
+// tokens (the first group of the second did not fit into the first), hence at most 2 floor(rows / Rcap) + 1.
+int cached_chunks(int64_t rows, int64_t Rcap) { return Rcap >= rows ? 1 : (int)(2 * (rows / Rcap) + 1); }
+
+constexpr int64_t CACHED_RCAP_RECOMMENDED = 65536;   // cache rows of the recommended workspace (if the batch has more)
+
+// workspace bytes of the cached backward with a cache of Rcap rows for a batch of at most `rows` tokens; 0 if invalid
+size_t cached_total(int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int64_t rows, int64_t Rcap, Plan* out = nullptr) {
+    Plan p;
+    if (Rcap > rows) Rcap = rows;
+    if (!make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, RAPID_DTYPE_BF16, Rcap, cached_chunks(rows, Rcap))) return 0;
+    size_chunks(p, Rcap);
+    if (out) *out = p;
+    return p.total + 1024;
+}
 
 // largest chunk that fits into `avail` bytes; 0 if even the minimum does not
 int64_t fit_chunk(const Plan& p, size_t avail) {
@@ -224,8 +270,71 @@ struct FwdIo {
     float rms_eps = 0.f;
 };
 
-// compaction, operand packing and the streaming log-softmax forward; leaves lse_c, tokc, seqc,
-// row_index, counts (and for bf16 Hc, Wvd) in the workspace for the backward
+// packs W as [Vpad, ldk] (the operand of the logits kernels)
+void pack_w_for_logits(const Plan& p, void* ws, const void* W, int w_layout, hipStream_t st) {
+    bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
+    if (w_layout == RAPID_W_VD)
+        launch_copy_pad_bf16((const bf16_t*)W, p.d, nullptr, Wvd, p.ldk, p.V, p.d, p.Vpad, p.dpad, nullptr, 0, st);
+    else
+        launch_transpose_pad_bf16((const bf16_t*)W, p.V, Wvd, p.ldk, p.d, p.V, p.dpad, p.Vpad, nullptr, 0, st);
+}
+
+// bf16 forward over the compact rows [base, base + rows) (rows a multiple of 256; `counts` holds the end of the
+// valid rows among them): token ids, packed hidden rows, sampled-token logits, streaming log-softmax, log-probs.
+// Leaves tokc, seqc, zy, lse_c (and Hc) of those rows in the workspace for the backward.  Wvd is packed already.
+void forward_rows_bf16(const Plan& p, void* ws, const FwdIo& io, const int32_t* counts, int64_t base, int64_t rows,
+                       hipStream_t st) {
+    int32_t* row_index = at<int32_t>(ws, p.row_index);
+    int32_t* tokc = at<int32_t>(ws, p.tokc);
+    bf16_t* Hc = at<bf16_t>(ws, p.Hc);
+    const float inv_temp = 1.0f / io.temperature;
+    {
+        Span sp(ST_COMPACT, st);
+        launch_gather_tokens(io.tokens, row_index, counts, base, rows, p.T, p.V, tokc, at<int32_t>(ws, p.seqc),
+                             io.dev_status, st);
+    }
+    {
+        Span sp(ST_PACK, st);
+        if (io.rms_weight)
+            launch_rmsnorm_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, (const bf16_t*)io.rms_weight, io.rms_eps,
+                                    Hc, p.ldk, base, rows, p.dpadR, counts, at<float>(ws, p.inv_rms), st);
+        else
+            launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc + base * p.ldk, p.ldk, rows, p.d, rows,
+                                 p.dpadR, counts, base, st);
+    }
+    FwdArgs a;
+    a.Wvd = at<bf16_t>(ws, p.Wvd); a.Hc = Hc; a.dpad = p.dpad; a.ldk = p.ldk;
+    a.tilesV = (int)(p.Vpad / 256); a.tilesM = (int)(rows / 256);
+    a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
+    a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
+    a.ld_part = p.ld_part; a.zy = at<float>(ws, p.zy); a.gi = g_gi_fwd;
+    a.zc = io.zc; a.ldz = p.ldv; a.dev_status = io.dev_status;
+    a.refz = at<float>(ws, p.refz); a.ref_logp = io.ref_logp; a.row_index = row_index;
+    a.part_row0 = base; a.zc_row0 = base;
+    {   // the sampled tokens' logits first: a storing forward uses them as its per-row reference
+        Span sp(ST_MERGE, st);
+        launch_token_logit(a, base, rows, st);
+    }
+    // The forward runs in blocks of token rows, all vocabulary tiles per block, so that a block's
+    // hidden rows stay in the memory-side cache while every XCD sweeps its share of W over them
+    // (one launch over all rows re-reads the hidden rows from HBM once per group of W panels).
+    const int64_t block_rows = (int64_t)g_fwd_block_tiles.load() * 256;
+    for (int64_t r0 = 0; r0 < rows; r0 += block_rows) {
+        const int64_t nrows = (rows - r0) < block_rows ? (rows - r0) : block_rows;
+        a.row0 = base + r0;
+        a.tilesM = (int)(nrows / 256);
+        Span sp(ST_FWD_LSE, st);
+        launch_fwd_lse(a, st);
+    }
+    {
+        Span sp(ST_MERGE, st);
+        launch_merge_lse(a.part_max, a.part_sum, p.P, a.ld_part, a.zy, row_index, counts, base, rows,
+                         at<float>(ws, p.lse_c), io.logp_out, io.lse_out, st);
+    }
+}
+
+// compaction, operand packing and the streaming log-softmax forward over the whole batch as one region;
+// leaves lse_c, tokc, seqc, row_index, counts (and for bf16 Hc, Wvd) in the workspace for the backward
 void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
     int32_t* counts = at<int32_t>(ws, p.counts);
     int32_t* row_index = at<int32_t>(ws, p.row_index);
@@ -237,57 +346,20 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
         Span sp(ST_COMPACT, st);
         launch_compaction(io.mask, p.N, p.T, at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), row_index, counts,
                           io.row_cap, io.dev_status, st);
-        launch_gather_tokens(io.tokens, row_index, counts, p.Mmax_pad, p.T, p.V, tokc, seqc, io.dev_status, st);
         launch_fill_f32(io.logp_out, p.Mmax, 0.f, st);
         if (io.lse_out) launch_fill_f32(io.lse_out, p.Mmax, 0.f, st);
     }
     if (p.dtype == RAPID_DTYPE_BF16) {
-        bf16_t* Hc = at<bf16_t>(ws, p.Hc);
-        bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
         {
             Span sp(ST_PACK, st);
-            if (io.rms_weight)
-                launch_rmsnorm_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, (const bf16_t*)io.rms_weight,
-                                        io.rms_eps, Hc, p.ldk, p.Mmax_pad, p.dpadR, counts, at<float>(ws, p.inv_rms), st);
-            else
-                launch_copy_pad_bf16((const bf16_t*)io.hidden, p.d, row_index, Hc, p.ldk, p.Mmax, p.d, p.Mmax_pad,
-                                     p.dpadR, counts, 0, st);
-            if (io.w_layout == RAPID_W_VD)
-                launch_copy_pad_bf16((const bf16_t*)io.W, p.d, nullptr, Wvd, p.ldk, p.V, p.d, p.Vpad, p.dpad,
-                                     nullptr, 0, st);
-            else
-                launch_transpose_pad_bf16((const bf16_t*)io.W, p.V, Wvd, p.ldk, p.d, p.V, p.dpad, p.Vpad, nullptr,
-                                          0, st);
+            pack_w_for_logits(p, ws, io.W, io.w_layout, st);
         }
-        FwdArgs a;
-        a.Wvd = Wvd; a.Hc = Hc; a.dpad = p.dpad; a.ldk = p.ldk;
-        a.tilesV = (int)(p.Vpad / 256); a.tilesM = (int)(p.Mmax_pad / 256);
-        a.V = p.V; a.inv_temp = inv_temp; a.tokc = tokc; a.counts = counts;
-        a.part_max = at<float>(ws, p.part_max); a.part_sum = at<float>(ws, p.part_sum);
-        a.ld_part = p.Mmax_pad; a.zy = at<float>(ws, p.zy); a.gi = g_gi_fwd;
-        a.zc = io.zc; a.ldz = p.ldv; a.dev_status = io.dev_status;
-        a.refz = at<float>(ws, p.refz); a.ref_logp = io.ref_logp; a.row_index = row_index;
-        {   // the sampled tokens' logits first: a storing forward uses them as its per-row reference
-            Span sp(ST_MERGE, st);
-            launch_token_logit(a, p.Mmax_pad, st);
-        }
-        // The forward runs in blocks of token rows, all vocabulary tiles per block, so that a block's
-        // hidden rows stay in the memory-side cache while every XCD sweeps its share of W over them
-        // (one launch over all rows re-reads the hidden rows from HBM once per group of W panels).
-        const int64_t block_rows = (int64_t)g_fwd_block_tiles * 256;
-        for (int64_t r0 = 0; r0 < p.Mmax_pad; r0 += block_rows) {
-            const int64_t rows = (p.Mmax_pad - r0) < block_rows ? (p.Mmax_pad - r0) : block_rows;
-            a.row0 = r0;
-            a.tilesM = (int)(rows / 256);
-            Span sp(ST_FWD_LSE, st);
-            launch_fwd_lse(a, st);
-        }
-        {
-            Span sp(ST_MERGE, st);
-            launch_merge_lse(a.part_max, a.part_sum, p.P, a.ld_part, a.zy, row_index, counts, p.Mmax_pad, lse_c,
-                             io.logp_out, io.lse_out, st);
-        }
+        forward_rows_bf16(p, ws, io, counts, 0, p.Mmax_pad, st);
     } else {
+        {
+            Span sp(ST_COMPACT, st);
+            launch_gather_tokens(io.tokens, row_index, counts, 0, p.Mmax_pad, p.T, p.V, tokc, seqc, io.dev_status, st);
+        }
         float* z = at<float>(ws, p.chunk0);
         Span sp(ST_F32, st);
         for (int64_t m0 = 0; m0 < p.Mmax; m0 += p.Mc) {
@@ -416,7 +488,7 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* o) {
 
 int rapid_set_tuning(int key, int value) {
     if (key >= 10 && key <= 12 && value >= 0 && value <= 1024) {
-        (key == 10 ? g_gi_fwd : key == 11 ? g_gi_dh : g_gi_dw) = (key != 11 && value == 0) ? 1 : value;
+        (key == 10 ? g_gi_fwd : key == 11 ? g_gi_dh : g_gi_dw).store((key != 11 && value == 0) ? 1 : value);
         return RAPID_OK;
     }
     if (key == 13 && value >= 1 && value <= (1 << 20)) {
@@ -433,6 +505,10 @@ int rapid_set_tuning(int key, int value) {
     }
     if (key == 14 && (value == 0 || value == 1)) {
         g_blocked_wdv = value;
+        return RAPID_OK;
+    }
+    if (key == 17 && (value == 0 || value == 1)) {
+        g_dh_split = value;
         return RAPID_OK;
     }
     if (key == 2 && (value == 0 || value == 4 || value == 8 || value == 16)) {
@@ -503,21 +579,25 @@ int rapid_profile_read(double* ms_by_stage, int64_t* spans_by_stage, int n_stage
     return RAPID_OK;
 }
 
+// cached backward, cache large enough for every token the batch may hold: one chunk
 size_t rapid_workspace_bytes_max_tokens(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype,
                                         int64_t max_tokens) {
     if (op != RAPID_OP_IW_PG_FWD_BWD_CACHED) return rapid_workspace_bytes(op, N, T, d, V, K, dtype);
-    Plan p;   // the chunk buffer holds every row that can hold a token
+    Plan p;
     if (max_tokens < 0 || dtype != RAPID_DTYPE_BF16 || !make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype))
         return 0;
-    size_chunks(p, cache_rows(p, max_tokens));
-    return p.total + 1024;
+    const int64_t rows = cache_rows(p, max_tokens);
+    return cached_total(N, T, d, V, K, rows, rows);
 }
 
 size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
     if (op == RAPID_OP_GROUP_ADVANTAGE) return 0;
-    if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) return rapid_workspace_bytes_max_tokens(op, N, T, d, V, K, dtype, 0);
-    if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
     Plan p;
+    if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) {   // a cache of the recommended number of rows, or of all rows if those are fewer
+        if (dtype != RAPID_DTYPE_BF16 || !make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype)) return 0;
+        return cached_total(N, T, d, V, K, p.Mmax_pad, CACHED_RCAP_RECOMMENDED);
+    }
+    if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
     if (!make_plan(p, op, N, T, d, V, K, dtype)) return 0;
     size_chunks(p, recommended_chunk(p));
     return p.total + 1024;
@@ -525,9 +605,12 @@ size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V,
 
 size_t rapid_workspace_min_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
     if (op == RAPID_OP_GROUP_ADVANTAGE) return 0;
-    if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) return rapid_workspace_bytes(op, N, T, d, V, K, dtype);
-    if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
     Plan p;
+    if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) {   // a cache of one row tile (every group must fit into it)
+        if (dtype != RAPID_DTYPE_BF16 || !make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype)) return 0;
+        return cached_total(N, T, d, V, K, p.Mmax_pad, ROW_TILE);
+    }
+    if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
     if (!make_plan(p, op, N, T, d, V, K, dtype)) return 0;
     size_chunks(p, ROW_TILE);
     return p.total + 1024;
@@ -591,8 +674,8 @@ int rapid_group_advantage(const float* rewards, const int32_t* group_ids, const 
     }
     int rc = check_arch();
     if (rc) return rc;
-    launch_group_advantage(rewards, group_ids, seq_logratio, N, K, eta, baseline_mode, adv_out, weight_out,
-                           group_mean_out, group_std_out, group_size_out, dev_status, (hipStream_t)stream);
+    launch_group_advantage(rewards, group_ids, seq_logratio, nullptr, N, K, eta, baseline_mode, adv_out, nullptr, weight_out,
+                           group_mean_out, group_std_out, group_size_out, nullptr, dev_status, (hipStream_t)stream);
     return check_launch("rapid_group_advantage");
 }
 
@@ -638,12 +721,6 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         set_error("dhidden_out and dW_out must be 16-byte aligned");
         return RAPID_ERR_SHAPE;
     }
-    const int64_t Mfit = fit_chunk(p, workspace_bytes);
-    if (Mfit < ROW_TILE) {
-        set_error("workspace of %zu bytes is below the minimum %zu", workspace_bytes,
-                  rapid_workspace_min_bytes(RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype));
-        return RAPID_ERR_WORKSPACE;
-    }
     const bool cached = o.logits_cache == 1;
     if (o.max_tokens < 0) {
         set_error("max_tokens must be >= 0");
@@ -651,12 +728,38 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     }
     rc = validate_rms(o.rms_weight, o.rms_eps, dtype);
     if (rc) return rc;
-    if (cached && Mfit < cache_rows(p, o.max_tokens)) {
-        set_error("workspace of %zu bytes is below the %zu the logits cache needs", workspace_bytes,
-                  rapid_workspace_bytes_max_tokens(RAPID_OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dtype, o.max_tokens));
-        return RAPID_ERR_WORKSPACE;
+    if (cached) {
+        // The cache holds every token if the workspace allows (one chunk: groups may lie anywhere in the
+        // batch); otherwise as many rows as fit, and the batch is worked through in chunks of whole groups.
+        const int64_t rows = cache_rows(p, o.max_tokens);
+        size_t need = cached_total(N, T, d, V, K, rows, rows, &p);
+        if (need == 0 || need > workspace_bytes) {
+            int64_t lo = 1, hi = rows / ROW_TILE - 1, best = 0;     // cache rows in row tiles
+            while (lo <= hi) {
+                const int64_t mid = (lo + hi) / 2;
+                need = cached_total(N, T, d, V, K, rows, mid * ROW_TILE);
+                if (need != 0 && need <= workspace_bytes) { best = mid; lo = mid + 1; } else { hi = mid - 1; }
+            }
+            // the size is not monotone everywhere (the number of regions steps down as the cache grows)
+            while (best > 0 && ((need = cached_total(N, T, d, V, K, rows, best * ROW_TILE, &p)) == 0 || need > workspace_bytes))
+                --best;
+            if (best == 0) {
+                set_error("workspace of %zu bytes is below the %zu the logits cache needs at least", workspace_bytes,
+                          rapid_workspace_min_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dtype));
+                return RAPID_ERR_WORKSPACE;
+            }
+        }
+    } else {
+        const int64_t Mfit = fit_chunk(p, workspace_bytes);
+        if (Mfit < ROW_TILE) {
+            set_error("workspace of %zu bytes is below the minimum %zu", workspace_bytes,
+                      rapid_workspace_min_bytes(RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype));
+            return RAPID_ERR_WORKSPACE;
+        }
+        // the fp32 path launches one block row per 16 chunk rows along the second grid dimension: its chunk
+        // stays at the recommended size however large the workspace is
+        size_chunks(p, (dtype == RAPID_DTYPE_F32 && Mfit > recommended_chunk(p)) ? recommended_chunk(p) : Mfit);
     }
-    size_chunks(p, Mfit);
     rc = check_arch();
     if (rc) return rc;
 
@@ -671,40 +774,166 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     double* s64 = at<double>(ws, p.s64);
     float* s32 = seq_logratio_out ? seq_logratio_out : at<float>(ws, p.s32);
     float* adv = adv_out ? adv_out : at<float>(ws, p.adv);
+    double* adv64 = at<double>(ws, p.adv64);
     float* g = at<float>(ws, p.g);
     float* rowg = at<float>(ws, p.rowg);
     const float inv_temp = 1.0f / o.temperature;
+    const int elem = dtype == RAPID_DTYPE_BF16 ? 2 : 4;
+    // token-level outer weight: per generation the sum and the log-maximum of its tokens' ratios
+    const bool per_token = o.ratio_level == 1 && !o.coef_override;
+    double* tsum = per_token ? at<double>(ws, p.tsum) : nullptr;
+    double* tmax = per_token ? at<double>(ws, p.tmax) : nullptr;
+    CoefArgs ca;
+    memset(&ca, 0, sizeof(ca));
+    ca.s64 = s64; ca.adv = adv; ca.adv64 = adv64; ca.coef_override = o.coef_override; ca.N = N; ca.eta = o.eta;
+    ca.coef_mode = o.coef_mode; ca.loss_scale = o.loss_scale; ca.normalized = o.normalized_grads;
+    ca.tsum = tsum; ca.tmax = tmax; ca.counts = counts; ca.g = g; ca.g64 = at<double>(ws, p.g64);
+    ca.loss_out = loss_out; ca.diag = diag_out; ca.write_g = 1;
 
-    // forward: current-policy log-probs of the sampled tokens
     FwdIo io{hidden, W, tokens, mask, o.w_layout, o.temperature, logp_cur, nullptr, dev_status};
-    if (cached) {   // the chunk buffer holds the ratios of every row, up to the p.Mc rows it was sized for
-        io.zc = at<bf16_t>(ws, p.chunk0);
-        io.row_cap = p.Mc;
-        io.ref_logp = logp_behav;
-    }
     io.rms_weight = o.rms_weight;
     io.rms_eps = o.rms_eps;
+
+    if (cached) {
+        // ---- cached backward: chunk after chunk of whole groups; forward with store, estimator, dHidden, dW
+        bf16_t* Hc = at<bf16_t>(ws, p.Hc);
+        bf16_t* cache = at<bf16_t>(ws, p.chunk0);
+        int32_t* tab = at<int32_t>(ws, p.tab);
+        int32_t* gen_chunk = at<int32_t>(ws, p.gen_chunk);
+        double* lam_state = at<double>(ws, p.lam_state);
+        double* lam_chunk = at<double>(ws, p.lam_chunk);
+        float* beta_scale = at<float>(ws, p.beta_scale);
+        // a normalised gradient that is added to the caller's dW goes through a buffer of its own: the
+        // running rescaling of the sum must not touch what the caller had in dW
+        const bool dw_staged = o.dw_dtype == RAPID_DTYPE_BF16 || (o.accumulate_dw && o.normalized_grads && p.Cmax > 1);
+        float* dW32 = dw_staged ? at<float>(ws, p.dw32) : (float*)dW_out;
+        const bool dw_adds_to_caller = o.accumulate_dw && !dw_staged;
+        io.zc = cache;
+        io.ref_logp = logp_behav;
+        {
+            Span sp(ST_COMPACT, st);
+            launch_compaction_chunked(mask, group_ids, N, T, K, p.Rcap, p.Cmax, at<int32_t>(ws, p.seq_len),
+                                      at<int32_t>(ws, p.cu), tab, at<int32_t>(ws, p.gen_row0), gen_chunk,
+                                      at<int32_t>(ws, p.gseen), row_index, counts, dev_status, st);
+            launch_fill_f32(logp_cur, p.Mmax, 0.f, st);
+            launch_fill_f64(lam_state, 1, -INFINITY, st);
+        }
+        const bool blocked_wdv = g_blocked_wdv.load() != 0;
+        {
+            Span sp(ST_PACK, st);
+            pack_w_for_logits(p, ws, W, o.w_layout, st);
+            bf16_t* Wdv = at<bf16_t>(ws, p.Wdv);
+            if (o.w_layout == RAPID_W_DV)
+                launch_copy_pad_bf16((const bf16_t*)W, p.V, nullptr, Wdv, p.ldv, p.d, p.V, p.dpadR, p.Vpad, nullptr, 0, st);
+            else
+                launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.ldv, p.V, p.d, p.Vpad, p.dpadR, nullptr, 0, st);
+            if (blocked_wdv)
+                launch_block_rows_bf16(Wdv, p.ldv, at<bf16_t>(ws, p.WdvB), p.dpadR, p.Vpad, p.dpadR % 256 == 0 ? 256 : 128, st);
+        }
+        {
+            Span sp(ST_ZERO, st);
+            launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, st);
+        }
+        const int cst = g_cached_step_tiles.load();
+        const int64_t cstep = cst > 0 ? (int64_t)cst * ROW_TILE : p.Rcap;
+        const int pace_every = g_pace_every.load();
+        for (int c = 0; c < p.Cmax; ++c) {
+            const int64_t base = (int64_t)c * p.Rcap;
+            const int32_t* cnt = tab + (int64_t)c * CH_WORDS;     // this chunk's row counters
+            const int32_t* gen_range = cnt + CH_G0;
+            forward_rows_bf16(p, ws, io, cnt, base, p.Rcap, st);
+            {
+                Span sp(ST_ESTIMATOR, st);
+                launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, o.eta, o.coef_mode == 1,
+                                    tsum, tmax, gen_range, dev_status, st);
+                launch_group_advantage(rewards, group_ids, nullptr, logp_behav ? s64 : nullptr, N, K, o.eta, o.baseline_mode,
+                                       adv, adv64, nullptr, nullptr, nullptr, nullptr, gen_range, dev_status, st);
+                CoefArgs cc = ca;
+                cc.gen_range = gen_range; cc.lam_state = lam_state; cc.lam_chunk = lam_chunk + c; cc.beta_out = beta_scale;
+                launch_coefficients(cc, st);
+                launch_row_coefficients(g, ca.g64, seqc, row_index, cnt, logp_cur, logp_behav, per_token, o.eta,
+                                        o.coef_mode == 1, base, p.Rcap, rowg, st);
+            }
+            {   // row factors, the sampled tokens' elements, hidden rows scaled by the factors
+                Span sp(ST_DZ, st);
+                launch_cache_finish(cache, p.ldv, Hc, p.ldk, tokc, at<float>(ws, p.zy), at<float>(ws, p.refz), lse_c, rowg,
+                                    inv_temp, cnt, base, p.Rcap, at<float>(ws, p.rowc), dev_status, st);
+            }
+            int piece = 0;
+            for (int64_t r0 = 0; r0 < p.Rcap; r0 += cstep, ++piece) {
+                const int64_t rows = (p.Rcap - r0) < cstep ? (p.Rcap - r0) : cstep;
+                bf16_t* dz = cache + r0 * p.ldv;
+                DhArgs ha;
+                ha.Wdv = at<bf16_t>(ws, p.Wdv); ha.WdvB = blocked_wdv ? at<bf16_t>(ws, p.WdvB) : nullptr; ha.dz = dz;
+                ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
+                ha.tilesM = (int)(rows / 256); ha.m0 = base + r0; ha.row_index = row_index; ha.counts = cnt;
+                ha.rowc = at<float>(ws, p.rowc);
+                ha.pace = pace_every > 0 ? at<unsigned>(ws, p.pace) : nullptr; ha.pace_every = pace_every;
+                if (ha.pace) launch_fill_f32((float*)ha.pace, 64, 0.f, st);
+                ha.dhidden = (bf16_t*)dhidden_out; ha.gi = g_gi_dh;
+                ha.part = g_dh_split.load() ? at<float>(ws, p.dh_part) : nullptr; ha.part_bytes = dh_part_bytes();
+                {
+                    Span sp(ST_DH, st);
+                    launch_dh(ha, st);
+                }
+                DwArgs wa;
+                wa.dz = dz; wa.Hc = Hc + (base + r0) * p.ldk; wa.Mc = rows; wa.ldz = p.ldv; wa.ldH = p.ldk;
+                wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = base + r0; wa.counts = cnt;
+                wa.dW = dW32; wa.w_layout = o.w_layout; wa.gi = g_gi_dw;
+                wa.beta = (c > 0 || piece > 0 || dw_adds_to_caller) ? 1 : 0;
+                // the sum over the earlier chunks is brought to this chunk's scale, once, by its first piece
+                wa.beta_scale = (c > 0 && piece == 0 && o.normalized_grads && !dw_adds_to_caller) ? beta_scale : nullptr;
+                {
+                    Span sp(ST_DW, st);
+                    launch_dw(wa, st);
+                }
+            }
+        }
+        {   // loss and diagnostics of the whole batch (every generation's ratio and advantage is known now)
+            Span sp(ST_ESTIMATOR, st);
+            CoefArgs cf = ca;
+            cf.write_g = 0;
+            launch_coefficients(cf, st);
+        }
+        if (o.normalized_grads && p.Cmax > 1) {   // rows of earlier chunks: from their chunk's scale to the final one
+            Span sp(ST_ZERO, st);
+            launch_rescale_rows(dhidden_out, mask, N, T, d, gen_chunk, lam_chunk, lam_state, st);
+        }
+        if (o.rms_weight) {   // dhidden holds dL/dh of the normalised state: on to dL/dweight and dL/dx
+            Span sp(ST_ZERO, st);
+            float* part = o.drms_weight_out ? at<float>(ws, p.rms_part) : nullptr;
+            if (part) launch_fill_f32(part, p.rms_blocks * d, 0.f, st);
+            const int64_t blocks_per_region = rmsnorm_dweight_blocks(p.Rcap);
+            for (int c = 0; c < p.Cmax; ++c)
+                launch_rmsnorm_backward((const bf16_t*)hidden, (bf16_t*)dhidden_out, d, (const bf16_t*)o.rms_weight, row_index,
+                                        tab + (int64_t)c * CH_WORDS, at<float>(ws, p.inv_rms), (int64_t)c * p.Rcap, p.Rcap,
+                                        part ? part + (int64_t)c * blocks_per_region * d : nullptr, st);
+            if (part) launch_rmsnorm_dweight_reduce(part, d, p.rms_blocks, o.drms_weight_out, st);
+        }
+        if (dw_staged) {
+            Span sp(ST_CONVERT, st);
+            if (o.dw_dtype == RAPID_DTYPE_BF16) launch_f32_to_bf16(dW32, (bf16_t*)dW_out, d * V, st);
+            else launch_f32_add(dW32, (float*)dW_out, d * V, st);
+        }
+        return check_launch("rapid_iw_pg_loss_fwd_bwd");
+    }
+
+    // ---- the backward that regenerates the logits (and the fp32 path): forward over the whole batch first
     run_forward(p, ws, io, st);
 
     // generation-level log ratios, clipped-weight group baseline, coefficients and loss
     {
         Span sp(ST_ESTIMATOR, st);
-        // token-level outer weight: per generation the sum and the log-maximum of its tokens' ratios
-        const bool per_token = o.ratio_level == 1 && !o.coef_override;
-        double* tsum = per_token ? at<double>(ws, p.tsum) : nullptr;
-        double* tmax = per_token ? at<double>(ws, p.tmax) : nullptr;
         launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, o.eta, o.coef_mode == 1,
-                            tsum, tmax, dev_status, st);
-        launch_group_advantage(rewards, group_ids, s32, N, K, o.eta, o.baseline_mode, adv, nullptr, nullptr,
-                               nullptr, nullptr, dev_status, st);
-        launch_coefficients(s64, adv, o.coef_override, N, o.eta, o.coef_mode, o.loss_scale, o.normalized_grads,
-                            tsum, tmax, counts, g, at<double>(ws, p.g64), loss_out, diag_out, st);
-        launch_row_coefficients(g, at<double>(ws, p.g64), seqc, row_index, counts, logp_cur, logp_behav, per_token,
-                                o.eta, o.coef_mode == 1, p.Mmax_pad, rowg, st);
+                            tsum, tmax, nullptr, dev_status, st);
+        launch_group_advantage(rewards, group_ids, nullptr, logp_behav ? s64 : nullptr, N, K, o.eta, o.baseline_mode, adv,
+                               adv64, nullptr, nullptr, nullptr, nullptr, nullptr, dev_status, st);
+        launch_coefficients(ca, st);
+        launch_row_coefficients(g, ca.g64, seqc, row_index, counts, logp_cur, logp_behav, per_token, o.eta,
+                                o.coef_mode == 1, 0, p.Mmax_pad, rowg, st);
     }
 
     // backward, in row chunks
-    const int elem = dtype == RAPID_DTYPE_BF16 ? 2 : 4;
     {
         Span sp(ST_ZERO, st);
         launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, st);
@@ -716,6 +945,7 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         bf16_t* Hc = at<bf16_t>(ws, p.Hc);
         bf16_t* Wvd = at<bf16_t>(ws, p.Wvd);
         bf16_t* Wdv = at<bf16_t>(ws, p.Wdv);
+        const bool blocked_wdv = g_blocked_wdv.load() != 0;
         {
             Span sp(ST_PACK, st);
             if (o.w_layout == RAPID_W_DV)
@@ -724,31 +954,22 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             else
                 launch_transpose_pad_bf16((const bf16_t*)W, p.d, Wdv, p.ldv, p.V, p.d, p.Vpad, p.dpadR, nullptr,
                                           0, st);
-            if (g_blocked_wdv)
+            if (blocked_wdv)
                 launch_block_rows_bf16(Wdv, p.ldv, at<bf16_t>(ws, p.WdvB), p.dpadR, p.Vpad, p.dpadR % 256 == 0 ? 256 : 128, st);
         }
-        // With the cache the chunk buffer holds every row's ratios p_v / p_y; one small pass makes
-        // them the backward's operands (row factors, the sampled tokens' elements, scaled hidden
-        // rows) and the backward walks the buffer in blocks.
-        if (cached) {
-            Span sp(ST_DZ, st);
-            launch_cache_finish(at<bf16_t>(ws, p.chunk0), p.ldv, Hc, p.ldk, tokc, at<float>(ws, p.zy), at<float>(ws, p.refz), lse_c,
-                                rowg, inv_temp, counts, p.Mmax_pad, at<float>(ws, p.rowc), dev_status, st);
-        }
-        const int64_t cstep = g_cached_step_tiles > 0 ? (int64_t)g_cached_step_tiles * ROW_TILE : p.Mc;
-        const int64_t step = cached ? (cstep < p.Mc ? cstep : p.Mc) : p.Mc;
+        const int64_t step = p.Mc;
         int chunk = 0;
         for (int64_t m0 = 0; m0 < p.Mmax_pad; m0 += step, ++chunk) {
             const int64_t rows = (p.Mmax_pad - m0) < step ? (p.Mmax_pad - m0) : step;   // multiple of 256
-            bf16_t* dz = at<bf16_t>(ws, p.chunk0) + (cached ? m0 * p.ldv : 0);
+            bf16_t* dz = at<bf16_t>(ws, p.chunk0);
             DzArgs za;
             za.Wvd = Wvd; za.Hc = Hc + m0 * p.ldk; za.dpad = p.dpad; za.ldk = p.ldk; za.ldz = p.ldv;
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
             za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
             za.tokc = tokc; za.lse_c = lse_c; za.rowg = rowg; za.counts = counts; za.dz = dz; za.gi = g_gi_fwd;
-            if (!cached) {
+            {
                 // like the forward, in sub-blocks of rows whose hidden rows stay in the memory-side cache
-                const int64_t sub = (int64_t)g_fwd_block_tiles * 256;
+                const int64_t sub = (int64_t)g_fwd_block_tiles.load() * 256;
                 for (int64_t r0 = 0; r0 < rows; r0 += sub) {
                     const int64_t nrows = (rows - r0) < sub ? (rows - r0) : sub;
                     DzArgs zs = za;
@@ -759,12 +980,14 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                 }
             }
             DhArgs ha;
-            ha.Wdv = Wdv; ha.WdvB = g_blocked_wdv ? at<bf16_t>(ws, p.WdvB) : nullptr; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
+            ha.Wdv = Wdv; ha.WdvB = blocked_wdv ? at<bf16_t>(ws, p.WdvB) : nullptr; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
             ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
-            ha.rowc = cached ? at<float>(ws, p.rowc) : nullptr;
-            ha.pace = g_pace_every > 0 ? at<unsigned>(ws, p.pace) : nullptr; ha.pace_every = g_pace_every;
+            ha.rowc = nullptr;
+            const int pace_every = g_pace_every.load();
+            ha.pace = pace_every > 0 ? at<unsigned>(ws, p.pace) : nullptr; ha.pace_every = pace_every;
             if (ha.pace) launch_fill_f32((float*)ha.pace, 64, 0.f, st);
             ha.dhidden = (bf16_t*)dhidden_out; ha.gi = g_gi_dh;
+            ha.part = g_dh_split.load() ? at<float>(ws, p.dh_part) : nullptr; ha.part_bytes = dh_part_bytes();
             {
                 Span sp(ST_DH, st);
                 launch_dh(ha, st);
@@ -780,9 +1003,11 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         }
         if (o.rms_weight) {   // dhidden holds dL/dh of the normalised state: on to dL/dweight and dL/dx
             Span sp(ST_ZERO, st);
-            launch_rmsnorm_backward((const bf16_t*)hidden, (bf16_t*)dhidden_out, d, (const bf16_t*)o.rms_weight,
-                                    row_index, counts, at<float>(ws, p.inv_rms), p.Mmax_pad, at<float>(ws, p.rms_part),
-                                    o.drms_weight_out, st);
+            float* part = o.drms_weight_out ? at<float>(ws, p.rms_part) : nullptr;
+            if (part) launch_fill_f32(part, p.rms_blocks * d, 0.f, st);
+            launch_rmsnorm_backward((const bf16_t*)hidden, (bf16_t*)dhidden_out, d, (const bf16_t*)o.rms_weight, row_index,
+                                    counts, at<float>(ws, p.inv_rms), 0, p.Mmax_pad, part, st);
+            if (part) launch_rmsnorm_dweight_reduce(part, d, p.rms_blocks, o.drms_weight_out, st);
         }
     } else {
         float* z = at<float>(ws, p.chunk0);

@@ -21,6 +21,16 @@ static inline int64_t padded_ld(int64_t x) { return ((x / 64) % 2 == 0) ? x + 64
 // device counters written by the compaction step: [0] = M (valid tokens), [1] = M rounded up to 256
 enum { CNT_M = 0, CNT_MR = 1, CNT_WORDS = 64 };
 
+// One entry of the chunk table of the cached backward (int32 x CH_WORDS per chunk): words 0 and 1 are
+// laid out like the counters above, so a kernel that is given `table + CH_WORDS * c` as its counters
+// works on chunk c alone.  Chunk c owns the compact rows [c * Rcap, c * Rcap + rows).
+enum { CH_M = 0,      // end of the chunk's valid rows (absolute compact row index)
+       CH_MR = 1,     // that end rounded up to a row tile
+       CH_G0 = 2,     // first generation of the chunk
+       CH_G1 = 3,     // one past its last generation
+       CH_ROWS = 4,   // valid rows
+       CH_WORDS = 8 };
+
 constexpr int ROW_TILE = 256;  // compact rows are padded to this
 constexpr int K_TILE = 64;     // contraction tile of the MFMA kernels (bf16 elements)
 
@@ -28,31 +38,70 @@ constexpr int K_TILE = 64;     // contraction tile of the MFMA kernels (bf16 ele
 // counts (optional): M and M rounded up to a row tile, both clipped to row_cap (sets RAPID_STATUS_TOKEN_BOUND)
 void launch_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_len, int32_t* cu_seqlen,
                        int32_t* row_index, int32_t* counts, int64_t row_cap, int32_t* dev_status, hipStream_t st);
+// Compaction for the cached backward: sequence lengths and their prefix sum as above, then the
+// generations are dealt to at most Cmax chunks of at most Rcap compact rows each, whole groups
+// (maximal runs of equal group id) at a time, in order, each chunk as full as it gets; chunk c's
+// rows start at compact row c * Rcap.  Writes the chunk table `tab` [Cmax][CH_WORDS], gen_row0 [N]
+// (compact row of each generation's first token, -1 for a generation that was left out),
+// gen_chunk [N], row_index [Cmax * Rcap] and counts[CNT_M] = the tokens that were placed.
+// Cmax == 1: one chunk takes every generation, groups may lie anywhere; tokens past Rcap are left
+// out (RAPID_STATUS_TOKEN_BOUND).  Cmax > 1: a group whose members are not adjacent, or whose tokens
+// exceed Rcap, sets RAPID_STATUS_GROUP_LAYOUT; more chunks than Cmax sets RAPID_STATUS_TOKEN_BOUND.
+// gseen [K] is scratch.
+void launch_compaction_chunked(const uint8_t* mask, const int32_t* group_ids, int64_t N, int64_t T, int64_t K,
+                               int64_t Rcap, int Cmax, int32_t* seq_len, int32_t* cu_seqlen, int32_t* tab,
+                               int32_t* gen_row0, int32_t* gen_chunk, int32_t* gseen, int32_t* row_index,
+                               int32_t* counts, int32_t* dev_status, hipStream_t st);
 void launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
-void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const int32_t* counts,
-                          int64_t Mmax_pad, int64_t T, int64_t V, int32_t* tokc, int32_t* seqc,
+// compact rows [row0, row0 + rows_max) (those below counts[CNT_MR])
+void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const int32_t* counts, int64_t row0,
+                          int64_t rows_max, int64_t T, int64_t V, int32_t* tokc, int32_t* seqc,
                           int32_t* dev_status, hipStream_t st);
-// lse/logp from per-slot partial (max, sumexp) and the gathered logit
+// lse/logp from per-slot partial (max, sumexp) and the gathered logit, compact rows [row0, row0 + rows_max);
+// the partials of row j sit at column j - row0
 void launch_merge_lse(const float* part_max, const float* part_sum, int P, int64_t ld_part,
-                      const float* zy, const int32_t* row_index, const int32_t* counts, int64_t Mmax_pad,
-                      float* lse_c, float* logp_out, float* lse_out, hipStream_t st);
+                      const float* zy, const int32_t* row_index, const int32_t* counts, int64_t row0,
+                      int64_t rows_max, float* lse_c, float* logp_out, float* lse_out, hipStream_t st);
+// The estimator kernels take `gen_range` (device, two words: first generation and one past the last; NULL =
+// all N): they then touch only those generations.
 // tsum/tmax (NULL or [N]): per generation, sum and log-maximum of its tokens' (clipped if clip_tokens) ratios
 void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N,
                          int64_t T, float* tok_logratio_out, double* s64, float* s32, float eta, int clip_tokens,
-                         double* tsum, double* tmax, int32_t* dev_status, hipStream_t st);
-void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, int64_t N,
-                            int64_t K, float eta, int baseline_mode, float* adv, float* weight,
-                            float* gmean, float* gstd, int32_t* gsize, int32_t* dev_status,
-                            hipStream_t st);
-// tsum/tmax given: token-level outer weight (g_n is then the generation's factor without a ratio)
-void launch_coefficients(const double* s64, const float* adv, const float* coef_override, int64_t N,
-                         float eta, int coef_mode, float loss_scale, int normalized, const double* tsum,
-                         const double* tmax, const int32_t* counts, float* g, double* g64, float* loss_out,
-                         rapid_iw_pg_diag* diag, hipStream_t st);
-// rowg[j] = dL/dlogp of compact row j (0 for padding rows): g of its generation, times its own ratio if per_token
+                         double* tsum, double* tmax, const int32_t* gen_range, int32_t* dev_status, hipStream_t st);
+// weights from s64 if given, else from s32, else 1; adv64 (NULL or [N]): the advantages before rounding to float
+void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, const double* s64,
+                            int64_t N, int64_t K, float eta, int baseline_mode, float* adv, double* adv64,
+                            float* weight, float* gmean, float* gstd, int32_t* gsize, const int32_t* gen_range,
+                            int32_t* dev_status, hipStream_t st);
+// tsum/tmax given: token-level outer weight (g_n is then the generation's factor without a ratio).
+// Three uses.  Whole batch (gen_range, lam_state NULL): coefficients, scale lambda, loss, diagnostics.
+// One chunk of the cached backward (gen_range and lam_state given): coefficients of the chunk's generations
+// only, scaled by exp(-Lambda) with Lambda = max(lam_state[0], the chunk's own lambda) (0 if not normalized);
+// writes Lambda back to lam_state[0] and to lam_chunk[0], and to beta_out[0] the factor
+// exp(old Lambda - new Lambda) that the gradient sums accumulated so far have to be multiplied by; no loss,
+// no diagnostics.  Closing pass (write_g = 0): loss and diagnostics of
+// the whole batch, no coefficient is written.
+struct CoefArgs {
+    const double* s64; const float* adv; const double* adv64; const float* coef_override; int64_t N;
+    float eta; int coef_mode; float loss_scale; int normalized;
+    const double* tsum; const double* tmax; const int32_t* counts;
+    float* g; double* g64; float* loss_out; rapid_iw_pg_diag* diag;
+    const int32_t* gen_range; double* lam_state; double* lam_chunk; float* beta_out; int write_g;
+};
+void launch_coefficients(const CoefArgs& a, hipStream_t st);
+// rowg[j] = dL/dlogp of compact row j in [row0, row0 + rows_max) (0 for padding rows): g of its generation,
+// times its own ratio if per_token
 void launch_row_coefficients(const float* g, const double* g64, const int32_t* seqc, const int32_t* row_index,
                              const int32_t* counts, const float* logp_cur, const float* logp_behav, int per_token,
-                             float eta, int clip_tokens, int64_t rows_max, float* rowg, hipStream_t st);
+                             float eta, int clip_tokens, int64_t row0, int64_t rows_max, float* rowg, hipStream_t st);
+// cached backward with normalized gradients: every valid dhidden row of generation n is multiplied by
+// exp(lam_chunk[gen_chunk[n]] - lam_state[0]) (the scale its chunk used against the final one)
+void launch_rescale_rows(void* dhidden, const uint8_t* mask, int64_t N, int64_t T, int64_t d, const int32_t* gen_chunk,
+                         const double* lam_chunk, const double* lam_state, hipStream_t st);
+void launch_fill_f64(double* p, int64_t n, double v, hipStream_t st);
+void launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st);
+// dst[i] += src[i]
+void launch_f32_add(const float* src, float* dst, int64_t n, hipStream_t st);
 void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, int64_t d, int elem_bytes,
                              hipStream_t st);
 void launch_f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t st);
@@ -72,17 +121,21 @@ void launch_transpose_pad_bf16(const bf16_t* src, int64_t ld_src, bf16_t* dst, i
                                hipStream_t st);
 
 // ---- rmsnorm.hip ------------------------------------------------------------------------------
-// dst row r (< counts[CNT_MR], grid covers Rpad) = bf16(src[row_index[r]] * weight / rms) for r < counts[CNT_M],
-// zero otherwise and in columns C .. Cpad; inv_rms[r] = 1 / sqrt(mean(x^2) + eps).  C % 8 == 0.
+// dst row r in [r0, r0 + Rpad) below counts[CNT_MR] = bf16(src[row_index[r]] * weight / rms) for r < counts[CNT_M],
+// zero otherwise and in columns C .. Cpad; inv_rms[r] = 1 / sqrt(mean(x^2) + eps).  C % 8 == 0.  dst and
+// inv_rms are indexed by compact row.
 void launch_rmsnorm_pad_bf16(const bf16_t* src, int64_t C, const int32_t* row_index, const bf16_t* weight, float eps,
-                             bf16_t* dst, int64_t ld_dst, int64_t Rpad, int64_t Cpad, const int32_t* counts,
+                             bf16_t* dst, int64_t ld_dst, int64_t r0, int64_t Rpad, int64_t Cpad, const int32_t* counts,
                              float* inv_rms, hipStream_t st);
-// dh [N*T, d] holds dL/dh at the valid positions: dweight (if not NULL) = dL/dweight via `part`
-// (rmsnorm_dweight_blocks(rows_max) x d floats), then dh becomes dL/dx in place
+// dh [N*T, d] holds dL/dh at the valid positions of the compact rows [row0, row0 + rows_max) below
+// counts[CNT_M]: if part != NULL, partial sums of dL/dweight over blocks of those rows go to
+// part [rmsnorm_dweight_blocks(rows_max)][d] (zeroed beforehand: a block without rows writes nothing); then dh
+// becomes dL/dx in place.  launch_rmsnorm_dweight_reduce sums nblk blocks of partial sums in order.
 int64_t rmsnorm_dweight_blocks(int64_t rows_max);
 void launch_rmsnorm_backward(const bf16_t* x, bf16_t* dh, int64_t d, const bf16_t* weight, const int32_t* row_index,
-                             const int32_t* counts, const float* inv_rms, int64_t rows_max, float* part,
-                             float* dweight, hipStream_t st);
+                             const int32_t* counts, const float* inv_rms, int64_t row0, int64_t rows_max, float* part,
+                             hipStream_t st);
+void launch_rmsnorm_dweight_reduce(const float* part, int64_t d, int64_t nblk, float* dweight, hipStream_t st);
 
 // ---- gemm_bf16.hip ----------------------------------------------------------------------------
 struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered logit
@@ -107,9 +160,12 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     const float* ref_logp;   // NULL, or [N*T] log-probs subtracted from zy to form refz
     const int32_t* row_index;
     int32_t* dev_status;  // may be NULL
+    int64_t part_row0 = 0;   // compact row whose partials sit in column 0 of part_max / part_sum
+    int64_t zc_row0 = 0;     // compact row stored in row 0 of zc
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
-void launch_token_logit(const FwdArgs& a, int64_t rows_max, hipStream_t st);   // zy (and refz) for all rows
+// zy (and refz) for the compact rows [row0, row0 + rows_max)
+void launch_token_logit(const FwdArgs& a, int64_t row0, int64_t rows_max, hipStream_t st);
 int fwd_slots_per_tile();
 
 struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, bf16 [Mc, Vpad]
@@ -129,11 +185,13 @@ struct DzArgs {           // logits tile -> dz = g (onehot - p) / temperature, b
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_dz(const DzArgs& a, hipStream_t st);
-// turns the ratios a storing forward left in u [rows_max, ldz] into the backward's operands: the
-// sampled token's element of each row, the row factors rowc [rows_max], and Hc scaled by them in place
+// turns the ratios a storing forward left in u [rows_max, ldz] (row 0 = compact row row0) into the
+// backward's operands: the sampled token's element of each row, the row factors rowc, and Hc scaled by
+// them in place (Hc, tokc, zy, refz, lse_c, rowg, rowc are indexed by compact row)
 void launch_cache_finish(bf16_t* u, int64_t ldz, bf16_t* Hc, int64_t ldk, const int32_t* tokc,
                          const float* zy, const float* refz, const float* lse_c, const float* rowg, float inv_temp,
-                         const int32_t* counts, int64_t rows_max, float* rowc, int32_t* dev_status, hipStream_t st);
+                         const int32_t* counts, int64_t row0, int64_t rows_max, float* rowc, int32_t* dev_status,
+                         hipStream_t st);
 
 struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     const bf16_t* Wdv;    // [dpadR, Vpad]
@@ -151,8 +209,11 @@ struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     int pace_every;       // K steps between meetings (power of two)
     bf16_t* dhidden;      // [N*T, d]
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
+    float* part = nullptr;    // NULL, or scratch of part_bytes: lets the kernel cut the tiles of a partly filled last round
+    size_t part_bytes = 0;    // along the contraction (needs 256 KiB per workgroup of the launch)
 };
 void launch_dh(const DhArgs& a, hipStream_t st);
+size_t dh_part_bytes();   // scratch that lets every dHidden launch cut its last round
 
 struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
     const bf16_t* dz;     // [Mc, Vpad] chunk (rows = tokens)
@@ -165,6 +226,7 @@ struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
     float* dW;            // fp32, layout per w_layout
     int w_layout;
     int beta;             // 0 overwrite, 1 accumulate
+    const float* beta_scale = nullptr;   // NULL, or device: with beta = 1 the old value is multiplied by beta_scale[0] first
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
 };
 void launch_dw(const DwArgs& a, hipStream_t st);

@@ -101,21 +101,113 @@ __global__ void scan_kernel(const int32_t* __restrict__ seq_len, int64_t N, int3
     }
 }
 
-// one wave per generation: flat positions of its valid tokens, in order
+// one wave per generation: flat positions of its valid tokens, in order, from compact row first_row[n]
+// on (a negative first row: the generation was left out).  The compact rows come in regions of
+// `region` rows; a generation never writes past the end of the region its first row lies in.
 __global__ void row_index_kernel(const uint8_t* __restrict__ mask, int64_t N, int64_t T,
-                                 const int32_t* __restrict__ cu, int32_t* __restrict__ row_index) {
+                                 const int32_t* __restrict__ first_row, int64_t region,
+                                 int32_t* __restrict__ row_index) {
     const int64_t n = blockIdx.x;
     if (n >= N) return;
-    int base = cu[n];
+    int64_t base = first_row[n];
+    if (base < 0) return;
+    const int64_t limit = (base / region + 1) * region;
     const int lane = threadIdx.x;
     for (int64_t t0 = 0; t0 < T; t0 += WAVE) {
         const int64_t t = t0 + lane;
         const bool v = t < T && mask[n * T + t] != 0;
         const unsigned long long b = __ballot(v);
         const int before = __popcll(b & ((1ull << lane) - 1ull));
-        if (v) row_index[base + before] = (int32_t)(n * T + t);
+        if (v && base + before < limit) row_index[base + before] = (int32_t)(n * T + t);
         base += __popcll(b);
     }
+}
+
+// Single block: deals the generations to chunks (see launch_compaction_chunked in rapid_internal.h).
+// Thread 0 walks the runs of equal group id in order and fills chunk after chunk; then all threads
+// give every generation its chunk and first compact row and count each run's group id once.
+__global__ __launch_bounds__(1024) void plan_chunks_kernel(const int32_t* __restrict__ cu,
+                                                           const int32_t* __restrict__ gid, int64_t N, int64_t K,
+                                                           int64_t Rcap, int Cmax, int32_t* __restrict__ gseen,
+                                                           int32_t* __restrict__ tab, int32_t* __restrict__ gen_row0,
+                                                           int32_t* __restrict__ gen_chunk,
+                                                           int32_t* __restrict__ counts,
+                                                           int32_t* __restrict__ dev_status) {
+    __shared__ int s_status;
+    if (threadIdx.x == 0) {
+        int status = 0, c = 0;
+        int64_t placed = 0;
+        auto close = [&](int64_t g0, int64_t g1, int64_t rows) {
+            if (rows > Rcap) rows = Rcap;
+            int32_t* e = tab + (int64_t)c * CH_WORDS;
+            e[CH_G0] = (int32_t)g0; e[CH_G1] = (int32_t)g1; e[CH_ROWS] = (int32_t)rows;
+            e[CH_M] = (int32_t)((int64_t)c * Rcap + rows);
+            e[CH_MR] = (int32_t)((int64_t)c * Rcap + (rows + ROW_TILE - 1) / ROW_TILE * ROW_TILE);
+            e[5] = e[6] = e[7] = 0;
+            placed += rows;
+            ++c;
+        };
+        if (Cmax == 1) {
+            const int64_t total = cu[N];
+            if (total > Rcap) status |= RAPID_STATUS_TOKEN_BOUND;
+            close(0, N, total);
+        } else {
+            int64_t chunk_g0 = 0, chunk_rows = 0, run0 = 0;
+            int run_gid = gid[0];
+            bool full = false;
+            for (int64_t n = 1; n <= N && !full; ++n) {
+                if (n < N && gid[n] == run_gid) continue;
+                const int64_t rows = (int64_t)cu[n] - (int64_t)cu[run0];   // the run [run0, n)
+                if (rows > Rcap) status |= RAPID_STATUS_GROUP_LAYOUT;      // placed alone, cut at Rcap
+                if (run0 > chunk_g0 && chunk_rows + rows > Rcap) {
+                    if (c == Cmax - 1) {            // no chunk left: the rest of the batch is left out
+                        status |= RAPID_STATUS_TOKEN_BOUND;
+                        full = true;
+                        break;
+                    }
+                    close(chunk_g0, run0, chunk_rows);
+                    chunk_g0 = run0;
+                    chunk_rows = 0;
+                }
+                chunk_rows += rows;
+                run0 = n;
+                if (n < N) run_gid = gid[n];
+            }
+            close(chunk_g0, run0, chunk_rows);      // run0 == N unless the chunks ran out
+        }
+        while (c < Cmax) close(N, N, 0);            // chunks that stay empty (close() counts c up)
+        counts[CNT_M] = (int32_t)placed;
+        counts[CNT_MR] = (int32_t)((placed + ROW_TILE - 1) / ROW_TILE * ROW_TILE);
+        s_status = status;
+    }
+    __syncthreads();
+    int status = 0;
+    for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
+        int c = -1;
+        for (int k = 0; k < Cmax; ++k)
+            if (n >= tab[k * CH_WORDS + CH_G0] && n < tab[k * CH_WORDS + CH_G1]) { c = k; break; }
+        gen_chunk[n] = c;
+        gen_row0[n] = c < 0 ? -1 : (int32_t)((int64_t)c * Rcap + ((int64_t)cu[n] - (int64_t)cu[tab[c * CH_WORDS + CH_G0]]));
+        if (Cmax > 1 && (n == 0 || gid[n] != gid[n - 1])) {       // first generation of a run
+            const int32_t g = gid[n];
+            if (g >= 0 && g < K && atomicAdd(&gseen[g], 1) > 0) status |= RAPID_STATUS_GROUP_LAYOUT;
+        }
+    }
+    if (threadIdx.x == 0) status |= s_status;
+    if (status && dev_status) atomicOr(dev_status, status);
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+__global__ void fill_f64_kernel(double* p, int64_t n, double v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+__global__ void f32_add_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] += src[i];
 }
 
 __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
@@ -125,12 +217,13 @@ __global__ void fill_f32_kernel(float* p, int64_t n, float v) {
 
 // compact token ids and generation ids; out-of-range ids are flagged and replaced by 0
 __global__ void gather_tokens_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ row_index,
-                                     const int32_t* __restrict__ counts, int64_t Mmax_pad, int64_t T, int64_t V,
-                                     int32_t* __restrict__ tokc, int32_t* __restrict__ seqc,
+                                     const int32_t* __restrict__ counts, int64_t row0, int64_t rows_max, int64_t T,
+                                     int64_t V, int32_t* __restrict__ tokc, int32_t* __restrict__ seqc,
                                      int32_t* __restrict__ dev_status) {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t jl = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t j = row0 + jl;
     const int M = counts[CNT_M], Mr = counts[CNT_MR];
-    if (j >= Mr || j >= Mmax_pad) return;
+    if (j >= Mr || jl >= rows_max) return;
     int tok = 0, seq = 0;
     if (j < M) {
         const int32_t pos = row_index[j];
@@ -149,9 +242,10 @@ __global__ void gather_tokens_kernel(const int32_t* __restrict__ tokens, const i
 __global__ void merge_lse_kernel(const float* __restrict__ part_max, const float* __restrict__ part_sum, int P,
                                  int64_t ld_part, const float* __restrict__ zy,
                                  const int32_t* __restrict__ row_index, const int32_t* __restrict__ counts,
-                                 float* __restrict__ lse_c, float* __restrict__ logp_out,
+                                 int64_t row0, float* __restrict__ lse_c, float* __restrict__ logp_out,
                                  float* __restrict__ lse_out) {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t jl = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // column of the partials
+    const int64_t j = row0 + jl;
     const int M = counts[CNT_M];
     if (j >= M) return;
     // one pass with a running maximum; slots are merged in slot order, so the result is reproducible.
@@ -165,8 +259,8 @@ __global__ void merge_lse_kernel(const float* __restrict__ part_max, const float
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const bool in = p0 + u < P;
-            pmv[u] = in ? part_max[(int64_t)(p0 + u) * ld_part + j] : 0.f;
-            psv[u] = in ? part_sum[(int64_t)(p0 + u) * ld_part + j] : 0.f;
+            pmv[u] = in ? part_max[(int64_t)(p0 + u) * ld_part + jl] : 0.f;
+            psv[u] = in ? part_sum[(int64_t)(p0 + u) * ld_part + jl] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -196,9 +290,10 @@ __global__ void seq_logratio_kernel(const float* __restrict__ logp_cur, const fl
                                     float* __restrict__ tok_lr, double* __restrict__ s64,
                                     float* __restrict__ s32, double log_eta, int clip_tokens,
                                     double* __restrict__ tsum, double* __restrict__ tmax,
-                                    int32_t* __restrict__ dev_status) {
+                                    const int32_t* __restrict__ gen_range, int32_t* __restrict__ dev_status) {
     const int64_t n = blockIdx.x;
     if (n >= N) return;
+    if (gen_range && (n < gen_range[0] || n >= gen_range[1])) return;
     double acc = 0.0, csum = 0.0, cmax = -INFINITY;
     bool bad = false;
     for (int64_t t = threadIdx.x; t < T; t += WAVE) {
@@ -234,51 +329,61 @@ __global__ void seq_logratio_kernel(const float* __restrict__ logp_cur, const fl
     }
 }
 
-__device__ inline double clipped_weight(const float* s32, int64_t n, double log_eta) {
+__device__ inline double clipped_weight(const float* s32, const double* s64, int64_t n, double log_eta) {
+    if (s64) return exp(fmin(s64[n], log_eta));
     if (!s32) return 1.0;
     return exp(fmin((double)s32[n], log_eta));
 }
 
 // pass 1 over generations: defaults for entries no group owns, and data checks
 __global__ void group_init_kernel(const float* __restrict__ rewards, const int32_t* __restrict__ group_ids,
-                                  const float* __restrict__ s32, int64_t N, int64_t K, double log_eta,
-                                  float* __restrict__ adv, float* __restrict__ weight,
+                                  const float* __restrict__ s32, const double* __restrict__ s64, int64_t N,
+                                  int64_t K, double log_eta, float* __restrict__ adv, double* __restrict__ adv64,
+                                  float* __restrict__ weight, const int32_t* __restrict__ gen_range,
                                   int32_t* __restrict__ dev_status) {
     const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
+    if (gen_range && (n < gen_range[0] || n >= gen_range[1])) return;
     int bits = 0;
     const int32_t k = group_ids[n];
     if (k < 0 || k >= K) bits |= RAPID_STATUS_BAD_GROUP;
     if (!isfinite(rewards[n])) bits |= RAPID_STATUS_NONFINITE_REWARD;
-    if (s32 && isnan(s32[n])) bits |= RAPID_STATUS_NONFINITE_LOGP;
+    if (s64 ? isnan(s64[n]) : (s32 && isnan(s32[n]))) bits |= RAPID_STATUS_NONFINITE_LOGP;
     if (bits && dev_status) atomicOr(dev_status, bits);
     adv[n] = 0.f;
-    if (weight) weight[n] = (float)clipped_weight(s32, n, log_eta);
+    if (adv64) adv64[n] = 0.0;
+    if (weight) weight[n] = (float)clipped_weight(s32, s64, n, log_eta);
 }
 
-// one block per group: size, mean/std of R, clipped-weight baseline, advantages of its members
+// one block per group: size, mean/std of R, clipped-weight baseline, advantages of its members.
+// With gen_range only the generations in the range are looked at (the caller guarantees that a group
+// lies inside or outside the range as a whole); a group without a member there writes nothing.
 __global__ void group_advantage_kernel(const float* __restrict__ rewards, const int32_t* __restrict__ group_ids,
-                                       const float* __restrict__ s32, int64_t N, double log_eta,
-                                       int baseline_mode, float* __restrict__ adv, float* __restrict__ gmean,
-                                       float* __restrict__ gstd, int32_t* __restrict__ gsize) {
+                                       const float* __restrict__ s32, const double* __restrict__ s64, int64_t N,
+                                       double log_eta, int baseline_mode, float* __restrict__ adv,
+                                       double* __restrict__ adv64, float* __restrict__ gmean,
+                                       float* __restrict__ gstd, int32_t* __restrict__ gsize,
+                                       const int32_t* __restrict__ gen_range) {
     __shared__ double sm[16];
     const int k = blockIdx.x;
+    const int64_t n_begin = gen_range ? gen_range[0] : 0, n_end = gen_range ? gen_range[1] : N;
     double cnt = 0.0, sum_r = 0.0, sum_wr = 0.0;
-    for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
+    for (int64_t n = n_begin + threadIdx.x; n < n_end; n += blockDim.x) {
         if (group_ids[n] == k) {
             float r = rewards[n];
             if (!isfinite(r)) r = 0.f;
             cnt += 1.0;
             sum_r += (double)r;
-            sum_wr += clipped_weight(s32, n, log_eta) * (double)r;
+            sum_wr += clipped_weight(s32, s64, n, log_eta) * (double)r;
         }
     }
     cnt = block_sum(cnt, sm);
     sum_r = block_sum(sum_r, sm);
     sum_wr = block_sum(sum_wr, sm);
+    if (gen_range && cnt == 0.0) return;   // uniform over the block
     const double mean = cnt > 0.0 ? sum_r / cnt : 0.0;
     double sq = 0.0;
-    for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
+    for (int64_t n = n_begin + threadIdx.x; n < n_end; n += blockDim.x) {
         if (group_ids[n] == k) {
             float r = rewards[n];
             if (!isfinite(r)) r = 0.f;
@@ -288,11 +393,12 @@ __global__ void group_advantage_kernel(const float* __restrict__ rewards, const 
             if (baseline_mode == 0) {
                 b = sum_wr / cnt;
             } else {
-                const double rest = sum_wr - clipped_weight(s32, n, log_eta) * (double)r;
+                const double rest = sum_wr - clipped_weight(s32, s64, n, log_eta) * (double)r;
                 if (baseline_mode == 1) b = rest / cnt;
                 else b = cnt > 1.0 ? rest / (cnt - 1.0) : 0.0;
             }
             adv[n] = (float)((double)r - b);
+            if (adv64) adv64[n] = (double)r - b;
         }
     }
     sq = block_sum(sq, sm);
@@ -303,72 +409,89 @@ __global__ void group_advantage_kernel(const float* __restrict__ rewards, const 
     }
 }
 
-// single block: coefficients g_n, the loss, diagnostics.  Generation-level outer weight (tsum NULL):
-// g_n = -(loss_scale/N) c_n A_n, loss = sum_n g_n.  Token-level (tsum, tmax given): g_n is the
-// generation's factor -(loss_scale/N) A_n, a token's coefficient is g_n c_{n,t}, and
-// loss = sum_n g_n sum_t c_{n,t}.  g64 keeps g_n in double for the per-row pass.
-__global__ void coefficients_kernel(const double* __restrict__ s64, const float* __restrict__ adv,
-                                    const float* __restrict__ coef_override, int64_t N, double log_eta,
-                                    int coef_mode, double log_loss_scale, int normalized,
-                                    const double* __restrict__ tsum, const double* __restrict__ tmax,
-                                    const int32_t* __restrict__ counts, float* __restrict__ g,
-                                    double* __restrict__ g64, float* __restrict__ loss_out,
-                                    rapid_iw_pg_diag* __restrict__ diag) {
+// single block: coefficients g_n, the loss, diagnostics (the three uses are described at CoefArgs).
+// Generation-level outer weight (tsum NULL): g_n = -(loss_scale/N) c_n A_n, loss = sum_n g_n.
+// Token-level (tsum, tmax given): g_n is the generation's factor -(loss_scale/N) A_n, a token's
+// coefficient is g_n c_{n,t}, and loss = sum_n g_n sum_t c_{n,t}.  g64 keeps g_n in double for the
+// per-row pass.
+__global__ void coefficients_kernel(CoefArgs a, double log_eta, double log_loss_scale) {
     __shared__ double sm[16];
+    const int64_t N = a.N;
     const double logN = log((double)N);
-    const bool per_token = tsum != nullptr && !coef_override;
+    const bool per_token = a.tsum != nullptr && !a.coef_override;
+    const bool chunk_pass = a.gen_range != nullptr;
+    const int64_t n_begin = chunk_pass ? a.gen_range[0] : 0, n_end = chunk_pass ? a.gen_range[1] : N;
+    auto advantage = [&](int64_t n) { return a.adv64 ? a.adv64[n] : (double)a.adv[n]; };
     double lam = 0.0;
-    if (!coef_override && normalized) {
+    if (!a.coef_override && a.normalized) {
         double mx = -INFINITY;
-        for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
-            const double a = (double)adv[n];
-            if (a != 0.0) {
-                const double lc = per_token ? tmax[n] : (coef_mode == 0 ? s64[n] : fmin(s64[n], log_eta));
-                mx = fmax(mx, lc + log(fabs(a)) + log_loss_scale - logN);   // -inf for a generation without tokens
+        for (int64_t n = n_begin + threadIdx.x; n < n_end; n += blockDim.x) {
+            const double av = advantage(n);
+            if (av != 0.0) {
+                const double lc = per_token ? a.tmax[n] : (a.coef_mode == 0 ? a.s64[n] : fmin(a.s64[n], log_eta));
+                mx = fmax(mx, lc + log(fabs(av)) + log_loss_scale - logN);   // -inf for a generation without tokens
             }
         }
         mx = block_max(mx, sm);
+        if (chunk_pass) {
+            const double before = a.lam_state[0];        // -inf: no chunk has carried a coefficient yet
+            const double now = fmax(before, mx);
+            __syncthreads();                             // everybody has read the old state
+            if (threadIdx.x == 0) {
+                a.lam_state[0] = now;
+                a.lam_chunk[0] = now;
+                a.beta_out[0] = (before == -INFINITY) ? 1.f : (float)exp(before - now);
+            }
+            mx = now;
+        }
         lam = (mx == -INFINITY) ? 0.0 : mx;
+    } else if (chunk_pass && threadIdx.x == 0) {
+        a.lam_state[0] = 0.0;
+        a.lam_chunk[0] = 0.0;
+        a.beta_out[0] = 1.f;
     }
     double loss = 0.0, slw = 0.0, salw = 0.0, maxs = 0.0, nclip = 0.0;
-    for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
-        const double s = s64[n];
+    for (int64_t n = n_begin + threadIdx.x; n < n_end; n += blockDim.x) {
+        const double s = a.s64[n];
         double gn;
-        if (coef_override) {
-            gn = (double)coef_override[n];
+        if (a.coef_override) {
+            gn = (double)a.coef_override[n];
         } else {
-            const double a = (double)adv[n];
-            if (a != 0.0) {
-                const double lc = per_token ? 0.0 : (coef_mode == 0 ? s : fmin(s, log_eta));
-                gn = (a > 0.0 ? -1.0 : 1.0) * exp(lc + log(fabs(a)) + log_loss_scale - logN - lam);
+            const double av = advantage(n);
+            if (av != 0.0) {
+                const double lc = per_token ? 0.0 : (a.coef_mode == 0 ? s : fmin(s, log_eta));
+                gn = (av > 0.0 ? -1.0 : 1.0) * exp(lc + log(fabs(av)) + log_loss_scale - logN - lam);
             } else {
                 gn = 0.0;
             }
         }
-        g[n] = (float)gn;
-        g64[n] = gn;
-        loss += per_token ? (gn != 0.0 ? gn * tsum[n] : 0.0) : gn;
+        if (a.write_g) {
+            a.g[n] = (float)gn;
+            a.g64[n] = gn;
+        }
+        loss += per_token ? (gn != 0.0 ? gn * a.tsum[n] : 0.0) : gn;
         const double lw = fmin(s, log_eta);
         slw += lw;
         salw += fabs(lw);
         maxs = fmax(maxs, fabs(s));
         nclip += s > log_eta ? 1.0 : 0.0;
     }
+    if (chunk_pass) return;
     loss = block_sum(loss, sm);
     slw = block_sum(slw, sm);
     salw = block_sum(salw, sm);
     nclip = block_sum(nclip, sm);
     maxs = block_max(maxs, sm);
     if (threadIdx.x == 0) {
-        loss_out[0] = (float)loss;
-        if (diag) {
-            diag->n_tokens = counts[CNT_M];
-            diag->n_clipped = (int32_t)nclip;
-            diag->n_sequences = (int32_t)N;
-            diag->mean_log_w = (float)(slw / (double)N);
-            diag->mean_abs_log_w = (float)(salw / (double)N);
-            diag->max_abs_s = (float)maxs;
-            diag->grad_log_scale = (float)lam;
+        a.loss_out[0] = (float)loss;
+        if (a.diag) {
+            a.diag->n_tokens = a.counts[CNT_M];
+            a.diag->n_clipped = (int32_t)nclip;
+            a.diag->n_sequences = (int32_t)N;
+            a.diag->mean_log_w = (float)(slw / (double)N);
+            a.diag->mean_abs_log_w = (float)(salw / (double)N);
+            a.diag->max_abs_s = (float)maxs;
+            a.diag->grad_log_scale = (float)lam;
         }
     }
 }
@@ -379,8 +502,8 @@ __global__ void row_coefficients_kernel(const float* __restrict__ g, const doubl
                                         const int32_t* __restrict__ seqc, const int32_t* __restrict__ row_index,
                                         const int32_t* __restrict__ counts, const float* __restrict__ logp_cur,
                                         const float* __restrict__ logp_behav, int per_token, double log_eta,
-                                        int clip_tokens, float* __restrict__ rowg) {
-    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+                                        int clip_tokens, int64_t row0, float* __restrict__ rowg) {
+    const int64_t j = row0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int M = counts[CNT_M], Mr = counts[CNT_MR];
     if (j >= Mr) return;
     float v = 0.f;
@@ -410,6 +533,26 @@ __global__ void zero_masked_rows_kernel(uint32_t* __restrict__ dh, const uint8_t
     for (int64_t i = threadIdx.x; i < words_per_row; i += blockDim.x) p[i] = 0u;
 }
 
+// one block per position of [N, T]: a valid position's bf16 gradient row times
+// exp(lam_chunk[chunk of its generation] - lam_final); rows whose factor is 1 are left alone
+__global__ void rescale_rows_kernel(bf16_t* __restrict__ dh, const uint8_t* __restrict__ mask, int64_t T, int64_t d,
+                                    const int32_t* __restrict__ gen_chunk, const double* __restrict__ lam_chunk,
+                                    const double* __restrict__ lam_state) {
+    const int64_t r = blockIdx.x;
+    if (mask[r] == 0) return;
+    const int c = gen_chunk[r / T];
+    if (c < 0) return;
+    const double dl = lam_chunk[c] - lam_state[0];
+    if (dl == 0.0 || !(dl < 0.0)) return;         // also skips a state that never left -inf (no coefficient anywhere)
+    const float f = (float)exp(dl);
+    bf16_t* p = dh + r * d;
+    for (int64_t i = threadIdx.x; i < d; i += blockDim.x) {
+        const float v = __builtin_bit_cast(float, (uint32_t)p[i] << 16) * f;
+        const __bf16 o = (__bf16)v;
+        p[i] = __builtin_bit_cast(bf16_t, o);
+    }
+}
+
 __global__ void f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -425,62 +568,87 @@ void launch_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_l
                        int32_t* row_index, int32_t* counts, int64_t row_cap, int32_t* dev_status, hipStream_t st) {
     seq_len_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, seq_len);
     scan_kernel<<<1, 1024, 0, st>>>(seq_len, N, cu_seqlen, counts, row_cap, dev_status);
-    if (row_index) row_index_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, cu_seqlen, row_index);
+    if (row_index) row_index_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, cu_seqlen, INT64_MAX / 4, row_index);
+}
+
+void launch_compaction_chunked(const uint8_t* mask, const int32_t* group_ids, int64_t N, int64_t T, int64_t K,
+                               int64_t Rcap, int Cmax, int32_t* seq_len, int32_t* cu_seqlen, int32_t* tab,
+                               int32_t* gen_row0, int32_t* gen_chunk, int32_t* gseen, int32_t* row_index,
+                               int32_t* counts, int32_t* dev_status, hipStream_t st) {
+    seq_len_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, seq_len);
+    scan_kernel<<<1, 1024, 0, st>>>(seq_len, N, cu_seqlen, nullptr, INT64_MAX, nullptr);
+    if (Cmax > 1) launch_fill_i32(gseen, K, 0, st);
+    plan_chunks_kernel<<<1, 1024, 0, st>>>(cu_seqlen, group_ids, N, K, Rcap, Cmax, gseen, tab, gen_row0, gen_chunk,
+                                           counts, dev_status);
+    row_index_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, gen_row0, Rcap, row_index);
 }
 
 void launch_fill_f32(float* p, int64_t n, float v, hipStream_t st) {
     if (n > 0) fill_f32_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, n, v);
 }
+void launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st) {
+    if (n > 0) fill_i32_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, n, v);
+}
+void launch_fill_f64(double* p, int64_t n, double v, hipStream_t st) {
+    if (n > 0) fill_f64_kernel<<<blocks_for(n, 256), 256, 0, st>>>(p, n, v);
+}
+void launch_f32_add(const float* src, float* dst, int64_t n, hipStream_t st) {
+    if (n > 0) f32_add_kernel<<<blocks_for(n, 256), 256, 0, st>>>(src, dst, n);
+}
 
-void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const int32_t* counts,
-                          int64_t Mmax_pad, int64_t T, int64_t V, int32_t* tokc, int32_t* seqc,
+void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const int32_t* counts, int64_t row0,
+                          int64_t rows_max, int64_t T, int64_t V, int32_t* tokc, int32_t* seqc,
                           int32_t* dev_status, hipStream_t st) {
-    gather_tokens_kernel<<<blocks_for(Mmax_pad, 256), 256, 0, st>>>(tokens, row_index, counts, Mmax_pad, T, V,
-                                                                    tokc, seqc, dev_status);
+    if (rows_max > 0)
+        gather_tokens_kernel<<<blocks_for(rows_max, 256), 256, 0, st>>>(tokens, row_index, counts, row0, rows_max, T, V,
+                                                                        tokc, seqc, dev_status);
 }
 
 void launch_merge_lse(const float* part_max, const float* part_sum, int P, int64_t ld_part, const float* zy,
-                      const int32_t* row_index, const int32_t* counts, int64_t Mmax_pad, float* lse_c,
+                      const int32_t* row_index, const int32_t* counts, int64_t row0, int64_t rows_max, float* lse_c,
                       float* logp_out, float* lse_out, hipStream_t st) {
-    merge_lse_kernel<<<blocks_for(Mmax_pad, 256), 256, 0, st>>>(part_max, part_sum, P, ld_part, zy, row_index,
-                                                                counts, lse_c, logp_out, lse_out);
+    if (rows_max > 0)
+        merge_lse_kernel<<<blocks_for(rows_max, 256), 256, 0, st>>>(part_max, part_sum, P, ld_part, zy, row_index,
+                                                                    counts, row0, lse_c, logp_out, lse_out);
 }
 
 void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N,
                          int64_t T, float* tok_logratio_out, double* s64, float* s32, float eta, int clip_tokens,
-                         double* tsum, double* tmax, int32_t* dev_status, hipStream_t st) {
+                         double* tsum, double* tmax, const int32_t* gen_range, int32_t* dev_status, hipStream_t st) {
     const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
     seq_logratio_kernel<<<(unsigned)N, WAVE, 0, st>>>(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64,
-                                                      s32, log_eta, clip_tokens, tsum, tmax, dev_status);
+                                                      s32, log_eta, clip_tokens, tsum, tmax, gen_range, dev_status);
 }
 
-void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, int64_t N,
-                            int64_t K, float eta, int baseline_mode, float* adv, float* weight, float* gmean,
-                            float* gstd, int32_t* gsize, int32_t* dev_status, hipStream_t st) {
+void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, const double* s64,
+                            int64_t N, int64_t K, float eta, int baseline_mode, float* adv, double* adv64,
+                            float* weight, float* gmean, float* gstd, int32_t* gsize, const int32_t* gen_range,
+                            int32_t* dev_status, hipStream_t st) {
     const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
-    group_init_kernel<<<blocks_for(N, 256), 256, 0, st>>>(rewards, group_ids, s32, N, K, log_eta, adv, weight,
-                                                          dev_status);
-    group_advantage_kernel<<<(unsigned)K, 256, 0, st>>>(rewards, group_ids, s32, N, log_eta, baseline_mode, adv,
-                                                        gmean, gstd, gsize);
+    group_init_kernel<<<blocks_for(N, 256), 256, 0, st>>>(rewards, group_ids, s32, s64, N, K, log_eta, adv, adv64,
+                                                          weight, gen_range, dev_status);
+    group_advantage_kernel<<<(unsigned)K, 256, 0, st>>>(rewards, group_ids, s32, s64, N, log_eta, baseline_mode, adv,
+                                                        adv64, gmean, gstd, gsize, gen_range);
 }
 
-void launch_coefficients(const double* s64, const float* adv, const float* coef_override, int64_t N, float eta,
-                         int coef_mode, float loss_scale, int normalized, const double* tsum, const double* tmax,
-                         const int32_t* counts, float* g, double* g64, float* loss_out, rapid_iw_pg_diag* diag,
-                         hipStream_t st) {
-    const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
-    coefficients_kernel<<<1, 1024, 0, st>>>(s64, adv, coef_override, N, log_eta, coef_mode,
-                                            log((double)loss_scale), normalized, tsum, tmax, counts, g, g64,
-                                            loss_out, diag);
+void launch_coefficients(const CoefArgs& a, hipStream_t st) {
+    const double log_eta = (a.eta > 0.f && std::isfinite(a.eta)) ? log((double)a.eta) : (double)INFINITY;
+    coefficients_kernel<<<1, 1024, 0, st>>>(a, log_eta, log((double)a.loss_scale));
 }
 
 void launch_row_coefficients(const float* g, const double* g64, const int32_t* seqc, const int32_t* row_index,
                              const int32_t* counts, const float* logp_cur, const float* logp_behav, int per_token,
-                             float eta, int clip_tokens, int64_t rows_max, float* rowg, hipStream_t st) {
+                             float eta, int clip_tokens, int64_t row0, int64_t rows_max, float* rowg, hipStream_t st) {
     const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
-    row_coefficients_kernel<<<blocks_for(rows_max, 256), 256, 0, st>>>(g, g64, seqc, row_index, counts, logp_cur,
-                                                                       logp_behav, per_token, log_eta, clip_tokens,
-                                                                       rowg);
+    if (rows_max > 0)
+        row_coefficients_kernel<<<blocks_for(rows_max, 256), 256, 0, st>>>(g, g64, seqc, row_index, counts, logp_cur,
+                                                                           logp_behav, per_token, log_eta,
+                                                                           clip_tokens, row0, rowg);
+}
+
+void launch_rescale_rows(void* dhidden, const uint8_t* mask, int64_t N, int64_t T, int64_t d, const int32_t* gen_chunk,
+                         const double* lam_chunk, const double* lam_state, hipStream_t st) {
+    rescale_rows_kernel<<<(unsigned)(N * T), 128, 0, st>>>((bf16_t*)dhidden, mask, T, d, gen_chunk, lam_chunk, lam_state);
 }
 
 void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, int64_t d, int elem_bytes,

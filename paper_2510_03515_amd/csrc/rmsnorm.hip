@@ -84,9 +84,9 @@ __global__ __launch_bounds__(256) void rmsnorm_pad_bf16_kernel(const bf16_t* __r
                                                                const bf16_t* __restrict__ weight, float eps,
                                                                bf16_t* __restrict__ dst, int64_t ld_dst, int64_t Cpad,
                                                                const int32_t* __restrict__ counts,
-                                                               float* __restrict__ inv_rms) {
+                                                               float* __restrict__ inv_rms, int64_t r0) {
     __shared__ double sm[4];
-    const int64_t r = blockIdx.x;
+    const int64_t r = r0 + blockIdx.x;
     const int M = counts[CNT_M], Mr = counts[CNT_MR];
     if (r >= Mr) return;
     bf16_t* drow = dst + r * ld_dst;
@@ -121,15 +121,16 @@ __global__ __launch_bounds__(256) void rmsnorm_pad_bf16_kernel(const bf16_t* __r
 }
 
 // dweight partials: block (rb, cb) sums dh[row][k] x[row][k] inv_rms[row] over the valid compact rows
-// rb*RB .. +RB for the 8 columns of each of its threads; part[rb][k]
+// row0 + rb*RB .. +RB for the 8 columns of each of its threads; part[rb][k] (a block without rows writes nothing:
+// `part` is zeroed beforehand)
 constexpr int RB = 512;
 __global__ __launch_bounds__(256) void rmsnorm_dweight_partial_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dh,
                                                                       int64_t d, const int32_t* __restrict__ row_index,
                                                                       const int32_t* __restrict__ counts,
                                                                       const float* __restrict__ inv_rms,
-                                                                      float* __restrict__ part) {
+                                                                      float* __restrict__ part, int64_t row0) {
     const int64_t c = (int64_t)blockIdx.y * blockDim.x + threadIdx.x;   // 8-column chunk
-    const int64_t r0 = (int64_t)blockIdx.x * RB;                       // row blocks along x: no 65535 limit
+    const int64_t r0 = row0 + (int64_t)blockIdx.x * RB;                // row blocks along x: no 65535 limit
     const int M = counts[CNT_M];
     if (c * 8 >= d || r0 >= M) return;   // the reduction reads the blocks that hold tokens only
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -148,14 +149,13 @@ __global__ __launch_bounds__(256) void rmsnorm_dweight_partial_kernel(const bf16
     for (int e = 0; e < 8; ++e) o[e] = acc[e];
 }
 
-// dweight[k] = sum over the row blocks that hold tokens, in block order (fp64 accumulate)
-__global__ void rmsnorm_dweight_reduce_kernel(const float* __restrict__ part, int64_t d, int64_t nblk_max,
-                                              const int32_t* __restrict__ counts, float* __restrict__ dweight) {
+// dweight[k] = sum over all row blocks, in block order (fp64 accumulate; blocks without rows hold zeros)
+__global__ void rmsnorm_dweight_reduce_kernel(const float* __restrict__ part, int64_t d, int64_t nblk,
+                                              float* __restrict__ dweight) {
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= d) return;
-    const int64_t nblk = ((int64_t)counts[CNT_M] + RB - 1) / RB;
     double acc = 0.0;
-    for (int64_t b = 0; b < nblk && b < nblk_max; ++b) acc += (double)part[b * d + k];
+    for (int64_t b = 0; b < nblk; ++b) acc += (double)part[b * d + k];
     dweight[k] = (float)acc;
 }
 
@@ -164,9 +164,9 @@ __global__ __launch_bounds__(256) void rmsnorm_dx_kernel(const bf16_t* __restric
                                                          const bf16_t* __restrict__ weight,
                                                          const int32_t* __restrict__ row_index,
                                                          const int32_t* __restrict__ counts,
-                                                         const float* __restrict__ inv_rms) {
+                                                         const float* __restrict__ inv_rms, int64_t r0) {
     __shared__ float sm[4];
-    const int64_t r = blockIdx.x;
+    const int64_t r = r0 + blockIdx.x;
     if (r >= counts[CNT_M]) return;
     const int64_t pos = row_index[r];
     const bf16_t* xr = x + pos * d;
@@ -198,26 +198,28 @@ __global__ __launch_bounds__(256) void rmsnorm_dx_kernel(const bf16_t* __restric
 }  // namespace
 
 void launch_rmsnorm_pad_bf16(const bf16_t* src, int64_t C, const int32_t* row_index, const bf16_t* weight, float eps,
-                             bf16_t* dst, int64_t ld_dst, int64_t Rpad, int64_t Cpad, const int32_t* counts,
+                             bf16_t* dst, int64_t ld_dst, int64_t r0, int64_t Rpad, int64_t Cpad, const int32_t* counts,
                              float* inv_rms, hipStream_t st) {
     if (Rpad <= 0) return;
     rmsnorm_pad_bf16_kernel<<<(unsigned)Rpad, 256, 0, st>>>(src, C, row_index, weight, eps, dst, ld_dst, Cpad, counts,
-                                                            inv_rms);
+                                                            inv_rms, r0);
 }
 
 int64_t rmsnorm_dweight_blocks(int64_t rows_max) { return (rows_max + RB - 1) / RB; }
 
 void launch_rmsnorm_backward(const bf16_t* x, bf16_t* dh, int64_t d, const bf16_t* weight, const int32_t* row_index,
-                             const int32_t* counts, const float* inv_rms, int64_t rows_max, float* part,
-                             float* dweight, hipStream_t st) {
+                             const int32_t* counts, const float* inv_rms, int64_t row0, int64_t rows_max, float* part,
+                             hipStream_t st) {
     if (rows_max <= 0) return;
-    if (dweight) {
-        const int64_t nblk = rmsnorm_dweight_blocks(rows_max);
-        dim3 grid((unsigned)nblk, (unsigned)((d / 8 + 255) / 256));
-        rmsnorm_dweight_partial_kernel<<<grid, 256, 0, st>>>(x, dh, d, row_index, counts, inv_rms, part);
-        rmsnorm_dweight_reduce_kernel<<<(unsigned)((d + 255) / 256), 256, 0, st>>>(part, d, nblk, counts, dweight);
+    if (part) {
+        dim3 grid((unsigned)rmsnorm_dweight_blocks(rows_max), (unsigned)((d / 8 + 255) / 256));
+        rmsnorm_dweight_partial_kernel<<<grid, 256, 0, st>>>(x, dh, d, row_index, counts, inv_rms, part, row0);
     }
-    rmsnorm_dx_kernel<<<(unsigned)rows_max, 256, 0, st>>>(x, dh, d, weight, row_index, counts, inv_rms);
+    rmsnorm_dx_kernel<<<(unsigned)rows_max, 256, 0, st>>>(x, dh, d, weight, row_index, counts, inv_rms, row0);
+}
+
+void launch_rmsnorm_dweight_reduce(const float* part, int64_t d, int64_t nblk, float* dweight, hipStream_t st) {
+    rmsnorm_dweight_reduce_kernel<<<(unsigned)((d + 255) / 256), 256, 0, st>>>(part, d, nblk, dweight);
 }
 
 }  // namespace rapid

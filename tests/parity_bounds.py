@@ -18,6 +18,14 @@ scale above by much (random signs: the errors of a long sum add like a random wa
 sum of magnitudes).  A gradient stored in bf16 (dw_dtype bf16) gets one more rounding: rel 2^-6.
 fp32 path: fp64 accumulation, fp32 storage: rel 1e-5 as for the norm.  atol = 1e-30 exempts rows
 whose coefficient is so small that fp32/bf16 intermediates leave the normal range.
+
+One more term, from the data and not from the kernels (coefficient_slack below): log-probabilities are
+stored as float (the behaviour pass stores them so; the current pass rounds the same way, which is what
+makes equal policies give ratios of exactly 1).  The oracle keeps its current log-probs in float64, so
+a generation's log ratio s_n differs from the oracle's by ds <= L_n 2^-24 max|logp|.  That moves the
+weight of every member of the group by the same relative amount, the baseline b = (1/N_k) sum w R by
+at most ds b, and the coefficient g_n ~ rho_n (R_n - b) by ds (1 + b / |A_n|) relative: an advantage
+that is a difference of nearly equal numbers amplifies it.  Each generation's rows get that much more.
 """
 import numpy as np
 
@@ -39,8 +47,24 @@ def worst_excess(got, ref, axis, rel):
     return float(ratio[idx]), idx
 
 
+def coefficient_slack(oracle_out, rewards, mask):
+    """Per generation: ds (1 + b / |A_n|), the relative error its coefficient may carry because stored
+    log-probs are floats (see above); 0 where the advantage is 0 (the coefficient is an exact 0).
+    oracle_out: the oracle's result dict (adv, weight, logp_cur)."""
+    adv = np.asarray(oracle_out["adv"], np.float64)
+    R = np.asarray(rewards, np.float64)
+    lengths = (np.asarray(mask) != 0).sum(axis=1)
+    ds = lengths * 2.0 ** -24 * max(float(np.abs(oracle_out["logp_cur"]).max()), 1.0)
+    b = np.abs(R - adv)                              # the baseline the generation's reward was compared with
+    slack = np.zeros_like(adv)
+    nz = adv != 0
+    slack[nz] = ds[nz] + ds.max() * b[nz] / np.abs(adv[nz])     # own ratio; the group's weights in the baseline
+    return slack
+
+
 def assert_dhidden_close(got, ref, dtype="bf16", rel=None):
-    """got, ref: [..., d]; every element within rel of its token row's largest magnitude."""
+    """got, ref: [..., d]; every element within rel of its token row's largest magnitude.  rel may be an
+    array that broadcasts against the rows (one tolerance per generation: shape [N, 1, 1])."""
     worst, idx = worst_excess(got, ref, -1, REL[dtype] if rel is None else rel)
     assert worst <= 1.0, f"dHidden element {idx}: error is {worst:.2f} x its bound"
     assert np.isfinite(np.asarray(got, np.float64)).all()

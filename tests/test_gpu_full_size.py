@@ -55,27 +55,31 @@ def _fp64_forward_leg(w, row_chunk=4096):
     return idx, lse, zy - lse
 
 
-@pytest.mark.parametrize("cfg,cache,cal", [(2, False, False), (2, True, False), (2, True, True), (2, False, True),
-                                           (1, False, False), (1, True, False), (3, False, False), (3, True, True)])
+@pytest.mark.parametrize("cfg,cache,cal", [(2, False, False), (2, "chunks", False), (2, "whole", True), (2, False, True),
+                                           (2, "chunks", True), (1, False, False), (1, "chunks", False), (3, False, False),
+                                           (3, "chunks", True)])
 def test_full_size_sampled_parity(rb, cfg, cache, cal):
     """cal: the calibrated companion of the workload (same shapes and seed, behaviour weights close
     enough that the generation-level ratios are O(1) and a few per cent clip: the paper's regime,
-    where every generation carries gradient and dz is dense).
+    where every generation carries gradient and dz is dense).  cache: False = the backward that regenerates
+    the logits; "chunks" = logits_cache with the recommended workspace (a cache of 65536 rows, the batch
+    in chunks of whole groups: the launch configuration bench.py times); "whole" = logits_cache with a
+    cache that holds every token of the batch at once.
 
     No expected value below comes from the library: per-position and per-generation references are
     the CPU oracle's; what needs every row of the batch (advantages, coefficients, loss, dW columns)
     is built by the oracle's own functions from the float64 leg above, which the oracle pins on the
     sampled positions and on whole generations (the two shortest and the longest)."""
     spec = wl.calibrated(wl.CONFIGS[cfg]) if cal else wl.CONFIGS[cfg]
-    print("generating", spec.name, "logits_cache" if cache else "", flush=True)
+    print("generating", spec.name, f"logits_cache ({cache})" if cache else "", flush=True)
     w = wl.make_workload(spec, seed=0, device="cuda")
     N, T, K = spec.N, spec.T, w["K"]
     n_tok = int(w["mask"].sum().item())
     logp_b, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"])
-    buf = rb.IwPgBuffers(w["hidden"], w["W"], K, logits_cache=cache, max_tokens=n_tok)
-    print("fused call", flush=True)
+    buf = rb.IwPgBuffers(w["hidden"], w["W"], K, logits_cache=bool(cache), max_tokens=n_tok if cache == "whole" else 0)
+    print("fused call, workspace %.1f GiB" % (buf.workspace.numel() / 2**30), flush=True)
     out = rb.rapid_iw_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], logp_b, w["rewards"],
-                                      w["group_ids"], K, buffers=buf, normalized_grads=True, logits_cache=cache,
+                                      w["group_ids"], K, buffers=buf, normalized_grads=True, logits_cache=bool(cache),
                                       max_tokens=n_tok)
     lp_cur2, lse_gpu = rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], want_lse=True)
     torch.cuda.synchronize()

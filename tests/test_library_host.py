@@ -20,9 +20,14 @@ def rb():
 
 
 def _declared():
-    src = open(os.path.join(ROOT, "include", "rapid.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(rapid_[a-z_0-9]+)\s*\(", src)))
+    """Every function declared in include/*.h (rapid.h: the product ABI; rapid_tuning.h: benchmark hooks)."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if f.endswith(".h"):
+            src = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, f)).read(), flags=re.S)
+            names |= set(re.findall(r"\b(rapid_[a-z_0-9]+)\s*\(", src))
+    return sorted(names)
 
 
 def test_exports_every_declared_symbol(rb):
@@ -56,13 +61,25 @@ def test_workspace_sizes(rb):
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, 0, 1, 1, 1, 1, 0) == 0       # invalid shape
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, 4, 4, 8, 8, 1, 7) == 0       # invalid dtype
     assert rb.rapid_workspace_bytes(rb.OP_LOGPROB_FWD, *args) < rec
-    # the cache: every padded position by default, the promised number of tokens (rounded to 256 rows) with a bound
-    full = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args)
+    # the cache: with a token bound, a cache of that many rows (rounded to 256) holds the whole batch: one chunk, and
+    # the compact row arrays shrink with it; without, every padded position
+    full = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, max_tokens=256 * 2048)
     half = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, max_tokens=300630)
-    ldv = 152064 + 64
-    assert full - half == (256 * 2048 - 300800) * ldv * 2
+    ldv, ldk, slots = 152064 + 64, 1536 + 64, 2 * 152064 // 256
+    rows = 256 * 2048 - 300800
+    # cache, packed hidden row, log-sum-exp partials, nine row arrays, the final norm's partial sums (d floats per 512 rows)
+    per_row = ldv * 2 + ldk * 2 + 2 * slots * 4 + 9 * 4 + 1536 * 4 // 512
+    assert abs((full - half) - rows * per_row) <= 8192              # alignment of the buffers
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, max_tokens=10**9) == full
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, *args, max_tokens=1000) == rec       # other ops ignore it
+    # recommended: a cache of 65536 rows, the batch in chunks of whole groups; it fits 32 GiB at this shape
+    chunked = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args)
+    smallest = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, minimum=True)
+    assert smallest < chunked < half and chunked < 32 * 2**30 and chunked > 65536 * ldv * 2
+    # a batch with fewer positions than that has the one-chunk size as its recommended size
+    small_args = (16, 128, 1536, 151936, 4, rb.DTYPE_BF16)
+    assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *small_args) == \
+        rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *small_args, max_tokens=16 * 128)
 
 
 def test_host_validation_returns_codes_without_a_gpu(rb):
@@ -160,7 +177,7 @@ def test_header_is_plain_c_and_links(tmp_path):
         pytest.skip("no gcc")
     names = _declared()
     src = tmp_path / "link_check.c"
-    src.write_text('#include "rapid.h"\n#include <stdio.h>\ntypedef void (*fn_t)(void);\nint main(void) {\n  fn_t f[] = {'
+    src.write_text('#include "rapid.h"\n#include "rapid_tuning.h"\n#include <stdio.h>\ntypedef void (*fn_t)(void);\nint main(void) {\n  fn_t f[] = {'
                    + ", ".join(f"(fn_t){n}" for n in names)
                    + '};\n  printf("%d %d\\n", (int)(sizeof f / sizeof f[0]), rapid_version());\n  return f[0] == 0;\n}\n')
     lib_dir = os.path.join(ROOT, "paper_2510_03515_amd")
