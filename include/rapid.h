@@ -184,6 +184,27 @@ int rapid_logprob_fwd(const void* hidden, const void* W, const int32_t* tokens, 
                       float temperature, float* logp_out, float* lse_out, int32_t* dev_status,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * rapid_logprob_fwd for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops that score behaviour log-probs between decoding steps,
+ * harnesses that forbid hipMalloc.  Same arguments without `workspace`, same results, bit for bit:
+ * the scratch is a static device array inside the library (768 MiB, RAPID_STATIC_SCRATCH_BYTES in the
+ * source; each GPU the entry point is used on holds its own copy from first use until the process
+ * ends).  The call allocates and frees nothing, on the device or through any allocating library.
+ *  - Shapes whose scratch (rapid_workspace_min_bytes(RAPID_OP_LOGPROB_FWD, ...)) exceeds the array
+ *    are refused with RAPID_ERR_WORKSPACE before any launch; the message names both sizes.  The
+ *    Qwen2.5-3B-shaped head (d = 2048, V = 151936, bf16) fits with up to 4096 positions per call.
+ *  - The first call on a device looks the array's address up (hipGetSymbolAddress, once per device,
+ *    kept): make that first call outside stream capture.
+ *  - All calls on one GPU share that GPU's array, which keeps the previous call's contents (every
+ *    word a call reads it has written itself first): calls that overlap in time on one GPU, on
+ *    whatever streams, race.  Serialise them.
+ */
+int rapid_logprob_fwd_static(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
+                             int64_t N, int64_t T, int64_t d, int64_t V, int dtype, int w_layout,
+                             float temperature, float* logp_out, float* lse_out, int32_t* dev_status,
+                             void* stream);
+
 /* rapid_logprob_fwd on h = hidden * rms_weight / sqrt(mean(hidden^2) + rms_eps) (see
  * rapid_iw_pg_opts.rms_weight; rms_weight: DEVICE [d] bf16, dtype must be RAPID_DTYPE_BF16): the
  * log-probs a behaviour policy with that final norm assigns.  Same workspace size, same errors,

@@ -25,7 +25,8 @@ STATUS_GROUP_LAYOUT = 64
 
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_workspace_bytes_max_tokens", "rapid_logprob_fwd", "rapid_logprob_fwd_rmsnorm",
-           "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step"]
+           "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step",
+           "rapid_logprob_fwd_static"]
 STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
           "dw", "f32_path", "dw_convert"]
 
@@ -76,6 +77,8 @@ def load():
     lib.rapid_workspace_bytes_max_tokens.restype = sz
     lib.rapid_logprob_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, f32, vp, vp, vp, vp, sz, vp]
     lib.rapid_logprob_fwd.restype = ci
+    lib.rapid_logprob_fwd_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, f32, vp, vp, vp, vp]
+    lib.rapid_logprob_fwd_static.restype = ci
     lib.rapid_logprob_fwd_rmsnorm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, f32, vp, f32, vp, vp, vp, vp, sz, vp]
     lib.rapid_logprob_fwd_rmsnorm.restype = ci
     lib.rapid_group_advantage.argtypes = [vp, vp, vp, i64, i64, f32, ci, vp, vp, vp, vp, vp, vp, vp]
@@ -200,6 +203,24 @@ def rapid_logprob_fwd(hidden, W, tokens, mask, w_layout=W_DV, temperature=1.0, w
                                     float(temperature), _ptr(logp), _ptr(lse), _ptr(dev_status),
                                     _ptr(workspace), workspace.numel(), _stream()))
     return logp, lse
+
+
+def rapid_logprob_fwd_static(hidden, W, tokens, mask, logp_out, lse_out=None, w_layout=W_DV, temperature=1.0,
+                             dev_status=None):
+    """rapid_logprob_fwd on the library's static scratch: no workspace, and nothing is allocated here
+    either (the caller brings the outputs).  Returns (logp_out, lse_out)."""
+    N, T, d = hidden.shape
+    V = W.shape[1] if w_layout == W_DV else W.shape[0]
+    dt = _dtype_code(hidden)
+    _need(hidden, hidden.dtype, "hidden"); _need(W, hidden.dtype, "W")
+    _need(tokens, torch.int32, "tokens"); _need(mask, torch.uint8, "mask")
+    _need(logp_out, torch.float32, "logp_out")
+    if lse_out is not None:
+        _need(lse_out, torch.float32, "lse_out")
+    _check(load().rapid_logprob_fwd_static(_ptr(hidden), _ptr(W), _ptr(tokens), _ptr(mask), N, T, d, V, dt, w_layout,
+                                           float(temperature), _ptr(logp_out), _ptr(lse_out), _ptr(dev_status),
+                                           _stream()))
+    return logp_out, lse_out
 
 
 def rapid_group_advantage(rewards, group_ids, K, seq_logratio=None, eta=2.0, baseline_mode=0,

@@ -6,9 +6,17 @@
 
 #include <atomic>
 #include <cmath>
+#include <mutex>
 
 #include "rapid_internal.h"
 #include "rapid_tuning.h"
+
+// Scratch of rapid_logprob_fwd_static, the entry point for callers that cannot allocate device
+// memory.  Every GPU the library is used on holds its own copy at its own address from the moment
+// this code object is loaded there until the process ends.  In host code the name is only a handle
+// for hipGetSymbolAddress: the per-device address it returns is what kernels and fills are given.
+#define RAPID_STATIC_SCRATCH_BYTES ((size_t)768 << 20)
+static __device__ __align__(256) unsigned char scratch[RAPID_STATIC_SCRATCH_BYTES];
 
 namespace rapid {
 
@@ -33,6 +41,31 @@ std::atomic<int> g_cached_step_tiles{256};    // row tiles per dHidden / dW laun
 std::atomic<int> g_pace_every{0};             // K steps between meetings of the dHidden workgroups (tuning key 16; 0 = off)
 std::atomic<int> g_fwd_block_tiles{64};       // row tiles per launch of the two logits kernels (tuning key 13)
 std::atomic<int> g_dh_split{1};               // dHidden cuts the tiles of a partly filled last round along the contraction (tuning key 17)
+
+// address of `scratch` on each device, looked up once per device with that device current
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        set_error("hipGetDevice failed, or device index beyond %d", MAX_DEVICES - 1);
+        return RAPID_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            set_error("hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+            return RAPID_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return RAPID_OK;
+}
 
 // Optional per-stage timing with HIP events on the caller's stream (off by default).
 enum Stage { ST_COMPACT = 0, ST_PACK, ST_FWD_LSE, ST_MERGE, ST_ESTIMATOR, ST_ZERO, ST_DZ, ST_DZ_T, ST_DH, ST_DW,
@@ -638,6 +671,27 @@ int rapid_logprob_fwd(const void* hidden, const void* W, const int32_t* tokens, 
                       float* lse_out, int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream) {
     return logprob_fwd(hidden, W, tokens, mask, N, T, d, V, dtype, w_layout, temperature, nullptr, 0.f, logp_out,
                        lse_out, dev_status, workspace, workspace_bytes, stream);
+}
+
+int rapid_logprob_fwd_static(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask, int64_t N,
+                             int64_t T, int64_t d, int64_t V, int dtype, int w_layout, float temperature,
+                             float* logp_out, float* lse_out, int32_t* dev_status, void* stream) {
+    const size_t need = rapid_workspace_min_bytes(RAPID_OP_LOGPROB_FWD, N, T, d, V, 1, dtype);
+    if (need == 0) {
+        set_error("bad shape/dtype N=%lld T=%lld d=%lld V=%lld dtype=%d", (long long)N, (long long)T, (long long)d,
+                  (long long)V, dtype);
+        return (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) ? RAPID_ERR_DTYPE : RAPID_ERR_SHAPE;
+    }
+    if (need > RAPID_STATIC_SCRATCH_BYTES) {
+        set_error("rapid_logprob_fwd_static: this shape needs %zu bytes of scratch, the static scratch holds %zu; "
+                  "use rapid_logprob_fwd with a workspace", need, (size_t)RAPID_STATIC_SCRATCH_BYTES);
+        return RAPID_ERR_WORKSPACE;
+    }
+    void* ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc) return rc;
+    return logprob_fwd(hidden, W, tokens, mask, N, T, d, V, dtype, w_layout, temperature, nullptr, 0.f, logp_out,
+                       lse_out, dev_status, ptr, RAPID_STATIC_SCRATCH_BYTES, stream);
 }
 
 int rapid_logprob_fwd_rmsnorm(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask, int64_t N,

@@ -135,6 +135,13 @@ def test_host_validation_returns_codes_without_a_gpu(rb):
                                          None, one, 1 << 30, None) == -3
     assert lib.rapid_logprob_fwd_rmsnorm(one, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, None, 1e-6, one, None,
                                          None, one, 1 << 30, None) == -1
+    # the entry point on the static scratch: shapes past its 768 MiB are refused on the host, with both sizes named
+    assert lib.rapid_logprob_fwd_static(one, one, one, one, 256, 2048, 1536, 151936, rb.DTYPE_BF16, rb.W_DV, 1.0, one,
+                                        None, None, None) == -4
+    assert b"static scratch holds 805306368" in lib.rapid_last_error()
+    assert lib.rapid_logprob_fwd_static(one, one, one, one, 0, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, None) == -2
+    assert lib.rapid_logprob_fwd_static(one, one, one, one, 4, 4, 8, 8, 5, rb.W_DV, 1.0, one, None, None, None) == -3
+    assert lib.rapid_logprob_fwd_static(None, one, one, one, 4, 4, 8, 8, rb.DTYPE_BF16, rb.W_DV, 1.0, one, None, None, None) in (-1, -6)
     o = rb.default_opts()
     o.loss_scale = -1.0
     assert lib.rapid_iw_pg_loss_fwd_bwd(*args()) == -2
