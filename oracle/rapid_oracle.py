@@ -16,6 +16,8 @@ Every function restates a passage of the RAPID paper (arXiv 2510.03515):
   generation first, the clip acts on the generation-level ratio.
 * Appendix A, RL hyper-parameter table: eta = 2.0.
 * Sec. 4.3, first paragraph: staleness = mean of the clipped weight in log scale.
+* Sec. 4.1, "Baselines", and Appendix A (KL coefficient 0.04, GRPO only): the loss steps of GRPO and
+  DAPO, restated at the end of this file from the papers the RAPID paper cites for them.
 
 Readings of the paper taken here (each also listed in the design document):
 
@@ -334,3 +336,106 @@ def compaction(mask):
     cu[1:] = np.cumsum(seq_len)
     row_index = np.flatnonzero(msk.reshape(-1)).astype(np.int64)
     return seq_len, cu, row_index
+
+
+# ----------------------------------------------------------------------------------------------------
+# Loss steps of the paper's RL baselines (Sec. 4.1, "Baselines": GRPO, Shao et al. 2024; DAPO, Yu et
+# al. 2025; Appendix A: KL coefficient 0.04 for GRPO only).  The paper does not print their objectives:
+# they are restated here from the cited papers, for a like-for-like comparison of the loss step on the
+# same kernels.  Parity unpinned by the paper; pinned by hand values, special cases and finite
+# differences of an objective written with explicit loops (tests).
+
+def normalized_group_advantage(rewards, group_ids, K, adv_eps=1e-4, std_ddof=0):
+    """A_n = (R_n - mean_k) / (std_k + adv_eps) over the group k of n (GRPO's outcome-supervision
+    advantage; DAPO uses the same).  std_ddof 0: population std (1/N_k), 1: sample std (1/(N_k - 1)),
+    0 for a group of one.  A group whose rewards are all equal has std 0 and A = 0 / adv_eps = 0: it
+    carries no policy-gradient signal (the reading taken for the zero-std case).
+    Returns dict(adv, group_mean, group_std, group_size)."""
+    R = _as64(rewards)
+    gid = np.asarray(group_ids).astype(np.int64)
+    N = R.shape[0]
+    if (gid < 0).any() or (gid >= K).any():
+        raise ValueError("group id outside [0, K)")
+    size = np.zeros(K, np.int64)
+    mean = np.zeros(K, _F)
+    std = np.zeros(K, _F)
+    for k in range(K):
+        members = [n for n in range(N) if gid[n] == k]
+        size[k] = len(members)
+        if members:
+            mean[k] = sum(R[n] for n in members) / len(members)
+            ss = sum((R[n] - mean[k]) ** 2 for n in members)
+            den = len(members) - std_ddof
+            std[k] = math.sqrt(ss / den) if den > 0 else 0.0
+    adv = np.zeros(N, _F)
+    for n in range(N):
+        num = R[n] - mean[gid[n]]
+        adv[n] = num / (std[gid[n]] + adv_eps) if num != 0.0 else 0.0     # 0 / 0 (equal rewards, adv_eps = 0) is 0
+    return dict(adv=adv, group_mean=mean, group_std=std, group_size=size)
+
+
+def clipped_token_coefficients(logp_cur, logp_old, logp_ref, mask, adv, eps_low=0.2, eps_high=0.2, kl_beta=0.0,
+                               norm_mode=0, loss_scale=1.0):
+    """Token-level clipped surrogate with an optional KL penalty, and its derivative with respect to
+    the current log-probs.
+
+    r_{n,t} = exp(logp_cur - logp_old)                                  (token-level ratio)
+    surr    = min(r A_n, clip(r, 1 - eps_low, 1 + eps_high) A_n)        (PPO-style clip; GRPO: 0.2 / 0.2,
+                                                                         DAPO: 0.2 / 0.28, "clip-higher")
+    kl      = exp(logp_ref - logp_cur) - (logp_ref - logp_cur) - 1      (the unbiased, non-negative estimator
+                                                                         GRPO uses; kl_beta = 0.04 in Appendix A,
+                                                                         0 for DAPO, which drops the term)
+    L = - loss_scale * sum_{n,t valid} omega_{n,t} (surr - kl_beta * kl)
+    omega = 1 / (N L_n)   norm_mode 0: mean over a generation's tokens, then over generations (GRPO)
+          = 1 / M         norm_mode 1: mean over all M valid tokens of the call (DAPO's token-level loss)
+    d surr / d logp_cur = r A_n where the unclipped term is the minimum (ties included), else 0: a token
+    whose ratio has left the clip range in the direction its advantage pushes gets no gradient.
+    d kl / d logp_cur = 1 - exp(logp_ref - logp_cur).
+    Returns (g [N,T] = dL/dlogp_cur, loss, dict(clip_fraction, mean_kl))."""
+    cur, old = _as64(logp_cur), _as64(logp_old)
+    msk = np.asarray(mask) != 0
+    A = _as64(adv)
+    N, T = cur.shape
+    M = int(msk.sum())
+    g = np.zeros((N, T), _F)
+    loss = 0.0
+    n_clipped = 0
+    kl_sum = 0.0
+    for n in range(N):
+        L = int(msk[n].sum())
+        for t in range(T):
+            if not msk[n, t]:
+                continue
+            omega = loss_scale / (N * L) if norm_mode == 0 else loss_scale / M
+            r = math.exp(cur[n, t] - old[n, t])
+            rc = min(max(r, 1.0 - eps_low), 1.0 + eps_high)
+            unclipped, clipped = r * A[n], rc * A[n]
+            surr = min(unclipped, clipped)
+            dsurr = r * A[n] if unclipped <= clipped else 0.0
+            if unclipped > clipped:
+                n_clipped += 1
+            kl = dkl = 0.0
+            if kl_beta != 0.0:
+                dref = float(logp_ref[n, t]) - cur[n, t]
+                kl = math.exp(dref) - dref - 1.0
+                dkl = 1.0 - math.exp(dref)
+                kl_sum += kl
+            loss -= omega * (surr - kl_beta * kl)
+            g[n, t] = -omega * (dsurr - kl_beta * dkl)
+    return g, loss, dict(clip_fraction=n_clipped / M if M else 0.0, mean_kl=kl_sum / M if M else 0.0)
+
+
+def clipped_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_old, logp_ref, rewards, group_ids, K, eps_low=0.2,
+                            eps_high=0.2, kl_beta=0.0, norm_mode=0, adv_eps=1e-4, std_ddof=0, loss_scale=1.0,
+                            temperature=1.0, row_chunk=2048):
+    """One loss step of GRPO (eps 0.2 / 0.2, kl_beta 0.04, norm_mode 0) or DAPO (eps 0.2 / 0.28, kl_beta 0,
+    norm_mode 1) through the LM head: current log-probs, std-normalised group advantages, the clipped
+    token-level surrogate above, and its gradients with respect to hidden and W."""
+    logp_cur, lse = logprob(hidden, W, tokens, mask, temperature, row_chunk)
+    ga = normalized_group_advantage(rewards, group_ids, K, adv_eps, std_ddof)
+    g, loss, diag = clipped_token_coefficients(logp_cur, logp_old, logp_ref, mask, ga["adv"], eps_low, eps_high, kl_beta,
+                                               norm_mode, loss_scale)
+    dH, dW = backward(hidden, W, tokens, mask, g, temperature, row_chunk)
+    return dict(loss=loss, dH=dH, dW=dW, logp_cur=logp_cur, adv=ga["adv"], g=g, group_mean=ga["group_mean"],
+                group_std=ga["group_std"], group_size=ga["group_size"], clip_fraction=diag["clip_fraction"],
+                mean_kl=diag["mean_kl"], n_tokens=int((np.asarray(mask) != 0).sum()))

@@ -2,7 +2,7 @@
 seeded synthetic inputs small enough for the oracle to finish in seconds but spanning several
 tiles and ragged tails.  Tolerances: integer/index outputs bit-exact; loss rel <= 1e-3;
 dHidden/dW relative (Frobenius) error <= 2e-2 in bf16 and <= 1e-5 in fp32, and every single
-element of both within 2^-7 (bf16; 1e-5 fp32) of the largest magnitude in its token row (dHidden) or
+element of both within 3 * 2^-8 (bf16; 1e-5 fp32) of the largest magnitude in its token row (dHidden) or
 vocabulary column (dW) of the oracle's tensor (parity_bounds.py)."""
 import math
 
@@ -266,7 +266,7 @@ def test_dw_bf16_and_accumulate(rb):
     assert _rel(_np(buf.dW) - 0.5, ref["dW"]) <= GRAD_RTOL["bf16"]
     # element by element, up to the fp32 rounding of 0.5 + x (half an ulp of 0.5 = 3e-8)
     err = np.abs(_np(buf.dW) - 0.5 - ref["dW"])
-    assert np.all(err <= 2.0 ** -7 * np.abs(ref["dW"]).max(axis=0, keepdims=True) + 6e-8)
+    assert np.all(err <= 3 * 2.0 ** -8 * np.abs(ref["dW"]).max(axis=0, keepdims=True) + 6e-8)
 
 
 @pytest.mark.parametrize("name", ["f32_cfg0", "bf16_small"])
@@ -636,7 +636,7 @@ def test_cached_backward_in_chunks_of_whole_groups(rb, size):
         torch.cuda.synchronize()
         want = ref["dW"] if norm else ref["dW"] * math.exp(ref["grad_log_scale"])
         err = np.abs(_np(out.dW) - 0.25 - want)
-        assert np.all(err <= 2.0 ** -7 * np.abs(want).max(axis=0, keepdims=True) + 6e-8), norm
+        assert np.all(err <= 3 * 2.0 ** -8 * np.abs(want).max(axis=0, keepdims=True) + 6e-8), norm
     # the final norm on the way in and out
     rng = np.random.default_rng(32)
     x = (g["hidden"].float() * torch.from_numpy(rng.uniform(0.3, 3.0, size=(N, T, 1))).float().cuda()).to(torch.bfloat16)

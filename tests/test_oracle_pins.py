@@ -603,3 +603,147 @@ def test_compaction():
     assert row_index.tolist() == ref_rows
     assert seq_len.tolist() == [int(mask[n].sum()) for n in range(5)]
     assert cu.tolist() == [0] + list(itertools.accumulate(seq_len.tolist()))
+
+
+# ---------------------------------------------------------------- baseline loss steps (GRPO, DAPO)
+def _py_clipped_objective(H, W, tok, mask, logp_old, logp_ref, adv, eps_low, eps_high, beta, norm_mode):
+    """The loss of the clipped token-level surrogate written out with explicit loops (independent of
+    the oracle's code): - sum omega (min(r A, clip(r) A) - beta kl)."""
+    N, T = len(tok), len(tok[0])
+    M = sum(1 for n in range(N) for t in range(T) if mask[n][t])
+    tot = 0.0
+    for n in range(N):
+        L = sum(1 for t in range(T) if mask[n][t])
+        for t in range(T):
+            if not mask[n][t]:
+                continue
+            lp = _py_logsoftmax_at(H[n][t], W, tok[n][t])
+            r = math.exp(lp - logp_old[n][t])
+            surr = min(r * adv[n], max(min(r, 1 + eps_high), 1 - eps_low) * adv[n])
+            kl = 0.0
+            if beta:
+                dlt = logp_ref[n][t] - lp
+                kl = math.exp(dlt) - dlt - 1.0
+            tot += (surr - beta * kl) / (N * L if norm_mode == 0 else M)
+    return -tot
+
+
+def test_clipped_surrogate_hand_example():
+    rows = np.array([l.split() for l in open(os.path.join(GOLDEN, "clipped_surrogate_hand_example.txt"))
+                     if l.strip() and not l.startswith("#")], dtype=np.float64)
+    r = rows[:, 2].reshape(2, 2)
+    A = np.array([1.0, -1.0])
+    cur = np.log(r)                  # logp_old = 0
+    g, loss, diag = orc.clipped_token_coefficients(cur, np.zeros((2, 2)), None, np.ones((2, 2)), A, 0.2, 0.2, 0.0, 0)
+    assert abs(loss - (-0.05)) < 1e-15
+    assert np.allclose(g.reshape(-1), -0.25 * rows[:, 4], atol=1e-15) and np.allclose(g.reshape(-1), [0, -0.225, 0, 0.275], atol=1e-15)
+    assert diag["clip_fraction"] == 0.5 == rows[:, 5].mean()
+    # token-level normalisation (DAPO): the same here, every generation has two tokens
+    g1, loss1, _ = orc.clipped_token_coefficients(cur, np.zeros((2, 2)), None, np.ones((2, 2)), A, 0.2, 0.2, 0.0, 1)
+    assert np.array_equal(g, g1) and loss == loss1
+    # clip-higher (DAPO's eps_high = 0.28): the 1.5 token is still clipped, now at 1.28
+    _, loss2, _ = orc.clipped_token_coefficients(cur, np.zeros((2, 2)), None, np.ones((2, 2)), A, 0.2, 0.28, 0.0, 1)
+    assert abs(loss2 - (-0.25 * (1.28 + 0.9 - 0.8 - 1.1))) < 1e-15
+    # the KL estimator and its derivative at log(pi_ref / pi) = ln 2, ln 0.5, 0 (one generation of three tokens, A = 0)
+    ref = np.array([[math.log(2.0), math.log(0.5), 0.0]])
+    g, loss, diag = orc.clipped_token_coefficients(np.zeros((1, 3)), np.zeros((1, 3)), ref, np.ones((1, 3)), np.zeros(1),
+                                                   0.2, 0.2, 0.04, 0)
+    kl = np.array([0.3068528194400547, 0.1931471805599453, 0.0])
+    assert abs(loss - 0.04 * kl.sum() / 3) < 1e-15 and abs(diag["mean_kl"] - kl.mean()) < 1e-15
+    assert np.allclose(g[0], 0.04 / 3 * np.array([-1.0, 0.5, 0.0]), atol=1e-15)     # dL/dlogp = omega beta (1 - exp(ref - cur))
+
+
+def test_normalized_group_advantage():
+    R = np.array([1.0, 0.0, 1.0, 1.0, 0.3, 0.3, 0.3, 7.0])
+    gid = np.array([0, 0, 0, 0, 1, 1, 1, 2])
+    out = orc.normalized_group_advantage(R, gid, 4, adv_eps=0.0, std_ddof=0)
+    # group 0: mean 0.75, population std sqrt(3/16) = 0.4330127: A = (0.25, -0.75, 0.25, 0.25) / 0.4330127
+    assert np.allclose(out["adv"][:4], np.array([0.25, -0.75, 0.25, 0.25]) / math.sqrt(3.0 / 16.0), atol=1e-15)
+    assert abs(out["adv"][:4].sum()) < 1e-15 and abs((out["adv"][:4] ** 2).mean() - 1.0) < 1e-14    # zero mean, unit variance
+    eps = orc.normalized_group_advantage(R, gid, 4, adv_eps=1e-4)
+    assert np.all(eps["adv"][4:] == 0.0)              # equal rewards, and a group of one: no signal
+    assert eps["group_size"].tolist() == [4, 3, 1, 0] and eps["group_std"][1] == 0.0
+    assert np.allclose(eps["adv"][:4], np.array([0.25, -0.75, 0.25, 0.25]) / (math.sqrt(3.0 / 16.0) + 1e-4), atol=1e-15)
+    s1 = orc.normalized_group_advantage(R, gid, 4, adv_eps=0.0, std_ddof=1)
+    assert np.allclose(s1["adv"][:4], np.array([0.25, -0.75, 0.25, 0.25]) / math.sqrt(0.25), atol=1e-15)   # sample std: sqrt(0.75/3)
+    assert s1["adv"][7] == 0.0 and np.allclose(s1["group_std"][:3], np.array([0.5, 0.0, 0.0]))
+    assert np.allclose(np.array([R[:4].std(), R[:4].std(ddof=1)]), [out["group_std"][0], s1["group_std"][0]])    # numpy leg
+
+
+@pytest.mark.parametrize("variant", ["grpo", "dapo"])
+def test_clipped_pg_finite_differences_and_autograd(variant):
+    kw = dict(grpo=dict(eps_low=0.2, eps_high=0.2, kl_beta=0.04, norm_mode=0),
+              dapo=dict(eps_low=0.2, eps_high=0.28, kl_beta=0.0, norm_mode=1))[variant]
+    H, W, W_old, tok, mask, R, gid, logp_old = _tiny(31, N=4, T=3, d=3, V=5, G=2)
+    rng = np.random.default_rng(5)
+    logp_old = logp_old + mask * rng.normal(size=logp_old.shape) * 0.3      # ratios spread around 1: some clip
+    logp_ref = logp_old + mask * rng.normal(size=logp_old.shape) * 0.2
+    out = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, logp_old, logp_ref, R, gid, 2, **kw)
+    assert 0.0 < out["clip_fraction"] < 1.0
+    # no ratio sits on a clip boundary (the objective has a kink there)
+    r = np.exp(out["logp_cur"] - logp_old)[mask != 0]
+    assert np.abs(r - (1 - kw["eps_low"])).min() > 1e-3 and np.abs(r - (1 + kw["eps_high"])).min() > 1e-3
+    f = lambda Hx, Wx: _py_clipped_objective(Hx.tolist(), Wx.tolist(), tok.tolist(), mask.tolist(), logp_old.tolist(),
+                                             logp_ref.tolist(), out["adv"].tolist(), kw["eps_low"], kw["eps_high"],
+                                             kw["kl_beta"], kw["norm_mode"])
+    assert abs(f(H, W) - out["loss"]) < 1e-14
+    h = 1e-6
+    for idx in np.ndindex(W.shape):
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += h; Wm[idx] -= h
+        assert abs((f(H, Wp) - f(H, Wm)) / (2 * h) - out["dW"][idx]) < 1e-7, idx
+    for idx in np.ndindex(H.shape):
+        Hp, Hm = H.copy(), H.copy()
+        Hp[idx] += h; Hm[idx] -= h
+        fd = (f(Hp, W) - f(Hm, W)) / (2 * h)
+        assert abs(fd - out["dH"][idx]) < 1e-7, idx
+        if mask[idx[0], idx[1]] == 0:
+            assert out["dH"][idx] == 0.0
+    # library leg: torch autograd of the same objective in plain tensor ops gives the oracle's dL/dlogp
+    lp = torch.tensor(out["logp_cur"], requires_grad=True)
+    m = torch.tensor(mask.astype(np.float64))
+    A = torch.tensor(out["adv"])[:, None]
+    ratio = torch.exp(lp - torch.tensor(logp_old))
+    surr = torch.minimum(ratio * A, torch.clamp(ratio, 1 - kw["eps_low"], 1 + kw["eps_high"]) * A)
+    dref = torch.tensor(logp_ref) - lp
+    per_tok = (surr - kw["kl_beta"] * (torch.exp(dref) - dref - 1)) * m
+    loss = -(per_tok.sum(1) / m.sum(1)).mean() if kw["norm_mode"] == 0 else -per_tok.sum() / m.sum()
+    loss.backward()
+    assert abs(loss.item() - out["loss"]) < 1e-14 and np.allclose(lp.grad.numpy(), out["g"], atol=1e-15)
+
+
+def test_clipped_pg_special_cases():
+    H, W, W_old, tok, mask, R, gid, _ = _tiny(33, N=6, T=4, d=3, V=6, G=3)
+    cur, _ = orc.logprob(H, W, tok, mask)
+    # (a) equal policies, no KL: every ratio is 1, nothing clips, and the gradient is that of the plain
+    # group-relative policy gradient with the normalised advantages, - omega A_n per valid token
+    out = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, cur, None, R, gid, 2, kl_beta=0.0, norm_mode=0)
+    L = mask.sum(1)
+    want = -(out["adv"] / (6 * L))[:, None] * (mask != 0)
+    assert np.allclose(out["g"], want, atol=1e-16) and out["clip_fraction"] == 0.0
+    dH, dW = orc.backward(H, W, tok, mask, want)
+    assert np.allclose(out["dW"], dW, atol=1e-16) and np.allclose(out["dH"], dH, atol=1e-16)
+    # its loss is - mean_n A_n, which is 0 for complete groups (advantages sum to zero per group)
+    assert abs(out["loss"]) < 1e-14
+    # (b) reference = current policy: the KL term and its gradient vanish
+    with_kl = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, cur, cur, R, gid, 2, kl_beta=0.04)
+    assert with_kl["mean_kl"] == 0.0 and np.array_equal(with_kl["g"], out["g"])
+    # (c) the KL estimator is non-negative and pulls the policy towards the reference
+    ref = cur + 0.5 * (mask != 0)
+    k = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, cur, ref, np.zeros(6), gid, 2, kl_beta=0.04)
+    assert k["mean_kl"] > 0 and k["loss"] > 0 and np.all(k["g"][mask != 0] < 0)        # descent raises log pi where pi_ref > pi
+    # (d) the two normalisations agree when all generations have the same length, and differ otherwise
+    full = np.ones_like(mask)
+    cur_f, _ = orc.logprob(H, W, tok, full)
+    old_f = cur_f + 0.1
+    a = orc.clipped_pg_loss_fwd_bwd(H, W, tok, full, old_f, None, R, gid, 2, norm_mode=0)
+    b = orc.clipped_pg_loss_fwd_bwd(H, W, tok, full, old_f, None, R, gid, 2, norm_mode=1)
+    assert abs(a["loss"] - b["loss"]) < 1e-15 and np.allclose(a["dW"], b["dW"], atol=1e-16)
+    if len(set(L.tolist())) > 1:
+        a = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, cur + 0.1 * (mask != 0), None, R, gid, 2, norm_mode=0)
+        b = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, cur + 0.1 * (mask != 0), None, R, gid, 2, norm_mode=1)
+        assert abs(a["loss"] - b["loss"]) > 1e-6
+    # (e) a group with equal rewards contributes nothing to the surrogate (A = 0): only the KL term is left
+    Rz = R.copy(); Rz[:3] = 0.5          # exactly representable: the group mean is exact
+    z = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, cur + 0.2 * (mask != 0), None, Rz, gid, 2)
+    assert np.all(z["adv"][:3] == 0.0) and np.all(z["g"][:3] == 0.0) and np.any(z["g"][3:] != 0.0)
