@@ -253,6 +253,53 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
                              size_t workspace_bytes, void* stream);
 
 /*
+ * Loss steps of the paper's RL baselines on the same kernels (Sec. 4.1, "Baselines": GRPO and DAPO; Appendix A:
+ * KL coefficient 0.04 for GRPO only), for a like-for-like comparison of one update step.  The paper does not
+ * print their objectives; they follow the papers it cites for them:
+ *   A_n     = (R_n - mean_k) / (std_k + adv_eps)   over the group k of n (std with divisor N_k - std_ddof; a group
+ *             of equal rewards has A = 0)
+ *   r_{n,t} = exp(logp_cur - logp_old)             token-level ratio (logp_old == NULL: all ratios 1)
+ *   surr    = min(r A_n, clip(r, 1 - eps_low, 1 + eps_high) A_n)
+ *   kl      = exp(logp_ref - logp_cur) - (logp_ref - logp_cur) - 1     (only if kl_beta != 0; logp_ref required then)
+ *   loss    = - loss_scale sum_{valid n,t} omega_{n,t} (surr - kl_beta kl)
+ *   omega   = 1 / (N L_n)  (norm_mode 0: mean over a generation's tokens, then over the N generations: GRPO)
+ *           = 1 / M        (norm_mode 1: mean over the M valid tokens of the call: DAPO)
+ * and its gradients dhidden and dW through the LM head, as in rapid_iw_pg_loss_fwd_bwd (same layouts, same
+ * workspace sizes: RAPID_OP_IW_PG_FWD_BWD, or RAPID_OP_IW_PG_FWD_BWD_CACHED with logits_cache = 1, same
+ * conditions).  A token whose ratio has left the clip range in the direction its advantage pushes gets no
+ * gradient from the surrogate.  rapid_clip_pg_default_opts: variant 0 = GRPO (eps 0.2 / 0.2, kl_beta 0.04, norm_mode 0),
+ * 1 = DAPO (eps 0.2 / 0.28, kl_beta 0, norm_mode 1; its sample filtering and reward shaping are the caller's).
+ * Optional outputs (NULL to skip): logp_cur_out [N,T], adv_out [N], diag_out (device).
+ */
+typedef struct rapid_clip_pg_opts {
+    float eps_low, eps_high;
+    float kl_beta;
+    int norm_mode;
+    float adv_eps;         /* 1e-4 */
+    int std_ddof;          /* 0 (default): population std; 1: sample std (0 for a group of one) */
+    float loss_scale;
+    float temperature;
+    int w_layout, dw_dtype, accumulate_dw, logits_cache;   /* as in rapid_iw_pg_opts */
+    int64_t max_tokens;    /* as in rapid_iw_pg_opts */
+} rapid_clip_pg_opts;
+
+typedef struct rapid_clip_pg_diag {
+    int64_t n_tokens;
+    int64_t n_clipped;     /* tokens whose surrogate took the clipped branch */
+    int32_t n_sequences;
+    float mean_kl;         /* mean over valid tokens of the KL estimate (0 without the term) */
+} rapid_clip_pg_diag;
+
+void rapid_clip_pg_default_opts(rapid_clip_pg_opts* opts, int variant);
+
+int rapid_clip_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
+                               const float* logp_old, const float* logp_ref, const float* rewards,
+                               const int32_t* group_ids, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K,
+                               int dtype, const rapid_clip_pg_opts* opts, float* loss_out, void* dhidden_out,
+                               void* dW_out, float* logp_cur_out, float* adv_out, rapid_clip_pg_diag* diag_out,
+                               int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The parameter update of Alg. 1's inner loop (the step after the gradient of Eq. (3)), for
  * the LM head alone and as plain gradient descent on the returned loss:
  *   master[i] -= lr * grad[i]   (fp32, n elements, same layout as dW_out)

@@ -26,7 +26,7 @@ STATUS_GROUP_LAYOUT = 64
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_workspace_bytes_max_tokens", "rapid_logprob_fwd", "rapid_logprob_fwd_rmsnorm",
            "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step",
-           "rapid_logprob_fwd_static"]
+           "rapid_logprob_fwd_static", "rapid_clip_pg_default_opts", "rapid_clip_pg_loss_fwd_bwd"]
 STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
           "dw", "f32_path", "dw_convert"]
 
@@ -44,6 +44,17 @@ class IwPgOpts(C.Structure):
                 ("logits_cache", C.c_int), ("ratio_level", C.c_int), ("max_tokens", C.c_int64),
                 ("coef_override", C.c_void_p), ("rms_weight", C.c_void_p), ("drms_weight_out", C.c_void_p),
                 ("rms_eps", C.c_float)]
+
+
+class ClipPgOpts(C.Structure):
+    _fields_ = [("eps_low", C.c_float), ("eps_high", C.c_float), ("kl_beta", C.c_float), ("norm_mode", C.c_int),
+                ("adv_eps", C.c_float), ("std_ddof", C.c_int), ("loss_scale", C.c_float), ("temperature", C.c_float),
+                ("w_layout", C.c_int), ("dw_dtype", C.c_int), ("accumulate_dw", C.c_int), ("logits_cache", C.c_int),
+                ("max_tokens", C.c_int64)]
+
+
+class ClipPgDiag(C.Structure):
+    _fields_ = [("n_tokens", C.c_int64), ("n_clipped", C.c_int64), ("n_sequences", C.c_int32), ("mean_kl", C.c_float)]
 
 
 class IwPgDiag(C.Structure):
@@ -86,6 +97,11 @@ def load():
     lib.rapid_iw_pg_loss_fwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci,
                                              C.POINTER(IwPgOpts), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.rapid_iw_pg_loss_fwd_bwd.restype = ci
+    lib.rapid_clip_pg_default_opts.argtypes = [C.POINTER(ClipPgOpts), ci]
+    lib.rapid_clip_pg_default_opts.restype = None
+    lib.rapid_clip_pg_loss_fwd_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, ci,
+                                               C.POINTER(ClipPgOpts), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.rapid_clip_pg_loss_fwd_bwd.restype = ci
     lib.rapid_compaction.argtypes = [vp, i64, i64, vp, vp, vp, vp]
     lib.rapid_compaction.restype = ci
     lib.rapid_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64), ci]
@@ -324,3 +340,51 @@ def rapid_iw_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_behav, rewards, group
         _ptr(b.seq_logratio) if opt else None, _ptr(b.adv) if opt else None,
         _ptr(b.diag) if opt else None, _ptr(b.dev_status), _ptr(b.workspace), b.workspace.numel(), _stream()))
     return b
+
+
+def clip_pg_default_opts(variant="grpo"):
+    o = ClipPgOpts()
+    load().rapid_clip_pg_default_opts(C.byref(o), {"grpo": 0, "dapo": 1}[variant])
+    return o
+
+
+def rapid_clip_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_old, logp_ref, rewards, group_ids, K, variant="grpo",
+                               buffers=None, w_layout=W_DV, accumulate_dw=False, logits_cache=False, max_tokens=0,
+                               optional_outputs=True, **overrides):
+    """The loss step of the GRPO ("grpo") or DAPO ("dapo") baseline on the current stream; `overrides` replace
+    fields of the variant's default options (eps_low, eps_high, kl_beta, norm_mode, adv_eps, std_ddof, loss_scale,
+    temperature).  Returns the IwPgBuffers that hold loss, dhidden, dW, logp_cur, adv; the call's diagnostics are in
+    buffers.clip_diag (read_clip_diag)."""
+    N, T, d = hidden.shape
+    V = W.shape[1] if w_layout == W_DV else W.shape[0]
+    dt = _dtype_code(hidden)
+    _need(hidden, hidden.dtype, "hidden"); _need(W, hidden.dtype, "W")
+    _need(tokens, torch.int32, "tokens"); _need(mask, torch.uint8, "mask")
+    for t, name in ((logp_old, "logp_old"), (logp_ref, "logp_ref")):
+        if t is not None:
+            _need(t, torch.float32, name)
+    _need(rewards, torch.float32, "rewards"); _need(group_ids, torch.int32, "group_ids")
+    if buffers is None:
+        buffers = IwPgBuffers(hidden, W, K, w_layout, logits_cache=logits_cache, max_tokens=max_tokens)
+    b = buffers
+    if getattr(b, "clip_diag", None) is None:
+        b.clip_diag = torch.zeros(C.sizeof(ClipPgDiag), dtype=torch.uint8, device=hidden.device)
+    o = clip_pg_default_opts(variant)
+    for k, v in overrides.items():
+        if not hasattr(o, k):
+            raise TypeError(f"unknown option {k}")
+        setattr(o, k, v)
+    o.w_layout, o.dw_dtype = int(w_layout), _dtype_code(b.dW)
+    o.accumulate_dw, o.logits_cache, o.max_tokens = int(bool(accumulate_dw)), int(bool(logits_cache)), int(max_tokens)
+    opt = optional_outputs
+    _check(load().rapid_clip_pg_loss_fwd_bwd(
+        _ptr(hidden), _ptr(W), _ptr(tokens), _ptr(mask), _ptr(logp_old), _ptr(logp_ref), _ptr(rewards), _ptr(group_ids),
+        N, T, d, V, K, dt, C.byref(o), _ptr(b.loss), _ptr(b.dhidden), _ptr(b.dW), _ptr(b.logp_cur) if opt else None,
+        _ptr(b.adv) if opt else None, _ptr(b.clip_diag) if opt else None, _ptr(b.dev_status), _ptr(b.workspace),
+        b.workspace.numel(), _stream()))
+    return b
+
+
+def read_clip_diag(buffers):
+    dg = ClipPgDiag.from_buffer_copy(bytes(buffers.clip_diag.cpu().numpy().tobytes()))
+    return {f: getattr(dg, f) for f, _ in ClipPgDiag._fields_}

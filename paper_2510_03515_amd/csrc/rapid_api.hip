@@ -733,15 +733,23 @@ int rapid_group_advantage(const float* rewards, const int32_t* group_ids, const 
     return check_launch("rapid_group_advantage");
 }
 
-int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
-                             const float* logp_behav, const float* rewards, const int32_t* group_ids, int64_t N,
-                             int64_t T, int64_t d, int64_t V, int64_t K, int dtype, const rapid_iw_pg_opts* opts,
-                             float* loss_out, void* dhidden_out, void* dW_out, float* logp_cur_out,
-                             float* tok_logratio_out, float* seq_logratio_out, float* adv_out,
-                             rapid_iw_pg_diag* diag_out, int32_t* dev_status, void* workspace,
-                             size_t workspace_bytes, void* stream) {
-    rapid_iw_pg_opts o;
-    if (opts) o = *opts; else rapid_iw_pg_default_opts(&o);
+}  // extern "C"
+
+// The clipped token-level surrogate of the baselines' loss steps, when the fused path runs for them: the
+// estimator stage differs (normalised advantages, per-token coefficients), everything else is shared.
+struct ClipSpec {
+    rapid_clip_pg_opts o;
+    const float* logp_ref;
+    rapid_clip_pg_diag* diag;
+};
+
+static int fused_call(const char* name, const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
+                      const float* logp_behav, const float* rewards, const int32_t* group_ids, int64_t N,
+                      int64_t T, int64_t d, int64_t V, int64_t K, int dtype, const rapid_iw_pg_opts& o,
+                      float* loss_out, void* dhidden_out, void* dW_out, float* logp_cur_out,
+                      float* tok_logratio_out, float* seq_logratio_out, float* adv_out,
+                      rapid_iw_pg_diag* diag_out, int32_t* dev_status, void* workspace,
+                      size_t workspace_bytes, void* stream, const ClipSpec* clip) {
     Plan p;
     if (!make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype)) {
         set_error("bad shape/dtype N=%lld T=%lld d=%lld V=%lld K=%lld dtype=%d", (long long)N, (long long)T,
@@ -844,6 +852,15 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
     ca.tsum = tsum; ca.tmax = tmax; ca.counts = counts; ca.g = g; ca.g64 = at<double>(ws, p.g64);
     ca.loss_out = loss_out; ca.diag = diag_out; ca.write_g = 1;
 
+    ClipArgs cl;
+    memset(&cl, 0, sizeof(cl));
+    if (clip) {
+        cl.logp_cur = logp_cur; cl.logp_old = logp_behav; cl.logp_ref = clip->o.kl_beta != 0.f ? clip->logp_ref : nullptr;
+        cl.mask = mask; cl.adv64 = adv64; cl.seq_len = at<int32_t>(ws, p.seq_len); cl.counts = counts; cl.N = N; cl.T = T;
+        cl.eps_low = clip->o.eps_low; cl.eps_high = clip->o.eps_high; cl.kl_beta = clip->o.kl_beta;
+        cl.loss_scale = clip->o.loss_scale; cl.norm_mode = clip->o.norm_mode;
+    }
+
     FwdIo io{hidden, W, tokens, mask, o.w_layout, o.temperature, logp_cur, nullptr, dev_status};
     io.rms_weight = o.rms_weight;
     io.rms_eps = o.rms_eps;
@@ -896,7 +913,14 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             const int32_t* cnt = tab + (int64_t)c * CH_WORDS;     // this chunk's row counters
             const int32_t* gen_range = cnt + CH_G0;
             forward_rows_bf16(p, ws, io, cnt, base, p.Rcap, st);
-            {
+            if (clip) {
+                Span sp(ST_ESTIMATOR, st);
+                launch_group_advantage(rewards, group_ids, nullptr, nullptr, N, K, 2.f, BASELINE_NORMALIZED, adv, adv64, nullptr,
+                                       nullptr, nullptr, nullptr, gen_range, dev_status, st, clip->o.adv_eps, clip->o.std_ddof);
+                launch_clip_generations(cl, gen_range, at<double>(ws, p.g64), at<double>(ws, p.tsum), at<double>(ws, p.tmax),
+                                        dev_status, st);
+                launch_clip_rows(cl, seqc, row_index, cnt, base, p.Rcap, rowg, st);
+            } else {
                 Span sp(ST_ESTIMATOR, st);
                 launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, o.eta, o.coef_mode == 1,
                                     tsum, tmax, gen_range, dev_status, st);
@@ -945,9 +969,14 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         }
         {   // loss and diagnostics of the whole batch (every generation's ratio and advantage is known now)
             Span sp(ST_ESTIMATOR, st);
-            CoefArgs cf = ca;
-            cf.write_g = 0;
-            launch_coefficients(cf, st);
+            if (clip) {
+                launch_clip_finish(at<double>(ws, p.g64), at<double>(ws, p.tsum), at<double>(ws, p.tmax), N, counts, loss_out,
+                                   clip->diag, st);
+            } else {
+                CoefArgs cf = ca;
+                cf.write_g = 0;
+                launch_coefficients(cf, st);
+            }
         }
         if (o.normalized_grads && p.Cmax > 1) {   // rows of earlier chunks: from their chunk's scale to the final one
             Span sp(ST_ZERO, st);
@@ -969,14 +998,21 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
             if (o.dw_dtype == RAPID_DTYPE_BF16) launch_f32_to_bf16(dW32, (bf16_t*)dW_out, d * V, st);
             else launch_f32_add(dW32, (float*)dW_out, d * V, st);
         }
-        return check_launch("rapid_iw_pg_loss_fwd_bwd");
+        return check_launch(name);
     }
 
     // ---- the backward that regenerates the logits (and the fp32 path): forward over the whole batch first
     run_forward(p, ws, io, st);
 
     // generation-level log ratios, clipped-weight group baseline, coefficients and loss
-    {
+    if (clip) {
+        Span sp(ST_ESTIMATOR, st);
+        launch_group_advantage(rewards, group_ids, nullptr, nullptr, N, K, 2.f, BASELINE_NORMALIZED, adv, adv64, nullptr, nullptr,
+                               nullptr, nullptr, nullptr, dev_status, st, clip->o.adv_eps, clip->o.std_ddof);
+        launch_clip_generations(cl, nullptr, at<double>(ws, p.g64), at<double>(ws, p.tsum), at<double>(ws, p.tmax), dev_status, st);
+        launch_clip_finish(at<double>(ws, p.g64), at<double>(ws, p.tsum), at<double>(ws, p.tmax), N, counts, loss_out, clip->diag, st);
+        launch_clip_rows(cl, seqc, row_index, counts, 0, p.Mmax_pad, rowg, st);
+    } else {
         Span sp(ST_ESTIMATOR, st);
         launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, o.eta, o.coef_mode == 1,
                             tsum, tmax, nullptr, dev_status, st);
@@ -1103,7 +1139,71 @@ int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* t
         Span sp(ST_CONVERT, st);
         launch_f32_to_bf16(dW32, (bf16_t*)dW_out, d * V, st);
     }
-    return check_launch("rapid_iw_pg_loss_fwd_bwd");
+    return check_launch(name);
+}
+
+extern "C" {
+
+int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
+                             const float* logp_behav, const float* rewards, const int32_t* group_ids, int64_t N,
+                             int64_t T, int64_t d, int64_t V, int64_t K, int dtype, const rapid_iw_pg_opts* opts,
+                             float* loss_out, void* dhidden_out, void* dW_out, float* logp_cur_out,
+                             float* tok_logratio_out, float* seq_logratio_out, float* adv_out,
+                             rapid_iw_pg_diag* diag_out, int32_t* dev_status, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    rapid_iw_pg_opts o;
+    if (opts) o = *opts; else rapid_iw_pg_default_opts(&o);
+    return fused_call("rapid_iw_pg_loss_fwd_bwd", hidden, W, tokens, mask, logp_behav, rewards, group_ids, N, T, d, V, K,
+                      dtype, o, loss_out, dhidden_out, dW_out, logp_cur_out, tok_logratio_out, seq_logratio_out, adv_out,
+                      diag_out, dev_status, workspace, workspace_bytes, stream, nullptr);
+}
+
+void rapid_clip_pg_default_opts(rapid_clip_pg_opts* o, int variant) {
+    if (!o) return;
+    memset(o, 0, sizeof(*o));
+    o->eps_low = 0.2f;
+    o->eps_high = variant == 1 ? 0.28f : 0.2f;
+    o->kl_beta = variant == 1 ? 0.f : 0.04f;
+    o->norm_mode = variant == 1 ? 1 : 0;
+    o->adv_eps = 1e-4f;
+    o->std_ddof = 0;
+    o->loss_scale = 1.0f;
+    o->temperature = 1.0f;
+    o->w_layout = RAPID_W_DV;
+    o->dw_dtype = RAPID_DTYPE_F32;
+}
+
+int rapid_clip_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* tokens, const uint8_t* mask,
+                               const float* logp_old, const float* logp_ref, const float* rewards,
+                               const int32_t* group_ids, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K,
+                               int dtype, const rapid_clip_pg_opts* opts, float* loss_out, void* dhidden_out,
+                               void* dW_out, float* logp_cur_out, float* adv_out, rapid_clip_pg_diag* diag_out,
+                               int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream) {
+    ClipSpec cs;
+    if (opts) cs.o = *opts; else rapid_clip_pg_default_opts(&cs.o, 0);
+    cs.logp_ref = logp_ref;
+    cs.diag = diag_out;
+    const rapid_clip_pg_opts& c = cs.o;
+    if (!(c.eps_low >= 0.f) || !(c.eps_low < 1.f) || !(c.eps_high >= 0.f) || !std::isfinite(c.eps_high) ||
+        !(c.kl_beta >= 0.f) || !std::isfinite(c.kl_beta) || !(c.adv_eps >= 0.f) || !std::isfinite(c.adv_eps)) {
+        set_error("eps_low must be in [0, 1), eps_high, kl_beta and adv_eps finite and >= 0");
+        return RAPID_ERR_SHAPE;
+    }
+    if (c.norm_mode < 0 || c.norm_mode > 1 || c.std_ddof < 0 || c.std_ddof > 1) {
+        set_error("unknown norm_mode / std_ddof");
+        return RAPID_ERR_DTYPE;
+    }
+    if (c.kl_beta != 0.f && !logp_ref) {
+        set_error("kl_beta != 0 needs logp_ref");
+        return RAPID_ERR_NULL;
+    }
+    rapid_iw_pg_opts o;     // the options the two calls share
+    rapid_iw_pg_default_opts(&o);
+    o.loss_scale = c.loss_scale; o.temperature = c.temperature; o.w_layout = c.w_layout; o.dw_dtype = c.dw_dtype;
+    o.accumulate_dw = c.accumulate_dw; o.logits_cache = c.logits_cache; o.max_tokens = c.max_tokens;
+    return fused_call("rapid_clip_pg_loss_fwd_bwd", hidden, W, tokens, mask, logp_old, rewards, group_ids, N, T, d, V, K,
+                      dtype, o, loss_out, dhidden_out, dW_out, logp_cur_out, nullptr, nullptr, adv_out, nullptr, dev_status,
+                      workspace, workspace_bytes, stream, &cs);
 }
 
 }  // extern "C"

@@ -68,11 +68,31 @@ void launch_merge_lse(const float* part_max, const float* part_sum, int P, int64
 void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N,
                          int64_t T, float* tok_logratio_out, double* s64, float* s32, float eta, int clip_tokens,
                          double* tsum, double* tmax, const int32_t* gen_range, int32_t* dev_status, hipStream_t st);
-// weights from s64 if given, else from s32, else 1; adv64 (NULL or [N]): the advantages before rounding to float
+// weights from s64 if given, else from s32, else 1; adv64 (NULL or [N]): the advantages before rounding to float.
+// baseline_mode 0..2 as in rapid.h; BASELINE_NORMALIZED: adv = (R - group mean) / (group std + adv_eps), the std
+// with divisor N_k - std_ddof (no weights).
+constexpr int BASELINE_NORMALIZED = 3;
 void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, const double* s64,
                             int64_t N, int64_t K, float eta, int baseline_mode, float* adv, double* adv64,
                             float* weight, float* gmean, float* gstd, int32_t* gsize, const int32_t* gen_range,
-                            int32_t* dev_status, hipStream_t st);
+                            int32_t* dev_status, hipStream_t st, float adv_eps = 0.f, int std_ddof = 0);
+
+// Token-level clipped surrogate with KL penalty (the loss step of the GRPO / DAPO baselines).
+struct ClipArgs {
+    const float* logp_cur; const float* logp_old; const float* logp_ref;   // [N,T]; old NULL: ratios 1; ref NULL: no KL term
+    const uint8_t* mask; const double* adv64; const int32_t* seq_len; const int32_t* counts;   // counts[CNT_M]: tokens of the call
+    int64_t N, T;
+    float eps_low, eps_high, kl_beta, loss_scale; int norm_mode;
+};
+// rowg[j] = dLoss/dlogp of compact row j in [row0, row0 + rows_max) (0 for padding rows)
+void launch_clip_rows(const ClipArgs& a, const int32_t* seqc, const int32_t* row_index, const int32_t* row_counts,
+                      int64_t row0, int64_t rows_max, float* rowg, hipStream_t st);
+// per generation (in gen_range): its share of the loss, its clipped tokens, the sum of its tokens' KL estimates
+void launch_clip_generations(const ClipArgs& a, const int32_t* gen_range, double* loss_n, double* clipped_n, double* kl_n,
+                             int32_t* dev_status, hipStream_t st);
+// loss and diagnostics from the per-generation sums
+void launch_clip_finish(const double* loss_n, const double* clipped_n, const double* kl_n, int64_t N, const int32_t* counts,
+                        float* loss_out, rapid_clip_pg_diag* diag, hipStream_t st);
 // tsum/tmax given: token-level outer weight (g_n is then the generation's factor without a ratio).
 // Three uses.  Whole batch (gen_range, lam_state NULL): coefficients, scale lambda, loss, diagnostics.
 // One chunk of the cached backward (gen_range and lam_state given): coefficients of the chunk's generations

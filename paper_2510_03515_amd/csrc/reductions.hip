@@ -363,7 +363,7 @@ __global__ void group_advantage_kernel(const float* __restrict__ rewards, const 
                                        double log_eta, int baseline_mode, float* __restrict__ adv,
                                        double* __restrict__ adv64, float* __restrict__ gmean,
                                        float* __restrict__ gstd, int32_t* __restrict__ gsize,
-                                       const int32_t* __restrict__ gen_range) {
+                                       const int32_t* __restrict__ gen_range, double adv_eps, int std_ddof) {
     __shared__ double sm[16];
     const int k = blockIdx.x;
     const int64_t n_begin = gen_range ? gen_range[0] : 0, n_end = gen_range ? gen_range[1] : N;
@@ -390,7 +390,9 @@ __global__ void group_advantage_kernel(const float* __restrict__ rewards, const 
             const double dlt = (double)r - mean;
             sq += dlt * dlt;
             double b;
-            if (baseline_mode == 0) {
+            if (baseline_mode == BASELINE_NORMALIZED) {
+                continue;                      // needs the group's std: third pass below
+            } else if (baseline_mode == 0) {
                 b = sum_wr / cnt;
             } else {
                 const double rest = sum_wr - clipped_weight(s32, s64, n, log_eta) * (double)r;
@@ -402,6 +404,20 @@ __global__ void group_advantage_kernel(const float* __restrict__ rewards, const 
         }
     }
     sq = block_sum(sq, sm);
+    if (baseline_mode == BASELINE_NORMALIZED) {   // (R - mean) / (std + eps); equal rewards give 0
+        const double den = cnt - (double)std_ddof;
+        const double sd = den > 0.0 ? sqrt(sq / den) : 0.0;
+        for (int64_t n = n_begin + threadIdx.x; n < n_end; n += blockDim.x) {
+            if (group_ids[n] == k) {
+                float r = rewards[n];
+                if (!isfinite(r)) r = 0.f;
+                const double num = (double)r - mean;
+                const double a = num != 0.0 ? num / (sd + adv_eps) : 0.0;
+                adv[n] = (float)a;
+                if (adv64) adv64[n] = a;
+            }
+        }
+    }
     if (threadIdx.x == 0) {
         if (gsize) gsize[k] = (int32_t)cnt;
         if (gmean) gmean[k] = (float)mean;
@@ -623,12 +639,143 @@ void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const u
 void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, const double* s64,
                             int64_t N, int64_t K, float eta, int baseline_mode, float* adv, double* adv64,
                             float* weight, float* gmean, float* gstd, int32_t* gsize, const int32_t* gen_range,
-                            int32_t* dev_status, hipStream_t st) {
+                            int32_t* dev_status, hipStream_t st, float adv_eps, int std_ddof) {
     const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
     group_init_kernel<<<blocks_for(N, 256), 256, 0, st>>>(rewards, group_ids, s32, s64, N, K, log_eta, adv, adv64,
                                                           weight, gen_range, dev_status);
     group_advantage_kernel<<<(unsigned)K, 256, 0, st>>>(rewards, group_ids, s32, s64, N, log_eta, baseline_mode, adv,
-                                                        adv64, gmean, gstd, gsize, gen_range);
+                                                        adv64, gmean, gstd, gsize, gen_range, (double)adv_eps, std_ddof);
+}
+
+// ---- the token-level clipped surrogate of the GRPO / DAPO loss steps ---------------------------
+namespace {
+
+struct ClipToken { double loss, dlogp, kl; bool clipped; };
+
+// one valid token: omega (surr - beta kl) and its derivative with respect to the current log-prob
+__device__ inline ClipToken clip_token(const ClipArgs& a, int64_t i, double adv, double omega, bool* bad) {
+    const double cur = (double)a.logp_cur[i];
+    double dlt = 0.0;
+    if (a.logp_old) {
+        const float lo = a.logp_old[i];
+        if (isfinite(lo)) dlt = cur - (double)lo; else *bad = true;
+    }
+    const double r = exp(dlt);
+    const double rc = fmin(fmax(r, 1.0 - (double)a.eps_low), 1.0 + (double)a.eps_high);
+    const double unclipped = r * adv, clipped = rc * adv;
+    ClipToken t;
+    t.clipped = unclipped > clipped;
+    const double surr = t.clipped ? clipped : unclipped;
+    const double dsurr = t.clipped ? 0.0 : unclipped;
+    double kl = 0.0, dkl = 0.0;
+    if (a.kl_beta != 0.f && a.logp_ref) {
+        const float lr = a.logp_ref[i];
+        if (isfinite(lr)) {
+            const double dref = (double)lr - cur;
+            const double e = exp(dref);
+            kl = e - dref - 1.0;
+            dkl = 1.0 - e;
+        } else {
+            *bad = true;
+        }
+    }
+    t.kl = kl;
+    t.loss = -omega * (surr - (double)a.kl_beta * kl);
+    t.dlogp = -omega * (dsurr - (double)a.kl_beta * dkl);
+    return t;
+}
+
+__device__ inline double clip_omega(const ClipArgs& a, int64_t n) {
+    if (a.norm_mode == 0) {
+        const int L = a.seq_len[n];
+        return L > 0 ? (double)a.loss_scale / ((double)a.N * (double)L) : 0.0;
+    }
+    const int M = a.counts[CNT_M];
+    return M > 0 ? (double)a.loss_scale / (double)M : 0.0;
+}
+
+__global__ void clip_rows_kernel(ClipArgs a, const int32_t* __restrict__ seqc, const int32_t* __restrict__ row_index,
+                                 const int32_t* __restrict__ row_counts, int64_t row0, float* __restrict__ rowg) {
+    const int64_t j = row0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int M = row_counts[CNT_M], Mr = row_counts[CNT_MR];
+    if (j >= Mr) return;
+    float v = 0.f;
+    if (j < M) {
+        const int32_t n = seqc[j];
+        bool bad = false;
+        v = (float)clip_token(a, row_index[j], a.adv64[n], clip_omega(a, n), &bad).dlogp;
+    }
+    rowg[j] = v;
+}
+
+// one wave per generation
+__global__ void clip_generations_kernel(ClipArgs a, const int32_t* __restrict__ gen_range, double* __restrict__ loss_n,
+                                        double* __restrict__ clipped_n, double* __restrict__ kl_n,
+                                        int32_t* __restrict__ dev_status) {
+    const int64_t n = blockIdx.x;
+    if (n >= a.N) return;
+    if (gen_range && (n < gen_range[0] || n >= gen_range[1])) return;
+    const double omega = clip_omega(a, n), adv = a.adv64[n];
+    double loss = 0.0, ncl = 0.0, kl = 0.0;
+    bool bad = false;
+    for (int64_t t = threadIdx.x; t < a.T; t += WAVE) {
+        const int64_t i = n * a.T + t;
+        if (a.mask[i] == 0) continue;
+        const ClipToken tk = clip_token(a, i, adv, omega, &bad);
+        loss += tk.loss;
+        ncl += tk.clipped ? 1.0 : 0.0;
+        kl += tk.kl;
+    }
+    loss = wave_sum(loss);
+    ncl = wave_sum(ncl);
+    kl = wave_sum(kl);
+    if (__any(bad) && threadIdx.x == 0 && dev_status) atomicOr(dev_status, RAPID_STATUS_NONFINITE_LOGP);
+    if (threadIdx.x == 0) {
+        loss_n[n] = loss;
+        clipped_n[n] = ncl;
+        kl_n[n] = kl;
+    }
+}
+
+__global__ void clip_finish_kernel(const double* __restrict__ loss_n, const double* __restrict__ clipped_n,
+                                   const double* __restrict__ kl_n, int64_t N, const int32_t* __restrict__ counts,
+                                   float* __restrict__ loss_out, rapid_clip_pg_diag* __restrict__ diag) {
+    __shared__ double sm[16];
+    double loss = 0.0, ncl = 0.0, kl = 0.0;
+    for (int64_t n = threadIdx.x; n < N; n += blockDim.x) {
+        loss += loss_n[n];
+        ncl += clipped_n[n];
+        kl += kl_n[n];
+    }
+    loss = block_sum(loss, sm);
+    ncl = block_sum(ncl, sm);
+    kl = block_sum(kl, sm);
+    if (threadIdx.x == 0) {
+        loss_out[0] = (float)loss;
+        if (diag) {
+            const int M = counts[CNT_M];
+            diag->n_tokens = M;
+            diag->n_clipped = (int64_t)ncl;
+            diag->n_sequences = (int32_t)N;
+            diag->mean_kl = M > 0 ? (float)(kl / (double)M) : 0.f;
+        }
+    }
+}
+
+}  // namespace
+
+void launch_clip_rows(const ClipArgs& a, const int32_t* seqc, const int32_t* row_index, const int32_t* row_counts,
+                      int64_t row0, int64_t rows_max, float* rowg, hipStream_t st) {
+    if (rows_max > 0)
+        clip_rows_kernel<<<blocks_for(rows_max, 256), 256, 0, st>>>(a, seqc, row_index, row_counts, row0, rowg);
+}
+void launch_clip_generations(const ClipArgs& a, const int32_t* gen_range, double* loss_n, double* clipped_n, double* kl_n,
+                             int32_t* dev_status, hipStream_t st) {
+    clip_generations_kernel<<<(unsigned)a.N, WAVE, 0, st>>>(a, gen_range, loss_n, clipped_n, kl_n, dev_status);
+}
+void launch_clip_finish(const double* loss_n, const double* clipped_n, const double* kl_n, int64_t N, const int32_t* counts,
+                        float* loss_out, rapid_clip_pg_diag* diag, hipStream_t st) {
+    clip_finish_kernel<<<1, 1024, 0, st>>>(loss_n, clipped_n, kl_n, N, counts, loss_out, diag);
 }
 
 void launch_coefficients(const CoefArgs& a, hipStream_t st) {

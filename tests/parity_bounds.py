@@ -66,6 +66,30 @@ def coefficient_slack(oracle_out, rewards, mask):
     return slack
 
 
+def token_coefficient_slack(coef_of_logp, logp_cur, mask, tokens, V):
+    """The same effect for estimators whose coefficient is per token (the baselines' clipped surrogate): the
+    library's current log-probs are floats, the oracle's are not, and a coefficient such as the KL term's
+    beta (1 - exp(ref - cur)) is a difference of nearly equal numbers now and then.  coef_of_logp(logp) must
+    return the oracle's coefficients [N,T] for current log-probs `logp`; it is evaluated at the oracle's
+    log-probs and at both ends of the float rounding interval around them.  Returns (relative slack per
+    token [N,T], relative slack per vocabulary column [V]): a token's rows of dHidden get the first; a
+    column of dW gets the largest slack among the tokens sampled there (it is their one-hot terms that
+    make up the column), and where nothing was sampled the coefficient-weighted mean."""
+    lp = np.asarray(logp_cur, np.float64)
+    msk = np.asarray(mask) != 0
+    ulp = 2.0 ** -24 * np.maximum(np.abs(lp), 1.0) * 1.001            # half a float spacing, a little generous
+    g0 = coef_of_logp(lp)
+    dg = np.maximum(np.abs(coef_of_logp(lp + ulp) - g0), np.abs(coef_of_logp(lp - ulp) - g0)) * msk
+    rel = np.zeros_like(g0)
+    nz = (g0 != 0) & msk
+    rel[nz] = dg[nz] / np.abs(g0[nz])
+    mean = float(dg.sum() / max(np.abs(g0).sum(), 1e-300))
+    col = np.full(V, mean)
+    tok = np.asarray(tokens)
+    np.maximum.at(col, tok[msk], rel[msk])
+    return rel, col
+
+
 def assert_dhidden_close(got, ref, dtype="bf16", rel=None):
     """got, ref: [..., d]; every element within rel of its token row's largest magnitude.  rel may be an
     array that broadcasts against the rows (one tolerance per generation: shape [N, 1, 1])."""
@@ -76,7 +100,7 @@ def assert_dhidden_close(got, ref, dtype="bf16", rel=None):
 
 def assert_dw_close(got, ref, dtype="bf16", rel=None):
     """got, ref: [d, V] (logical layout); every element within rel of its vocabulary column's largest
-    magnitude."""
+    magnitude.  rel may be an array over the columns (shape [V])."""
     worst, idx = worst_excess(got, ref, 0, REL[dtype] if rel is None else rel)
     assert worst <= 1.0, f"dW element {idx}: error is {worst:.2f} x its bound"
     assert np.isfinite(np.asarray(got, np.float64)).all()

@@ -891,3 +891,129 @@ def test_autograd_wrapper_against_plain_pytorch(rb):
     W = g["W"].clone().requires_grad_(True)
     (3.0 * iw_pg_loss(body(x).to(torch.bfloat16), W, tok, mask, logp_b, R, g["group_ids"], K)).backward()
     assert _rel(_np(W.grad.float()), 3.0 * _np(dW0)) <= 1e-2
+
+
+# ----------------------------------------------------------------------------- baselines' loss steps
+def _clip_inputs(rb, spec, seed, ref_shift=0.02, temperature=1.0):
+    """Old-policy log-probs from the workload's W_old; reference log-probs from a third set of weights
+    (the policy before the first update, further away than the old policy)."""
+    w, g = _make(spec, seed)
+    gen = torch.Generator().manual_seed(100 + seed)
+    W_ref = (w["W_old"].float() + ref_shift * torch.randn(w["W"].shape, generator=gen)).to(w["W"].dtype).cuda()
+    # the old policy a few updates away, so that token ratios leave the clip range on both sides
+    W_old = (w["W_old"].float() + 0.03 * torch.randn(w["W"].shape, generator=gen)).to(w["W"].dtype).cuda()
+    lp_old, _ = rb.rapid_logprob_fwd(g["hidden"], W_old, g["tokens"], g["mask"], temperature=temperature)
+    lp_ref, _ = rb.rapid_logprob_fwd(g["hidden"], W_ref, g["tokens"], g["mask"], temperature=temperature)
+    return w, g, lp_old, lp_ref
+
+
+def _check_clip(rb, spec, w, out, ref, dtype_tol):
+    assert out.dev_status.item() == 0
+    assert np.abs(_np(out.logp_cur) - ref["logp_cur"]).max() <= LOGP_ATOL[spec.dtype]
+    assert np.allclose(_np(out.adv), ref["adv"], atol=1e-5, rtol=1e-5)
+    assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * max(abs(ref["loss"]), 1e-30), (out.loss.item(), ref["loss"])
+    # what the float storage of the current log-probs may do to each token's coefficient (parity_bounds.py)
+    mask = _np(w["mask"])
+    tok_slack, col_slack = pb.token_coefficient_slack(ref["coef_of_logp"], ref["logp_cur"], mask, _np(w["tokens"]), spec.V)
+    rel = pb.REL[spec.dtype] if dtype_tol is None else dtype_tol
+    got_dh, got_dw = _np(out.dhidden), _np(out.dW)
+    assert _rel(got_dh, ref["dH"]) <= GRAD_RTOL[spec.dtype] and _rel(got_dw, ref["dW"]) <= GRAD_RTOL[spec.dtype]
+    pb.assert_dhidden_close(got_dh, ref["dH"], spec.dtype, rel + tok_slack[:, :, None])
+    pb.assert_dw_close(got_dw, ref["dW"], spec.dtype, rel + col_slack[None, :])
+    assert np.all(_np(out.dhidden)[_np(w["mask"]) == 0] == 0.0)
+    dg = rb.read_clip_diag(out)
+    assert dg["n_tokens"] == ref["n_tokens"] and dg["n_sequences"] == len(ref["adv"])
+    # the clip decision is taken from float log-probs on one side and float64 ones on the other: tokens whose
+    # ratio is within 1e-5 of a clip boundary may fall either way
+    r = np.exp(ref["logp_cur"] - ref["logp_old"])[_np(w["mask"]) != 0]
+    near = int(((np.abs(r - (1 - ref["eps"][0])) < 1e-5) | (np.abs(r - (1 + ref["eps"][1])) < 1e-5)).sum())
+    assert abs(dg["n_clipped"] - round(ref["clip_fraction"] * ref["n_tokens"])) <= near
+    assert abs(dg["mean_kl"] - ref["mean_kl"]) <= 1e-5 + 1e-3 * ref["mean_kl"]
+
+
+@pytest.mark.parametrize("name", ["f32_cfg0", "f32_ragged", "bf16_small", "bf16_ragged"])
+@pytest.mark.parametrize("variant", ["grpo", "dapo"])
+def test_clip_pg_loss_step(rb, name, variant):
+    """The loss step of the GRPO and DAPO baselines on the same kernels: every output against the
+    oracle, with the variants' default options and with others (sample std, no advantage epsilon,
+    temperature, loss scale, the other normalisation), in both backward modes and both layouts."""
+    spec = SPECS[name]
+    print(f"clip pg {variant} {name}", flush=True)
+    for kw in (dict(), dict(std_ddof=1, adv_eps=0.0, loss_scale=0.5), dict(norm_mode=1 if variant == "grpo" else 0, eps_high=0.1),
+               dict(temperature=0.8)):
+        temp = kw.get("temperature", 1.0)
+        w, g, lp_old, lp_ref = _clip_inputs(rb, spec, seed=2, temperature=temp)
+        H, W, tok, mask = _oracle_inputs(w)
+        o = rb.clip_pg_default_opts(variant)
+        okw = dict(eps_low=o.eps_low, eps_high=o.eps_high, kl_beta=o.kl_beta, norm_mode=o.norm_mode, adv_eps=o.adv_eps,
+                   std_ddof=o.std_ddof)
+        okw.update(kw)
+        ref = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, _np(lp_old), _np(lp_ref), _np(w["rewards"]), _np(w["group_ids"]),
+                                          w["K"], **okw)
+        ref["logp_old"], ref["eps"] = _np(lp_old), (okw["eps_low"], okw["eps_high"])
+        ckw = {k: v for k, v in okw.items() if k in ("eps_low", "eps_high", "kl_beta", "norm_mode", "loss_scale")}
+        ref["coef_of_logp"] = lambda lp, ckw=ckw, ref=ref: orc.clipped_token_coefficients(
+            lp, _np(lp_old), _np(lp_ref), mask, ref["adv"], **ckw)[0]
+        assert 0.0 < ref["clip_fraction"] < 0.9
+        for cache in ((False, True) if spec.dtype == "bf16" else (False,)):
+            out = rb.rapid_clip_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], lp_old, lp_ref, g["rewards"],
+                                                g["group_ids"], w["K"], variant=variant, logits_cache=cache, **kw)
+            torch.cuda.synchronize()
+            _check_clip(rb, spec, w, out, ref, None)
+    if spec.dtype == "bf16":      # [V, d] weights, bf16 dW, accumulation
+        Wt = g["W"].t().contiguous()
+        buf = rb.IwPgBuffers(g["hidden"], Wt, w["K"], w_layout=rb.W_VD, dw_dtype=torch.bfloat16)
+        out = rb.rapid_clip_pg_loss_fwd_bwd(g["hidden"], Wt, g["tokens"], g["mask"], lp_old, lp_ref, g["rewards"], g["group_ids"],
+                                            w["K"], variant=variant, buffers=buf, w_layout=rb.W_VD, temperature=0.8)
+        torch.cuda.synchronize()
+        _dw_ok(_np(out.dW).T, ref["dW"], rel=2.0 ** -6)
+        assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+
+
+def test_clip_pg_special_cases_and_chunks(rb):
+    """Equal policies: every ratio is exactly 1, nothing clips, the KL term vanishes against itself, and
+    the gradients are those of the plain group-relative gradient with normalised advantages (the oracle's
+    backward with -omega A_n); logp_old = NULL is the same call.  A non-finite stored log-prob is flagged.
+    And the chunked cache: same results from chunks of whole groups."""
+    spec = CHUNKY
+    w, g = _make(spec, seed=6)
+    H, W, tok, mask = _oracle_inputs(w)
+    N, T, d = g["hidden"].shape
+    K = w["K"]
+    cur, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])
+    a = rb.rapid_clip_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], cur, cur, g["rewards"], g["group_ids"], K)
+    torch.cuda.synchronize()
+    dga = rb.read_clip_diag(a)
+    assert dga["n_clipped"] == 0 and dga["mean_kl"] == 0.0 and torch.equal(a.logp_cur, cur)
+    ga = orc.normalized_group_advantage(_np(w["rewards"]), _np(w["group_ids"]), K)
+    L = mask.sum(1)
+    coef = -(ga["adv"] / (N * L))[:, None] * (mask != 0)
+    dH, dW = orc.backward(H, W, tok, mask, coef)
+    _dh_ok(a.dhidden, dH)
+    _dw_ok(a.dW, dW)
+    assert abs(a.loss.item() - (-(ga["adv"]).mean())) <= 1e-6
+    b = rb.rapid_clip_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], None, None, g["rewards"], g["group_ids"], K,
+                                      variant="dapo", norm_mode=0)
+    torch.cuda.synchronize()
+    assert torch.equal(a.dW, b.dW) and torch.equal(a.dhidden, b.dhidden) and torch.equal(a.loss, b.loss)
+    bad = cur.clone()
+    n_bad, t_bad = np.argwhere(mask == 1)[5]
+    bad[n_bad, t_bad] = float("nan")
+    c = rb.rapid_clip_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], bad, cur, g["rewards"], g["group_ids"], K)
+    torch.cuda.synchronize()
+    assert c.dev_status.item() & rb.STATUS_NONFINITE_LOGP and torch.isfinite(c.dW).all() and torch.isfinite(c.loss).all()
+    # chunks of whole groups
+    w, g, lp_old, lp_ref = _clip_inputs(rb, spec, seed=6)
+    least = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, spec.V, K, rb.DTYPE_BF16, minimum=True)
+    for variant in ("grpo", "dapo"):
+        o = rb.clip_pg_default_opts(variant)
+        ref = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, _np(lp_old), _np(lp_ref), _np(w["rewards"]), _np(w["group_ids"]), K,
+                                          eps_low=o.eps_low, eps_high=o.eps_high, kl_beta=o.kl_beta, norm_mode=o.norm_mode)
+        ref["logp_old"], ref["eps"] = _np(lp_old), (o.eps_low, o.eps_high)
+        ref["coef_of_logp"] = lambda lp, o=o, ref=ref: orc.clipped_token_coefficients(
+            lp, _np(lp_old), _np(lp_ref), mask, ref["adv"], o.eps_low, o.eps_high, o.kl_beta, o.norm_mode)[0]
+        buf = rb.IwPgBuffers(g["hidden"], g["W"], K, workspace_bytes=least)
+        out = rb.rapid_clip_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], lp_old, lp_ref, g["rewards"],
+                                            g["group_ids"], K, variant=variant, buffers=buf, logits_cache=True)
+        torch.cuda.synchronize()
+        _check_clip(rb, spec, w, out, ref, None)

@@ -52,6 +52,30 @@ def test_struct_layouts_match_header(rb):
     assert not o.rms_weight and not o.drms_weight_out and abs(o.rms_eps - 1e-6) < 1e-12
 
 
+def test_clip_pg_structs_and_validation(rb):
+    """The baselines' loss step: struct layouts as in the header, the two variants' defaults (GRPO: eps 0.2 / 0.2,
+    KL 0.04 as in the paper's Appendix A, per-generation mean; DAPO: eps 0.2 / 0.28, no KL, token mean), and its own
+    host checks."""
+    lib = rb.load()
+    assert C.sizeof(rb.ClipPgOpts) == 56 and rb.ClipPgOpts.max_tokens.offset == 48 and C.sizeof(rb.ClipPgDiag) == 24
+    g, dd = rb.clip_pg_default_opts("grpo"), rb.clip_pg_default_opts("dapo")
+    assert abs(g.eps_low - 0.2) < 1e-7 and abs(g.eps_high - 0.2) < 1e-7 and abs(g.kl_beta - 0.04) < 1e-8 and g.norm_mode == 0
+    assert abs(dd.eps_low - 0.2) < 1e-7 and abs(dd.eps_high - 0.28) < 1e-7 and dd.kl_beta == 0.0 and dd.norm_mode == 1
+    assert abs(g.adv_eps - 1e-4) < 1e-10 and g.std_ddof == 0 and g.loss_scale == 1.0 and g.temperature == 1.0
+    one = C.c_void_p(256)
+    args = lambda o, ref=one: [one, one, one, one, one, ref, one, one, 4, 4, 8, 8, 1, rb.DTYPE_BF16, C.byref(o), one, one, one,
+                               None, None, None, None, one, 1 << 30, None]
+    assert lib.rapid_clip_pg_loss_fwd_bwd(*args(g, None)) == -1 and b"logp_ref" in lib.rapid_last_error()   # KL without a reference
+    g.eps_low = 1.5
+    assert lib.rapid_clip_pg_loss_fwd_bwd(*args(g)) == -2
+    g = rb.clip_pg_default_opts("grpo"); g.norm_mode = 3
+    assert lib.rapid_clip_pg_loss_fwd_bwd(*args(g)) == -3
+    g = rb.clip_pg_default_opts("grpo"); g.kl_beta = -1.0
+    assert lib.rapid_clip_pg_loss_fwd_bwd(*args(g)) == -2
+    assert lib.rapid_clip_pg_loss_fwd_bwd(*[one, one, one, one, one, None, None, one, 4, 4, 8, 8, 1, rb.DTYPE_BF16, C.byref(dd),
+                                            one, one, one, None, None, None, None, one, 1 << 30, None]) == -1   # rewards
+
+
 def test_workspace_sizes(rb):
     args = (256, 2048, 1536, 151936, 32, rb.DTYPE_BF16)
     rec = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, *args)
