@@ -230,6 +230,17 @@ int rapid_group_advantage(const float* rewards, const int32_t* group_ids, const 
                           int32_t* group_size_out, int32_t* dev_status, void* stream);
 
 /*
+ * Token- and generation-level log ratios (Sec. 3.4, the ratio of Eq. (3); Sec. 4.3: token ratios are accumulated
+ * over the generation, the clip acts on the result), the reduction step of the fused call as a call of its own:
+ *   tok_logratio_out[n,t] = mask (logp_cur - logp_behav)   ([N,T] fp32, may be NULL)
+ *   seq_logratio_out[n]   = sum_t tok_logratio[n,t]        ([N] fp32, fp64 accumulation in a fixed order)
+ * A non-finite behaviour log-prob at a valid position counts as a log ratio of 0 and sets
+ * RAPID_STATUS_NONFINITE_LOGP.  No workspace.
+ */
+int rapid_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N, int64_t T,
+                       float* tok_logratio_out, float* seq_logratio_out, int32_t* dev_status, void* stream);
+
+/*
  * One mini-batch of Alg. 1's IW-GRPG: advantages by Eq. (5), loss and gradients by Eq. (3).
  *   logp      = as rapid_logprob_fwd on the current W
  *   s_n       = sum_t mask (logp - logp_behav)            (generation-level log ratio, Sec. 4.3)
@@ -304,9 +315,20 @@ int rapid_clip_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t*
  * the LM head alone and as plain gradient descent on the returned loss:
  *   master[i] -= lr * grad[i]   (fp32, n elements, same layout as dW_out)
  * and, if w_out != NULL, w_out[i] = the updated weight in `dtype` (the W of the next call).
- * The optimiser of the paper's experiments (Appendix A) is not part of this library.
  */
 int rapid_sgd_step(float* master, const float* grad, int64_t n, float lr, void* w_out, int dtype, void* stream);
+
+/*
+ * The same update with AdamW (decoupled weight decay), the optimiser family of the paper's training runs
+ * (Appendix A gives the learning rate, 1e-6; the remaining constants are the caller's).  Step number `step` >= 1:
+ *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2
+ *   master -= lr * ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) + weight_decay * master )
+ * master, exp_avg (m) and exp_avg_sq (v) are fp32 device arrays of n elements that the caller keeps between
+ * steps (m and v start at zero); w_out as in rapid_sgd_step.
+ */
+int rapid_adamw_step(float* master, const float* grad, float* exp_avg, float* exp_avg_sq, int64_t n, float lr,
+                     float beta1, float beta2, float eps, float weight_decay, int64_t step, void* w_out, int dtype,
+                     void* stream);
 
 /*
  * Integer bookkeeping of the padding mask (device outputs; seq_len_out and cu_seqlen_out are

@@ -439,3 +439,17 @@ def clipped_pg_loss_fwd_bwd(hidden, W, tokens, mask, logp_old, logp_ref, rewards
     return dict(loss=loss, dH=dH, dW=dW, logp_cur=logp_cur, adv=ga["adv"], g=g, group_mean=ga["group_mean"],
                 group_std=ga["group_std"], group_size=ga["group_size"], clip_fraction=diag["clip_fraction"],
                 mean_kl=diag["mean_kl"], n_tokens=int((np.asarray(mask) != 0).sum()))
+
+
+def adamw_step(w, grad, exp_avg, exp_avg_sq, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+    """One step of AdamW (Adam with decoupled weight decay, Loshchilov & Hutter 2019), the optimiser family
+    of the paper's training runs (Appendix A lists the learning rate; Alg. 1's update line is this step).
+    m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
+    w <- w - lr ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) + weight_decay w ).
+    Returns (w, m, v) as new float64 arrays; step counts from 1."""
+    w, g, m, v = _as64(w), _as64(grad), _as64(exp_avg), _as64(exp_avg_sq)
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** step)
+    v_hat = v / (1.0 - beta2 ** step)
+    return w - lr * (m_hat / (np.sqrt(v_hat) + eps) + weight_decay * w), m, v

@@ -26,7 +26,8 @@ STATUS_GROUP_LAYOUT = 64
 EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_workspace_bytes_max_tokens", "rapid_logprob_fwd", "rapid_logprob_fwd_rmsnorm",
            "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step",
-           "rapid_logprob_fwd_static", "rapid_clip_pg_default_opts", "rapid_clip_pg_loss_fwd_bwd"]
+           "rapid_logprob_fwd_static", "rapid_clip_pg_default_opts", "rapid_clip_pg_loss_fwd_bwd",
+           "rapid_seq_logratio", "rapid_adamw_step"]
 STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
           "dw", "f32_path", "dw_convert"]
 
@@ -110,6 +111,10 @@ def load():
     lib.rapid_mfma_probe.restype = ci
     lib.rapid_sgd_step.argtypes = [vp, vp, i64, C.c_float, vp, ci, vp]
     lib.rapid_sgd_step.restype = ci
+    lib.rapid_adamw_step.argtypes = [vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i64, vp, ci, vp]
+    lib.rapid_adamw_step.restype = ci
+    lib.rapid_seq_logratio.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, vp]
+    lib.rapid_seq_logratio.restype = ci
     _lib = lib
     return lib
 
@@ -161,6 +166,30 @@ def rapid_sgd_step(master, grad, lr, w_out=None):
     assert master.numel() == grad.numel() and (w_out is None or w_out.numel() == master.numel())
     dt = DTYPE_F32 if w_out is None else _dtype_code(w_out)
     _check(load().rapid_sgd_step(_ptr(master), _ptr(grad), master.numel(), float(lr), _ptr(w_out), dt, _stream()))
+
+
+def rapid_adamw_step(master, grad, exp_avg, exp_avg_sq, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+                     w_out=None):
+    """One AdamW step on fp32 master weights (exp_avg / exp_avg_sq: the optimiser state, zero before step 1), and
+    w_out (bf16 or fp32, optional) = the updated weights."""
+    for t, name in ((master, "master"), (grad, "grad"), (exp_avg, "exp_avg"), (exp_avg_sq, "exp_avg_sq")):
+        _need(t, torch.float32, name)
+    assert master.numel() == grad.numel() == exp_avg.numel() == exp_avg_sq.numel()
+    dt = DTYPE_F32 if w_out is None else _dtype_code(w_out)
+    _check(load().rapid_adamw_step(_ptr(master), _ptr(grad), _ptr(exp_avg), _ptr(exp_avg_sq), master.numel(), float(lr),
+                                   float(beta1), float(beta2), float(eps), float(weight_decay), int(step), _ptr(w_out), dt,
+                                   _stream()))
+
+
+def rapid_seq_logratio(logp_cur, logp_behav, mask, want_tokens=False, dev_status=None):
+    """Returns (seq_logratio [N] f32, tok_logratio [N,T] f32 or None)."""
+    N, T = mask.shape
+    _need(logp_cur, torch.float32, "logp_cur"); _need(logp_behav, torch.float32, "logp_behav"); _need(mask, torch.uint8, "mask")
+    s = torch.empty(N, dtype=torch.float32, device=mask.device)
+    tok = torch.empty((N, T), dtype=torch.float32, device=mask.device) if want_tokens else None
+    _check(load().rapid_seq_logratio(_ptr(logp_cur), _ptr(logp_behav), _ptr(mask), N, T, _ptr(tok), _ptr(s),
+                                     _ptr(dev_status), _stream()))
+    return s, tok
 
 
 def rapid_profile_read():

@@ -576,6 +576,46 @@ int rapid_sgd_step(float* master, const float* grad, int64_t n, float lr, void* 
     return check_launch("rapid_sgd_step");
 }
 
+int rapid_adamw_step(float* master, const float* grad, float* exp_avg, float* exp_avg_sq, int64_t n, float lr,
+                     float beta1, float beta2, float eps, float weight_decay, int64_t step, void* w_out, int dtype,
+                     void* stream) {
+    if (!master || !grad || !exp_avg || !exp_avg_sq) {
+        set_error("master, grad, exp_avg and exp_avg_sq must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    if (n <= 0 || step < 1 || !std::isfinite(lr) || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) ||
+        !(eps >= 0.f) || !std::isfinite(eps) || !std::isfinite(weight_decay)) {
+        set_error("n > 0, step >= 1, lr finite, betas in [0, 1), eps >= 0 and weight_decay finite are required");
+        return RAPID_ERR_SHAPE;
+    }
+    if (dtype != RAPID_DTYPE_F32 && dtype != RAPID_DTYPE_BF16) {
+        set_error("unknown dtype %d", dtype);
+        return RAPID_ERR_DTYPE;
+    }
+    int rc = check_arch();
+    if (rc) return rc;
+    launch_adamw_step(master, grad, exp_avg, exp_avg_sq, n, lr, beta1, beta2, eps, weight_decay, step, w_out, dtype,
+                      (hipStream_t)stream);
+    return check_launch("rapid_adamw_step");
+}
+
+int rapid_seq_logratio(const float* logp_cur, const float* logp_behav, const uint8_t* mask, int64_t N, int64_t T,
+                       float* tok_logratio_out, float* seq_logratio_out, int32_t* dev_status, void* stream) {
+    if (!logp_cur || !logp_behav || !mask || !seq_logratio_out) {
+        set_error("logp_cur, logp_behav, mask and seq_logratio_out must not be NULL");
+        return RAPID_ERR_NULL;
+    }
+    if (N <= 0 || T <= 0 || N * T > (int64_t)2000000000) {
+        set_error("bad shape N=%lld T=%lld", (long long)N, (long long)T);
+        return RAPID_ERR_SHAPE;
+    }
+    int rc = check_arch();
+    if (rc) return rc;
+    launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, nullptr, seq_logratio_out, 2.f, 0, nullptr,
+                        nullptr, nullptr, dev_status, (hipStream_t)stream);
+    return check_launch("rapid_seq_logratio");
+}
+
 int rapid_mfma_probe(int random_operands, int iters, double* tflops_out, double* ms_out, void* stream) {
     if (iters < 1 || iters > 10000000) {
         set_error("iters must be in 1 .. 10^7");

@@ -255,6 +255,8 @@ void set_cu_count(int n);              // compute units of the device: the contr
 
 
 void launch_sgd_step(float* master, const float* grad, int64_t n, float lr, void* w_out, int dtype, hipStream_t st);
+void launch_adamw_step(float* master, const float* grad, float* m, float* v, int64_t n, float lr, float beta1, float beta2,
+                       float eps, float weight_decay, int64_t step, void* w_out, int dtype, hipStream_t st);
 
 // ---- probe.hip -----------------------------------------------------------------------------------
 int run_mfma_probe(int random_operands, int iters, int num_cu, double* tflops_out, double* ms_out, hipStream_t st);

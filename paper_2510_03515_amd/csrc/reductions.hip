@@ -320,7 +320,7 @@ __global__ void seq_logratio_kernel(const float* __restrict__ logp_cur, const fl
         cmax = wave_max(cmax);
     }
     if (threadIdx.x == 0) {
-        s64[n] = acc;
+        if (s64) s64[n] = acc;
         if (s32) s32[n] = (float)acc;
         if (tsum) {
             tsum[n] = csum;
@@ -823,6 +823,38 @@ __global__ void sgd_step_kernel(float* __restrict__ master, const float* __restr
 }
 void launch_sgd_step(float* master, const float* grad, int64_t n, float lr, void* w_out, int dtype, hipStream_t st) {
     if (n > 0) sgd_step_kernel<<<blocks_for(n, 256), 256, 0, st>>>(master, grad, n, lr, w_out, dtype);
+}
+
+// AdamW: bias corrections 1 - beta^step are formed on the host in double
+__global__ void adamw_step_kernel(float* __restrict__ master, const float* __restrict__ grad, float* __restrict__ m,
+                                  float* __restrict__ v, int64_t n, float lr, float beta1, float beta2, float eps,
+                                  float weight_decay, float inv_bc1, float inv_bc2, void* __restrict__ w_out, int dtype) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float g = grad[i];
+    const float mi = beta1 * m[i] + (1.f - beta1) * g;
+    const float vi = beta2 * v[i] + (1.f - beta2) * g * g;
+    m[i] = mi;
+    v[i] = vi;
+    const float w0 = master[i];
+    const float w = w0 - lr * ((mi * inv_bc1) / (sqrtf(vi * inv_bc2) + eps) + weight_decay * w0);
+    master[i] = w;
+    if (w_out) {
+        if (dtype == RAPID_DTYPE_BF16) {
+            const __bf16 r = (__bf16)w;
+            ((bf16_t*)w_out)[i] = __builtin_bit_cast(bf16_t, r);
+        } else {
+            ((float*)w_out)[i] = w;
+        }
+    }
+}
+void launch_adamw_step(float* master, const float* grad, float* m, float* v, int64_t n, float lr, float beta1, float beta2,
+                       float eps, float weight_decay, int64_t step, void* w_out, int dtype, hipStream_t st) {
+    const float inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
+    const float inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+    if (n > 0)
+        adamw_step_kernel<<<blocks_for(n, 256), 256, 0, st>>>(master, grad, m, v, n, lr, beta1, beta2, eps, weight_decay,
+                                                              inv_bc1, inv_bc2, w_out, dtype);
 }
 
 void launch_f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t st) {

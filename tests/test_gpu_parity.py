@@ -713,6 +713,10 @@ def test_inner_loop_on_synthetic_bandit(rb):
     assert np.abs(_np(out.seq_logratio) - ref["seq_logratio"]).max() <= S_ATOL
     assert abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
     _dw_ok(out.dW, ref["dW"])
+    # the same loop with AdamW as the update: first step on-policy as well, staleness grows, the estimate improves
+    log_a, summary_a, _ = loop.iw_grpg(g, inner_steps=6, lr=2e-3, optimizer="adamw")
+    assert log_a[0]["staleness"] == 0.0 and log_a[-1]["staleness"] > log_a[1]["staleness"] > 0
+    assert summary_a["reward_final_is_estimate"] > summary_a["reward_behaviour"]
     # the update itself: fp32 master, bf16 copy
     m = torch.randn(1000, device="cuda"); gr = torch.randn(1000, device="cuda"); wo = torch.empty(1000, dtype=torch.bfloat16, device="cuda")
     m0 = m.clone()
@@ -850,49 +854,6 @@ def test_fused_shuffled_groups_mask_holes_and_bad_values(rb):
     _dw_ok(out.dW, ref["dW"])
 
 
-def test_autograd_wrapper_against_plain_pytorch(rb):
-    """The fused call as a PyTorch loss: gradients reach a PyTorch body through `hidden`, and they
-    agree with torch's own autograd of the same estimator written in plain fp32 PyTorch ops on the
-    GPU (a leg independent of the oracle): loss, dL/dW and dL/d(body weight)."""
-    from paper_2510_03515_amd.autograd import iw_pg_loss
-    spec = SPECS["bf16_small"]
-    w, g = _make(spec)
-    N, T, d = g["hidden"].shape
-    torch.manual_seed(3)
-    body = torch.nn.Linear(d, d, bias=False).cuda()
-    with torch.no_grad():
-        body.weight.copy_(torch.eye(d, device="cuda") + 0.05 * torch.randn(d, d, device="cuda"))
-    x = g["hidden"].float()
-    mask, tok, R, gid, K = g["mask"], g["tokens"], g["rewards"], g["group_ids"].long(), w["K"]
-    logp_b, _ = rb.rapid_logprob_fwd(body(x).to(torch.bfloat16).detach(), g["W_old"], tok, mask)
-
-    def plain(hidden, W):
-        z = hidden.float() @ W.float()
-        logp = torch.log_softmax(z, -1).gather(-1, tok.long()[..., None]).squeeze(-1)
-        s = ((logp - logp_b) * mask).sum(1)
-        wgt = torch.exp(torch.clamp(s, max=math.log(2.0))).detach()
-        cnt = torch.zeros(K, device="cuda").index_add(0, gid, torch.ones_like(R))
-        base = torch.zeros(K, device="cuda").index_add(0, gid, wgt * R) / cnt
-        adv = (R - base[gid]).detach()
-        return -(torch.exp(s) * adv).mean()
-
-    grads = []
-    for fn in (lambda h, W: iw_pg_loss(h, W, tok, mask, logp_b, R, g["group_ids"], K), plain):
-        body.zero_grad()
-        W = g["W"].clone().requires_grad_(True)
-        loss = fn(body(x).to(torch.bfloat16), W)
-        loss.backward()
-        grads.append((loss.item(), W.grad.float().clone(), body.weight.grad.clone()))
-    (l0, dW0, db0), (l1, dW1, db1) = grads
-    assert abs(l0 - l1) <= 2e-3 * abs(l1)
-    assert _rel(_np(dW0), _np(dW1)) <= 3e-2 and _rel(_np(db0), _np(db1)) <= 3e-2
-    # the incoming gradient scales both
-    body.zero_grad()
-    W = g["W"].clone().requires_grad_(True)
-    (3.0 * iw_pg_loss(body(x).to(torch.bfloat16), W, tok, mask, logp_b, R, g["group_ids"], K)).backward()
-    assert _rel(_np(W.grad.float()), 3.0 * _np(dW0)) <= 1e-2
-
-
 # ----------------------------------------------------------------------------- baselines' loss steps
 def _clip_inputs(rb, spec, seed, ref_shift=0.02, temperature=1.0):
     """Old-policy log-probs from the workload's W_old; reference log-probs from a third set of weights
@@ -1017,3 +978,45 @@ def test_clip_pg_special_cases_and_chunks(rb):
                                             g["group_ids"], K, variant=variant, buffers=buf, logits_cache=True)
         torch.cuda.synchronize()
         _check_clip(rb, spec, w, out, ref, None)
+
+
+def test_seq_logratio_and_adamw_entry_points(rb):
+    """The ratio reduction as a call of its own (arbitrary masks, a non-finite stored log-prob), and the
+    AdamW update of the inner loop over a few steps, both against the oracle."""
+    rng = np.random.default_rng(51)
+    N, T = 37, 301
+    cur = (-rng.random((N, T)) * 12).astype(np.float32)
+    beh = (cur + rng.normal(size=(N, T)).astype(np.float32) * 0.3).astype(np.float32)
+    mask = (rng.random((N, T)) < 0.7).astype(np.uint8)
+    mask[3] = 0
+    s, tok = rb.rapid_seq_logratio(torch.from_numpy(cur).cuda(), torch.from_numpy(beh).cuda(), torch.from_numpy(mask).cuda(),
+                                   want_tokens=True)
+    torch.cuda.synchronize()
+    assert np.abs(_np(s) - orc.seq_logratio(cur, beh, mask)).max() <= 2e-5          # float storage of a sum of ~200 terms
+    # the difference of two floats, formed exactly and rounded to float once: the same bits as the oracle's, rounded
+    assert np.array_equal(_np(tok), orc.token_logratio(cur, beh, mask).astype(np.float32).astype(np.float64))
+    assert s[3].item() == 0.0
+    beh_bad = beh.copy()
+    n_bad, t_bad = np.argwhere(mask == 1)[11]
+    beh_bad[n_bad, t_bad] = np.inf
+    status = torch.zeros(1, dtype=torch.int32).cuda()
+    s2, _ = rb.rapid_seq_logratio(torch.from_numpy(cur).cuda(), torch.from_numpy(beh_bad).cuda(), torch.from_numpy(mask).cuda(),
+                                  dev_status=status)
+    torch.cuda.synchronize()
+    beh0 = beh.copy(); beh0[n_bad, t_bad] = cur[n_bad, t_bad]
+    assert status.item() & rb.STATUS_NONFINITE_LOGP and np.abs(_np(s2) - orc.seq_logratio(cur, beh0, mask)).max() <= 2e-5
+    # AdamW
+    n = 5000
+    w0 = rng.normal(size=n).astype(np.float32)
+    master = torch.from_numpy(w0.copy()).cuda()
+    m, v = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    wo = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    w_ref, m_ref, v_ref = w0.astype(np.float64), np.zeros(n), np.zeros(n)
+    lr, b1, b2, eps, wd = (float(np.float32(x)) for x in (1e-2, 0.9, 0.999, 1e-8, 0.05))    # the ABI takes floats
+    for step in range(1, 5):
+        g = (rng.normal(size=n) * 10.0 ** rng.integers(-4, 1)).astype(np.float32)
+        rb.rapid_adamw_step(master, torch.from_numpy(g).cuda(), m, v, step, lr, b1, b2, eps, wd, w_out=wo)
+        w_ref, m_ref, v_ref = orc.adamw_step(w_ref, g, m_ref, v_ref, step, lr, b1, b2, eps, wd)
+        torch.cuda.synchronize()
+        assert np.abs(_np(master) - w_ref).max() <= 1e-5 and np.allclose(_np(m), m_ref, rtol=1e-5, atol=1e-9)
+        assert np.allclose(_np(v), v_ref, rtol=1e-5, atol=1e-12) and torch.equal(wo, master.to(torch.bfloat16))

@@ -747,3 +747,23 @@ def test_clipped_pg_special_cases():
     Rz = R.copy(); Rz[:3] = 0.5          # exactly representable: the group mean is exact
     z = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, cur + 0.2 * (mask != 0), None, Rz, gid, 2)
     assert np.all(z["adv"][:3] == 0.0) and np.all(z["g"][:3] == 0.0) and np.any(z["g"][3:] != 0.0)
+
+
+def test_adamw_step_against_torch():
+    """Library leg: torch.optim.AdamW in float64 over five steps, with and without weight decay; and the
+    first step's closed form: m_hat = g, v_hat = g^2, so w moves by lr * sign(g) (up to eps)."""
+    rng = np.random.default_rng(41)
+    for wd in (0.0, 0.1):
+        w0 = rng.normal(size=37)
+        p = torch.nn.Parameter(torch.tensor(w0))
+        opt = torch.optim.AdamW([p], lr=3e-3, betas=(0.9, 0.95), eps=1e-8, weight_decay=wd)
+        w, m, v = w0.copy(), np.zeros(37), np.zeros(37)
+        for step in range(1, 6):
+            g = rng.normal(size=37) * 10.0 ** rng.integers(-3, 2)
+            p.grad = torch.tensor(g)
+            opt.step()
+            w, m, v = orc.adamw_step(w, g, m, v, step, 3e-3, 0.9, 0.95, 1e-8, wd)
+            assert np.allclose(w, p.detach().numpy(), rtol=0, atol=1e-14), (wd, step)
+    g = np.array([0.5, -2.0, 1e-3])
+    w, _, _ = orc.adamw_step(np.zeros(3), g, np.zeros(3), np.zeros(3), 1, 0.01, eps=0.0)
+    assert np.allclose(w, -0.01 * np.sign(g), atol=1e-15)
