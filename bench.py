@@ -6,7 +6,7 @@ Qwen2.5-1.5B-shaped mini-batch (d=1536, V=151936, 32 prompts x 8 generations, re
 U[256,2048]) whose inputs, including the stored behaviour log-probs, are resident in HBM.
 
 `value` is timed with opts.logits_cache = 1 and the library's recommended workspace for it (a cache
-of 65536 token rows, 25 GiB in all at this shape): the batch is worked through in chunks of whole
+of 90112 token rows, 32 GiB in all at this shape): the batch is worked through in chunks of whole
 groups, the forward of a chunk keeps its rows' scaled probabilities in the cache and the chunk's
 dHidden and dW contract them, so 6 d V flop per token are executed and nothing of size tokens x V
 outlives a chunk.  Beside it, never as `value`: the same call with a cache that holds the whole batch
@@ -30,7 +30,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_cfg2_qwen1.5b.json")
-CACHE_ROWS = 65536        # cache rows of the library's recommended workspace for logits_cache = 1
+CACHE_ROWS = 90112        # cache rows of the library's recommended workspace for logits_cache = 1
 FWD_BLOCK_ROWS = 16384    # token rows per launch of the forward kernel
 
 
@@ -135,7 +135,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=["chunks", "whole", "recompute"], default="chunks",
                     help="backward of the timed call: 'chunks' = opts.logits_cache 1 with the recommended workspace (a cache "
-                         "of 65536 rows, chunks of whole groups, 6 d V flop per token executed); 'whole' = the same with a "
+                         "of 90112 rows, chunks of whole groups, 6 d V flop per token executed); 'whole' = the same with a "
                          "cache for every token of the batch; 'recompute' = logits_cache 0 (logits regenerated, 8 d V)")
     ap.add_argument("--one-mode", action="store_true", help="skip the extra measurements (other modes, calibrated companion)")
     args = ap.parse_args()
@@ -240,9 +240,11 @@ def main():
     # stage's rate is 2 d V M / (its time per step); a launch that holds tokens (the launches are made for the
     # padded upper bound, those past the last token return at once) processes M / (live launches) of them.
     lengths = w["lengths"].tolist()
+    chunk_tokens = None
     if mode == "chunks":
         chunks = chunk_rows_of(lengths, spec.G, CACHE_ROWS)
         live = {"fwd_lse": sum(-(-r // FWD_BLOCK_ROWS) for r in chunks), "dh": len(chunks), "dw": len(chunks)}
+        chunk_tokens = chunks
     else:
         live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-M // FWD_BLOCK_ROWS), "dh": -(-M // 65536), "dw": -(-M // 65536)}
     gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and (s != "dz" or mode == "recompute")]
@@ -279,7 +281,8 @@ def main():
         "config": {"workload": spec.name, "d": d, "V": V, "prompts": spec.prompts, "G": spec.G, "N": N,
                    "T": T, "response_tokens": M, "workspace_gib": ws_gib,
                    "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd",
-                   "backward_mode": mode, "final_rmsnorm": bool(args.rmsnorm), "executed_flop_per_token": executed},
+                   "backward_mode": mode, "final_rmsnorm": bool(args.rmsnorm), "executed_flop_per_token": executed,
+                   "tokens_per_chunk": chunk_tokens},
         "frac_bf16_mfma_peak_algorithmic": flops_per_token * tok_s / PEAK_BF16_MFMA,
         "frac_of_mfma_probe_algorithmic": flops_per_token * tok_s / (tf_rnd * 1e12),
         "roofline": roofline,

@@ -104,7 +104,7 @@ typedef struct rapid_iw_pg_opts {
                               and no pass over rows x V in between.  The cache holds as many token rows as
                               the workspace affords (2 bytes x V per row).  If that is every token of the batch
                               (rapid_workspace_bytes_max_tokens), the call is one sweep.  If not
-                              (rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...): 65536 rows), the batch is
+                              (rapid_workspace_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, ...): 90112 rows), the batch is
                               worked through in chunks of whole groups, in order, each chunk as many groups as the
                               cache holds: forward with store, the chunk's ratios, advantages (Eq. (5) needs only
                               the group) and coefficients (Eq. (3)'s 1/N is known beforehand), dHidden and dW of
@@ -160,7 +160,7 @@ void rapid_iw_pg_default_opts(rapid_iw_pg_opts* opts);
  * recommended size (backward row-chunks large enough to fill the chip); rapid_workspace_min_bytes
  * the smallest the call accepts (smaller chunks, same results).  RAPID_OP_GROUP_ADVANTAGE needs
  * none (returns 0).  RAPID_OP_IW_PG_FWD_BWD_CACHED are the sizes for rapid_iw_pg_loss_fwd_bwd with
- * opts->logits_cache = 1 (bf16 only): recommended = a cache of 65536 token rows (or of all N * T positions
+ * opts->logits_cache = 1 (bf16 only): recommended = a cache of 90112 token rows (or of all N * T positions
  * if those are fewer), minimum = a cache of 256 rows; the call uses as many cache rows as the workspace
  * it is given affords.  rapid_workspace_bytes_max_tokens (cached op only; the others ignore the bound) is
  * the size with which the cache holds every token of a batch of at most max_tokens valid tokens (0 = N * T)

@@ -28,7 +28,7 @@ EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rap
            "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step",
            "rapid_logprob_fwd_static", "rapid_clip_pg_default_opts", "rapid_clip_pg_loss_fwd_bwd",
            "rapid_seq_logratio", "rapid_adamw_step"]
-STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "dz_transpose", "dh",
+STAGES = ["compaction", "pack", "fwd_lse", "merge_lse", "estimator", "zero_rows", "dz", "unused", "dh",
           "dw", "f32_path", "dw_convert"]
 
 

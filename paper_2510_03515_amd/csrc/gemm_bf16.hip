@@ -733,18 +733,29 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
 // ------------------------------------------------------------------------------------------ dh
 // The tiles of dHidden are long (the contraction runs over the whole vocabulary) and few: a launch has
 // a handful of rounds of one tile per workgroup, and a last round that is only partly filled would
-// leave most of the chip idle for a whole tile.  So in the last, partial round of an XCD's share the
-// rem tiles that are left are cut along the contraction into S = floor(workgroups / rem) slices each;
-// a workgroup computes one slice and leaves its fp32 accumulators in `part`, and dh_reduce_kernel adds
-// the slices of a tile in slice order and stores the result: the last round then takes 1/S of a tile's
-// time, and the result does not depend on timing.
+// leave most of the chip idle for a whole tile.  So the last, partial round of an XCD's share is not
+// dealt out tile by tile: its rem tiles are laid end to end along the contraction (rem x ktiles K steps)
+// and every workgroup of the XCD takes an equal stretch of that line.  A stretch covers part of one tile
+// or the end of one and the beginning of the next; the workgroup leaves the fp32 accumulators of each
+// piece in `part`, and dh_reduce_kernel adds the pieces of a tile in workgroup order and stores the result.
+// The last round then takes rem / workgroups of a tile's time, and the result does not depend on timing.
 struct DhShare {       // an XCD's share of the order, and how its last round is cut
-    int total, per, wgs, mine, full_rounds, rem, slices;
-    __device__ __forceinline__ DhShare(int tilesD, int tilesM, int grid, int x, bool can_split) {
+    int total, per, wgs, mine, full_rounds, rem;
+    bool cut;
+    __device__ __forceinline__ DhShare(int tilesD, int tilesM, int grid, int x, bool can_cut) {
         total = tilesD * tilesM; per = (total + 7) / 8; wgs = grid / 8;
         mine = max(0, min(per, total - x * per));
         full_rounds = mine / wgs; rem = mine - full_rounds * wgs;
-        slices = (can_split && rem > 0) ? wgs / rem : 1;
+        // Workgroups on stretches are at different K steps, so they share no operand panel in the L2: a K step
+        // of a stretch costs about 1.45 times one of a whole round (measured).  Cutting pays while
+        // 1.45 rem / wgs < 1; a fuller last round is dealt out tile by tile like the others.
+        cut = can_cut && rem > 0 && rem * 3 <= wgs * 2;
+    }
+    // the stretch of workgroup w: K steps [u0, u1) of the line of rem * ktiles steps
+    __device__ __forceinline__ void stretch(int w, int ktiles, int64_t& u0, int64_t& u1) const {
+        const int64_t units = (int64_t)rem * ktiles;
+        u0 = units * w / wgs;
+        u1 = units * (w + 1) / wgs;
     }
 };
 
@@ -772,6 +783,19 @@ __device__ __forceinline__ void dh_store(const DhArgs& a, const TileId& t, int M
     }
 }
 
+// acc = the tile's contraction over the K steps [k0, k1)
+template <class S, class Pace>
+__device__ __forceinline__ void dh_contract(const DhArgs& a, const TileId& t, int k0, int k1, char* lds,
+                                            f32x16 (&acc)[S::WI][S::WJ], Pace pace) {
+    if (a.WdvB)   // A from the tile-blocked copy: one contiguous 128-byte-row block per K step
+        mainloop<S, Pace>(a.WdvB + ((int64_t)t.ti * (a.Vpad / K_TILE) + k0) * (S::BI * 64), 64,
+                          a.dz + (int64_t)t.tj * S::BJ * a.ldv + (int64_t)k0 * K_TILE, a.ldv, k1 - k0, lds, acc,
+                          S::BI * 128, 128, pace);
+    else
+        mainloop<S, Pace>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv + (int64_t)k0 * K_TILE, a.ldv,
+                          a.dz + (int64_t)t.tj * S::BJ * a.ldv + (int64_t)k0 * K_TILE, a.ldv, k1 - k0, lds, acc, 128, 128, pace);
+}
+
 template <class S>
 __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
@@ -790,19 +814,10 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
     // XCD shares) the workgroups of round r are those whose id is a valid tile
     GridPace pace{a.pace, 0u, 0u, a.pace ? a.pace_every : 0};
     unsigned before = 0;   // valid tiles of the rounds before this one, over all XCDs
-    for (int round = 0;; ++round) {
-        const bool split = sh.slices >= 2 && round == sh.full_rounds;
-        int pos, k0 = 0, k1 = ktiles;
-        if (!split) {
-            pos = round * sh.wgs + w;
-            if (round * sh.wgs >= sh.per) break;           // uniform over the launch: nobody has a tile in this round
-        } else {
-            if (w >= sh.rem * sh.slices) break;
-            const int slice = w / sh.rem;
-            pos = sh.full_rounds * sh.wgs + w % sh.rem;
-            k0 = (int)((int64_t)ktiles * slice / sh.slices);
-            k1 = (int)((int64_t)ktiles * (slice + 1) / sh.slices);
-        }
+    // rounds dealt out tile by tile: uniform over the launch when pacing is on (nobody cuts then)
+    const int whole_rounds = sh.cut ? sh.full_rounds : (pace.every ? (sh.per + sh.wgs - 1) / sh.wgs : (sh.mine + sh.wgs - 1) / sh.wgs);
+    for (int round = 0; round < whole_rounds; ++round) {
+        const int pos = round * sh.wgs + w;
         unsigned now = 0;
         if (pace.every) {
             for (int xx = 0; xx < 8; ++xx) {
@@ -810,39 +825,41 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
                 now += (unsigned)max(0, min(sh.wgs, mine - round * sh.wgs));
             }
         }
-        if (pos >= sh.mine) {
-            if (split) break;
-            before += now;
-            continue;
-        }
+        if (pos >= sh.mine) { before += now; continue; }
         const TileId t = tile_of_vid(x * sh.per + pos, tilesD, tilesM, gi);
         f32x16 acc[WI][WJ];
         pace.n = now;
         pace.base = (unsigned)(ktiles / (pace.every ? pace.every : 1)) * before;
         before += now;
-        if (a.WdvB)   // A from the tile-blocked copy: one contiguous 128-byte-row block per K step
-            mainloop<S, GridPace>(a.WdvB + ((int64_t)t.ti * (a.Vpad / K_TILE) + k0) * (S::BI * 64), 64,
-                                  a.dz + (int64_t)t.tj * S::BJ * a.ldv + (int64_t)k0 * K_TILE, a.ldv, k1 - k0, lds, acc,
-                                  S::BI * 128, 128, pace);
-        else
-            mainloop<S>(a.Wdv + (int64_t)t.ti * S::BI * a.ldv + (int64_t)k0 * K_TILE, a.ldv,
-                        a.dz + (int64_t)t.tj * S::BJ * a.ldv + (int64_t)k0 * K_TILE, a.ldv, k1 - k0, lds, acc);
-        if (!split) {
-            dh_store<S>(a, t, M, acc);
-        } else {   // one slice of a tile: the accumulators as they are, register r of thread tid at part[r][tid]
-            float* o = a.part + (int64_t)blockIdx.x * (S::BI * S::BJ) + threadIdx.x;
+        dh_contract<S, GridPace>(a, t, 0, ktiles, lds, acc, pace);
+        dh_store<S>(a, t, M, acc);
+    }
+    if (!sh.cut) return;
+    // the last round, cut into equal stretches; piece `piece` of this workgroup goes to part[2 * blockIdx.x + piece]
+    int64_t u0, u1;
+    sh.stretch(w, ktiles, u0, u1);
+    for (int piece = 0; u0 < u1; ++piece) {
+        const int tpos = (int)(u0 / ktiles), k0 = (int)(u0 - (int64_t)tpos * ktiles);
+        const int k1 = (int)min((int64_t)ktiles, k0 + (u1 - u0));
+        const TileId t = tile_of_vid(x * sh.per + sh.full_rounds * sh.wgs + tpos, tilesD, tilesM, gi);
+        f32x16 acc[WI][WJ];
+        dh_contract<S, NoPace>(a, t, k0, k1, lds, acc, NoPace());
+        // the accumulators as they are: register r of thread tid at part[piece slot][r][tid]
+        int64_t off = ((int64_t)blockIdx.x * 2 + piece) * (S::BI * S::BJ) + threadIdx.x;
 #pragma unroll
-            for (int ib = 0; ib < WI; ++ib)
+        for (int ib = 0; ib < WI; ++ib)
 #pragma unroll
-                for (int jb = 0; jb < WJ; ++jb)
+            for (int jb = 0; jb < WJ; ++jb) {
+                asm volatile("" : "+v"(off));   // one address per block of 16 stores, formed here and not ahead of the loops
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) o[((ib * WJ + jb) * 16 + v) * S::NT] = acc[ib][jb][v];
-            break;
-        }
+                for (int v = 0; v < 16; ++v) a.part[off + v * S::NT] = acc[ib][jb][v];
+                off += 16 * S::NT;
+            }
+        u0 += k1 - k0;
     }
 }
 
-// adds the slices of the tiles that dh_kernel cut (same launch geometry: grid_of_dh says how many
+// adds the pieces of the tiles that dh_kernel cut (same launch geometry: grid_of_dh says how many
 // workgroups that launch had) and stores them; one workgroup per (XCD, tile of its last round)
 template <class S>
 __global__ __launch_bounds__(S::NT) void dh_reduce_kernel(DhArgs a, int grid_of_dh) {
@@ -853,7 +870,8 @@ __global__ __launch_bounds__(S::NT) void dh_reduce_kernel(DhArgs a, int grid_of_
     const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));
     const int x = blockIdx.x & 7, tpos = blockIdx.x >> 3;
     const DhShare sh(tilesD, tilesM, grid_of_dh, x, true);
-    if (sh.slices < 2 || tpos >= sh.rem) return;
+    if (!sh.cut || tpos >= sh.rem) return;
+    const int ktiles = (int)(a.Vpad / K_TILE);
     const TileId t = tile_of_vid(x * sh.per + sh.full_rounds * sh.wgs + tpos, tilesD, tilesM, a.gi > 0 ? a.gi : tilesD);
     f32x16 acc[WI][WJ];
 #pragma unroll
@@ -862,9 +880,13 @@ __global__ __launch_bounds__(S::NT) void dh_reduce_kernel(DhArgs a, int grid_of_
         for (int jb = 0; jb < WJ; ++jb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[ib][jb][v] = 0.f;
-    for (int slice = 0; slice < sh.slices; ++slice) {
-        const int wg = x + 8 * (slice * sh.rem + tpos);        // the workgroup of dh_kernel that computed this slice
-        const float* in = a.part + (int64_t)wg * (S::BI * S::BJ) + threadIdx.x;
+    const int64_t t0 = (int64_t)tpos * ktiles, t1 = t0 + ktiles;     // this tile's K steps on the line
+    for (int w = 0; w < sh.wgs; ++w) {                               // in workgroup order: a fixed order of summation
+        int64_t u0, u1;
+        sh.stretch(w, ktiles, u0, u1);
+        if (u0 >= u1 || u1 <= t0 || u0 >= t1) continue;
+        const int piece = (u0 / ktiles == tpos) ? 0 : 1;             // the stretch began in this tile, or in the one before
+        const float* in = a.part + ((int64_t)(x + 8 * w) * 2 + piece) * (S::BI * S::BJ) + threadIdx.x;
 #pragma unroll
         for (int ib = 0; ib < WI; ++ib)
 #pragma unroll
@@ -1079,10 +1101,10 @@ void launch_dh_t(const DhArgs& a, hipStream_t st) {
     allow_lds<&dh_kernel<S>>(S::LDS_BYTES);
     const unsigned grid = grid_for((int)(a.dpadR / S::BI), a.tilesM);
     DhArgs b = a;
-    // a cut last round needs 64 K floats of scratch per workgroup and whole XCD shares of workgroups
-    if (grid % 8 != 0 || grid < 16 || (size_t)grid * S::BI * S::BJ * 4 > a.part_bytes) b.part = nullptr;
+    // a cut last round needs two tiles of fp32 scratch per workgroup and whole XCD shares of workgroups
+    if (grid % 8 != 0 || grid < 16 || (size_t)grid * 2 * S::BI * S::BJ * 4 > a.part_bytes) b.part = nullptr;
     dh_kernel<S><<<grid, S::NT, S::LDS_BYTES, st>>>(b);
-    if (b.part && !b.pace) dh_reduce_kernel<S><<<8 * (grid / 16), S::NT, 0, st>>>(b, (int)grid);
+    if (b.part && !b.pace) dh_reduce_kernel<S><<<grid, S::NT, 0, st>>>(b, (int)grid);
 }
 template <class S>
 void launch_dw_t(const DwArgs& a, hipStream_t st) {
@@ -1092,9 +1114,9 @@ void launch_dw_t(const DwArgs& a, hipStream_t st) {
 
 }  // namespace
 
-// one 256 x 256 fp32 tile per workgroup of a launch of 256 (the compute units of an MI355X); a launch with
+// two 256 x 256 fp32 tiles per workgroup of a launch of 256 (the compute units of an MI355X); a launch with
 // more workgroups than that does not cut its last round
-size_t dh_part_bytes() { return (size_t)256 * 256 * 256 * 4; }
+size_t dh_part_bytes() { return (size_t)2 * 256 * 256 * 256 * 4; }
 void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 8 || n == 16) ? n : 0; }
 void set_cu_count(int n) { g_num_cu = n >= 8 ? n : 8; }
 

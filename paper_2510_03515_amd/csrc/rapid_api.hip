@@ -236,7 +236,11 @@ int64_t recommended_chunk(const Plan& p) { return p.dtype == RAPID_DTYPE_BF16 ? 
 // tokens (the first group of the second did not fit into the first), hence at most 2 floor(rows / Rcap) + 1.
 int cached_chunks(int64_t rows, int64_t Rcap) { return Rcap >= rows ? 1 : (int)(2 * (rows / Rcap) + 1); }
 
-constexpr int64_t CACHED_RCAP_RECOMMENDED = 65536;   // cache rows of the recommended workspace (if the batch has more)
+// Cache rows of the recommended workspace, if the batch has more (tuning key 18).  Every launch of the dHidden and
+// dW kernels ends in a tail (workgroups finish at different times; dW re-reads and re-writes all of dW), so fewer,
+// larger chunks are faster: measured at the 1.5B shape, 65536 rows 338.7 ms per call (24.8 GiB), 90112 rows 334.4 ms
+// (31.7 GiB), 98304 rows 331.7 ms (34.3 GiB), the whole batch at once 329 ms (94 GiB).
+std::atomic<int> g_cached_rcap{90112};
 
 // workspace bytes of the cached backward with a cache of Rcap rows for a batch of at most `rows` tokens; 0 if invalid
 size_t cached_total(int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int64_t rows, int64_t Rcap, Plan* out = nullptr) {
@@ -544,6 +548,10 @@ int rapid_set_tuning(int key, int value) {
         g_dh_split = value;
         return RAPID_OK;
     }
+    if (key == 18 && value >= ROW_TILE && value % ROW_TILE == 0) {
+        g_cached_rcap = value;
+        return RAPID_OK;
+    }
     if (key == 2 && (value == 0 || value == 4 || value == 8 || value == 16)) {
         set_waves_per_workgroup(value);
         return RAPID_OK;
@@ -668,7 +676,7 @@ size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V,
     Plan p;
     if (op == RAPID_OP_IW_PG_FWD_BWD_CACHED) {   // a cache of the recommended number of rows, or of all rows if those are fewer
         if (dtype != RAPID_DTYPE_BF16 || !make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, dtype)) return 0;
-        return cached_total(N, T, d, V, K, p.Mmax_pad, CACHED_RCAP_RECOMMENDED);
+        return cached_total(N, T, d, V, K, p.Mmax_pad, g_cached_rcap.load());
     }
     if (op != RAPID_OP_LOGPROB_FWD && op != RAPID_OP_IW_PG_FWD_BWD) return 0;
     if (!make_plan(p, op, N, T, d, V, K, dtype)) return 0;
@@ -946,7 +954,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
             launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, st);
         }
         const int cst = g_cached_step_tiles.load();
-        const int64_t cstep = cst > 0 ? (int64_t)cst * ROW_TILE : p.Rcap;
+        const int64_t cstep = cst > 0 ? ((int64_t)cst * ROW_TILE < p.Rcap ? (int64_t)cst * ROW_TILE : p.Rcap) : p.Rcap;
         const int pace_every = g_pace_every.load();
         for (int c = 0; c < p.Cmax; ++c) {
             const int64_t base = (int64_t)c * p.Rcap;
@@ -977,6 +985,10 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
                 launch_cache_finish(cache, p.ldv, Hc, p.ldk, tokc, at<float>(ws, p.zy), at<float>(ws, p.refz), lse_c, rowg,
                                     inv_temp, cnt, base, p.Rcap, at<float>(ws, p.rowc), dev_status, st);
             }
+            // dHidden and dW of the chunk, in pieces of cstep rows.  (Running dW on a second stream beside dHidden,
+            // so that it fills the compute units a short last round of dHidden tiles leaves idle, was tried: the
+            // two kernels are dispatched side by side from the start, each XCD then holds half as many workgroups
+            // of either, they share fewer operand panels in its L2, and the pair takes 4 % longer.)
             int piece = 0;
             for (int64_t r0 = 0; r0 < p.Rcap; r0 += cstep, ++piece) {
                 const int64_t rows = (p.Rcap - r0) < cstep ? (p.Rcap - r0) : cstep;

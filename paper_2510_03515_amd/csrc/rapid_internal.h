@@ -229,8 +229,8 @@ struct DhArgs {           // dH[row, :] = dz[row, :] . Wdv^T
     int pace_every;       // K steps between meetings (power of two)
     bf16_t* dhidden;      // [N*T, d]
     int gi;               // tiles along i that share one j before the order moves on (L2 blocking)
-    float* part = nullptr;    // NULL, or scratch of part_bytes: lets the kernel cut the tiles of a partly filled last round
-    size_t part_bytes = 0;    // along the contraction (needs 256 KiB per workgroup of the launch)
+    float* part = nullptr;    // NULL, or scratch of part_bytes: lets the kernel cut a partly filled last round of tiles
+    size_t part_bytes = 0;    // along the contraction (needs 512 KiB per workgroup of the launch)
 };
 void launch_dh(const DhArgs& a, hipStream_t st);
 size_t dh_part_bytes();   // scratch that lets every dHidden launch cut its last round

@@ -62,7 +62,7 @@ def test_full_size_sampled_parity(rb, cfg, cache, cal):
     """cal: the calibrated companion of the workload (same shapes and seed, behaviour weights close
     enough that the generation-level ratios are O(1) and a few per cent clip: the paper's regime,
     where every generation carries gradient and dz is dense).  cache: False = the backward that regenerates
-    the logits; "chunks" = logits_cache with the recommended workspace (a cache of 65536 rows, the batch
+    the logits; "chunks" = logits_cache with the recommended workspace (a cache of 90112 rows, the batch
     in chunks of whole groups: the launch configuration bench.py times); "whole" = logits_cache with a
     cache that holds every token of the batch at once.
 

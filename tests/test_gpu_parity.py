@@ -555,8 +555,11 @@ def test_logits_cache_sized_for_a_token_bound(rb):
     out = rb.rapid_iw_pg_loss_fwd_bwd(*args, buffers=small_buf, logits_cache=True, max_tokens=M)
     torch.cuda.synchronize()
     assert out.dev_status.item() == 0
-    for k in ("loss", "dhidden", "dW", "logp_cur", "seq_logratio", "adv"):
+    for k in ("loss", "dW", "logp_cur", "seq_logratio", "adv"):
         assert torch.equal(getattr(out, k), getattr(full, k)), k
+    # dHidden cuts a partly filled last round of tiles along the vocabulary, and where it cuts depends on the
+    # number of workgroups of the launch, which follows the rows the cache was sized for: another order of summation
+    assert _rel(_np(out.dhidden), _np(full.dhidden)) <= 2e-3
     ref_dW, ref_dH = full.dW.clone(), full.dhidden.clone()
     out = rb.rapid_iw_pg_loss_fwd_bwd(*args, buffers=small_buf, logits_cache=True, max_tokens=M + 600)   # in chunks now
     torch.cuda.synchronize()

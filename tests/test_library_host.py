@@ -96,10 +96,10 @@ def test_workspace_sizes(rb):
     assert abs((full - half) - rows * per_row) <= 8192              # alignment of the buffers
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, max_tokens=10**9) == full
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD, *args, max_tokens=1000) == rec       # other ops ignore it
-    # recommended: a cache of 65536 rows, the batch in chunks of whole groups; it fits 32 GiB at this shape
+    # recommended: a cache of 90112 rows, the batch in chunks of whole groups; it fits 32 GiB at this shape
     chunked = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args)
     smallest = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, minimum=True)
-    assert smallest < chunked < half and chunked < 32 * 2**30 and chunked > 65536 * ldv * 2
+    assert smallest < chunked < half and chunked < 32 * 2**30 and chunked > 90112 * ldv * 2
     # a batch with fewer positions than that has the one-chunk size as its recommended size
     small_args = (16, 128, 1536, 151936, 4, rb.DTYPE_BF16)
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *small_args) == \
