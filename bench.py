@@ -30,8 +30,8 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA = 2.5e15   # MI355X dense bf16, FLOP/s
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_cfg2_qwen1.5b.json")
-CACHE_ROWS = 90112        # cache rows of the library's recommended workspace for logits_cache = 1
 FWD_BLOCK_ROWS = 16384    # token rows per launch of the forward kernel
+BWD_BLOCK_ROWS = 65536    # token rows per launch of the dHidden and dW kernels
 
 
 def measured_traffic(version, mode, stage):
@@ -240,13 +240,16 @@ def main():
     # stage's rate is 2 d V M / (its time per step); a launch that holds tokens (the launches are made for the
     # padded upper bound, those past the last token return at once) processes M / (live launches) of them.
     lengths = w["lengths"].tolist()
-    chunk_tokens = None
+    chunk_tokens = cache_rows = None
     if mode == "chunks":
-        chunks = chunk_rows_of(lengths, spec.G, CACHE_ROWS)
-        live = {"fwd_lse": sum(-(-r // FWD_BLOCK_ROWS) for r in chunks), "dh": len(chunks), "dw": len(chunks)}
+        # the window the library takes from the workspace it was given (host arithmetic, the call's own)
+        cache_rows = rb.rapid_logits_cache_rows(N, T, d, V, w["K"], M, int(round(ws_gib * 2**30)))
+        chunks = chunk_rows_of(lengths, spec.G, cache_rows)
+        live = {"fwd_lse": sum(-(-r // FWD_BLOCK_ROWS) for r in chunks)}
+        live["dh"] = live["dw"] = sum(-(-r // BWD_BLOCK_ROWS) for r in chunks)
         chunk_tokens = chunks
     else:
-        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-M // FWD_BLOCK_ROWS), "dh": -(-M // 65536), "dw": -(-M // 65536)}
+        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-M // FWD_BLOCK_ROWS), "dh": -(-M // BWD_BLOCK_ROWS), "dw": -(-M // BWD_BLOCK_ROWS)}
     gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and (s != "dz" or mode == "recompute")]
     if gemm_stages:
         per_stage = {}
@@ -282,7 +285,7 @@ def main():
                    "T": T, "response_tokens": M, "workspace_gib": ws_gib,
                    "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd",
                    "backward_mode": mode, "final_rmsnorm": bool(args.rmsnorm), "executed_flop_per_token": executed,
-                   "tokens_per_chunk": chunk_tokens},
+                   "cache_rows": cache_rows, "tokens_per_chunk": chunk_tokens},
         "frac_bf16_mfma_peak_algorithmic": flops_per_token * tok_s / PEAK_BF16_MFMA,
         "frac_of_mfma_probe_algorithmic": flops_per_token * tok_s / (tf_rnd * 1e12),
         "roofline": roofline,

@@ -171,6 +171,13 @@ size_t rapid_workspace_min_bytes(int op, int64_t N, int64_t T, int64_t d, int64_
 size_t rapid_workspace_bytes_max_tokens(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype,
                                         int64_t max_tokens);
 
+/* Host arithmetic only: the number of token rows the cache of a logits_cache = 1 call would hold if it were given
+ * `workspace_bytes` of workspace and opts->max_tokens = max_tokens (0 = N * T).  Every token of the batch (one chunk) if
+ * that fits, otherwise the largest window that does; a window's chunks are whole groups in batch order, each as many
+ * groups as fit.  0 if the workspace is below the minimum or an argument is invalid. */
+int64_t rapid_logits_cache_rows(int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int64_t max_tokens,
+                                size_t workspace_bytes);
+
 /*
  * Behaviour / current-policy log-probabilities of the sampled tokens (Sec. 3.1: pi(y_t | .) is
  * the softmax of the LM head; Alg. 1, the step that snapshots the current policy as the behaviour

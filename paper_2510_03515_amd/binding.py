@@ -23,7 +23,7 @@ STATUS_BAD_TOKEN, STATUS_BAD_GROUP, STATUS_NONFINITE_REWARD, STATUS_NONFINITE_LO
 STATUS_TOKEN_BOUND = 32
 STATUS_GROUP_LAYOUT = 64
 
-EXPORTS = ["rapid_version", "rapid_last_error", "rapid_iw_pg_default_opts", "rapid_set_tuning",
+EXPORTS = ["rapid_version", "rapid_last_error", "rapid_logits_cache_rows", "rapid_iw_pg_default_opts", "rapid_set_tuning",
            "rapid_workspace_bytes", "rapid_workspace_min_bytes", "rapid_workspace_bytes_max_tokens", "rapid_logprob_fwd", "rapid_logprob_fwd_rmsnorm",
            "rapid_group_advantage", "rapid_iw_pg_loss_fwd_bwd", "rapid_compaction", "rapid_profile_read", "rapid_mfma_probe", "rapid_sgd_step",
            "rapid_logprob_fwd_static", "rapid_clip_pg_default_opts", "rapid_clip_pg_loss_fwd_bwd",
@@ -87,6 +87,8 @@ def load():
         fn.restype = sz
     lib.rapid_workspace_bytes_max_tokens.argtypes = [ci, i64, i64, i64, i64, i64, ci, i64]
     lib.rapid_workspace_bytes_max_tokens.restype = sz
+    lib.rapid_logits_cache_rows.argtypes = [i64, i64, i64, i64, i64, i64, sz]
+    lib.rapid_logits_cache_rows.restype = i64
     lib.rapid_logprob_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, f32, vp, vp, vp, vp, sz, vp]
     lib.rapid_logprob_fwd.restype = ci
     lib.rapid_logprob_fwd_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, f32, vp, vp, vp, vp]
@@ -208,6 +210,10 @@ def rapid_workspace_bytes(op, N, T, d, V, K, dtype, minimum=False, max_tokens=0)
         return lib.rapid_workspace_bytes_max_tokens(op, N, T, d, V, K, dtype, int(max_tokens))
     fn = lib.rapid_workspace_min_bytes if minimum else lib.rapid_workspace_bytes
     return fn(op, N, T, d, V, K, dtype)
+
+
+def rapid_logits_cache_rows(N, T, d, V, K, max_tokens, workspace_bytes):
+    return load().rapid_logits_cache_rows(N, T, d, V, K, int(max_tokens), int(workspace_bytes))
 
 
 def alloc_workspace(nbytes, device="cuda"):

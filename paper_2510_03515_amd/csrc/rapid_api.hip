@@ -252,6 +252,23 @@ size_t cached_total(int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int64
     return p.total + 1024;
 }
 
+// Cache rows a call with this workspace works with: every row of the batch if that fits (one chunk), otherwise the
+// largest window that does; 0 if not even one row tile fits.  Fills `out` with the plan of that geometry.
+int64_t choose_cache(int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int64_t rows, size_t workspace_bytes, Plan* out) {
+    size_t need = cached_total(N, T, d, V, K, rows, rows, out);
+    if (need != 0 && need <= workspace_bytes) return rows;
+    int64_t lo = 1, hi = rows / ROW_TILE - 1, best = 0;     // cache rows in row tiles
+    while (lo <= hi) {
+        const int64_t mid = (lo + hi) / 2;
+        need = cached_total(N, T, d, V, K, rows, mid * ROW_TILE);
+        if (need != 0 && need <= workspace_bytes) { best = mid; lo = mid + 1; } else { hi = mid - 1; }
+    }
+    // the size is not monotone everywhere (the number of regions steps down as the cache grows)
+    while (best > 0 && ((need = cached_total(N, T, d, V, K, rows, best * ROW_TILE, out)) == 0 || need > workspace_bytes))
+        --best;
+    return best * ROW_TILE;
+}
+
 // largest chunk that fits into `avail` bytes; 0 if even the minimum does not
 int64_t fit_chunk(const Plan& p, size_t avail) {
     if (!p.per_row) return avail >= p.fixed ? ROW_TILE : 0;
@@ -498,7 +515,7 @@ using namespace rapid;
 
 extern "C" {
 
-int rapid_version(void) { return 6; }
+int rapid_version(void) { return 7; }
 
 const char* rapid_last_error(void) { return g_err; }
 
@@ -671,6 +688,12 @@ size_t rapid_workspace_bytes_max_tokens(int op, int64_t N, int64_t T, int64_t d,
     return cached_total(N, T, d, V, K, rows, rows);
 }
 
+int64_t rapid_logits_cache_rows(int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int64_t max_tokens, size_t workspace_bytes) {
+    Plan p;
+    if (max_tokens < 0 || !make_plan(p, RAPID_OP_IW_PG_FWD_BWD, N, T, d, V, K, RAPID_DTYPE_BF16)) return 0;
+    return choose_cache(N, T, d, V, K, cache_rows(p, max_tokens), workspace_bytes, &p);
+}
+
 size_t rapid_workspace_bytes(int op, int64_t N, int64_t T, int64_t d, int64_t V, int64_t K, int dtype) {
     if (op == RAPID_OP_GROUP_ADVANTAGE) return 0;
     Plan p;
@@ -841,23 +864,10 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
     if (cached) {
         // The cache holds every token if the workspace allows (one chunk: groups may lie anywhere in the
         // batch); otherwise as many rows as fit, and the batch is worked through in chunks of whole groups.
-        const int64_t rows = cache_rows(p, o.max_tokens);
-        size_t need = cached_total(N, T, d, V, K, rows, rows, &p);
-        if (need == 0 || need > workspace_bytes) {
-            int64_t lo = 1, hi = rows / ROW_TILE - 1, best = 0;     // cache rows in row tiles
-            while (lo <= hi) {
-                const int64_t mid = (lo + hi) / 2;
-                need = cached_total(N, T, d, V, K, rows, mid * ROW_TILE);
-                if (need != 0 && need <= workspace_bytes) { best = mid; lo = mid + 1; } else { hi = mid - 1; }
-            }
-            // the size is not monotone everywhere (the number of regions steps down as the cache grows)
-            while (best > 0 && ((need = cached_total(N, T, d, V, K, rows, best * ROW_TILE, &p)) == 0 || need > workspace_bytes))
-                --best;
-            if (best == 0) {
-                set_error("workspace of %zu bytes is below the %zu the logits cache needs at least", workspace_bytes,
-                          rapid_workspace_min_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dtype));
-                return RAPID_ERR_WORKSPACE;
-            }
+        if (choose_cache(N, T, d, V, K, cache_rows(p, o.max_tokens), workspace_bytes, &p) == 0) {
+            set_error("workspace of %zu bytes is below the %zu the logits cache needs at least", workspace_bytes,
+                      rapid_workspace_min_bytes(RAPID_OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, dtype));
+            return RAPID_ERR_WORKSPACE;
         }
     } else {
         const int64_t Mfit = fit_chunk(p, workspace_bytes);

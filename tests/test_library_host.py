@@ -100,6 +100,16 @@ def test_workspace_sizes(rb):
     chunked = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args)
     smallest = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *args, minimum=True)
     assert smallest < chunked < half and chunked < 32 * 2**30 and chunked > 90112 * ldv * 2
+    # the window a call takes from a given workspace: the recommended size gives 90112 rows when no token bound is
+    # promised, more when the bound shrinks the per-row arrays (fewer regions); the one-chunk size gives every row;
+    # below the minimum nothing
+    dims = args[:5]
+    assert rb.rapid_logits_cache_rows(*dims, 0, chunked) == 90112
+    assert 90112 <= rb.rapid_logits_cache_rows(*dims, 300630, chunked) < 300800
+    assert rb.rapid_logits_cache_rows(*dims, 300630, half) == 300800
+    assert rb.rapid_logits_cache_rows(*dims, 0, full) == 256 * 2048
+    assert rb.rapid_logits_cache_rows(*dims, 0, smallest) == 256 and rb.rapid_logits_cache_rows(*dims, 0, smallest - 4096) == 0
+    assert rb.rapid_logits_cache_rows(*dims, 0, chunked - 4096) == 90112 - 256
     # a batch with fewer positions than that has the one-chunk size as its recommended size
     small_args = (16, 128, 1536, 151936, 4, rb.DTYPE_BF16)
     assert rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, *small_args) == \
