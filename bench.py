@@ -9,7 +9,9 @@ U[256,2048]) whose inputs, including the stored behaviour log-probs, are residen
 of 90112 token rows, 32 GiB in all at this shape): the batch is worked through in chunks of whole
 groups, the forward of a chunk keeps its rows' scaled probabilities in the cache and the chunk's
 dHidden and dW contract them, so 6 d V flop per token are executed and nothing of size tokens x V
-outlives a chunk.  Beside it, never as `value`: the same call with a cache that holds the whole batch
+outlives a chunk.  Generations of a group whose rewards are all 0 have advantage 0 by Eq. (5) and so
+no gradient; the cached backward leaves them out of dHidden and dW (exactly), and the flop counts
+here leave them out as well (`response_tokens_with_gradient`).  Beside it, never as `value`: the same call with a cache that holds the whole batch
 at once ("whole", 94 GiB), with the backward that regenerates the logits ("recompute", 8 d V flop
 per token), and on the workload's calibrated companion (dense gradients: every generation carries
 weight).
@@ -49,18 +51,28 @@ def measured_traffic(version, mode, stage):
     return (e.get("bytes_per_launch"), t.get("source")) if e else (None, None)
 
 
-def chunk_rows_of(lengths, G, cap):
+def chunk_rows_of(lengths, G, cap, with_gradient):
     """Host replica of the library's chunking (whole groups in order, each chunk as full as the cache
-    allows), for reporting only: the tokens of every chunk."""
-    chunks, cur = [], 0
+    allows), for reporting only: the tokens of every chunk, and how many of them carry gradient."""
+    chunks, cur, cur_live = [], 0, 0
     for k in range(0, len(lengths), G):
         rows = int(sum(lengths[k:k + G]))
         if cur and cur + rows > cap:
-            chunks.append(cur)
-            cur = 0
+            chunks.append((cur, cur_live))
+            cur = cur_live = 0
         cur += rows
-    chunks.append(cur)
+        cur_live += int(sum(l for l, g in zip(lengths[k:k + G], with_gradient[k:k + G]) if g))
+    chunks.append((cur, cur_live))
     return chunks
+
+
+def generations_with_gradient(w):
+    """Per generation: does its group have a reward that is not 0 (host arithmetic on the workload)."""
+    import numpy as np
+    rew, gid = w["rewards"].cpu().numpy(), w["group_ids"].cpu().numpy()
+    live = np.zeros(int(w["K"]), dtype=bool)
+    np.logical_or.at(live, gid, rew != 0)
+    return live[gid]
 
 
 def cpu_baseline(w, rb, group=2, logits_cache=False):
@@ -215,10 +227,8 @@ def main():
         ws = rb.alloc_workspace(ws_bytes)
         dt, stages = timed(lambda: rb.rapid_logprob_fwd(w["hidden"], w["W"], w["tokens"], w["mask"], workspace=ws, **rms))
         ws_gib = ws_bytes / 2**30
-        flops_per_token = 2.0 * d * V
         mode = "forward only"
     else:
-        flops_per_token = 6.0 * d * V
         mode = args.mode
         res = fused_mode(w, rms, M, mode)
         if res is None:              # no cache for this dtype, or no room
@@ -229,6 +239,13 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     tok_s = M * args.steps / dt
+    # Algorithmic work of one call: 2 d V flop per response token for the logits, and 2 d V each for dHidden and dW
+    # per token that carries gradient.  A generation whose whole group has reward 0 has advantage 0 (Eq. (5)) and
+    # gradient 0 whatever its ratio is; the cached backward leaves such generations out of the two contractions
+    # (exactly: their rows are zeros), so they are not counted as work either.
+    with_gradient = None if fwd_only else generations_with_gradient(w)
+    M_grad = 0 if fwd_only else int(w["lengths"].cpu().numpy()[with_gradient].sum())
+    flops_per_call = 2.0 * d * V * M + 4.0 * d * V * M_grad
     executed = {"forward only": 2.0, "chunks": 6.0, "whole": 6.0, "recompute": 8.0}[mode] * d * V
 
     # the MFMA pipe on its own (no memory traffic), outside the timed region: what the published
@@ -240,22 +257,24 @@ def main():
     # stage's rate is 2 d V M / (its time per step); a launch that holds tokens (the launches are made for the
     # padded upper bound, those past the last token return at once) processes M / (live launches) of them.
     lengths = w["lengths"].tolist()
-    chunk_tokens = cache_rows = None
+    chunk_tokens = chunk_tokens_grad = cache_rows = None
     if mode == "chunks":
         # the window the library takes from the workspace it was given (host arithmetic, the call's own)
         cache_rows = rb.rapid_logits_cache_rows(N, T, d, V, w["K"], M, int(round(ws_gib * 2**30)))
-        chunks = chunk_rows_of(lengths, spec.G, cache_rows)
-        live = {"fwd_lse": sum(-(-r // FWD_BLOCK_ROWS) for r in chunks)}
-        live["dh"] = live["dw"] = sum(-(-r // BWD_BLOCK_ROWS) for r in chunks)
-        chunk_tokens = chunks
+        chunks = chunk_rows_of(lengths, spec.G, cache_rows, with_gradient.tolist())
+        live = {"fwd_lse": sum(-(-r // FWD_BLOCK_ROWS) for r, _ in chunks)}
+        live["dh"] = live["dw"] = sum(-(-g // BWD_BLOCK_ROWS) for _, g in chunks)
+        chunk_tokens = [r for r, _ in chunks]
+        chunk_tokens_grad = [g for _, g in chunks]
     else:
-        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-M // FWD_BLOCK_ROWS), "dh": -(-M // BWD_BLOCK_ROWS), "dw": -(-M // BWD_BLOCK_ROWS)}
+        Mb = M_grad if mode == "whole" else M     # the cached backward leaves the rows without gradient out
+        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-M // FWD_BLOCK_ROWS), "dh": -(-Mb // BWD_BLOCK_ROWS), "dw": -(-Mb // BWD_BLOCK_ROWS)}
     gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and (s != "dz" or mode == "recompute")]
     if gemm_stages:
         per_stage = {}
         for st_name in gemm_stages:
             ms = stages[st_name]["ms_per_step"]
-            rate = 2.0 * d * V * M / (ms * 1e-3) / 1e12
+            rate = 2.0 * d * V * (M_grad if st_name in ("dh", "dw") and mode != "recompute" else M) / (ms * 1e-3) / 1e12
             per_stage[st_name] = {"achieved": rate, "frac": rate * 1e12 / PEAK_BF16_MFMA, "frac_of_probe": rate / tf_rnd,
                                   "ms_per_step": ms, "live_launches_per_step": live.get(st_name),
                                   "avg_live_launch_ms": ms / live[st_name] if live.get(st_name) else None}
@@ -282,12 +301,14 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "d": d, "V": V, "prompts": spec.prompts, "G": spec.G, "N": N,
-                   "T": T, "response_tokens": M, "workspace_gib": ws_gib,
+                   "T": T, "response_tokens": M, "response_tokens_with_gradient": None if fwd_only else M_grad,
+                   "workspace_gib": ws_gib,
                    "call": "rapid_logprob_fwd" if fwd_only else "rapid_iw_pg_loss_fwd_bwd",
                    "backward_mode": mode, "final_rmsnorm": bool(args.rmsnorm), "executed_flop_per_token": executed,
-                   "cache_rows": cache_rows, "tokens_per_chunk": chunk_tokens},
-        "frac_bf16_mfma_peak_algorithmic": flops_per_token * tok_s / PEAK_BF16_MFMA,
-        "frac_of_mfma_probe_algorithmic": flops_per_token * tok_s / (tf_rnd * 1e12),
+                   "cache_rows": cache_rows, "tokens_per_chunk": chunk_tokens,
+                   "tokens_with_gradient_per_chunk": chunk_tokens_grad},
+        "frac_bf16_mfma_peak_algorithmic": flops_per_call / (dt / args.steps) / PEAK_BF16_MFMA,
+        "frac_of_mfma_probe_algorithmic": flops_per_call / (dt / args.steps) / (tf_rnd * 1e12),
         "roofline": roofline,
         "stages": stages,
         "mfma_probe": {"unit": "TFLOP/s", "small_integer_operands": tf_int, "random_bf16_operands": tf_rnd,
@@ -297,7 +318,7 @@ def main():
         def summary(res, m, M_):
             return None if res is None else {
                 "backward_mode": m, "value": M_ * args.steps / res[0], "unit": "tokens/s", "ms_per_step": res[0] / args.steps * 1e3,
-                "frac_bf16_mfma_peak_algorithmic": flops_per_token * M_ * args.steps / res[0] / PEAK_BF16_MFMA,
+                "frac_bf16_mfma_peak_algorithmic": flops_per_call / (res[0] / args.steps) / PEAK_BF16_MFMA,
                 "workspace_gib": res[2], "executed_flop_per_token": (8.0 if m == "recompute" else 6.0) * d * V,
                 "stages_ms_per_step": {k: v["ms_per_step"] for k, v in res[1].items()}}
         # the same call in its other backward modes, timed the same way; reported beside `value`, never as it

@@ -40,6 +40,7 @@ std::atomic<int> g_probe_cus{256};            // compute units of the current de
 std::atomic<int> g_cached_step_tiles{256};    // row tiles per dHidden / dW launch with the cache (tuning key 15; 0 = all rows)
 std::atomic<int> g_pace_every{0};             // K steps between meetings of the dHidden workgroups (tuning key 16; 0 = off)
 std::atomic<int> g_fwd_block_tiles{64};       // row tiles per launch of the two logits kernels (tuning key 13)
+std::atomic<int> g_skip_idle{1};              // cached backward: generations without gradient are left out of dHidden / dW (tuning key 19)
 std::atomic<int> g_dh_split{1};               // dHidden cuts the tiles of a partly filled last round along the contraction (tuning key 17)
 
 // address of `scratch` on each device, looked up once per device with that device current
@@ -115,7 +116,7 @@ struct Plan {
     size_t fixed, total;
     // offsets into the workspace
     size_t counts, pace, seq_len, cu, row_index, tokc, seqc, zy, refz, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, adv64, g, g64, tsum, tmax,
-        Hc, Wvd, Wdv, WdvB, dh_part, part_max, part_sum, dw32, chunk0, tab, gen_row0, gen_chunk, gseen, lam_state, lam_chunk, beta_scale;
+        Hc, Wvd, Wdv, WdvB, dh_part, part_max, part_sum, dw32, chunk0, tab, gen_row0, gen_chunk, gseen, lam_state, lam_chunk, beta_scale, idle, len_live, cu_live, live_group;
 };
 
 size_t take(size_t& cur, size_t bytes) {
@@ -174,6 +175,10 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
             p.gen_row0 = take(cur, (size_t)N * 4);
             p.gen_chunk = take(cur, (size_t)N * 4);
             p.gseen = take(cur, (size_t)K * 4);
+            p.idle = take(cur, (size_t)N * 4);
+            p.len_live = take(cur, (size_t)N * 4);
+            p.cu_live = take(cur, (size_t)(N + 1) * 4);
+            p.live_group = take(cur, (size_t)K * 4);
             p.lam_state = take(cur, 2 * 8);
             p.lam_chunk = take(cur, (size_t)Cmax * 8);
             p.beta_scale = take(cur, 64);
@@ -565,6 +570,10 @@ int rapid_set_tuning(int key, int value) {
         g_dh_split = value;
         return RAPID_OK;
     }
+    if (key == 19 && (value == 0 || value == 1)) {
+        g_skip_idle = value;
+        return RAPID_OK;
+    }
     if (key == 18 && value >= ROW_TILE && value % ROW_TILE == 0) {
         g_cached_rcap = value;
         return RAPID_OK;
@@ -939,11 +948,20 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
         const bool dw_adds_to_caller = o.accumulate_dw && !dw_staged;
         io.zc = cache;
         io.ref_logp = logp_behav;
+        // Generations whose coefficient is zero before any log-prob is known (a group whose rewards are all 0, or a
+        // zero override) come last inside their chunk, and dHidden and dW stop in front of them.  With the
+        // baselines' KL term every token carries gradient: nothing is idle then.
+        IdleArgs idle_args;
+        if (g_skip_idle.load() && !(clip && clip->o.kl_beta != 0.f)) {
+            idle_args.rewards = rewards; idle_args.coef_override = clip ? nullptr : o.coef_override;
+            idle_args.idle = at<int32_t>(ws, p.idle); idle_args.len_live = at<int32_t>(ws, p.len_live);
+            idle_args.cu_live = at<int32_t>(ws, p.cu_live); idle_args.live_group = at<int32_t>(ws, p.live_group);
+        }
         {
             Span sp(ST_COMPACT, st);
             launch_compaction_chunked(mask, group_ids, N, T, K, p.Rcap, p.Cmax, at<int32_t>(ws, p.seq_len),
                                       at<int32_t>(ws, p.cu), tab, at<int32_t>(ws, p.gen_row0), gen_chunk,
-                                      at<int32_t>(ws, p.gseen), row_index, counts, dev_status, st);
+                                      at<int32_t>(ws, p.gseen), row_index, counts, dev_status, idle_args, st);
             launch_fill_f32(logp_cur, p.Mmax, 0.f, st);
             launch_fill_f64(lam_state, 1, -INFINITY, st);
         }
@@ -961,7 +979,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
         }
         {
             Span sp(ST_ZERO, st);
-            launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, st);
+            launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, idle_args.idle, T, st);
         }
         const int cst = g_cached_step_tiles.load();
         const int64_t cstep = cst > 0 ? ((int64_t)cst * ROW_TILE < p.Rcap ? (int64_t)cst * ROW_TILE : p.Rcap) : p.Rcap;
@@ -1006,7 +1024,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
                 DhArgs ha;
                 ha.Wdv = at<bf16_t>(ws, p.Wdv); ha.WdvB = blocked_wdv ? at<bf16_t>(ws, p.WdvB) : nullptr; ha.dz = dz;
                 ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
-                ha.tilesM = (int)(rows / 256); ha.m0 = base + r0; ha.row_index = row_index; ha.counts = cnt;
+                ha.tilesM = (int)(rows / 256); ha.m0 = base + r0; ha.row_index = row_index; ha.counts = cnt + CH_LIVE;
                 ha.rowc = at<float>(ws, p.rowc);
                 ha.pace = pace_every > 0 ? at<unsigned>(ws, p.pace) : nullptr; ha.pace_every = pace_every;
                 if (ha.pace) launch_fill_f32((float*)ha.pace, 64, 0.f, st);
@@ -1018,7 +1036,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
                 }
                 DwArgs wa;
                 wa.dz = dz; wa.Hc = Hc + (base + r0) * p.ldk; wa.Mc = rows; wa.ldz = p.ldv; wa.ldH = p.ldk;
-                wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = base + r0; wa.counts = cnt;
+                wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = base + r0; wa.counts = cnt + CH_LIVE;
                 wa.dW = dW32; wa.w_layout = o.w_layout; wa.gi = g_gi_dw;
                 wa.beta = (c > 0 || piece > 0 || dw_adds_to_caller) ? 1 : 0;
                 // the sum over the earlier chunks is brought to this chunk's scale, once, by its first piece
@@ -1088,7 +1106,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
     // backward, in row chunks
     {
         Span sp(ST_ZERO, st);
-        launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, st);
+        launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, nullptr, T, st);
     }
     const bool dw_staged = o.dw_dtype == RAPID_DTYPE_BF16;
     float* dW32 = dw_staged ? at<float>(ws, p.dw32) : (float*)dW_out;

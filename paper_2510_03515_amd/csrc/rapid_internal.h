@@ -29,6 +29,8 @@ enum { CH_M = 0,      // end of the chunk's valid rows (absolute compact row ind
        CH_G0 = 2,     // first generation of the chunk
        CH_G1 = 3,     // one past its last generation
        CH_ROWS = 4,   // valid rows
+       CH_LIVE = 5,   // end of the rows that carry gradient (they come first; see IdleArgs); CH_LIVE, CH_LIVER lie
+       CH_LIVER = 6,  // like CNT_M, CNT_MR: a kernel given tab + CH_LIVE as its counters stops at them
        CH_WORDS = 8 };
 
 constexpr int ROW_TILE = 256;  // compact rows are padded to this
@@ -48,10 +50,21 @@ void launch_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_l
 // out (RAPID_STATUS_TOKEN_BOUND).  Cmax > 1: a group whose members are not adjacent, or whose tokens
 // exceed Rcap, sets RAPID_STATUS_GROUP_LAYOUT; more chunks than Cmax sets RAPID_STATUS_TOKEN_BOUND.
 // gseen [K] is scratch.
+// IdleArgs (idle == NULL: off): generations whose coefficient is zero whatever their log-probs are (all rewards
+// of the group exactly 0, or a coefficient override of 0) are marked in idle [N] and placed behind the others
+// inside their chunk; the chunk's CH_LIVE / CH_LIVER say where the rows that carry gradient end.
+struct IdleArgs {
+    const float* rewards = nullptr;        // [N]
+    const float* coef_override = nullptr;  // [N] or NULL; if given it alone decides
+    int32_t* idle = nullptr;               // out [N]
+    int32_t* len_live = nullptr;           // scratch [N]
+    int32_t* cu_live = nullptr;            // scratch [N + 1]
+    int32_t* live_group = nullptr;         // scratch [K]
+};
 void launch_compaction_chunked(const uint8_t* mask, const int32_t* group_ids, int64_t N, int64_t T, int64_t K,
                                int64_t Rcap, int Cmax, int32_t* seq_len, int32_t* cu_seqlen, int32_t* tab,
                                int32_t* gen_row0, int32_t* gen_chunk, int32_t* gseen, int32_t* row_index,
-                               int32_t* counts, int32_t* dev_status, hipStream_t st);
+                               int32_t* counts, int32_t* dev_status, const IdleArgs& z, hipStream_t st);
 void launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
 // compact rows [row0, row0 + rows_max) (those below counts[CNT_MR])
 void launch_gather_tokens(const int32_t* tokens, const int32_t* row_index, const int32_t* counts, int64_t row0,
@@ -122,8 +135,9 @@ void launch_fill_f64(double* p, int64_t n, double v, hipStream_t st);
 void launch_fill_i32(int32_t* p, int64_t n, int32_t v, hipStream_t st);
 // dst[i] += src[i]
 void launch_f32_add(const float* src, float* dst, int64_t n, hipStream_t st);
+// rows of masked positions, and (idle != NULL) of every position of an idle generation, set to zero
 void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, int64_t d, int elem_bytes,
-                             hipStream_t st);
+                             const int32_t* idle, int64_t T, hipStream_t st);
 void launch_f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t st);
 
 // ---- pack.hip ---------------------------------------------------------------------------------

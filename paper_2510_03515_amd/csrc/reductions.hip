@@ -123,10 +123,48 @@ __global__ void row_index_kernel(const uint8_t* __restrict__ mask, int64_t N, in
     }
 }
 
+// Generations whose coefficient dLoss/dlogp is zero whatever the log-probs turn out to be: every reward of the
+// group is exactly 0 (then the weighted baseline of Eq. (5) is 0 too, A_n = R_n - b = 0, in every baseline mode;
+// likewise the normalised advantage of the clipped surrogate), or the caller's coefficient override is 0.
+// Their rows get no gradient: dHidden rows are zero and they add nothing to dW, so the two gradient
+// contractions can leave them out.  Step 1: live_group[g] = 1 for a group with a reward that is not 0.
+__global__ void live_groups_kernel(const float* __restrict__ rewards, const int32_t* __restrict__ gid, int64_t N,
+                                   int64_t K, int32_t* __restrict__ live_group) {
+    const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    const float R = rewards[n];
+    const int32_t g = gid[n];
+    // a reward that is not finite counts as 0 in the estimator as well; equal values from several threads
+    if (g >= 0 && g < K && isfinite(R) && R != 0.f) live_group[g] = 1;
+}
+// Step 2: idle[n], and the generation's length if it is not idle (for the prefix sum the chunk plan uses).
+// A generation with a group id outside [0, K) is never idle.
+__global__ void idle_generations_kernel(const int32_t* __restrict__ gid, const float* __restrict__ coef_override,
+                                        const int32_t* __restrict__ live_group, const int32_t* __restrict__ seq_len,
+                                        int64_t N, int64_t K, int32_t* __restrict__ idle,
+                                        int32_t* __restrict__ len_live) {
+    const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    bool z;
+    if (coef_override) {
+        z = coef_override[n] == 0.f;
+    } else {
+        const int32_t g = gid[n];
+        z = g >= 0 && g < K && live_group[g] == 0;
+    }
+    idle[n] = z ? 1 : 0;
+    len_live[n] = z ? 0 : seq_len[n];
+}
+
 // Single block: deals the generations to chunks (see launch_compaction_chunked in rapid_internal.h).
 // Thread 0 walks the runs of equal group id in order and fills chunk after chunk; then all threads
 // give every generation its chunk and first compact row and count each run's group id once.
+// With `idle` (see idle_generations_kernel; cu_live = prefix sum of the other generations' lengths) a chunk's
+// rows are ordered: the generations that carry gradient first, in batch order, then the idle ones, so that the
+// two gradient contractions stop at CH_LIVE.
 __global__ __launch_bounds__(1024) void plan_chunks_kernel(const int32_t* __restrict__ cu,
+                                                           const int32_t* __restrict__ cu_live,
+                                                           const int32_t* __restrict__ idle,
                                                            const int32_t* __restrict__ gid, int64_t N, int64_t K,
                                                            int64_t Rcap, int Cmax, int32_t* __restrict__ gseen,
                                                            int32_t* __restrict__ tab, int32_t* __restrict__ gen_row0,
@@ -143,7 +181,11 @@ __global__ __launch_bounds__(1024) void plan_chunks_kernel(const int32_t* __rest
             e[CH_G0] = (int32_t)g0; e[CH_G1] = (int32_t)g1; e[CH_ROWS] = (int32_t)rows;
             e[CH_M] = (int32_t)((int64_t)c * Rcap + rows);
             e[CH_MR] = (int32_t)((int64_t)c * Rcap + (rows + ROW_TILE - 1) / ROW_TILE * ROW_TILE);
-            e[5] = e[6] = e[7] = 0;
+            int64_t live = cu_live ? (int64_t)cu_live[g1] - (int64_t)cu_live[g0] : rows;
+            if (live > rows) live = rows;           // only when the chunk was cut short (its outputs are unusable then)
+            e[CH_LIVE] = (int32_t)((int64_t)c * Rcap + live);
+            e[CH_LIVER] = (int32_t)((int64_t)c * Rcap + (live + ROW_TILE - 1) / ROW_TILE * ROW_TILE);
+            e[7] = 0;
             placed += rows;
             ++c;
         };
@@ -187,7 +229,19 @@ __global__ __launch_bounds__(1024) void plan_chunks_kernel(const int32_t* __rest
         for (int k = 0; k < Cmax; ++k)
             if (n >= tab[k * CH_WORDS + CH_G0] && n < tab[k * CH_WORDS + CH_G1]) { c = k; break; }
         gen_chunk[n] = c;
-        gen_row0[n] = c < 0 ? -1 : (int32_t)((int64_t)c * Rcap + ((int64_t)cu[n] - (int64_t)cu[tab[c * CH_WORDS + CH_G0]]));
+        int64_t row0 = -1;
+        if (c >= 0) {
+            const int64_t g0 = tab[c * CH_WORDS + CH_G0], g1 = tab[c * CH_WORDS + CH_G1];
+            const int64_t before = (int64_t)cu[n] - (int64_t)cu[g0];            // tokens of the chunk's earlier generations
+            if (cu_live) {
+                const int64_t live_before = (int64_t)cu_live[n] - (int64_t)cu_live[g0];
+                const int64_t live_all = (int64_t)cu_live[g1] - (int64_t)cu_live[g0];
+                row0 = (int64_t)c * Rcap + (idle[n] ? live_all + (before - live_before) : live_before);
+            } else {
+                row0 = (int64_t)c * Rcap + before;
+            }
+        }
+        gen_row0[n] = (int32_t)row0;
         if (Cmax > 1 && (n == 0 || gid[n] != gid[n - 1])) {       // first generation of a run
             const int32_t g = gid[n];
             if (g >= 0 && g < K && atomicAdd(&gseen[g], 1) > 0) status |= RAPID_STATUS_GROUP_LAYOUT;
@@ -540,11 +594,13 @@ __global__ void row_coefficients_kernel(const float* __restrict__ g, const doubl
     rowg[j] = v;
 }
 
-// zero the gradient rows of masked positions: one block per position
+// zero the gradient rows of masked positions, and of every position of an idle generation (idle may be
+// NULL): one block per position
 __global__ void zero_masked_rows_kernel(uint32_t* __restrict__ dh, const uint8_t* __restrict__ mask,
-                                        int64_t rows, int64_t words_per_row) {
+                                        int64_t rows, int64_t words_per_row, const int32_t* __restrict__ idle,
+                                        int64_t T) {
     const int64_t r = blockIdx.x;
-    if (r >= rows || mask[r] != 0) return;
+    if (r >= rows || (mask[r] != 0 && !(idle && idle[r / T]))) return;
     uint32_t* p = dh + r * words_per_row;
     for (int64_t i = threadIdx.x; i < words_per_row; i += blockDim.x) p[i] = 0u;
 }
@@ -590,12 +646,21 @@ void launch_compaction(const uint8_t* mask, int64_t N, int64_t T, int32_t* seq_l
 void launch_compaction_chunked(const uint8_t* mask, const int32_t* group_ids, int64_t N, int64_t T, int64_t K,
                                int64_t Rcap, int Cmax, int32_t* seq_len, int32_t* cu_seqlen, int32_t* tab,
                                int32_t* gen_row0, int32_t* gen_chunk, int32_t* gseen, int32_t* row_index,
-                               int32_t* counts, int32_t* dev_status, hipStream_t st) {
+                               int32_t* counts, int32_t* dev_status, const IdleArgs& z, hipStream_t st) {
     seq_len_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, seq_len);
     scan_kernel<<<1, 1024, 0, st>>>(seq_len, N, cu_seqlen, nullptr, INT64_MAX, nullptr);
+    if (z.idle) {
+        if (!z.coef_override) {
+            launch_fill_i32(z.live_group, K, 0, st);
+            live_groups_kernel<<<blocks_for(N, 256), 256, 0, st>>>(z.rewards, group_ids, N, K, z.live_group);
+        }
+        idle_generations_kernel<<<blocks_for(N, 256), 256, 0, st>>>(group_ids, z.coef_override, z.live_group, seq_len, N, K,
+                                                                    z.idle, z.len_live);
+        scan_kernel<<<1, 1024, 0, st>>>(z.len_live, N, z.cu_live, nullptr, INT64_MAX, nullptr);
+    }
     if (Cmax > 1) launch_fill_i32(gseen, K, 0, st);
-    plan_chunks_kernel<<<1, 1024, 0, st>>>(cu_seqlen, group_ids, N, K, Rcap, Cmax, gseen, tab, gen_row0, gen_chunk,
-                                           counts, dev_status);
+    plan_chunks_kernel<<<1, 1024, 0, st>>>(cu_seqlen, z.idle ? z.cu_live : nullptr, z.idle, group_ids, N, K, Rcap, Cmax, gseen,
+                                           tab, gen_row0, gen_chunk, counts, dev_status);
     row_index_kernel<<<(unsigned)N, WAVE, 0, st>>>(mask, N, T, gen_row0, Rcap, row_index);
 }
 
@@ -799,10 +864,10 @@ void launch_rescale_rows(void* dhidden, const uint8_t* mask, int64_t N, int64_t 
 }
 
 void launch_zero_masked_rows(void* dhidden, const uint8_t* mask, int64_t rows, int64_t d, int elem_bytes,
-                             hipStream_t st) {
+                             const int32_t* idle, int64_t T, hipStream_t st) {
     // d * elem_bytes is a multiple of 4 for every accepted shape (bf16 needs d % 8 == 0)
     zero_masked_rows_kernel<<<(unsigned)rows, 128, 0, st>>>((uint32_t*)dhidden, mask, rows,
-                                                            d * elem_bytes / 4);
+                                                            d * elem_bytes / 4, idle, T);
 }
 
 // master -= lr * grad; optionally also the updated weights in the contraction dtype

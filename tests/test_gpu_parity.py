@@ -687,6 +687,84 @@ def test_cached_backward_in_chunks_needs_adjacent_groups_that_fit(rb):
         _check_pair(rb, spec, out, ref)
 
 
+@pytest.mark.parametrize("size", ["minimum", "middle", "whole"])
+def test_generations_without_gradient_are_left_out(rb, size):
+    """A group whose rewards are all 0 has A_n = 0 whatever the ratios are (Eq. (5): the weighted baseline of zeros is
+    0), so its generations get no gradient; the cached backward puts them last inside their chunk and its two
+    gradient contractions stop in front of them.  Every output must be what the oracle, which leaves nothing out,
+    gives: zero groups at the start, in the middle (across chunk boundaries) and at the end of the batch, every
+    group zero, a coefficient override with zeros, and the baselines' step without a KL term; also against the
+    same call with the skipping switched off."""
+    spec = CHUNKY
+    w, g = _make(spec, seed=9)
+    N, T, d = g["hidden"].shape
+    V, K = spec.V, w["K"]
+    least = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16, minimum=True)
+    whole = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16, max_tokens=N * T)
+    nbytes = {"minimum": least, "middle": (least + whole) // 2, "whole": whole}[size]
+    H, W, tok, mask = _oracle_inputs(w)
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+    gid = _np(w["group_ids"]).astype(np.int64)
+    R0 = _np(w["rewards"]).astype(np.float32)
+
+    def run(rewards, **kw):
+        buf = rb.IwPgBuffers(g["hidden"], g["W"], K, workspace_bytes=nbytes)
+        out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, torch.from_numpy(rewards).cuda(),
+                                          g["group_ids"], K, buffers=buf, logits_cache=True, **kw)
+        torch.cuda.synchronize()
+        return out
+
+    for zero_groups in ([0], [2, 3], [K - 1], [0, 1, 3, 4, K - 1], list(range(K))):
+        print(f"zero-reward groups {zero_groups}, window {size}", flush=True)
+        R = R0.copy()
+        R[np.isin(gid, zero_groups)] = 0.0
+        for kw in (dict(), dict(normalized_grads=True, ratio_level=1)):
+            out = run(R, **kw)
+            ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), R, _np(w["group_ids"]), K, **kw)
+            ref["slack"] = pb.coefficient_slack(ref, R, mask)
+            idle_rows = np.isin(gid, zero_groups)
+            assert np.all(ref["dH"][idle_rows] == 0.0) and np.all(_np(out.dhidden)[idle_rows] == 0.0)
+            if len(zero_groups) == K:              # nothing carries gradient: exact zeros everywhere
+                assert out.loss.item() == 0.0 and not _np(out.dW).any() and not _np(out.dhidden).any()
+                assert np.abs(_np(out.logp_cur) - ref["logp_cur"]).max() <= LOGP_ATOL["bf16"]
+                assert out.read_diag()["n_tokens"] == ref["n_tokens"] and out.dev_status.item() == 0
+                continue
+            _check_pair(rb, spec, out, ref)
+            rb.rapid_set_tuning(19, 0)             # the same call with every generation in the contractions
+            try:
+                full = run(R, **kw)
+            finally:
+                rb.rapid_set_tuning(19, 1)
+            assert torch.equal(full.logp_cur, out.logp_cur) and full.loss.item() == out.loss.item()
+            assert _rel(_np(out.dW), _np(full.dW)) <= 2e-3 and _rel(_np(out.dhidden), _np(full.dhidden)) <= 2e-3
+    # a coefficient override with zeros decides by itself (here: two generations of different groups, rewards untouched)
+    coef = np.linspace(-1.0, 1.0, N).astype(np.float32) / N
+    coef[[1, 5, N - 1]] = 0.0
+    out = run(R0, coef_override=torch.from_numpy(coef).cuda())
+    ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), R0, _np(w["group_ids"]), K, coef_override=coef)
+    assert out.dev_status.item() == 0 and abs(out.loss.item() - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    _dh_ok(out.dhidden, ref["dH"])
+    _dw_ok(out.dW, ref["dW"])
+    assert not _np(out.dhidden)[[1, 5, N - 1]].any()
+    # the baselines' step: without a KL term (DAPO) a zero group is idle; with one (GRPO) every token carries gradient
+    R = R0.copy()
+    R[np.isin(gid, [1, 4])] = 0.0
+    ref_w = (g["W"].float() + 0.01 * torch.randn(g["W"].shape, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3))).to(torch.bfloat16)
+    logp_ref, _ = rb.rapid_logprob_fwd(g["hidden"], ref_w, g["tokens"], g["mask"])
+    for variant in ("dapo", "grpo"):
+        buf = rb.IwPgBuffers(g["hidden"], g["W"], K, workspace_bytes=nbytes)
+        out = rb.rapid_clip_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, logp_ref, torch.from_numpy(R).cuda(),
+                                            g["group_ids"], K, variant=variant, buffers=buf, logits_cache=True)
+        torch.cuda.synchronize()
+        co = rb.clip_pg_default_opts(variant)
+        o = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(logp_ref), R, _np(w["group_ids"]), K,
+                                        eps_low=co.eps_low, eps_high=co.eps_high, kl_beta=co.kl_beta, norm_mode=co.norm_mode)
+        assert out.dev_status.item() == 0 and abs(out.loss.item() - o["loss"]) <= LOSS_RTOL * abs(o["loss"]), variant
+        assert _rel(_np(out.dW), o["dW"]) <= GRAD_RTOL["bf16"] and _rel(_np(out.dhidden), o["dH"]) <= GRAD_RTOL["bf16"], variant
+        if variant == "dapo":
+            assert not _np(out.dhidden)[np.isin(gid, [1, 4])].any()
+
+
 def test_inner_loop_on_synthetic_bandit(rb):
     """Alg. 1's inner loop, H mini-batches of one inference batch: the first step is exactly on-policy,
     staleness grows with the step index, the estimated reward of the policy improves, and a call at
