@@ -10,7 +10,7 @@ of 90112 token rows, 32 GiB in all at this shape): the batch is worked through i
 groups, the forward of a chunk keeps its rows' scaled probabilities in the cache and the chunk's
 dHidden and dW contract them, so 6 d V flop per token are executed and nothing of size tokens x V
 outlives a chunk.  Generations of a group whose rewards are all 0 have advantage 0 by Eq. (5) and so
-no gradient; the cached backward leaves them out of dHidden and dW (exactly), and the flop counts
+no gradient; the backward leaves them out of its contractions (exactly), and the flop counts
 here leave them out as well (`response_tokens_with_gradient`).  Beside it, never as `value`: the same call with a cache that holds the whole batch
 at once ("whole", 94 GiB), with the backward that regenerates the logits ("recompute", 8 d V flop
 per token), and on the workload's calibrated companion (dense gradients: every generation carries
@@ -241,7 +241,7 @@ def main():
     tok_s = M * args.steps / dt
     # Algorithmic work of one call: 2 d V flop per response token for the logits, and 2 d V each for dHidden and dW
     # per token that carries gradient.  A generation whose whole group has reward 0 has advantage 0 (Eq. (5)) and
-    # gradient 0 whatever its ratio is; the cached backward leaves such generations out of the two contractions
+    # gradient 0 whatever its ratio is; the backward leaves such generations out of its contractions
     # (exactly: their rows are zeros), so they are not counted as work either.
     with_gradient = None if fwd_only else generations_with_gradient(w)
     M_grad = 0 if fwd_only else int(w["lengths"].cpu().numpy()[with_gradient].sum())
@@ -267,14 +267,14 @@ def main():
         chunk_tokens = [r for r, _ in chunks]
         chunk_tokens_grad = [g for _, g in chunks]
     else:
-        Mb = M_grad if mode == "whole" else M     # the cached backward leaves the rows without gradient out
-        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-M // FWD_BLOCK_ROWS), "dh": -(-Mb // BWD_BLOCK_ROWS), "dw": -(-Mb // BWD_BLOCK_ROWS)}
+        Mb = M_grad if spec.dtype == "bf16" else M     # the backward leaves the rows without gradient out
+        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-Mb // FWD_BLOCK_ROWS), "dh": -(-Mb // BWD_BLOCK_ROWS), "dw": -(-Mb // BWD_BLOCK_ROWS)}
     gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and (s != "dz" or mode == "recompute")]
     if gemm_stages:
         per_stage = {}
         for st_name in gemm_stages:
             ms = stages[st_name]["ms_per_step"]
-            rate = 2.0 * d * V * (M_grad if st_name in ("dh", "dw") and mode != "recompute" else M) / (ms * 1e-3) / 1e12
+            rate = 2.0 * d * V * (M if st_name == "fwd_lse" else M_grad) / (ms * 1e-3) / 1e12
             per_stage[st_name] = {"achieved": rate, "frac": rate * 1e12 / PEAK_BF16_MFMA, "frac_of_probe": rate / tf_rnd,
                                   "ms_per_step": ms, "live_launches_per_step": live.get(st_name),
                                   "avg_live_launch_ms": ms / live[st_name] if live.get(st_name) else None}

@@ -260,6 +260,11 @@ int rapid_seq_logratio(const float* logp_cur, const float* logp_behav, const uin
  * policy gradient of Sec. 3.3 (Eq. (1) with the advantages of Eq. (2)).
  * Optional outputs (NULL to skip): logp_cur_out, tok_logratio_out [N,T]; seq_logratio_out,
  * adv_out [N]; diag_out.  loss_out [1], dhidden_out [N,T,d] and dW_out are required.
+ * Generations without gradient (bf16 inputs): if every reward of a group is exactly 0, Eq. (5) gives its members
+ * A_n = 0 whatever their ratios are (the weighted baseline of zeros is 0; likewise both leave-one-out forms), so their
+ * rows of dhidden are zero and they add nothing to dW.  The call decides this from the rewards (or from zeros in
+ * coef_override) before the forward, orders such generations behind the others and ends the backward's contractions
+ * in front of them; their log-probs, ratios and diagnostics are computed as for any other generation.
  */
 int rapid_iw_pg_loss_fwd_bwd(const void* hidden, const void* W, const int32_t* tokens,
                              const uint8_t* mask, const float* logp_behav, const float* rewards,

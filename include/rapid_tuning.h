@@ -44,7 +44,10 @@ extern "C" {
  *        The sums are taken in another order: results differ by fp32 rounding of the accumulators.
  * key 18: cache rows (a multiple of 256, default 90112) of the size rapid_workspace_bytes recommends for
  *        RAPID_OP_IW_PG_FWD_BWD_CACHED.  A call uses whatever its workspace affords; this only moves the
- *        recommendation. */
+ *        recommendation.
+ * key 19: 1 (default) / 0: generations without gradient (a group whose rewards are all 0, a zero coefficient
+ *        override) are ordered behind the others and left out of the backward's contractions; 0 keeps them in,
+ *        for measuring what that saves.  Same results up to the order of the sums. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

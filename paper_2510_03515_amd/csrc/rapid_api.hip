@@ -170,8 +170,8 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
         if (dtype == RAPID_DTYPE_BF16) p.rms_part = take(cur, (size_t)p.rms_blocks * d * 4);
         p.rowg = take(cur, (size_t)p.Mmax_pad * 4);
         p.adv64 = take(cur, (size_t)N * 8);
-        if (Cmax > 0) {
-            p.tab = take(cur, (size_t)Cmax * CH_WORDS * 4);
+        if (dtype == RAPID_DTYPE_BF16) {   // the chunk plan; without the cache the whole batch is its one chunk
+            p.tab = take(cur, (size_t)(Cmax > 0 ? Cmax : 1) * CH_WORDS * 4);
             p.gen_row0 = take(cur, (size_t)N * 4);
             p.gen_chunk = take(cur, (size_t)N * 4);
             p.gseen = take(cur, (size_t)K * 4);
@@ -179,6 +179,8 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
             p.len_live = take(cur, (size_t)N * 4);
             p.cu_live = take(cur, (size_t)(N + 1) * 4);
             p.live_group = take(cur, (size_t)K * 4);
+        }
+        if (Cmax > 0) {
             p.lam_state = take(cur, 2 * 8);
             p.lam_chunk = take(cur, (size_t)Cmax * 8);
             p.beta_scale = take(cur, 64);
@@ -327,6 +329,10 @@ struct FwdIo {
     const float* ref_logp = nullptr;    // with zc: the behaviour log-probs, for the reference of the stored values
     const void* rms_weight = nullptr;   // if set (bf16 only): hidden is normalised while it is packed
     float rms_eps = 0.f;
+    // if idle.idle is set (backward call, bf16): the rows of the generations it marks come behind the others and
+    // the chunk table's one entry says where those end
+    IdleArgs idle;
+    const int32_t* group_ids = nullptr;
 };
 
 // packs W as [Vpad, ldk] (the operand of the logits kernels)
@@ -403,8 +409,14 @@ void run_forward(const Plan& p, void* ws, const FwdIo& io, hipStream_t st) {
     const float inv_temp = 1.0f / io.temperature;
     {
         Span sp(ST_COMPACT, st);
-        launch_compaction(io.mask, p.N, p.T, at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), row_index, counts,
-                          io.row_cap, io.dev_status, st);
+        if (io.idle.idle)
+            launch_compaction_chunked(io.mask, io.group_ids, p.N, p.T, p.K, io.row_cap < p.Mmax_pad ? io.row_cap : p.Mmax_pad, 1,
+                                      at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), at<int32_t>(ws, p.tab),
+                                      at<int32_t>(ws, p.gen_row0), at<int32_t>(ws, p.gen_chunk), at<int32_t>(ws, p.gseen),
+                                      row_index, counts, io.dev_status, io.idle, st);
+        else
+            launch_compaction(io.mask, p.N, p.T, at<int32_t>(ws, p.seq_len), at<int32_t>(ws, p.cu), row_index, counts,
+                              io.row_cap, io.dev_status, st);
         launch_fill_f32(io.logp_out, p.Mmax, 0.f, st);
         if (io.lse_out) launch_fill_f32(io.lse_out, p.Mmax, 0.f, st);
     }
@@ -1081,7 +1093,17 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
         return check_launch(name);
     }
 
-    // ---- the backward that regenerates the logits (and the fp32 path): forward over the whole batch first
+    // ---- the backward that regenerates the logits (and the fp32 path): forward over the whole batch first.
+    // bf16: the generations without gradient (see the cached backward above) come last, and dz, dHidden and dW
+    // stop in front of them
+    const int32_t* bwd_counts = counts;
+    if (dtype == RAPID_DTYPE_BF16 && g_skip_idle.load() && !(clip && clip->o.kl_beta != 0.f)) {
+        io.idle.rewards = rewards; io.idle.coef_override = clip ? nullptr : o.coef_override;
+        io.idle.idle = at<int32_t>(ws, p.idle); io.idle.len_live = at<int32_t>(ws, p.len_live);
+        io.idle.cu_live = at<int32_t>(ws, p.cu_live); io.idle.live_group = at<int32_t>(ws, p.live_group);
+        io.group_ids = group_ids;
+        bwd_counts = at<int32_t>(ws, p.tab) + CH_LIVE;
+    }
     run_forward(p, ws, io, st);
 
     // generation-level log ratios, clipped-weight group baseline, coefficients and loss
@@ -1106,7 +1128,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
     // backward, in row chunks
     {
         Span sp(ST_ZERO, st);
-        launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, nullptr, T, st);
+        launch_zero_masked_rows(dhidden_out, mask, p.Mmax, d, elem, io.idle.idle, T, st);
     }
     const bool dw_staged = o.dw_dtype == RAPID_DTYPE_BF16;
     float* dW32 = dw_staged ? at<float>(ws, p.dw32) : (float*)dW_out;
@@ -1136,7 +1158,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
             za.Wvd = Wvd; za.Hc = Hc + m0 * p.ldk; za.dpad = p.dpad; za.ldk = p.ldk; za.ldz = p.ldv;
             za.tilesV = (int)(p.Vpad / 256); za.tilesM = (int)(rows / 256);
             za.V = p.V; za.Vpad = p.Vpad; za.inv_temp = inv_temp; za.m0 = m0;
-            za.tokc = tokc; za.lse_c = lse_c; za.rowg = rowg; za.counts = counts; za.dz = dz; za.gi = g_gi_fwd;
+            za.tokc = tokc; za.lse_c = lse_c; za.rowg = rowg; za.counts = bwd_counts; za.dz = dz; za.gi = g_gi_fwd;
             {
                 // like the forward, in sub-blocks of rows whose hidden rows stay in the memory-side cache
                 const int64_t sub = (int64_t)g_fwd_block_tiles.load() * 256;
@@ -1151,7 +1173,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
             }
             DhArgs ha;
             ha.Wdv = Wdv; ha.WdvB = blocked_wdv ? at<bf16_t>(ws, p.WdvB) : nullptr; ha.dz = dz; ha.Vpad = p.Vpad; ha.ldv = p.ldv; ha.d = p.d; ha.dpadR = p.dpadR;
-            ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = counts;
+            ha.tilesM = (int)(rows / 256); ha.m0 = m0; ha.row_index = row_index; ha.counts = bwd_counts;
             ha.rowc = nullptr;
             const int pace_every = g_pace_every.load();
             ha.pace = pace_every > 0 ? at<unsigned>(ws, p.pace) : nullptr; ha.pace_every = pace_every;
@@ -1164,7 +1186,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
             }
             DwArgs wa;
             wa.dz = dz; wa.Hc = Hc + m0 * p.ldk; wa.Mc = step; wa.ldz = p.ldv; wa.ldH = p.ldk;
-            wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = m0; wa.counts = counts;
+            wa.d = p.d; wa.dpadR = p.dpadR; wa.V = p.V; wa.Vpad = p.Vpad; wa.m0 = m0; wa.counts = bwd_counts;
             wa.dW = dW32; wa.w_layout = o.w_layout; wa.beta = (chunk > 0 || o.accumulate_dw) ? 1 : 0; wa.gi = g_gi_dw;
             {
                 Span sp(ST_DW, st);

@@ -687,21 +687,23 @@ def test_cached_backward_in_chunks_needs_adjacent_groups_that_fit(rb):
         _check_pair(rb, spec, out, ref)
 
 
-@pytest.mark.parametrize("size", ["minimum", "middle", "whole"])
+@pytest.mark.parametrize("size", ["minimum", "middle", "whole", "recompute"])
 def test_generations_without_gradient_are_left_out(rb, size):
     """A group whose rewards are all 0 has A_n = 0 whatever the ratios are (Eq. (5): the weighted baseline of zeros is
     0), so its generations get no gradient; the cached backward puts them last inside their chunk and its two
     gradient contractions stop in front of them.  Every output must be what the oracle, which leaves nothing out,
     gives: zero groups at the start, in the middle (across chunk boundaries) and at the end of the batch, every
     group zero, a coefficient override with zeros, and the baselines' step without a KL term; also against the
-    same call with the skipping switched off."""
+    same call with the skipping switched off.  "recompute": the backward that regenerates the logits does the
+    same with the batch as its one chunk."""
     spec = CHUNKY
     w, g = _make(spec, seed=9)
     N, T, d = g["hidden"].shape
     V, K = spec.V, w["K"]
     least = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16, minimum=True)
     whole = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, V, K, rb.DTYPE_BF16, max_tokens=N * T)
-    nbytes = {"minimum": least, "middle": (least + whole) // 2, "whole": whole}[size]
+    cache = size != "recompute"
+    nbytes = {"minimum": least, "middle": (least + whole) // 2, "whole": whole, "recompute": None}[size]
     H, W, tok, mask = _oracle_inputs(w)
     logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
     gid = _np(w["group_ids"]).astype(np.int64)
@@ -710,7 +712,7 @@ def test_generations_without_gradient_are_left_out(rb, size):
     def run(rewards, **kw):
         buf = rb.IwPgBuffers(g["hidden"], g["W"], K, workspace_bytes=nbytes)
         out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, torch.from_numpy(rewards).cuda(),
-                                          g["group_ids"], K, buffers=buf, logits_cache=True, **kw)
+                                          g["group_ids"], K, buffers=buf, logits_cache=cache, **kw)
         torch.cuda.synchronize()
         return out
 
@@ -754,7 +756,7 @@ def test_generations_without_gradient_are_left_out(rb, size):
     for variant in ("dapo", "grpo"):
         buf = rb.IwPgBuffers(g["hidden"], g["W"], K, workspace_bytes=nbytes)
         out = rb.rapid_clip_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, logp_ref, torch.from_numpy(R).cuda(),
-                                            g["group_ids"], K, variant=variant, buffers=buf, logits_cache=True)
+                                            g["group_ids"], K, variant=variant, buffers=buf, logits_cache=cache)
         torch.cuda.synchronize()
         co = rb.clip_pg_default_opts(variant)
         o = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(logp_ref), R, _np(w["group_ids"]), K,
