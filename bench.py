@@ -239,13 +239,15 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     tok_s = M * args.steps / dt
-    # Algorithmic work of one call: 2 d V flop per response token for the logits, and 2 d V each for dHidden and dW
+    # Work one call needs: 2 d V flop per response token for the logits, and 2 d V each for dHidden and dW
     # per token that carries gradient.  A generation whose whole group has reward 0 has advantage 0 (Eq. (5)) and
     # gradient 0 whatever its ratio is; the backward leaves such generations out of its contractions
     # (exactly: their rows are zeros), so they are not counted as work either.
     with_gradient = None if fwd_only else generations_with_gradient(w)
     M_grad = 0 if fwd_only else int(w["lengths"].cpu().numpy()[with_gradient].sum())
-    flops_per_call = 2.0 * d * V * M + 4.0 * d * V * M_grad
+    flops_needed = 2.0 * d * V * M + 4.0 * d * V * M_grad
+    # the scope table's count: 6 d V per response token (2 d V for the forward-only workload), whatever its reward
+    flops_per_call = (2.0 if fwd_only else 6.0) * d * V * M
     executed = {"forward only": 2.0, "chunks": 6.0, "whole": 6.0, "recompute": 8.0}[mode] * d * V
 
     # the MFMA pipe on its own (no memory traffic), outside the timed region: what the published
@@ -263,12 +265,14 @@ def main():
         cache_rows = rb.rapid_logits_cache_rows(N, T, d, V, w["K"], M, int(round(ws_gib * 2**30)))
         chunks = chunk_rows_of(lengths, spec.G, cache_rows, with_gradient.tolist())
         live = {"fwd_lse": sum(-(-r // FWD_BLOCK_ROWS) for r, _ in chunks)}
-        live["dh"] = live["dw"] = sum(-(-g // BWD_BLOCK_ROWS) for _, g in chunks)
+        live["dh"] = sum(-(-g // BWD_BLOCK_ROWS) for _, g in chunks)
+        live["dw"] = sum(1 for _, g in chunks if g)          # one dW launch per chunk
         chunk_tokens = [r for r, _ in chunks]
         chunk_tokens_grad = [g for _, g in chunks]
     else:
         Mb = M_grad if spec.dtype == "bf16" else M     # the backward leaves the rows without gradient out
-        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-Mb // FWD_BLOCK_ROWS), "dh": -(-Mb // BWD_BLOCK_ROWS), "dw": -(-Mb // BWD_BLOCK_ROWS)}
+        live = {"fwd_lse": -(-M // FWD_BLOCK_ROWS), "dz": -(-Mb // FWD_BLOCK_ROWS), "dh": -(-Mb // BWD_BLOCK_ROWS),
+                "dw": 1 if mode == "whole" else -(-Mb // BWD_BLOCK_ROWS)}
     gemm_stages = [s for s in ("fwd_lse", "dz", "dh", "dw") if s in stages and (s != "dz" or mode == "recompute")]
     if gemm_stages:
         per_stage = {}
@@ -309,6 +313,7 @@ def main():
                    "tokens_with_gradient_per_chunk": chunk_tokens_grad},
         "frac_bf16_mfma_peak_algorithmic": flops_per_call / (dt / args.steps) / PEAK_BF16_MFMA,
         "frac_of_mfma_probe_algorithmic": flops_per_call / (dt / args.steps) / (tf_rnd * 1e12),
+        "frac_bf16_mfma_peak_needed_work": flops_needed / (dt / args.steps) / PEAK_BF16_MFMA,
         "roofline": roofline,
         "stages": stages,
         "mfma_probe": {"unit": "TFLOP/s", "small_integer_operands": tf_int, "random_bf16_operands": tf_rnd,

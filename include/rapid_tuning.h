@@ -1,7 +1,7 @@
 /*
  * rapid_tuning.h -- benchmark and tuning hooks of librapid_hip.so.  NOT part of the product ABI in
  * rapid.h: nothing here is needed to compute anything, the results of every call in rapid.h are the
- * same whatever is set here (up to the fp32 rounding noted at key 15), and two of the calls below
+ * same whatever is set here (up to the fp32 rounding noted at keys 17 and 20), and two of the calls below
  * wait for the device, which no call in rapid.h ever does.  bench.py and the tests of the kernels'
  * launch geometries use them.
  */
@@ -29,10 +29,9 @@ extern "C" {
  * key 14: 1 (default) / 0: the dHidden kernel reads W from a tile-blocked copy (one contiguous
  *        32 KiB block per 256-row tile and 64-column step) / from the row-major copy.  Results
  *        are identical.
- * key 15: with logits_cache = 1, token-row tiles (of 256 rows) per launch of the dHidden and dW
- *        kernels, default 256 (0 = all rows in one launch; multiples of 128 fill whole rounds of
- *        workgroups).  dW sums over the launches in a fixed order, so results depend on it only
- *        through fp32 rounding.
+ * key 15: with logits_cache = 1, token-row tiles (of 256 rows) per launch of the dHidden kernel,
+ *        default 256 (0 = all rows of the chunk in one launch; multiples of 128 fill whole rounds of
+ *        workgroups).  Results depend on it only through which tiles key 17 cuts.
  * key 16: K steps (of 64 vocabulary entries; a power of two; default 0 = off) between meetings
  *        of the dHidden kernel's workgroups: they count themselves in on a workspace word and wait,
  *        for a bounded time, for the others, so that all XCDs sweep W together and share it through
@@ -47,7 +46,10 @@ extern "C" {
  *        recommendation.
  * key 19: 1 (default) / 0: generations without gradient (a group whose rewards are all 0, a zero coefficient
  *        override) are ordered behind the others and left out of the backward's contractions; 0 keeps them in,
- *        for measuring what that saves.  Same results up to the order of the sums. */
+ *        for measuring what that saves.  Same results up to the order of the sums.
+ * key 20: row tiles (of 256 rows) per dW launch of the cached backward; 0 (default) = all rows of the chunk in one
+ *        launch.  dW sums over its launches in a fixed order, so results depend on the key only through fp32
+ *        rounding. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of
