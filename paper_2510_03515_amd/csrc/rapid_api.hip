@@ -117,7 +117,7 @@ struct Plan {
     size_t fixed, total;
     // offsets into the workspace
     size_t counts, pace, seq_len, cu, row_index, tokc, seqc, zy, refz, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, adv64, g, g64, tsum, tmax,
-        Hc, Wvd, Wdv, WdvB, dh_part, part_max, part_sum, dw32, chunk0, tab, gen_row0, gen_chunk, gseen, lam_state, lam_chunk, beta_scale, idle, len_live, cu_live, live_group;
+        Hc, Wvd, Wdv, WdvB, dh_part, part_max, part_sum, dw32, chunk0, tab, gen_row0, gen_chunk, gseen, lam_state, lam_chunk, beta_scale, idle, len_live, cu_live, live_group, gruns;
 };
 
 size_t take(size_t& cur, size_t bytes) {
@@ -171,6 +171,7 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
         if (dtype == RAPID_DTYPE_BF16) p.rms_part = take(cur, (size_t)p.rms_blocks * d * 4);
         p.rowg = take(cur, (size_t)p.Mmax_pad * 4);
         p.adv64 = take(cur, (size_t)N * 8);
+        p.gruns = take(cur, (size_t)(3 * K + 1) * 4);
         if (dtype == RAPID_DTYPE_BF16) {   // the chunk plan; without the cache the whole batch is its one chunk
             p.tab = take(cur, (size_t)(Cmax > 0 ? Cmax : 1) * CH_WORDS * 4);
             p.gen_row0 = take(cur, (size_t)N * 4);
@@ -945,6 +946,10 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
         cl.loss_scale = clip->o.loss_scale; cl.norm_mode = clip->o.norm_mode;
     }
 
+    // where each group lies in the batch: groups that are one run are reduced over that run alone
+    int32_t* gruns = at<int32_t>(ws, p.gruns);
+    launch_group_runs(group_ids, N, K, gruns, st);
+
     FwdIo io{hidden, W, tokens, mask, o.w_layout, o.temperature, logp_cur, nullptr, dev_status};
     io.rms_weight = o.rms_weight;
     io.rms_eps = o.rms_eps;
@@ -1011,7 +1016,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
             if (clip) {
                 Span sp(ST_ESTIMATOR, st);
                 launch_group_advantage(rewards, group_ids, nullptr, nullptr, N, K, 2.f, BASELINE_NORMALIZED, adv, adv64, nullptr,
-                                       nullptr, nullptr, nullptr, gen_range, dev_status, st, clip->o.adv_eps, clip->o.std_ddof);
+                                       nullptr, nullptr, nullptr, gen_range, dev_status, st, clip->o.adv_eps, clip->o.std_ddof, gruns);
                 launch_clip_generations(cl, gen_range, at<double>(ws, p.g64), at<double>(ws, p.tsum), at<double>(ws, p.tmax),
                                         dev_status, st);
                 launch_clip_rows(cl, seqc, row_index, cnt, base, p.Rcap, rowg, st);
@@ -1020,7 +1025,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
                 launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, o.eta, o.coef_mode == 1,
                                     tsum, tmax, gen_range, dev_status, st);
                 launch_group_advantage(rewards, group_ids, nullptr, logp_behav ? s64 : nullptr, N, K, o.eta, o.baseline_mode,
-                                       adv, adv64, nullptr, nullptr, nullptr, nullptr, gen_range, dev_status, st);
+                                       adv, adv64, nullptr, nullptr, nullptr, nullptr, gen_range, dev_status, st, 0.f, 0, gruns);
                 CoefArgs cc = ca;
                 cc.gen_range = gen_range; cc.lam_state = lam_state; cc.lam_chunk = lam_chunk + c; cc.beta_out = beta_scale;
                 launch_coefficients(cc, st);
@@ -1117,7 +1122,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
     if (clip) {
         Span sp(ST_ESTIMATOR, st);
         launch_group_advantage(rewards, group_ids, nullptr, nullptr, N, K, 2.f, BASELINE_NORMALIZED, adv, adv64, nullptr, nullptr,
-                               nullptr, nullptr, nullptr, dev_status, st, clip->o.adv_eps, clip->o.std_ddof);
+                               nullptr, nullptr, nullptr, dev_status, st, clip->o.adv_eps, clip->o.std_ddof, gruns);
         launch_clip_generations(cl, nullptr, at<double>(ws, p.g64), at<double>(ws, p.tsum), at<double>(ws, p.tmax), dev_status, st);
         launch_clip_finish(at<double>(ws, p.g64), at<double>(ws, p.tsum), at<double>(ws, p.tmax), N, counts, loss_out, clip->diag, st);
         launch_clip_rows(cl, seqc, row_index, counts, 0, p.Mmax_pad, rowg, st);
@@ -1126,7 +1131,7 @@ static int fused_call(const char* name, const void* hidden, const void* W, const
         launch_seq_logratio(logp_cur, logp_behav, mask, N, T, tok_logratio_out, s64, s32, o.eta, o.coef_mode == 1,
                             tsum, tmax, nullptr, dev_status, st);
         launch_group_advantage(rewards, group_ids, nullptr, logp_behav ? s64 : nullptr, N, K, o.eta, o.baseline_mode, adv,
-                               adv64, nullptr, nullptr, nullptr, nullptr, nullptr, dev_status, st);
+                               adv64, nullptr, nullptr, nullptr, nullptr, nullptr, dev_status, st, 0.f, 0, gruns);
         launch_coefficients(ca, st);
         launch_row_coefficients(g, ca.g64, seqc, row_index, counts, logp_cur, logp_behav, per_token, o.eta,
                                 o.coef_mode == 1, 0, p.Mmax_pad, rowg, st);

@@ -88,7 +88,11 @@ constexpr int BASELINE_NORMALIZED = 3;
 void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, const double* s64,
                             int64_t N, int64_t K, float eta, int baseline_mode, float* adv, double* adv64,
                             float* weight, float* gmean, float* gstd, int32_t* gsize, const int32_t* gen_range,
-                            int32_t* dev_status, hipStream_t st, float adv_eps = 0.f, int std_ddof = 0);
+                            int32_t* dev_status, hipStream_t st, float adv_eps = 0.f, int std_ddof = 0,
+                            const int32_t* runs = nullptr);
+// runs [3K + 1] (see group_runs_kernel): where each group lies in the batch; given to launch_group_advantage it
+// lets a group that is one run of the batch look at that run alone
+void launch_group_runs(const int32_t* group_ids, int64_t N, int64_t K, int32_t* runs, hipStream_t st);
 
 // Token-level clipped surrogate with KL penalty (the loss step of the GRPO / DAPO baselines).
 struct ClipArgs {

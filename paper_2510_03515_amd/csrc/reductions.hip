@@ -66,23 +66,34 @@ __global__ void seq_len_kernel(const uint8_t* __restrict__ mask, int64_t N, int6
 // out of everything downstream and RAPID_STATUS_TOKEN_BOUND is set.
 __global__ void scan_kernel(const int32_t* __restrict__ seq_len, int64_t N, int32_t* __restrict__ cu,
                             int32_t* __restrict__ counts, int64_t row_cap, int32_t* __restrict__ dev_status) {
+    constexpr int PER = 8;   // consecutive entries per thread: 8192 per sweep of the block
     __shared__ int sm[1024];
     __shared__ int carry;
     if (threadIdx.x == 0) carry = 0;
     __syncthreads();
-    for (int64_t base = 0; base < N; base += 1024) {
-        const int64_t n = base + threadIdx.x;
-        const int v = n < N ? seq_len[n] : 0;
-        sm[threadIdx.x] = v;
+    for (int64_t base = 0; base < N; base += 1024 * PER) {
+        const int64_t n0 = base + (int64_t)threadIdx.x * PER;
+        int v[PER], mine = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            v[u] = n0 + u < N ? seq_len[n0 + u] : 0;
+            mine += v[u];
+        }
+        sm[threadIdx.x] = mine;
         __syncthreads();
-        for (int o = 1; o < 1024; o <<= 1) {   // Hillis-Steele inclusive scan
+        for (int o = 1; o < 1024; o <<= 1) {   // Hillis-Steele inclusive scan of the threads' sums
             int add = threadIdx.x >= o ? sm[threadIdx.x - o] : 0;
             __syncthreads();
             sm[threadIdx.x] += add;
             __syncthreads();
         }
         const int incl = sm[threadIdx.x];
-        if (n < N && cu) cu[n] = carry + incl - v;
+        int run = carry + incl - mine;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            if (n0 + u < N && cu) cu[n0 + u] = run;
+            run += v[u];
+        }
         __syncthreads();
         if (threadIdx.x == 1023) carry += incl;
         __syncthreads();
@@ -409,6 +420,22 @@ __global__ void group_init_kernel(const float* __restrict__ rewards, const int32
     if (weight) weight[n] = (float)clipped_weight(s32, s64, n, log_eta);
 }
 
+// Where each group lies in the batch: runs[k] = number of maximal runs of group id k, runs[K + k] / runs[2K + k] =
+// begin / end of (the last of) them, runs[3K] = 1 if some group has more than one run.  With one run per group,
+// which is how a sampler that draws G generations per prompt lays a batch out, the per-group pass below visits
+// each generation once instead of once per group.  runs [3K + 1] must be zero on entry.
+__global__ void group_runs_kernel(const int32_t* __restrict__ gid, int64_t N, int64_t K, int32_t* __restrict__ runs) {
+    const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    const int32_t g = gid[n];
+    if (g < 0 || g >= K) return;
+    if (n == 0 || gid[n - 1] != g) {
+        if (atomicAdd(&runs[g], 1) > 0) runs[3 * K] = 1;
+        runs[K + g] = (int32_t)n;
+    }
+    if (n == N - 1 || gid[n + 1] != g) runs[2 * K + g] = (int32_t)(n + 1);
+}
+
 // one block per group: size, mean/std of R, clipped-weight baseline, advantages of its members.
 // With gen_range only the generations in the range are looked at (the caller guarantees that a group
 // lies inside or outside the range as a whole); a group without a member there writes nothing.
@@ -417,10 +444,16 @@ __global__ void group_advantage_kernel(const float* __restrict__ rewards, const 
                                        double log_eta, int baseline_mode, float* __restrict__ adv,
                                        double* __restrict__ adv64, float* __restrict__ gmean,
                                        float* __restrict__ gstd, int32_t* __restrict__ gsize,
-                                       const int32_t* __restrict__ gen_range, double adv_eps, int std_ddof) {
+                                       const int32_t* __restrict__ gen_range, double adv_eps, int std_ddof,
+                                       const int32_t* __restrict__ runs, int64_t K) {
     __shared__ double sm[16];
     const int k = blockIdx.x;
-    const int64_t n_begin = gen_range ? gen_range[0] : 0, n_end = gen_range ? gen_range[1] : N;
+    int64_t n_begin = gen_range ? gen_range[0] : 0, n_end = gen_range ? gen_range[1] : N;
+    if (runs && runs[3 * K] == 0) {   // every group is one run of the batch: look at that run only
+        const int64_t r0 = runs[k] ? runs[K + k] : 0, r1 = runs[k] ? runs[2 * K + k] : 0;
+        n_begin = n_begin > r0 ? n_begin : r0;
+        n_end = n_end < r1 ? n_end : r1;
+    }
     double cnt = 0.0, sum_r = 0.0, sum_wr = 0.0;
     for (int64_t n = n_begin + threadIdx.x; n < n_end; n += blockDim.x) {
         if (group_ids[n] == k) {
@@ -704,12 +737,18 @@ void launch_seq_logratio(const float* logp_cur, const float* logp_behav, const u
 void launch_group_advantage(const float* rewards, const int32_t* group_ids, const float* s32, const double* s64,
                             int64_t N, int64_t K, float eta, int baseline_mode, float* adv, double* adv64,
                             float* weight, float* gmean, float* gstd, int32_t* gsize, const int32_t* gen_range,
-                            int32_t* dev_status, hipStream_t st, float adv_eps, int std_ddof) {
+                            int32_t* dev_status, hipStream_t st, float adv_eps, int std_ddof, const int32_t* runs) {
     const double log_eta = (eta > 0.f && std::isfinite(eta)) ? log((double)eta) : (double)INFINITY;
     group_init_kernel<<<blocks_for(N, 256), 256, 0, st>>>(rewards, group_ids, s32, s64, N, K, log_eta, adv, adv64,
                                                           weight, gen_range, dev_status);
     group_advantage_kernel<<<(unsigned)K, 256, 0, st>>>(rewards, group_ids, s32, s64, N, log_eta, baseline_mode, adv,
-                                                        adv64, gmean, gstd, gsize, gen_range, (double)adv_eps, std_ddof);
+                                                        adv64, gmean, gstd, gsize, gen_range, (double)adv_eps, std_ddof,
+                                                        runs, K);
+}
+
+void launch_group_runs(const int32_t* group_ids, int64_t N, int64_t K, int32_t* runs, hipStream_t st) {
+    launch_fill_i32(runs, 3 * K + 1, 0, st);
+    group_runs_kernel<<<blocks_for(N, 256), 256, 0, st>>>(group_ids, N, K, runs);
 }
 
 // ---- the token-level clipped surrogate of the GRPO / DAPO loss steps ---------------------------

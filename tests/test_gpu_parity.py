@@ -68,7 +68,7 @@ def _oracle_inputs(w):
 
 
 # ----------------------------------------------------------------------------- integer work
-@pytest.mark.parametrize("N,T,p", [(1, 1, 1.0), (5, 9, 0.6), (37, 200, 0.5), (3, 1500, 0.9), (64, 64, 0.0)])
+@pytest.mark.parametrize("N,T,p", [(1, 1, 1.0), (5, 9, 0.6), (37, 200, 0.5), (3, 1500, 0.9), (64, 64, 0.0), (20011, 3, 0.6)])
 def test_compaction_bit_exact(rb, N, T, p):
     print(f"compaction N={N} T={T} p={p}", flush=True)
     rng = np.random.default_rng(N * 1000 + T)
@@ -765,6 +765,28 @@ def test_generations_without_gradient_are_left_out(rb, size):
         assert _rel(_np(out.dW), o["dW"]) <= GRAD_RTOL["bf16"] and _rel(_np(out.dhidden), o["dH"]) <= GRAD_RTOL["bf16"], variant
         if variant == "dapo":
             assert not _np(out.dhidden)[np.isin(gid, [1, 4])].any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_many_short_generations(rb, dtype):
+    """Nine thousand generations in three thousand groups: the prefix sum over the generations takes more than one
+    sweep of its block, and the per-group reductions go over each group's run of the batch (groups adjacent) or,
+    with the group ids shuffled, over the whole batch; every output against the oracle, in both backward modes."""
+    spec = wl.small_spec("many", dtype, d=16, V=40, prompts=3000, G=3, len_lo=1, len_hi=3, sigma=0.05, reward="uniform")
+    w, g = _make(spec, seed=2)
+    H, W, tok, mask = _oracle_inputs(w)
+    K = w["K"]
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+    shuffled = g["group_ids"][torch.randperm(len(g["group_ids"]), generator=torch.Generator().manual_seed(1)).cuda()].contiguous()
+    for gid in (g["group_ids"], shuffled):
+        ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(w["rewards"]), _np(gid), K)
+        ref["slack"] = pb.coefficient_slack(ref, _np(w["rewards"]), mask)
+        for cache in ((False, True) if dtype == "bf16" else (False,)):
+            print(f"many generations {dtype}, cache {cache}, shuffled {gid is shuffled}", flush=True)
+            out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"], gid, K,
+                                              logits_cache=cache)
+            torch.cuda.synchronize()
+            _check_pair(rb, spec, out, ref)
 
 
 def test_inner_loop_on_synthetic_bandit(rb):
