@@ -267,7 +267,8 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     //   read f0 of tile kt+1 | MFMA f1 + first half of the requests for tile kt+2 (into `cur`)
     // After the barrier tile kt+1 is complete and nobody reads `cur` any more.  Steps past the last
     // tile re-request the last tile into the idle stage, which keeps the loop free of branches and
-    // every address in bounds.
+    // every address in bounds.  (Skipping those requests with a uniform branch each was tried: the logits
+    // kernels, where they are 6 % of the memory -> LDS traffic, got 2 % slower and dHidden 5 %.)
     Frags<WI, WJ> f0, f1;
     constexpr int NR = WI + WJ;   // LDS reads per sub-step
     constexpr int RA = S::BI / (8 * S::NW), RB = S::BJ / (8 * S::NW), SR = 8 * S::NW;
@@ -606,24 +607,13 @@ __device__ __forceinline__ void store_tile_through_lds(char* lds, const Lane<S>&
 // the token's own drift, so u is close to the probability itself; without behaviour log-probs it is
 // the sampled token's logit and u = p_v / p_y.  The exponent is clamped at 2^115 (a logit 79 above
 // the reference); a clamp sets RAPID_STATUS_LOGIT_RANGE.
+// Epilogue of a logits tile: per token row j (one lane pair) the max and the sum of exponentials over this
+// wave's 128 vocabulary columns.  The logit of the sampled token is gathered by a separate small kernel,
+// so the per-element work is one max, one fma, one exp and one add (STORE: and one multiply).
 template <class S, bool STORE>
-__global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
+__device__ __forceinline__ void fwd_epilogue(const FwdArgs& a, const TileId& t, int64_t j_tile, int M, char* lds,
+                                             f32x16 (&acc)[S::WI][S::WJ]) {
     constexpr int WI = S::WI, WJ = S::WJ;
-    extern __shared__ __attribute__((aligned(128))) char lds[];
-    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
-    if (a.row0 >= Mr) return;
-    // the order (and with it the split over the XCDs) covers the row tiles that hold tokens only
-    const int tilesM = min(a.tilesM, (int)((Mr - a.row0 + S::BJ - 1) / S::BJ));
-    for (int pid = blockIdx.x, ids = ids_for(a.tilesV, tilesM); pid < ids; pid += gridDim.x) {
-    const TileId t = map_tile(pid, a.tilesV, tilesM, a.gi);
-    const int64_t j_tile = a.row0 + (int64_t)t.tj * S::BJ;   // first token row of the tile
-    if (!t.valid) continue;
-    f32x16 acc[WI][WJ];
-    mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk, a.Hc + j_tile * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds,
-                acc);
-    // Epilogue: per token row j (one lane pair) the max and the sum of exponentials over this wave's
-    // 128 vocabulary columns.  The logit of the sampled token is gathered by a separate small kernel,
-    // so the per-element work is one max, one fma, one exp and one add (STORE: and one multiply).
     const Lane<S> L;
     const int i_base = t.ti * S::BI + L.wave_i * (WI * 32);
     const int n_valid = (int)a.V - i_base;          // columns of this wave that exist (>= 128: all)
@@ -690,7 +680,168 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
             a.part_sum[slot * a.ld_part + (j - a.part_row0)] = ls;
         }
     }
+}
+
+template <class S, bool STORE>
+__global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
+    constexpr int WI = S::WI, WJ = S::WJ;
+    extern __shared__ __attribute__((aligned(128))) char lds[];
+    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
+    if (a.row0 >= Mr) return;
+    // the order (and with it the split over the XCDs) covers the row tiles that hold tokens only
+    const int tilesM = min(a.tilesM, (int)((Mr - a.row0 + S::BJ - 1) / S::BJ));
+    for (int pid = blockIdx.x, ids = ids_for(a.tilesV, tilesM); pid < ids; pid += gridDim.x) {
+    const TileId t = map_tile(pid, a.tilesV, tilesM, a.gi);
+    const int64_t j_tile = a.row0 + (int64_t)t.tj * S::BJ;   // first token row of the tile
+    if (!t.valid) continue;
+    f32x16 acc[WI][WJ];
+    mainloop<S>(a.Wvd + (int64_t)t.ti * S::BI * a.ldk, a.ldk, a.Hc + j_tile * a.ldk, a.ldk, (int)(a.dpad / K_TILE), lds,
+                acc);
+    fwd_epilogue<S, STORE>(a, t, j_tile, M, lds, acc);
     }
+}
+
+// ---------------------------------------------------------------- fwd_lse, two workgroups per CU
+// The tiles of the logits kernels are short (K = d is a few dozen steps) and end in an epilogue the MFMA
+// pipe does not take part in (max, exp, sum over the accumulators; STORE: the staged store).  With one
+// workgroup per CU nothing else is resident to use the pipe meanwhile.  This variant runs TWO workgroups
+// of 4 waves per CU, each on a 256 (vocabulary) x 128 (token rows) tile, so one workgroup's epilogue and
+// tile fill overlap the other's main loop.  Each wave still owns 128 x 64 (the same fragments per MFMA as
+// the 8-wave kernel).  For two workgroups to fit, K advances 32 per step through three LDS stages of
+// 24 KiB (72 KiB per workgroup).  Half-line rows would double the L2 requests, so W comes from a copy that
+// is blocked per (256-row tile, K step): 16 KiB contiguous, already in the LDS order, and a request is a
+// straight 1 KiB copy; the hidden rows stay row-major (half a line per row and step, a third of the bytes).
+//
+// LDS layout of a stage: 256 W rows, then 128 hidden rows, 64 bytes each = 4 chunks of 16 bytes; chunk c of
+// row r sits at position c ^ ((r >> 2) & 3), which makes the ds_read_b128 fragment reads conflict free
+// (16 consecutive lanes = 16 consecutive rows of one chunk index cover 256 distinct bytes).
+struct Fwd2 {
+    using S = Geo<2, 2, 4, 2>;                     // 4 waves of 128 x 64: a 256 x 128 tile
+    static constexpr int K_STEP = 32;
+    static constexpr int A_BYTES = 256 * 64, B_BYTES = 128 * 64, STAGE = A_BYTES + B_BYTES, NSTAGE = 3;
+    static constexpr int LDS_BYTES = STAGE * NSTAGE;
+};
+
+// acc = W_tile . H_tile^T over `ksteps` steps of 32.  wblk: the tile's first block of the blocked copy of W
+// (ksteps blocks of 16 KiB follow each other); B: first hidden row of the tile, row-major, ldb elements.
+__device__ __forceinline__ void mainloop32(const char* __restrict__ wblk, const bf16_t* __restrict__ B, int64_t ldb,
+                                           int ksteps, char* lds, f32x16 (&acc)[4][2]) {
+    using S = Fwd2::S;
+    constexpr int WI = 4, WJ = 2;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_i = wave & 1, wave_j = wave >> 1;
+
+    // requests: a wave makes 4 for W (1 KiB each, linear) and 2 for the hidden rows (16 rows x 64 bytes each)
+    const char* ga = wblk + wave * 1024 + lane * 16;
+    const int gchunk = (lane & 3) ^ ((lane >> 4) & 3);            // chunk that belongs at slot lane % 4 of row lane / 4
+    const char* gb = (const char*)(B + (int64_t)(wave * 16 + (lane >> 2)) * ldb + gchunk * 8);
+    const int64_t b_round = 64 * ldb * 2;                         // the wave's next 16 rows are 64 rows on
+    const int dst_wave = wave * 1024;
+
+    // fragment reads
+    const int frow = lane & 31, fhi = lane >> 5;
+    const int x0 = (fhi ^ ((frow >> 2) & 3)) * 16, x1 = x0 ^ 32;  // chunk 2 ks + fhi at its swizzled position
+    const int a_off = (wave_i * 128 + frow) * 64;
+    const int b_off = Fwd2::A_BYTES + (wave_j * 64 + frow) * 64;
+
+#pragma unroll
+    for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ib][jb][v] = 0.f;
+    if (ksteps <= 0) return;
+
+    int src_step = 0;       // K step the next requests fetch (clamped to the last one: the loop has no branches
+    char* dst;              // and every address stays in bounds), and the stage they go to
+    auto request = [&](int r) {
+        if (r < 4)
+            load_to_lds_16(ga + (int64_t)src_step * Fwd2::A_BYTES + r * 4096, dst + dst_wave + r * 4096);
+        else
+            load_to_lds_16(gb + (int64_t)src_step * 64 + (r - 4) * b_round, dst + Fwd2::A_BYTES + dst_wave + (r - 4) * 4096);
+    };
+    auto read_frags = [&](Frags<WI, WJ>& f, const char* stage, int x) {
+        const uint32_t la = lds_addr(stage) + a_off + x, lb = lds_addr(stage) + b_off + x;
+        f.a[0] = ds_read128<0>(la); f.a[1] = ds_read128<2048>(la); f.a[2] = ds_read128<4096>(la); f.a[3] = ds_read128<6144>(la);
+        f.b[0] = ds_read128<0>(lb); f.b[1] = ds_read128<2048>(lb);
+    };
+
+    // everybody is done with the stages of the tile before (reads, trailing requests, a staged epilogue)
+    lds_barrier();
+    char* cur = lds;
+    char* nxt = lds + Fwd2::STAGE;
+    char* fil = lds + 2 * Fwd2::STAGE;
+    dst = cur; src_step = 0;
+#pragma unroll
+    for (int r = 0; r < 6; ++r) request(r);
+    dst = nxt; src_step = ksteps > 1 ? 1 : 0;
+#pragma unroll
+    for (int r = 0; r < 6; ++r) request(r);
+    asm volatile("s_waitcnt vmcnt(6)" ::: "memory");   // step 0 has landed (loads complete in order)
+    lds_barrier();
+    Frags<WI, WJ> f0, f1;
+    read_frags(f0, cur, x0);
+    wait_frags<0>(f0);
+    // One K step on stage `cur` (its first fragments f0 are in registers):
+    //   read f1 (second half of the step) | MFMA f0 + the requests for step kt+2 into `fil`
+    //   wait: own reads of `cur` done, own requests for step kt+1 landed; barrier
+    //   read f0 of step kt+1              | MFMA f1
+    // `fil` was read during step kt-1, and everybody passed the barrier at the end of that step.
+    for (int kt = 0; kt < ksteps; ++kt) {
+        fence();
+        read_frags(f1, cur, x1);
+        fence();
+        dst = fil;
+        src_step = kt + 2 < ksteps ? kt + 2 : ksteps - 1;
+        mma_block_requesting<S, 0, 12>(f0, acc, request);   // requests 0..5 after MFMAs 0, 1, 2, 4, 5, 6
+        fence();
+        wait_frags<0>(f1);
+        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        lds_barrier();
+        read_frags(f0, nxt, x0);
+        fence();
+        mma_block<WI, WJ>(f1, acc);
+        fence();
+        wait_frags<0>(f0);
+        char* t = cur; cur = nxt; nxt = fil; fil = t;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests for steps that do not exist
+}
+
+template <bool STORE>
+__global__ __launch_bounds__(256, 2) void fwd_lse2_kernel(FwdArgs a) {
+    using S = Fwd2::S;
+    extern __shared__ __attribute__((aligned(128))) char lds[];
+    const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
+    if (a.row0 >= Mr) return;
+    // 128-row tiles; the order covers the row tiles that hold tokens only
+    const int tilesM = min(a.tilesM * 2, (int)((Mr - a.row0 + S::BJ - 1) / S::BJ));
+    const int ksteps = (int)(a.dpad / Fwd2::K_STEP);
+    for (int pid = blockIdx.x, ids = ids_for(a.tilesV, tilesM); pid < ids; pid += gridDim.x) {
+        const TileId t = map_tile(pid, a.tilesV, tilesM, a.gi);
+        if (!t.valid) continue;
+        const int64_t j_tile = a.row0 + (int64_t)t.tj * S::BJ;
+        f32x16 acc[4][2];
+        mainloop32((const char*)a.WvdB + (int64_t)t.ti * ksteps * Fwd2::A_BYTES, a.Hc + j_tile * a.ldk, a.ldk, ksteps, lds, acc);
+        fwd_epilogue<S, STORE>(a, t, j_tile, M, lds, acc);
+    }
+}
+
+// W as the two-workgroup forward reads it: for every 256-row tile and K step of 32 a 16 KiB block, row r's
+// chunk c (8 elements) at position c ^ ((r >> 2) & 3) of the row's 64 bytes.  One thread per 16-byte chunk.
+__global__ void block_w32_kernel(const bf16_t* __restrict__ Wvd, int64_t ldk, bf16_t* __restrict__ out, int64_t Vpad,
+                                 int64_t dpad) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // destination chunk
+    const int64_t ksteps = dpad / 32, total = Vpad * ksteps * 4;
+    if (o >= total) return;
+    const int64_t tile = o / (ksteps * 1024), rem = o % (ksteps * 1024);
+    const int64_t ks = rem / 1024;
+    const int within = (int)(rem % 1024), row = within >> 2, pos = within & 3;
+    const int c = pos ^ ((row >> 2) & 3);
+    const uint4 v = *(const uint4*)(Wvd + (tile * 256 + row) * ldk + ks * 32 + c * 8);
+    *(uint4*)(out + o * 8) = v;
 }
 
 // ------------------------------------------------------------------------------------------ dz
@@ -1121,7 +1272,23 @@ void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 8 || n == 16) ? 
 void set_cu_count(int n) { g_num_cu = n >= 8 ? n : 8; }
 
 
+void launch_block_w32(const bf16_t* Wvd, int64_t ldk, bf16_t* out, int64_t Vpad, int64_t dpad, hipStream_t st) {
+    const int64_t chunks = Vpad * (dpad / 32) * 4;
+    block_w32_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(Wvd, ldk, out, Vpad, dpad);
+}
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
+    if (a.WvdB) {   // two workgroups of 4 waves per CU on 256 x 128 tiles
+        const int ids = ids_for(a.tilesV, a.tilesM * 2), slots = g_num_cu.load() / 8 * 8 * 2;
+        const unsigned grid = (unsigned)(ids < slots ? ids : slots);
+        if (a.zc) {
+            allow_lds<&fwd_lse2_kernel<true>>(Fwd2::LDS_BYTES);
+            fwd_lse2_kernel<true><<<grid, 256, Fwd2::LDS_BYTES, st>>>(a);
+        } else {
+            allow_lds<&fwd_lse2_kernel<false>>(Fwd2::LDS_BYTES);
+            fwd_lse2_kernel<false><<<grid, 256, Fwd2::LDS_BYTES, st>>>(a);
+        }
+        return;
+    }
     const int w = waves_for(8);
     if (w == 16) launch_fwd_lse_t<G16>(a, st); else if (w == 8) launch_fwd_lse_t<G8>(a, st); else launch_fwd_lse_t<G4>(a, st);
 }

@@ -41,6 +41,7 @@ std::atomic<int> g_cached_dw_step_tiles{0};   // row tiles per dW launch with th
 std::atomic<int> g_cached_step_tiles{256};    // row tiles per dHidden / dW launch with the cache (tuning key 15; 0 = all rows)
 std::atomic<int> g_pace_every{0};             // K steps between meetings of the dHidden workgroups (tuning key 16; 0 = off)
 std::atomic<int> g_fwd_block_tiles{64};       // row tiles per launch of the two logits kernels (tuning key 13)
+std::atomic<int> g_fwd_two_wg{0};             // logits kernels: two 4-wave workgroups per CU on 256 x 128 tiles (tuning key 21)
 std::atomic<int> g_skip_idle{1};              // cached backward: generations without gradient are left out of dHidden / dW (tuning key 19)
 std::atomic<int> g_dh_split{1};               // dHidden cuts the tiles of a partly filled last round along the contraction (tuning key 17)
 
@@ -111,13 +112,14 @@ struct Plan {
     // (Mmax_pad = Cmax * Rcap then); the cache and the log-sum-exp partials hold one region.  Cmax = 0 otherwise.
     int64_t Rcap;
     int Cmax;
+    bool two_wg;        // the forward runs two workgroups per CU and reads W from its K-blocked copy (Wvd32)
     int64_t ld_part;    // columns of the log-sum-exp partials
     int64_t rms_blocks; // row blocks of the final norm's dweight partial sums
     size_t per_row;     // chunk bytes per row
     size_t fixed, total;
     // offsets into the workspace
     size_t counts, pace, seq_len, cu, row_index, tokc, seqc, zy, refz, lse_c, inv_rms, rms_part, rowc, rowg, logp_tmp, s64, s32, adv, adv64, g, g64, tsum, tmax,
-        Hc, Wvd, Wdv, WdvB, dh_part, part_max, part_sum, dw32, chunk0, tab, gen_row0, gen_chunk, gseen, lam_state, lam_chunk, beta_scale, idle, len_live, cu_live, live_group, gruns;
+        Hc, Wvd, Wdv, WdvB, dh_part, part_max, part_sum, dw32, chunk0, tab, gen_row0, gen_chunk, gseen, lam_state, lam_chunk, beta_scale, idle, len_live, cu_live, live_group, gruns, Wvd32;
 };
 
 size_t take(size_t& cur, size_t bytes) {
@@ -200,6 +202,8 @@ bool make_plan(Plan& p, int op, int64_t N, int64_t T, int64_t d, int64_t V, int6
     if (dtype == RAPID_DTYPE_BF16) {
         p.Hc = take(cur, (size_t)p.Mmax_pad * p.ldk * 2);
         p.Wvd = take(cur, (size_t)p.Vpad * p.ldk * 2);
+        p.two_wg = g_fwd_two_wg.load() != 0;
+        if (p.two_wg) p.Wvd32 = take(cur, (size_t)p.Vpad * p.dpad * 2);
         p.part_max = take(cur, (size_t)p.P * p.ld_part * 4);
         p.part_sum = take(cur, (size_t)p.P * p.ld_part * 4);
         if (bwd) {
@@ -344,6 +348,7 @@ void pack_w_for_logits(const Plan& p, void* ws, const void* W, int w_layout, hip
         launch_copy_pad_bf16((const bf16_t*)W, p.d, nullptr, Wvd, p.ldk, p.V, p.d, p.Vpad, p.dpad, nullptr, 0, st);
     else
         launch_transpose_pad_bf16((const bf16_t*)W, p.V, Wvd, p.ldk, p.d, p.V, p.dpad, p.Vpad, nullptr, 0, st);
+    if (p.two_wg) launch_block_w32(Wvd, p.ldk, at<bf16_t>(ws, p.Wvd32), p.Vpad, p.dpad, st);
 }
 
 // bf16 forward over the compact rows [base, base + rows) (rows a multiple of 256; `counts` holds the end of the
@@ -378,6 +383,7 @@ void forward_rows_bf16(const Plan& p, void* ws, const FwdIo& io, const int32_t* 
     a.zc = io.zc; a.ldz = p.ldv; a.dev_status = io.dev_status;
     a.refz = at<float>(ws, p.refz); a.ref_logp = io.ref_logp; a.row_index = row_index;
     a.part_row0 = base; a.zc_row0 = base;
+    a.WvdB = p.two_wg ? at<bf16_t>(ws, p.Wvd32) : nullptr;
     {   // the sampled tokens' logits first: a storing forward uses them as its per-row reference
         Span sp(ST_MERGE, st);
         launch_token_logit(a, base, rows, st);
@@ -582,6 +588,10 @@ int rapid_set_tuning(int key, int value) {
     }
     if (key == 17 && (value == 0 || value == 1)) {
         g_dh_split = value;
+        return RAPID_OK;
+    }
+    if (key == 21 && (value == 0 || value == 1)) {
+        g_fwd_two_wg = value;
         return RAPID_OK;
     }
     if (key == 20 && value >= 0) {

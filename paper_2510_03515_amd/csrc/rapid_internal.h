@@ -200,8 +200,12 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     int32_t* dev_status;  // may be NULL
     int64_t part_row0 = 0;   // compact row whose partials sit in column 0 of part_max / part_sum
     int64_t zc_row0 = 0;     // compact row stored in row 0 of zc
+    const bf16_t* WvdB = nullptr;   // if set: W blocked per (256-row tile, K step of 32) (launch_block_w32); selects the
+                                    // kernel that runs two workgroups per CU
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
+// out [Vpad * dpad]: Wvd [Vpad, ldk] in blocks of 256 rows x 32 columns, in the LDS order of the two-workgroup forward
+void launch_block_w32(const bf16_t* Wvd, int64_t ldk, bf16_t* out, int64_t Vpad, int64_t dpad, hipStream_t st);
 // zy (and refz) for the compact rows [row0, row0 + rows_max)
 void launch_token_logit(const FwdArgs& a, int64_t row0, int64_t rows_max, hipStream_t st);
 int fwd_slots_per_tile();

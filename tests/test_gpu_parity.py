@@ -846,6 +846,45 @@ def test_other_workgroup_geometries(rb, waves):
         rb.rapid_set_tuning(2, 0)
 
 
+def test_forward_with_two_workgroups_per_cu(rb):
+    """Tuning key 21: the logits kernel as two 4-wave workgroups per CU on 256 x 128 tiles, K steps of 32 through
+    three LDS stages, W from its K-blocked copy.  Same tolerances against the oracle: the behaviour pass, the fused
+    call in both backward modes and layouts, the chunked cache; and the same log-probs, bit for bit, as the
+    default kernel (the same products summed in the same order per accumulator)."""
+    try:
+        base = {}
+        for name in ("bf16_small", "bf16_ragged"):
+            w, g = _make(SPECS[name])
+            base[name] = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])[0].clone()
+        rb.rapid_set_tuning(21, 1)
+        for name in ("bf16_small", "bf16_ragged"):
+            print(f"two workgroups per CU: {name}", flush=True)
+            w, g = _make(SPECS[name])
+            lp, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])
+            torch.cuda.synchronize()
+            assert torch.equal(lp, base[name])
+            for cache in (False, True):
+                w, out, ref = _run_pair(rb, SPECS[name], logits_cache=cache)
+                _check_pair(rb, SPECS[name], out, ref)
+        w, out, ref = _run_pair(rb, SPECS["bf16_ragged"], layout="vd", logits_cache=True)
+        _check_pair(rb, SPECS["bf16_ragged"], out, ref, "vd")
+        # chunks of whole groups at the smallest window
+        spec = CHUNKY
+        w, g = _make(spec, seed=4)
+        N, T, d = g["hidden"].shape
+        least = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, spec.V, w["K"], rb.DTYPE_BF16, minimum=True)
+        logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+        buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], workspace_bytes=least)
+        out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"], g["group_ids"], w["K"],
+                                          buffers=buf, logits_cache=True)
+        torch.cuda.synchronize()
+        H, W, tok, mask = _oracle_inputs(w)
+        ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(w["rewards"]), _np(w["group_ids"]), w["K"])
+        _check_pair(rb, spec, out, ref)
+    finally:
+        rb.rapid_set_tuning(21, 0)
+
+
 def test_dhidden_pacing_is_timing_only(rb):
     """Tuning key 16: the dHidden workgroups meet every so many K steps (a vocabulary of 20 000 makes
     313 steps, so meetings every 64 steps do happen here, with fewer workgroups than CUs): same bits
