@@ -1024,28 +1024,54 @@ __global__ __launch_bounds__(S::NT) void dh_reduce_kernel(DhArgs a, int grid_of_
     if (!sh.cut || tpos >= sh.rem) return;
     const int ktiles = (int)(a.Vpad / K_TILE);
     const TileId t = tile_of_vid(x * sh.per + sh.full_rounds * sh.wgs + tpos, tilesD, tilesM, a.gi > 0 ? a.gi : tilesD);
-    f32x16 acc[WI][WJ];
-#pragma unroll
-    for (int ib = 0; ib < WI; ++ib)
-#pragma unroll
-        for (int jb = 0; jb < WJ; ++jb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[ib][jb][v] = 0.f;
     const int64_t t0 = (int64_t)tpos * ktiles, t1 = t0 + ktiles;     // this tile's K steps on the line
-    for (int w = 0; w < sh.wgs; ++w) {                               // in workgroup order: a fixed order of summation
+    // the workgroups whose stretch touched this tile are consecutive: [w_first, w_last]
+    int w_first = sh.wgs, w_last = -1;
+    for (int w = 0; w < sh.wgs; ++w) {
         int64_t u0, u1;
         sh.stretch(w, ktiles, u0, u1);
         if (u0 >= u1 || u1 <= t0 || u0 >= t1) continue;
-        const int piece = (u0 / ktiles == tpos) ? 0 : 1;             // the stretch began in this tile, or in the one before
-        const float* in = a.part + ((int64_t)(x + 8 * w) * 2 + piece) * (S::BI * S::BJ) + threadIdx.x;
-#pragma unroll
-        for (int ib = 0; ib < WI; ++ib)
-#pragma unroll
-            for (int jb = 0; jb < WJ; ++jb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[ib][jb][v] += in[((ib * WJ + jb) * 16 + v) * S::NT];
+        w_first = min(w_first, w);
+        w_last = w;
     }
-    dh_store<S>(a, t, M, acc);
+    // One 32 x 32 block at a time, its pieces added in workgroup order (a fixed order of summation).  The 16
+    // loads of a piece are independent and in flight together; with all 256 accumulators of the tile live at
+    // once the loads went out one by one, each a trip to memory, and a tile with five pieces took 3 ms.
+    const Lane<S> L;
+    const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
+#pragma unroll
+    for (int jb = 0; jb < WJ; ++jb) {
+        const int64_t j = a.m0 + (int64_t)t.tj * S::BJ + L.wave_j * (WJ * 32) + jb * 32 + L.lj;
+        const bool row_live = j < M;
+        bf16_t* out = a.dhidden + (row_live ? (int64_t)a.row_index[j] * a.d : 0);
+        const float cj = (a.rowc && row_live) ? a.rowc[j] : 1.f;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib) {
+            float sum[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum[v] = 0.f;
+            for (int w = w_first; w <= w_last; ++w) {
+                int64_t u0, u1;
+                sh.stretch(w, ktiles, u0, u1);
+                if (u0 >= u1) continue;                              // an empty stretch (fewer K steps than workgroups)
+                const int piece = (u0 / ktiles == tpos) ? 0 : 1;     // the stretch began in this tile, or in the one before
+                const float* in = a.part + ((int64_t)(x + 8 * w) * 2 + piece) * (S::BI * S::BJ) + threadIdx.x +
+                                  (int64_t)((ib * WJ + jb) * 16) * S::NT;
+                float got[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) got[v] = in[v * S::NT];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum[v] += got[v];
+            }
+            if (!row_live) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t i0 = i_base + ib * 32 + q * 8 + L.hi * 4;
+                if (i0 < a.d)
+                    *(uint2*)(out + i0) = pack_bf16x4(cj * sum[q * 4], cj * sum[q * 4 + 1], cj * sum[q * 4 + 2], cj * sum[q * 4 + 3]);
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------ dw

@@ -303,42 +303,68 @@ __global__ void gather_tokens_kernel(const int32_t* __restrict__ tokens, const i
     seqc[j] = seq;
 }
 
-// lse[j] = log sum_p part_sum[p][j] exp(part_max[p][j]) ; logp = zy - lse, scattered to [N,T]
-__global__ void merge_lse_kernel(const float* __restrict__ part_max, const float* __restrict__ part_sum, int P,
+// lse[j] = log sum_p part_sum[p][j] exp(part_max[p][j]) ; logp = zy - lse, scattered to [N,T].
+// Four lanes share a column: lane group q (lanes 16 q .. 16 q + 15 of a wave) folds the slots
+// [q P/4, (q+1) P/4) of 16 neighbouring columns, then the four (max, sum) pairs of a column are merged in
+// the order ((0, 1), (2, 3)).  A thread's loads are a dependent chain of P / 32 batches; one thread per column
+// left a 90 000-row chunk with too few threads to cover the memory latency.
+__global__ __launch_bounds__(256) void merge_lse_kernel(const float* __restrict__ part_max, const float* __restrict__ part_sum, int P,
                                  int64_t ld_part, const float* __restrict__ zy,
                                  const int32_t* __restrict__ row_index, const int32_t* __restrict__ counts,
                                  int64_t row0, float* __restrict__ lse_c, float* __restrict__ logp_out,
                                  float* __restrict__ lse_out) {
-    const int64_t jl = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // column of the partials
+    const int lane = threadIdx.x & 63, q = lane >> 4;
+    // 64 columns per block of 256 threads: wave w covers columns 16 w .. 16 w + 15 of the block
+    const int64_t jl = (int64_t)blockIdx.x * 64 + (threadIdx.x >> 6) * 16 + (lane & 15);
     const int64_t j = row0 + jl;
     const int M = counts[CNT_M];
-    if (j >= M) return;
-    // one pass with a running maximum; slots are merged in slot order, so the result is reproducible.
+    const bool live = j < M;
+    // one pass with a running maximum; slots are merged in a fixed order, so the result is reproducible.
     // The weights exp(pm - mx) are fp32 (relative error 1e-7, far below the fp32 rounding of the
     // partial sums themselves), the accumulation fp64.
     float mx = -INFINITY;
     double acc = 0.0;
     constexpr int UN = 8;   // slots loaded ahead of the fold: the loads of a batch are in flight together
-    for (int p0 = 0; p0 < P; p0 += UN) {
-        float pmv[UN], psv[UN];
+    const int p_begin = (int)((int64_t)P * q / 4), p_end = (int)((int64_t)P * (q + 1) / 4);
+    if (live) {
+        for (int p0 = p_begin; p0 < p_end; p0 += UN) {
+            float pmv[UN], psv[UN];
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const bool in = p0 + u < P;
-            pmv[u] = in ? part_max[(int64_t)(p0 + u) * ld_part + jl] : 0.f;
-            psv[u] = in ? part_sum[(int64_t)(p0 + u) * ld_part + jl] : 0.f;
-        }
+            for (int u = 0; u < UN; ++u) {
+                const bool in = p0 + u < p_end;
+                pmv[u] = in ? part_max[(int64_t)(p0 + u) * ld_part + jl] : 0.f;
+                psv[u] = in ? part_sum[(int64_t)(p0 + u) * ld_part + jl] : 0.f;
+            }
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const float pm = pmv[u], ps = psv[u];
-            if (!(ps > 0.f)) continue;
-            if (pm > mx) {
-                acc = acc * (double)__expf(mx - pm) + (double)ps;   // exp(-inf) = 0 on the first slot
-                mx = pm;
-            } else {
-                acc += (double)ps * (double)__expf(pm - mx);
+            for (int u = 0; u < UN; ++u) {
+                const float pm = pmv[u], ps = psv[u];
+                if (!(ps > 0.f)) continue;
+                if (pm > mx) {
+                    acc = acc * (double)__expf(mx - pm) + (double)ps;   // exp(-inf) = 0 on the first slot
+                    mx = pm;
+                } else {
+                    acc += (double)ps * (double)__expf(pm - mx);
+                }
             }
         }
     }
+    // merge the four lane groups of the column: (0, 1) and (2, 3), then the two results
+#pragma unroll
+    for (int step = 16; step <= 32; step <<= 1) {
+        const float omx = __shfl_xor(mx, step, 64);
+        const double oacc = __shfl_xor(acc, step, 64);
+        // both partners compute the same merged pair: the lower lane's operand first
+        const bool low = (lane & step) == 0;
+        const float m0 = low ? mx : omx, m1 = low ? omx : mx;
+        const double a0 = low ? acc : oacc, a1 = low ? oacc : acc;
+        const float mm = fmaxf(m0, m1);
+        double r = 0.0;
+        if (a0 > 0.0) r += a0 * (double)__expf(m0 - mm);
+        if (a1 > 0.0) r += a1 * (double)__expf(m1 - mm);
+        mx = mm;
+        acc = r;
+    }
+    if (!live || q != 0) return;
     const double lse = (double)mx + log(acc);
     const float lse_f = (float)lse;
     lse_c[j] = lse_f;
@@ -722,7 +748,7 @@ void launch_merge_lse(const float* part_max, const float* part_sum, int P, int64
                       const int32_t* row_index, const int32_t* counts, int64_t row0, int64_t rows_max, float* lse_c,
                       float* logp_out, float* lse_out, hipStream_t st) {
     if (rows_max > 0)
-        merge_lse_kernel<<<blocks_for(rows_max, 256), 256, 0, st>>>(part_max, part_sum, P, ld_part, zy, row_index,
+        merge_lse_kernel<<<blocks_for(rows_max, 64), 256, 0, st>>>(part_max, part_sum, P, ld_part, zy, row_index,
                                                                     counts, row0, lse_c, logp_out, lse_out);
 }
 

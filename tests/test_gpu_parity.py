@@ -885,6 +885,40 @@ def test_forward_with_two_workgroups_per_cu(rb):
         rb.rapid_set_tuning(21, 0)
 
 
+@pytest.mark.parametrize("V", [520, 200])
+def test_dhidden_cut_last_round(rb, V):
+    """dHidden with more tiles than workgroups and a last round that fills a fraction of them: 140 row tiles x 2
+    column tiles = 280 tiles on 256 workgroups, 35 per XCD, so each XCD's last round holds 3 tiles, which are cut
+    along the vocabulary into 32 stretches, written as partial tiles and summed by the reduce pass.  V = 520 is 12
+    K steps per tile; V = 200 is 4, fewer K steps on the line than workgroups, so some stretches are empty.  Against
+    the oracle in both backward modes, and against the same call with the cut switched off (tuning key 17)."""
+    spec = wl.small_spec("dh_cut", "bf16", d=512, V=V, prompts=35, G=4, len_lo=256, len_hi=256, sigma=0.02, reward="uniform")
+    w, g = _make(spec, seed=3)
+    H, W, tok, mask = _oracle_inputs(w)
+    K = w["K"]
+    logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+    ref = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, _np(logp_b), _np(w["rewards"]), _np(w["group_ids"]), K)
+    ref["slack"] = pb.coefficient_slack(ref, _np(w["rewards"]), mask)
+    for cache in (False, True):
+        print(f"dHidden cut, V={V}, cache {cache}", flush=True)
+        out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"], g["group_ids"], K,
+                                          logits_cache=cache, max_tokens=int(mask.sum()))
+        torch.cuda.synchronize()
+        _check_pair(rb, spec, out, ref)
+        dh_cut = out.dhidden.clone()
+        try:
+            rb.rapid_set_tuning(17, 0)
+            out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"], g["group_ids"], K,
+                                              logits_cache=cache, max_tokens=int(mask.sum()))
+            torch.cuda.synchronize()
+        finally:
+            rb.rapid_set_tuning(17, 1)
+        _check_pair(rb, spec, out, ref)
+        # the same products in another order of summation: equal up to the fp32 rounding of the accumulators
+        assert _rel(_np(dh_cut), _np(out.dhidden)) <= 2e-3
+        assert not torch.equal(dh_cut, out.dhidden) or V == 200
+
+
 def test_dhidden_pacing_is_timing_only(rb):
     """Tuning key 16: the dHidden workgroups meet every so many K steps (a vocabulary of 20 000 makes
     313 steps, so meetings every 64 steps do happen here, with fewer workgroups than CUs): same bits
