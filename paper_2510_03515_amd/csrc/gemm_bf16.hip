@@ -607,6 +607,7 @@ __device__ __forceinline__ void store_tile_through_lds(char* lds, const Lane<S>&
 // the token's own drift, so u is close to the probability itself; without behaviour log-probs it is
 // the sampled token's logit and u = p_v / p_y.  The exponent is clamped at 2^115 (a logit 79 above
 // the reference); a clamp sets RAPID_STATUS_LOGIT_RANGE.
+//
 // Epilogue of a logits tile: per token row j (one lane pair) the max and the sum of exponentials over this
 // wave's 128 vocabulary columns.  The logit of the sampled token is gathered by a separate small kernel,
 // so the per-element work is one max, one fma, one exp and one add (STORE: and one multiply).
@@ -682,6 +683,7 @@ __device__ __forceinline__ void fwd_epilogue(const FwdArgs& a, const TileId& t, 
     }
 }
 
+// one workgroup per CU on 256 x 256 tiles: the logits tile on MFMA, then the epilogue above
 template <class S, bool STORE>
 __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;

@@ -173,6 +173,37 @@ def test_zero_variance_groups():
     assert empty["group_size"][2] == 0 and empty["group_mean"][2] == 0 and empty["group_std"][2] == 0
 
 
+def test_all_zero_reward_group_carries_no_gradient():
+    """What lets an implementation leave such generations out of the backward: if every reward of a group is 0,
+    Eq. (5)'s weighted baseline is a mean of zeros, so A_n = 0 for its members whatever their ratios are, in
+    every baseline mode, with either outer weight and either ratio level; their rows of dHidden are exact zeros
+    and dW is what the other groups alone give.  The same holds for the baselines' normalised advantage when
+    there is no KL term; with one, every token carries gradient."""
+    H, W, W_old, tok, mask, R, gid, logp_b = _tiny(seed=5, N=6, T=4, d=3, V=5, G=2)
+    R = R.copy()
+    R[gid == 1] = 0.0
+    rest = gid != 1
+    for kw in (dict(), dict(baseline_mode=1), dict(baseline_mode=2), dict(coef_mode=1, eta=1.1), dict(ratio_level=1),
+               dict(normalized_grads=True)):
+        out = orc.iw_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, R, gid, 3, **kw)
+        assert np.all(out["adv"][gid == 1] == 0.0) and np.all(out["dH"][gid == 1] == 0.0), kw
+        assert np.abs(out["dH"][rest]).max() > 0
+        # the same batch without that group's generations: their share of dW is nothing (1/N stays that of the
+        # full batch: loss_scale carries it)
+        sub = orc.iw_pg_loss_fwd_bwd(H[rest], W, tok[rest], mask[rest], logp_b[rest], R[rest], np.array([0, 0, 1, 1]), 2,
+                                     loss_scale=rest.sum() / len(R), **kw)
+        scale = np.exp(sub["grad_log_scale"] - out["grad_log_scale"]) if kw.get("normalized_grads") else 1.0
+        assert np.allclose(out["dW"], sub["dW"] * scale, rtol=1e-12, atol=1e-15), kw
+        assert np.isclose(out["loss"], sub["loss"] * scale, rtol=1e-12)
+    logp_ref, _ = orc.logprob(H, W + 0.05, tok, mask)
+    no_kl = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, logp_ref, R, gid, 3, eps_low=0.2, eps_high=0.28, kl_beta=0.0,
+                                        norm_mode=1)
+    assert np.all(no_kl["adv"][gid == 1] == 0.0) and np.all(no_kl["dH"][gid == 1] == 0.0)
+    kl = orc.clipped_pg_loss_fwd_bwd(H, W, tok, mask, logp_b, logp_ref, R, gid, 3, eps_low=0.2, eps_high=0.2, kl_beta=0.04,
+                                     norm_mode=0)
+    assert np.all(kl["adv"][gid == 1] == 0.0) and np.abs(kl["dH"][gid == 1]).max() > 0
+
+
 # ---------------------------------------------------------------- log-probabilities
 def test_logprob_closed_forms():
     rng = np.random.default_rng(2)
