@@ -190,6 +190,89 @@ def test_full_size_sampled_parity(rb, cfg, cache, cal):
         pb.assert_dw_close(got[:, None], col[:, None])
 
 
+@pytest.mark.parametrize("variant,cache", [("grpo", True), ("dapo", False)])
+def test_full_size_clip_pg_sampled(rb, variant, cache):
+    """The loss step of a baseline (Sec. 4.1) at full size: config 1's shapes (d=896, V=151936, 128 generations,
+    ~76k response tokens), GRPO with its KL term against a reference policy through the chunked cache, DAPO through
+    the backward that regenerates the logits.  References as in test_full_size_sampled_parity: the float64 leg for
+    the current log-probs (pinned by the oracle on sampled positions), then the oracle's own advantage and
+    token-coefficient functions; sampled dHidden rows and dW columns, every element."""
+    spec = wl.CONFIGS[1]
+    print("generating", spec.name, variant, flush=True)
+    w = wl.make_workload(spec, seed=0, device="cuda")
+    N, T, K, V = spec.N, spec.T, w["K"], spec.V
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    W_ref = (w["W"].float() + 0.004 * torch.randn(w["W"].shape, device="cuda", generator=gen)).to(torch.bfloat16)
+    lp_old, _ = rb.rapid_logprob_fwd(w["hidden"], w["W_old"], w["tokens"], w["mask"])
+    lp_ref, _ = rb.rapid_logprob_fwd(w["hidden"], W_ref, w["tokens"], w["mask"])
+    del W_ref
+    out = rb.rapid_clip_pg_loss_fwd_bwd(w["hidden"], w["W"], w["tokens"], w["mask"], lp_old, lp_ref, w["rewards"], w["group_ids"], K,
+                                        variant=variant, logits_cache=cache)
+    torch.cuda.synchronize()
+    assert out.dev_status.item() == 0
+    mask = w["mask"].cpu().numpy()
+    lengths = mask.sum(1)
+    W64 = _f64(w["W"])
+    rng = np.random.default_rng(1)
+    print("float64 leg", flush=True)
+    idx, lse_leg, logp_leg = _fp64_forward_leg(w)
+    lp_leg_nt = np.zeros(N * T); lp_leg_nt[idx.cpu().numpy()] = logp_leg.cpu().numpy(); lp_leg_nt = lp_leg_nt.reshape(N, T)
+    lp_gpu = _f64(out.logp_cur)
+    for _ in range(12):
+        n = int(rng.integers(0, N)); t = int(rng.integers(0, lengths[n]))
+        lp, _ = _row_oracle(w, W64, n, t)
+        assert abs(lp_leg_nt[n, t] - lp) <= 1e-9 and abs(lp_gpu[n, t] - lp) <= 2e-5, (n, t)
+    assert np.abs(lp_gpu - lp_leg_nt).max() <= 2e-5
+    # advantages, per-token coefficients, loss and diagnostics by the oracle
+    o = rb.clip_pg_default_opts(variant)
+    R, gid = _f64(w["rewards"]), w["group_ids"].cpu().numpy()
+    adv = orc.normalized_group_advantage(R, gid, K, adv_eps=o.adv_eps, std_ddof=o.std_ddof)["adv"]
+    assert np.abs(_f64(out.adv) - adv).max() <= 1e-3 * max(np.abs(adv).max(), 1.0)
+    ckw = dict(eps_low=o.eps_low, eps_high=o.eps_high, kl_beta=o.kl_beta, norm_mode=o.norm_mode)
+    old64, ref64 = _f64(lp_old), _f64(lp_ref)
+    print("token coefficients", flush=True)
+    g_ref, loss_ref, info = orc.clipped_token_coefficients(lp_leg_nt, old64, ref64, mask, adv, **ckw)
+    assert abs(out.loss.item() - loss_ref) <= 1e-3 * abs(loss_ref)
+    dg = rb.read_clip_diag(out)
+    assert dg["n_tokens"] == int(mask.sum()) and dg["n_sequences"] == N
+    r = np.exp(lp_leg_nt - old64)[mask != 0]
+    near = int(((np.abs(r - (1 - o.eps_low)) < 1e-5) | (np.abs(r - (1 + o.eps_high)) < 1e-5)).sum())
+    assert abs(dg["n_clipped"] - round(info["clip_fraction"] * dg["n_tokens"])) <= near
+    assert 0.0 < info["clip_fraction"] < 0.9
+    assert abs(dg["mean_kl"] - info["mean_kl"]) <= 1e-5 + 1e-3 * info["mean_kl"]
+    tok_slack, col_slack = pb.token_coefficient_slack(
+        lambda lp: orc.clipped_token_coefficients(lp, old64, ref64, mask, adv, **ckw)[0], lp_leg_nt, mask, w["tokens"].cpu().numpy(), V)
+    # sampled dHidden rows, every element
+    print("sampled dH rows", flush=True)
+    dH = out.dhidden
+    cand = np.argwhere((mask != 0) & (g_ref != 0))
+    for n, t in [tuple(cand[0]), tuple(cand[-1])] + [tuple(cand[i]) for i in rng.integers(0, len(cand), 6)]:
+        dh_ref, _ = orc.backward(_f64(w["hidden"][n:n + 1, t:t + 1]), W64, w["tokens"][n:n + 1, t:t + 1].cpu().numpy(),
+                                 np.ones((1, 1), np.uint8), np.array([[g_ref[n, t]]]))
+        got = _f64(dH[n, t])
+        assert np.linalg.norm(got - dh_ref[0, 0]) <= 2e-2 * np.linalg.norm(dh_ref[0, 0]), (n, t)
+        pb.assert_dhidden_close(got, dh_ref[0, 0], rel=pb.REL["bf16"] + tok_slack[n, t])
+    assert torch.all(dH[w["mask"] == 0] == 0)
+    if variant == "dapo":      # without a KL term, tokens whose ratio left the clip range the way their advantage pushes get nothing
+        dead = np.argwhere((mask != 0) & (g_ref == 0))
+        for n, t in dead[:: max(1, len(dead) // 8)][:8]:
+            assert not dH[int(n), int(t)].any()
+    # sampled dW columns, every element
+    print("sampled dW columns", flush=True)
+    dW = out.dW
+    Hv = w["hidden"].view(N * T, -1)[idx].double()
+    g_rows = torch.tensor(g_ref.reshape(-1), device="cuda")[idx]
+    tok_rows = w["tokens"].view(-1)[idx]
+    hot = [int(w["tokens"][int(n), int(t)].item()) for n, t in cand[:: max(1, len(cand) // 3)][:3]]
+    for v in [0, V - 1] + hot + [int(x) for x in rng.integers(0, V, 3)]:
+        z = Hv @ w["W"][:, v].double()
+        coef = g_rows * ((tok_rows == v).double() - torch.exp(z - lse_leg))
+        col = (Hv * coef[:, None]).sum(0).cpu().numpy()
+        got = _f64(dW[:, v])
+        assert np.linalg.norm(got - col) <= 2e-2 * max(np.linalg.norm(col), 1e-30), v
+        pb.assert_dw_close(got[:, None], col[:, None], rel=pb.REL["bf16"] + col_slack[v])
+
+
 def test_config4_behaviour_pass_sampled(rb):
     spec = wl.CONFIGS[4]
     print("generating", spec.name, flush=True)
