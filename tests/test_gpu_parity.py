@@ -950,16 +950,25 @@ def test_row_major_w_for_dhidden(rb):
     assert torch.equal(out.dhidden, out2.dhidden) and torch.equal(out.dW, out2.dW)
 
 
-@pytest.mark.parametrize("mode", [dict(), dict(logits_cache=True, ratio_level=1, coef_mode=1)])
+@pytest.mark.parametrize("mode", [dict(), dict(logits_cache=True, ratio_level=1, coef_mode=1),
+                                  dict(logits_cache=True, normalized_grads=True, chunks=True)])
 def test_hip_graph_replay_matches_eager(rb, mode):
     """The fused call only enqueues kernels on the caller's stream (no allocation, no host read of
     device data, no memset nodes), so it can be captured into a HIP graph; every replay, with eager
-    work in between, gives the bits of the eager call (default options, and the cache with the
-    token-level weight)."""
-    spec = SPECS["bf16_ragged"]
+    work in between, gives the bits of the eager call (default options; the cache with the
+    token-level weight; the cache at its smallest window, i.e. several chunks of whole groups whose
+    sizes only the device knows, with the running rescale of normalised gradients)."""
+    mode = dict(mode)
+    chunks = mode.pop("chunks", False)
+    spec = CHUNKY if chunks else SPECS["bf16_ragged"]
     w, g = _make(spec)
     logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
-    buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], logits_cache=mode.get("logits_cache", False))
+    if chunks:
+        N, T, d = g["hidden"].shape
+        least = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, spec.V, w["K"], rb.DTYPE_BF16, minimum=True)
+        buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], workspace_bytes=least)
+    else:
+        buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], logits_cache=mode.get("logits_cache", False))
     call = lambda: rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"],
                                                g["group_ids"], w["K"], buffers=buf, **mode)
     call()
