@@ -191,7 +191,14 @@ def _check_pair(rb, spec, out, ref, layout="dv"):
     assert np.abs(_np(out.tok_logratio) - ref["tok_logratio"]).max() <= 2 * LOGP_ATOL[spec.dtype]
     assert np.allclose(_np(out.adv), ref["adv"], atol=1e-3 if spec.dtype == "bf16" else 1e-5)
     loss = out.loss.item()
-    assert abs(loss - ref["loss"]) <= LOSS_RTOL * max(abs(ref["loss"]), 1e-30), (loss, ref["loss"])
+    # The loss is a sum of per-generation terms that may cancel (on-policy, complete groups: exactly 0 in the
+    # library, whose ratios are exactly 1 there, and a rounding residue in the oracle, whose current log-probs
+    # are float64 against float stored ones): each term gets the slack its coefficient has.
+    tol = LOSS_RTOL * max(abs(ref["loss"]), 1e-30)
+    if ref.get("slack") is not None:
+        per_gen = np.abs(np.asarray(ref["g"], np.float64)).reshape(len(ref["adv"]), -1).max(axis=1)
+        tol += float((per_gen * np.maximum(ref["slack"], 2.0 ** -23)).sum())
+    assert abs(loss - ref["loss"]) <= tol, (loss, ref["loss"], tol)
     _dh_ok(out.dhidden, ref["dH"], spec.dtype, slack=ref.get("slack"))
     _dw_ok(dW, ref["dW"], spec.dtype, slack=ref.get("slack"))
     mask0 = ref["logp_cur"] == 0
@@ -785,6 +792,53 @@ def test_many_short_generations(rb, dtype):
             print(f"many generations {dtype}, cache {cache}, shuffled {gid is shuffled}", flush=True)
             out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"], gid, K,
                                               logits_cache=cache)
+            torch.cuda.synchronize()
+            _check_pair(rb, spec, out, ref)
+
+
+def _random_specs(count, seed):
+    """Seeded shapes off every tile boundary: d a multiple of 8 (bf16) or anything (f32), V from a handful to a few
+    tiles, group counts and lengths from one token up."""
+    rng = np.random.default_rng(seed)
+    specs = []
+    for i in range(count):
+        dtype = "bf16" if i % 3 else "f32"
+        d = int(rng.integers(1, 41)) * 8 if dtype == "bf16" else int(rng.integers(1, 90))
+        V = int(rng.choice([rng.integers(2, 40), rng.integers(40, 600), rng.integers(600, 1400)]))
+        prompts, G = int(rng.integers(1, 7)), int(rng.integers(1, 6))
+        lo = int(rng.integers(1, 30))
+        hi = lo + int(rng.integers(0, 90))
+        specs.append(wl.small_spec(f"random{i}", dtype, d=d, V=V, prompts=prompts, G=G, len_lo=lo, len_hi=hi,
+                                   sigma=float(rng.choice([0.0, 0.01, 0.05])), reward=str(rng.choice(["bernoulli", "uniform"]))))
+    return specs
+
+
+@pytest.mark.parametrize("spec", _random_specs(18, seed=2024), ids=lambda s: f"{s.name}-{s.dtype}-d{s.d}-V{s.V}-{s.prompts}x{s.G}-L{s.len_lo}-{s.len_hi}")
+def test_random_shapes(rb, spec):
+    """A seeded sweep of small shapes that sit on no tile boundary: every output of the fused call against the
+    oracle, with the regenerating backward and (bf16) with the cache at its smallest window and at its default size,
+    options drawn per shape."""
+    rng = np.random.default_rng(spec.d * 1000 + spec.V)
+    kw = dict(baseline_mode=int(rng.integers(0, 3)), coef_mode=int(rng.integers(0, 2)), eta=float(rng.choice([1.2, 2.0, math.inf])),
+              normalized_grads=bool(rng.integers(0, 2)))
+    if spec.dtype == "bf16" and rng.integers(0, 3) == 0:
+        kw["ratio_level"] = 1
+    print(f"random shape {spec} {kw}", flush=True)
+    for cache in ((False, True) if spec.dtype == "bf16" else (False,)):
+        w, out, ref = _run_pair(rb, spec, seed=7, logits_cache=cache, **kw)
+        _check_pair(rb, spec, out, ref)
+        if kw["normalized_grads"]:
+            assert abs(out.read_diag()["grad_log_scale"] - ref["grad_log_scale"]) <= 1e-3
+    if spec.dtype == "bf16":       # smallest window: chunks of whole groups (a group of more than 256 tokens cannot go through it)
+        w, g = _make(spec, seed=7)
+        lengths = _np(w["mask"]).sum(1).reshape(spec.prompts, spec.G).sum(1)
+        if lengths.max() <= 256:
+            N, T, d = g["hidden"].shape
+            least = rb.rapid_workspace_bytes(rb.OP_IW_PG_FWD_BWD_CACHED, N, T, d, spec.V, w["K"], rb.DTYPE_BF16, minimum=True)
+            logp_b, _ = rb.rapid_logprob_fwd(g["hidden"], g["W_old"], g["tokens"], g["mask"])
+            buf = rb.IwPgBuffers(g["hidden"], g["W"], w["K"], workspace_bytes=least)
+            out = rb.rapid_iw_pg_loss_fwd_bwd(g["hidden"], g["W"], g["tokens"], g["mask"], logp_b, g["rewards"], g["group_ids"],
+                                              w["K"], buffers=buf, logits_cache=True, **kw)
             torch.cuda.synchronize()
             _check_pair(rb, spec, out, ref)
 
