@@ -12,7 +12,7 @@ dHidden and dW contract them, so 6 d V flop per token are executed and nothing o
 outlives a chunk.  Generations of a group whose rewards are all 0 have advantage 0 by Eq. (5) and so
 no gradient; the backward leaves them out of its contractions (exactly), and the flop counts
 here leave them out as well (`response_tokens_with_gradient`).  Beside it, never as `value`: the same call with a cache that holds the whole batch
-at once ("whole", 94 GiB), with the backward that regenerates the logits ("recompute", 8 d V flop
+at once ("whole", 91 GiB), with the backward that regenerates the logits ("recompute", 8 d V flop
 per token), and on the workload's calibrated companion (dense gradients: every generation carries
 weight).
 

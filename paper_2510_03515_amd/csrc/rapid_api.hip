@@ -252,7 +252,7 @@ int cached_chunks(int64_t rows, int64_t Rcap) { return Rcap >= rows ? 1 : (int)(
 // Cache rows of the recommended workspace, if the batch has more (tuning key 18).  Every launch of the dHidden and
 // dW kernels ends in a tail (workgroups finish at different times; dW re-reads and re-writes all of dW), so fewer,
 // larger chunks are faster: measured at the 1.5B shape, 65536 rows 338.7 ms per call (24.8 GiB), 90112 rows 334.4 ms
-// (31.7 GiB), 98304 rows 331.7 ms (34.3 GiB), the whole batch at once 329 ms (94 GiB).
+// (31.7 GiB), 98304 rows 331.7 ms (34.3 GiB), the whole batch at once 329 ms (91 GiB).
 std::atomic<int> g_cached_rcap{90112};
 
 // workspace bytes of the cached backward with a cache of Rcap rows for a batch of at most `rows` tokens; 0 if invalid
