@@ -50,10 +50,11 @@ extern "C" {
  * key 20: row tiles (of 256 rows) per dW launch of the cached backward; 0 (default) = all rows of the chunk in one
  *        launch.  dW sums over its launches in a fixed order, so results depend on the key only through fp32
  *        rounding.
- * key 21: 0 (default) / 1: the forward logits kernel as two 4-wave workgroups per CU on 256 x 128 tiles (K steps
- *        of 32, three LDS stages, W from a K-blocked copy that adds Vpad x dpad x 2 bytes to every workspace size
- *        while the key is set: set it before asking for sizes).  Identical results; measured slower (more L2
- *        traffic, lower clock), kept for that measurement. */
+ * key 21: 0 (default), or a variant of the forward logits kernel that takes K steps of 32 with W from a K-blocked
+ *        copy (which adds Vpad x dpad x 2 bytes to every workspace size while the key is set: set it before
+ *        asking for sizes): 1 = two 4-wave workgroups per CU on 256 x 128 tiles, three LDS stages; 2 = one 8-wave
+ *        workgroup per CU on 256 x 256 tiles, four stages, requests three steps ahead; 3 = the same with 4 waves
+ *        of 128 x 128.  Identical results; measured slower or equal, kept for those measurements. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

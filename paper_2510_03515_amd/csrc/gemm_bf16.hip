@@ -717,36 +717,43 @@ __global__ __launch_bounds__(S::NT) void fwd_lse_kernel(FwdArgs a) {
 // LDS layout of a stage: 256 W rows, then 128 hidden rows, 64 bytes each = 4 chunks of 16 bytes; chunk c of
 // row r sits at position c ^ ((r >> 2) & 3), which makes the ds_read_b128 fragment reads conflict free
 // (16 consecutive lanes = 16 consecutive rows of one chunk index cover 256 distinct bytes).
-struct Fwd2 {
-    using S = Geo<2, 2, 4, 2>;                     // 4 waves of 128 x 64: a 256 x 128 tile
-    static constexpr int K_STEP = 32;
-    static constexpr int A_BYTES = 256 * 64, B_BYTES = 128 * 64, STAGE = A_BYTES + B_BYTES, NSTAGE = 3;
+template <int NWJ_, int NSTAGE_, int WJ_ = 2>
+struct FwdK32 {
+    using S = Geo<2, NWJ_, 4, WJ_>;                // 2 x NWJ waves of 128 x (32 WJ): a 256 x (32 WJ NWJ) tile
+    static constexpr int K_STEP = 32, NSTAGE = NSTAGE_, NW = 2 * NWJ_;
+    static constexpr int A_BYTES = 256 * 64, B_BYTES = S::BJ * 64, STAGE = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = STAGE * NSTAGE;
+    static constexpr int RA = 16 / NW, RB = S::BJ / 16 / NW, R = RA + RB;   // 1 KiB requests per wave and step
 };
+using Fwd2 = FwdK32<2, 3>;   // two workgroups per CU: 4 waves, 256 x 128, 72 KiB
+using Fwd3 = FwdK32<4, 4>;   // one workgroup per CU: 8 waves, 256 x 256, 128 KiB, requests three steps ahead
+using Fwd4 = FwdK32<2, 4, 4>;   // the same with 4 waves of 128 x 128 (a third fewer LDS fragment reads per MFMA)
 
 // acc = W_tile . H_tile^T over `ksteps` steps of 32.  wblk: the tile's first block of the blocked copy of W
 // (ksteps blocks of 16 KiB follow each other); B: first hidden row of the tile, row-major, ldb elements.
+// The requests run NSTAGE - 1 steps ahead of the MFMAs.
+template <class F2>
 __device__ __forceinline__ void mainloop32(const char* __restrict__ wblk, const bf16_t* __restrict__ B, int64_t ldb,
-                                           int ksteps, char* lds, f32x16 (&acc)[4][2]) {
-    using S = Fwd2::S;
-    constexpr int WI = 4, WJ = 2;
+                                           int ksteps, char* lds, f32x16 (&acc)[4][F2::S::WJ]) {
+    using S = typename F2::S;
+    constexpr int WI = 4, WJ = S::WJ, NW = F2::NW, RA = F2::RA, R = F2::R, NST = F2::NSTAGE, D = NST - 1;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_i = wave & 1, wave_j = wave >> 1;
 
-    // requests: a wave makes 4 for W (1 KiB each, linear) and 2 for the hidden rows (16 rows x 64 bytes each)
+    // requests: 1 KiB each; request r of a wave is unit r NW + wave of its operand (W: linear; hidden rows: 16 rows)
     const char* ga = wblk + wave * 1024 + lane * 16;
     const int gchunk = (lane & 3) ^ ((lane >> 4) & 3);            // chunk that belongs at slot lane % 4 of row lane / 4
     const char* gb = (const char*)(B + (int64_t)(wave * 16 + (lane >> 2)) * ldb + gchunk * 8);
-    const int64_t b_round = 64 * ldb * 2;                         // the wave's next 16 rows are 64 rows on
+    const int64_t b_round = (int64_t)(16 * NW) * ldb * 2;         // the wave's next 16 rows
     const int dst_wave = wave * 1024;
 
     // fragment reads
     const int frow = lane & 31, fhi = lane >> 5;
     const int x0 = (fhi ^ ((frow >> 2) & 3)) * 16, x1 = x0 ^ 32;  // chunk 2 ks + fhi at its swizzled position
     const int a_off = (wave_i * 128 + frow) * 64;
-    const int b_off = Fwd2::A_BYTES + (wave_j * 64 + frow) * 64;
+    const int b_off = F2::A_BYTES + (wave_j * (WJ * 32) + frow) * 64;
 
 #pragma unroll
     for (int ib = 0; ib < WI; ++ib)
@@ -759,74 +766,79 @@ __device__ __forceinline__ void mainloop32(const char* __restrict__ wblk, const 
     int src_step = 0;       // K step the next requests fetch (clamped to the last one: the loop has no branches
     char* dst;              // and every address stays in bounds), and the stage they go to
     auto request = [&](int r) {
-        if (r < 4)
-            load_to_lds_16(ga + (int64_t)src_step * Fwd2::A_BYTES + r * 4096, dst + dst_wave + r * 4096);
+        if (r < RA)
+            load_to_lds_16(ga + (int64_t)src_step * F2::A_BYTES + r * (NW * 1024), dst + dst_wave + r * (NW * 1024));
         else
-            load_to_lds_16(gb + (int64_t)src_step * 64 + (r - 4) * b_round, dst + Fwd2::A_BYTES + dst_wave + (r - 4) * 4096);
+            load_to_lds_16(gb + (int64_t)src_step * 64 + (r - RA) * b_round,
+                           dst + F2::A_BYTES + dst_wave + (r - RA) * (NW * 1024));
     };
     auto read_frags = [&](Frags<WI, WJ>& f, const char* stage, int x) {
         const uint32_t la = lds_addr(stage) + a_off + x, lb = lds_addr(stage) + b_off + x;
         f.a[0] = ds_read128<0>(la); f.a[1] = ds_read128<2048>(la); f.a[2] = ds_read128<4096>(la); f.a[3] = ds_read128<6144>(la);
         f.b[0] = ds_read128<0>(lb); f.b[1] = ds_read128<2048>(lb);
+        if constexpr (WJ == 4) { f.b[2] = ds_read128<4096>(lb); f.b[3] = ds_read128<6144>(lb); }
     };
 
     // everybody is done with the stages of the tile before (reads, trailing requests, a staged epilogue)
     lds_barrier();
-    char* cur = lds;
-    char* nxt = lds + Fwd2::STAGE;
-    char* fil = lds + 2 * Fwd2::STAGE;
-    dst = cur; src_step = 0;
 #pragma unroll
-    for (int r = 0; r < 6; ++r) request(r);
-    dst = nxt; src_step = ksteps > 1 ? 1 : 0;
+    for (int st = 0; st < D; ++st) {                  // steps 0 .. D-1 into stages 0 .. D-1
+        dst = lds + st * F2::STAGE;
+        src_step = st < ksteps ? st : ksteps - 1;
 #pragma unroll
-    for (int r = 0; r < 6; ++r) request(r);
-    asm volatile("s_waitcnt vmcnt(6)" ::: "memory");   // step 0 has landed (loads complete in order)
+        for (int r = 0; r < R; ++r) request(r);
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 1) * R) : "memory");   // step 0 has landed (loads complete in order)
     lds_barrier();
     Frags<WI, WJ> f0, f1;
-    read_frags(f0, cur, x0);
+    read_frags(f0, lds, x0);
     wait_frags<0>(f0);
     // One K step on stage `cur` (its first fragments f0 are in registers):
-    //   read f1 (second half of the step) | MFMA f0 + the requests for step kt+2 into `fil`
+    //   read f1 (second half of the step) | MFMA f0 + the requests for step kt+D into stage (kt+D) % NSTAGE
     //   wait: own reads of `cur` done, own requests for step kt+1 landed; barrier
     //   read f0 of step kt+1              | MFMA f1
-    // `fil` was read during step kt-1, and everybody passed the barrier at the end of that step.
+    // The stage the requests go to was read during step kt-1, and everybody passed the barrier at the end of it.
+    int cur_i = 0, fil_i = D;
     for (int kt = 0; kt < ksteps; ++kt) {
+        char* cur = lds + cur_i * F2::STAGE;
+        const int nxt_i = cur_i + 1 == NST ? 0 : cur_i + 1;
+        char* nxt = lds + nxt_i * F2::STAGE;
         fence();
         read_frags(f1, cur, x1);
         fence();
-        dst = fil;
-        src_step = kt + 2 < ksteps ? kt + 2 : ksteps - 1;
-        mma_block_requesting<S, 0, 12>(f0, acc, request);   // requests 0..5 after MFMAs 0, 1, 2, 4, 5, 6
+        dst = lds + fil_i * F2::STAGE;
+        src_step = kt + D < ksteps ? kt + D : ksteps - 1;
+        mma_block_requesting<S, 0, 2 * R>(f0, acc, request);   // the R requests spread over the 8 MFMAs
         fence();
         wait_frags<0>(f1);
-        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 1) * R) : "memory");
         lds_barrier();
         read_frags(f0, nxt, x0);
         fence();
         mma_block<WI, WJ>(f1, acc);
         fence();
         wait_frags<0>(f0);
-        char* t = cur; cur = nxt; nxt = fil; fil = t;
+        cur_i = nxt_i;
+        fil_i = fil_i + 1 == NST ? 0 : fil_i + 1;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests for steps that do not exist
 }
 
-template <bool STORE>
-__global__ __launch_bounds__(256, 2) void fwd_lse2_kernel(FwdArgs a) {
-    using S = Fwd2::S;
+template <class F2, bool STORE>
+__global__ __launch_bounds__(64 * F2::NW, (F2::NW == 4 && F2::S::WJ == 2) ? 2 : 1) void fwd_lse2_kernel(FwdArgs a) {
+    using S = typename F2::S;
     extern __shared__ __attribute__((aligned(128))) char lds[];
     const int M = a.counts[CNT_M], Mr = a.counts[CNT_MR];
     if (a.row0 >= Mr) return;
-    // 128-row tiles; the order covers the row tiles that hold tokens only
-    const int tilesM = min(a.tilesM * 2, (int)((Mr - a.row0 + S::BJ - 1) / S::BJ));
-    const int ksteps = (int)(a.dpad / Fwd2::K_STEP);
+    // the order covers the row tiles that hold tokens only
+    const int tilesM = min(a.tilesM * (256 / S::BJ), (int)((Mr - a.row0 + S::BJ - 1) / S::BJ));
+    const int ksteps = (int)(a.dpad / F2::K_STEP);
     for (int pid = blockIdx.x, ids = ids_for(a.tilesV, tilesM); pid < ids; pid += gridDim.x) {
         const TileId t = map_tile(pid, a.tilesV, tilesM, a.gi);
         if (!t.valid) continue;
         const int64_t j_tile = a.row0 + (int64_t)t.tj * S::BJ;
-        f32x16 acc[4][2];
-        mainloop32((const char*)a.WvdB + (int64_t)t.ti * ksteps * Fwd2::A_BYTES, a.Hc + j_tile * a.ldk, a.ldk, ksteps, lds, acc);
+        f32x16 acc[4][S::WJ];
+        mainloop32<F2>((const char*)a.WvdB + (int64_t)t.ti * ksteps * F2::A_BYTES, a.Hc + j_tile * a.ldk, a.ldk, ksteps, lds, acc);
         fwd_epilogue<S, STORE>(a, t, j_tile, M, lds, acc);
     }
 }
@@ -1305,15 +1317,37 @@ void launch_block_w32(const bf16_t* Wvd, int64_t ldk, bf16_t* out, int64_t Vpad,
     block_w32_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(Wvd, ldk, out, Vpad, dpad);
 }
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st) {
+    if (a.WvdB && a.k32_mode == 3) {   // one workgroup of 4 waves per CU, K steps of 32 requested three steps ahead
+        const unsigned grid = grid_for(a.tilesV, a.tilesM);
+        if (a.zc) {
+            allow_lds<&fwd_lse2_kernel<Fwd4, true>>(Fwd4::LDS_BYTES);
+            fwd_lse2_kernel<Fwd4, true><<<grid, 256, Fwd4::LDS_BYTES, st>>>(a);
+        } else {
+            allow_lds<&fwd_lse2_kernel<Fwd4, false>>(Fwd4::LDS_BYTES);
+            fwd_lse2_kernel<Fwd4, false><<<grid, 256, Fwd4::LDS_BYTES, st>>>(a);
+        }
+        return;
+    }
+    if (a.WvdB && a.k32_mode == 2) {   // one workgroup of 8 waves per CU, K steps of 32 requested three steps ahead
+        const unsigned grid = grid_for(a.tilesV, a.tilesM);
+        if (a.zc) {
+            allow_lds<&fwd_lse2_kernel<Fwd3, true>>(Fwd3::LDS_BYTES);
+            fwd_lse2_kernel<Fwd3, true><<<grid, 512, Fwd3::LDS_BYTES, st>>>(a);
+        } else {
+            allow_lds<&fwd_lse2_kernel<Fwd3, false>>(Fwd3::LDS_BYTES);
+            fwd_lse2_kernel<Fwd3, false><<<grid, 512, Fwd3::LDS_BYTES, st>>>(a);
+        }
+        return;
+    }
     if (a.WvdB) {   // two workgroups of 4 waves per CU on 256 x 128 tiles
         const int ids = ids_for(a.tilesV, a.tilesM * 2), slots = g_num_cu.load() / 8 * 8 * 2;
         const unsigned grid = (unsigned)(ids < slots ? ids : slots);
         if (a.zc) {
-            allow_lds<&fwd_lse2_kernel<true>>(Fwd2::LDS_BYTES);
-            fwd_lse2_kernel<true><<<grid, 256, Fwd2::LDS_BYTES, st>>>(a);
+            allow_lds<&fwd_lse2_kernel<Fwd2, true>>(Fwd2::LDS_BYTES);
+            fwd_lse2_kernel<Fwd2, true><<<grid, 256, Fwd2::LDS_BYTES, st>>>(a);
         } else {
-            allow_lds<&fwd_lse2_kernel<false>>(Fwd2::LDS_BYTES);
-            fwd_lse2_kernel<false><<<grid, 256, Fwd2::LDS_BYTES, st>>>(a);
+            allow_lds<&fwd_lse2_kernel<Fwd2, false>>(Fwd2::LDS_BYTES);
+            fwd_lse2_kernel<Fwd2, false><<<grid, 256, Fwd2::LDS_BYTES, st>>>(a);
         }
         return;
     }

@@ -384,6 +384,7 @@ void forward_rows_bf16(const Plan& p, void* ws, const FwdIo& io, const int32_t* 
     a.refz = at<float>(ws, p.refz); a.ref_logp = io.ref_logp; a.row_index = row_index;
     a.part_row0 = base; a.zc_row0 = base;
     a.WvdB = p.two_wg ? at<bf16_t>(ws, p.Wvd32) : nullptr;
+    a.k32_mode = g_fwd_two_wg.load();
     {   // the sampled tokens' logits first: a storing forward uses them as its per-row reference
         Span sp(ST_MERGE, st);
         launch_token_logit(a, base, rows, st);
@@ -590,7 +591,7 @@ int rapid_set_tuning(int key, int value) {
         g_dh_split = value;
         return RAPID_OK;
     }
-    if (key == 21 && (value == 0 || value == 1)) {
+    if (key == 21 && value >= 0 && value <= 3) {
         g_fwd_two_wg = value;
         return RAPID_OK;
     }

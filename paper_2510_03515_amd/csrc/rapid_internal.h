@@ -202,6 +202,8 @@ struct FwdArgs {          // logits tile -> per-slot (max, sumexp) and gathered 
     int64_t zc_row0 = 0;     // compact row stored in row 0 of zc
     const bf16_t* WvdB = nullptr;   // if set: W blocked per (256-row tile, K step of 32) (launch_block_w32); selects the
                                     // kernel that runs two workgroups per CU
+    int k32_mode = 1;               // with WvdB: 1 = two 4-wave workgroups per CU on 256 x 128 tiles, 2 = one 8-wave
+                                    // workgroup per CU on 256 x 256 tiles with requests three K steps ahead
 };
 void launch_fwd_lse(const FwdArgs& a, hipStream_t st);
 // out [Vpad * dpad]: Wvd [Vpad, ldk] in blocks of 256 rows x 32 columns, in the LDS order of the two-workgroup forward

@@ -900,9 +900,11 @@ def test_other_workgroup_geometries(rb, waves):
         rb.rapid_set_tuning(2, 0)
 
 
-def test_forward_with_two_workgroups_per_cu(rb):
-    """Tuning key 21: the logits kernel as two 4-wave workgroups per CU on 256 x 128 tiles, K steps of 32 through
-    three LDS stages, W from its K-blocked copy.  Same tolerances against the oracle: the behaviour pass, the fused
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_forward_with_k_steps_of_32(rb, variant):
+    """Tuning key 21: the logits kernel with K steps of 32 and W from its K-blocked copy, as two 4-wave workgroups
+    per CU on 256 x 128 tiles through three LDS stages (1), or as one 8-wave workgroup on 256 x 256 tiles through
+    four stages, requests three steps ahead (2), or that with 4 waves of 128 x 128 (3).  Same tolerances against the oracle: the behaviour pass, the fused
     call in both backward modes and layouts, the chunked cache; and the same log-probs, bit for bit, as the
     default kernel (the same products summed in the same order per accumulator)."""
     try:
@@ -910,9 +912,9 @@ def test_forward_with_two_workgroups_per_cu(rb):
         for name in ("bf16_small", "bf16_ragged"):
             w, g = _make(SPECS[name])
             base[name] = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])[0].clone()
-        rb.rapid_set_tuning(21, 1)
+        rb.rapid_set_tuning(21, variant)
         for name in ("bf16_small", "bf16_ragged"):
-            print(f"two workgroups per CU: {name}", flush=True)
+            print(f"K steps of 32, variant {variant}: {name}", flush=True)
             w, g = _make(SPECS[name])
             lp, _ = rb.rapid_logprob_fwd(g["hidden"], g["W"], g["tokens"], g["mask"])
             torch.cuda.synchronize()
