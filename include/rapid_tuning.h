@@ -54,7 +54,9 @@ extern "C" {
  *        copy (which adds Vpad x dpad x 2 bytes to every workspace size while the key is set: set it before
  *        asking for sizes): 1 = two 4-wave workgroups per CU on 256 x 128 tiles, three LDS stages; 2 = one 8-wave
  *        workgroup per CU on 256 x 256 tiles, four stages, requests three steps ahead; 3 = the same with 4 waves
- *        of 128 x 128.  Identical results; measured slower or equal, kept for those measurements. */
+ *        of 128 x 128.  Identical results; measured slower or equal, kept for those measurements.
+ * key 22: 0 (default) / 1: the dW kernel with K steps of 32 rows through four LDS stages, requests three steps
+ *        ahead.  Identical results; measured 2 % slower, kept for that measurement. */
 int rapid_set_tuning(int key, int value);
 
 /* Per-stage timing for benchmarks.  rapid_set_tuning(1, 1) makes every later call bracket each of

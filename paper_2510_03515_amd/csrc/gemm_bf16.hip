@@ -339,15 +339,15 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 // operand (row of the operand = column of the tile, 4 of its 8 k values).
 // A row is cut into 64-byte segments and segment g of row r is kept at position g ^ (r % SEGS),
 // so that the four rows one transpose read touches per 32 lanes fall on different banks.
-template <int COLS, int NW>
+template <int COLS, int NW, int STEP = 64>         // STEP: rows (contraction indices) per K step
 struct KMajor {
     static constexpr int ROW_BYTES = COLS * 2;
     static constexpr int CPR = COLS / 8;          // 16-byte chunks per row
     static constexpr int RPI = 64 / CPR;          // rows covered by one wave-wide load instruction
-    static constexpr int ROUNDS = 64 / (NW * RPI);
+    static constexpr int ROUNDS = STEP / (NW * RPI);
     static constexpr int ROUND_ROWS = NW * RPI;
     static constexpr int SEGS = CPR / 4;          // 64-byte segments per row
-    static constexpr int TILE_BYTES = 64 * ROW_BYTES;
+    static constexpr int TILE_BYTES = STEP * ROW_BYTES;
 };
 
 template <int COLS, int NW>
@@ -502,6 +502,111 @@ __device__ __forceinline__ void mainloop_kmajor(const bf16_t* __restrict__ A, in
         mma_block_requesting<S, 0, T>(f1, acc, request);
         fence();
         wait_frags<0>(f0);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests for steps that do not exist
+}
+
+// The same contraction with K steps of 32 rows through NST LDS stages (NST x 32 rows = the same LDS as two
+// steps of 64), the requests NST - 1 steps ahead of the MFMAs: the streamed operand of dW comes from HBM, and
+// one step of lead is less than a trip there.  Same LDS layout per row, same fragments, same order of
+// summation per accumulator: identical results.
+template <class S, int NST>
+__device__ __forceinline__ void mainloop_kmajor32(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
+                                                  int64_t ldb, int ksteps, char* lds, f32x16 (&acc)[S::WI][S::WJ]) {
+    constexpr int WI = S::WI, WJ = S::WJ;
+    using KA = KMajor<S::BI, S::NW, 32>;
+    using KB = KMajor<S::BJ, S::NW, 32>;
+    static_assert(KA::ROUNDS >= 1 && KB::ROUNDS >= 1, "a wave instruction must not span more than a step");
+    constexpr int STAGE = KA::TILE_BYTES + KB::TILE_BYTES, D = NST - 1, T = KA::ROUNDS + KB::ROUNDS;
+    static_assert(NST * STAGE <= S::LDS_BYTES, "stages must fit the kernel's LDS");
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_i = wave % S::NWI, wave_j = wave / S::NWI;
+
+    auto lane_voff = [&](int cpr, int segs, int rpi, int64_t ld) -> uint32_t {
+        const int lrow = lane / cpr, p = lane % cpr;
+        const int row_low = (wave * rpi + lrow) & (segs - 1);
+        const int gseg = (p >> 2) ^ row_low;
+        return (uint32_t)(((int64_t)lrow * ld + (gseg * 4 + (p & 3)) * 8) * 2);
+    };
+    const uint32_t voff_a = lane_voff(KA::CPR, KA::SEGS, KA::RPI, lda);
+    const uint32_t voff_b = lane_voff(KB::CPR, KB::SEGS, KB::RPI, ldb);
+    const char* ga = (const char*)(A + (int64_t)(wave * KA::RPI) * lda) + voff_a;
+    const char* gb = (const char*)(B + (int64_t)(wave * KB::RPI) * ldb) + voff_b;
+    const int64_t round_a = (int64_t)KA::ROUND_ROWS * lda * 2, round_b = (int64_t)KB::ROUND_ROWS * ldb * 2;
+    const int64_t step_a = 32 * lda * 2, step_b = 32 * ldb * 2;
+    const int lds_wave_a = wave * KA::RPI * KA::ROW_BYTES;
+    const int lds_wave_b = KA::TILE_BYTES + wave * KB::RPI * KB::ROW_BYTES;
+
+    const int q = (lane & 15) >> 2;
+    const int sub_bytes = (2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) * 16 + 8 * (lane & 1);
+    const int rowpart = 8 * (lane >> 5) + q;
+    int xa[WI][2], xb[WJ][2];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int sw = 4 * r + q;   // low bits of the row this lane addresses in half r
+        const int base_a = (rowpart + 4 * r) * KA::ROW_BYTES + ((((wave_i * WI) ^ (sw & (KA::SEGS - 1))) * 64)) + sub_bytes;
+        const int base_b = KA::TILE_BYTES + (rowpart + 4 * r) * KB::ROW_BYTES +
+                           ((((wave_j * WJ) ^ (sw & (KB::SEGS - 1))) * 64)) + sub_bytes;
+#pragma unroll
+        for (int ib = 0; ib < WI; ++ib) xa[ib][r] = base_a ^ (ib * 64);
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb) xb[jb][r] = base_b ^ (jb * 64);
+    }
+
+#pragma unroll
+    for (int ib = 0; ib < WI; ++ib)
+#pragma unroll
+        for (int jb = 0; jb < WJ; ++jb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[ib][jb][v] = 0.f;
+    if (ksteps <= 0) return;
+
+    int src_step = 0;       // K step the next requests fetch (clamped to the last one), and the stage they go to
+    char* dst;
+    auto request = [&](int r) {
+        if (r < KA::ROUNDS)
+            load_to_lds_16(ga + src_step * step_a + r * round_a, dst + lds_wave_a + r * (KA::ROUND_ROWS * KA::ROW_BYTES));
+        else
+            load_to_lds_16(gb + src_step * step_b + (r - KA::ROUNDS) * round_b,
+                           dst + lds_wave_b + (r - KA::ROUNDS) * (KB::ROUND_ROWS * KB::ROW_BYTES));
+    };
+    lds_barrier();   // see mainloop
+#pragma unroll
+    for (int st = 0; st < D; ++st) {
+        dst = lds + st * STAGE;
+        src_step = st < ksteps ? st : ksteps - 1;
+#pragma unroll
+        for (int r = 0; r < T; ++r) request(r);
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 1) * T) : "memory");   // step 0 has landed
+    lds_barrier();
+    Frags<WI, WJ> f0, f1;
+    load_frags_kmajor<0, S>(f0, lds_addr(lds), xa, xb);
+    wait_frags<0>(f0);
+    int cur_i = 0, fil_i = D;
+    for (int kt = 0; kt < ksteps; ++kt) {
+        const uint32_t lc = lds_addr(lds + cur_i * STAGE);
+        const int nxt_i = cur_i + 1 == NST ? 0 : cur_i + 1;
+        const uint32_t ln = lds_addr(lds + nxt_i * STAGE);
+        fence();
+        load_frags_kmajor<1, S>(f1, lc, xa, xb);
+        fence();
+        dst = lds + fil_i * STAGE;
+        src_step = kt + D < ksteps ? kt + D : ksteps - 1;
+        mma_block_requesting<S, 0, 2 * T>(f0, acc, request);   // the T requests for step kt + D, spread over the MFMAs
+        fence();
+        wait_frags<0>(f1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 1) * T) : "memory");   // own requests for step kt + 1 have landed
+        lds_barrier();
+        load_frags_kmajor<0, S>(f0, ln, xa, xb);
+        fence();
+        mma_block<WI, WJ>(f1, acc);
+        fence();
+        wait_frags<0>(f0);
+        cur_i = nxt_i;
+        fil_i = fil_i + 1 == NST ? 0 : fil_i + 1;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests for steps that do not exist
 }
@@ -1089,7 +1194,7 @@ __global__ __launch_bounds__(S::NT) void dh_reduce_kernel(DhArgs a, int grid_of_
 }
 
 // ------------------------------------------------------------------------------------------ dw
-template <class S>
+template <class S, bool DEEP = false>
 __global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
     constexpr int WI = S::WI, WJ = S::WJ;
     extern __shared__ __attribute__((aligned(128))) char lds[];
@@ -1102,8 +1207,11 @@ __global__ __launch_bounds__(S::NT) void dw_kernel(DwArgs a) {
     const TileId t = map_tile(pid, tilesV, tilesD, a.gi);
     if (!t.valid) continue;
     f32x16 acc[WI][WJ];
-    mainloop_kmajor<S>(a.dz + (int64_t)t.ti * S::BI, a.ldz, a.Hc + (int64_t)t.tj * S::BJ, a.ldH,
-                            (int)(rows / K_TILE), lds, acc);
+    if constexpr (DEEP)
+        mainloop_kmajor32<S, 4>(a.dz + (int64_t)t.ti * S::BI, a.ldz, a.Hc + (int64_t)t.tj * S::BJ, a.ldH, (int)(rows / 32), lds, acc);
+    else
+        mainloop_kmajor<S>(a.dz + (int64_t)t.ti * S::BI, a.ldz, a.Hc + (int64_t)t.tj * S::BJ, a.ldH,
+                           (int)(rows / K_TILE), lds, acc);
     const Lane<S> L;
     const int64_t i_base = (int64_t)t.ti * S::BI + L.wave_i * (WI * 32);
     const bool vec = (a.V % 4) == 0;
@@ -1297,10 +1405,10 @@ void launch_dh_t(const DhArgs& a, hipStream_t st) {
     dh_kernel<S><<<grid, S::NT, S::LDS_BYTES, st>>>(b);
     if (b.part && !b.pace) dh_reduce_kernel<S><<<grid, S::NT, 0, st>>>(b, (int)grid);
 }
-template <class S>
+template <class S, bool DEEP = false>
 void launch_dw_t(const DwArgs& a, hipStream_t st) {
-    allow_lds<&dw_kernel<S>>(S::LDS_BYTES);
-    dw_kernel<S><<<grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ)), S::NT, S::LDS_BYTES, st>>>(a);
+    allow_lds<&dw_kernel<S, DEEP>>(S::LDS_BYTES);
+    dw_kernel<S, DEEP><<<grid_for((int)(a.Vpad / S::BI), (int)(a.dpadR / S::BJ)), S::NT, S::LDS_BYTES, st>>>(a);
 }
 
 }  // namespace
@@ -1387,8 +1495,14 @@ void launch_dh(const DhArgs& a, hipStream_t st) {
     }
 }
 
+std::atomic<int> g_dw_deep{0};
+void set_dw_deep(int on) { g_dw_deep = on ? 1 : 0; }
 void launch_dw(const DwArgs& a, hipStream_t st) {
     const int w = waves_for(8);
+    if (g_dw_deep.load() && w == 8) {   // K steps of 32 rows, requests three steps ahead
+        if (a.dpadR % 256 == 0) launch_dw_t<G8, true>(a, st); else launch_dw_t<G8_J128, true>(a, st);
+        return;
+    }
     if (a.dpadR % 256 == 0) {
         if (w == 16) launch_dw_t<G16>(a, st); else if (w == 8) launch_dw_t<G8>(a, st); else launch_dw_t<G4>(a, st);
     } else {   // d padded to a multiple of 128 only

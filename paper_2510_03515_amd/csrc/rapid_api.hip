@@ -591,6 +591,10 @@ int rapid_set_tuning(int key, int value) {
         g_dh_split = value;
         return RAPID_OK;
     }
+    if (key == 22 && (value == 0 || value == 1)) {
+        set_dw_deep(value);
+        return RAPID_OK;
+    }
     if (key == 21 && value >= 0 && value <= 3) {
         g_fwd_two_wg = value;
         return RAPID_OK;

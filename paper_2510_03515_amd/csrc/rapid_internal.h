@@ -275,6 +275,7 @@ struct DwArgs {           // dW (+)= Hc^T . dz over the chunk's rows
 };
 void launch_dw(const DwArgs& a, hipStream_t st);
 void set_waves_per_workgroup(int n);   // 4, 8 or 16 waves per contraction workgroup
+void set_dw_deep(int on);              // dW with K steps of 32 rows and requests three steps ahead
 void set_cu_count(int n);              // compute units of the device: the contraction kernels launch one workgroup each
 
 

@@ -975,6 +975,27 @@ def test_dhidden_cut_last_round(rb, V):
         assert not torch.equal(dh_cut, out.dhidden) or V == 200
 
 
+def test_dw_with_k_steps_of_32(rb):
+    """Tuning key 22: the dW kernel with K steps of 32 rows through four LDS stages, requests three steps ahead.  The
+    same products are added in the same order per accumulator, so dW must come out bit for bit as from the default
+    loop; shapes with one row tile, several, a d padded to 128-wide tiles, and the 35840-row batch of the cut test."""
+    cases = [("bf16_small", SPECS["bf16_small"], 0), ("bf16_ragged", SPECS["bf16_ragged"], 0), ("chunky", CHUNKY, 4),
+             ("long", wl.small_spec("dh_cut", "bf16", d=512, V=520, prompts=35, G=4, len_lo=256, len_hi=256, sigma=0.02,
+                                    reward="uniform"), 3)]
+    for name, spec, seed in cases:
+        for cache in (False, True):
+            print(f"dW K steps of 32: {name}, cache {cache}", flush=True)
+            w, out, ref = _run_pair(rb, spec, seed=seed, logits_cache=cache)
+            base = out.dW.clone()
+            try:
+                rb.rapid_set_tuning(22, 1)
+                w, out, ref = _run_pair(rb, spec, seed=seed, logits_cache=cache)
+            finally:
+                rb.rapid_set_tuning(22, 0)
+            assert torch.equal(out.dW, base)
+            _check_pair(rb, spec, out, ref)
+
+
 def test_dhidden_pacing_is_timing_only(rb):
     """Tuning key 16: the dHidden workgroups meet every so many K steps (a vocabulary of 20 000 makes
     313 steps, so meetings every 64 steps do happen here, with fewer workgroups than CUs): same bits
