@@ -37,10 +37,10 @@ extern "C" {
  *        for a bounded time, for the others, so that all XCDs sweep W together and share it through
  *        the memory-side cache.  A timing hint only: results are identical, and a meeting that runs
  *        out of time switches the pacing off for the rest of the launch.
- * key 17: 1 (default) / 0: the dHidden kernel lays the tiles of a partly filled last round of workgroups end
- *        to end along the vocabulary and gives every workgroup an equal stretch (the pieces of a tile are
- *        summed in a fixed order by a small second kernel), instead of leaving workgroups idle for a whole tile.
- *        The sums are taken in another order: results differ by fp32 rounding of the accumulators.
+ * key 17: 1 (default) / 0: the dHidden kernel cuts the contraction of the tiles of a partly filled last round of
+ *        workgroups into equal segments and deals the (tile, segment) units out in short rounds (the pieces of a
+ *        tile are summed in a fixed order by a small second kernel), instead of leaving workgroups idle for a
+ *        whole tile.  The sums are taken in another order: results differ by fp32 rounding of the accumulators.
  * key 18: cache rows (a multiple of 256, default 90112) of the size rapid_workspace_bytes recommends for
  *        RAPID_OP_IW_PG_FWD_BWD_CACHED.  A call uses whatever its workspace affords; this only moves the
  *        recommendation.

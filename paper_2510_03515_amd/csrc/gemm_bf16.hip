@@ -1004,28 +1004,32 @@ __global__ __launch_bounds__(S::NT) void dz_kernel(DzArgs a) {
 // The tiles of dHidden are long (the contraction runs over the whole vocabulary) and few: a launch has
 // a handful of rounds of one tile per workgroup, and a last round that is only partly filled would
 // leave most of the chip idle for a whole tile.  So the last, partial round of an XCD's share is not
-// dealt out tile by tile: its rem tiles are laid end to end along the contraction (rem x ktiles K steps)
-// and every workgroup of the XCD takes an equal stretch of that line.  A stretch covers part of one tile
-// or the end of one and the beginning of the next; the workgroup leaves the fp32 accumulators of each
-// piece in `part`, and dh_reduce_kernel adds the pieces of a tile in workgroup order and stores the result.
-// The last round then takes rem / workgroups of a tile's time, and the result does not depend on timing.
+// dealt out tile by tile: the contraction of each of its rem tiles is cut into S equal segments, and the
+// rem x S (tile, segment) units are dealt out in short rounds, segment by segment, so that the workgroups
+// of a short round are on the same K steps and share operand panels in the L2 as in a whole round.  A
+// workgroup leaves the fp32 accumulators of a unit in `part`, and dh_reduce_kernel adds the S pieces of a
+// tile in segment order and stores the result.  The last round then takes ceil(rem S / workgroups) / S of
+// a tile's time, and the result does not depend on timing.
+constexpr int DH_UNITS_PER_XCD = 64;   // partial tiles an XCD's last round may leave (dh_part_bytes)
 struct DhShare {       // an XCD's share of the order, and how its last round is cut
-    int total, per, wgs, mine, full_rounds, rem;
+    int total, per, wgs, mine, full_rounds, rem, segs;
     bool cut;
-    __device__ __forceinline__ DhShare(int tilesD, int tilesM, int grid, int x, bool can_cut) {
+    __device__ __forceinline__ DhShare(int tilesD, int tilesM, int grid, int x, int ktiles, bool can_cut) {
         total = tilesD * tilesM; per = (total + 7) / 8; wgs = grid / 8;
         mine = max(0, min(per, total - x * per));
         full_rounds = mine / wgs; rem = mine - full_rounds * wgs;
-        // Workgroups on stretches are at different K steps, so they share no operand panel in the L2: a K step
-        // of a stretch costs about 1.45 times one of a whole round (measured).  Cutting pays while
-        // 1.45 rem / wgs < 1; a fuller last round is dealt out tile by tile like the others.
-        cut = can_cut && rem > 0 && rem * 3 <= wgs * 2;
-    }
-    // the stretch of workgroup w: K steps [u0, u1) of the line of rem * ktiles steps
-    __device__ __forceinline__ void stretch(int w, int ktiles, int64_t& u0, int64_t& u1) const {
-        const int64_t units = (int64_t)rem * ktiles;
-        u0 = units * w / wgs;
-        u1 = units * (w + 1) / wgs;
+        // the number of segments that makes the last round shortest: rounds(S) / S with rounds(S) = ceil(rem S / wgs)
+        segs = 1;
+        int best_rounds = 1;
+        if (can_cut && rem > 0) {
+            for (int sg = 2; sg <= 8 && sg <= ktiles && rem * sg <= DH_UNITS_PER_XCD; ++sg) {
+                const int r = (rem * sg + wgs - 1) / wgs;
+                if (r * segs < best_rounds * sg) { segs = sg; best_rounds = r; }
+            }
+        }
+        // a cut costs a second pass over the partial tiles: it has to save a fifth of a tile's time at least
+        cut = segs > 1 && best_rounds * 5 <= segs * 4;
+        if (!cut) segs = 1;
     }
 };
 
@@ -1077,8 +1081,8 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
     // short last chunk would otherwise leave whole XCDs with nothing but empty tiles
     const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));
     const int x = blockIdx.x & 7, w = blockIdx.x >> 3;
-    const DhShare sh(tilesD, tilesM, gridDim.x, x, a.part != nullptr && a.pace == nullptr);
     const int ktiles = (int)(a.Vpad / K_TILE);
+    const DhShare sh(tilesD, tilesM, gridDim.x, x, ktiles, a.part != nullptr && a.pace == nullptr);
     const int gi = a.gi > 0 ? a.gi : tilesD;
     // pacing of the launch's workgroups (see GridPace): with total = 8 * per tiles (or fewer in the last
     // XCD shares) the workgroups of round r are those whose id is a valid tile
@@ -1105,17 +1109,16 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
         dh_store<S>(a, t, M, acc);
     }
     if (!sh.cut) return;
-    // the last round, cut into equal stretches; piece `piece` of this workgroup goes to part[2 * blockIdx.x + piece]
-    int64_t u0, u1;
-    sh.stretch(w, ktiles, u0, u1);
-    for (int piece = 0; u0 < u1; ++piece) {
-        const int tpos = (int)(u0 / ktiles), k0 = (int)(u0 - (int64_t)tpos * ktiles);
-        const int k1 = (int)min((int64_t)ktiles, k0 + (u1 - u0));
+    // the last round: unit u = (segment u / rem, tile u % rem), dealt out in rounds of one unit per workgroup;
+    // its accumulators go to part[x * DH_UNITS_PER_XCD + u]
+    for (int u = w; u < sh.rem * sh.segs; u += sh.wgs) {
+        const int seg = u / sh.rem, tpos = u - seg * sh.rem;
+        const int k0 = (int)((int64_t)ktiles * seg / sh.segs), k1 = (int)((int64_t)ktiles * (seg + 1) / sh.segs);
         const TileId t = tile_of_vid(x * sh.per + sh.full_rounds * sh.wgs + tpos, tilesD, tilesM, gi);
         f32x16 acc[WI][WJ];
         dh_contract<S, NoPace>(a, t, k0, k1, lds, acc, NoPace());
-        // the accumulators as they are: register r of thread tid at part[piece slot][r][tid]
-        int64_t off = ((int64_t)blockIdx.x * 2 + piece) * (S::BI * S::BJ) + threadIdx.x;
+        // the accumulators as they are: register r of thread tid at part[unit slot][r][tid]
+        int64_t off = ((int64_t)x * DH_UNITS_PER_XCD + u) * (S::BI * S::BJ) + threadIdx.x;
 #pragma unroll
         for (int ib = 0; ib < WI; ++ib)
 #pragma unroll
@@ -1125,7 +1128,6 @@ __global__ __launch_bounds__(S::NT) void dh_kernel(DhArgs a) {
                 for (int v = 0; v < 16; ++v) a.part[off + v * S::NT] = acc[ib][jb][v];
                 off += 16 * S::NT;
             }
-        u0 += k1 - k0;
     }
 }
 
@@ -1139,21 +1141,11 @@ __global__ __launch_bounds__(S::NT) void dh_reduce_kernel(DhArgs a, int grid_of_
     if (a.m0 >= Mr) return;
     const int tilesM = min(a.tilesM, (int)((Mr - a.m0 + S::BJ - 1) / S::BJ));
     const int x = blockIdx.x & 7, tpos = blockIdx.x >> 3;
-    const DhShare sh(tilesD, tilesM, grid_of_dh, x, true);
-    if (!sh.cut || tpos >= sh.rem) return;
     const int ktiles = (int)(a.Vpad / K_TILE);
+    const DhShare sh(tilesD, tilesM, grid_of_dh, x, ktiles, true);
+    if (!sh.cut || tpos >= sh.rem) return;
     const TileId t = tile_of_vid(x * sh.per + sh.full_rounds * sh.wgs + tpos, tilesD, tilesM, a.gi > 0 ? a.gi : tilesD);
-    const int64_t t0 = (int64_t)tpos * ktiles, t1 = t0 + ktiles;     // this tile's K steps on the line
-    // the workgroups whose stretch touched this tile are consecutive: [w_first, w_last]
-    int w_first = sh.wgs, w_last = -1;
-    for (int w = 0; w < sh.wgs; ++w) {
-        int64_t u0, u1;
-        sh.stretch(w, ktiles, u0, u1);
-        if (u0 >= u1 || u1 <= t0 || u0 >= t1) continue;
-        w_first = min(w_first, w);
-        w_last = w;
-    }
-    // One 32 x 32 block at a time, its pieces added in workgroup order (a fixed order of summation).  The 16
+    // One 32 x 32 block at a time, its pieces added in segment order (a fixed order of summation).  The 16
     // loads of a piece are independent and in flight together; with all 256 accumulators of the tile live at
     // once the loads went out one by one, each a trip to memory, and a tile with five pieces took 3 ms.
     const Lane<S> L;
@@ -1169,12 +1161,8 @@ __global__ __launch_bounds__(S::NT) void dh_reduce_kernel(DhArgs a, int grid_of_
             float sum[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) sum[v] = 0.f;
-            for (int w = w_first; w <= w_last; ++w) {
-                int64_t u0, u1;
-                sh.stretch(w, ktiles, u0, u1);
-                if (u0 >= u1) continue;                              // an empty stretch (fewer K steps than workgroups)
-                const int piece = (u0 / ktiles == tpos) ? 0 : 1;     // the stretch began in this tile, or in the one before
-                const float* in = a.part + ((int64_t)(x + 8 * w) * 2 + piece) * (S::BI * S::BJ) + threadIdx.x +
+            for (int seg = 0; seg < sh.segs; ++seg) {
+                const float* in = a.part + ((int64_t)x * DH_UNITS_PER_XCD + seg * sh.rem + tpos) * (S::BI * S::BJ) + threadIdx.x +
                                   (int64_t)((ib * WJ + jb) * 16) * S::NT;
                 float got[16];
 #pragma unroll
@@ -1400,8 +1388,8 @@ void launch_dh_t(const DhArgs& a, hipStream_t st) {
     allow_lds<&dh_kernel<S>>(S::LDS_BYTES);
     const unsigned grid = grid_for((int)(a.dpadR / S::BI), a.tilesM);
     DhArgs b = a;
-    // a cut last round needs two tiles of fp32 scratch per workgroup and whole XCD shares of workgroups
-    if (grid % 8 != 0 || grid < 16 || (size_t)grid * 2 * S::BI * S::BJ * 4 > a.part_bytes) b.part = nullptr;
+    // a cut last round needs DH_UNITS_PER_XCD tiles of fp32 scratch per XCD and whole XCD shares of workgroups
+    if (grid % 8 != 0 || grid < 16 || (size_t)8 * DH_UNITS_PER_XCD * S::BI * S::BJ * 4 > a.part_bytes) b.part = nullptr;
     dh_kernel<S><<<grid, S::NT, S::LDS_BYTES, st>>>(b);
     if (b.part && !b.pace) dh_reduce_kernel<S><<<grid, S::NT, 0, st>>>(b, (int)grid);
 }
@@ -1413,9 +1401,8 @@ void launch_dw_t(const DwArgs& a, hipStream_t st) {
 
 }  // namespace
 
-// two 256 x 256 fp32 tiles per workgroup of a launch of 256 (the compute units of an MI355X); a launch with
-// more workgroups than that does not cut its last round
-size_t dh_part_bytes() { return (size_t)2 * 256 * 256 * 256 * 4; }
+// DH_UNITS_PER_XCD fp32 tiles of 256 x 256 for each of the 8 XCDs
+size_t dh_part_bytes() { return (size_t)8 * DH_UNITS_PER_XCD * 256 * 256 * 4; }
 void set_waves_per_workgroup(int n) { g_waves = (n == 4 || n == 8 || n == 16) ? n : 0; }
 void set_cu_count(int n) { g_num_cu = n >= 8 ? n : 8; }
 

@@ -944,9 +944,9 @@ def test_forward_with_k_steps_of_32(rb, variant):
 @pytest.mark.parametrize("V", [520, 200])
 def test_dhidden_cut_last_round(rb, V):
     """dHidden with more tiles than workgroups and a last round that fills a fraction of them: 140 row tiles x 2
-    column tiles = 280 tiles on 256 workgroups, 35 per XCD, so each XCD's last round holds 3 tiles, which are cut
-    along the vocabulary into 32 stretches, written as partial tiles and summed by the reduce pass.  V = 520 is 12
-    K steps per tile; V = 200 is 4, fewer K steps on the line than workgroups, so some stretches are empty.  Against
+    column tiles = 280 tiles on 256 workgroups, 35 per XCD, so each XCD's last round holds 3 tiles, whose contraction
+    is cut into segments, written as partial tiles and summed by the reduce pass.  V = 520 is 12 K steps per tile
+    (8 segments of one or two steps); V = 200 is 4 (4 segments of one step).  Against
     the oracle in both backward modes, and against the same call with the cut switched off (tuning key 17)."""
     spec = wl.small_spec("dh_cut", "bf16", d=512, V=V, prompts=35, G=4, len_lo=256, len_hi=256, sigma=0.02, reward="uniform")
     w, g = _make(spec, seed=3)
